@@ -1,0 +1,307 @@
+"""Pins for the oracle's two sub-networks and for whole decodes with the LSTM
+network: torch CPU library routines, closed forms, special cases, invariants.
+No GPU."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from synth import ModelDims, make_model, param_count
+
+
+def small_model(durations=(), seed=7, **kw):
+    # all widths different so a transposed operand cannot go unnoticed
+    dims = ModelDims(F=5, E=7, H=6, L=2, J=4, V1=9, durations=tuple(durations))
+    return make_model(dims, seed, weight_range=0.8, **kw)
+
+
+def torch_pred(model, last, state, dtype):
+    d = model.dims
+    lstm = torch.nn.LSTM(d.E, d.H, num_layers=d.L).to(dtype)
+    with torch.no_grad():
+        for l in range(d.L):
+            getattr(lstm, f"weight_ih_l{l}").copy_(torch.from_numpy(model.w_ih[l]).to(dtype))
+            getattr(lstm, f"weight_hh_l{l}").copy_(torch.from_numpy(model.w_hh[l]).to(dtype))
+            getattr(lstm, f"bias_ih_l{l}").copy_(torch.from_numpy(model.b_ih[l]).to(dtype))
+            getattr(lstm, f"bias_hh_l{l}").copy_(torch.from_numpy(model.b_hh[l]).to(dtype))
+        st = torch.from_numpy(np.asarray(state)).to(dtype).reshape(d.L, 2, d.H)
+        h0 = st[:, 0, :].reshape(d.L, 1, d.H).contiguous()
+        c0 = st[:, 1, :].reshape(d.L, 1, d.H).contiguous()
+        x = torch.from_numpy(model.emb[last]).to(dtype).reshape(1, 1, d.E)
+        out, (h1, c1) = lstm(x, (h0, c0))
+    new_state = torch.stack([h1[:, 0, :], c1[:, 0, :]], dim=1).reshape(-1)
+    return out.reshape(-1).numpy(), new_state.numpy()
+
+
+def torch_joint(model, x_row, g, dtype):
+    F = torch.nn.functional
+    t = lambda a: torch.from_numpy(np.asarray(a)).to(dtype)
+    p = F.linear(t(x_row), t(model.w_enc), t(model.b_enc))
+    q = F.linear(t(g), t(model.w_pred), t(model.b_pred))
+    return F.linear(torch.relu(p + q), t(model.w_out), t(model.b_out)).numpy()
+
+
+@pytest.mark.parametrize("real,dtype,tol", [("float", torch.float32, 2e-6),
+                                            ("double", torch.float64, 1e-13)])
+def test_prediction_network_matches_torch_lstm(real, dtype, tol):
+    model = small_model()
+    net = oracle.LstmNet(model, real)
+    state = np.zeros(net.state_size)
+    rng = np.random.default_rng(0)
+    for step in range(6):
+        last = int(rng.integers(0, model.dims.V1))
+        g, s2 = net.pred(last, state)
+        g_t, s_t = torch_pred(model, last, state, dtype)
+        assert np.max(np.abs(g - g_t)) <= tol
+        assert np.max(np.abs(s2 - s_t)) <= tol
+        assert np.array_equal(g, s2[(model.dims.L - 1) * 2 * model.dims.H:][:model.dims.H])
+        state = s2
+
+
+@pytest.mark.parametrize("real,dtype,tol", [("float", torch.float32, 5e-6),
+                                            ("double", torch.float64, 1e-13)])
+def test_joint_matches_torch_linear(real, dtype, tol):
+    model = small_model(durations=(0, 1, 2))
+    net = oracle.LstmNet(model, real)
+    rng = np.random.default_rng(1)
+    for _ in range(5):
+        x = rng.standard_normal(model.dims.F)
+        g = rng.uniform(-1, 1, model.dims.H)
+        got = net.joint(net.prep(x), g)
+        want = torch_joint(model, x, g, dtype)
+        assert got.shape == (model.dims.n_out,)
+        assert np.max(np.abs(got - want)) <= tol * max(1.0, np.max(np.abs(want)))
+
+
+def test_zero_weight_lstm_closed_form():
+    """With all weight matrices zero the cell is driven by the biases alone:
+    c_n = s(b_f) c_{n-1} + s(b_i) tanh(b_g),  h_n = s(b_o) tanh(c_n)."""
+    model = small_model()
+    d = model.dims
+    for l in range(d.L):
+        model.w_ih[l][:] = 0
+        model.w_hh[l][:] = 0
+    net = oracle.LstmNet(model, "double")
+    sig = lambda v: 1.0 / (1.0 + np.exp(-v))
+    state = np.zeros(net.state_size)
+    c = [np.zeros(d.H) for _ in range(d.L)]
+    for n in range(4):
+        g, state = net.pred(3, state)
+        for l in range(d.L):
+            b = (model.b_ih[l] + model.b_hh[l]).astype(np.float64)
+            bi, bf, bg, bo = b[:d.H], b[d.H:2 * d.H], b[2 * d.H:3 * d.H], b[3 * d.H:]
+            c[l] = sig(bf) * c[l] + sig(bi) * np.tanh(bg)
+            h = sig(bo) * np.tanh(c[l])
+            assert np.allclose(state[l * 2 * d.H:l * 2 * d.H + d.H], h, atol=1e-14)
+            assert np.allclose(state[l * 2 * d.H + d.H:(l + 1) * 2 * d.H], c[l], atol=1e-14)
+        assert np.allclose(g, h, atol=1e-14)
+
+
+def test_parakeet_shape_has_the_papers_parameter_count():
+    # Introduction: prediction and joint networks together hold about 8.9 million parameters
+    assert param_count(synth.CONFIGS[2]["dims"]) == 8_943_105
+    assert param_count(synth.CONFIGS[4]["dims"]) == 8_946_310
+    assert param_count(synth.CONFIGS[0]["dims"]) == 43_793
+    assert param_count(synth.CONFIGS[1]["dims"]) == 1_171_457
+
+
+def test_start_of_sequence_is_a_zero_embedding():
+    for cfg in range(5):
+        c = synth.CONFIGS[cfg]
+        m = make_model(c["dims"], c["seed"], **c["model_kw"]) if cfg < 2 else None
+        if m is not None:
+            assert np.all(m.emb[m.dims.blank] == 0)
+
+
+def decode_all(w, real="float", **kw):
+    net = oracle.LstmNet(w.model, real)
+    scheds = ["label", "seq"] if w.model.dims.D else ["frame", "label", "seq"]
+    return {s: oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, s, record=True, **kw)
+            for s in scheds}
+
+
+def assert_same(a, b):
+    assert np.array_equal(a.tok_len, b.tok_len)
+    assert np.array_equal(a.raw_tokens, b.raw_tokens)
+    for i in range(len(a.tokens)):
+        assert np.array_equal(a.frames[i], b.frames[i])
+        assert np.array_equal(a.scores[i], b.scores[i])      # bit-identical logits
+        assert np.array_equal(a.durs[i], b.durs[i])
+        assert np.array_equal(a.records.t[i], b.records.t[i])
+        assert np.array_equal(a.records.margin[i], b.records.margin[i])
+
+
+def check_invariants(w, r, S):
+    blank = w.model.dims.blank
+    for b in range(w.B):
+        n = int(min(max(w.enc_len[b], 0), w.T))
+        assert r.tok_len[b] <= S * n
+        fr = r.frames[b]
+        assert np.all(np.diff(fr) >= 0)
+        if len(fr):
+            assert fr.max() < n and np.bincount(fr).max() <= S
+        assert np.all(r.tokens[b] != blank) and np.all(r.tokens[b] >= 0)
+        if not w.model.dims.D:
+            per_frame = np.bincount(fr, minlength=n) if n else np.zeros(0, int)
+            forced = int((per_frame == S).sum())
+            assert len(r.records.k[b]) == n + r.tok_len[b] - forced
+
+
+@pytest.mark.parametrize("cfg,kw", [
+    (0, {}),
+    (1, {}),
+    (2, dict(B=6, T=40, len_lo=15, len_hi=40)),
+    (4, dict(B=6, T=60, len_lo=20, len_hi=60)),
+])
+def test_schedules_agree_bit_for_bit(cfg, kw):
+    """Frame looping, label looping and the per-utterance decode give identical
+    tokens, frames and scores (the paper's exactness claim), with NaN padding."""
+    w = synth.make_workload(cfg, pad="nan", **kw)
+    rs = decode_all(w)
+    for s, r in rs.items():
+        assert r.status == 0
+        assert_same(r, rs["seq"])
+        check_invariants(w, r, w.max_symbols)
+    assert rs["seq"].tok_len.sum() > 0
+
+
+def test_frame_looping_masked_rows_do_not_matter():
+    """Algorithm 1 also runs the networks on rows that are already masked;
+    their results are discarded, so evaluating them changes nothing."""
+    w = synth.make_workload(1, pad="normal", T=60, len_lo=20, len_hi=60)
+    net = oracle.LstmNet(w.model)
+    a = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "frame", record=True)
+    b = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "frame", record=True,
+                      eval_masked=True)
+    assert_same(a, b)
+    assert b.stats["pred_rows"] == b.stats["inner"] * w.B > a.stats["pred_rows"]
+
+
+def test_batch_row_equals_single_utterance_and_permutation():
+    w = synth.make_workload(1, pad="nan", T=50, len_lo=10, len_hi=50)
+    net = oracle.LstmNet(w.model)
+    perm = np.random.default_rng(3).permutation(w.B)
+    for sched in ["frame", "label", "seq"]:
+        full = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, sched)
+        shuf = oracle.decode(net, w.enc_out[perm], w.enc_len[perm], w.max_symbols, sched)
+        for i, b in enumerate(perm):
+            assert np.array_equal(shuf.tokens[i], full.tokens[b])
+        for b in range(w.B):
+            one = oracle.decode(net, w.enc_out[b:b + 1], w.enc_len[b:b + 1], w.max_symbols, sched)
+            assert np.array_equal(one.tokens[0], full.tokens[b])
+            assert np.array_equal(one.scores[0], full.scores[b])
+
+
+def test_tdt_batch_row_equals_single_utterance():
+    w = synth.make_workload(4, pad="nan", B=5, T=50, len_lo=10, len_hi=50)
+    net = oracle.LstmNet(w.model)
+    full = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "tdt")
+    for b in range(w.B):
+        one = oracle.decode(net, w.enc_out[b:b + 1], w.enc_len[b:b + 1], w.max_symbols, "tdt")
+        assert np.array_equal(one.tokens[0], full.tokens[b])
+        assert np.array_equal(one.durs[0], full.durs[b])
+
+
+@pytest.mark.parametrize("sched", ["frame", "label", "seq"])
+def test_all_blank_and_never_blank_closed_forms(sched):
+    S = 3
+    w = synth.make_workload(1, T=30, len_lo=5, len_hi=30, model_overrides=dict(blank_bias=1e4))
+    net = oracle.LstmNet(w.model)
+    r = oracle.decode(net, w.enc_out, w.enc_len, S, sched, record=True)
+    assert np.all(r.tok_len == 0)
+    assert [len(k) for k in r.records.k] == w.enc_len.tolist()   # one evaluation per frame
+    w = synth.make_workload(1, T=30, len_lo=5, len_hi=30, model_overrides=dict(blank_bias=-1e4))
+    net = oracle.LstmNet(w.model)
+    r = oracle.decode(net, w.enc_out, w.enc_len, S, sched, record=True)
+    assert r.tok_len.tolist() == (S * w.enc_len).tolist()
+    for b in range(w.B):
+        assert r.frames[b].tolist() == np.repeat(np.arange(w.enc_len[b]), S).tolist()
+
+
+def test_max_symbols_one_gives_at_most_one_label_per_frame():
+    w = synth.make_workload(1, T=60, len_lo=20, len_hi=60)
+    net = oracle.LstmNet(w.model)
+    for sched in ["frame", "label", "seq"]:
+        r = oracle.decode(net, w.enc_out, w.enc_len, 1, sched, record=True)
+        for b in range(w.B):
+            assert len(set(r.frames[b].tolist())) == len(r.frames[b])
+            assert len(r.records.k[b]) == w.enc_len[b]
+
+
+def tdt_from(cfg_kw, dur_bias):
+    return synth.make_workload(4, B=4, T=50, len_lo=20, len_hi=50,
+                               model_overrides=dict(dur_bias=dur_bias), **cfg_kw)
+
+
+def test_tdt_reduces_to_rnnt_when_duration_is_pinned():
+    """Duration head forced to 0: TDT is RNN-T with the same token weights.
+    Forced to 1: RNN-T with max_symbols = 1."""
+    big = 1e4
+    w0 = tdt_from({}, (big, 0, 0, 0, 0))
+    w1 = tdt_from({}, (0, big, 0, 0, 0))
+    m = w0.model
+    V1 = m.dims.V1
+    rn_dims = synth.ModelDims(F=m.dims.F, E=m.dims.E, H=m.dims.H, L=m.dims.L, J=m.dims.J, V1=V1)
+    rn = synth.Model(rn_dims, m.emb, m.w_ih, m.w_hh, m.b_ih, m.b_hh, m.w_enc, m.b_enc,
+                     m.w_pred, m.b_pred, m.w_out[:V1].copy(), m.b_out[:V1].copy(),
+                     np.zeros(0, np.int32))
+    rnet = oracle.LstmNet(rn)
+    for sched in ["label", "seq"]:
+        S = w0.max_symbols
+        t0 = oracle.decode(oracle.LstmNet(w0.model), w0.enc_out, w0.enc_len, S, sched)
+        r0 = oracle.decode(rnet, w0.enc_out, w0.enc_len, S, sched)
+        assert np.array_equal(t0.raw_tokens, r0.raw_tokens) and t0.tok_len.sum() > 0
+        assert all(np.all(d == 0) for d in t0.durs)
+        t1 = oracle.decode(oracle.LstmNet(w1.model), w1.enc_out, w1.enc_len, S, sched)
+        r1 = oracle.decode(rnet, w1.enc_out, w1.enc_len, 1, sched)
+        assert np.array_equal(t1.tok_len, r1.tok_len)
+        for b in range(w1.B):
+            assert np.array_equal(t1.tokens[b], r1.tokens[b])
+            assert np.array_equal(t1.frames[b], r1.frames[b])
+
+
+def test_float_and_double_builds_agree_away_from_ties():
+    w = synth.make_workload(1, T=80, len_lo=40, len_hi=80)
+    f32 = oracle.decode(oracle.LstmNet(w.model, "float"), w.enc_out, w.enc_len,
+                        w.max_symbols, "seq", record=True)
+    f64 = oracle.decode(oracle.LstmNet(w.model, "double"), w.enc_out, w.enc_len,
+                        w.max_symbols, "seq", record=True)
+    for b in range(w.B):
+        if f32.records.margin[b].min() > 1e-5:
+            assert np.array_equal(f32.tokens[b], f64.tokens[b])
+            assert np.allclose(f32.scores[b], f64.scores[b], rtol=1e-5, atol=1e-5)
+
+
+def test_follow_reports_departures():
+    w = synth.make_workload(1, T=40, len_lo=30, len_hi=40)
+    net = oracle.LstmNet(w.model)
+    r = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "seq")
+    b = int(np.argmax(r.tok_len))
+    ok = oracle.follow(net, w.enc_out[b], w.enc_len[b], w.max_symbols, r.tokens[b], r.frames[b])
+    assert ok.departures == 0 and ok.worst_gap == 0.0
+    toks = r.tokens[b].copy()
+    toks[1] = (toks[1] + 1) % w.model.dims.blank
+    bad = oracle.follow(net, w.enc_out[b], w.enc_len[b], w.max_symbols, toks, r.frames[b])
+    assert bad.departures >= 1 and bad.worst_gap > 0
+    assert bad.where[0]["u"] == 1 and bad.where[0]["want"] == int(r.tokens[b][1])
+    # a hypothesis no walk can produce: a frame index beyond the utterance
+    fr = r.frames[b].copy()
+    fr[-1] = w.enc_len[b] + 3
+    assert oracle.follow(net, w.enc_out[b], w.enc_len[b], w.max_symbols, r.tokens[b], fr).departures == -1
+
+
+def test_stored_oracle_tokens_are_reproduced():
+    """tests/golden/oracle_tokens.json was written by tests/golden/make_golden.py
+    from the oracle alone; a change in the generator or the oracle shows here."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mg = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mg)
+    with open(os.path.join(here, "golden", "oracle_tokens.json")) as fh:
+        stored = json.load(fh)
+    for name, case in mg.CASES.items():
+        assert mg.run(case) == stored[name], name
