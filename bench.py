@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the RNN-T greedy-decoding hot path on one MI355X.
+
+A step is one whole decode call (encoder-side joint projection + persistent
+decode kernel) over the Parakeet-RNN-T-1.1B-shaped synthetic batch (B = 32,
+T ~ U[200, 500], F = 1024), inputs and packed weights resident in HBM.  Prints
+one JSON line: frames/s with the roofline of the decode kernel and the CPU
+oracle timed on the host cores beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--variant frame|label|tdt]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(dims, B, variant, enc_len, tok_frames, S):
+    """Bytes the method must touch per launch: every weight once per batched
+    step of the schedule (Algorithm 1 / label looping run on the whole batch),
+    recurrent state read and written, embedding and projected-frame rows."""
+    H, L, J, E, nout = dims.H, dims.L, dims.J, dims.E, dims.n_out
+    lstm_w = sum(4 * H * ((E if l == 0 else H) + H) + 8 * H for l in range(L))
+    pred_bytes = 4 * (lstm_w + J * H + J) + 4 * (2 * L * 2 * B * H) + 4 * B * E
+    joint_bytes = 4 * (nout * J + nout) + 4 * B * J
+    counts = [np.bincount(f, minlength=int(n))[:int(n)] if int(n) else np.zeros(0, int)
+              for f, n in zip(tok_frames, enc_len)]
+    tok = np.array([len(f) for f in tok_frames])
+    if variant == "frame":
+        steps = 0
+        for t in range(int(enc_len.max())):
+            per_row = [min(S, int(c[t]) + 1) for c, n in zip(counts, enc_len) if t < n]
+            steps += max(per_row)
+        pred_steps, joint_steps = steps, steps      # prediction() runs at every inner step
+    else:
+        pred_steps = int(tok.max()) + 1
+        if variant == "tdt":
+            joint_steps = int(tok.max()) + 1        # lower bound: one evaluation per label
+        else:
+            forced = np.array([int((c == S).sum()) for c in counts])
+            joint_steps = int((enc_len + tok - forced).max())
+    return pred_steps * pred_bytes + joint_steps * joint_bytes, pred_steps, joint_steps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--variant", default="frame", choices=["frame", "label", "tdt"])
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-variants", action="store_true",
+                    help="also time the other decoders and list them under 'variants'")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the batch shards with no exchange; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2406_03791_amd as pkg
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    pkg.load_library()
+
+    def run_variant(variant, steps, warmup):
+        cfg = {"frame": 2, "label": 3, "tdt": 4}[variant]
+        w = synth.make_workload(cfg, B=args.batch)
+        eng = pkg.Engine(w.model, w.B, w.T)
+        enc = torch.from_numpy(w.enc_out).cuda().contiguous()
+        ln = torch.from_numpy(w.enc_len).cuda()
+        out = eng.alloc_outputs(w.B, w.T * w.max_symbols)
+        for _ in range(warmup):
+            eng.decode(variant, enc, ln, w.max_symbols, out=out)
+        torch.cuda.synchronize()
+        dec_ms, proj_ms = [], []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            eng.decode(variant, enc, ln, w.max_symbols, out=out)
+            # the stats call waits for the device: each step is timed on its own events
+            st = eng.stats()
+            dec_ms.append(st["decode_ms"])
+            proj_ms.append(st["projection_ms"])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        status = eng.status()
+        tok_len = out["tok_len"].cpu().numpy()
+        frames = [out["frames"][b, :tok_len[b]].cpu().numpy() for b in range(w.B)]
+        tokens = [out["tokens"][b, :tok_len[b]].cpu().numpy() for b in range(w.B)]
+        res = dict(w=w, wall=wall, steps=steps, dec_ms=float(np.mean(dec_ms)),
+                   proj_ms=float(np.mean(proj_ms)), dec_ms_min=float(np.min(dec_ms)), stats=st,
+                   status=status, frames=frames, tokens=tokens, tok_len=tok_len)
+        eng.close()
+        return res
+
+    r = run_variant(args.variant, args.steps, args.warmup)
+    w = r["w"]
+    n_frames = w.frames
+    ms_per_step = 1e3 * r["wall"] / r["steps"]
+    value = n_frames * r["steps"] / r["wall"]
+    alg_bytes, pred_steps, joint_steps = algorithmic_bytes(
+        w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols)
+    achieved = alg_bytes / (r["dec_ms"] * 1e-3) / 1e9
+    line = {
+        "metric": "encoder frames decoded/sec, Parakeet-1.1B decoder shape, B=32",
+        "value": value, "unit": "frames/s", "n_gpus": 1, "steps": r["steps"],
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "us_per_frame": 1e6 / value,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config {dict(frame=2, label=3, tdt=4)[args.variant]}: "
+                               f"{w.name}, B={w.B}, T<={w.T}, frames={n_frames}, "
+                               f"max_symbols={w.max_symbols}, variant={args.variant}",
+                   "tokens": int(r["tok_len"].sum()), "device_status": r["status"],
+                   "kernel_ms": {"decode": r["dec_ms"], "decode_min": r["dec_ms_min"],
+                                 "encoder_projection": r["proj_ms"]},
+                   "engine": r["stats"]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "decode_kernel", "algorithmic_bytes": alg_bytes,
+                     "schedule_steps": {"prediction": pred_steps, "joint": joint_steps}},
+    }
+    if args.all_variants:
+        line["variants"] = {}
+        for v in ("frame", "label", "tdt"):
+            if v == args.variant:
+                continue
+            rv = run_variant(v, max(3, args.steps // 2), 2)
+            line["variants"][v] = {"frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"],
+                                   "decode_ms": rv["dec_ms"], "status": rv["status"]}
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = min(16, os.cpu_count() or 1)
+        net = oracle.LstmNet(w.model)
+        sched = "seq"
+        t0 = time.perf_counter()
+        ref = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, sched, n_threads=cores)
+        dt = time.perf_counter() - t0
+        same = sum(int(np.array_equal(ref.tokens[b], r["tokens"][b])) for b in range(w.B))
+        line["cpu_baseline"] = {"value": n_frames / dt, "unit": "frames/s", "cores": cores,
+                                "kind": "oracle",
+                                "sample": f"the whole batch once ({w.B} utterances, {n_frames} "
+                                          f"frames), per-utterance decode, one utterance per "
+                                          f"thread, {dt:.2f} s wall",
+                                "rows_token_identical_to_gpu": same}
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

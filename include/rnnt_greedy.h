@@ -1,0 +1,200 @@
+/*
+ * rnnt_greedy.h -- C ABI of the MI355X (gfx950) engine for exact batched
+ * RNN-T / TDT greedy decoding.
+ *
+ * The library runs the whole data-dependent decoding loop of the paper
+ * "Speed of Light Exact Greedy Decoding for RNN-T Speech Recognition Models on
+ * GPU" on the device: one launch of the encoder-side joint projection and one
+ * launch of a persistent decode kernel per call, no host round trip per step
+ * (the paper's Section "Algorithm Implementation" explains why the per-step
+ * host contact is what makes the baseline slow).
+ *
+ * Conventions
+ *   - All pointers named in rnnt_model_desc and all tensor arguments of the
+ *     decode calls are DEVICE pointers unless marked HOST.  fp32, row-major.
+ *   - Linear and LSTM weights are [out, in]; LSTM gate order along `out` is
+ *     input, forget, cell, output (i, f, g, o); two bias vectors per layer.
+ *   - The caller owns every buffer it passes and keeps it alive until the work
+ *     queued on `stream` has finished.  The engine owns its packed copy of the
+ *     weights and its workspace; decode calls allocate nothing.
+ *   - Decode calls only enqueue work on `stream` and return; they never wait
+ *     for the device and never read device memory from the host.
+ *   - One engine serves one call at a time (shared workspace): calls on the
+ *     same engine must be ordered by the caller (same stream or events).
+ *   - Return value: RNNT_OK (0) or a negative RNNT_ERR_* code, detected on the
+ *     host before anything is queued.  Conditions only the device can see are
+ *     reported through rnnt_engine_status().
+ */
+#ifndef RNNT_GREEDY_H
+#define RNNT_GREEDY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rnnt_engine rnnt_engine;
+/* A hipStream_t, passed as an opaque pointer so this header needs no HIP. */
+typedef void *rnnt_stream_t;
+
+enum {
+    RNNT_OK = 0,
+    RNNT_ERR_NULL = -1,        /* a required pointer is NULL                   */
+    RNNT_ERR_SHAPE = -2,       /* a dimension or count is out of range         */
+    RNNT_ERR_VARIANT = -3,     /* RNN-T call on a TDT engine or the reverse    */
+    RNNT_ERR_HIP = -4,         /* a HIP runtime call failed                    */
+    RNNT_ERR_UNSUPPORTED = -5  /* the device or the model does not fit         */
+};
+
+/* Bits of the device status word (rnnt_engine_status). */
+enum {
+    RNNT_DEV_LEN_CLAMPED = 1,   /* some enc_len[b] was outside [0, T]           */
+    RNNT_DEV_OVERFLOW = 2,      /* more tokens than `cap`; the excess is dropped */
+    RNNT_DEV_ABORTED = 4        /* a bounded wait expired: outputs are invalid   */
+};
+
+/* Flags of rnnt_engine_create. */
+enum {
+    RNNT_FLAG_DEFAULT = 0
+};
+
+/*
+ * The decoder's weights (prediction network = embedding + L stacked LSTM
+ * layers; joint = W_out relu(W_enc f + b_enc + W_pred g + b_pred) + b_out,
+ * the structure behind the paper's prediction() and joint() in Algorithm 1).
+ * HOST struct holding DEVICE pointers; everything is copied and repacked by
+ * rnnt_engine_create, so the struct and the weights may be freed afterwards.
+ */
+typedef struct rnnt_model_desc {
+    int32_t F;       /* encoder output features                                */
+    int32_t E;       /* embedding width                                        */
+    int32_t H;       /* LSTM hidden width                                      */
+    int32_t L;       /* LSTM layers (1..4)                                     */
+    int32_t J;       /* joint hidden width                                     */
+    int32_t V1;      /* vocabulary size including blank                        */
+    int32_t blank;   /* blank index in [0, V1); also the start-of-sequence     */
+                     /* label fed to the prediction network first              */
+    int32_t D;       /* number of durations: 0 = RNN-T, >0 = TDT (at most 8)   */
+    const int32_t *durations;      /* HOST, [D], e.g. {0,1,2,3,4}              */
+    const float *emb;              /* [V1, E]                                  */
+    const float *const *w_ih;      /* HOST array of L device pointers [4H,in_l] */
+    const float *const *w_hh;      /* HOST array of L device pointers [4H, H]  */
+    const float *const *b_ih;      /* HOST array of L device pointers [4H]     */
+    const float *const *b_hh;      /* HOST array of L device pointers [4H]     */
+    const float *w_enc, *b_enc;    /* [J, F], [J]                              */
+    const float *w_pred, *b_pred;  /* [J, H], [J]                              */
+    const float *w_out, *b_out;    /* [V1 + D, J], [V1 + D]; token logits      */
+                                   /* first, then the D duration logits        */
+} rnnt_model_desc;
+
+/* Work counters of the last decode call (rnnt_engine_stats). */
+typedef struct rnnt_stats {
+    int64_t pred_steps;   /* batched prediction-network steps, summed over teams */
+    int64_t joint_steps;  /* batched joint steps (chunks), summed over teams     */
+    int64_t max_pred_steps;   /* the same, for the team that did the most        */
+    int64_t max_joint_steps;
+    int64_t joint_samples;    /* (utterance, frame) pairs the joint evaluated    */
+    int64_t barrier_polls;    /* polls spent in team barriers                    */
+    int32_t n_teams;          /* work-group teams used by the call               */
+    int32_t team_size;        /* work-groups per team                            */
+    int32_t lookahead;        /* frames examined per utterance per joint step    */
+    int32_t xcd_mismatch;     /* teams whose work-groups were not on one XCD     */
+    float projection_ms;      /* device time of the encoder-projection kernel    */
+    float decode_ms;          /* device time of the persistent decode kernel,    */
+                              /* both from HIP events recorded on the call's     */
+                              /* stream around each launch                       */
+} rnnt_stats;
+
+/*
+ * Create an engine for up to max_B utterances of up to max_T frames.
+ * Copies and repacks the weights on the current device, allocates the
+ * workspace (projected frames [max_B, max_T, J], state, exchange buffers).
+ * Synchronous.  *out is set only on success.
+ */
+int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T,
+                       int32_t flags, rnnt_engine **out);
+
+/* Free the engine's device memory.  Synchronises the device first. */
+int rnnt_engine_destroy(rnnt_engine *eng);
+
+/*
+ * Frame-looping greedy decoding: Algorithm 1 of the paper.  An outer loop over
+ * frames shared by the utterances of a team, an inner loop of at most
+ * max_symbols steps that ends when every utterance has produced a blank.
+ *
+ *   enc_out     [B, T, F]   encoder output; frames t >= enc_len[b] are padding
+ *                           and may hold anything, NaN included
+ *   enc_len     [B]         valid frames per utterance; values outside [0, T]
+ *                           are clamped on the device (RNNT_DEV_LEN_CLAMPED)
+ *   tokens_out  [B, cap]    emitted labels in order; entries at and beyond
+ *                           tok_len_out[b] are set to -1
+ *   tok_len_out [B]         number of labels emitted (counts labels dropped
+ *                           for lack of room too; cap >= T * max_symbols
+ *                           always suffices)
+ *   frames_out  [B, cap]    or NULL: frame index of each label
+ *   logit_out   [B, cap]    or NULL: the winning (maximum) token logit
+ * Errors: RNNT_ERR_NULL, RNNT_ERR_SHAPE (B, T outside the engine's limits,
+ * max_symbols < 1, cap < 1), RNNT_ERR_VARIANT on a TDT engine.
+ */
+int rnnt_greedy_decode(rnnt_engine *eng, const float *enc_out, const int32_t *enc_len,
+                       int32_t B, int32_t T, int32_t max_symbols,
+                       int32_t *tokens_out, int32_t *tok_len_out, int32_t cap,
+                       int32_t *frames_out, float *logit_out, rnnt_stream_t stream);
+
+/*
+ * Label-looping greedy decoding (the schedule described at the end of the
+ * paper's Related Work section: every utterance advances its own frame index,
+ * the outer loop runs once per label, the inner loop skips blanks).  Same
+ * arguments and the same outputs, token for token, as rnnt_greedy_decode.
+ */
+int rnnt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int32_t *enc_len,
+                              int32_t B, int32_t T, int32_t max_symbols,
+                              int32_t *tokens_out, int32_t *tok_len_out, int32_t cap,
+                              int32_t *frames_out, float *logit_out, rnnt_stream_t stream);
+
+/*
+ * Label-looping decoding of a token-and-duration transducer (the TDT rows of
+ * the paper's Table 1): the argmax over the D duration logits advances the
+ * frame index; a blank advances it by at least one frame; a label with
+ * duration 0 stays on the frame, at most max_symbols times in a row.
+ *   durations_out [B, cap] or NULL: duration value of each label.
+ * RNNT_ERR_VARIANT on an engine created with D == 0.
+ */
+int tdt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int32_t *enc_len,
+                             int32_t B, int32_t T, int32_t max_symbols,
+                             int32_t *tokens_out, int32_t *tok_len_out, int32_t cap,
+                             int32_t *frames_out, float *logit_out, int32_t *durations_out,
+                             rnnt_stream_t stream);
+
+/*
+ * The encoder-side joint projection alone (W_enc f + b_enc for every valid
+ * frame), the part of joint() in Algorithm 1 that does not depend on the
+ * prediction network and is therefore taken out of the loop.
+ *   proj_out [B, T, J]; rows at t >= enc_len[b] are left untouched.
+ */
+int rnnt_encoder_projection(rnnt_engine *eng, const float *enc_out, const int32_t *enc_len,
+                            int32_t B, int32_t T, float *proj_out, rnnt_stream_t stream);
+
+/* Device status word of the last decode call (RNNT_DEV_* bits).  Waits for
+ * the device.  *status_out is HOST memory. */
+int rnnt_engine_status(rnnt_engine *eng, int32_t *status_out);
+
+/* Work counters of the last decode call.  Waits for the device.  HOST out. */
+int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out);
+
+/*
+ * Tuning knobs, for measurement: number of teams (0 = chosen from B),
+ * lookahead frames per joint step in the label-looping calls (0 = chosen from
+ * the rows per team; 1 = one frame per step).  Returns RNNT_ERR_SHAPE for
+ * values the engine cannot run.
+ */
+int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t lookahead);
+
+/* Text for a return code; for RNNT_ERR_HIP includes the last HIP error text. */
+const char *rnnt_status_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNNT_GREEDY_H */

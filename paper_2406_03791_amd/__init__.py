@@ -1,0 +1,24 @@
+"""MI355X (gfx950) engine for exact batched RNN-T / TDT greedy decoding.
+
+The package is a thin binding over the C ABI in include/rnnt_greedy.h
+(librnnt_greedy.so, built from csrc/ by build.py): the functions below carry the
+C names and only marshal arguments; every step of the decode runs in the HIP
+kernels.  There is no fallback: importing fails if the library is not built.
+"""
+from .binding import (  # noqa: F401
+    Engine,
+    RnntError,
+    RnntStats,
+    lib_path,
+    load_library,
+    rnnt_encoder_projection,
+    rnnt_engine_configure,
+    rnnt_engine_create,
+    rnnt_engine_destroy,
+    rnnt_engine_stats,
+    rnnt_engine_status,
+    rnnt_greedy_decode,
+    rnnt_label_looping_decode,
+    rnnt_status_string,
+    tdt_label_looping_decode,
+)

@@ -1,0 +1,685 @@
+// Persistent decode kernel for exact RNN-T / TDT greedy decoding on gfx950.
+//
+// One launch runs the whole data-dependent double loop of Algorithm 1 (or of
+// its label-looping form) on the device.  The work-groups form independent
+// teams, each on one XCD when the dispatcher deals work-groups round-robin over
+// the XCDs; a team owns a subset of the utterances and runs the loops for them
+// with its own barrier, so no team ever waits for another.  Inside a team every
+// dense stage is split over the ranks by output columns and exchanged through
+// small global buffers; the loop control (blank mask, symbols_added, not_blank,
+// per-utterance frame index) is recomputed identically by every rank from the
+// exchanged argmax results, so there is no controller rank and no flag to wait
+// for besides the barrier itself.
+#include "engine.h"
+
+namespace rnnt {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct Ctl {
+    int b[kMaxRows], len[kMaxRows], t[kMaxRows], n[kMaxRows], last[kMaxRows];
+    int cnt[kMaxRows], sel[kMaxRows], active[kMaxRows], searching[kMaxRows], mask[kMaxRows];
+    int hold_k[kMaxRows], hold_d[kMaxRows];
+    float hold_v[kMaxRows];
+    int s_row[kMaxSamples], s_frame[kMaxSamples], s_valid[kMaxSamples];
+    int s_k[kMaxSamples], s_d[kMaxSamples];
+    float s_v[kMaxSamples];
+    int R, ns, any, status, bar_ok, committed;
+    int durations[kMaxDur];
+};
+
+// Values other work-groups will read go through device-scope atomics so that
+// they are written through to, and read from, the level all XCDs share.
+__device__ __forceinline__ void xstore(float *p, float v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned *>(p), __float_as_uint(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float xload(const float *p)
+{
+    return __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned *>(p),
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void xstore64(unsigned long long *p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long xload64(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct Wg {
+    int team, rank, tid, lane, wave;
+    unsigned epoch;
+    long long polls;
+};
+
+// Team barrier with a bounded wait.  Returns false when the wait expired or
+// another work-group raised the abort flag; the caller then leaves the kernel.
+__device__ __forceinline__ bool team_barrier(const DecodeParams &p, Wg &w, Ctl &c)
+{
+    __threadfence();
+    __syncthreads();
+    w.epoch += 1;
+    if (w.tid == 0) {
+        unsigned *ctr = p.bar + w.team * 32;
+        const unsigned target = w.epoch * (unsigned)p.team_size;
+        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned spins = 0;
+        int ok = 1;
+        while (__hip_atomic_load(ctr, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            ++spins;
+            if ((spins & 127u) == 0 &&
+                __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                ok = 0;
+                break;
+            }
+            if (spins > p.spin_limit) {
+                __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        w.polls += spins;
+        c.bar_ok = ok;
+    }
+    __syncthreads();
+    return c.bar_ok != 0;
+}
+
+// One dense stage for this rank:  red[task][rg][col][row] = sum over the task's
+// K slice of x[row][k] * W[col][k], rows in groups of 4 (RG groups).
+//   x            LDS, rows `xstride` floats apart; input vector `inp` of a group
+//                starts `x_inp_stride` floats further (inp = group / groups_per_inp)
+//   n_tasks      groups owned by this rank * nks
+//   red_aliases_x  the results overwrite x (only valid with a single slot)
+template <int RG>
+__device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n_tasks,
+                                          const float *x, int xstride, int x_inp_stride,
+                                          int groups_per_inp, float *red, bool red_aliases_x)
+{
+    const int blk = w.lane >> 2, r4 = w.lane & 3;
+    for (int slot = 0; slot < sd.slots; ++slot) {
+        const int task = slot * kBlocksPerWg + w.wave * 16 + blk;
+        const bool live = task < n_tasks;
+        const int g = live ? task / sd.nks : 0;
+        const int ks = live ? task - g * sd.nks : 0;
+        const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * 4;
+        const float4 *wp = sd.w + (long long)w.rank * sd.rank_stride +
+                           ((long long)(slot * kWaves + w.wave) * sd.nsteps) * 64 + w.lane;
+        v4f acc[RG];
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){0.f, 0.f, 0.f, 0.f};
+        float4 nxt[kStepUnroll];
+#pragma unroll
+        for (int u = 0; u < kStepUnroll; ++u)
+            nxt[u] = live ? wp[u * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < sd.nsteps; i += kStepUnroll) {
+            float4 cur[kStepUnroll];
+#pragma unroll
+            for (int u = 0; u < kStepUnroll; ++u) cur[u] = nxt[u];
+            if (live && i + kStepUnroll < sd.nsteps) {
+#pragma unroll
+                for (int u = 0; u < kStepUnroll; ++u) nxt[u] = wp[(i + kStepUnroll + u) * 64];
+            }
+#pragma unroll
+            for (int u = 0; u < kStepUnroll; ++u) {
+#pragma unroll
+                for (int rg = 0; rg < RG; ++rg) {
+                    const float4 xv =
+                        *reinterpret_cast<const float4 *>(xr + rg * 4 * xstride + (i + u) * 4);
+                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.x, cur[u].x, acc[rg], 0, 0, 0);
+                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.y, cur[u].y, acc[rg], 0, 0, 0);
+                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.z, cur[u].z, acc[rg], 0, 0, 0);
+                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.w, cur[u].w, acc[rg], 0, 0, 0);
+                }
+            }
+        }
+        // when the partial sums reuse the memory of x, wait until every wave has read x
+        if (red_aliases_x) __syncthreads();
+        if (live) {
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                float4 o = make_float4(acc[rg][0], acc[rg][1], acc[rg][2], acc[rg][3]);
+                *reinterpret_cast<float4 *>(red + ((task * RG + rg) * 4 + r4) * 4) = o;
+            }
+        }
+    }
+}
+
+// Sum of the K-slice partials of (group g, row, column j).
+template <int RG>
+__device__ __forceinline__ float reduce_tasks(const float *red, int nks, int g, int row, int j)
+{
+    float s = 0.f;
+    for (int ks = 0; ks < nks; ++ks)
+        s += red[(((g * nks + ks) * RG + (row >> 2)) * 4 + j) * 4 + (row & 3)];
+    return s;
+}
+
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+struct Lds {
+    float *xz, *red, *c, *part;
+    float *cand_v;
+    int *cand_i;
+    float *dcand_v;
+    int *dcand_i;
+};
+
+// c state of this rank's units: [layer][sel][unit][row]
+__device__ __forceinline__ float *c_slot(const DecodeParams &p, const Lds &l, int layer, int sel,
+                                         int u, int row)
+{
+    return l.c + ((layer * 2 + sel) * p.nu_max + u) * kMaxRows + row;
+}
+__device__ __forceinline__ float *h_slot(const DecodeParams &p, int team, int sel, int layer,
+                                         int row)
+{
+    return p.hbuf + ((((long long)team * 2 + sel) * p.L + layer) * kMaxRows + row) * p.H;
+}
+
+// Fill RG*4 activation rows of `len` floats each into LDS from a global exchange
+// buffer; the tail up to kpad and the rows beyond R are zero.
+__device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, const Ctl &c, float *dst, int rows_pad,
+                          int len, int kpad, int layer, bool candidate)
+{
+    for (int idx = w.tid; idx < rows_pad * kpad; idx += kThreads) {
+        const int r = idx / kpad, k = idx - r * kpad;
+        float v = 0.f;
+        if (r < c.R && k < len) {
+            const int sel = candidate ? (c.sel[r] ^ 1) : c.sel[r];
+            v = xload(h_slot(p, w.team, sel, layer, r) + k);
+        }
+        dst[r * p.xstride + k] = v;
+    }
+}
+
+__device__ __forceinline__ void lstm_point(float gi, float gf, float gg, float go, float c_old,
+                                           float &c_new, float &h_new)
+{
+    const float i_ = sigmoidf_(gi), f_ = sigmoidf_(gf), g_ = tanhf(gg), o_ = sigmoidf_(go);
+    c_new = f_ * c_old + i_ * g_;
+    h_new = o_ * tanhf(c_new);
+}
+
+// One prediction-network step for all rows of the team, from (last, committed
+// state) to the candidate state and q = W_pred h'_top + b_pred.
+template <int RG>
+__device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ctl &c, const Lds &l)
+{
+    const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
+    const int rows_pad = RG * 4;
+    const int inp_stride = rows_pad * p.xstride;
+    // stage 0: recurrent parts of every layer, layer 0 completes
+    for (int layer = 0; layer < p.L; ++layer)
+        fill_rows(p, w, c, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
+    __syncthreads();
+    run_stage<RG>(p.st0, w, p.L * nu * p.st0.nks, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1, l.red, false);
+    __syncthreads();
+    for (int e = w.tid; e < p.L * nu * c.R; e += kThreads) {
+        const int layer = e / (nu * c.R);
+        const int rem = e - layer * nu * c.R;
+        const int u = rem / c.R, r = rem - u * c.R;
+        const int g = layer * nu + u;
+        float a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = reduce_tasks<RG>(l.red, p.st0.nks, g, r, j);
+        if (layer == 0) {
+            const float4 t0 = *reinterpret_cast<const float4 *>(
+                p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
+            float cn, hn;
+            lstm_point(a[0] + t0.x, a[1] + t0.y, a[2] + t0.z, a[3] + t0.w,
+                       *c_slot(p, l, 0, c.sel[r], u, r), cn, hn);
+            *c_slot(p, l, 0, c.sel[r] ^ 1, u, r) = cn;
+            xstore(h_slot(p, w.team, c.sel[r] ^ 1, 0, r) + u0 + u, hn);
+        } else {
+            const float4 bl = *reinterpret_cast<const float4 *>(
+                p.bias_l + ((long long)layer * p.H + (u0 + u)) * 4);
+            float *dst = l.part + ((layer * p.nu_max + u) * kMaxRows + r) * 4;
+            dst[0] = a[0] + bl.x; dst[1] = a[1] + bl.y; dst[2] = a[2] + bl.z; dst[3] = a[3] + bl.w;
+        }
+    }
+    if (!team_barrier(p, w, c)) return false;
+    // stages 1..L-1: input part of layer `layer` from the candidate h of the layer below
+#pragma unroll
+    for (int layer = 1; layer < kMaxLayers; ++layer) {
+        if (layer >= p.L) break;
+        const StageDev &sd = p.stl[layer];
+        fill_rows(p, w, c, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
+        __syncthreads();
+        run_stage<RG>(sd, w, nu * sd.nks, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        __syncthreads();
+        for (int e = w.tid; e < nu * c.R; e += kThreads) {
+            const int u = e / c.R, r = e - u * c.R;
+            float a[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[j] = reduce_tasks<RG>(l.red, sd.nks, u, r, j);
+            const float *pt = l.part + ((layer * p.nu_max + u) * kMaxRows + r) * 4;
+            float cn, hn;
+            lstm_point(a[0] + pt[0], a[1] + pt[1], a[2] + pt[2], a[3] + pt[3],
+                       *c_slot(p, l, layer, c.sel[r], u, r), cn, hn);
+            *c_slot(p, l, layer, c.sel[r] ^ 1, u, r) = cn;
+            xstore(h_slot(p, w.team, c.sel[r] ^ 1, layer, r) + u0 + u, hn);
+        }
+        if (!team_barrier(p, w, c)) return false;
+    }
+    // prediction-side joint projection
+    {
+        const int ng_all = (p.J + 3) / 4;
+        const int g0 = range_lo(w.rank, p.team_size, ng_all);
+        const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
+        fill_rows(p, w, c, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
+        __syncthreads();
+        run_stage<RG>(p.spred, w, ng * p.spred.nks, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        __syncthreads();
+        for (int e = w.tid; e < ng * c.R; e += kThreads) {
+            const int g = e / c.R, r = e - g * c.R;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = (g0 + g) * 4 + j;
+                if (col < p.J) {
+                    const float q = reduce_tasks<RG>(l.red, p.spred.nks, g, r, j) + p.b_pred[col];
+                    xstore(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + col, q);
+                }
+            }
+        }
+        if (!team_barrier(p, w, c)) return false;
+    }
+    return true;
+}
+
+__device__ __forceinline__ unsigned long long pack_cand(float v, int idx)
+{
+    return ((unsigned long long)__float_as_uint(v) << 32) | (unsigned)idx;
+}
+
+// Joint network + argmax for the c.ns samples listed in c.s_row / c.s_frame /
+// c.s_valid.  Leaves c.s_k, c.s_v (token argmax and its logit) and c.s_d
+// (duration index) for every valid sample.
+template <int RG>
+__device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c, const Lds &l, int parity)
+{
+    const int ns = c.ns;
+    const int rows_pad = RG * 4;
+    const int kpad = p.sjoint.kpad;
+    // z = relu(P[b, frame] + q[row]) for every sample
+    for (int idx = w.tid; idx < rows_pad * kpad; idx += kThreads) {
+        const int s = idx / kpad, k = idx - s * kpad;
+        float v = 0.f;
+        if (s < ns && k < p.J && c.s_valid[s]) {
+            const int r = c.s_row[s];
+            const float pe = p.P[((long long)c.b[r] * p.T + c.s_frame[s]) * p.J + k];
+            const float q = xload(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k);
+            v = fmaxf(pe + q, 0.f);
+        }
+        l.xz[s * p.xstride + k] = v;
+    }
+    __syncthreads();
+    const int ng_all = (p.NOUT + 3) / 4;
+    const int g0 = range_lo(w.rank, p.team_size, ng_all);
+    const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
+    // with one slot the partial sums may overwrite z once every wave is done with it
+    const bool alias = p.sjoint.slots == 1;
+    float *red = alias ? l.xz : l.red;
+    run_stage<RG>(p.sjoint, w, ng * p.sjoint.nks, l.xz, p.xstride, 0, 1 << 30, red, alias);
+    __syncthreads();
+    // per (group, sample): best of the group's four columns
+    for (int e = w.tid; e < ng * ns; e += kThreads) {
+        const int g = e / ns, s = e - g * ns;
+        float bv = -INFINITY, dv = -INFINITY;
+        int bi = 0x7fffffff, di = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = (g0 + g) * 4 + j;
+            if (col < p.NOUT) {
+                const float v = reduce_tasks<RG>(red, p.sjoint.nks, g, s, j) + p.b_out[col];
+                if (col < p.V1) { if (v > bv) { bv = v; bi = col; } }
+                else { if (v > dv) { dv = v; di = col - p.V1; } }
+            }
+        }
+        l.cand_v[s * p.gj_max + g] = bv; l.cand_i[s * p.gj_max + g] = bi;
+        l.dcand_v[s * p.gj_max + g] = dv; l.dcand_i[s * p.gj_max + g] = di;
+    }
+    __syncthreads();
+    // this rank's partial per sample (groups ascend, strict > keeps the lowest index)
+    if (w.tid < ns) {
+        const int s = w.tid;
+        float bv = -INFINITY, dv = -INFINITY;
+        int bi = 0x7fffffff, di = 0x7fffffff;
+        for (int g = 0; g < ng; ++g) {
+            const float v = l.cand_v[s * p.gj_max + g];
+            if (v > bv) { bv = v; bi = l.cand_i[s * p.gj_max + g]; }
+            const float d = l.dcand_v[s * p.gj_max + g];
+            if (d > dv) { dv = d; di = l.dcand_i[s * p.gj_max + g]; }
+        }
+        const long long o = (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size + w.rank;
+        xstore64(p.part + o, pack_cand(bv, bi));
+        if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di));
+    }
+    if (!team_barrier(p, w, c)) return false;
+    // final argmax over the ranks, 16 lanes per sample
+    {
+        const int s = w.tid >> 4, sub = w.tid & 15;
+        float bv = -INFINITY, dv = -INFINITY;
+        int bi = 0x7fffffff, di = 0x7fffffff;
+        if (s < ns && c.s_valid[s]) {
+            const long long o = (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size;
+            for (int r = sub; r < p.team_size; r += 16) {
+                const unsigned long long pk = xload64(p.part + o + r);
+                const float v = __uint_as_float((unsigned)(pk >> 32));
+                const int i = (int)(unsigned)pk;
+                if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+                if (p.D > 0) {
+                    const unsigned long long dk = xload64(p.dpart + o + r);
+                    const float d = __uint_as_float((unsigned)(dk >> 32));
+                    const int j = (int)(unsigned)dk;
+                    if (d > dv || (d == dv && j < di)) { dv = d; di = j; }
+                }
+            }
+        }
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, 16);
+            const int oi = __shfl_xor(bi, off, 16);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            const float od = __shfl_xor(dv, off, 16);
+            const int oj = __shfl_xor(di, off, 16);
+            if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
+        }
+        if (s < ns && sub == 0) {
+            // no finite logit (NaN input inside enc_len): fall back to blank, never index out of range
+            if ((unsigned)bi >= (unsigned)p.V1) bi = p.blank;
+            c.s_k[s] = bi; c.s_v[s] = bv; c.s_d[s] = (p.D > 0 && di < p.D) ? di : 0;
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
+__device__ __forceinline__ bool joint_any(const DecodeParams &p, Wg &w, Ctl &c, const Lds &l, int parity)
+{
+    const int rg = (c.ns + 3) >> 2;
+    if (rg <= 1) return joint_step<1>(p, w, c, l, parity);
+    if (rg <= 2) return joint_step<2>(p, w, c, l, parity);
+    if (rg <= 4) return joint_step<4>(p, w, c, l, parity);
+    return joint_step<8>(p, w, c, l, parity);
+}
+
+// Row r emits label k at frame t (rank 0 writes the outputs).
+__device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, Ctl &c, int r, int k,
+                                         int t, float v, int dval)
+{
+    const int n = c.cnt[r];
+    if (w.rank == 0) {
+        if (n < p.cap) {
+            const long long o = (long long)c.b[r] * p.cap + n;
+            p.tokens[o] = k;
+            if (p.frames) p.frames[o] = t;
+            if (p.logits) p.logits[o] = v;
+            if (p.durs) p.durs[o] = dval;
+        } else {
+            atomicOr(&c.status, 2);
+        }
+    }
+    c.cnt[r] = n + 1;
+    c.last[r] = k;
+    c.sel[r] ^= 1;     // the candidate state becomes the state
+}
+
+template <int RG>
+__global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
+{
+    extern __shared__ __align__(16) float dyn_lds[];
+    __shared__ Ctl c;
+    Wg w;
+    w.tid = threadIdx.x; w.lane = w.tid & 63; w.wave = w.tid >> 6;
+    w.team = blockIdx.x % p.n_teams; w.rank = blockIdx.x / p.n_teams;
+    w.epoch = 0; w.polls = 0;
+    Lds l;
+    l.xz = dyn_lds + p.lds_xz; l.red = dyn_lds + p.lds_red; l.c = dyn_lds + p.lds_c;
+    l.part = dyn_lds + p.lds_part;
+    l.cand_v = dyn_lds + p.lds_cand;
+    l.cand_i = reinterpret_cast<int *>(l.cand_v + kMaxSamples * p.gj_max);
+    l.dcand_v = reinterpret_cast<float *>(l.cand_i + kMaxSamples * p.gj_max);
+    l.dcand_i = reinterpret_cast<int *>(l.dcand_v + kMaxSamples * p.gj_max);
+
+    if (w.tid == 0) {
+        // XCC_ID hardware register, bits [3:0]
+        p.xcc[blockIdx.x] = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
+    }
+    // rows of this team: b = team, team + n_teams, ...
+    const int R = (p.B > w.team) ? (p.B - w.team + p.n_teams - 1) / p.n_teams : 0;
+    if (R == 0) return;            // the whole team leaves: no barrier is ever entered
+    if (w.tid == 0) {
+        c.R = R; c.ns = 0; c.bar_ok = 1; c.committed = 0; c.status = 0; c.any = 0;
+#pragma unroll
+        for (int i = 0; i < kMaxDur; ++i) c.durations[i] = p.durations[i];
+    }
+    __syncthreads();
+    if (w.tid < kMaxRows) {
+        const int r = w.tid;
+        int b = 0, len = 0;
+        if (r < R) {
+            b = w.team + r * p.n_teams;
+            len = p.enc_len[b];
+            if (len < 0 || len > p.T) atomicOr(&c.status, 1);
+            len = min(max(len, 0), p.T);
+        }
+        c.b[r] = b; c.len[r] = len; c.t[r] = 0; c.n[r] = 0; c.last[r] = p.blank;
+        c.cnt[r] = 0; c.sel[r] = 0; c.active[r] = (r < R && len > 0); c.searching[r] = 0;
+        c.mask[r] = 1; c.hold_k[r] = 0; c.hold_d[r] = 0; c.hold_v[r] = 0.f;
+    }
+    __syncthreads();
+    // zero state: c of both selectors, committed h of this rank's units
+    const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
+    for (int i = w.tid; i < p.L * 2 * p.nu_max * kMaxRows; i += kThreads) l.c[i] = 0.f;
+    for (int i = w.tid; i < p.L * R * nu; i += kThreads) {
+        const int layer = i / (R * nu), rem = i - layer * R * nu;
+        const int r = rem / nu, u = rem - r * nu;
+        xstore(h_slot(p, w.team, 0, layer, r) + u0 + u, 0.f);
+    }
+    // output fill: every rank clears a share of its team's rows
+    for (int r = 0; r < R; ++r) {
+        const long long o = (long long)c.b[r] * p.cap;
+        for (int i = w.rank * kThreads + w.tid; i < p.cap; i += p.team_size * kThreads) {
+            p.tokens[o + i] = -1;
+            if (p.frames) p.frames[o + i] = -1;
+            if (p.logits) p.logits[o + i] = 0.f;
+            if (p.durs) p.durs[o + i] = -1;
+        }
+    }
+    if (!team_barrier(p, w, c)) return;
+
+    long long n_pred = 0, n_joint = 0, n_samples = 0;
+    int parity = 0;
+    bool ok = true;
+
+    if (p.variant == kFrameLooping) {
+        // Algorithm 1 on this team's rows.
+        int max_out_len = 0;
+        for (int r = 0; r < R; ++r) max_out_len = max(max_out_len, c.len[r]);
+        bool need_pred = true;     // nothing computed yet for (last_label, hidden)
+        for (int time_idx = 0; ok && time_idx < max_out_len; ++time_idx) {
+            if (w.tid < R) c.mask[w.tid] = time_idx >= c.len[w.tid];   // blank_mask
+            int symbols_added = 0;
+            bool not_blank = true;
+            __syncthreads();
+            while (ok && not_blank && symbols_added < p.S) {
+                if (need_pred) {
+                    // g, hidden_prime = prediction(last_label, hidden); skipped when neither
+                    // input changed since the last evaluation (same result)
+                    ok = prediction_step<RG>(p, w, c, l);
+                    if (!ok) break;
+                    ++n_pred;
+                    need_pred = false;
+                }
+                if (w.tid < kMaxSamples) {
+                    const int s = w.tid;
+                    c.s_row[s] = s; c.s_frame[s] = time_idx;
+                    c.s_valid[s] = (s < R) && !c.mask[s];
+                }
+                if (w.tid == 0) c.ns = R;
+                __syncthreads();
+                ok = joint_any(p, w, c, l, parity);      // logp = joint(f, g); k, v = logp.max()
+                if (!ok) break;
+                parity ^= 1; ++n_joint; n_samples += R;
+                if (w.tid == 0) {
+                    int any = 0, committed = 0;
+                    for (int r = 0; r < R; ++r) {
+                        if (c.mask[r]) continue;
+                        const int k = c.s_k[r];
+                        if (k == p.blank) { c.mask[r] = 1; }          // blank_mask |= (k == blank)
+                        else { emit_row(p, w, c, r, k, time_idx, c.s_v[r], 0); committed = 1; any = 1; }
+                    }
+                    c.any = any; c.committed = committed;
+                }
+                __syncthreads();
+                not_blank = c.any != 0;
+                need_pred = need_pred || (c.committed != 0);
+                symbols_added += 1;
+                __syncthreads();
+            }
+        }
+    } else {
+        // Label looping (RNN-T and TDT).
+        const bool tdt = p.D > 0;
+        int la = p.lookahead;
+        if (la * R > kMaxSamples) la = kMaxSamples / R;
+        if (la < 1) la = 1;
+        bool any_active = false;
+        for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
+        while (ok && any_active) {
+            ok = prediction_step<RG>(p, w, c, l);
+            if (!ok) break;
+            ++n_pred;
+            if (w.tid < R) c.searching[w.tid] = c.active[w.tid];
+            __syncthreads();
+            bool any_searching = true;
+            while (ok && any_searching) {
+                if (w.tid < kMaxSamples) {
+                    const int s = w.tid, r = s / la, i = s - r * la;
+                    int valid = 0, fr = 0, row = 0;
+                    if (r < R) {
+                        row = r; fr = c.t[r] + i;
+                        valid = c.searching[r] && fr < c.len[r];
+                    }
+                    c.s_row[s] = row; c.s_frame[s] = fr; c.s_valid[s] = valid;
+                }
+                if (w.tid == 0) c.ns = R * la;
+                __syncthreads();
+                ok = joint_any(p, w, c, l, parity);
+                if (!ok) break;
+                parity ^= 1; ++n_joint;
+                if (w.tid < R && c.searching[w.tid]) {
+                    const int r = w.tid;
+                    int pos = 0, found = 0;
+                    while (pos < la && c.t[r] + pos < c.len[r]) {
+                        const int s = r * la + pos;
+                        const int k = c.s_k[s];
+                        const int dval = tdt ? c.durations[c.s_d[s]] : 0;
+                        if (k == p.blank) {
+                            pos += tdt ? max(dval, 1) : 1;
+                            c.n[r] = 0;
+                        } else {
+                            found = 1;
+                            c.hold_k[r] = k; c.hold_v[r] = c.s_v[s]; c.hold_d[r] = dval;
+                            break;
+                        }
+                    }
+                    c.t[r] += pos;
+                    if (found) c.searching[r] = 0;
+                    else if (c.t[r] >= c.len[r]) { c.searching[r] = 0; c.active[r] = 0; }
+                }
+                __syncthreads();
+                any_searching = false;
+                for (int r = 0; r < R; ++r) any_searching = any_searching || c.searching[r];
+                for (int s = 0; s < R * la; ++s) n_samples += c.s_valid[s];
+                __syncthreads();
+            }
+            if (!ok) break;
+            if (w.tid < R && c.active[w.tid]) {
+                const int r = w.tid;
+                const int dval = c.hold_d[r];
+                emit_row(p, w, c, r, c.hold_k[r], c.t[r], c.hold_v[r], dval);
+                if (tdt && dval > 0) { c.t[r] += dval; c.n[r] = 0; }
+                else { c.n[r] += 1; if (c.n[r] == p.S) { c.t[r] += 1; c.n[r] = 0; } }
+                c.active[r] = c.t[r] < c.len[r];
+            }
+            __syncthreads();
+            any_active = false;
+            for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
+            __syncthreads();
+        }
+    }
+    // epilogue
+    __syncthreads();
+    if (w.rank == 0 && w.tid < R) p.tok_len[c.b[w.tid]] = c.cnt[w.tid];
+    if (w.rank == 0 && w.tid == 0) {
+        int st = c.status;
+        if (!ok) st |= 4;
+        if (st) atomicOr(p.status, st);
+        long long *sp = p.stats + (long long)w.team * kStatCount;
+        sp[kStatPred] = n_pred; sp[kStatJoint] = n_joint; sp[kStatSamples] = n_samples;
+        sp[kStatPolls] = w.polls;
+    } else if (!ok && w.tid == 0) {
+        atomicOr(p.status, 4);
+    }
+}
+
+__global__ void reset_kernel(unsigned *bar, int n_bar, unsigned *abort_flag, int *status,
+                             long long *stats, int n_stats)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_bar) bar[i] = 0u;
+    if (i < n_stats) stats[i] = 0;
+    if (i == 0) { *abort_flag = 0u; *status = 0; }
+}
+
+template <int RG>
+static hipError_t launch_rg(const DecodeParams &p, hipStream_t stream)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<RG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_bytes);
+    if (e != hipSuccess) return e;
+    DecodeParams pc = p;
+    void *args[] = {&pc};
+    return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&decode_kernel<RG>),
+                                      dim3(p.n_teams * p.team_size), dim3(kThreads), args,
+                                      p.lds_bytes, stream);
+}
+
+hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
+{
+    const int n_bar = p.n_teams * 32, n_stats = p.n_teams * kStatCount;
+    const int n = n_bar > n_stats ? n_bar : n_stats;
+    hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.bar, n_bar,
+                       p.abort_flag, p.status, p.stats, n_stats);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int rows = (p.B + p.n_teams - 1) / p.n_teams;
+    const int rg = (rows + 3) / 4;
+    if (rg <= 1) return launch_rg<1>(p, stream);
+    if (rg <= 2) return launch_rg<2>(p, stream);
+    return launch_rg<4>(p, stream);
+}
+
+hipError_t decode_kernel_limits(int *max_dyn_lds_bytes, int *max_coresident_wgs)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return e;
+    hipFuncAttributes fa;
+    e = hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(&decode_kernel<1>));
+    if (e != hipSuccess) return e;
+    *max_dyn_lds_bytes = (int)prop.sharedMemPerBlock - (int)fa.sharedSizeBytes;
+    *max_coresident_wgs = prop.multiProcessorCount;
+    return hipSuccess;
+}
+
+}  // namespace rnnt

@@ -1,0 +1,70 @@
+// Internal declarations shared by the host API, the encoder-projection kernel
+// and the persistent decode kernel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.h"
+
+namespace rnnt {
+
+enum Variant { kFrameLooping = 0, kLabelLooping = 1, kTdtLabelLooping = 2 };
+
+// Packed weights of one dense stage on the device.
+struct StageDev {
+    const float4 *w;       // [rank][slot][wave][step][lane]
+    int nks, nsteps, slots, kpad;
+    long long rank_stride; // float4 elements per rank
+};
+
+// Slots of the per-team statistics record.
+enum { kStatPred = 0, kStatJoint = 1, kStatSamples = 2, kStatPolls = 3, kStatCount = 8 };
+
+struct DecodeParams {
+    int F, E, H, L, J, V1, D, blank, NOUT;
+    int durations[kMaxDur];
+    int B, T, S, cap, variant;
+    int n_teams, team_size, lookahead;
+    int xstride;            // floats per activation row in LDS
+    int nu_max;             // most hidden units owned by a rank
+    int gj_max;             // most joint output groups owned by a rank
+    // dynamic LDS layout, offsets in floats
+    int lds_xz, lds_red, lds_c, lds_part, lds_cand;
+    unsigned lds_bytes;
+    unsigned spin_limit;
+    const int *enc_len;     // [B]
+    const float *P;         // [B, T, J] projected frames
+    int *tokens; int *tok_len; int *frames; float *logits; int *durs;
+    StageDev st0;                 // recurrent (h) parts of all layers
+    StageDev stl[kMaxLayers];     // input parts of layers 1..L-1 (index = layer)
+    StageDev spred;               // prediction-side joint projection
+    StageDev sjoint;              // joint output projection
+    const float *T0;        // [V1][H][4]: W_ih0 emb[v] + b_ih0 + b_hh0, gates of a unit adjacent
+    const float *bias_l;    // [L][H][4]: b_ih + b_hh of layers >= 1 (layer 0 unused)
+    const float *b_pred;    // [J]
+    const float *b_out;     // [NOUT]
+    // team workspace
+    float *hbuf;                  // [n_teams][2][L][kMaxRows][H]
+    float *qbuf;                  // [n_teams][kMaxRows][J]
+    unsigned long long *part;     // [n_teams][2][kMaxSamples][team_size] token partial argmax
+    unsigned long long *dpart;    // same for durations
+    unsigned *bar;                // [n_teams * 32]: one counter per team, 128 B apart
+    unsigned *abort_flag;
+    int *status;
+    long long *stats;             // [n_teams][kStatCount]
+    int *xcc;                     // [n_teams * team_size]
+};
+
+hipError_t launch_decode(const DecodeParams &p, hipStream_t stream);
+// Largest dynamic LDS the decode kernel may use on this device.
+hipError_t decode_kernel_limits(int *max_dyn_lds_bytes, int *max_coresident_wgs);
+
+hipError_t launch_encoder_projection(const float *enc_out, const int *enc_len, const float *w_enc,
+                                     const float *b_enc, float *proj, int B, int T, int F, int J,
+                                     hipStream_t stream);
+// T0[v][u][g] = b_ih0[g*H+u] + b_hh0[g*H+u] + sum_e W_ih0[g*H+u][e] * emb[v][e]
+hipError_t launch_fold_embedding(const float *emb, const float *w_ih0, const float *b_ih0,
+                                 const float *b_hh0, float *T0, int V1, int E, int H,
+                                 hipStream_t stream);
+
+}  // namespace rnnt

@@ -1,0 +1,78 @@
+// Work decomposition shared by the host-side weight packer and the decode kernel.
+//
+// A team of `ts` work-groups decodes a subset of the batch.  Every dense stage
+// of a step (LSTM gates, prediction-side joint projection, joint output
+// projection) is a small-M product  out[rows, N] = x[rows, K] * W[N, K]^T.  Its
+// N outputs are cut into groups of 4 columns (for the LSTM: the four gates of
+// one hidden unit) that are dealt to the ranks of the team in contiguous
+// ranges; inside a rank each group is cut again along K into `nks` slices.
+// One (group, K-slice) pair is a task; a task runs on one 4-lane block of a
+// wavefront with v_mfma_f32_4x4x1 (4 rows x 4 columns per block, 16 blocks per
+// wave, 8 waves = 128 blocks per work-group).  Tasks beyond 128 go to further
+// "slots", processed one after the other.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define RNNT_HD __host__ __device__
+
+namespace rnnt {
+
+constexpr int kThreads = 512;        // threads per work-group (8 wavefronts)
+constexpr int kWaves = 8;
+constexpr int kBlocksPerWg = 128;    // 4-lane MFMA blocks per work-group
+constexpr int kMaxLayers = 4;
+constexpr int kMaxDur = 8;
+constexpr int kMaxRows = 16;         // utterances per team
+constexpr int kMaxSamples = 32;      // (utterance, frame) pairs per joint step
+constexpr int kStepUnroll = 4;       // K steps (of 4 floats) per software-pipeline batch
+
+// Contiguous share of n items owned by `rank` out of `ts`.
+RNNT_HD inline int range_lo(int rank, int ts, int n) { return (int)(((int64_t)rank * n) / ts); }
+RNNT_HD inline int range_hi(int rank, int ts, int n) { return (int)(((int64_t)(rank + 1) * n) / ts); }
+
+struct StagePlan {
+    int K;          // input length in floats
+    int nks;        // K slices per group
+    int nsteps;     // float4 steps per task (multiple of kStepUnroll)
+    int slots;      // passes over the 128 blocks
+    int kpad;       // nks * nsteps * 4: padded input length
+    int64_t rank_stride;   // float4 elements of packed weights per rank
+};
+
+// groups_max: largest number of groups any rank owns in this stage.
+// Picks the number of K slices that fills the 128 blocks best while keeping the
+// zero padding of K (slices are whole multiples of kStepUnroll steps) below 1/8.
+inline StagePlan make_stage_plan(int K, int groups_max)
+{
+    StagePlan p{};
+    p.K = K;
+    const int k4 = (K + 3) / 4;
+    if (groups_max < 1) groups_max = 1;
+    auto steps_for = [&](int nks) {
+        int n = (k4 + nks - 1) / nks;
+        return ((n + kStepUnroll - 1) / kStepUnroll) * kStepUnroll;
+    };
+    if (groups_max <= kBlocksPerWg) {
+        int cap = kBlocksPerWg / groups_max;
+        const int cap_k = k4 / kStepUnroll > 0 ? k4 / kStepUnroll : 1;
+        if (cap > cap_k) cap = cap_k;
+        if (cap < 1) cap = 1;
+        int best = 1;
+        for (int nks = cap; nks >= 1; --nks) {
+            const int kpad4 = nks * steps_for(nks);
+            if (kpad4 * 8 <= k4 * 9 || nks == 1) { best = nks; break; }
+        }
+        p.nks = best;
+        p.slots = 1;
+    } else {
+        p.nks = 1;
+        p.slots = (groups_max + kBlocksPerWg - 1) / kBlocksPerWg;
+    }
+    p.nsteps = steps_for(p.nks);
+    p.kpad = p.nks * p.nsteps * 4;
+    p.rank_stride = (int64_t)p.slots * kWaves * p.nsteps * 64;
+    return p;
+}
+
+}  // namespace rnnt

@@ -1,0 +1,61 @@
+"""Comparison of a GPU decode with the oracle's, row by row.
+
+Bar: token sequences bit-exact; emitted logits within 1e-4 relative.  A row
+whose tokens differ is only accepted if the oracle, walked along the GPU's
+hypothesis, departs from its own argmax solely at evaluations where the chosen
+logit lies less than 1e-5 (absolute, fp32) below the maximum; every such row is
+reported.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+
+MARGIN = 1e-5
+LOGIT_RTOL = 1e-4
+
+
+def to_lists(out, B):
+    """Device tensors of one decode -> numpy rows cut at tok_len."""
+    tok_len = out["tok_len"].cpu().numpy()
+    cap = out["tokens"].shape[1]
+    n = np.minimum(tok_len, cap)
+    cut = lambda key: [out[key][b, :n[b]].cpu().numpy() for b in range(B)]
+    res = dict(tok_len=tok_len, tokens=cut("tokens"), frames=cut("frames"), logits=cut("logits"),
+               raw_tokens=out["tokens"].cpu().numpy())
+    res["durs"] = cut("durs") if "durs" in out else [np.zeros(n[b], np.int32) for b in range(B)]
+    return res
+
+
+def compare(w, net, ref, got, S, check_fill=True):
+    """ref: oracle.Decoded; got: to_lists(...) of the GPU run.  Returns the list
+    of accepted near-tie rows; raises AssertionError on a real mismatch."""
+    near_ties = []
+    B = w.B
+    for b in range(B):
+        same = (got["tok_len"][b] == ref.tok_len[b]
+                and np.array_equal(got["tokens"][b], ref.tokens[b])
+                and np.array_equal(got["frames"][b], ref.frames[b])
+                and np.array_equal(got["durs"][b], ref.durs[b]))
+        if same:
+            rv, gv = ref.scores[b].astype(np.float64), got["logits"][b].astype(np.float64)
+            tol = LOGIT_RTOL * np.maximum(1.0, np.abs(rv))
+            assert np.all(np.abs(rv - gv) <= tol), (
+                f"row {b}: logits differ by {np.max(np.abs(rv - gv)):.3e}")
+        else:
+            f = oracle.follow(net, w.enc_out[b], int(w.enc_len[b]), S, got["tokens"][b],
+                              got["frames"][b], got["durs"][b] if w.model.dims.D else None)
+            assert f.departures > 0, (
+                f"row {b}: GPU hypothesis differs from the oracle's and is "
+                f"{'impossible' if f.departures < 0 else 'identical under follow?'}; "
+                f"oracle {ref.tokens[b][:12]} gpu {got['tokens'][b][:12]}")
+            assert f.worst_gap < MARGIN, (
+                f"row {b}: GPU departs from the oracle argmax by {f.worst_gap:.3e} "
+                f"(allowed < {MARGIN}) at {f.where[:3]}")
+            near_ties.append(dict(row=b, departures=f.departures, worst_gap=f.worst_gap,
+                                  where=f.where[:4]))
+        if check_fill:
+            n = int(min(got["tok_len"][b], got["raw_tokens"].shape[1]))
+            assert np.all(got["raw_tokens"][b, n:] == -1), f"row {b}: fill beyond tok_len"
+    return near_ties
