@@ -55,20 +55,33 @@ struct Wg {
     long long polls;
 };
 
+// Wait until this wave's own loads and stores have been performed.  Exchange
+// data is written with device-scope atomic stores (written through to the level
+// all XCDs share), so once they are acknowledged nothing has to be flushed: the
+// barrier needs no cache write-back or invalidate, which on this part cost tens
+// of microseconds per barrier.  The asm is also a compiler barrier for memory.
+__device__ __forceinline__ void wait_own_memory_ops()
+{
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+}
+
 // Team barrier with a bounded wait.  Returns false when the wait expired or
 // another work-group raised the abort flag; the caller then leaves the kernel.
+// Ordering: every thread completes its exchange stores, the work-group meets,
+// thread 0 announces arrival with a relaxed device-scope add and polls the
+// counter; data is read afterwards with device-scope atomic loads only.
 __device__ __forceinline__ bool team_barrier(const DecodeParams &p, Wg &w, Ctl &c)
 {
-    __threadfence();
+    wait_own_memory_ops();
     __syncthreads();
     w.epoch += 1;
     if (w.tid == 0) {
         unsigned *ctr = p.bar + w.team * 32;
         const unsigned target = w.epoch * (unsigned)p.team_size;
-        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned spins = 0;
         int ok = 1;
-        while (__hip_atomic_load(ctr, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
             ++spins;
             if ((spins & 127u) == 0 &&
                 __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
@@ -162,7 +175,7 @@ __device__ __forceinline__ float reduce_tasks(const float *red, int nks, int g, 
 __device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
 
 struct Lds {
-    float *xz, *red, *c, *part;
+    float *xz, *red, *c, *part, *q;
     float *cand_v;
     int *cand_i;
     float *dcand_v;
@@ -182,18 +195,46 @@ __device__ __forceinline__ float *h_slot(const DecodeParams &p, int team, int se
 }
 
 // Fill RG*4 activation rows of `len` floats each into LDS from a global exchange
-// buffer; the tail up to kpad and the rows beyond R are zero.
-__device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, const Ctl &c, float *dst, int rows_pad,
-                          int len, int kpad, int layer, bool candidate)
+// buffer; the tail up to kpad and the rows beyond R are zero.  Loads are issued
+// in batches so that their latencies overlap.
+__device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, const Ctl &c, float *dst,
+                                          int rows_pad, int len, int kpad, int layer, bool candidate)
 {
-    for (int idx = w.tid; idx < rows_pad * kpad; idx += kThreads) {
-        const int r = idx / kpad, k = idx - r * kpad;
-        float v = 0.f;
-        if (r < c.R && k < len) {
-            const int sel = candidate ? (c.sel[r] ^ 1) : c.sel[r];
-            v = xload(h_slot(p, w.team, sel, layer, r) + k);
+    constexpr int NB = 6;
+    const int kp2 = kpad >> 1;               // kpad is a multiple of 4
+    const int total = rows_pad * kp2;        // pairs of floats
+    const bool pairs = (len & 1) == 0;       // rows start 8-byte aligned
+    for (int base = w.tid; base < total; base += NB * kThreads) {
+        float2 v[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int idx = base + u * kThreads;
+            v[u] = make_float2(0.f, 0.f);
+            if (idx < total) {
+                const int r = idx / kp2, k = (idx - r * kp2) * 2;
+                if (r < c.R && k < len) {
+                    const int sel = candidate ? (c.sel[r] ^ 1) : c.sel[r];
+                    const float *src = h_slot(p, w.team, sel, layer, r) + k;
+                    if (pairs) {
+                        const unsigned long long q =
+                            xload64(reinterpret_cast<const unsigned long long *>(src));
+                        v[u].x = __uint_as_float((unsigned)q);
+                        v[u].y = __uint_as_float((unsigned)(q >> 32));
+                    } else {
+                        v[u].x = xload(src);
+                        if (k + 1 < len) v[u].y = xload(src + 1);
+                    }
+                }
+            }
         }
-        dst[r * p.xstride + k] = v;
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int idx = base + u * kThreads;
+            if (idx < total) {
+                const int r = idx / kp2, k = (idx - r * kp2) * 2;
+                *reinterpret_cast<float2 *>(dst + r * p.xstride + k) = v[u];
+            }
+        }
     }
 }
 
@@ -217,6 +258,17 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
     for (int layer = 0; layer < p.L; ++layer)
         fill_rows(p, w, c, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
     __syncthreads();
+    // the additive term of this thread's first epilogue item (embedding term of layer 0,
+    // bias of the layers above) is fetched before the product so its latency is hidden
+    float4 pre = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (w.tid < p.L * nu * c.R) {
+        const int layer = w.tid / (nu * c.R);
+        const int rem = w.tid - layer * nu * c.R;
+        const int u = rem / c.R, r = rem - u * c.R;
+        pre = *reinterpret_cast<const float4 *>(
+            layer == 0 ? p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4
+                       : p.bias_l + ((long long)layer * p.H + (u0 + u)) * 4);
+    }
     run_stage<RG>(p.st0, w, p.L * nu * p.st0.nks, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1, l.red, false);
     __syncthreads();
     for (int e = w.tid; e < p.L * nu * c.R; e += kThreads) {
@@ -228,7 +280,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
 #pragma unroll
         for (int j = 0; j < 4; ++j) a[j] = reduce_tasks<RG>(l.red, p.st0.nks, g, r, j);
         if (layer == 0) {
-            const float4 t0 = *reinterpret_cast<const float4 *>(
+            const float4 t0 = e == w.tid ? pre : *reinterpret_cast<const float4 *>(
                 p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
             float cn, hn;
             lstm_point(a[0] + t0.x, a[1] + t0.y, a[2] + t0.z, a[3] + t0.w,
@@ -236,7 +288,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
             *c_slot(p, l, 0, c.sel[r] ^ 1, u, r) = cn;
             xstore(h_slot(p, w.team, c.sel[r] ^ 1, 0, r) + u0 + u, hn);
         } else {
-            const float4 bl = *reinterpret_cast<const float4 *>(
+            const float4 bl = e == w.tid ? pre : *reinterpret_cast<const float4 *>(
                 p.bias_l + ((long long)layer * p.H + (u0 + u)) * 4);
             float *dst = l.part + ((layer * p.nu_max + u) * kMaxRows + r) * 4;
             dst[0] = a[0] + bl.x; dst[1] = a[1] + bl.y; dst[2] = a[2] + bl.z; dst[3] = a[3] + bl.w;
@@ -287,6 +339,30 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
             }
         }
         if (!team_barrier(p, w, c)) return false;
+        if (p.q_in_lds) {
+            // q of every row of the team, read once per prediction step
+            constexpr int NB = 6;
+            const int total = rows_pad * p.qstride;
+            for (int base = w.tid; base < total; base += NB * kThreads) {
+                float v[NB];
+#pragma unroll
+                for (int u = 0; u < NB; ++u) {
+                    const int idx = base + u * kThreads;
+                    v[u] = 0.f;
+                    if (idx < total) {
+                        const int r = idx / p.qstride, k = idx - r * p.qstride;
+                        if (r < c.R && k < p.J)
+                            v[u] = xload(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < NB; ++u) {
+                    const int idx = base + u * kThreads;
+                    if (idx < total) l.q[idx] = v[u];
+                }
+            }
+            __syncthreads();
+        }
     }
     return true;
 }
@@ -305,17 +381,63 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
     const int ns = c.ns;
     const int rows_pad = RG * 4;
     const int kpad = p.sjoint.kpad;
-    // z = relu(P[b, frame] + q[row]) for every sample
-    for (int idx = w.tid; idx < rows_pad * kpad; idx += kThreads) {
-        const int s = idx / kpad, k = idx - s * kpad;
-        float v = 0.f;
-        if (s < ns && k < p.J && c.s_valid[s]) {
-            const int r = c.s_row[s];
-            const float pe = p.P[((long long)c.b[r] * p.T + c.s_frame[s]) * p.J + k];
-            const float q = xload(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k);
-            v = fmaxf(pe + q, 0.f);
+    // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time
+    {
+        constexpr int NB = 4;
+        const int k4n = kpad >> 2;
+        const int total = rows_pad * k4n;
+        const bool vec = (p.J & 3) == 0;
+        for (int base = w.tid; base < total; base += NB * kThreads) {
+            float4 pe[NB], qv[NB];
+            bool live[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int idx = base + u * kThreads;
+                pe[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                qv[u] = pe[u];
+                live[u] = false;
+                if (idx < total) {
+                    const int s = idx / k4n, k = (idx - s * k4n) * 4;
+                    if (s < ns && k < p.J && c.s_valid[s]) {
+                        live[u] = true;
+                        const int r = c.s_row[s];
+                        const float *pr = p.P + ((long long)c.b[r] * p.T + c.s_frame[s]) * p.J + k;
+                        if (vec) {
+                            pe[u] = *reinterpret_cast<const float4 *>(pr);
+                        } else {
+                            pe[u].x = pr[0];
+                            if (k + 1 < p.J) pe[u].y = pr[1];
+                            if (k + 2 < p.J) pe[u].z = pr[2];
+                            if (k + 3 < p.J) pe[u].w = pr[3];
+                        }
+                        if (p.q_in_lds) {
+                            qv[u] = *reinterpret_cast<const float4 *>(l.q + r * p.qstride + k);
+                        } else {
+                            const float *qr = p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k;
+                            qv[u].x = xload(qr);
+                            if (k + 1 < p.J) qv[u].y = xload(qr + 1);
+                            if (k + 2 < p.J) qv[u].z = xload(qr + 2);
+                            if (k + 3 < p.J) qv[u].w = xload(qr + 3);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int idx = base + u * kThreads;
+                if (idx < total) {
+                    const int s = idx / k4n, k = (idx - s * k4n) * 4;
+                    float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (live[u]) {
+                        z.x = fmaxf(pe[u].x + qv[u].x, 0.f);
+                        if (k + 1 < p.J) z.y = fmaxf(pe[u].y + qv[u].y, 0.f);
+                        if (k + 2 < p.J) z.z = fmaxf(pe[u].z + qv[u].z, 0.f);
+                        if (k + 3 < p.J) z.w = fmaxf(pe[u].w + qv[u].w, 0.f);
+                    }
+                    *reinterpret_cast<float4 *>(l.xz + s * p.xstride + k) = z;
+                }
+            }
         }
-        l.xz[s * p.xstride + k] = v;
     }
     __syncthreads();
     const int ng_all = (p.NOUT + 3) / 4;
@@ -440,7 +562,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     w.epoch = 0; w.polls = 0;
     Lds l;
     l.xz = dyn_lds + p.lds_xz; l.red = dyn_lds + p.lds_red; l.c = dyn_lds + p.lds_c;
-    l.part = dyn_lds + p.lds_part;
+    l.part = dyn_lds + p.lds_part; l.q = dyn_lds + p.lds_q;
     l.cand_v = dyn_lds + p.lds_cand;
     l.cand_i = reinterpret_cast<int *>(l.cand_v + kMaxSamples * p.gj_max);
     l.dcand_v = reinterpret_cast<float *>(l.cand_i + kMaxSamples * p.gj_max);

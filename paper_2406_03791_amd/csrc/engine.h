@@ -29,7 +29,9 @@ struct DecodeParams {
     int nu_max;             // most hidden units owned by a rank
     int gj_max;             // most joint output groups owned by a rank
     // dynamic LDS layout, offsets in floats
-    int lds_xz, lds_red, lds_c, lds_part, lds_cand;
+    int lds_xz, lds_red, lds_c, lds_part, lds_cand, lds_q;
+    int q_in_lds;           // q = W_pred h + b_pred of the team's rows is kept in LDS
+    int qstride;            // floats per q row in LDS
     unsigned lds_bytes;
     unsigned spin_limit;
     const int *enc_len;     // [B]

@@ -67,7 +67,8 @@ struct rnnt_engine {
     PackedStage st0, stl[kMaxLayers], spred, sjoint;
     // plan
     int xstride = 0, nu_max = 0, gj_max = 0;
-    int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_cand = 0;
+    int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_cand = 0, lds_q = 0;
+    int q_in_lds = 0, qstride = 0;
     unsigned lds_bytes = 0;
     int last_B = 0;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before projection, before decode, after
@@ -155,8 +156,12 @@ int plan_and_pack(rnnt_engine *e, int n_teams)
     e->lds_c = take(L * 2 * nu_max * kMaxRows);
     e->lds_part = take(L * nu_max * kMaxRows * 4);
     e->lds_cand = take(4 * kMaxSamples * gj_max);
+    if ((unsigned)off * 4u + 2048u > (unsigned)kLdsBytes) return RNNT_ERR_UNSUPPORTED;
+    // q of the team's rows stays in LDS between joint steps when there is room
+    e->qstride = (J + 3) & ~3;
+    e->q_in_lds = ((unsigned)(off + rows_pad * e->qstride) * 4u + 2048u <= (unsigned)kLdsBytes);
+    e->lds_q = e->q_in_lds ? take(rows_pad * e->qstride) : 0;
     e->lds_bytes = (unsigned)off * 4u;
-    if (e->lds_bytes + 2048u > (unsigned)kLdsBytes) return RNNT_ERR_UNSUPPORTED;
     e->xstride = xstride; e->nu_max = nu_max; e->gj_max = gj_max;
 
     // weights
@@ -258,6 +263,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.xstride = e->xstride; p.nu_max = e->nu_max; p.gj_max = e->gj_max;
     p.lds_xz = e->lds_xz; p.lds_red = e->lds_red; p.lds_c = e->lds_c; p.lds_part = e->lds_part;
     p.lds_cand = e->lds_cand; p.lds_bytes = e->lds_bytes;
+    p.lds_q = e->lds_q; p.q_in_lds = e->q_in_lds; p.qstride = e->qstride;
     p.spin_limit = 1u << 22;
     p.enc_len = enc_len; p.P = e->P.as<float>();
     p.tokens = tokens_out; p.tok_len = tok_len_out; p.frames = frames_out; p.logits = logit_out;
