@@ -24,7 +24,8 @@ struct Ctl {
     int s_row[kMaxSamples], s_frame[kMaxSamples], s_valid[kMaxSamples];
     int s_k[kMaxSamples], s_d[kMaxSamples];
     float s_v[kMaxSamples];
-    int R, ns, any, status, bar_ok, committed;
+    int R, ns, any, bar_ok, committed;
+    int st_clamped, st_overflow;   // set to 1 by any thread (same value from all writers)
     int durations[kMaxDur];
 };
 
@@ -53,7 +54,18 @@ struct Wg {
     int team, rank, tid, lane, wave;
     unsigned epoch;
     long long polls;
+#ifdef RNNT_PROFILE
+    long long t_last;
+    long long prof[24];
+#endif
 };
+
+// Phase timers (100 MHz wall clock), compiled in only for profiling builds.
+#ifdef RNNT_PROFILE
+#define PROF_MARK(w, slot) do { long long t_ = wall_clock64(); (w).prof[slot] += t_ - (w).t_last; (w).t_last = t_; } while (0)
+#else
+#define PROF_MARK(w, slot) do { } while (0)
+#endif
 
 // Wait until this wave's own loads and stores have been performed.  Exchange
 // data is written with device-scope atomic stores (written through to the level
@@ -102,40 +114,70 @@ __device__ __forceinline__ bool team_barrier(const DecodeParams &p, Wg &w, Ctl &
     return c.bar_ok != 0;
 }
 
+// The packed weights of a stage are a fixed stream per lane, independent of the
+// data, so their loads can start before the stage's input is there: kAhead
+// batches of kStepUnroll float4 steps are kept in flight in registers.
+constexpr int kAhead = 2;
+
+struct WeightStream {
+    const float4 *wp;
+    int task;
+    bool live;
+    float4 q[kAhead][kStepUnroll];
+};
+
+__device__ __forceinline__ void stream_begin(WeightStream &ws, const StageDev &sd, const Wg &w,
+                                             int n_tasks, int slot)
+{
+    ws.task = slot * kBlocksPerWg + w.wave * 16 + (w.lane >> 2);
+    ws.live = ws.task < n_tasks;
+    ws.wp = sd.w + (long long)w.rank * sd.rank_stride +
+            ((long long)(slot * kWaves + w.wave) * sd.nsteps) * 64 + w.lane;
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a)
+#pragma unroll
+        for (int u = 0; u < kStepUnroll; ++u) {
+            const int step = a * kStepUnroll + u;
+            ws.q[a][u] = (ws.live && step < sd.nsteps) ? ws.wp[step * 64]
+                                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+}
+
 // One dense stage for this rank:  red[task][rg][col][row] = sum over the task's
 // K slice of x[row][k] * W[col][k], rows in groups of 4 (RG groups).
+//   ws           weight stream of slot 0, begun by the caller
 //   x            LDS, rows `xstride` floats apart; input vector `inp` of a group
 //                starts `x_inp_stride` floats further (inp = group / groups_per_inp)
-//   n_tasks      groups owned by this rank * nks
 //   red_aliases_x  the results overwrite x (only valid with a single slot)
 template <int RG>
 __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n_tasks,
-                                          const float *x, int xstride, int x_inp_stride,
-                                          int groups_per_inp, float *red, bool red_aliases_x)
+                                          WeightStream &ws, const float *x, int xstride,
+                                          int x_inp_stride, int groups_per_inp, float *red,
+                                          bool red_aliases_x)
 {
-    const int blk = w.lane >> 2, r4 = w.lane & 3;
+    const int r4 = w.lane & 3;
     for (int slot = 0; slot < sd.slots; ++slot) {
-        const int task = slot * kBlocksPerWg + w.wave * 16 + blk;
-        const bool live = task < n_tasks;
+        if (slot > 0) stream_begin(ws, sd, w, n_tasks, slot);
+        const int task = ws.task;
+        const bool live = ws.live;
         const int g = live ? task / sd.nks : 0;
         const int ks = live ? task - g * sd.nks : 0;
         const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * 4;
-        const float4 *wp = sd.w + (long long)w.rank * sd.rank_stride +
-                           ((long long)(slot * kWaves + w.wave) * sd.nsteps) * 64 + w.lane;
         v4f acc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){0.f, 0.f, 0.f, 0.f};
-        float4 nxt[kStepUnroll];
-#pragma unroll
-        for (int u = 0; u < kStepUnroll; ++u)
-            nxt[u] = live ? wp[u * 64] : make_float4(0.f, 0.f, 0.f, 0.f);
         for (int i = 0; i < sd.nsteps; i += kStepUnroll) {
             float4 cur[kStepUnroll];
 #pragma unroll
-            for (int u = 0; u < kStepUnroll; ++u) cur[u] = nxt[u];
-            if (live && i + kStepUnroll < sd.nsteps) {
+            for (int u = 0; u < kStepUnroll; ++u) cur[u] = ws.q[0][u];
 #pragma unroll
-                for (int u = 0; u < kStepUnroll; ++u) nxt[u] = wp[(i + kStepUnroll + u) * 64];
+            for (int a = 0; a + 1 < kAhead; ++a)
+#pragma unroll
+                for (int u = 0; u < kStepUnroll; ++u) ws.q[a][u] = ws.q[a + 1][u];
+            if (live && i + kAhead * kStepUnroll < sd.nsteps) {
+#pragma unroll
+                for (int u = 0; u < kStepUnroll; ++u)
+                    ws.q[kAhead - 1][u] = ws.wp[(i + kAhead * kStepUnroll + u) * 64];
             }
 #pragma unroll
             for (int u = 0; u < kStepUnroll; ++u) {
@@ -162,24 +204,25 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
     }
 }
 
-// Sum of the K-slice partials of (group g, row, column j).
+// Sums of the K-slice partials of (group g, row) for its four columns, slices
+// added in ascending order.  The loop is unrolled so the LDS reads overlap.
 template <int RG>
-__device__ __forceinline__ float reduce_tasks(const float *red, int nks, int g, int row, int j)
+__device__ __forceinline__ void reduce_tasks4(const float *red, int nks, int g, int row, float (&a)[4])
 {
-    float s = 0.f;
-    for (int ks = 0; ks < nks; ++ks)
-        s += red[(((g * nks + ks) * RG + (row >> 2)) * 4 + j) * 4 + (row & 3)];
-    return s;
+    const float *src = red + ((g * nks * RG + (row >> 2)) * 4) * 4 + (row & 3);
+    a[0] = a[1] = a[2] = a[3] = 0.f;
+#pragma unroll 4
+    for (int ks = 0; ks < nks; ++ks) {
+        const float *q = src + ks * RG * 16;
+        a[0] += q[0]; a[1] += q[4]; a[2] += q[8]; a[3] += q[12];
+    }
 }
 
 __device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
 
 struct Lds {
     float *xz, *red, *c, *part, *q;
-    float *cand_v;
-    int *cand_i;
-    float *dcand_v;
-    int *dcand_i;
+    float *b_pred, *b_out, *b_lstm;   // this rank's slices of the bias vectors
 };
 
 // c state of this rank's units: [layer][sel][unit][row]
@@ -255,30 +298,40 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
     const int rows_pad = RG * 4;
     const int inp_stride = rows_pad * p.xstride;
     // stage 0: recurrent parts of every layer, layer 0 completes
+    PROF_MARK(w, 18);
+    WeightStream ws;
+    stream_begin(ws, p.st0, w, p.L * nu * p.st0.nks, 0);
     for (int layer = 0; layer < p.L; ++layer)
         fill_rows(p, w, c, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
     __syncthreads();
     // the additive term of this thread's first epilogue item (embedding term of layer 0,
     // bias of the layers above) is fetched before the product so its latency is hidden
+    PROF_MARK(w, 0);
     float4 pre = make_float4(0.f, 0.f, 0.f, 0.f);
     if (w.tid < p.L * nu * c.R) {
         const int layer = w.tid / (nu * c.R);
         const int rem = w.tid - layer * nu * c.R;
         const int u = rem / c.R, r = rem - u * c.R;
-        pre = *reinterpret_cast<const float4 *>(
-            layer == 0 ? p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4
-                       : p.bias_l + ((long long)layer * p.H + (u0 + u)) * 4);
+        if (layer == 0)
+            pre = *reinterpret_cast<const float4 *>(p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
     }
-    run_stage<RG>(p.st0, w, p.L * nu * p.st0.nks, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1, l.red, false);
+    run_stage<RG>(p.st0, w, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
+                  l.red, false);
+    // the next stage's weights start moving while this one finishes and the team meets
+    const int ng_all_p = (p.J + 3) / 4;
+    const int gp0 = range_lo(w.rank, p.team_size, ng_all_p);
+    const int ngp = range_hi(w.rank, p.team_size, ng_all_p) - gp0;
+    if (p.L > 1) stream_begin(ws, p.stl[1], w, nu * p.stl[1].nks, 0);
+    else stream_begin(ws, p.spred, w, ngp * p.spred.nks, 0);
     __syncthreads();
+    PROF_MARK(w, 1);
     for (int e = w.tid; e < p.L * nu * c.R; e += kThreads) {
         const int layer = e / (nu * c.R);
         const int rem = e - layer * nu * c.R;
         const int u = rem / c.R, r = rem - u * c.R;
         const int g = layer * nu + u;
         float a[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = reduce_tasks<RG>(l.red, p.st0.nks, g, r, j);
+        reduce_tasks4<RG>(l.red, p.st0.nks, g, r, a);
         if (layer == 0) {
             const float4 t0 = e == w.tid ? pre : *reinterpret_cast<const float4 *>(
                 p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
@@ -288,13 +341,14 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
             *c_slot(p, l, 0, c.sel[r] ^ 1, u, r) = cn;
             xstore(h_slot(p, w.team, c.sel[r] ^ 1, 0, r) + u0 + u, hn);
         } else {
-            const float4 bl = e == w.tid ? pre : *reinterpret_cast<const float4 *>(
-                p.bias_l + ((long long)layer * p.H + (u0 + u)) * 4);
+            const float4 bl = *reinterpret_cast<const float4 *>(l.b_lstm + (layer * p.nu_max + u) * 4);
             float *dst = l.part + ((layer * p.nu_max + u) * kMaxRows + r) * 4;
             dst[0] = a[0] + bl.x; dst[1] = a[1] + bl.y; dst[2] = a[2] + bl.z; dst[3] = a[3] + bl.w;
         }
     }
+    PROF_MARK(w, 2);
     if (!team_barrier(p, w, c)) return false;
+    PROF_MARK(w, 3);
     // stages 1..L-1: input part of layer `layer` from the candidate h of the layer below
 #pragma unroll
     for (int layer = 1; layer < kMaxLayers; ++layer) {
@@ -302,13 +356,18 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
         const StageDev &sd = p.stl[layer];
         fill_rows(p, w, c, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
         __syncthreads();
-        run_stage<RG>(sd, w, nu * sd.nks, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        PROF_MARK(w, 4);
+        run_stage<RG>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        if (layer + 1 < kMaxLayers && layer + 1 < p.L)
+            stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w,
+                         nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks, 0);
+        else stream_begin(ws, p.spred, w, ngp * p.spred.nks, 0);
         __syncthreads();
+        PROF_MARK(w, 5);
         for (int e = w.tid; e < nu * c.R; e += kThreads) {
             const int u = e / c.R, r = e - u * c.R;
             float a[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) a[j] = reduce_tasks<RG>(l.red, sd.nks, u, r, j);
+            reduce_tasks4<RG>(l.red, sd.nks, u, r, a);
             const float *pt = l.part + ((layer * p.nu_max + u) * kMaxRows + r) * 4;
             float cn, hn;
             lstm_point(a[0] + pt[0], a[1] + pt[1], a[2] + pt[2], a[3] + pt[3],
@@ -316,29 +375,33 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
             *c_slot(p, l, layer, c.sel[r] ^ 1, u, r) = cn;
             xstore(h_slot(p, w.team, c.sel[r] ^ 1, layer, r) + u0 + u, hn);
         }
+        PROF_MARK(w, 6);
         if (!team_barrier(p, w, c)) return false;
+        PROF_MARK(w, 7);
     }
     // prediction-side joint projection
     {
-        const int ng_all = (p.J + 3) / 4;
-        const int g0 = range_lo(w.rank, p.team_size, ng_all);
-        const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
+        const int g0 = gp0, ng = ngp;
         fill_rows(p, w, c, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
         __syncthreads();
-        run_stage<RG>(p.spred, w, ng * p.spred.nks, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        PROF_MARK(w, 8);
+        run_stage<RG>(p.spred, w, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
         __syncthreads();
+        PROF_MARK(w, 9);
         for (int e = w.tid; e < ng * c.R; e += kThreads) {
             const int g = e / c.R, r = e - g * c.R;
+            float a[4];
+            reduce_tasks4<RG>(l.red, p.spred.nks, g, r, a);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int col = (g0 + g) * 4 + j;
-                if (col < p.J) {
-                    const float q = reduce_tasks<RG>(l.red, p.spred.nks, g, r, j) + p.b_pred[col];
-                    xstore(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + col, q);
-                }
+                if (col < p.J)
+                    xstore(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + col, a[j] + l.b_pred[g * 4 + j]);
             }
         }
+        PROF_MARK(w, 10);
         if (!team_barrier(p, w, c)) return false;
+        PROF_MARK(w, 11);
         if (p.q_in_lds) {
             // q of every row of the team, read once per prediction step
             constexpr int NB = 6;
@@ -363,6 +426,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
             }
             __syncthreads();
         }
+        PROF_MARK(w, 12);
     }
     return true;
 }
@@ -381,25 +445,28 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
     const int ns = c.ns;
     const int rows_pad = RG * 4;
     const int kpad = p.sjoint.kpad;
-    // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time
+    const int ng_all = (p.NOUT + 3) / 4;
+    const int g0 = range_lo(w.rank, p.team_size, ng_all);
+    const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
+    PROF_MARK(w, 18);
+    WeightStream ws;
+    stream_begin(ws, p.sjoint, w, ng * p.sjoint.nks, 0);
+    // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time;
+    // the loads of a batch are all issued before the first use
     {
-        constexpr int NB = 4;
+        constexpr int NB = 6;
         const int k4n = kpad >> 2;
         const int total = rows_pad * k4n;
         const bool vec = (p.J & 3) == 0;
         for (int base = w.tid; base < total; base += NB * kThreads) {
-            float4 pe[NB], qv[NB];
-            bool live[NB];
+            float4 pe[NB];
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
                 const int idx = base + u * kThreads;
                 pe[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                qv[u] = pe[u];
-                live[u] = false;
                 if (idx < total) {
                     const int s = idx / k4n, k = (idx - s * k4n) * 4;
                     if (s < ns && k < p.J && c.s_valid[s]) {
-                        live[u] = true;
                         const int r = c.s_row[s];
                         const float *pr = p.P + ((long long)c.b[r] * p.T + c.s_frame[s]) * p.J + k;
                         if (vec) {
@@ -410,15 +477,6 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
                             if (k + 2 < p.J) pe[u].z = pr[2];
                             if (k + 3 < p.J) pe[u].w = pr[3];
                         }
-                        if (p.q_in_lds) {
-                            qv[u] = *reinterpret_cast<const float4 *>(l.q + r * p.qstride + k);
-                        } else {
-                            const float *qr = p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k;
-                            qv[u].x = xload(qr);
-                            if (k + 1 < p.J) qv[u].y = xload(qr + 1);
-                            if (k + 2 < p.J) qv[u].z = xload(qr + 2);
-                            if (k + 3 < p.J) qv[u].w = xload(qr + 3);
-                        }
                     }
                 }
             }
@@ -428,11 +486,22 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
                 if (idx < total) {
                     const int s = idx / k4n, k = (idx - s * k4n) * 4;
                     float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (live[u]) {
-                        z.x = fmaxf(pe[u].x + qv[u].x, 0.f);
-                        if (k + 1 < p.J) z.y = fmaxf(pe[u].y + qv[u].y, 0.f);
-                        if (k + 2 < p.J) z.z = fmaxf(pe[u].z + qv[u].z, 0.f);
-                        if (k + 3 < p.J) z.w = fmaxf(pe[u].w + qv[u].w, 0.f);
+                    if (s < ns && k < p.J && c.s_valid[s]) {
+                        const int r = c.s_row[s];
+                        float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (p.q_in_lds) {
+                            qv = *reinterpret_cast<const float4 *>(l.q + r * p.qstride + k);
+                        } else {
+                            const float *qr = p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k;
+                            qv.x = xload(qr);
+                            if (k + 1 < p.J) qv.y = xload(qr + 1);
+                            if (k + 2 < p.J) qv.z = xload(qr + 2);
+                            if (k + 3 < p.J) qv.w = xload(qr + 3);
+                        }
+                        z.x = fmaxf(pe[u].x + qv.x, 0.f);
+                        if (k + 1 < p.J) z.y = fmaxf(pe[u].y + qv.y, 0.f);
+                        if (k + 2 < p.J) z.z = fmaxf(pe[u].z + qv.z, 0.f);
+                        if (k + 3 < p.J) z.w = fmaxf(pe[u].w + qv.w, 0.f);
                     }
                     *reinterpret_cast<float4 *>(l.xz + s * p.xstride + k) = z;
                 }
@@ -440,48 +509,58 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
         }
     }
     __syncthreads();
-    const int ng_all = (p.NOUT + 3) / 4;
-    const int g0 = range_lo(w.rank, p.team_size, ng_all);
-    const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
+    PROF_MARK(w, 13);
     // with one slot the partial sums may overwrite z once every wave is done with it
     const bool alias = p.sjoint.slots == 1;
     float *red = alias ? l.xz : l.red;
-    run_stage<RG>(p.sjoint, w, ng * p.sjoint.nks, l.xz, p.xstride, 0, 1 << 30, red, alias);
+    run_stage<RG>(p.sjoint, w, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias);
     __syncthreads();
-    // per (group, sample): best of the group's four columns
-    for (int e = w.tid; e < ng * ns; e += kThreads) {
-        const int g = e / ns, s = e - g * ns;
-        float bv = -INFINITY, dv = -INFINITY;
-        int bi = 0x7fffffff, di = 0x7fffffff;
+    PROF_MARK(w, 14);
+    // Per sample, this rank's best token column and best duration column.  GP
+    // adjacent lanes share a sample and each takes the groups gl, gl + GP, ...;
+    // groups ascend with the lane, so a strict > keeps the lowest index.
+    {
+        int gp = 1;
+        while (gp < ng && gp < 64) gp <<= 1;
+        for (int base = 0; base < ns * gp; base += kThreads) {
+            const int e = base + w.tid;
+            const int s = e / gp, gl = e - s * gp;
+            float bv = -INFINITY, dv = -INFINITY;
+            int bi = 0x7fffffff, di = 0x7fffffff;
+            if (s < ns) {
+                for (int g = gl; g < ng; g += gp) {
+                    float a[4];
+                    reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = (g0 + g) * 4 + j;
-            if (col < p.NOUT) {
-                const float v = reduce_tasks<RG>(red, p.sjoint.nks, g, s, j) + p.b_out[col];
-                if (col < p.V1) { if (v > bv) { bv = v; bi = col; } }
-                else { if (v > dv) { dv = v; di = col - p.V1; } }
+                    for (int j = 0; j < 4; ++j) {
+                        const int col = (g0 + g) * 4 + j;
+                        if (col < p.NOUT) {
+                            const float v = a[j] + l.b_out[g * 4 + j];
+                            if (col < p.V1) { if (v > bv) { bv = v; bi = col; } }
+                            else { if (v > dv) { dv = v; di = col - p.V1; } }
+                        }
+                    }
+                }
+            }
+            for (int off = 1; off < gp; off <<= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oi = __shfl_xor(bi, off);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                const float od = __shfl_xor(dv, off);
+                const int oj = __shfl_xor(di, off);
+                if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
+            }
+            if (s < ns && gl == 0) {
+                const long long o =
+                    (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size + w.rank;
+                xstore64(p.part + o, pack_cand(bv, bi));
+                if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di));
             }
         }
-        l.cand_v[s * p.gj_max + g] = bv; l.cand_i[s * p.gj_max + g] = bi;
-        l.dcand_v[s * p.gj_max + g] = dv; l.dcand_i[s * p.gj_max + g] = di;
     }
-    __syncthreads();
-    // this rank's partial per sample (groups ascend, strict > keeps the lowest index)
-    if (w.tid < ns) {
-        const int s = w.tid;
-        float bv = -INFINITY, dv = -INFINITY;
-        int bi = 0x7fffffff, di = 0x7fffffff;
-        for (int g = 0; g < ng; ++g) {
-            const float v = l.cand_v[s * p.gj_max + g];
-            if (v > bv) { bv = v; bi = l.cand_i[s * p.gj_max + g]; }
-            const float d = l.dcand_v[s * p.gj_max + g];
-            if (d > dv) { dv = d; di = l.dcand_i[s * p.gj_max + g]; }
-        }
-        const long long o = (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size + w.rank;
-        xstore64(p.part + o, pack_cand(bv, bi));
-        if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di));
-    }
+    PROF_MARK(w, 15);
     if (!team_barrier(p, w, c)) return false;
+    PROF_MARK(w, 16);
     // final argmax over the ranks, 16 lanes per sample
     {
         const int s = w.tid >> 4, sub = w.tid & 15;
@@ -518,6 +597,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
         }
     }
     __syncthreads();
+    PROF_MARK(w, 17);
     return true;
 }
 
@@ -543,7 +623,7 @@ __device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, Ctl
             if (p.logits) p.logits[o] = v;
             if (p.durs) p.durs[o] = dval;
         } else {
-            atomicOr(&c.status, 2);
+            c.st_overflow = 1;
         }
     }
     c.cnt[r] = n + 1;
@@ -560,13 +640,16 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     w.tid = threadIdx.x; w.lane = w.tid & 63; w.wave = w.tid >> 6;
     w.team = blockIdx.x % p.n_teams; w.rank = blockIdx.x / p.n_teams;
     w.epoch = 0; w.polls = 0;
+#ifdef RNNT_PROFILE
+    for (int i = 0; i < 24; ++i) w.prof[i] = 0;
+    w.t_last = wall_clock64();
+#endif
     Lds l;
     l.xz = dyn_lds + p.lds_xz; l.red = dyn_lds + p.lds_red; l.c = dyn_lds + p.lds_c;
     l.part = dyn_lds + p.lds_part; l.q = dyn_lds + p.lds_q;
-    l.cand_v = dyn_lds + p.lds_cand;
-    l.cand_i = reinterpret_cast<int *>(l.cand_v + kMaxSamples * p.gj_max);
-    l.dcand_v = reinterpret_cast<float *>(l.cand_i + kMaxSamples * p.gj_max);
-    l.dcand_i = reinterpret_cast<int *>(l.dcand_v + kMaxSamples * p.gj_max);
+    l.b_pred = dyn_lds + p.lds_bias;
+    l.b_out = l.b_pred + 4 * p.gp_max;
+    l.b_lstm = l.b_out + 4 * p.gj_max;
 
     if (w.tid == 0) {
         // XCC_ID hardware register, bits [3:0]
@@ -576,7 +659,8 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     const int R = (p.B > w.team) ? (p.B - w.team + p.n_teams - 1) / p.n_teams : 0;
     if (R == 0) return;            // the whole team leaves: no barrier is ever entered
     if (w.tid == 0) {
-        c.R = R; c.ns = 0; c.bar_ok = 1; c.committed = 0; c.status = 0; c.any = 0;
+        c.R = R; c.ns = 0; c.bar_ok = 1; c.committed = 0; c.any = 0;
+        c.st_clamped = 0; c.st_overflow = 0;
 #pragma unroll
         for (int i = 0; i < kMaxDur; ++i) c.durations[i] = p.durations[i];
     }
@@ -587,7 +671,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         if (r < R) {
             b = w.team + r * p.n_teams;
             len = p.enc_len[b];
-            if (len < 0 || len > p.T) atomicOr(&c.status, 1);
+            if (len < 0 || len > p.T) c.st_clamped = 1;
             len = min(max(len, 0), p.T);
         }
         c.b[r] = b; c.len[r] = len; c.t[r] = 0; c.n[r] = 0; c.last[r] = p.blank;
@@ -595,6 +679,21 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         c.mask[r] = 1; c.hold_k[r] = 0; c.hold_d[r] = 0; c.hold_v[r] = 0.f;
     }
     __syncthreads();
+    // this rank's slices of the bias vectors
+    {
+        const int gpa = (p.J + 3) / 4, gja = (p.NOUT + 3) / 4;
+        const int gp0 = range_lo(w.rank, p.team_size, gpa), ngp = range_hi(w.rank, p.team_size, gpa) - gp0;
+        const int gj0 = range_lo(w.rank, p.team_size, gja), ngj = range_hi(w.rank, p.team_size, gja) - gj0;
+        const int hu0 = range_lo(w.rank, p.team_size, p.H), hnu = range_hi(w.rank, p.team_size, p.H) - hu0;
+        for (int i = w.tid; i < ngp * 4; i += kThreads)
+            l.b_pred[i] = (gp0 * 4 + i < p.J) ? p.b_pred[gp0 * 4 + i] : 0.f;
+        for (int i = w.tid; i < ngj * 4; i += kThreads)
+            l.b_out[i] = (gj0 * 4 + i < p.NOUT) ? p.b_out[gj0 * 4 + i] : 0.f;
+        for (int i = w.tid; i < p.L * hnu * 4; i += kThreads) {
+            const int layer = i / (hnu * 4), rem = i - layer * hnu * 4;
+            l.b_lstm[(layer * p.nu_max) * 4 + rem] = p.bias_l[((long long)layer * p.H + hu0) * 4 + rem];
+        }
+    }
     // zero state: c of both selectors, committed h of this rank's units
     const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
     for (int i = w.tid; i < p.L * 2 * p.nu_max * kMaxRows; i += kThreads) l.c[i] = 0.f;
@@ -740,12 +839,15 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     __syncthreads();
     if (w.rank == 0 && w.tid < R) p.tok_len[c.b[w.tid]] = c.cnt[w.tid];
     if (w.rank == 0 && w.tid == 0) {
-        int st = c.status;
+        int st = (c.st_clamped ? 1 : 0) | (c.st_overflow ? 2 : 0);
         if (!ok) st |= 4;
         if (st) atomicOr(p.status, st);
-        long long *sp = p.stats + (long long)w.team * kStatCount;
+        long long *sp = p.stats + (long long)w.team * kStatStride;
         sp[kStatPred] = n_pred; sp[kStatJoint] = n_joint; sp[kStatSamples] = n_samples;
         sp[kStatPolls] = w.polls;
+#ifdef RNNT_PROFILE
+        for (int i = 0; i < 24; ++i) sp[kStatCount + i] = w.prof[i];
+#endif
     } else if (!ok && w.tid == 0) {
         atomicOr(p.status, 4);
     }
@@ -775,7 +877,7 @@ static hipError_t launch_rg(const DecodeParams &p, hipStream_t stream)
 
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
 {
-    const int n_bar = p.n_teams * 32, n_stats = p.n_teams * kStatCount;
+    const int n_bar = p.n_teams * 32, n_stats = p.n_teams * kStatStride;
     const int n = n_bar > n_stats ? n_bar : n_stats;
     hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.bar, n_bar,
                        p.abort_flag, p.status, p.stats, n_stats);

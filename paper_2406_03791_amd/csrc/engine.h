@@ -18,7 +18,8 @@ struct StageDev {
 };
 
 // Slots of the per-team statistics record.
-enum { kStatPred = 0, kStatJoint = 1, kStatSamples = 2, kStatPolls = 3, kStatCount = 8 };
+enum { kStatPred = 0, kStatJoint = 1, kStatSamples = 2, kStatPolls = 3, kStatCount = 8,
+       kStatProf = 24, kStatStride = kStatCount + kStatProf };
 
 struct DecodeParams {
     int F, E, H, L, J, V1, D, blank, NOUT;
@@ -28,8 +29,9 @@ struct DecodeParams {
     int xstride;            // floats per activation row in LDS
     int nu_max;             // most hidden units owned by a rank
     int gj_max;             // most joint output groups owned by a rank
+    int gp_max;             // most prediction-projection output groups owned by a rank
     // dynamic LDS layout, offsets in floats
-    int lds_xz, lds_red, lds_c, lds_part, lds_cand, lds_q;
+    int lds_xz, lds_red, lds_c, lds_part, lds_bias, lds_q;
     int q_in_lds;           // q = W_pred h + b_pred of the team's rows is kept in LDS
     int qstride;            // floats per q row in LDS
     unsigned lds_bytes;
@@ -53,7 +55,7 @@ struct DecodeParams {
     unsigned *bar;                // [n_teams * 32]: one counter per team, 128 B apart
     unsigned *abort_flag;
     int *status;
-    long long *stats;             // [n_teams][kStatCount]
+    long long *stats;             // [n_teams][kStatStride]; phase timers after the counters
     int *xcc;                     // [n_teams * team_size]
 };
 

@@ -66,8 +66,8 @@ struct rnnt_engine {
     DevBuf P, hbuf, qbuf, part, dpart, bar, abort_flag, status, stats, xcc;
     PackedStage st0, stl[kMaxLayers], spred, sjoint;
     // plan
-    int xstride = 0, nu_max = 0, gj_max = 0;
-    int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_cand = 0, lds_q = 0;
+    int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
+    int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
     int q_in_lds = 0, qstride = 0;
     unsigned lds_bytes = 0;
     int last_B = 0;
@@ -155,14 +155,14 @@ int plan_and_pack(rnnt_engine *e, int n_teams)
     e->lds_red = take(red);
     e->lds_c = take(L * 2 * nu_max * kMaxRows);
     e->lds_part = take(L * nu_max * kMaxRows * 4);
-    e->lds_cand = take(4 * kMaxSamples * gj_max);
+    e->lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
     if ((unsigned)off * 4u + 2048u > (unsigned)kLdsBytes) return RNNT_ERR_UNSUPPORTED;
     // q of the team's rows stays in LDS between joint steps when there is room
     e->qstride = (J + 3) & ~3;
     e->q_in_lds = ((unsigned)(off + rows_pad * e->qstride) * 4u + 2048u <= (unsigned)kLdsBytes);
     e->lds_q = e->q_in_lds ? take(rows_pad * e->qstride) : 0;
     e->lds_bytes = (unsigned)off * 4u;
-    e->xstride = xstride; e->nu_max = nu_max; e->gj_max = gj_max;
+    e->xstride = xstride; e->nu_max = nu_max; e->gj_max = gj_max; e->gp_max = gp_max;
 
     // weights
     int rc;
@@ -196,11 +196,11 @@ int plan_and_pack(rnnt_engine *e, int n_teams)
     HIP_TRY(e->part.alloc((size_t)n_teams * 2 * kMaxSamples * ts * sizeof(unsigned long long)));
     HIP_TRY(e->dpart.alloc((size_t)n_teams * 2 * kMaxSamples * ts * sizeof(unsigned long long)));
     HIP_TRY(e->bar.alloc((size_t)n_teams * 32 * sizeof(unsigned)));
-    HIP_TRY(e->stats.alloc((size_t)n_teams * kStatCount * sizeof(long long)));
+    HIP_TRY(e->stats.alloc((size_t)n_teams * kStatStride * sizeof(long long)));
     HIP_TRY(e->xcc.alloc((size_t)n_teams * ts * sizeof(int)));
     HIP_TRY(hipMemset(e->hbuf.p, 0, (size_t)n_teams * 2 * L * kMaxRows * H * sizeof(float)));
     HIP_TRY(hipMemset(e->qbuf.p, 0, (size_t)n_teams * kMaxRows * J * sizeof(float)));
-    HIP_TRY(hipMemset(e->stats.p, 0, (size_t)n_teams * kStatCount * sizeof(long long)));
+    HIP_TRY(hipMemset(e->stats.p, 0, (size_t)n_teams * kStatStride * sizeof(long long)));
     HIP_TRY(hipMemset(e->xcc.p, 0, (size_t)n_teams * ts * sizeof(int)));
     HIP_TRY(hipDeviceSynchronize());
     e->n_teams = n_teams;
@@ -262,7 +262,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.lookahead = effective_lookahead(e, rows);
     p.xstride = e->xstride; p.nu_max = e->nu_max; p.gj_max = e->gj_max;
     p.lds_xz = e->lds_xz; p.lds_red = e->lds_red; p.lds_c = e->lds_c; p.lds_part = e->lds_part;
-    p.lds_cand = e->lds_cand; p.lds_bytes = e->lds_bytes;
+    p.lds_bias = e->lds_bias; p.lds_bytes = e->lds_bytes; p.gp_max = e->gp_max;
     p.lds_q = e->lds_q; p.q_in_lds = e->q_in_lds; p.qstride = e->qstride;
     p.spin_limit = 1u << 22;
     p.enc_len = enc_len; p.P = e->P.as<float>();
@@ -466,13 +466,13 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
 {
     if (!eng || !out) return RNNT_ERR_NULL;
     HIP_TRY(hipDeviceSynchronize());
-    std::vector<long long> st((size_t)eng->n_teams * kStatCount);
+    std::vector<long long> st((size_t)eng->n_teams * kStatStride);
     std::vector<int> xcc((size_t)eng->n_teams * eng->team_size);
     HIP_TRY(hipMemcpy(st.data(), eng->stats.p, st.size() * sizeof(long long), hipMemcpyDeviceToHost));
     HIP_TRY(hipMemcpy(xcc.data(), eng->xcc.p, xcc.size() * sizeof(int), hipMemcpyDeviceToHost));
     std::memset(out, 0, sizeof(*out));
     for (int t = 0; t < eng->n_teams; ++t) {
-        const long long *s = st.data() + (size_t)t * kStatCount;
+        const long long *s = st.data() + (size_t)t * kStatStride;
         out->pred_steps += s[kStatPred];
         out->joint_steps += s[kStatJoint];
         out->joint_samples += s[kStatSamples];
@@ -487,6 +487,13 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
             else if (id != first) mixed = 1;
         }
         if (t < std::min(eng->last_B, eng->n_teams)) out->xcd_mismatch += mixed;
+    }
+    if (const char *dump = std::getenv("RNNT_DUMP_PHASES")) {
+        if (dump[0] == '1') {
+            std::fprintf(stderr, "phase timers of team 0, rank 0 (us):");
+            for (int i = 0; i < kStatProf; ++i) std::fprintf(stderr, " %d:%.1f", i, st[kStatCount + i] * 0.01);
+            std::fprintf(stderr, "\n");
+        }
     }
     out->n_teams = eng->n_teams;
     out->team_size = eng->team_size;
