@@ -52,6 +52,21 @@ def algorithmic_bytes(dims, B, variant, enc_len, tok_frames, S):
     return pred_steps * pred_bytes + joint_steps * joint_bytes, pred_steps, joint_steps
 
 
+def profiled_traffic(variant):
+    """HBM bytes per launch of the decode kernel from the committed rocprofv3
+    counter summary (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy-kernel
+    calibration stated there), or None when there is no summary."""
+    tag = {"frame": "frame_looping", "label": "label_looping", "tdt": "tdt_label_looping"}[variant]
+    path = os.path.join(ROOT, "profiles", f"decode_kernel_parakeet_b32_{tag}.md")
+    try:
+        for ln in open(path):
+            if ln.startswith("decode_kernel_traffic_bytes_per_launch:"):
+                return float(ln.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -144,7 +159,8 @@ def main() -> int:
                                  "encoder_projection": r["proj_ms"]},
                    "engine": r["stats"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": profiled_traffic(args.variant) if args.batch == 32 else None,
                      "kernel": "decode_kernel", "algorithmic_bytes": alg_bytes,
                      "schedule_steps": {"prediction": pred_steps, "joint": joint_steps}},
     }

@@ -10,6 +10,8 @@
 // per-utterance frame index) is recomputed identically by every rank from the
 // exchanged argmax results, so there is no controller rank and no flag to wait
 // for besides the barrier itself.
+#include <cstdlib>
+
 #include "engine.h"
 
 namespace rnnt {
@@ -870,6 +872,19 @@ static hipError_t launch_rg(const DecodeParams &p, hipStream_t stream)
     if (e != hipSuccess) return e;
     DecodeParams pc = p;
     void *args[] = {&pc};
+    // The cooperative launch guarantees that all work-groups are resident together, which
+    // the team barriers rely on.  RNNT_PLAIN_LAUNCH=1 uses an ordinary launch instead (the
+    // grid is one work-group per compute unit, so on an otherwise idle device it is
+    // resident too, and every wait in the kernel is bounded): rocprofv3 crashes at process
+    // exit after a cooperative launch was traced.
+    static const bool plain = [] {
+        const char *v = std::getenv("RNNT_PLAIN_LAUNCH");
+        return v && v[0] == '1';
+    }();
+    if (plain)
+        return hipLaunchKernel(reinterpret_cast<const void *>(&decode_kernel<RG>),
+                               dim3(p.n_teams * p.team_size), dim3(kThreads), args, p.lds_bytes,
+                               stream);
     return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&decode_kernel<RG>),
                                       dim3(p.n_teams * p.team_size), dim3(kThreads), args,
                                       p.lds_bytes, stream);
