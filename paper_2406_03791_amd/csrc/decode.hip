@@ -119,18 +119,22 @@ __device__ __forceinline__ bool team_barrier(const DecodeParams &p, Wg &w, Ctl &
 // The packed weights of a stage are a fixed stream per lane, independent of the
 // data, so their loads can start before the stage's input is there: kAhead
 // batches of kStepUnroll float4 steps are kept in flight in registers.
-constexpr int kAhead = 2;
+constexpr int kAheadPred = 2;    // prediction stages: pure streaming, few accumulators
+constexpr int kAheadJoint = 2;   // joint stage: 8 row groups of accumulators are live too
 
+template <int AH>
 struct WeightStream {
     const float4 *wp;
     int task;
     bool live;
-    float4 q[kAhead][kStepUnroll];
+    float4 q[AH][kStepUnroll];
 };
 
-__device__ __forceinline__ void stream_begin(WeightStream &ws, const StageDev &sd, const Wg &w,
+template <int AH>
+__device__ __forceinline__ void stream_begin(WeightStream<AH> &ws, const StageDev &sd, const Wg &w,
                                              int n_tasks, int slot)
 {
+    constexpr int kAhead = AH;
     ws.task = slot * kBlocksPerWg + w.wave * 16 + (w.lane >> 2);
     ws.live = ws.task < n_tasks;
     ws.wp = sd.w + (long long)w.rank * sd.rank_stride +
@@ -151,12 +155,13 @@ __device__ __forceinline__ void stream_begin(WeightStream &ws, const StageDev &s
 //   x            LDS, rows `xstride` floats apart; input vector `inp` of a group
 //                starts `x_inp_stride` floats further (inp = group / groups_per_inp)
 //   red_aliases_x  the results overwrite x (only valid with a single slot)
-template <int RG>
+template <int RG, int AH>
 __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n_tasks,
-                                          WeightStream &ws, const float *x, int xstride,
+                                          WeightStream<AH> &ws, const float *x, int xstride,
                                           int x_inp_stride, int groups_per_inp, float *red,
                                           bool red_aliases_x)
 {
+    constexpr int kAhead = AH;
     const int r4 = w.lane & 3;
     for (int slot = 0; slot < sd.slots; ++slot) {
         if (slot > 0) stream_begin(ws, sd, w, n_tasks, slot);
@@ -168,29 +173,46 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         v4f acc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){0.f, 0.f, 0.f, 0.f};
-        for (int i = 0; i < sd.nsteps; i += kStepUnroll) {
-            float4 cur[kStepUnroll];
+        // activations of the step after the current one are fetched from LDS while the
+        // current step's MFMAs issue; the scheduling barriers keep the compiler from
+        // hoisting more LDS reads than that (they would occupy hundreds of registers)
+        float4 xa[RG], xb[RG];
 #pragma unroll
-            for (int u = 0; u < kStepUnroll; ++u) cur[u] = ws.q[0][u];
+        for (int rg = 0; rg < RG; ++rg)
+            xa[rg] = *reinterpret_cast<const float4 *>(xr + rg * 4 * xstride);
+        // Each pass of the loop consumes the kAhead batches in turn and refills a batch in
+        // place as soon as it has been used, so the stream needs no register moves.
+#pragma unroll 1
+        for (int i0 = 0; i0 < sd.nsteps; i0 += kAhead * kStepUnroll) {
 #pragma unroll
-            for (int a = 0; a + 1 < kAhead; ++a)
+            for (int a = 0; a < kAhead; ++a) {
+                const int i = i0 + a * kStepUnroll;
+                if (i < sd.nsteps) {
 #pragma unroll
-                for (int u = 0; u < kStepUnroll; ++u) ws.q[a][u] = ws.q[a + 1][u];
-            if (live && i + kAhead * kStepUnroll < sd.nsteps) {
+                    for (int u = 0; u < kStepUnroll; ++u) {
+                        // the row is 4 floats longer than kpad, so the read past the last
+                        // step stays inside it
 #pragma unroll
-                for (int u = 0; u < kStepUnroll; ++u)
-                    ws.q[kAhead - 1][u] = ws.wp[(i + kAhead * kStepUnroll + u) * 64];
-            }
+                        for (int rg = 0; rg < RG; ++rg)
+                            xb[rg] = *reinterpret_cast<const float4 *>(xr + rg * 4 * xstride +
+                                                                       (i + u + 1) * 4);
+                        const float4 wv = ws.q[a][u];
 #pragma unroll
-            for (int u = 0; u < kStepUnroll; ++u) {
+                        for (int rg = 0; rg < RG; ++rg) {
+                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].x, wv.x, acc[rg], 0, 0, 0);
+                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].y, wv.y, acc[rg], 0, 0, 0);
+                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].z, wv.z, acc[rg], 0, 0, 0);
+                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].w, wv.w, acc[rg], 0, 0, 0);
+                        }
 #pragma unroll
-                for (int rg = 0; rg < RG; ++rg) {
-                    const float4 xv =
-                        *reinterpret_cast<const float4 *>(xr + rg * 4 * xstride + (i + u) * 4);
-                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.x, cur[u].x, acc[rg], 0, 0, 0);
-                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.y, cur[u].y, acc[rg], 0, 0, 0);
-                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.z, cur[u].z, acc[rg], 0, 0, 0);
-                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv.w, cur[u].w, acc[rg], 0, 0, 0);
+                        for (int rg = 0; rg < RG; ++rg) xa[rg] = xb[rg];
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (live && i + kAhead * kStepUnroll < sd.nsteps) {
+#pragma unroll
+                        for (int u = 0; u < kStepUnroll; ++u)
+                            ws.q[a][u] = ws.wp[(i + kAhead * kStepUnroll + u) * 64];
+                    }
                 }
             }
         }
@@ -301,7 +323,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
     const int inp_stride = rows_pad * p.xstride;
     // stage 0: recurrent parts of every layer, layer 0 completes
     PROF_MARK(w, 18);
-    WeightStream ws;
+    WeightStream<kAheadPred> ws;
     stream_begin(ws, p.st0, w, p.L * nu * p.st0.nks, 0);
     for (int layer = 0; layer < p.L; ++layer)
         fill_rows(p, w, c, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
@@ -451,7 +473,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
     const int g0 = range_lo(w.rank, p.team_size, ng_all);
     const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
     PROF_MARK(w, 18);
-    WeightStream ws;
+    WeightStream<kAheadJoint> ws;
     stream_begin(ws, p.sjoint, w, ng * p.sjoint.nks, 0);
     // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time;
     // the loads of a batch are all issued before the first use
@@ -563,14 +585,15 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
     PROF_MARK(w, 15);
     if (!team_barrier(p, w, c)) return false;
     PROF_MARK(w, 16);
-    // final argmax over the ranks, 16 lanes per sample
+    // final argmax over the ranks, a few adjacent lanes per sample
     {
-        const int s = w.tid >> 4, sub = w.tid & 15;
+        constexpr int LPS = kThreads / kMaxSamples;   // lanes per sample
+        const int s = w.tid / LPS, sub = w.tid % LPS;
         float bv = -INFINITY, dv = -INFINITY;
         int bi = 0x7fffffff, di = 0x7fffffff;
         if (s < ns && c.s_valid[s]) {
             const long long o = (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size;
-            for (int r = sub; r < p.team_size; r += 16) {
+            for (int r = sub; r < p.team_size; r += LPS) {
                 const unsigned long long pk = xload64(p.part + o + r);
                 const float v = __uint_as_float((unsigned)(pk >> 32));
                 const int i = (int)(unsigned)pk;
@@ -584,12 +607,12 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
             }
         }
 #pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, 16);
-            const int oi = __shfl_xor(bi, off, 16);
+        for (int off = LPS / 2; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, LPS);
+            const int oi = __shfl_xor(bi, off, LPS);
             if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-            const float od = __shfl_xor(dv, off, 16);
-            const int oj = __shfl_xor(di, off, 16);
+            const float od = __shfl_xor(dv, off, LPS);
+            const int oj = __shfl_xor(di, off, LPS);
             if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
         }
         if (s < ns && sub == 0) {

@@ -323,7 +323,11 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     for (int i = 0; i < d.D; ++i) e->durations[i] = d.durations[i];
     e->NOUT = d.V1 + d.D;
     e->max_B = max_B; e->max_T = max_T;
-    int n_teams = std::min(8, (int)max_B);
+    // Teams per device, chosen from measurements on MI355X: small teams mean less lock-step
+    // waiting between utterances and more independent step chains per XCD to hide the
+    // exchange latency, large teams mean fewer copies of the weight stream.  8 teams of 32
+    // work-groups (one XCD each) up to 16 utterances, 16 teams up to 48, 32 teams beyond.
+    int n_teams = max_B <= 16 ? 8 : (max_B <= 48 ? 16 : 32);
     while ((max_B + n_teams - 1) / n_teams > kMaxRows) n_teams *= 2;
     e->n_wg = (prop.multiProcessorCount / n_teams) * n_teams;
     if (e->n_wg < n_teams) return RNNT_ERR_UNSUPPORTED;
@@ -490,7 +494,8 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
     }
     if (const char *dump = std::getenv("RNNT_DUMP_PHASES")) {
         if (dump[0] == '1') {
-            std::fprintf(stderr, "phase timers of team 0, rank 0 (us):");
+            std::fprintf(stderr, "team 0: %lld prediction steps, %lld joint steps; phase timers of rank 0 (us):",
+                         st[kStatPred], st[kStatJoint]);
             for (int i = 0; i < kStatProf; ++i) std::fprintf(stderr, " %d:%.1f", i, st[kStatCount + i] * 0.01);
             std::fprintf(stderr, "\n");
         }

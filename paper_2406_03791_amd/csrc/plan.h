@@ -8,7 +8,7 @@
 // ranges; inside a rank each group is cut again along K into `nks` slices.
 // One (group, K-slice) pair is a task; a task runs on one 4-lane block of a
 // wavefront with v_mfma_f32_4x4x1 (4 rows x 4 columns per block, 16 blocks per
-// wave, 8 waves = 128 blocks per work-group).  Tasks beyond 128 go to further
+// wave, kBlocksPerWg blocks per work-group).  Tasks beyond that go to further
 // "slots", processed one after the other.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -18,9 +18,9 @@
 
 namespace rnnt {
 
-constexpr int kThreads = 512;        // threads per work-group (8 wavefronts)
-constexpr int kWaves = 8;
-constexpr int kBlocksPerWg = 128;    // 4-lane MFMA blocks per work-group
+constexpr int kThreads = 512;        // threads per work-group (8 wavefronts, 2 per SIMD)
+constexpr int kWaves = kThreads / 64;
+constexpr int kBlocksPerWg = kWaves * 16;   // 4-lane MFMA blocks per work-group
 constexpr int kMaxLayers = 4;
 constexpr int kMaxDur = 8;
 constexpr int kMaxRows = 16;         // utterances per team

@@ -49,7 +49,7 @@ def test_status_strings_and_null_checks_need_no_gpu():
 
 def test_stage_planner_covers_k_and_fits_the_blocks():
     """Host logic of the weight packer, re-stated: every (groups, K) choice must
-    cover K with nks slices of nsteps float4 steps and fit 128 blocks per slot."""
+    cover K with nks slices of nsteps float4 steps and fit the blocks of a slot."""
     import subprocess
     import tempfile
     src = r'''
@@ -61,7 +61,7 @@ int main() {
     for (int g = 1; g <= 300; g += (g < 40 ? 1 : 13)) {
       rnnt::StagePlan p = rnnt::make_stage_plan(K, g);
       if (p.kpad < K || p.kpad != p.nks * p.nsteps * 4 || p.nsteps % rnnt::kStepUnroll) bad++;
-      if (g * p.nks > 128 * p.slots) bad++;
+      if (g * p.nks > rnnt::kBlocksPerWg * p.slots) bad++;
       if (p.slots > 1 && p.nks != 1) bad++;
     }
   std::printf("%d\n", bad);
