@@ -122,7 +122,21 @@ __device__ __forceinline__ bool team_barrier(const DecodeParams &p, Wg &w, Ctl &
 constexpr int kAheadPred = 2;    // prediction stages: pure streaming, few accumulators
 constexpr int kAheadJoint = 2;   // joint stage: 8 row groups of accumulators are live too
 
-template <int AH>
+// Optional non-temporal weight loads.  Measured on MI355X they are slower for the prediction
+// stages (the teams that share an XCD stream the same packed weights and profit from each
+// other's L2 lines), so every stream currently uses ordinary loads.
+template <bool NT>
+__device__ __forceinline__ float4 load_weight(const float4 *p)
+{
+    if (NT) {
+        const float *f = reinterpret_cast<const float *>(p);
+        return make_float4(__builtin_nontemporal_load(f), __builtin_nontemporal_load(f + 1),
+                           __builtin_nontemporal_load(f + 2), __builtin_nontemporal_load(f + 3));
+    }
+    return *p;
+}
+
+template <int AH, bool NT>
 struct WeightStream {
     const float4 *wp;
     int task;
@@ -130,8 +144,8 @@ struct WeightStream {
     float4 q[AH][kStepUnroll];
 };
 
-template <int AH>
-__device__ __forceinline__ void stream_begin(WeightStream<AH> &ws, const StageDev &sd, const Wg &w,
+template <int AH, bool NT>
+__device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const StageDev &sd, const Wg &w,
                                              int n_tasks, int slot)
 {
     constexpr int kAhead = AH;
@@ -144,7 +158,7 @@ __device__ __forceinline__ void stream_begin(WeightStream<AH> &ws, const StageDe
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
             const int step = a * kStepUnroll + u;
-            ws.q[a][u] = (ws.live && step < sd.nsteps) ? ws.wp[step * 64]
+            ws.q[a][u] = (ws.live && step < sd.nsteps) ? load_weight<NT>(ws.wp + step * 64)
                                                        : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 }
@@ -155,9 +169,9 @@ __device__ __forceinline__ void stream_begin(WeightStream<AH> &ws, const StageDe
 //   x            LDS, rows `xstride` floats apart; input vector `inp` of a group
 //                starts `x_inp_stride` floats further (inp = group / groups_per_inp)
 //   red_aliases_x  the results overwrite x (only valid with a single slot)
-template <int RG, int AH>
+template <int RG, int AH, bool NT>
 __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n_tasks,
-                                          WeightStream<AH> &ws, const float *x, int xstride,
+                                          WeightStream<AH, NT> &ws, const float *x, int xstride,
                                           int x_inp_stride, int groups_per_inp, float *red,
                                           bool red_aliases_x)
 {
@@ -211,7 +225,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
                     if (live && i + kAhead * kStepUnroll < sd.nsteps) {
 #pragma unroll
                         for (int u = 0; u < kStepUnroll; ++u)
-                            ws.q[a][u] = ws.wp[(i + kAhead * kStepUnroll + u) * 64];
+                            ws.q[a][u] = load_weight<NT>(ws.wp + (i + kAhead * kStepUnroll + u) * 64);
                     }
                 }
             }
@@ -323,7 +337,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
     const int inp_stride = rows_pad * p.xstride;
     // stage 0: recurrent parts of every layer, layer 0 completes
     PROF_MARK(w, 18);
-    WeightStream<kAheadPred> ws;
+    WeightStream<kAheadPred, false> ws;
     stream_begin(ws, p.st0, w, p.L * nu * p.st0.nks, 0);
     for (int layer = 0; layer < p.L; ++layer)
         fill_rows(p, w, c, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
@@ -473,7 +487,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
     const int g0 = range_lo(w.rank, p.team_size, ng_all);
     const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
     PROF_MARK(w, 18);
-    WeightStream<kAheadJoint> ws;
+    WeightStream<kAheadJoint, false> ws;
     stream_begin(ws, p.sjoint, w, ng * p.sjoint.nks, 0);
     // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time;
     // the loads of a batch are all issued before the first use
@@ -680,8 +694,15 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         // XCC_ID hardware register, bits [3:0]
         p.xcc[blockIdx.x] = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
     }
-    // rows of this team: b = team, team + n_teams, ...
-    const int R = (p.B > w.team) ? (p.B - w.team + p.n_teams - 1) / p.n_teams : 0;
+    // Rows of this team.  Utterances are ranked by length (longest first, ties by index)
+    // and dealt to the teams in serpentine order (0..n-1, n-1..0, ...), so that the sums of
+    // the lengths, which is what a team's work grows with, come out even.  Every work-group
+    // computes the same assignment from enc_len.
+    int R = 0;
+    for (int q = 0; q * p.n_teams < p.B; ++q) {
+        const int m = ((q & 1) && p.serpentine) ? p.n_teams - 1 - w.team : w.team;
+        if (q * p.n_teams + m < p.B) ++R;
+    }
     if (R == 0) return;            // the whole team leaves: no barrier is ever entered
     if (w.tid == 0) {
         c.R = R; c.ns = 0; c.bar_ok = 1; c.committed = 0; c.any = 0;
@@ -689,19 +710,25 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 #pragma unroll
         for (int i = 0; i < kMaxDur; ++i) c.durations[i] = p.durations[i];
     }
-    __syncthreads();
     if (w.tid < kMaxRows) {
         const int r = w.tid;
-        int b = 0, len = 0;
-        if (r < R) {
-            b = w.team + r * p.n_teams;
-            len = p.enc_len[b];
-            if (len < 0 || len > p.T) c.st_clamped = 1;
-            len = min(max(len, 0), p.T);
-        }
-        c.b[r] = b; c.len[r] = len; c.t[r] = 0; c.n[r] = 0; c.last[r] = p.blank;
-        c.cnt[r] = 0; c.sel[r] = 0; c.active[r] = (r < R && len > 0); c.searching[r] = 0;
+        c.b[r] = 0; c.len[r] = 0; c.t[r] = 0; c.n[r] = 0; c.last[r] = p.blank;
+        c.cnt[r] = 0; c.sel[r] = 0; c.active[r] = 0; c.searching[r] = 0;
         c.mask[r] = 1; c.hold_k[r] = 0; c.hold_d[r] = 0; c.hold_v[r] = 0.f;
+    }
+    __syncthreads();
+    for (int b = w.tid; b < p.B; b += kThreads) {
+        const int raw = p.enc_len[b];
+        if (raw < 0 || raw > p.T) c.st_clamped = 1;
+        const int len = min(max(raw, 0), p.T);
+        int pos = 0;
+        for (int o = 0; o < p.B; ++o) {
+            const int lo = min(max(p.enc_len[o], 0), p.T);
+            pos += (lo > len || (lo == len && o < b)) ? 1 : 0;
+        }
+        const int q = pos / p.n_teams, m = pos - q * p.n_teams;
+        const int team = ((q & 1) && p.serpentine) ? p.n_teams - 1 - m : m;
+        if (team == w.team) { c.b[q] = b; c.len[q] = len; c.active[q] = len > 0; }
     }
     __syncthreads();
     // this rank's slices of the bias vectors

@@ -26,6 +26,7 @@ struct DecodeParams {
     int durations[kMaxDur];
     int B, T, S, cap, variant;
     int n_teams, team_size, lookahead;
+    int serpentine;         // deal length-ranked utterances to teams 0..n-1, n-1..0, ... (else 0..n-1, 0..n-1)
     int xstride;            // floats per activation row in LDS
     int nu_max;             // most hidden units owned by a rank
     int gj_max;             // most joint output groups owned by a rank

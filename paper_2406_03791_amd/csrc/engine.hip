@@ -258,6 +258,10 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     for (int i = 0; i < kMaxDur; ++i) p.durations[i] = e->durations[i];
     p.B = B; p.T = T; p.S = S; p.cap = cap; p.variant = variant;
     p.n_teams = e->n_teams; p.team_size = e->team_size;
+    {
+        const char *v = std::getenv("RNNT_SERPENTINE");
+        p.serpentine = v ? (v[0] == '1') : 1;
+    }
     const int rows = (B + e->n_teams - 1) / e->n_teams;
     p.lookahead = effective_lookahead(e, rows);
     p.xstride = e->xstride; p.nu_max = e->nu_max; p.gj_max = e->gj_max;
