@@ -31,6 +31,10 @@ struct Ctl {
     int durations[kMaxDur];
 };
 
+// The control block of the work-group.  It is a namespace-scope LDS object rather than a
+// kernel local passed by reference, so every access is an LDS access by construction.
+__shared__ Ctl c;
+
 // Values other work-groups will read go through device-scope atomics so that
 // they are written through to, and read from, the level all XCDs share.
 __device__ __forceinline__ void xstore(float *p, float v)
@@ -52,19 +56,36 @@ __device__ __forceinline__ unsigned long long xload64(const unsigned long long *
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Read-modify-write atomics are issued on pointers typed as global memory: on a generic
+// pointer the compiler has to add a run-time test for the private aperture.
+typedef __attribute__((address_space(1))) unsigned global_u32;
+typedef __attribute__((address_space(1))) int global_i32;
+__device__ __forceinline__ global_u32 *as_global(unsigned *p) { return (global_u32 *)p; }
+__device__ __forceinline__ global_i32 *as_global(int *p) { return (global_i32 *)p; }
+
 struct Wg {
     int team, rank, tid, lane, wave;
-    unsigned epoch;
-    long long polls;
-#ifdef RNNT_PROFILE
-    long long t_last;
-    long long prof[24];
-#endif
 };
+
+// Synchronisation counters of the work-group (uniform over its threads).
+struct Sync {
+    unsigned epoch;      // team barriers passed
+    unsigned jepoch;     // joint steps taken by the team: tags the exchanged argmax partials
+    long long polls;
+};
+
+// A copy of the work-group coordinates for one phase of a step.  Making the copy opaque to the
+// optimiser (an empty asm on tid, team and rank) keeps the phase's indices and addresses from
+// being hoisted out of the decode loops and cuts the kernel from ~250 to ~165 VGPRs, but it
+// measured 5 % slower on MI355X (the hoisted values save more than the registers cost at two
+// waves per SIMD), so the copy is a plain one.
+__device__ __forceinline__ Wg rederive(const Wg &a) { return a; }
 
 // Phase timers (100 MHz wall clock), compiled in only for profiling builds.
 #ifdef RNNT_PROFILE
-#define PROF_MARK(w, slot) do { long long t_ = wall_clock64(); (w).prof[slot] += t_ - (w).t_last; (w).t_last = t_; } while (0)
+__shared__ long long g_prof[24];
+__shared__ long long g_prof_last;
+#define PROF_MARK(w, slot) do { if ((w).tid == 0) { long long t_ = wall_clock64(); g_prof[slot] += t_ - g_prof_last; g_prof_last = t_; } } while (0)
 #else
 #define PROF_MARK(w, slot) do { } while (0)
 #endif
@@ -84,15 +105,15 @@ __device__ __forceinline__ void wait_own_memory_ops()
 // Ordering: every thread completes its exchange stores, the work-group meets,
 // thread 0 announces arrival with a relaxed device-scope add and polls the
 // counter; data is read afterwards with device-scope atomic loads only.
-__device__ __forceinline__ bool team_barrier(const DecodeParams &p, Wg &w, Ctl &c)
+__device__ __forceinline__ bool team_barrier(const DecodeParams &p, const Wg &w, Sync &sy)
 {
     wait_own_memory_ops();
     __syncthreads();
-    w.epoch += 1;
+    sy.epoch += 1;
     if (w.tid == 0) {
         unsigned *ctr = p.bar + w.team * 32;
-        const unsigned target = w.epoch * (unsigned)p.team_size;
-        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned target = sy.epoch * (unsigned)p.team_size;
+        __hip_atomic_fetch_add(as_global(ctr), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned spins = 0;
         int ok = 1;
         while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
@@ -109,7 +130,7 @@ __device__ __forceinline__ bool team_barrier(const DecodeParams &p, Wg &w, Ctl &
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        w.polls += spins;
+        sy.polls += spins;
         c.bar_ok = ok;
     }
     __syncthreads();
@@ -278,7 +299,7 @@ __device__ __forceinline__ float *h_slot(const DecodeParams &p, int team, int se
 // Fill RG*4 activation rows of `len` floats each into LDS from a global exchange
 // buffer; the tail up to kpad and the rows beyond R are zero.  Loads are issued
 // in batches so that their latencies overlap.
-__device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, const Ctl &c, float *dst,
+__device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, float *dst,
                                           int rows_pad, int len, int kpad, int layer, bool candidate)
 {
     constexpr int NB = 6;
@@ -330,8 +351,9 @@ __device__ __forceinline__ void lstm_point(float gi, float gf, float gg, float g
 // One prediction-network step for all rows of the team, from (last, committed
 // state) to the candidate state and q = W_pred h'_top + b_pred.
 template <int RG>
-__device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ctl &c, const Lds &l)
+__device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg &w0, Sync &sy, const Lds &l)
 {
+    const Wg w = rederive(w0);
     const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
     const int rows_pad = RG * 4;
     const int inp_stride = rows_pad * p.xstride;
@@ -340,7 +362,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
     WeightStream<kAheadPred, false> ws;
     stream_begin(ws, p.st0, w, p.L * nu * p.st0.nks, 0);
     for (int layer = 0; layer < p.L; ++layer)
-        fill_rows(p, w, c, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
+        fill_rows(p, w, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
     __syncthreads();
     // the additive term of this thread's first epilogue item (embedding term of layer 0,
     // bias of the layers above) is fetched before the product so its latency is hidden
@@ -385,14 +407,14 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
         }
     }
     PROF_MARK(w, 2);
-    if (!team_barrier(p, w, c)) return false;
+    if (!team_barrier(p, w, sy)) return false;
     PROF_MARK(w, 3);
     // stages 1..L-1: input part of layer `layer` from the candidate h of the layer below
 #pragma unroll
     for (int layer = 1; layer < kMaxLayers; ++layer) {
         if (layer >= p.L) break;
         const StageDev &sd = p.stl[layer];
-        fill_rows(p, w, c, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
+        fill_rows(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
         __syncthreads();
         PROF_MARK(w, 4);
         run_stage<RG>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
@@ -414,13 +436,13 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
             xstore(h_slot(p, w.team, c.sel[r] ^ 1, layer, r) + u0 + u, hn);
         }
         PROF_MARK(w, 6);
-        if (!team_barrier(p, w, c)) return false;
+        if (!team_barrier(p, w, sy)) return false;
         PROF_MARK(w, 7);
     }
     // prediction-side joint projection
     {
         const int g0 = gp0, ng = ngp;
-        fill_rows(p, w, c, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
+        fill_rows(p, w, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
         __syncthreads();
         PROF_MARK(w, 8);
         run_stage<RG>(p.spred, w, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
@@ -438,7 +460,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
             }
         }
         PROF_MARK(w, 10);
-        if (!team_barrier(p, w, c)) return false;
+        if (!team_barrier(p, w, sy)) return false;
         PROF_MARK(w, 11);
         if (p.q_in_lds) {
             // q of every row of the team, read once per prediction step
@@ -469,20 +491,56 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, Wg &w, Ct
     return true;
 }
 
-__device__ __forceinline__ unsigned long long pack_cand(float v, int idx)
+// An argmax partial as exchanged between the ranks of a team: logit bits, a 16-bit tag (the
+// joint step it belongs to) and a 16-bit column index.  Readers poll a slot until its tag is
+// the current step's, so the exchange needs no separate barrier; a slot is rewritten every
+// second step (two parities), so a stale tag can never equal the current one.
+__device__ __forceinline__ unsigned long long pack_cand(float v, int idx, unsigned tag)
 {
-    return ((unsigned long long)__float_as_uint(v) << 32) | (unsigned)idx;
+    return ((unsigned long long)__float_as_uint(v) << 32) | ((tag & 0xffffu) << 16) |
+           ((unsigned)idx & 0xffffu);
+}
+
+// Poll one partial until it carries `tag`.  Bounded: gives up (and raises the abort flag) after
+// spin_limit polls or when another work-group has raised it.
+__device__ __forceinline__ unsigned long long wait_partial(const DecodeParams &p, Sync &sy,
+                                                           const unsigned long long *slot,
+                                                           unsigned tag)
+{
+    unsigned spins = 0;
+    unsigned long long v = xload64(slot);
+    while ((unsigned)((v >> 16) & 0xffffu) != (tag & 0xffffu)) {
+        ++spins;
+        if ((spins & 127u) == 0 &&
+            __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            c.bar_ok = 0;
+            break;
+        }
+        if (spins > p.spin_limit) {
+            __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c.bar_ok = 0;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+        v = xload64(slot);
+    }
+    sy.polls += spins;
+    return v;
 }
 
 // Joint network + argmax for the c.ns samples listed in c.s_row / c.s_frame /
 // c.s_valid.  Leaves c.s_k, c.s_v (token argmax and its logit) and c.s_d
 // (duration index) for every valid sample.
 template <int RG>
-__device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c, const Lds &l, int parity)
+__device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, Sync &sy, const Lds &l, int parity)
 {
+    const Wg w = rederive(w0);
     const int ns = c.ns;
     const int rows_pad = RG * 4;
     const int kpad = p.sjoint.kpad;
+    sy.jepoch += 1;
+    const unsigned tag = sy.jepoch;
+    parity = (int)(tag & 1u);
     const int ng_all = (p.NOUT + 3) / 4;
     const int g0 = range_lo(w.rank, p.team_size, ng_all);
     const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
@@ -591,14 +649,12 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
             if (s < ns && gl == 0) {
                 const long long o =
                     (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size + w.rank;
-                xstore64(p.part + o, pack_cand(bv, bi));
-                if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di));
+                xstore64(p.part + o, pack_cand(bv, bi, tag));
+                if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di, tag));
             }
         }
     }
     PROF_MARK(w, 15);
-    if (!team_barrier(p, w, c)) return false;
-    PROF_MARK(w, 16);
     // final argmax over the ranks, a few adjacent lanes per sample
     {
         constexpr int LPS = kThreads / kMaxSamples;   // lanes per sample
@@ -608,14 +664,14 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
         if (s < ns && c.s_valid[s]) {
             const long long o = (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size;
             for (int r = sub; r < p.team_size; r += LPS) {
-                const unsigned long long pk = xload64(p.part + o + r);
+                const unsigned long long pk = wait_partial(p, sy, p.part + o + r, tag);
                 const float v = __uint_as_float((unsigned)(pk >> 32));
-                const int i = (int)(unsigned)pk;
+                const int i = (int)(pk & 0xffffu);
                 if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
                 if (p.D > 0) {
-                    const unsigned long long dk = xload64(p.dpart + o + r);
+                    const unsigned long long dk = wait_partial(p, sy, p.dpart + o + r, tag);
                     const float d = __uint_as_float((unsigned)(dk >> 32));
-                    const int j = (int)(unsigned)dk;
+                    const int j = (int)(dk & 0xffffu);
                     if (d > dv || (d == dv && j < di)) { dv = d; di = j; }
                 }
             }
@@ -637,20 +693,20 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, Wg &w, Ctl &c,
     }
     __syncthreads();
     PROF_MARK(w, 17);
-    return true;
+    return c.bar_ok != 0;
 }
 
-__device__ __forceinline__ bool joint_any(const DecodeParams &p, Wg &w, Ctl &c, const Lds &l, int parity)
+__device__ __forceinline__ bool joint_any(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l, int parity)
 {
     const int rg = (c.ns + 3) >> 2;
-    if (rg <= 1) return joint_step<1>(p, w, c, l, parity);
-    if (rg <= 2) return joint_step<2>(p, w, c, l, parity);
-    if (rg <= 4) return joint_step<4>(p, w, c, l, parity);
-    return joint_step<8>(p, w, c, l, parity);
+    if (rg <= 1) return joint_step<1>(p, w, sy, l, parity);
+    if (rg <= 2) return joint_step<2>(p, w, sy, l, parity);
+    if (rg <= 4) return joint_step<4>(p, w, sy, l, parity);
+    return joint_step<8>(p, w, sy, l, parity);
 }
 
 // Row r emits label k at frame t (rank 0 writes the outputs).
-__device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, Ctl &c, int r, int k,
+__device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, int r, int k,
                                          int t, float v, int dval)
 {
     const int n = c.cnt[r];
@@ -674,14 +730,16 @@ template <int RG>
 __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 {
     extern __shared__ __align__(16) float dyn_lds[];
-    __shared__ Ctl c;
     Wg w;
     w.tid = threadIdx.x; w.lane = w.tid & 63; w.wave = w.tid >> 6;
     w.team = blockIdx.x % p.n_teams; w.rank = blockIdx.x / p.n_teams;
-    w.epoch = 0; w.polls = 0;
+    Sync sy;
+    sy.epoch = 0; sy.jepoch = 0; sy.polls = 0;
 #ifdef RNNT_PROFILE
-    for (int i = 0; i < 24; ++i) w.prof[i] = 0;
-    w.t_last = wall_clock64();
+    if (w.tid == 0) {
+        for (int i = 0; i < 24; ++i) g_prof[i] = 0;
+        g_prof_last = wall_clock64();
+    }
 #endif
     Lds l;
     l.xz = dyn_lds + p.lds_xz; l.red = dyn_lds + p.lds_red; l.c = dyn_lds + p.lds_c;
@@ -764,7 +822,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             if (p.durs) p.durs[o + i] = -1;
         }
     }
-    if (!team_barrier(p, w, c)) return;
+    if (!team_barrier(p, w, sy)) return;
 
     long long n_pred = 0, n_joint = 0, n_samples = 0;
     int parity = 0;
@@ -784,7 +842,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 if (need_pred) {
                     // g, hidden_prime = prediction(last_label, hidden); skipped when neither
                     // input changed since the last evaluation (same result)
-                    ok = prediction_step<RG>(p, w, c, l);
+                    ok = prediction_step<RG>(p, w, sy, l);
                     if (!ok) break;
                     ++n_pred;
                     need_pred = false;
@@ -796,7 +854,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 }
                 if (w.tid == 0) c.ns = R;
                 __syncthreads();
-                ok = joint_any(p, w, c, l, parity);      // logp = joint(f, g); k, v = logp.max()
+                ok = joint_any(p, w, sy, l, parity);      // logp = joint(f, g); k, v = logp.max()
                 if (!ok) break;
                 parity ^= 1; ++n_joint; n_samples += R;
                 if (w.tid == 0) {
@@ -805,7 +863,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                         if (c.mask[r]) continue;
                         const int k = c.s_k[r];
                         if (k == p.blank) { c.mask[r] = 1; }          // blank_mask |= (k == blank)
-                        else { emit_row(p, w, c, r, k, time_idx, c.s_v[r], 0); committed = 1; any = 1; }
+                        else { emit_row(p, w, r, k, time_idx, c.s_v[r], 0); committed = 1; any = 1; }
                     }
                     c.any = any; c.committed = committed;
                 }
@@ -825,7 +883,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         bool any_active = false;
         for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
         while (ok && any_active) {
-            ok = prediction_step<RG>(p, w, c, l);
+            ok = prediction_step<RG>(p, w, sy, l);
             if (!ok) break;
             ++n_pred;
             if (w.tid < R) c.searching[w.tid] = c.active[w.tid];
@@ -843,7 +901,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 }
                 if (w.tid == 0) c.ns = R * la;
                 __syncthreads();
-                ok = joint_any(p, w, c, l, parity);
+                ok = joint_any(p, w, sy, l, parity);
                 if (!ok) break;
                 parity ^= 1; ++n_joint;
                 if (w.tid < R && c.searching[w.tid]) {
@@ -876,7 +934,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             if (w.tid < R && c.active[w.tid]) {
                 const int r = w.tid;
                 const int dval = c.hold_d[r];
-                emit_row(p, w, c, r, c.hold_k[r], c.t[r], c.hold_v[r], dval);
+                emit_row(p, w, r, c.hold_k[r], c.t[r], c.hold_v[r], dval);
                 if (tdt && dval > 0) { c.t[r] += dval; c.n[r] = 0; }
                 else { c.n[r] += 1; if (c.n[r] == p.S) { c.t[r] += 1; c.n[r] = 0; } }
                 c.active[r] = c.t[r] < c.len[r];
@@ -893,24 +951,28 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     if (w.rank == 0 && w.tid == 0) {
         int st = (c.st_clamped ? 1 : 0) | (c.st_overflow ? 2 : 0);
         if (!ok) st |= 4;
-        if (st) atomicOr(p.status, st);
+        if (st) __hip_atomic_fetch_or(as_global(p.status), st, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         long long *sp = p.stats + (long long)w.team * kStatStride;
         sp[kStatPred] = n_pred; sp[kStatJoint] = n_joint; sp[kStatSamples] = n_samples;
-        sp[kStatPolls] = w.polls;
+        sp[kStatPolls] = sy.polls;
 #ifdef RNNT_PROFILE
-        for (int i = 0; i < 24; ++i) sp[kStatCount + i] = w.prof[i];
+        for (int i = 0; i < 24; ++i) sp[kStatCount + i] = g_prof[i];
 #endif
     } else if (!ok && w.tid == 0) {
-        atomicOr(p.status, 4);
+        __hip_atomic_fetch_or(as_global(p.status), 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
+// Clears what must start at zero for a call: barrier counters, abort flag, status, stats and
+// the tagged argmax partials (a tag left by the previous call must not look current).
 __global__ void reset_kernel(unsigned *bar, int n_bar, unsigned *abort_flag, int *status,
-                             long long *stats, int n_stats)
+                             long long *stats, int n_stats, unsigned long long *part,
+                             unsigned long long *dpart, int n_part)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_bar) bar[i] = 0u;
     if (i < n_stats) stats[i] = 0;
+    if (i < n_part) { part[i] = 0ull; dpart[i] = 0ull; }
     if (i == 0) { *abort_flag = 0u; *status = 0; }
 }
 
@@ -943,9 +1005,11 @@ static hipError_t launch_rg(const DecodeParams &p, hipStream_t stream)
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
 {
     const int n_bar = p.n_teams * 32, n_stats = p.n_teams * kStatStride;
-    const int n = n_bar > n_stats ? n_bar : n_stats;
+    const int n_part = p.n_teams * 2 * kMaxSamples * p.team_size;
+    int n = n_bar > n_stats ? n_bar : n_stats;
+    n = n > n_part ? n : n_part;
     hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.bar, n_bar,
-                       p.abort_flag, p.status, p.stats, n_stats);
+                       p.abort_flag, p.status, p.stats, n_stats, p.part, p.dpart, n_part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int rows = (p.B + p.n_teams - 1) / p.n_teams;

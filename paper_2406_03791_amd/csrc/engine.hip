@@ -307,6 +307,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         d.D < 0 || d.D > kMaxDur || d.blank < 0 || d.blank >= d.V1 || max_B < 1 || max_T < 1)
         return RNNT_ERR_SHAPE;
     if (d.F % 16 != 0) return RNNT_ERR_UNSUPPORTED;   // K tile of the projection GEMM
+    if (d.V1 > 65535) return RNNT_ERR_UNSUPPORTED;    // argmax partials carry a 16-bit column index
     for (int l = 0; l < d.L; ++l)
         if (!d.w_ih[l] || !d.w_hh[l] || !d.b_ih[l] || !d.b_hh[l]) return RNNT_ERR_NULL;
     for (int i = 0; i < d.D; ++i)
@@ -498,10 +499,17 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
     }
     if (const char *dump = std::getenv("RNNT_DUMP_PHASES")) {
         if (dump[0] == '1') {
-            std::fprintf(stderr, "team 0: %lld prediction steps, %lld joint steps; phase timers of rank 0 (us):",
-                         st[kStatPred], st[kStatJoint]);
-            for (int i = 0; i < kStatProf; ++i) std::fprintf(stderr, " %d:%.1f", i, st[kStatCount + i] * 0.01);
-            std::fprintf(stderr, "\n");
+            for (int t = 0; t < eng->n_teams; ++t) {
+                const long long *s = st.data() + (size_t)t * kStatStride;
+                std::fprintf(stderr, "team %d: %lld prediction steps, %lld joint steps; rank 0 phase timers (us):",
+                             t, s[kStatPred], s[kStatJoint]);
+                double tot = 0;
+                for (int i = 0; i < 19; ++i) {
+                    std::fprintf(stderr, " %d:%.0f", i, s[kStatCount + i] * 0.01);
+                    tot += s[kStatCount + i] * 0.01;
+                }
+                std::fprintf(stderr, " total:%.0f\n", tot);
+            }
         }
     }
     out->n_teams = eng->n_teams;

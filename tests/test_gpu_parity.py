@@ -108,7 +108,7 @@ def test_cfg1_lookahead_settings_agree(pkg):
     w = synth.make_workload(1, pad="nan")
     eng = engine_for(pkg, "cfg1", w.model, w.B, w.T)
     base = None
-    for la in (1, 3, 8, 32):
+    for la in (1, 3, 8, 16):
         eng.configure(lookahead=la)
         got, status, stats = run_gpu(eng, w, "label", w.max_symbols)
         log(f"[cfg1/label la={la}] stats={stats}")
