@@ -91,7 +91,8 @@ typedef struct rnnt_model_desc {
 /* Work counters of the last decode call (rnnt_engine_stats). */
 typedef struct rnnt_stats {
     int64_t pred_steps;   /* batched prediction-network steps, summed over teams */
-    int64_t joint_steps;  /* batched joint steps (chunks), summed over teams     */
+    int64_t joint_steps;  /* batched joint steps (chunks), summed over the first */
+                          /* joint group of every team                           */
     int64_t max_pred_steps;   /* the same, for the team that did the most        */
     int64_t max_joint_steps;
     int64_t joint_samples;    /* (utterance, frame) pairs the joint evaluated    */
@@ -100,6 +101,9 @@ typedef struct rnnt_stats {
     int32_t team_size;        /* work-groups per team                            */
     int32_t lookahead;        /* frames examined per utterance per joint step    */
     int32_t xcd_mismatch;     /* teams whose work-groups were not on one XCD     */
+    int32_t joint_groups;     /* groups per team that search for labels on their */
+                              /* own (1 = the whole team together)               */
+    int32_t reserved_;
     float projection_ms;      /* device time of the encoder-projection kernel    */
     float decode_ms;          /* device time of the persistent decode kernel,    */
                               /* both from HIP events recorded on the call's     */
@@ -184,12 +188,20 @@ int rnnt_engine_status(rnnt_engine *eng, int32_t *status_out);
 int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out);
 
 /*
- * Tuning knobs, for measurement: number of teams (0 = chosen from B),
- * lookahead frames per joint step in the label-looping calls (0 = chosen from
- * the rows per team; 1 = one frame per step).  Returns RNNT_ERR_SHAPE for
- * values the engine cannot run.
+ * Tuning knobs, for measurement.  n_teams > 0: cut the device into that many
+ * teams for every decoder; 0 keeps the current layout (the default one is
+ * chosen from max_B).  joint_groups (needs n_teams > 0): joint groups per team
+ * in the label-looping calls, 0 or 1 = none; Algorithm 1 always runs plain
+ * teams.  lookahead: frames examined per utterance per joint step in the
+ * label-looping calls (0 = default of 8, 1 = one frame per step).
+ * Synchronous; repacks the weights when n_teams is given.  Returns
+ * RNNT_ERR_SHAPE for values the engine cannot run (the work-groups do not
+ * divide into the teams or groups, more than 16 utterances per team) and
+ * RNNT_ERR_UNSUPPORTED when the layout does not fit the LDS; the default
+ * layouts are then back in force.
  */
-int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t lookahead);
+int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_groups,
+                          int32_t lookahead);
 
 /* Text for a return code; for RNNT_ERR_HIP includes the last HIP error text. */
 const char *rnnt_status_string(int code);

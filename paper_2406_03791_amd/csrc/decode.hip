@@ -65,6 +65,7 @@ __device__ __forceinline__ global_i32 *as_global(int *p) { return (global_i32 *)
 
 struct Wg {
     int team, rank, tid, lane, wave;
+    int jg, jrank;       // joint group inside the team and rank inside that group
 };
 
 // Synchronisation counters of the work-group (uniform over its threads).
@@ -167,12 +168,12 @@ struct WeightStream {
 
 template <int AH, bool NT>
 __device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const StageDev &sd, const Wg &w,
-                                             int n_tasks, int slot)
+                                             int rank, int n_tasks, int slot)
 {
     constexpr int kAhead = AH;
     ws.task = slot * kBlocksPerWg + w.wave * 16 + (w.lane >> 2);
     ws.live = ws.task < n_tasks;
-    ws.wp = sd.w + (long long)w.rank * sd.rank_stride +
+    ws.wp = sd.w + (long long)rank * sd.rank_stride +
             ((long long)(slot * kWaves + w.wave) * sd.nsteps) * 64 + w.lane;
 #pragma unroll
     for (int a = 0; a < kAhead; ++a)
@@ -191,7 +192,7 @@ __device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const Sta
 //                starts `x_inp_stride` floats further (inp = group / groups_per_inp)
 //   red_aliases_x  the results overwrite x (only valid with a single slot)
 template <int RG, int AH, bool NT>
-__device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n_tasks,
+__device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int rank, int n_tasks,
                                           WeightStream<AH, NT> &ws, const float *x, int xstride,
                                           int x_inp_stride, int groups_per_inp, float *red,
                                           bool red_aliases_x)
@@ -199,7 +200,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
     constexpr int kAhead = AH;
     const int r4 = w.lane & 3;
     for (int slot = 0; slot < sd.slots; ++slot) {
-        if (slot > 0) stream_begin(ws, sd, w, n_tasks, slot);
+        if (slot > 0) stream_begin(ws, sd, w, rank, n_tasks, slot);
         const int task = ws.task;
         const bool live = ws.live;
         const int g = live ? task / sd.nks : 0;
@@ -360,7 +361,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
     // stage 0: recurrent parts of every layer, layer 0 completes
     PROF_MARK(w, 18);
     WeightStream<kAheadPred, false> ws;
-    stream_begin(ws, p.st0, w, p.L * nu * p.st0.nks, 0);
+    stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks, 0);
     for (int layer = 0; layer < p.L; ++layer)
         fill_rows(p, w, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
     __syncthreads();
@@ -375,14 +376,14 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         if (layer == 0)
             pre = *reinterpret_cast<const float4 *>(p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
     }
-    run_stage<RG>(p.st0, w, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
+    run_stage<RG>(p.st0, w, w.rank, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
                   l.red, false);
     // the next stage's weights start moving while this one finishes and the team meets
     const int ng_all_p = (p.J + 3) / 4;
     const int gp0 = range_lo(w.rank, p.team_size, ng_all_p);
     const int ngp = range_hi(w.rank, p.team_size, ng_all_p) - gp0;
-    if (p.L > 1) stream_begin(ws, p.stl[1], w, nu * p.stl[1].nks, 0);
-    else stream_begin(ws, p.spred, w, ngp * p.spred.nks, 0);
+    if (p.L > 1) stream_begin(ws, p.stl[1], w, w.rank, nu * p.stl[1].nks, 0);
+    else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks, 0);
     __syncthreads();
     PROF_MARK(w, 1);
     for (int e = w.tid; e < p.L * nu * c.R; e += kThreads) {
@@ -417,11 +418,11 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
         __syncthreads();
         PROF_MARK(w, 4);
-        run_stage<RG>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        run_stage<RG>(sd, w, w.rank, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
         if (layer + 1 < kMaxLayers && layer + 1 < p.L)
-            stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w,
+            stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
                          nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks, 0);
-        else stream_begin(ws, p.spred, w, ngp * p.spred.nks, 0);
+        else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks, 0);
         __syncthreads();
         PROF_MARK(w, 5);
         for (int e = w.tid; e < nu * c.R; e += kThreads) {
@@ -445,7 +446,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows(p, w, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
         __syncthreads();
         PROF_MARK(w, 8);
-        run_stage<RG>(p.spred, w, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        run_stage<RG>(p.spred, w, w.rank, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
         __syncthreads();
         PROF_MARK(w, 9);
         for (int e = w.tid; e < ng * c.R; e += kThreads) {
@@ -463,9 +464,10 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         if (!team_barrier(p, w, sy)) return false;
         PROF_MARK(w, 11);
         if (p.q_in_lds) {
-            // q of every row of the team, read once per prediction step
+            // q of the rows this joint group searches for, read once per prediction step
             constexpr int NB = 6;
-            const int total = rows_pad * p.qstride;
+            const int own = c.R > w.jg ? (c.R - w.jg + p.groups - 1) / p.groups : 0;
+            const int total = own * p.qstride;
             for (int base = w.tid; base < total; base += NB * kThreads) {
                 float v[NB];
 #pragma unroll
@@ -473,8 +475,9 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
                     const int idx = base + u * kThreads;
                     v[u] = 0.f;
                     if (idx < total) {
-                        const int r = idx / p.qstride, k = idx - r * p.qstride;
-                        if (r < c.R && k < p.J)
+                        const int j = idx / p.qstride, k = idx - j * p.qstride;
+                        const int r = w.jg + j * p.groups;
+                        if (k < p.J)
                             v[u] = xload(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k);
                     }
                 }
@@ -542,11 +545,11 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
     const unsigned tag = sy.jepoch;
     parity = (int)(tag & 1u);
     const int ng_all = (p.NOUT + 3) / 4;
-    const int g0 = range_lo(w.rank, p.team_size, ng_all);
-    const int ng = range_hi(w.rank, p.team_size, ng_all) - g0;
+    const int g0 = range_lo(w.jrank, p.jteam_size, ng_all);
+    const int ng = range_hi(w.jrank, p.jteam_size, ng_all) - g0;
     PROF_MARK(w, 18);
     WeightStream<kAheadJoint, false> ws;
-    stream_begin(ws, p.sjoint, w, ng * p.sjoint.nks, 0);
+    stream_begin(ws, p.sjoint, w, w.jrank, ng * p.sjoint.nks, 0);
     // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time;
     // the loads of a batch are all issued before the first use
     {
@@ -586,7 +589,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
                         const int r = c.s_row[s];
                         float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
                         if (p.q_in_lds) {
-                            qv = *reinterpret_cast<const float4 *>(l.q + r * p.qstride + k);
+                            qv = *reinterpret_cast<const float4 *>(l.q + (r / p.groups) * p.qstride + k);
                         } else {
                             const float *qr = p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k;
                             qv.x = xload(qr);
@@ -609,7 +612,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
     // with one slot the partial sums may overwrite z once every wave is done with it
     const bool alias = p.sjoint.slots == 1;
     float *red = alias ? l.xz : l.red;
-    run_stage<RG>(p.sjoint, w, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias);
+    run_stage<RG>(p.sjoint, w, w.jrank, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias);
     __syncthreads();
     PROF_MARK(w, 14);
     // Per sample, this rank's best token column and best duration column.  GP
@@ -648,7 +651,8 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
             }
             if (s < ns && gl == 0) {
                 const long long o =
-                    (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size + w.rank;
+                    (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) *
+                        p.jteam_size + w.jrank;
                 xstore64(p.part + o, pack_cand(bv, bi, tag));
                 if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di, tag));
             }
@@ -662,8 +666,9 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
         float bv = -INFINITY, dv = -INFINITY;
         int bi = 0x7fffffff, di = 0x7fffffff;
         if (s < ns && c.s_valid[s]) {
-            const long long o = (((long long)w.team * 2 + parity) * kMaxSamples + s) * p.team_size;
-            for (int r = sub; r < p.team_size; r += LPS) {
+            const long long o =
+                (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) * p.jteam_size;
+            for (int r = sub; r < p.jteam_size; r += LPS) {
                 const unsigned long long pk = wait_partial(p, sy, p.part + o + r, tag);
                 const float v = __uint_as_float((unsigned)(pk >> 32));
                 const int i = (int)(pk & 0xffffu);
@@ -710,7 +715,7 @@ __device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, int
                                          int t, float v, int dval)
 {
     const int n = c.cnt[r];
-    if (w.rank == 0) {
+    if (w.jrank == 0) {
         if (n < p.cap) {
             const long long o = (long long)c.b[r] * p.cap + n;
             p.tokens[o] = k;
@@ -733,6 +738,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     Wg w;
     w.tid = threadIdx.x; w.lane = w.tid & 63; w.wave = w.tid >> 6;
     w.team = blockIdx.x % p.n_teams; w.rank = blockIdx.x / p.n_teams;
+    w.jg = w.rank / p.jteam_size; w.jrank = w.rank - w.jg * p.jteam_size;
     Sync sy;
     sy.epoch = 0; sy.jepoch = 0; sy.polls = 0;
 #ifdef RNNT_PROFILE
@@ -793,7 +799,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     {
         const int gpa = (p.J + 3) / 4, gja = (p.NOUT + 3) / 4;
         const int gp0 = range_lo(w.rank, p.team_size, gpa), ngp = range_hi(w.rank, p.team_size, gpa) - gp0;
-        const int gj0 = range_lo(w.rank, p.team_size, gja), ngj = range_hi(w.rank, p.team_size, gja) - gj0;
+        const int gj0 = range_lo(w.jrank, p.jteam_size, gja), ngj = range_hi(w.jrank, p.jteam_size, gja) - gj0;
         const int hu0 = range_lo(w.rank, p.team_size, p.H), hnu = range_hi(w.rank, p.team_size, p.H) - hu0;
         for (int i = w.tid; i < ngp * 4; i += kThreads)
             l.b_pred[i] = (gp0 * 4 + i < p.J) ? p.b_pred[gp0 * 4 + i] : 0.f;
@@ -875,40 +881,48 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             }
         }
     } else {
-        // Label looping (RNN-T and TDT).
+        // Label looping (RNN-T and TDT).  The team runs the prediction network for all its
+        // rows; each of its joint groups then searches the next label of its own rows (row r
+        // belongs to group r mod groups) without waiting for the other groups, and publishes
+        // what the next prediction step needs of them: last label, state selector, activity.
         const bool tdt = p.D > 0;
+        const int G = p.groups, g = w.jg;
+        const int rj = R > g ? (R - g + G - 1) / G : 0;      // rows of this group
         int la = p.lookahead;
-        if (la * R > kMaxSamples) la = kMaxSamples / R;
+        if (la * rj > kMaxSamples) la = kMaxSamples / rj;
         if (la < 1) la = 1;
+        unsigned outer = 0;
         bool any_active = false;
         for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
         while (ok && any_active) {
+            ++outer;
             ok = prediction_step<RG>(p, w, sy, l);
             if (!ok) break;
             ++n_pred;
-            if (w.tid < R) c.searching[w.tid] = c.active[w.tid];
+            if (w.tid < R) c.searching[w.tid] = (w.tid % G == g) && c.active[w.tid];
             __syncthreads();
-            bool any_searching = true;
+            bool any_searching = false;
+            for (int j = 0; j < rj; ++j) any_searching = any_searching || c.searching[g + j * G];
             while (ok && any_searching) {
                 if (w.tid < kMaxSamples) {
-                    const int s = w.tid, r = s / la, i = s - r * la;
+                    const int s = w.tid, j = s / la, i = s - j * la;
                     int valid = 0, fr = 0, row = 0;
-                    if (r < R) {
-                        row = r; fr = c.t[r] + i;
-                        valid = c.searching[r] && fr < c.len[r];
+                    if (j < rj) {
+                        row = g + j * G; fr = c.t[row] + i;
+                        valid = c.searching[row] && fr < c.len[row];
                     }
                     c.s_row[s] = row; c.s_frame[s] = fr; c.s_valid[s] = valid;
                 }
-                if (w.tid == 0) c.ns = R * la;
+                if (w.tid == 0) c.ns = rj * la;
                 __syncthreads();
                 ok = joint_any(p, w, sy, l, parity);
                 if (!ok) break;
                 parity ^= 1; ++n_joint;
-                if (w.tid < R && c.searching[w.tid]) {
-                    const int r = w.tid;
+                if (w.tid < rj && c.searching[g + w.tid * G]) {
+                    const int j = w.tid, r = g + j * G;
                     int pos = 0, found = 0;
                     while (pos < la && c.t[r] + pos < c.len[r]) {
-                        const int s = r * la + pos;
+                        const int s = j * la + pos;
                         const int k = c.s_k[s];
                         const int dval = tdt ? c.durations[c.s_d[s]] : 0;
                         if (k == p.blank) {
@@ -926,13 +940,13 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 }
                 __syncthreads();
                 any_searching = false;
-                for (int r = 0; r < R; ++r) any_searching = any_searching || c.searching[r];
-                for (int s = 0; s < R * la; ++s) n_samples += c.s_valid[s];
+                for (int j = 0; j < rj; ++j) any_searching = any_searching || c.searching[g + j * G];
+                for (int s = 0; s < rj * la; ++s) n_samples += c.s_valid[s];
                 __syncthreads();
             }
             if (!ok) break;
-            if (w.tid < R && c.active[w.tid]) {
-                const int r = w.tid;
+            if (w.tid < rj && c.active[g + w.tid * G]) {
+                const int r = g + w.tid * G;
                 const int dval = c.hold_d[r];
                 emit_row(p, w, r, c.hold_k[r], c.t[r], c.hold_v[r], dval);
                 if (tdt && dval > 0) { c.t[r] += dval; c.n[r] = 0; }
@@ -940,6 +954,44 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 c.active[r] = c.t[r] < c.len[r];
             }
             __syncthreads();
+            if (G > 1) {
+                // tell the other groups about this group's rows, learn about theirs
+                if (w.jrank == 0 && w.tid < rj) {
+                    const int r = g + w.tid * G;
+                    const unsigned payload = ((unsigned)c.last[r] & 0xffffu) |
+                                             ((unsigned)c.sel[r] << 16) | ((unsigned)c.active[r] << 17);
+                    xstore64(p.rowx + (long long)w.team * kMaxRows + r,
+                             ((unsigned long long)outer << 32) | payload);
+                }
+                if (w.tid < R && w.tid % G != g) {
+                    const int r = w.tid;
+                    const unsigned long long *slot = p.rowx + (long long)w.team * kMaxRows + r;
+                    unsigned spins = 0;
+                    unsigned long long v = xload64(slot);
+                    while ((unsigned)(v >> 32) != outer) {
+                        ++spins;
+                        if ((spins & 127u) == 0 &&
+                            __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                            c.bar_ok = 0;
+                            break;
+                        }
+                        if (spins > p.spin_limit) {
+                            __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            c.bar_ok = 0;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                        v = xload64(slot);
+                    }
+                    sy.polls += spins;
+                    const unsigned payload = (unsigned)v;
+                    c.last[r] = (int)(payload & 0xffffu);
+                    c.sel[r] = (int)((payload >> 16) & 1u);
+                    c.active[r] = (int)((payload >> 17) & 1u);
+                }
+                __syncthreads();
+                ok = c.bar_ok != 0;
+            }
             any_active = false;
             for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
             __syncthreads();
@@ -947,11 +999,13 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     }
     // epilogue
     __syncthreads();
-    if (w.rank == 0 && w.tid < R) p.tok_len[c.b[w.tid]] = c.cnt[w.tid];
-    if (w.rank == 0 && w.tid == 0) {
+    if (w.jrank == 0 && w.tid < R && w.tid % p.groups == w.jg) p.tok_len[c.b[w.tid]] = c.cnt[w.tid];
+    if (w.jrank == 0 && w.tid == 0) {
         int st = (c.st_clamped ? 1 : 0) | (c.st_overflow ? 2 : 0);
         if (!ok) st |= 4;
         if (st) __hip_atomic_fetch_or(as_global(p.status), st, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (w.rank == 0 && w.tid == 0) {
         long long *sp = p.stats + (long long)w.team * kStatStride;
         sp[kStatPred] = n_pred; sp[kStatJoint] = n_joint; sp[kStatSamples] = n_samples;
         sp[kStatPolls] = sy.polls;
@@ -964,15 +1018,18 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 }
 
 // Clears what must start at zero for a call: barrier counters, abort flag, status, stats and
-// the tagged argmax partials (a tag left by the previous call must not look current).
+// the tagged argmax partials and row states (a tag left by the previous call must not look
+// current).
 __global__ void reset_kernel(unsigned *bar, int n_bar, unsigned *abort_flag, int *status,
                              long long *stats, int n_stats, unsigned long long *part,
-                             unsigned long long *dpart, int n_part)
+                             unsigned long long *dpart, int n_part, unsigned long long *rowx,
+                             int n_rowx)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_bar) bar[i] = 0u;
     if (i < n_stats) stats[i] = 0;
     if (i < n_part) { part[i] = 0ull; dpart[i] = 0ull; }
+    if (i < n_rowx) rowx[i] = 0ull;
     if (i == 0) { *abort_flag = 0u; *status = 0; }
 }
 
@@ -1005,11 +1062,12 @@ static hipError_t launch_rg(const DecodeParams &p, hipStream_t stream)
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
 {
     const int n_bar = p.n_teams * 32, n_stats = p.n_teams * kStatStride;
-    const int n_part = p.n_teams * 2 * kMaxSamples * p.team_size;
+    const int n_part = p.n_teams * p.groups * 2 * kMaxSamples * p.jteam_size;
     int n = n_bar > n_stats ? n_bar : n_stats;
     n = n > n_part ? n : n_part;
     hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.bar, n_bar,
-                       p.abort_flag, p.status, p.stats, n_stats, p.part, p.dpart, n_part);
+                       p.abort_flag, p.status, p.stats, n_stats, p.part, p.dpart, n_part, p.rowx,
+                       p.n_teams * kMaxRows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int rows = (p.B + p.n_teams - 1) / p.n_teams;

@@ -26,6 +26,7 @@ struct DecodeParams {
     int durations[kMaxDur];
     int B, T, S, cap, variant;
     int n_teams, team_size, lookahead;
+    int groups, jteam_size; // joint groups per team and work-groups per joint group
     int serpentine;         // deal length-ranked utterances to teams 0..n-1, n-1..0, ... (else 0..n-1, 0..n-1)
     int xstride;            // floats per activation row in LDS
     int nu_max;             // most hidden units owned by a rank
@@ -51,8 +52,9 @@ struct DecodeParams {
     // team workspace
     float *hbuf;                  // [n_teams][2][L][kMaxRows][H]
     float *qbuf;                  // [n_teams][kMaxRows][J]
-    unsigned long long *part;     // [n_teams][2][kMaxSamples][team_size] token partial argmax
+    unsigned long long *part;     // [n_teams * groups][2][kMaxSamples][jteam_size] token partial argmax
     unsigned long long *dpart;    // same for durations
+    unsigned long long *rowx;     // [n_teams][kMaxRows]: row state published by the owning joint group
     unsigned *bar;                // [n_teams * 32]: one counter per team, 128 B apart
     unsigned *abort_flag;
     int *status;

@@ -52,24 +52,36 @@ struct PackedStage {
 
 }  // namespace
 
+// One way of cutting the device into teams, with the weights packed for it and its workspace.
+// A team of `team_size` work-groups runs the prediction network for all its utterances; it is
+// made of `groups` joint groups of `jteam_size` work-groups, each of which owns a share of the
+// team's utterances and searches for their next labels on its own.  groups == 1 is the plain
+// arrangement (Algorithm 1 always uses it: its lock-step covers the whole team).
+struct TeamConfig {
+    int n_teams = 0, team_size = 0, groups = 1, jteam_size = 0;
+    PackedStage st0, stl[kMaxLayers], spred, sjoint;
+    DevBuf hbuf, qbuf, part, dpart, rowx, bar, stats, xcc;
+    int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
+    int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
+    int q_in_lds = 0, qstride = 0;
+    unsigned lds_bytes = 0;
+};
+
 struct rnnt_engine {
     rnnt_model_desc d{};
     int durations[kMaxDur] = {0};
     int NOUT = 0, max_B = 0, max_T = 0;
     int n_wg = 0;          // work-groups the device can keep resident (one per CU)
-    int n_teams = 0, team_size = 0, lookahead = 0;
-    // host copies of the weights that get repacked when the team size changes
+    int lookahead = 0;
+    // host copies of the weights that get repacked when the team layout changes
     std::vector<std::vector<float>> w_ih, w_hh;
     std::vector<float> w_pred, w_out;
     // device: weights used as they are, derived tables, workspace
     DevBuf w_enc, b_enc, T0, bias_l, b_pred, b_out;
-    DevBuf P, hbuf, qbuf, part, dpart, bar, abort_flag, status, stats, xcc;
-    PackedStage st0, stl[kMaxLayers], spred, sjoint;
-    // plan
-    int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
-    int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
-    int q_in_lds = 0, qstride = 0;
-    unsigned lds_bytes = 0;
+    DevBuf P, abort_flag, status;
+    TeamConfig frame_cfg;   // Algorithm 1
+    TeamConfig label_cfg;   // label looping, RNN-T and TDT
+    const TeamConfig *last_cfg = nullptr;
     int last_B = 0;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before projection, before decode, after
     bool timed = false;
@@ -108,65 +120,70 @@ int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups
     return RNNT_OK;
 }
 
-// Choose the stage plans and the LDS layout for `n_teams` teams and upload the
-// repacked weights.  Synchronous.
-int plan_and_pack(rnnt_engine *e, int n_teams)
+// Choose the stage plans and the LDS layout for `n_teams` teams of `groups` joint groups and
+// upload the repacked weights.  Synchronous.
+int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
 {
     const rnnt_model_desc &d = e->d;
-    if (n_teams < 1 || n_teams > e->n_wg) return RNNT_ERR_SHAPE;
+    if (n_teams < 1 || n_teams > e->n_wg || groups < 1) return RNNT_ERR_SHAPE;
     const int ts = e->n_wg / n_teams;
-    if (ts < 1) return RNNT_ERR_SHAPE;
+    if (ts < 1 || ts % groups != 0) return RNNT_ERR_SHAPE;
+    const int tj = ts / groups;
     const int rows_max = (e->max_B + n_teams - 1) / n_teams;
     if (rows_max > kMaxRows) return RNNT_ERR_SHAPE;
     const int H = d.H, L = d.L, J = d.J;
     auto nu_of = [&](int r) { return range_hi(r, ts, H) - range_lo(r, ts, H); };
     const int gp_all = (J + 3) / 4, gj_all = (e->NOUT + 3) / 4;
     auto gp_of = [&](int r) { return range_hi(r, ts, gp_all) - range_lo(r, ts, gp_all); };
-    auto gj_of = [&](int r) { return range_hi(r, ts, gj_all) - range_lo(r, ts, gj_all); };
+    auto gj_of = [&](int r) { return range_hi(r, tj, gj_all) - range_lo(r, tj, gj_all); };
     int nu_max = 0, gp_max = 0, gj_max = 0;
     for (int r = 0; r < ts; ++r) {
         nu_max = std::max(nu_max, nu_of(r));
         gp_max = std::max(gp_max, gp_of(r));
-        gj_max = std::max(gj_max, gj_of(r));
     }
-    e->st0.plan = make_stage_plan(H, L * nu_max);
-    for (int l = 1; l < L; ++l) e->stl[l].plan = make_stage_plan(H, nu_max);
-    e->spred.plan = make_stage_plan(H, gp_max);
-    e->sjoint.plan = make_stage_plan(J, gj_max);
+    for (int r = 0; r < tj; ++r) gj_max = std::max(gj_max, gj_of(r));
+    t.st0.plan = make_stage_plan(H, L * nu_max);
+    for (int l = 1; l < L; ++l) t.stl[l].plan = make_stage_plan(H, nu_max);
+    t.spred.plan = make_stage_plan(H, gp_max);
+    t.sjoint.plan = make_stage_plan(J, gj_max);
 
     // LDS layout
-    int kpad = std::max({e->st0.plan.kpad, e->spred.plan.kpad, e->sjoint.plan.kpad});
-    for (int l = 1; l < L; ++l) kpad = std::max(kpad, e->stl[l].plan.kpad);
+    int kpad = std::max({t.st0.plan.kpad, t.spred.plan.kpad, t.sjoint.plan.kpad});
+    for (int l = 1; l < L; ++l) kpad = std::max(kpad, t.stl[l].plan.kpad);
     const int xstride = kpad + 4;
     const int rgp = (rows_max + 3) / 4, rows_pad = rgp * 4;
     const int rgj = kMaxSamples / 4;
-    auto red_need = [&](const StagePlan &pl, int groups, int rg) {
-        return std::min(groups * pl.nks, kBlocksPerWg * pl.slots) * rg * 16;
+    auto red_need = [&](const StagePlan &pl, int grp, int rg) {
+        return std::min(grp * pl.nks, kBlocksPerWg * pl.slots) * rg * 16;
     };
     int xz = std::max(L * rows_pad * xstride, kMaxSamples * xstride);
-    int red = red_need(e->st0.plan, L * nu_max, rgp);
-    for (int l = 1; l < L; ++l) red = std::max(red, red_need(e->stl[l].plan, nu_max, rgp));
-    red = std::max(red, red_need(e->spred.plan, gp_max, rgp));
-    if (e->sjoint.plan.slots == 1) xz = std::max(xz, red_need(e->sjoint.plan, gj_max, rgj));
-    else red = std::max(red, red_need(e->sjoint.plan, gj_max, rgj));
+    int red = red_need(t.st0.plan, L * nu_max, rgp);
+    for (int l = 1; l < L; ++l) red = std::max(red, red_need(t.stl[l].plan, nu_max, rgp));
+    red = std::max(red, red_need(t.spred.plan, gp_max, rgp));
+    if (t.sjoint.plan.slots == 1) xz = std::max(xz, red_need(t.sjoint.plan, gj_max, rgj));
+    else red = std::max(red, red_need(t.sjoint.plan, gj_max, rgj));
     int off = 0;
     auto take = [&](int n) { int o = off; off += (n + 3) & ~3; return o; };
-    e->lds_xz = take(xz);
-    e->lds_red = take(red);
-    e->lds_c = take(L * 2 * nu_max * kMaxRows);
-    e->lds_part = take(L * nu_max * kMaxRows * 4);
-    e->lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
+    t.lds_xz = take(xz);
+    t.lds_red = take(red);
+    t.lds_c = take(L * 2 * nu_max * kMaxRows);
+    t.lds_part = take(L * nu_max * kMaxRows * 4);
+    t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
     if ((unsigned)off * 4u + 2048u > (unsigned)kLdsBytes) return RNNT_ERR_UNSUPPORTED;
     // q of the team's rows stays in LDS between joint steps when there is room
-    e->qstride = (J + 3) & ~3;
-    e->q_in_lds = ((unsigned)(off + rows_pad * e->qstride) * 4u + 2048u <= (unsigned)kLdsBytes);
-    e->lds_q = e->q_in_lds ? take(rows_pad * e->qstride) : 0;
-    e->lds_bytes = (unsigned)off * 4u;
-    e->xstride = xstride; e->nu_max = nu_max; e->gj_max = gj_max; e->gp_max = gp_max;
+    t.qstride = (J + 3) & ~3;
+    const int q_rows = (rows_max + groups - 1) / groups;   // a joint group keeps its own rows only
+    t.q_in_lds = ((unsigned)(off + q_rows * t.qstride) * 4u + 2048u <= (unsigned)kLdsBytes);
+    // joint groups that search on their own read q while the rest of the team may already be
+    // rewriting the global copy: they need the LDS copy
+    if (groups > 1 && !t.q_in_lds) return RNNT_ERR_UNSUPPORTED;
+    t.lds_q = t.q_in_lds ? take(q_rows * t.qstride) : 0;
+    t.lds_bytes = (unsigned)off * 4u;
+    t.xstride = xstride; t.nu_max = nu_max; t.gj_max = gj_max; t.gp_max = gp_max;
 
     // weights
     int rc;
-    rc = upload_stage(e->st0, ts, [&](int r) { return L * nu_of(r); },
+    rc = upload_stage(t.st0, ts, [&](int r) { return L * nu_of(r); },
                       [&](int r, int g, int j) -> const float * {
                           const int nu = nu_of(r);
                           const int layer = g / nu, u = range_lo(r, ts, H) + g % nu;
@@ -174,38 +191,72 @@ int plan_and_pack(rnnt_engine *e, int n_teams)
                       });
     if (rc) return rc;
     for (int l = 1; l < L; ++l) {
-        rc = upload_stage(e->stl[l], ts, nu_of, [&](int r, int g, int j) -> const float * {
+        rc = upload_stage(t.stl[l], ts, nu_of, [&](int r, int g, int j) -> const float * {
             return e->w_ih[l].data() + (size_t)(j * H + range_lo(r, ts, H) + g) * H;
         });
         if (rc) return rc;
     }
-    rc = upload_stage(e->spred, ts, gp_of, [&](int r, int g, int j) -> const float * {
+    rc = upload_stage(t.spred, ts, gp_of, [&](int r, int g, int j) -> const float * {
         const int col = (range_lo(r, ts, gp_all) + g) * 4 + j;
         return col < J ? e->w_pred.data() + (size_t)col * H : nullptr;
     });
     if (rc) return rc;
-    rc = upload_stage(e->sjoint, ts, gj_of, [&](int r, int g, int j) -> const float * {
-        const int col = (range_lo(r, ts, gj_all) + g) * 4 + j;
+    rc = upload_stage(t.sjoint, tj, gj_of, [&](int r, int g, int j) -> const float * {
+        const int col = (range_lo(r, tj, gj_all) + g) * 4 + j;
         return col < e->NOUT ? e->w_out.data() + (size_t)col * J : nullptr;
     });
     if (rc) return rc;
 
     // team workspace
-    HIP_TRY(e->hbuf.alloc((size_t)n_teams * 2 * L * kMaxRows * H * sizeof(float)));
-    HIP_TRY(e->qbuf.alloc((size_t)n_teams * kMaxRows * J * sizeof(float)));
-    HIP_TRY(e->part.alloc((size_t)n_teams * 2 * kMaxSamples * ts * sizeof(unsigned long long)));
-    HIP_TRY(e->dpart.alloc((size_t)n_teams * 2 * kMaxSamples * ts * sizeof(unsigned long long)));
-    HIP_TRY(e->bar.alloc((size_t)n_teams * 32 * sizeof(unsigned)));
-    HIP_TRY(e->stats.alloc((size_t)n_teams * kStatStride * sizeof(long long)));
-    HIP_TRY(e->xcc.alloc((size_t)n_teams * ts * sizeof(int)));
-    HIP_TRY(hipMemset(e->hbuf.p, 0, (size_t)n_teams * 2 * L * kMaxRows * H * sizeof(float)));
-    HIP_TRY(hipMemset(e->qbuf.p, 0, (size_t)n_teams * kMaxRows * J * sizeof(float)));
-    HIP_TRY(hipMemset(e->stats.p, 0, (size_t)n_teams * kStatStride * sizeof(long long)));
-    HIP_TRY(hipMemset(e->xcc.p, 0, (size_t)n_teams * ts * sizeof(int)));
+    const size_t n_part = (size_t)n_teams * groups * 2 * kMaxSamples * tj;
+    HIP_TRY(t.hbuf.alloc((size_t)n_teams * 2 * L * kMaxRows * H * sizeof(float)));
+    HIP_TRY(t.qbuf.alloc((size_t)n_teams * kMaxRows * J * sizeof(float)));
+    HIP_TRY(t.part.alloc(n_part * sizeof(unsigned long long)));
+    HIP_TRY(t.dpart.alloc(n_part * sizeof(unsigned long long)));
+    HIP_TRY(t.rowx.alloc((size_t)n_teams * kMaxRows * sizeof(unsigned long long)));
+    HIP_TRY(t.bar.alloc((size_t)n_teams * 32 * sizeof(unsigned)));
+    HIP_TRY(t.stats.alloc((size_t)n_teams * kStatStride * sizeof(long long)));
+    HIP_TRY(t.xcc.alloc((size_t)n_teams * ts * sizeof(int)));
+    HIP_TRY(hipMemset(t.hbuf.p, 0, (size_t)n_teams * 2 * L * kMaxRows * H * sizeof(float)));
+    HIP_TRY(hipMemset(t.qbuf.p, 0, (size_t)n_teams * kMaxRows * J * sizeof(float)));
+    HIP_TRY(hipMemset(t.stats.p, 0, (size_t)n_teams * kStatStride * sizeof(long long)));
+    HIP_TRY(hipMemset(t.xcc.p, 0, (size_t)n_teams * ts * sizeof(int)));
     HIP_TRY(hipDeviceSynchronize());
-    e->n_teams = n_teams;
-    e->team_size = ts;
+    t.n_teams = n_teams;
+    t.team_size = ts;
+    t.groups = groups;
+    t.jteam_size = tj;
     return RNNT_OK;
+}
+
+// Default team layouts, chosen from measurements on MI355X.
+//   Algorithm 1: small teams mean less lock-step waiting between utterances and more
+//   independent step chains per XCD to hide the exchange latency, large teams fewer copies of
+//   the weight stream: 8 teams of 32 work-groups (one XCD each) up to 16 utterances, 16 teams
+//   up to 48, 32 teams beyond.
+//   Label looping: larger teams run the prediction network for all their utterances (one
+//   weight stream per team and label), split into joint groups of at least 8 work-groups (4
+//   beyond 64 utterances) that search for the labels of their own utterances independently.
+int default_layouts(rnnt_engine *e)
+{
+    const int max_B = e->max_B;
+    int nf = max_B <= 16 ? 8 : (max_B <= 48 ? 16 : 32);
+    while ((max_B + nf - 1) / nf > kMaxRows) nf *= 2;
+    int rc = plan_and_pack(e, e->frame_cfg, nf, 1);
+    if (rc) return rc;
+    int nl = max_B <= 48 ? 8 : 16;
+    while ((max_B + nl - 1) / nl > kMaxRows) nl *= 2;
+    const int rows = (max_B + nl - 1) / nl;
+    const int ts = e->n_wg / nl, min_group = max_B > 64 ? 4 : 8;
+    int groups = 1;
+    while (groups * 2 <= rows && ts % (groups * 2) == 0 && ts / (groups * 2) >= min_group)
+        groups *= 2;
+    rc = plan_and_pack(e, e->label_cfg, nl, groups);
+    while (rc == RNNT_ERR_UNSUPPORTED && groups > 1) {
+        groups /= 2;
+        rc = plan_and_pack(e, e->label_cfg, nl, groups);
+    }
+    return rc;
 }
 
 int fetch(std::vector<float> &dst, const float *dev, size_t n)
@@ -215,10 +266,12 @@ int fetch(std::vector<float> &dst, const float *dev, size_t n)
     return RNNT_OK;
 }
 
-// Frames examined per utterance per joint step: the configured value, else 8,
-// never more than the kMaxSamples samples a step can hold.
-int effective_lookahead(const rnnt_engine *e, int rows)
+// Frames examined per utterance per joint step: the configured value, else 8, never more
+// than the kMaxSamples samples a joint group's step can hold.
+int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
 {
+    const int rows_team = (B + t.n_teams - 1) / t.n_teams;
+    const int rows = std::max(1, (rows_team + t.groups - 1) / t.groups);
     int la = e->lookahead > 0 ? e->lookahead : 8;
     if (la * rows > kMaxSamples) la = std::max(1, kMaxSamples / rows);
     return la;
@@ -248,6 +301,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
                int32_t *frames_out, float *logit_out, int32_t *durs_out, hipStream_t stream)
 {
     const rnnt_model_desc &d = e->d;
+    const TeamConfig &t = variant == kFrameLooping ? e->frame_cfg : e->label_cfg;
     HIP_TRY(hipEventRecord(e->ev[0], stream));
     HIP_TRY(launch_encoder_projection(enc_out, enc_len, e->w_enc.as<float>(), e->b_enc.as<float>(),
                                       e->P.as<float>(), B, T, d.F, d.J, stream));
@@ -257,32 +311,34 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.blank = d.blank; p.NOUT = e->NOUT;
     for (int i = 0; i < kMaxDur; ++i) p.durations[i] = e->durations[i];
     p.B = B; p.T = T; p.S = S; p.cap = cap; p.variant = variant;
-    p.n_teams = e->n_teams; p.team_size = e->team_size;
+    p.n_teams = t.n_teams; p.team_size = t.team_size;
+    p.groups = t.groups; p.jteam_size = t.jteam_size;
     {
         const char *v = std::getenv("RNNT_SERPENTINE");
         p.serpentine = v ? (v[0] == '1') : 1;
     }
-    const int rows = (B + e->n_teams - 1) / e->n_teams;
-    p.lookahead = effective_lookahead(e, rows);
-    p.xstride = e->xstride; p.nu_max = e->nu_max; p.gj_max = e->gj_max;
-    p.lds_xz = e->lds_xz; p.lds_red = e->lds_red; p.lds_c = e->lds_c; p.lds_part = e->lds_part;
-    p.lds_bias = e->lds_bias; p.lds_bytes = e->lds_bytes; p.gp_max = e->gp_max;
-    p.lds_q = e->lds_q; p.q_in_lds = e->q_in_lds; p.qstride = e->qstride;
+    p.lookahead = effective_lookahead(e, t, B);
+    p.xstride = t.xstride; p.nu_max = t.nu_max; p.gj_max = t.gj_max;
+    p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
+    p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
+    p.lds_q = t.lds_q; p.q_in_lds = t.q_in_lds; p.qstride = t.qstride;
     p.spin_limit = 1u << 22;
     p.enc_len = enc_len; p.P = e->P.as<float>();
     p.tokens = tokens_out; p.tok_len = tok_len_out; p.frames = frames_out; p.logits = logit_out;
     p.durs = durs_out;
-    p.st0 = dev_stage(e->st0);
-    for (int l = 1; l < d.L; ++l) p.stl[l] = dev_stage(e->stl[l]);
-    p.spred = dev_stage(e->spred);
-    p.sjoint = dev_stage(e->sjoint);
+    p.st0 = dev_stage(t.st0);
+    for (int l = 1; l < d.L; ++l) p.stl[l] = dev_stage(t.stl[l]);
+    p.spred = dev_stage(t.spred);
+    p.sjoint = dev_stage(t.sjoint);
     p.T0 = e->T0.as<float>(); p.bias_l = e->bias_l.as<float>();
     p.b_pred = e->b_pred.as<float>(); p.b_out = e->b_out.as<float>();
-    p.hbuf = e->hbuf.as<float>(); p.qbuf = e->qbuf.as<float>();
-    p.part = e->part.as<unsigned long long>(); p.dpart = e->dpart.as<unsigned long long>();
-    p.bar = e->bar.as<unsigned>(); p.abort_flag = e->abort_flag.as<unsigned>();
-    p.status = e->status.as<int>(); p.stats = e->stats.as<long long>(); p.xcc = e->xcc.as<int>();
+    p.hbuf = t.hbuf.as<float>(); p.qbuf = t.qbuf.as<float>();
+    p.part = t.part.as<unsigned long long>(); p.dpart = t.dpart.as<unsigned long long>();
+    p.rowx = t.rowx.as<unsigned long long>();
+    p.bar = t.bar.as<unsigned>(); p.abort_flag = e->abort_flag.as<unsigned>();
+    p.status = e->status.as<int>(); p.stats = t.stats.as<long long>(); p.xcc = t.xcc.as<int>();
     e->last_B = B;
+    e->last_cfg = &t;
     HIP_TRY(launch_decode(p, stream));
     HIP_TRY(hipEventRecord(e->ev[2], stream));
     e->timed = true;
@@ -328,14 +384,8 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     for (int i = 0; i < d.D; ++i) e->durations[i] = d.durations[i];
     e->NOUT = d.V1 + d.D;
     e->max_B = max_B; e->max_T = max_T;
-    // Teams per device, chosen from measurements on MI355X: small teams mean less lock-step
-    // waiting between utterances and more independent step chains per XCD to hide the
-    // exchange latency, large teams mean fewer copies of the weight stream.  8 teams of 32
-    // work-groups (one XCD each) up to 16 utterances, 16 teams up to 48, 32 teams beyond.
-    int n_teams = max_B <= 16 ? 8 : (max_B <= 48 ? 16 : 32);
-    while ((max_B + n_teams - 1) / n_teams > kMaxRows) n_teams *= 2;
-    e->n_wg = (prop.multiProcessorCount / n_teams) * n_teams;
-    if (e->n_wg < n_teams) return RNNT_ERR_UNSUPPORTED;
+    e->n_wg = (prop.multiProcessorCount / 32) * 32;   // every layout divides it
+    if (e->n_wg < 32) return RNNT_ERR_UNSUPPORTED;
 
     const size_t H = d.H, J = d.J;
     int rc;
@@ -373,7 +423,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     HIP_TRY(e->status.alloc(sizeof(int)));
     HIP_TRY(hipMemset(e->abort_flag.p, 0, sizeof(unsigned)));
     HIP_TRY(hipMemset(e->status.p, 0, sizeof(int)));
-    if ((rc = plan_and_pack(e, n_teams))) return rc;
+    if ((rc = default_layouts(e))) return rc;
     for (auto &x : e->ev) HIP_TRY(hipEventCreate(&x));
     HIP_TRY(hipDeviceSynchronize());
     guard.e = nullptr;
@@ -390,22 +440,20 @@ int rnnt_engine_destroy(rnnt_engine *eng)
     return RNNT_OK;
 }
 
-int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t lookahead)
+int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_groups, int32_t lookahead)
 {
     if (!eng) return RNNT_ERR_NULL;
-    if (lookahead < 0 || lookahead > kMaxSamples || n_teams < 0) return RNNT_ERR_SHAPE;
+    if (lookahead < 0 || lookahead > kMaxSamples || n_teams < 0 || joint_groups < 0)
+        return RNNT_ERR_SHAPE;
+    if (n_teams == 0 && joint_groups != 0) return RNNT_ERR_SHAPE;
     HIP_TRY(hipDeviceSynchronize());
-    if (n_teams > 0 && n_teams != eng->n_teams) {
-        hipDeviceProp_t prop;
-        int dev = 0;
-        HIP_TRY(hipGetDevice(&dev));
-        HIP_TRY(hipGetDeviceProperties(&prop, dev));
-        const int old_wg = eng->n_wg, old_teams = eng->n_teams;
-        eng->n_wg = (prop.multiProcessorCount / n_teams) * n_teams;
-        int rc = eng->n_wg >= n_teams ? plan_and_pack(eng, n_teams) : RNNT_ERR_SHAPE;
-        if (rc) {   // put the previous configuration back
-            eng->n_wg = old_wg;
-            (void)plan_and_pack(eng, old_teams);
+    if (n_teams > 0) {
+        // plain teams for Algorithm 1; the label-looping decoders split each team further
+        if (eng->n_wg % n_teams != 0) return RNNT_ERR_SHAPE;
+        int rc = plan_and_pack(eng, eng->frame_cfg, n_teams, 1);
+        if (!rc) rc = plan_and_pack(eng, eng->label_cfg, n_teams, joint_groups ? joint_groups : 1);
+        if (rc) {   // put the default layouts back
+            (void)default_layouts(eng);
             return rc;
         }
     }
@@ -475,47 +523,49 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
 {
     if (!eng || !out) return RNNT_ERR_NULL;
     HIP_TRY(hipDeviceSynchronize());
-    std::vector<long long> st((size_t)eng->n_teams * kStatStride);
-    std::vector<int> xcc((size_t)eng->n_teams * eng->team_size);
-    HIP_TRY(hipMemcpy(st.data(), eng->stats.p, st.size() * sizeof(long long), hipMemcpyDeviceToHost));
-    HIP_TRY(hipMemcpy(xcc.data(), eng->xcc.p, xcc.size() * sizeof(int), hipMemcpyDeviceToHost));
     std::memset(out, 0, sizeof(*out));
-    for (int t = 0; t < eng->n_teams; ++t) {
-        const long long *s = st.data() + (size_t)t * kStatStride;
+    const TeamConfig *t = eng->last_cfg;
+    if (!t) return RNNT_OK;
+    std::vector<long long> st((size_t)t->n_teams * kStatStride);
+    std::vector<int> xcc((size_t)t->n_teams * t->team_size);
+    HIP_TRY(hipMemcpy(st.data(), t->stats.p, st.size() * sizeof(long long), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(xcc.data(), t->xcc.p, xcc.size() * sizeof(int), hipMemcpyDeviceToHost));
+    for (int i = 0; i < t->n_teams; ++i) {
+        const long long *s = st.data() + (size_t)i * kStatStride;
         out->pred_steps += s[kStatPred];
         out->joint_steps += s[kStatJoint];
         out->joint_samples += s[kStatSamples];
         out->barrier_polls += s[kStatPolls];
         out->max_pred_steps = std::max<int64_t>(out->max_pred_steps, s[kStatPred]);
         out->max_joint_steps = std::max<int64_t>(out->max_joint_steps, s[kStatJoint]);
-        // work-group i belongs to team i % n_teams
+        // work-group b belongs to team b % n_teams
         int first = -1, mixed = 0;
-        for (int r = 0; r < eng->team_size; ++r) {
-            const int id = xcc[(size_t)r * eng->n_teams + t];
+        for (int r = 0; r < t->team_size; ++r) {
+            const int id = xcc[(size_t)r * t->n_teams + i];
             if (first < 0) first = id;
             else if (id != first) mixed = 1;
         }
-        if (t < std::min(eng->last_B, eng->n_teams)) out->xcd_mismatch += mixed;
+        if (i < std::min(eng->last_B, t->n_teams)) out->xcd_mismatch += mixed;
     }
     if (const char *dump = std::getenv("RNNT_DUMP_PHASES")) {
         if (dump[0] == '1') {
-            for (int t = 0; t < eng->n_teams; ++t) {
-                const long long *s = st.data() + (size_t)t * kStatStride;
+            for (int i = 0; i < t->n_teams; ++i) {
+                const long long *s = st.data() + (size_t)i * kStatStride;
                 std::fprintf(stderr, "team %d: %lld prediction steps, %lld joint steps; rank 0 phase timers (us):",
-                             t, s[kStatPred], s[kStatJoint]);
+                             i, s[kStatPred], s[kStatJoint]);
                 double tot = 0;
-                for (int i = 0; i < 19; ++i) {
-                    std::fprintf(stderr, " %d:%.0f", i, s[kStatCount + i] * 0.01);
-                    tot += s[kStatCount + i] * 0.01;
+                for (int k = 0; k < 20; ++k) {
+                    std::fprintf(stderr, " %d:%.0f", k, s[kStatCount + k] * 0.01);
+                    tot += s[kStatCount + k] * 0.01;
                 }
                 std::fprintf(stderr, " total:%.0f\n", tot);
             }
         }
     }
-    out->n_teams = eng->n_teams;
-    out->team_size = eng->team_size;
-    const int rows = (eng->last_B + eng->n_teams - 1) / std::max(1, eng->n_teams);
-    out->lookahead = effective_lookahead(eng, std::max(1, rows));
+    out->n_teams = t->n_teams;
+    out->team_size = t->team_size;
+    out->joint_groups = t->groups;
+    out->lookahead = effective_lookahead(eng, *t, std::max(1, eng->last_B));
     if (eng->timed) {
         HIP_TRY(hipEventElapsedTime(&out->projection_ms, eng->ev[0], eng->ev[1]));
         HIP_TRY(hipEventElapsedTime(&out->decode_ms, eng->ev[1], eng->ev[2]));
