@@ -7,17 +7,38 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip"]
+SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip",
+           "decode_f1.hip", "decode_f2.hip", "decode_f4.hip",
+           "decode_l1.hip", "decode_l2.hip", "decode_l4.hip"]
 LIB = os.path.join(HERE, "librnnt_greedy.so")
-FLAGS = (["-DRNNT_PROFILE"] if os.environ.get("RNNT_PROFILE") else []) + ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-command-line-argument"]
+OBJ_DIR = os.path.join(HERE, "_build")
+FLAGS = ((["-DRNNT_PROFILE"] if os.environ.get("RNNT_PROFILE") else []) +
+         os.environ.get("RNNT_EXTRA_FLAGS", "").split() +
+         ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-Wall", "-Wno-unused-command-line-argument"])
 
 
-def build(verbose: bool = False) -> str:
-    cmd = ["hipcc", *FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def build(verbose: bool = False, jobs: int = 8) -> str:
+    """Compile every source to an object (in parallel: the decode kernels are instantiated
+    in several translation units for that reason) and link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    os.makedirs(OBJ_DIR, exist_ok=True)
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+        cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, os.cpu_count() or 1))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     if verbose:
-        print(" ".join(cmd))
+        print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     return LIB
 

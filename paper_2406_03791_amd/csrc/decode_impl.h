@@ -1,0 +1,1081 @@
+// Persistent decode kernel (device code, included by the translation units that instantiate it) for exact RNN-T / TDT greedy decoding on gfx950.
+//
+// One launch runs the whole data-dependent double loop of Algorithm 1 (or of
+// its label-looping form) on the device.  The work-groups form independent
+// teams, each on one XCD when the dispatcher deals work-groups round-robin over
+// the XCDs; a team owns a subset of the utterances and runs the loops for them
+// with its own barrier, so no team ever waits for another.  Inside a team every
+// dense stage is split over the ranks by output columns and exchanged through
+// small global buffers; the loop control (blank mask, symbols_added, not_blank,
+// per-utterance frame index) is recomputed identically by every rank from the
+// exchanged argmax results, so there is no controller rank and no flag to wait
+// for besides the barrier itself.
+#pragma once
+#include <cstdlib>
+
+#include "engine.h"
+
+namespace rnnt {
+namespace {
+
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct Ctl {
+    int b[kMaxRows], len[kMaxRows], t[kMaxRows], n[kMaxRows], last[kMaxRows];
+    int cnt[kMaxRows], sel[kMaxRows], active[kMaxRows], searching[kMaxRows], mask[kMaxRows];
+    int hold_k[kMaxRows], hold_d[kMaxRows];
+    float hold_v[kMaxRows];
+    int s_row[kMaxSamples], s_frame[kMaxSamples], s_valid[kMaxSamples];
+    int s_k[kMaxSamples], s_d[kMaxSamples];
+    float s_v[kMaxSamples];
+    int R, ns, any, bar_ok, committed;
+    int st_clamped, st_overflow;   // set to 1 by any thread (same value from all writers)
+    int durations[kMaxDur];
+};
+
+// The control block of the work-group.  It is a namespace-scope LDS object rather than a
+// kernel local passed by reference, so every access is an LDS access by construction.
+__shared__ Ctl c;
+
+// Values other work-groups will read go through device-scope atomics so that
+// they are written through to, and read from, the level all XCDs share.
+__device__ __forceinline__ void xstore(float *p, float v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned *>(p), __float_as_uint(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float xload(const float *p)
+{
+    return __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned *>(p),
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void xstore64(unsigned long long *p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long xload64(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Read-modify-write atomics are issued on pointers typed as global memory: on a generic
+// pointer the compiler has to add a run-time test for the private aperture.
+typedef __attribute__((address_space(1))) unsigned global_u32;
+typedef __attribute__((address_space(1))) int global_i32;
+__device__ __forceinline__ global_u32 *as_global(unsigned *p) { return (global_u32 *)p; }
+__device__ __forceinline__ global_i32 *as_global(int *p) { return (global_i32 *)p; }
+
+struct Wg {
+    int team, rank, tid, lane, wave;
+    int jg, jrank;       // joint group inside the team and rank inside that group
+};
+
+// Synchronisation counters of the work-group (uniform over its threads).
+struct Sync {
+    unsigned epoch;      // team barriers passed
+    unsigned jepoch;     // joint steps taken by the team: tags the exchanged argmax partials
+    long long polls;
+};
+
+// A copy of the work-group coordinates for one phase of a step.  Making the copy opaque to the
+// optimiser (an empty asm on tid, team and rank) keeps the phase's indices and addresses from
+// being hoisted out of the decode loops and cuts the kernel from ~250 to ~165 VGPRs, but it
+// measured 5 % slower on MI355X (the hoisted values save more than the registers cost at two
+// waves per SIMD), so the copy is a plain one.
+__device__ __forceinline__ Wg rederive(const Wg &a) { return a; }
+
+// Phase timers (100 MHz wall clock), compiled in only for profiling builds.
+#ifdef RNNT_PROFILE
+__shared__ long long g_prof[24];
+__shared__ long long g_prof_last;
+#define PROF_MARK(w, slot) do { if ((w).tid == 0) { long long t_ = wall_clock64(); g_prof[slot] += t_ - g_prof_last; g_prof_last = t_; } } while (0)
+#else
+#define PROF_MARK(w, slot) do { } while (0)
+#endif
+
+// Wait until this wave's own loads and stores have been performed.  Exchange
+// data is written with device-scope atomic stores (written through to the level
+// all XCDs share), so once they are acknowledged nothing has to be flushed: the
+// barrier needs no cache write-back or invalidate, which on this part cost tens
+// of microseconds per barrier.  The asm is also a compiler barrier for memory.
+__device__ __forceinline__ void wait_own_memory_ops()
+{
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+}
+
+// Team barrier with a bounded wait.  Returns false when the wait expired or
+// another work-group raised the abort flag; the caller then leaves the kernel.
+// Ordering: every thread completes its exchange stores, the work-group meets,
+// thread 0 announces arrival with a relaxed device-scope add and polls the
+// counter; data is read afterwards with device-scope atomic loads only.
+__device__ __forceinline__ bool team_barrier(const DecodeParams &p, const Wg &w, Sync &sy)
+{
+    wait_own_memory_ops();
+    __syncthreads();
+    sy.epoch += 1;
+    if (w.tid == 0) {
+        unsigned *ctr = p.bar + w.team * 32;
+        const unsigned target = sy.epoch * (unsigned)p.team_size;
+        __hip_atomic_fetch_add(as_global(ctr), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned spins = 0;
+        int ok = 1;
+        while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            ++spins;
+            if ((spins & 127u) == 0 &&
+                __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                ok = 0;
+                break;
+            }
+            if (spins > p.spin_limit) {
+                __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        sy.polls += spins;
+        c.bar_ok = ok;
+    }
+    __syncthreads();
+    return c.bar_ok != 0;
+}
+
+// The packed weights of a stage are a fixed stream per lane, independent of the
+// data, so their loads can start before the stage's input is there: kAhead
+// batches of kStepUnroll float4 steps are kept in flight in registers.
+#ifndef RNNT_NT_PRED
+#define RNNT_NT_PRED 0
+#endif
+#ifndef RNNT_NT_JOINT
+#define RNNT_NT_JOINT 0
+#endif
+#ifndef RNNT_AHEAD_PRED
+#define RNNT_AHEAD_PRED 2
+#endif
+#ifndef RNNT_AHEAD_JOINT
+#define RNNT_AHEAD_JOINT 2
+#endif
+constexpr int kAheadPred = RNNT_AHEAD_PRED;     // prediction stages: pure streaming, few accumulators
+constexpr int kAheadJoint = RNNT_AHEAD_JOINT;   // joint stage: 8 row groups of accumulators are live too
+
+// Optional non-temporal weight loads.  Measured on MI355X they are slower for the prediction
+// stages (the teams that share an XCD stream the same packed weights and profit from each
+// other's L2 lines), so every stream currently uses ordinary loads.
+template <bool NT>
+__device__ __forceinline__ float4 load_weight(const float4 *p)
+{
+    if (NT) {
+        // one 16-byte load marked non-temporal (streaming): the line is not kept in L2
+        const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+        return make_float4(v[0], v[1], v[2], v[3]);
+    }
+    return *p;
+}
+
+template <int AH, bool NT>
+struct WeightStream {
+    const float4 *wp;
+    int task;
+    bool live;
+    float4 q[AH][kStepUnroll];
+};
+
+template <int AH, bool NT>
+__device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const StageDev &sd, const Wg &w,
+                                             int rank, int n_tasks, int slot)
+{
+    constexpr int kAhead = AH;
+    ws.task = slot * kBlocksPerWg + w.wave * 16 + (w.lane >> 2);
+    ws.live = ws.task < n_tasks;
+    ws.wp = sd.w + (long long)rank * sd.rank_stride +
+            ((long long)(slot * kWaves + w.wave) * sd.nsteps) * 64 + w.lane;
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a)
+#pragma unroll
+        for (int u = 0; u < kStepUnroll; ++u) {
+            const int step = a * kStepUnroll + u;
+            ws.q[a][u] = (ws.live && step < sd.nsteps) ? load_weight<NT>(ws.wp + step * 64)
+                                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+}
+
+// One dense stage for this rank:  red[task][rg][col][row] = sum over the task's
+// K slice of x[row][k] * W[col][k], rows in groups of 4 (RG groups).
+//   ws           weight stream of slot 0, begun by the caller
+//   x            LDS, rows `xstride` floats apart; input vector `inp` of a group
+//                starts `x_inp_stride` floats further (inp = group / groups_per_inp)
+//   red_aliases_x  the results overwrite x (only valid with a single slot)
+template <int RG, int AH, bool NT>
+__device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int rank, int n_tasks,
+                                          WeightStream<AH, NT> &ws, const float *x, int xstride,
+                                          int x_inp_stride, int groups_per_inp, float *red,
+                                          bool red_aliases_x)
+{
+    constexpr int kAhead = AH;
+    const int r4 = w.lane & 3;
+    for (int slot = 0; slot < sd.slots; ++slot) {
+        if (slot > 0) stream_begin(ws, sd, w, rank, n_tasks, slot);
+        const int task = ws.task;
+        const bool live = ws.live;
+        const int g = live ? task / sd.nks : 0;
+        const int ks = live ? task - g * sd.nks : 0;
+        const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * 4;
+        v4f acc[RG];
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){0.f, 0.f, 0.f, 0.f};
+        // activations of the step after the current one are fetched from LDS while the
+        // current step's MFMAs issue; the scheduling barriers keep the compiler from
+        // hoisting more LDS reads than that (they would occupy hundreds of registers)
+        float4 xa[RG], xb[RG];
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg)
+            xa[rg] = *reinterpret_cast<const float4 *>(xr + rg * 4 * xstride);
+        // Each pass of the loop consumes the kAhead batches in turn and refills a batch in
+        // place as soon as it has been used, so the stream needs no register moves.
+#pragma unroll 1
+        for (int i0 = 0; i0 < sd.nsteps; i0 += kAhead * kStepUnroll) {
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                const int i = i0 + a * kStepUnroll;
+                if (i < sd.nsteps) {
+#pragma unroll
+                    for (int u = 0; u < kStepUnroll; ++u) {
+                        // the row is 4 floats longer than kpad, so the read past the last
+                        // step stays inside it
+#pragma unroll
+                        for (int rg = 0; rg < RG; ++rg)
+                            xb[rg] = *reinterpret_cast<const float4 *>(xr + rg * 4 * xstride +
+                                                                       (i + u + 1) * 4);
+                        const float4 wv = ws.q[a][u];
+#pragma unroll
+                        for (int rg = 0; rg < RG; ++rg) {
+                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].x, wv.x, acc[rg], 0, 0, 0);
+                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].y, wv.y, acc[rg], 0, 0, 0);
+                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].z, wv.z, acc[rg], 0, 0, 0);
+                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].w, wv.w, acc[rg], 0, 0, 0);
+                        }
+#pragma unroll
+                        for (int rg = 0; rg < RG; ++rg) xa[rg] = xb[rg];
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (live && i + kAhead * kStepUnroll < sd.nsteps) {
+#pragma unroll
+                        for (int u = 0; u < kStepUnroll; ++u)
+                            ws.q[a][u] = load_weight<NT>(ws.wp + (i + kAhead * kStepUnroll + u) * 64);
+                    }
+                }
+            }
+        }
+        // when the partial sums reuse the memory of x, wait until every wave has read x
+        if (red_aliases_x) __syncthreads();
+        if (live) {
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                float4 o = make_float4(acc[rg][0], acc[rg][1], acc[rg][2], acc[rg][3]);
+                *reinterpret_cast<float4 *>(red + ((task * RG + rg) * 4 + r4) * 4) = o;
+            }
+        }
+    }
+}
+
+// Sums of the K-slice partials of (group g, row) for its four columns, slices
+// added in ascending order.  The loop is unrolled so the LDS reads overlap.
+template <int RG>
+__device__ __forceinline__ void reduce_tasks4(const float *red, int nks, int g, int row, float (&a)[4])
+{
+    const float *src = red + ((g * nks * RG + (row >> 2)) * 4) * 4 + (row & 3);
+    a[0] = a[1] = a[2] = a[3] = 0.f;
+#pragma unroll 4
+    for (int ks = 0; ks < nks; ++ks) {
+        const float *q = src + ks * RG * 16;
+        a[0] += q[0]; a[1] += q[4]; a[2] += q[8]; a[3] += q[12];
+    }
+}
+
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+struct Lds {
+    float *xz, *red, *c, *part, *q;
+    float *b_pred, *b_out, *b_lstm;   // this rank's slices of the bias vectors
+};
+
+// c state of this rank's units: [layer][sel][unit][row]
+__device__ __forceinline__ float *c_slot(const DecodeParams &p, const Lds &l, int layer, int sel,
+                                         int u, int row)
+{
+    return l.c + ((layer * 2 + sel) * p.nu_max + u) * p.rcap + row;
+}
+__device__ __forceinline__ float *h_slot(const DecodeParams &p, int team, int sel, int layer,
+                                         int row)
+{
+    return p.hbuf + ((((long long)team * 2 + sel) * p.L + layer) * kMaxRows + row) * p.H;
+}
+
+// Fill RG*4 activation rows of `len` floats each into LDS from a global exchange
+// buffer; the tail up to kpad and the rows beyond R are zero.  Loads are issued
+// in batches so that their latencies overlap.
+__device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, float *dst,
+                                          int rows_pad, int len, int kpad, int layer, bool candidate)
+{
+    constexpr int NB = 6;
+    const int kp2 = kpad >> 1;               // kpad is a multiple of 4
+    const int total = rows_pad * kp2;        // pairs of floats
+    const bool pairs = (len & 1) == 0;       // rows start 8-byte aligned
+    for (int base = w.tid; base < total; base += NB * kThreads) {
+        float2 v[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int idx = base + u * kThreads;
+            v[u] = make_float2(0.f, 0.f);
+            if (idx < total) {
+                const int r = idx / kp2, k = (idx - r * kp2) * 2;
+                if (r < c.R && k < len) {
+                    const int sel = candidate ? (c.sel[r] ^ 1) : c.sel[r];
+                    const float *src = h_slot(p, w.team, sel, layer, r) + k;
+                    if (pairs) {
+                        const unsigned long long q =
+                            xload64(reinterpret_cast<const unsigned long long *>(src));
+                        v[u].x = __uint_as_float((unsigned)q);
+                        v[u].y = __uint_as_float((unsigned)(q >> 32));
+                    } else {
+                        v[u].x = xload(src);
+                        if (k + 1 < len) v[u].y = xload(src + 1);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int idx = base + u * kThreads;
+            if (idx < total) {
+                const int r = idx / kp2, k = (idx - r * kp2) * 2;
+                *reinterpret_cast<float2 *>(dst + r * p.xstride + k) = v[u];
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ void lstm_point(float gi, float gf, float gg, float go, float c_old,
+                                           float &c_new, float &h_new)
+{
+    const float i_ = sigmoidf_(gi), f_ = sigmoidf_(gf), g_ = tanhf(gg), o_ = sigmoidf_(go);
+    c_new = f_ * c_old + i_ * g_;
+    h_new = o_ * tanhf(c_new);
+}
+
+// One prediction-network step for all rows of the team, from (last, committed
+// state) to the candidate state and q = W_pred h'_top + b_pred.
+template <int RG>
+__device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg &w0, Sync &sy, const Lds &l)
+{
+    const Wg w = rederive(w0);
+    const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
+    const int rows_pad = RG * 4;
+    const int inp_stride = rows_pad * p.xstride;
+    // stage 0: recurrent parts of every layer, layer 0 completes
+    PROF_MARK(w, 18);
+    WeightStream<kAheadPred, RNNT_NT_PRED != 0> ws;
+    stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks, 0);
+    for (int layer = 0; layer < p.L; ++layer)
+        fill_rows(p, w, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
+    __syncthreads();
+    // the additive term of this thread's first epilogue item (embedding term of layer 0,
+    // bias of the layers above) is fetched before the product so its latency is hidden
+    PROF_MARK(w, 0);
+    float4 pre = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (w.tid < p.L * nu * c.R) {
+        const int layer = w.tid / (nu * c.R);
+        const int rem = w.tid - layer * nu * c.R;
+        const int u = rem / c.R, r = rem - u * c.R;
+        if (layer == 0)
+            pre = *reinterpret_cast<const float4 *>(p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
+    }
+    run_stage<RG>(p.st0, w, w.rank, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
+                  l.red, false);
+    // the next stage's weights start moving while this one finishes and the team meets
+    const int ng_all_p = (p.J + 3) / 4;
+    const int gp0 = range_lo(w.rank, p.team_size, ng_all_p);
+    const int ngp = range_hi(w.rank, p.team_size, ng_all_p) - gp0;
+    if (p.L > 1) stream_begin(ws, p.stl[1], w, w.rank, nu * p.stl[1].nks, 0);
+    else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks, 0);
+    __syncthreads();
+    PROF_MARK(w, 1);
+    for (int e = w.tid; e < p.L * nu * c.R; e += kThreads) {
+        const int layer = e / (nu * c.R);
+        const int rem = e - layer * nu * c.R;
+        const int u = rem / c.R, r = rem - u * c.R;
+        const int g = layer * nu + u;
+        float a[4];
+        reduce_tasks4<RG>(l.red, p.st0.nks, g, r, a);
+        if (layer == 0) {
+            const float4 t0 = e == w.tid ? pre : *reinterpret_cast<const float4 *>(
+                p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
+            float cn, hn;
+            lstm_point(a[0] + t0.x, a[1] + t0.y, a[2] + t0.z, a[3] + t0.w,
+                       *c_slot(p, l, 0, c.sel[r], u, r), cn, hn);
+            *c_slot(p, l, 0, c.sel[r] ^ 1, u, r) = cn;
+            xstore(h_slot(p, w.team, c.sel[r] ^ 1, 0, r) + u0 + u, hn);
+        } else {
+            const float4 bl = *reinterpret_cast<const float4 *>(l.b_lstm + (layer * p.nu_max + u) * 4);
+            float *dst = l.part + ((layer * p.nu_max + u) * p.rcap + r) * 4;
+            dst[0] = a[0] + bl.x; dst[1] = a[1] + bl.y; dst[2] = a[2] + bl.z; dst[3] = a[3] + bl.w;
+        }
+    }
+    PROF_MARK(w, 2);
+    if (!team_barrier(p, w, sy)) return false;
+    PROF_MARK(w, 3);
+    // stages 1..L-1: input part of layer `layer` from the candidate h of the layer below
+#pragma unroll
+    for (int layer = 1; layer < kMaxLayers; ++layer) {
+        if (layer >= p.L) break;
+        const StageDev &sd = p.stl[layer];
+        fill_rows(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
+        __syncthreads();
+        PROF_MARK(w, 4);
+        run_stage<RG>(sd, w, w.rank, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        if (layer + 1 < kMaxLayers && layer + 1 < p.L)
+            stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
+                         nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks, 0);
+        else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks, 0);
+        __syncthreads();
+        PROF_MARK(w, 5);
+        for (int e = w.tid; e < nu * c.R; e += kThreads) {
+            const int u = e / c.R, r = e - u * c.R;
+            float a[4];
+            reduce_tasks4<RG>(l.red, sd.nks, u, r, a);
+            const float *pt = l.part + ((layer * p.nu_max + u) * p.rcap + r) * 4;
+            float cn, hn;
+            lstm_point(a[0] + pt[0], a[1] + pt[1], a[2] + pt[2], a[3] + pt[3],
+                       *c_slot(p, l, layer, c.sel[r], u, r), cn, hn);
+            *c_slot(p, l, layer, c.sel[r] ^ 1, u, r) = cn;
+            xstore(h_slot(p, w.team, c.sel[r] ^ 1, layer, r) + u0 + u, hn);
+        }
+        PROF_MARK(w, 6);
+        if (!team_barrier(p, w, sy)) return false;
+        PROF_MARK(w, 7);
+    }
+    // prediction-side joint projection
+    {
+        const int g0 = gp0, ng = ngp;
+        fill_rows(p, w, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
+        __syncthreads();
+        PROF_MARK(w, 8);
+        run_stage<RG>(p.spred, w, w.rank, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        __syncthreads();
+        PROF_MARK(w, 9);
+        for (int e = w.tid; e < ng * c.R; e += kThreads) {
+            const int g = e / c.R, r = e - g * c.R;
+            float a[4];
+            reduce_tasks4<RG>(l.red, p.spred.nks, g, r, a);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = (g0 + g) * 4 + j;
+                if (col < p.J)
+                    xstore(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + col, a[j] + l.b_pred[g * 4 + j]);
+            }
+        }
+        PROF_MARK(w, 10);
+        if (!team_barrier(p, w, sy)) return false;
+        PROF_MARK(w, 11);
+        if (p.q_in_lds) {
+            // q of the rows this joint group searches for, read once per prediction step
+            constexpr int NB = 6;
+            const int own = c.R > w.jg ? (c.R - w.jg + p.groups - 1) / p.groups : 0;
+            const int total = own * p.qstride;
+            for (int base = w.tid; base < total; base += NB * kThreads) {
+                float v[NB];
+#pragma unroll
+                for (int u = 0; u < NB; ++u) {
+                    const int idx = base + u * kThreads;
+                    v[u] = 0.f;
+                    if (idx < total) {
+                        const int j = idx / p.qstride, k = idx - j * p.qstride;
+                        const int r = w.jg + j * p.groups;
+                        if (k < p.J)
+                            v[u] = xload(p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < NB; ++u) {
+                    const int idx = base + u * kThreads;
+                    if (idx < total) l.q[idx] = v[u];
+                }
+            }
+            __syncthreads();
+        }
+        PROF_MARK(w, 12);
+    }
+    return true;
+}
+
+// An argmax partial as exchanged between the ranks of a team: logit bits, a 16-bit tag (the
+// joint step it belongs to) and a 16-bit column index.  Readers poll a slot until its tag is
+// the current step's, so the exchange needs no separate barrier; a slot is rewritten every
+// second step (two parities), so a stale tag can never equal the current one.
+__device__ __forceinline__ unsigned long long pack_cand(float v, int idx, unsigned tag)
+{
+    return ((unsigned long long)__float_as_uint(v) << 32) | ((tag & 0xffffu) << 16) |
+           ((unsigned)idx & 0xffffu);
+}
+
+// Poll one partial until it carries `tag`.  Bounded: gives up (and raises the abort flag) after
+// spin_limit polls or when another work-group has raised it.
+__device__ __forceinline__ unsigned long long wait_partial(const DecodeParams &p, Sync &sy,
+                                                           const unsigned long long *slot,
+                                                           unsigned tag)
+{
+    unsigned spins = 0;
+    unsigned long long v = xload64(slot);
+    while ((unsigned)((v >> 16) & 0xffffu) != (tag & 0xffffu)) {
+        ++spins;
+        if ((spins & 127u) == 0 &&
+            __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            c.bar_ok = 0;
+            break;
+        }
+        if (spins > p.spin_limit) {
+            __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c.bar_ok = 0;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+        v = xload64(slot);
+    }
+    sy.polls += spins;
+    return v;
+}
+
+// Joint network + argmax for the c.ns samples listed in c.s_row / c.s_frame /
+// c.s_valid.  Leaves c.s_k, c.s_v (token argmax and its logit) and c.s_d
+// (duration index) for every valid sample.
+template <int RG>
+__device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, Sync &sy, const Lds &l, int parity)
+{
+    const Wg w = rederive(w0);
+    const int ns = c.ns;
+    const int rows_pad = RG * 4;
+    const int kpad = p.sjoint.kpad;
+    sy.jepoch += 1;
+    const unsigned tag = sy.jepoch;
+    parity = (int)(tag & 1u);
+    const int ng_all = (p.NOUT + 3) / 4;
+    const int g0 = range_lo(w.jrank, p.jteam_size, ng_all);
+    const int ng = range_hi(w.jrank, p.jteam_size, ng_all) - g0;
+    PROF_MARK(w, 18);
+    WeightStream<kAheadJoint, RNNT_NT_JOINT != 0> ws;
+    stream_begin(ws, p.sjoint, w, w.jrank, ng * p.sjoint.nks, 0);
+    // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time;
+    // the loads of a batch are all issued before the first use
+    {
+        constexpr int NB = 6;
+        const int k4n = kpad >> 2;
+        const int total = rows_pad * k4n;
+        const bool vec = (p.J & 3) == 0;
+        for (int base = w.tid; base < total; base += NB * kThreads) {
+            float4 pe[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int idx = base + u * kThreads;
+                pe[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (idx < total) {
+                    const int s = idx / k4n, k = (idx - s * k4n) * 4;
+                    if (s < ns && k < p.J && c.s_valid[s]) {
+                        const int r = c.s_row[s];
+                        const float *pr = p.P + ((long long)c.b[r] * p.T + c.s_frame[s]) * p.J + k;
+                        if (vec) {
+                            pe[u] = *reinterpret_cast<const float4 *>(pr);
+                        } else {
+                            pe[u].x = pr[0];
+                            if (k + 1 < p.J) pe[u].y = pr[1];
+                            if (k + 2 < p.J) pe[u].z = pr[2];
+                            if (k + 3 < p.J) pe[u].w = pr[3];
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int idx = base + u * kThreads;
+                if (idx < total) {
+                    const int s = idx / k4n, k = (idx - s * k4n) * 4;
+                    float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (s < ns && k < p.J && c.s_valid[s]) {
+                        const int r = c.s_row[s];
+                        float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (p.q_in_lds) {
+                            qv = *reinterpret_cast<const float4 *>(l.q + (r / p.groups) * p.qstride + k);
+                        } else {
+                            const float *qr = p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k;
+                            qv.x = xload(qr);
+                            if (k + 1 < p.J) qv.y = xload(qr + 1);
+                            if (k + 2 < p.J) qv.z = xload(qr + 2);
+                            if (k + 3 < p.J) qv.w = xload(qr + 3);
+                        }
+                        z.x = fmaxf(pe[u].x + qv.x, 0.f);
+                        if (k + 1 < p.J) z.y = fmaxf(pe[u].y + qv.y, 0.f);
+                        if (k + 2 < p.J) z.z = fmaxf(pe[u].z + qv.z, 0.f);
+                        if (k + 3 < p.J) z.w = fmaxf(pe[u].w + qv.w, 0.f);
+                    }
+                    *reinterpret_cast<float4 *>(l.xz + s * p.xstride + k) = z;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    PROF_MARK(w, 13);
+    // with one slot the partial sums may overwrite z once every wave is done with it
+    const bool alias = p.sjoint.slots == 1;
+    float *red = alias ? l.xz : l.red;
+    run_stage<RG>(p.sjoint, w, w.jrank, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias);
+    __syncthreads();
+    PROF_MARK(w, 14);
+    // Per sample, this rank's best token column and best duration column.  GP
+    // adjacent lanes share a sample and each takes the groups gl, gl + GP, ...;
+    // groups ascend with the lane, so a strict > keeps the lowest index.
+    {
+        int gp = 1;
+        while (gp < ng && gp < 64) gp <<= 1;
+        for (int base = 0; base < ns * gp; base += kThreads) {
+            const int e = base + w.tid;
+            const int s = e / gp, gl = e - s * gp;
+            float bv = -INFINITY, dv = -INFINITY;
+            int bi = 0x7fffffff, di = 0x7fffffff;
+            if (s < ns) {
+                for (int g = gl; g < ng; g += gp) {
+                    float a[4];
+                    reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int col = (g0 + g) * 4 + j;
+                        if (col < p.NOUT) {
+                            const float v = a[j] + l.b_out[g * 4 + j];
+                            if (col < p.V1) { if (v > bv) { bv = v; bi = col; } }
+                            else { if (v > dv) { dv = v; di = col - p.V1; } }
+                        }
+                    }
+                }
+            }
+            for (int off = 1; off < gp; off <<= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oi = __shfl_xor(bi, off);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                const float od = __shfl_xor(dv, off);
+                const int oj = __shfl_xor(di, off);
+                if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
+            }
+            if (s < ns && gl == 0) {
+                const long long o =
+                    (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) *
+                        p.jteam_size + w.jrank;
+                xstore64(p.part + o, pack_cand(bv, bi, tag));
+                if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di, tag));
+            }
+        }
+    }
+    PROF_MARK(w, 15);
+    // final argmax over the ranks, a few adjacent lanes per sample
+    {
+        constexpr int LPS = kThreads / kMaxSamples;   // lanes per sample
+        const int s = w.tid / LPS, sub = w.tid % LPS;
+        float bv = -INFINITY, dv = -INFINITY;
+        int bi = 0x7fffffff, di = 0x7fffffff;
+        if (s < ns && c.s_valid[s]) {
+            const long long o =
+                (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) * p.jteam_size;
+            for (int r = sub; r < p.jteam_size; r += LPS) {
+                const unsigned long long pk = wait_partial(p, sy, p.part + o + r, tag);
+                const float v = __uint_as_float((unsigned)(pk >> 32));
+                const int i = (int)(pk & 0xffffu);
+                if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+                if (p.D > 0) {
+                    const unsigned long long dk = wait_partial(p, sy, p.dpart + o + r, tag);
+                    const float d = __uint_as_float((unsigned)(dk >> 32));
+                    const int j = (int)(dk & 0xffffu);
+                    if (d > dv || (d == dv && j < di)) { dv = d; di = j; }
+                }
+            }
+        }
+#pragma unroll
+        for (int off = LPS / 2; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, LPS);
+            const int oi = __shfl_xor(bi, off, LPS);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            const float od = __shfl_xor(dv, off, LPS);
+            const int oj = __shfl_xor(di, off, LPS);
+            if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
+        }
+        if (s < ns && sub == 0) {
+            // no finite logit (NaN input inside enc_len): fall back to blank, never index out of range
+            if ((unsigned)bi >= (unsigned)p.V1) bi = p.blank;
+            c.s_k[s] = bi; c.s_v[s] = bv; c.s_d[s] = (p.D > 0 && di < p.D) ? di : 0;
+        }
+    }
+    __syncthreads();
+    PROF_MARK(w, 17);
+    return c.bar_ok != 0;
+}
+
+// Row r emits label k at frame t (rank 0 writes the outputs).
+__device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, int r, int k,
+                                         int t, float v, int dval)
+{
+    const int n = c.cnt[r];
+    if (w.jrank == 0) {
+        if (n < p.cap) {
+            const long long o = (long long)c.b[r] * p.cap + n;
+            p.tokens[o] = k;
+            if (p.frames) p.frames[o] = t;
+            if (p.logits) p.logits[o] = v;
+            if (p.durs) p.durs[o] = dval;
+        } else {
+            c.st_overflow = 1;
+        }
+    }
+    c.cnt[r] = n + 1;
+    c.last[r] = k;
+    c.sel[r] ^= 1;     // the candidate state becomes the state
+}
+
+// RG: row groups (of 4) of a team in the prediction stages; RGJ: row groups a joint step is
+// laid out for (its samples never exceed 4 * RGJ); VARIANT: which loop nest.
+template <int RG, int RGJ, int VARIANT>
+__global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
+{
+    extern __shared__ __align__(16) float dyn_lds[];
+    Wg w;
+    w.tid = threadIdx.x; w.lane = w.tid & 63; w.wave = w.tid >> 6;
+    w.team = blockIdx.x % p.n_teams; w.rank = blockIdx.x / p.n_teams;
+    w.jg = w.rank / p.jteam_size; w.jrank = w.rank - w.jg * p.jteam_size;
+    Sync sy;
+    sy.epoch = 0; sy.jepoch = 0; sy.polls = 0;
+#ifdef RNNT_PROFILE
+    if (w.tid == 0) {
+        for (int i = 0; i < 24; ++i) g_prof[i] = 0;
+        g_prof_last = wall_clock64();
+    }
+#endif
+    Lds l;
+    l.xz = dyn_lds + p.lds_xz; l.red = dyn_lds + p.lds_red; l.c = dyn_lds + p.lds_c;
+    l.part = dyn_lds + p.lds_part; l.q = dyn_lds + p.lds_q;
+    l.b_pred = dyn_lds + p.lds_bias;
+    l.b_out = l.b_pred + 4 * p.gp_max;
+    l.b_lstm = l.b_out + 4 * p.gj_max;
+
+    if (w.tid == 0) {
+        // XCC_ID hardware register, bits [3:0]
+        p.xcc[blockIdx.x] = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
+    }
+    // Rows of this team.  Utterances are ranked by length (longest first, ties by index)
+    // and dealt to the teams in serpentine order (0..n-1, n-1..0, ...), so that the sums of
+    // the lengths, which is what a team's work grows with, come out even.  Every work-group
+    // computes the same assignment from enc_len.
+    int R = 0;
+    for (int q = 0; q * p.n_teams < p.B; ++q) {
+        const int m = ((q & 1) && p.serpentine) ? p.n_teams - 1 - w.team : w.team;
+        if (q * p.n_teams + m < p.B) ++R;
+    }
+    if (R == 0) return;            // the whole team leaves: no barrier is ever entered
+    if (w.tid == 0) {
+        c.R = R; c.ns = 0; c.bar_ok = 1; c.committed = 0; c.any = 0;
+        c.st_clamped = 0; c.st_overflow = 0;
+#pragma unroll
+        for (int i = 0; i < kMaxDur; ++i) c.durations[i] = p.durations[i];
+    }
+    if (w.tid < kMaxRows) {
+        const int r = w.tid;
+        c.b[r] = 0; c.len[r] = 0; c.t[r] = 0; c.n[r] = 0; c.last[r] = p.blank;
+        c.cnt[r] = 0; c.sel[r] = 0; c.active[r] = 0; c.searching[r] = 0;
+        c.mask[r] = 1; c.hold_k[r] = 0; c.hold_d[r] = 0; c.hold_v[r] = 0.f;
+    }
+    __syncthreads();
+    for (int b = w.tid; b < p.B; b += kThreads) {
+        const int raw = p.enc_len[b];
+        if (raw < 0 || raw > p.T) c.st_clamped = 1;
+        const int len = min(max(raw, 0), p.T);
+        int pos = 0;
+        for (int o = 0; o < p.B; ++o) {
+            const int lo = min(max(p.enc_len[o], 0), p.T);
+            pos += (lo > len || (lo == len && o < b)) ? 1 : 0;
+        }
+        const int q = pos / p.n_teams, m = pos - q * p.n_teams;
+        const int team = ((q & 1) && p.serpentine) ? p.n_teams - 1 - m : m;
+        if (team == w.team) { c.b[q] = b; c.len[q] = len; c.active[q] = len > 0; }
+    }
+    __syncthreads();
+    // this rank's slices of the bias vectors
+    {
+        const int gpa = (p.J + 3) / 4, gja = (p.NOUT + 3) / 4;
+        const int gp0 = range_lo(w.rank, p.team_size, gpa), ngp = range_hi(w.rank, p.team_size, gpa) - gp0;
+        const int gj0 = range_lo(w.jrank, p.jteam_size, gja), ngj = range_hi(w.jrank, p.jteam_size, gja) - gj0;
+        const int hu0 = range_lo(w.rank, p.team_size, p.H), hnu = range_hi(w.rank, p.team_size, p.H) - hu0;
+        for (int i = w.tid; i < ngp * 4; i += kThreads)
+            l.b_pred[i] = (gp0 * 4 + i < p.J) ? p.b_pred[gp0 * 4 + i] : 0.f;
+        for (int i = w.tid; i < ngj * 4; i += kThreads)
+            l.b_out[i] = (gj0 * 4 + i < p.NOUT) ? p.b_out[gj0 * 4 + i] : 0.f;
+        for (int i = w.tid; i < p.L * hnu * 4; i += kThreads) {
+            const int layer = i / (hnu * 4), rem = i - layer * hnu * 4;
+            l.b_lstm[(layer * p.nu_max) * 4 + rem] = p.bias_l[((long long)layer * p.H + hu0) * 4 + rem];
+        }
+    }
+    // zero state: c of both selectors, committed h of this rank's units
+    const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
+    for (int i = w.tid; i < p.L * 2 * p.nu_max * p.rcap; i += kThreads) l.c[i] = 0.f;
+    for (int i = w.tid; i < p.L * R * nu; i += kThreads) {
+        const int layer = i / (R * nu), rem = i - layer * R * nu;
+        const int r = rem / nu, u = rem - r * nu;
+        xstore(h_slot(p, w.team, 0, layer, r) + u0 + u, 0.f);
+    }
+    // output fill: every rank clears a share of its team's rows
+    for (int r = 0; r < R; ++r) {
+        const long long o = (long long)c.b[r] * p.cap;
+        for (int i = w.rank * kThreads + w.tid; i < p.cap; i += p.team_size * kThreads) {
+            p.tokens[o + i] = -1;
+            if (p.frames) p.frames[o + i] = -1;
+            if (p.logits) p.logits[o + i] = 0.f;
+            if (p.durs) p.durs[o + i] = -1;
+        }
+    }
+    if (!team_barrier(p, w, sy)) return;
+
+    long long n_pred = 0, n_joint = 0, n_samples = 0;
+    int parity = 0;
+    bool ok = true;
+
+    if constexpr (VARIANT == kFrameLooping) {
+        // Algorithm 1 on this team's rows.  A joint step also evaluates the next frames of
+        // every row with the same g (lookahead); those results stand in for the first joint
+        // evaluation of the following frames for as long as no row emits, that is, for as
+        // long as no (last_label, hidden) changes: the same values the algorithm would compute.
+        int la = p.lookahead;
+        if (la * R > RGJ * 4) la = RGJ * 4 / R;      // the host sized RGJ for lookahead * rows
+        if (la < 1) la = 1;
+        int max_out_len = 0;
+        for (int r = 0; r < R; ++r) max_out_len = max(max_out_len, c.len[r]);
+        bool need_pred = true;     // nothing computed yet for (last_label, hidden)
+        int win0 = 0, win_n = 0;   // frames [win0, win0 + win_n) have results for the current g
+        for (int time_idx = 0; ok && time_idx < max_out_len; ++time_idx) {
+            if (w.tid < R) c.mask[w.tid] = time_idx >= c.len[w.tid];   // blank_mask
+            int symbols_added = 0;
+            bool not_blank = true;
+            __syncthreads();
+            while (ok && not_blank && symbols_added < p.S) {
+                if (need_pred) {
+                    // g, hidden_prime = prediction(last_label, hidden); skipped when neither
+                    // input changed since the last evaluation (same result)
+                    ok = prediction_step<RG>(p, w, sy, l);
+                    if (!ok) break;
+                    ++n_pred;
+                    need_pred = false;
+                    win_n = 0;
+                }
+                int off = 0;
+                if (symbols_added == 0 && time_idx >= win0 && time_idx < win0 + win_n) {
+                    off = time_idx - win0;
+                } else {
+                    const int n_ahead = min(la, max_out_len - time_idx);
+                    if (w.tid < kMaxSamples) {
+                        const int s = w.tid, i = s / R, r = s - i * R;
+                        const int fr = time_idx + i;
+                        c.s_row[s] = r; c.s_frame[s] = fr;
+                        c.s_valid[s] = i < n_ahead && (i == 0 ? !c.mask[r] : fr < c.len[r]);
+                    }
+                    if (w.tid == 0) c.ns = R * n_ahead;
+                    __syncthreads();
+                    ok = joint_step<RGJ>(p, w, sy, l, parity);      // logp = joint(f, g); k, v = logp.max()
+                    if (!ok) break;
+                    parity ^= 1; ++n_joint; n_samples += R * n_ahead;
+                    win0 = time_idx; win_n = n_ahead;
+                }
+                if (w.tid == 0) {
+                    int any = 0;
+                    for (int r = 0; r < R; ++r) {
+                        if (c.mask[r]) continue;
+                        const int k = c.s_k[off * R + r];
+                        if (k == p.blank) { c.mask[r] = 1; }          // blank_mask |= (k == blank)
+                        else { emit_row(p, w, r, k, time_idx, c.s_v[off * R + r], 0); any = 1; }
+                    }
+                    c.any = any;
+                }
+                __syncthreads();
+                not_blank = c.any != 0;
+                need_pred = need_pred || not_blank;
+                symbols_added += 1;
+                __syncthreads();
+            }
+        }
+    } else {
+        // Label looping (RNN-T and TDT).  The team runs the prediction network for all its
+        // rows; each of its joint groups then searches the next label of its own rows (row r
+        // belongs to group r mod groups) without waiting for the other groups, and publishes
+        // what the next prediction step needs of them: last label, state selector, activity.
+        const bool tdt = p.D > 0;
+        const int G = p.groups, g = w.jg;
+        const int rj = R > g ? (R - g + G - 1) / G : 0;      // rows of this group
+        int la = p.lookahead;
+        if (rj > 0 && la * rj > RGJ * 4) la = RGJ * 4 / rj;   // the host sized RGJ for lookahead * rows
+        if (la < 1) la = 1;
+        unsigned outer = 0;
+        bool any_active = false;
+        for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
+        while (ok && any_active) {
+            ++outer;
+            ok = prediction_step<RG>(p, w, sy, l);
+            if (!ok) break;
+            ++n_pred;
+            if (w.tid < R) c.searching[w.tid] = (w.tid % G == g) && c.active[w.tid];
+            __syncthreads();
+            bool any_searching = false;
+            for (int j = 0; j < rj; ++j) any_searching = any_searching || c.searching[g + j * G];
+            while (ok && any_searching) {
+                if (w.tid < kMaxSamples) {
+                    const int s = w.tid, j = s / la, i = s - j * la;
+                    int valid = 0, fr = 0, row = 0;
+                    if (j < rj) {
+                        row = g + j * G; fr = c.t[row] + i;
+                        valid = c.searching[row] && fr < c.len[row];
+                    }
+                    c.s_row[s] = row; c.s_frame[s] = fr; c.s_valid[s] = valid;
+                }
+                if (w.tid == 0) c.ns = rj * la;
+                __syncthreads();
+                ok = joint_step<RGJ>(p, w, sy, l, parity);
+                if (!ok) break;
+                parity ^= 1; ++n_joint;
+                if (w.tid < rj && c.searching[g + w.tid * G]) {
+                    const int j = w.tid, r = g + j * G;
+                    int pos = 0, found = 0;
+                    while (pos < la && c.t[r] + pos < c.len[r]) {
+                        const int s = j * la + pos;
+                        const int k = c.s_k[s];
+                        const int dval = tdt ? c.durations[c.s_d[s]] : 0;
+                        if (k == p.blank) {
+                            pos += tdt ? max(dval, 1) : 1;
+                            c.n[r] = 0;
+                        } else {
+                            found = 1;
+                            c.hold_k[r] = k; c.hold_v[r] = c.s_v[s]; c.hold_d[r] = dval;
+                            break;
+                        }
+                    }
+                    c.t[r] += pos;
+                    if (found) c.searching[r] = 0;
+                    else if (c.t[r] >= c.len[r]) { c.searching[r] = 0; c.active[r] = 0; }
+                }
+                __syncthreads();
+                any_searching = false;
+                for (int j = 0; j < rj; ++j) any_searching = any_searching || c.searching[g + j * G];
+                for (int s = 0; s < rj * la; ++s) n_samples += c.s_valid[s];
+                __syncthreads();
+            }
+            if (!ok) break;
+            if (w.tid < rj && c.active[g + w.tid * G]) {
+                const int r = g + w.tid * G;
+                const int dval = c.hold_d[r];
+                emit_row(p, w, r, c.hold_k[r], c.t[r], c.hold_v[r], dval);
+                if (tdt && dval > 0) { c.t[r] += dval; c.n[r] = 0; }
+                else { c.n[r] += 1; if (c.n[r] == p.S) { c.t[r] += 1; c.n[r] = 0; } }
+                c.active[r] = c.t[r] < c.len[r];
+            }
+            __syncthreads();
+            if (G > 1) {
+                // tell the other groups about this group's rows, learn about theirs
+                if (w.jrank == 0 && w.tid < rj) {
+                    const int r = g + w.tid * G;
+                    const unsigned payload = ((unsigned)c.last[r] & 0xffffu) |
+                                             ((unsigned)c.sel[r] << 16) | ((unsigned)c.active[r] << 17);
+                    xstore64(p.rowx + (long long)w.team * kMaxRows + r,
+                             ((unsigned long long)outer << 32) | payload);
+                }
+                if (w.tid < R && w.tid % G != g) {
+                    const int r = w.tid;
+                    const unsigned long long *slot = p.rowx + (long long)w.team * kMaxRows + r;
+                    unsigned spins = 0;
+                    unsigned long long v = xload64(slot);
+                    while ((unsigned)(v >> 32) != outer) {
+                        ++spins;
+                        if ((spins & 127u) == 0 &&
+                            __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                            c.bar_ok = 0;
+                            break;
+                        }
+                        if (spins > p.spin_limit) {
+                            __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            c.bar_ok = 0;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                        v = xload64(slot);
+                    }
+                    sy.polls += spins;
+                    const unsigned payload = (unsigned)v;
+                    c.last[r] = (int)(payload & 0xffffu);
+                    c.sel[r] = (int)((payload >> 16) & 1u);
+                    c.active[r] = (int)((payload >> 17) & 1u);
+                }
+                __syncthreads();
+                ok = c.bar_ok != 0;
+            }
+            any_active = false;
+            for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
+            __syncthreads();
+        }
+    }
+    // epilogue
+    __syncthreads();
+    if (w.jrank == 0 && w.tid < R && w.tid % p.groups == w.jg) p.tok_len[c.b[w.tid]] = c.cnt[w.tid];
+    if (w.jrank == 0 && w.tid == 0) {
+        int st = (c.st_clamped ? 1 : 0) | (c.st_overflow ? 2 : 0);
+        if (!ok) st |= 4;
+        if (st) __hip_atomic_fetch_or(as_global(p.status), st, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (w.rank == 0 && w.tid == 0) {
+        long long *sp = p.stats + (long long)w.team * kStatStride;
+        sp[kStatPred] = n_pred; sp[kStatJoint] = n_joint; sp[kStatSamples] = n_samples;
+        sp[kStatPolls] = sy.polls;
+#ifdef RNNT_PROFILE
+        for (int i = 0; i < 24; ++i) sp[kStatCount + i] = g_prof[i];
+#endif
+    } else if (!ok && w.tid == 0) {
+        __hip_atomic_fetch_or(as_global(p.status), 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+
+template <int RG, int RGJ, int VARIANT>
+hipError_t launch_one(const DecodeParams &p, hipStream_t stream)
+{
+    const void *fn = reinterpret_cast<const void *>(&decode_kernel<RG, RGJ, VARIANT>);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_bytes);
+    if (e != hipSuccess) return e;
+    DecodeParams pc = p;
+    void *args[] = {&pc};
+    // The cooperative launch guarantees that all work-groups are resident together, which
+    // the team barriers rely on.  RNNT_PLAIN_LAUNCH=1 uses an ordinary launch instead (the
+    // grid is one work-group per compute unit, so on an otherwise idle device it is
+    // resident too, and every wait in the kernel is bounded): rocprofv3 crashes at process
+    // exit after a cooperative launch was traced.
+    static const bool plain = [] {
+        const char *v = std::getenv("RNNT_PLAIN_LAUNCH");
+        return v && v[0] == '1';
+    }();
+    const dim3 grid(p.n_teams * p.team_size), block(kThreads);
+    if (plain) return hipLaunchKernel(fn, grid, block, args, p.lds_bytes, stream);
+    return hipLaunchCooperativeKernel(fn, grid, block, args, p.lds_bytes, stream);
+}
+
+// Launch for one loop nest and one prediction row-group count; rgj (1, 2, 4 or 8) picks the
+// joint-step layout.
+template <int RG, int VARIANT>
+hipError_t launch_variant(const DecodeParams &p, int rgj, hipStream_t stream)
+{
+    switch (rgj) {
+    case 1: return launch_one<RG, 1, VARIANT>(p, stream);
+    case 2: return launch_one<RG, 2, VARIANT>(p, stream);
+    case 4: return launch_one<RG, 4, VARIANT>(p, stream);
+    default: return launch_one<RG, 8, VARIANT>(p, stream);
+    }
+}
+
+}  // namespace
+}  // namespace rnnt

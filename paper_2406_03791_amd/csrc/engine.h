@@ -34,6 +34,7 @@ struct DecodeParams {
     int gp_max;             // most prediction-projection output groups owned by a rank
     // dynamic LDS layout, offsets in floats
     int lds_xz, lds_red, lds_c, lds_part, lds_bias, lds_q;
+    int rcap;               // rows the LDS state buffers are laid out for (>= rows of any team)
     int q_in_lds;           // q = W_pred h + b_pred of the team's rows is kept in LDS
     int qstride;            // floats per q row in LDS
     unsigned lds_bytes;
@@ -63,8 +64,6 @@ struct DecodeParams {
 };
 
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream);
-// Largest dynamic LDS the decode kernel may use on this device.
-hipError_t decode_kernel_limits(int *max_dyn_lds_bytes, int *max_coresident_wgs);
 
 hipError_t launch_encoder_projection(const float *enc_out, const int *enc_len, const float *w_enc,
                                      const float *b_enc, float *proj, int B, int T, int F, int J,

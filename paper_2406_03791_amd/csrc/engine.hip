@@ -34,6 +34,7 @@ int hip_fail(hipError_t e, const char *what)
     } while (0)
 
 constexpr int kLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit
+constexpr int kStaticLds = 3072;        // kept free for the kernel's static LDS (control block)
 
 struct DevBuf {
     void *p = nullptr;
@@ -64,6 +65,7 @@ struct TeamConfig {
     int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
     int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
     int q_in_lds = 0, qstride = 0;
+    int rcap = 0;
     unsigned lds_bytes = 0;
 };
 
@@ -166,14 +168,15 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     auto take = [&](int n) { int o = off; off += (n + 3) & ~3; return o; };
     t.lds_xz = take(xz);
     t.lds_red = take(red);
-    t.lds_c = take(L * 2 * nu_max * kMaxRows);
-    t.lds_part = take(L * nu_max * kMaxRows * 4);
+    t.rcap = rows_max;
+    t.lds_c = take(L * 2 * nu_max * rows_max);
+    t.lds_part = take(L * nu_max * rows_max * 4);
     t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
-    if ((unsigned)off * 4u + 2048u > (unsigned)kLdsBytes) return RNNT_ERR_UNSUPPORTED;
+    if ((unsigned)off * 4u + (unsigned)kStaticLds > (unsigned)kLdsBytes) return RNNT_ERR_UNSUPPORTED;
     // q of the team's rows stays in LDS between joint steps when there is room
     t.qstride = (J + 3) & ~3;
     const int q_rows = (rows_max + groups - 1) / groups;   // a joint group keeps its own rows only
-    t.q_in_lds = ((unsigned)(off + q_rows * t.qstride) * 4u + 2048u <= (unsigned)kLdsBytes);
+    t.q_in_lds = ((unsigned)(off + q_rows * t.qstride) * 4u + (unsigned)kStaticLds <= (unsigned)kLdsBytes);
     // joint groups that search on their own read q while the rest of the team may already be
     // rewriting the global copy: they need the LDS copy
     if (groups > 1 && !t.q_in_lds) return RNNT_ERR_UNSUPPORTED;
@@ -230,17 +233,13 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
 }
 
 // Default team layouts, chosen from measurements on MI355X.
-//   Algorithm 1: small teams mean less lock-step waiting between utterances and more
-//   independent step chains per XCD to hide the exchange latency, large teams fewer copies of
-//   the weight stream: 8 teams of 32 work-groups (one XCD each) up to 16 utterances, 16 teams
-//   up to 48, 32 teams beyond.
-//   Label looping: larger teams run the prediction network for all their utterances (one
-//   weight stream per team and label), split into joint groups of at least 8 work-groups (4
-//   beyond 64 utterances) that search for the labels of their own utterances independently.
+//   Algorithm 1: one utterance per team while the teams keep at least 8 work-groups (no
+//   lock-step waiting between utterances, and a prediction step per label of one utterance
+//   only): 8, 16 or 32 teams; beyond 32 utterances the teams take several rows each.
 int default_layouts(rnnt_engine *e)
 {
     const int max_B = e->max_B;
-    int nf = max_B <= 16 ? 8 : (max_B <= 48 ? 16 : 32);
+    int nf = max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32);
     while ((max_B + nf - 1) / nf > kMaxRows) nf *= 2;
     int rc = plan_and_pack(e, e->frame_cfg, nf, 1);
     if (rc) return rc;
@@ -266,13 +265,15 @@ int fetch(std::vector<float> &dst, const float *dev, size_t n)
     return RNNT_OK;
 }
 
-// Frames examined per utterance per joint step: the configured value, else 8, never more
-// than the kMaxSamples samples a joint group's step can hold.
+// Frames examined per utterance per joint step: the configured value, else 8 (Algorithm 1:
+// as many as keep a step at 16 samples, at most 8), never more than the kMaxSamples samples
+// a joint group's step can hold.
 int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
 {
     const int rows_team = (B + t.n_teams - 1) / t.n_teams;
     const int rows = std::max(1, (rows_team + t.groups - 1) / t.groups);
     int la = e->lookahead > 0 ? e->lookahead : 8;
+    if (e->lookahead == 0 && &t == &e->frame_cfg) la = std::min(8, std::max(1, 16 / rows));
     if (la * rows > kMaxSamples) la = std::max(1, kMaxSamples / rows);
     return la;
 }
@@ -322,6 +323,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
     p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
     p.lds_q = t.lds_q; p.q_in_lds = t.q_in_lds; p.qstride = t.qstride;
+    p.rcap = t.rcap;
     p.spin_limit = 1u << 22;
     p.enc_len = enc_len; p.P = e->P.as<float>();
     p.tokens = tokens_out; p.tok_len = tok_len_out; p.frames = frames_out; p.logits = logit_out;

@@ -107,15 +107,11 @@ def test_cfg1_small_frame_and_label(pkg):
 def test_cfg1_lookahead_settings_agree(pkg):
     w = synth.make_workload(1, pad="nan")
     eng = engine_for(pkg, "cfg1", w.model, w.B, w.T)
-    base = None
-    for la in (1, 3, 8, 16):
-        eng.configure(lookahead=la)
-        got, status, stats = run_gpu(eng, w, "label", w.max_symbols)
-        log(f"[cfg1/label la={la}] stats={stats}")
-        assert status == 0 and stats["lookahead"] == la
-        if base is None:
-            base = got
-        assert np.array_equal(got["raw_tokens"], base["raw_tokens"])
+    for variant in ("label", "frame"):
+        for la in (1, 3, 8, 16):
+            eng.configure(lookahead=la)
+            _, _, stats = check(pkg, w, variant, f"cfg1 la={la}", engine=eng)
+            assert stats["lookahead"] == la
     eng.configure(lookahead=0)
 
 
