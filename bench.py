@@ -52,6 +52,19 @@ def algorithmic_bytes(dims, B, variant, enc_len, tok_frames, S):
     return pred_steps * pred_bytes + joint_steps * joint_bytes, pred_steps, joint_steps
 
 
+def issued_weight_bytes(dims, stats):
+    """Weight bytes the teams asked for, from the device's own step counters: every prediction
+    step of a team streams the recurrent and upper-layer LSTM weights and W_pred (layer 0's
+    input weights are folded into a table and never stream), every joint step of a joint
+    group streams W_out.  The joint counter covers the first group of each team; the other
+    groups are taken to be alike.  Part of it is served by the L2 of an XCD that several
+    teams share, so the profiled HBM traffic is lower."""
+    H, L, J = dims.H, dims.L, dims.J
+    pred = 4 * (sum(4 * H * (H + (H if l else 0)) for l in range(L)) + J * H)
+    joint = 4 * dims.n_out * J
+    return stats["pred_steps"] * pred + stats["joint_steps"] * stats["joint_groups"] * joint
+
+
 def profiled_traffic(variant):
     """HBM bytes per launch of the decode kernel from the committed rocprofv3
     counter summary (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy-kernel
@@ -162,7 +175,8 @@ def main() -> int:
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": profiled_traffic(args.variant) if args.batch == 32 else None,
                      "kernel": "decode_kernel", "algorithmic_bytes": alg_bytes,
-                     "schedule_steps": {"prediction": pred_steps, "joint": joint_steps}},
+                     "schedule_steps": {"prediction": pred_steps, "joint": joint_steps},
+                     "issued_weight_bytes": issued_weight_bytes(w.model.dims, r["stats"])},
     }
     if args.all_variants:
         line["variants"] = {}
