@@ -83,7 +83,18 @@ struct Sync {
 // being hoisted out of the decode loops and cuts the kernel from ~250 to ~165 VGPRs, but it
 // measured 5 % slower on MI355X (the hoisted values save more than the registers cost at two
 // waves per SIMD), so the copy is a plain one.
-__device__ __forceinline__ Wg rederive(const Wg &a) { return a; }
+#ifndef RNNT_REDERIVE
+#define RNNT_REDERIVE 0
+#endif
+__device__ __forceinline__ Wg rederive(const Wg &a)
+{
+    Wg b = a;
+#if RNNT_REDERIVE
+    asm volatile("" : "+v"(b.tid), "+s"(b.team), "+s"(b.rank));
+    b.lane = b.tid & 63; b.wave = b.tid >> 6;
+#endif
+    return b;
+}
 
 // Phase timers (100 MHz wall clock), compiled in only for profiling builds.
 #ifdef RNNT_PROFILE
@@ -564,16 +575,15 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
     const int ng = range_hi(w.jrank, p.jteam_size, ng_all) - g0;
     PROF_MARK(w, 18);
     WeightStream<kAheadJoint, RNNT_NT_JOINT != 0> ws;
-    stream_begin(ws, p.sjoint, w, w.jrank, ng * p.sjoint.nks, 0);
-    // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time;
-    // the loads of a batch are all issued before the first use
+    // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time; the loads of a
+    // batch are all issued before the first use.  The first batch of gathers goes out before
+    // the weight stream begins: a wave's loads return in order, and z is needed first.
     {
         constexpr int NB = 6;
         const int k4n = kpad >> 2;
         const int total = rows_pad * k4n;
         const bool vec = (p.J & 3) == 0;
-        for (int base = w.tid; base < total; base += NB * kThreads) {
-            float4 pe[NB];
+        auto gather = [&](int base, float4 (&pe)[NB]) {
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
                 const int idx = base + u * kThreads;
@@ -594,6 +604,8 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
                     }
                 }
             }
+        };
+        auto combine = [&](int base, const float4 (&pe)[NB]) {
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
                 const int idx = base + u * kThreads;
@@ -620,6 +632,16 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
                     *reinterpret_cast<float4 *>(l.xz + s * p.xstride + k) = z;
                 }
             }
+        };
+        float4 pe[NB];
+        gather(w.tid, pe);
+        __builtin_amdgcn_sched_barrier(0);
+        stream_begin(ws, p.sjoint, w, w.jrank, ng * p.sjoint.nks, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        combine(w.tid, pe);
+        for (int base = w.tid + NB * kThreads; base < total; base += NB * kThreads) {
+            gather(base, pe);
+            combine(base, pe);
         }
     }
     __syncthreads();
