@@ -49,7 +49,10 @@ def algorithmic_bytes(dims, B, variant, enc_len, tok_frames, S):
         else:
             forced = np.array([int((c == S).sum()) for c in counts])
             joint_steps = int((enc_len + tok - forced).max())
-    return pred_steps * pred_bytes + joint_steps * joint_bytes, pred_steps, joint_steps
+    pred_flops = 2 * B * (sum(4 * H * ((E if l == 0 else H) + H) for l in range(L)) + J * H)
+    joint_flops = 2 * B * J * nout
+    return (pred_steps * pred_bytes + joint_steps * joint_bytes, pred_steps, joint_steps,
+            pred_steps * pred_flops + joint_steps * joint_flops)
 
 
 def issued_weight_bytes(dims, stats):
@@ -91,6 +94,9 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead of the decode: under rocprofv3 "
                          "--pmc it gives the FETCH_SIZE / WRITE_SIZE reading for a known traffic")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time Algorithm 1 and label looping over batch sizes 1..128 on the "
+                         "typical workload and on the adversarial batches; listed under 'sweep'")
     ap.add_argument("--all-variants", action="store_true",
                     help="also time the other decoders and list them under 'variants'")
     args = ap.parse_args()
@@ -155,7 +161,7 @@ def main() -> int:
     n_frames = w.frames
     ms_per_step = 1e3 * r["wall"] / r["steps"]
     value = n_frames * r["steps"] / r["wall"]
-    alg_bytes, pred_steps, joint_steps = algorithmic_bytes(
+    alg_bytes, pred_steps, joint_steps, alg_flops = algorithmic_bytes(
         w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols)
     achieved = alg_bytes / (r["dec_ms"] * 1e-3) / 1e9
     line = {
@@ -176,7 +182,14 @@ def main() -> int:
                      "traffic": profiled_traffic(args.variant) if args.batch == 32 else None,
                      "kernel": "decode_kernel", "algorithmic_bytes": alg_bytes,
                      "schedule_steps": {"prediction": pred_steps, "joint": joint_steps},
-                     "issued_weight_bytes": issued_weight_bytes(w.model.dims, r["stats"])},
+                     "issued_weight_bytes": issued_weight_bytes(w.model.dims, r["stats"]),
+                     # the same schedule priced in flops against the fp32 matrix peak: small,
+                     # the path is not a dense contraction at these batch sizes
+                     "mfma": {"algorithmic_flops": alg_flops, "peak": 157.3, "unit": "TFLOP/s",
+                              "achieved": alg_flops / (r["dec_ms"] * 1e-3) / 1e12,
+                              "frac": alg_flops / (r["dec_ms"] * 1e-3) / 1e12 / 157.3},
+                     "gpu_busy_frac": (r["dec_ms"] + r["proj_ms"]) / ms_per_step,
+                     "us_per_lockstep_frame": 1e3 * ms_per_step / int(w.enc_len.max())},
     }
     if args.all_variants:
         line["variants"] = {}
@@ -186,6 +199,34 @@ def main() -> int:
             rv = run_variant(v, max(3, args.steps // 2), 2)
             line["variants"][v] = {"frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"],
                                    "decode_ms": rv["dec_ms"], "status": rv["status"]}
+    if args.sweep:
+        # batch-size and input-pattern sweep: how the two schedules take a slow row, the
+        # alternating batch and an input that emits max_symbols labels on every frame
+        line["sweep"] = []
+        for kind in ("typical",) + tuple(synth.PATTERNS[1:]):
+            for B in (1, 8, 32, 128):
+                if kind == "typical":
+                    ws = synth.make_workload(2, B=B)
+                else:
+                    ws = synth.make_adversarial(kind, cfg=2, B=B, T=200)
+                eng = pkg.Engine(ws.model, ws.B, ws.T)
+                enc = torch.from_numpy(ws.enc_out).cuda().contiguous()
+                ln = torch.from_numpy(ws.enc_len).cuda()
+                out = eng.alloc_outputs(ws.B, ws.T * ws.max_symbols)
+                for v in ("frame", "label"):
+                    ms = []
+                    for i in range(4):
+                        eng.decode(v, enc, ln, ws.max_symbols, out=out)
+                        st = eng.stats()
+                        if i:
+                            ms.append(st["decode_ms"] + st["projection_ms"])
+                    line["sweep"].append({
+                        "workload": kind, "B": B, "T": ws.T, "variant": v, "frames": ws.frames,
+                        "tokens": int(out["tok_len"].sum().item()), "call_ms": float(np.median(ms)),
+                        "frames_per_s": ws.frames / (float(np.median(ms)) * 1e-3),
+                        "max_pred_steps": st["max_pred_steps"], "max_joint_steps": st["max_joint_steps"],
+                        "status": eng.status()})
+                eng.close()
     if not args.no_cpu_baseline:
         import oracle
         cores = min(16, os.cpu_count() or 1)

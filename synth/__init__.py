@@ -1,7 +1,8 @@
 """Seeded synthetic inputs for the RNN-T greedy-decoding hot path.
 
-This module only draws random numbers and lays them out; it contains none of
-the decoder's arithmetic.  Both the CPU oracle and the HIP path consume the
+The package only draws random numbers, solves for steering frames from the
+weights (adversarial.py) and lays arrays out; it contains none of the decoder's
+arithmetic.  Both the CPU oracle and the HIP path consume the
 arrays produced here, so neither depends on the other.
 
 Random numbers come from a counter-based generator written out below
@@ -20,7 +21,10 @@ from .workloads import (
     param_count,
 )
 
+from .adversarial import PATTERNS, emit_mask, make_adversarial, steer_frames
+
 __all__ = [
+    "PATTERNS", "emit_mask", "make_adversarial", "steer_frames",
     "Stream", "uniform", "normal", "randint",
     "ModelDims", "Model", "Workload", "CONFIGS",
     "make_model", "make_inputs", "make_workload", "param_count",

@@ -217,3 +217,17 @@ def test_repeat_and_permutation_invariance(pkg):
     p, _, _ = run_gpu(eng, wp, "label", w.max_symbols)
     for i, b in enumerate(perm):
         assert np.array_equal(p["tokens"][i], a["tokens"][b])
+
+
+def test_adversarial_batches(pkg):
+    """Steered inputs: all blank, max_symbols labels on every frame, the alternating batch and
+    one slow row among blank ones; Algorithm 1 and label looping against the oracle."""
+    eng = None
+    for pat in synth.PATTERNS:
+        w = synth.make_adversarial(pat, cfg=2, B=5, T=24)
+        eng = eng or engine_for(pkg, "cfg2-adv", w.model, 5, 24)
+        want = synth.emit_mask(pat, w.B, w.T).sum(axis=1) * w.max_symbols
+        for variant in ("frame", "label"):
+            ref, got, stats = check(pkg, w, variant, f"adv/{pat}", engine=eng)
+            assert ref.tok_len.tolist() == want.tolist()
+            assert [len(t) for t in got["tokens"]] == want.tolist()
