@@ -235,15 +235,19 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
 // Default team layouts, chosen from measurements on MI355X.
 //   Algorithm 1: one utterance per team while the teams keep at least 8 work-groups (no
 //   lock-step waiting between utterances, and a prediction step per label of one utterance
-//   only): 8, 16 or 32 teams; beyond 32 utterances the teams take several rows each.
+//   only): 4, 8, 16 or 32 teams; beyond 32 utterances the teams take several rows each.
+//   Up to 8 utterances (label looping) or 4 (Algorithm 1) teams of 64 work-groups on two
+//   XCDs are faster than idle XCDs, although their exchange crosses the fabric.
 int default_layouts(rnnt_engine *e)
 {
     const int max_B = e->max_B;
-    int nf = max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32);
+    int nf = max_B <= 4 ? 4 : (max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32));
+    while (nf > 1 && e->n_wg % nf != 0) nf /= 2;
     while ((max_B + nf - 1) / nf > kMaxRows) nf *= 2;
     int rc = plan_and_pack(e, e->frame_cfg, nf, 1);
     if (rc) return rc;
-    int nl = max_B <= 48 ? 8 : 16;
+    int nl = max_B <= 8 ? 4 : (max_B <= 48 ? 8 : 16);
+    while (nl > 1 && e->n_wg % nl != 0) nl /= 2;
     while ((max_B + nl - 1) / nl > kMaxRows) nl *= 2;
     const int rows = (max_B + nl - 1) / nl;
     const int ts = e->n_wg / nl, min_group = max_B > 64 ? 4 : 8;

@@ -100,8 +100,15 @@ def test_cfg1_small_frame_and_label(pkg):
     _, a, _ = check(pkg, w, "frame", "cfg1")
     _, b, _ = check(pkg, w, "label", "cfg1")
     assert np.array_equal(a["raw_tokens"], b["raw_tokens"])
+    # with one team layout for both decoders the same kernels run on the same operands: same bits
+    eng = pkg.Engine(w.model, w.B, w.T)
+    eng.configure(n_teams=8)
+    a, _, _ = run_gpu(eng, w, "frame", w.max_symbols)
+    b, _, _ = run_gpu(eng, w, "label", w.max_symbols)
+    eng.close()
+    assert np.array_equal(a["raw_tokens"], b["raw_tokens"])
     for i in range(w.B):
-        assert np.array_equal(a["logits"][i], b["logits"][i])   # same kernels, same bits
+        assert np.array_equal(a["logits"][i], b["logits"][i])
 
 
 def test_cfg1_lookahead_settings_agree(pkg):
