@@ -103,7 +103,8 @@ typedef struct rnnt_stats {
     int32_t xcd_mismatch;     /* teams whose work-groups were not on one XCD     */
     int32_t joint_groups;     /* groups per team that search for labels on their */
                               /* own (1 = the whole team together)               */
-    int32_t reserved_;
+    int32_t search_steps;     /* joint steps a label search may take before the  */
+                              /* next prediction step (0 = no limit)             */
     float projection_ms;      /* device time of the encoder-projection kernel    */
     float decode_ms;          /* device time of the persistent decode kernel,    */
                               /* both from HIP events recorded on the call's     */
@@ -192,8 +193,12 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out);
  * teams for every decoder; 0 keeps the current layout (the default one is
  * chosen from max_B).  joint_groups (needs n_teams > 0): joint groups per team
  * in the label-looping calls, 0 or 1 = none; Algorithm 1 always runs plain
- * teams.  lookahead: frames examined per utterance per joint step in the
- * label-looping calls (0 = default of 8, 1 = one frame per step).
+ * teams.  lookahead: frames examined per utterance per joint step (0 = default:
+ * 8 in the label-looping calls, up to 8 with at most 16 samples per step in
+ * Algorithm 1; 1 = one frame per step).  search_steps: joint steps a search of
+ * the label-looping calls may take before the team runs its next prediction
+ * step for the rows that have their label (0 = chosen per call from the rows
+ * per team, -1 = no limit).  None of the knobs changes a token.
  * Synchronous; repacks the weights when n_teams is given.  Returns
  * RNNT_ERR_SHAPE for values the engine cannot run (the work-groups do not
  * divide into the teams or groups, more than 16 utterances per team) and
@@ -201,7 +206,7 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out);
  * layouts are then back in force.
  */
 int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_groups,
-                          int32_t lookahead);
+                          int32_t lookahead, int32_t search_steps);
 
 /* Text for a return code; for RNNT_ERR_HIP includes the last HIP error text. */
 const char *rnnt_status_string(int code);

@@ -48,7 +48,7 @@ class RnntStats(C.Structure):
         ("joint_samples", C.c_int64), ("barrier_polls", C.c_int64),
         ("n_teams", C.c_int32), ("team_size", C.c_int32),
         ("lookahead", C.c_int32), ("xcd_mismatch", C.c_int32),
-        ("joint_groups", C.c_int32), ("reserved_", C.c_int32),
+        ("joint_groups", C.c_int32), ("search_steps", C.c_int32),
         ("projection_ms", C.c_float), ("decode_ms", C.c_float),
     ]
 
@@ -86,7 +86,7 @@ def load_library():
                                                 C.c_int32, C.c_void_p, C.c_void_p]
         lib.rnnt_engine_status.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         lib.rnnt_engine_stats.argtypes = [C.c_void_p, C.POINTER(RnntStats)]
-        lib.rnnt_engine_configure.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
+        lib.rnnt_engine_configure.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         lib.rnnt_status_string.argtypes = [C.c_int]
         lib.rnnt_status_string.restype = C.c_char_p
         for name in EXPORTS:
@@ -136,9 +136,10 @@ def rnnt_engine_destroy(eng) -> None:
     _check(load_library().rnnt_engine_destroy(eng))
 
 
-def rnnt_engine_configure(eng, n_teams: int = 0, joint_groups: int = 0, lookahead: int = 0) -> None:
+def rnnt_engine_configure(eng, n_teams: int = 0, joint_groups: int = 0, lookahead: int = 0,
+                          search_steps: int = 0) -> None:
     _check(load_library().rnnt_engine_configure(eng, int(n_teams), int(joint_groups),
-                                                int(lookahead)))
+                                                int(lookahead), int(search_steps)))
 
 
 def _decode(fn, eng, enc_out, enc_len, B, T, max_symbols, tokens_out, tok_len_out, cap,
@@ -213,8 +214,9 @@ class Engine:
         except Exception:
             pass
 
-    def configure(self, n_teams: int = 0, joint_groups: int = 0, lookahead: int = 0) -> None:
-        rnnt_engine_configure(self.handle, n_teams, joint_groups, lookahead)
+    def configure(self, n_teams: int = 0, joint_groups: int = 0, lookahead: int = 0,
+                  search_steps: int = 0) -> None:
+        rnnt_engine_configure(self.handle, n_teams, joint_groups, lookahead, search_steps)
 
     def alloc_outputs(self, B: int, cap: int):
         t = self.torch

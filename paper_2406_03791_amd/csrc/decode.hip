@@ -35,7 +35,7 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     n = n > n_part ? n : n_part;
     hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.bar, n_bar,
                        p.abort_flag, p.status, p.stats, n_stats, p.part, p.dpart, n_part, p.rowx,
-                       p.n_teams * kMaxRows);
+                       p.n_teams * 2 * kMaxRows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // kernels are instantiated per loop nest, per row-group count of the prediction stages

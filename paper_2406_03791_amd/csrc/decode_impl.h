@@ -25,6 +25,7 @@ struct Ctl {
     int b[kMaxRows], len[kMaxRows], t[kMaxRows], n[kMaxRows], last[kMaxRows];
     int cnt[kMaxRows], sel[kMaxRows], active[kMaxRows], searching[kMaxRows], mask[kMaxRows];
     int hold_k[kMaxRows], hold_d[kMaxRows];
+    int emitted[kMaxRows];         // label looping: the row emitted in the current outer iteration
     float hold_v[kMaxRows];
     int s_row[kMaxSamples], s_frame[kMaxSamples], s_valid[kMaxSamples];
     int s_k[kMaxSamples], s_d[kMaxSamples];
@@ -808,7 +809,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         const int r = w.tid;
         c.b[r] = 0; c.len[r] = 0; c.t[r] = 0; c.n[r] = 0; c.last[r] = p.blank;
         c.cnt[r] = 0; c.sel[r] = 0; c.active[r] = 0; c.searching[r] = 0;
-        c.mask[r] = 1; c.hold_k[r] = 0; c.hold_d[r] = 0; c.hold_v[r] = 0.f;
+        c.mask[r] = 1; c.hold_k[r] = 0; c.hold_d[r] = 0; c.hold_v[r] = 0.f; c.emitted[r] = 0;
     }
     __syncthreads();
     for (int b = w.tid; b < p.B; b += kThreads) {
@@ -940,16 +941,25 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         unsigned outer = 0;
         bool any_active = false;
         for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
+        bool need_pred = true;
         while (ok && any_active) {
             ++outer;
-            ok = prediction_step<RG>(p, w, sy, l);
-            if (!ok) break;
-            ++n_pred;
-            if (w.tid < R) c.searching[w.tid] = (w.tid % G == g) && c.active[w.tid];
+            if (need_pred) {
+                ok = prediction_step<RG>(p, w, sy, l);
+                if (!ok) break;
+                ++n_pred;
+            }
+            if (w.tid < R) { c.searching[w.tid] = (w.tid % G == g) && c.active[w.tid]; c.emitted[w.tid] = 0; }
             __syncthreads();
             bool any_searching = false;
             for (int j = 0; j < rj; ++j) any_searching = any_searching || c.searching[g + j * G];
-            while (ok && any_searching) {
+            // A search is cut off after search_steps joint steps (0: never): rows that have
+            // found their label go on to the next prediction step instead of waiting for a row
+            // in a long run of blanks; that row keeps its state through the step (prediction()
+            // of unchanged inputs gives the same g) and searches on afterwards.  When no row
+            // of the team emitted, nothing changed and the prediction step is skipped.
+            int steps_left = p.search_steps > 0 ? p.search_steps : 0x7fffffff;
+            while (ok && any_searching && steps_left-- > 0) {
                 if (w.tid < kMaxSamples) {
                     const int s = w.tid, j = s / la, i = s - j * la;
                     int valid = 0, fr = 0, row = 0;
@@ -991,13 +1001,14 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 __syncthreads();
             }
             if (!ok) break;
-            if (w.tid < rj && c.active[g + w.tid * G]) {
+            if (w.tid < rj && c.active[g + w.tid * G] && !c.searching[g + w.tid * G]) {
                 const int r = g + w.tid * G;
                 const int dval = c.hold_d[r];
                 emit_row(p, w, r, c.hold_k[r], c.t[r], c.hold_v[r], dval);
                 if (tdt && dval > 0) { c.t[r] += dval; c.n[r] = 0; }
                 else { c.n[r] += 1; if (c.n[r] == p.S) { c.t[r] += 1; c.n[r] = 0; } }
                 c.active[r] = c.t[r] < c.len[r];
+                c.emitted[r] = 1;
             }
             __syncthreads();
             if (G > 1) {
@@ -1005,13 +1016,18 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 if (w.jrank == 0 && w.tid < rj) {
                     const int r = g + w.tid * G;
                     const unsigned payload = ((unsigned)c.last[r] & 0xffffu) |
-                                             ((unsigned)c.sel[r] << 16) | ((unsigned)c.active[r] << 17);
-                    xstore64(p.rowx + (long long)w.team * kMaxRows + r,
+                                             ((unsigned)c.sel[r] << 16) | ((unsigned)c.active[r] << 17) |
+                                             ((unsigned)c.emitted[r] << 18);
+                    // two slots per row, by parity of the iteration: a group that runs ahead
+                    // writes the other slot, and cannot reach this one again before every group
+                    // has published for the iteration in between, that is, after reading this one
+                    xstore64(p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r,
                              ((unsigned long long)outer << 32) | payload);
                 }
                 if (w.tid < R && w.tid % G != g) {
                     const int r = w.tid;
-                    const unsigned long long *slot = p.rowx + (long long)w.team * kMaxRows + r;
+                    const unsigned long long *slot =
+                        p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r;
                     unsigned spins = 0;
                     unsigned long long v = xload64(slot);
                     while ((unsigned)(v >> 32) != outer) {
@@ -1034,12 +1050,17 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                     c.last[r] = (int)(payload & 0xffffu);
                     c.sel[r] = (int)((payload >> 16) & 1u);
                     c.active[r] = (int)((payload >> 17) & 1u);
+                    c.emitted[r] = (int)((payload >> 18) & 1u);
                 }
                 __syncthreads();
                 ok = c.bar_ok != 0;
             }
             any_active = false;
-            for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
+            need_pred = false;
+            for (int r = 0; r < R; ++r) {
+                any_active = any_active || c.active[r];
+                need_pred = need_pred || c.emitted[r];
+            }
             __syncthreads();
         }
     }

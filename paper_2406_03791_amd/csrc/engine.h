@@ -26,6 +26,7 @@ struct DecodeParams {
     int durations[kMaxDur];
     int B, T, S, cap, variant;
     int n_teams, team_size, lookahead;
+    int search_steps;       // label looping: joint steps per search before the next prediction step (0: no limit)
     int groups, jteam_size; // joint groups per team and work-groups per joint group
     int serpentine;         // deal length-ranked utterances to teams 0..n-1, n-1..0, ... (else 0..n-1, 0..n-1)
     int xstride;            // floats per activation row in LDS
@@ -55,7 +56,7 @@ struct DecodeParams {
     float *qbuf;                  // [n_teams][kMaxRows][J]
     unsigned long long *part;     // [n_teams * groups][2][kMaxSamples][jteam_size] token partial argmax
     unsigned long long *dpart;    // same for durations
-    unsigned long long *rowx;     // [n_teams][kMaxRows]: row state published by the owning joint group
+    unsigned long long *rowx;     // [n_teams][2][kMaxRows]: row state published by the owning joint group
     unsigned *bar;                // [n_teams * 32]: one counter per team, 128 B apart
     unsigned *abort_flag;
     int *status;

@@ -75,6 +75,7 @@ struct rnnt_engine {
     int NOUT = 0, max_B = 0, max_T = 0;
     int n_wg = 0;          // work-groups the device can keep resident (one per CU)
     int lookahead = 0;
+    int search_steps = 0;  // 0: chosen per call, -1: no limit, > 0: as given
     // host copies of the weights that get repacked when the team layout changes
     std::vector<std::vector<float>> w_ih, w_hh;
     std::vector<float> w_pred, w_out;
@@ -216,7 +217,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     HIP_TRY(t.qbuf.alloc((size_t)n_teams * kMaxRows * J * sizeof(float)));
     HIP_TRY(t.part.alloc(n_part * sizeof(unsigned long long)));
     HIP_TRY(t.dpart.alloc(n_part * sizeof(unsigned long long)));
-    HIP_TRY(t.rowx.alloc((size_t)n_teams * kMaxRows * sizeof(unsigned long long)));
+    HIP_TRY(t.rowx.alloc((size_t)n_teams * 2 * kMaxRows * sizeof(unsigned long long)));
     HIP_TRY(t.bar.alloc((size_t)n_teams * 32 * sizeof(unsigned)));
     HIP_TRY(t.stats.alloc((size_t)n_teams * kStatStride * sizeof(long long)));
     HIP_TRY(t.xcc.alloc((size_t)n_teams * ts * sizeof(int)));
@@ -282,6 +283,20 @@ int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
     return la;
 }
 
+// Joint steps a label-looping search may take before the team's next prediction step (0: no
+// limit): the configured value, else chosen from measurements.  A group with two or more rows
+// stops after one step, so that a row in a long run of blanks does not hold up the rows that
+// have their label; single-row groups of a team with four or more rows stop after two.
+int effective_search_steps(const rnnt_engine *e, const TeamConfig &t, int B)
+{
+    if (e->search_steps < 0) return 0;
+    if (e->search_steps > 0) return e->search_steps;
+    const int rows_team = (B + t.n_teams - 1) / t.n_teams;
+    const int rows_group = (rows_team + t.groups - 1) / t.groups;
+    if (rows_group >= 2) return 1;
+    return rows_team >= 4 ? 2 : 0;
+}
+
 StageDev dev_stage(const PackedStage &ps)
 {
     StageDev s;
@@ -323,6 +338,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
         p.serpentine = v ? (v[0] == '1') : 1;
     }
     p.lookahead = effective_lookahead(e, t, B);
+    p.search_steps = effective_search_steps(e, t, B);
     p.xstride = t.xstride; p.nu_max = t.nu_max; p.gj_max = t.gj_max;
     p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
     p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
@@ -446,12 +462,14 @@ int rnnt_engine_destroy(rnnt_engine *eng)
     return RNNT_OK;
 }
 
-int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_groups, int32_t lookahead)
+int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_groups, int32_t lookahead,
+                          int32_t search_steps)
 {
     if (!eng) return RNNT_ERR_NULL;
     if (lookahead < 0 || lookahead > kMaxSamples || n_teams < 0 || joint_groups < 0)
         return RNNT_ERR_SHAPE;
     if (n_teams == 0 && joint_groups != 0) return RNNT_ERR_SHAPE;
+    if (search_steps < -1) return RNNT_ERR_SHAPE;
     HIP_TRY(hipDeviceSynchronize());
     if (n_teams > 0) {
         // plain teams for Algorithm 1; the label-looping decoders split each team further
@@ -464,6 +482,7 @@ int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_group
         }
     }
     eng->lookahead = lookahead;
+    eng->search_steps = search_steps;
     return RNNT_OK;
 }
 
@@ -572,6 +591,7 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
     out->team_size = t->team_size;
     out->joint_groups = t->groups;
     out->lookahead = effective_lookahead(eng, *t, std::max(1, eng->last_B));
+    out->search_steps = effective_search_steps(eng, *t, std::max(1, eng->last_B));
     if (eng->timed) {
         HIP_TRY(hipEventElapsedTime(&out->projection_ms, eng->ev[0], eng->ev[1]));
         HIP_TRY(hipEventElapsedTime(&out->decode_ms, eng->ev[1], eng->ev[2]));

@@ -122,6 +122,22 @@ def test_cfg1_lookahead_settings_agree(pkg):
     eng.configure(lookahead=0)
 
 
+def test_search_cut_off_settings_agree(pkg):
+    """Label looping with the search cut off after 1, 2, 3 joint steps or never, with and
+    without joint groups, RNN-T and TDT: the tokens do not change."""
+    for cfg, variant, kw in [(3, "label", dict(B=12, T=120, len_lo=40, len_hi=120)),
+                             (4, "tdt", dict(B=12, T=120, len_lo=40, len_hi=120))]:
+        w = synth.make_workload(cfg, pad="nan", **kw)
+        eng = pkg.Engine(w.model, w.B, w.T)
+        for n_teams, groups in [(0, 0), (8, 1), (4, 2), (2, 4)]:
+            for ss in (-1, 1, 2, 3):
+                eng.configure(n_teams=n_teams, joint_groups=groups, search_steps=ss)
+                _, _, stats = check(pkg, w, variant, f"cfg{cfg} teams={n_teams}/{groups} ss={ss}",
+                                    engine=eng)
+                assert stats["search_steps"] == (0 if ss < 0 else ss)
+        eng.close()
+
+
 def test_edge_cases(pkg):
     w = synth.make_workload(1, pad="nan", T=40, len_lo=5, len_hi=40)
     eng = engine_for(pkg, "cfg1", w.model, 8, 200)
