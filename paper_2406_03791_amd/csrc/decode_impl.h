@@ -1,4 +1,5 @@
-// Persistent decode kernel (device code, included by the translation units that instantiate it) for exact RNN-T / TDT greedy decoding on gfx950.
+// Persistent decode kernel for exact RNN-T / TDT greedy decoding on gfx950: the device code,
+// included by the translation units that instantiate it (decode_f*.hip, decode_l*.hip).
 //
 // One launch runs the whole data-dependent double loop of Algorithm 1 (or of
 // its label-looping form) on the device.  The work-groups form independent
@@ -8,8 +9,9 @@
 // dense stage is split over the ranks by output columns and exchanged through
 // small global buffers; the loop control (blank mask, symbols_added, not_blank,
 // per-utterance frame index) is recomputed identically by every rank from the
-// exchanged argmax results, so there is no controller rank and no flag to wait
-// for besides the barrier itself.
+// exchanged argmax results, so there is no controller rank.  Label looping adds
+// joint groups inside a team: the team runs the prediction network for all its
+// rows together, the groups search for the labels of their own rows on their own.
 #pragma once
 #include <cstdlib>
 
@@ -17,7 +19,6 @@
 
 namespace rnnt {
 namespace {
-
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -83,7 +84,8 @@ struct Sync {
 // optimiser (an empty asm on tid, team and rank) keeps the phase's indices and addresses from
 // being hoisted out of the decode loops and cuts the kernel from ~250 to ~165 VGPRs, but it
 // measured 5 % slower on MI355X (the hoisted values save more than the registers cost at two
-// waves per SIMD), so the copy is a plain one.
+// waves per SIMD), so the copy is a plain one unless the library is built with
+// -DRNNT_REDERIVE=1.
 #ifndef RNNT_REDERIVE
 #define RNNT_REDERIVE 0
 #endif
@@ -171,9 +173,11 @@ __device__ __forceinline__ bool team_barrier(const DecodeParams &p, const Wg &w,
 constexpr int kAheadPred = RNNT_AHEAD_PRED;     // prediction stages: pure streaming, few accumulators
 constexpr int kAheadJoint = RNNT_AHEAD_JOINT;   // joint stage: 8 row groups of accumulators are live too
 
-// Optional non-temporal weight loads.  Measured on MI355X they are slower for the prediction
-// stages (the teams that share an XCD stream the same packed weights and profit from each
-// other's L2 lines), so every stream currently uses ordinary loads.
+// Optional non-temporal weight loads (-DRNNT_NT_PRED=1, -DRNNT_NT_JOINT=1).  Measured on MI355X
+// they are slower (by a third where the teams of an XCD stream the same packed weights and
+// profit from each other's L2 lines), so every stream uses ordinary loads by default.  Deeper
+// windows (-DRNNT_AHEAD_PRED, -DRNNT_AHEAD_JOINT) measured slower too: a wave's loads return
+// in order, so the exchange loads behind a longer window wait longer.
 template <bool NT>
 __device__ __forceinline__ float4 load_weight(const float4 *p)
 {
