@@ -126,10 +126,15 @@ def main() -> int:
                                                "launches": 4}}))
         return 0
 
-    def run_variant(variant, steps, warmup):
+    def run_variant(variant, steps, warmup, bf16_weights=False):
         cfg = {"frame": 2, "label": 3, "tdt": 4}[variant]
         w = synth.make_workload(cfg, B=args.batch)
-        eng = pkg.Engine(w.model, w.B, w.T)
+        if bf16_weights:
+            # the model a bf16 checkpoint would give for the streamed matrices, kept as bf16 by
+            # the engine (lossless); fp32 arithmetic, checked against the oracle on that model
+            import dataclasses
+            w = dataclasses.replace(w, model=synth.with_bf16_streamed_weights(w.model))
+        eng = pkg.Engine(w.model, w.B, w.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS if bf16_weights else 0)
         enc = torch.from_numpy(w.enc_out).cuda().contiguous()
         ln = torch.from_numpy(w.enc_len).cuda()
         out = eng.alloc_outputs(w.B, w.T * w.max_symbols)
@@ -199,6 +204,18 @@ def main() -> int:
             rv = run_variant(v, max(3, args.steps // 2), 2)
             line["variants"][v] = {"frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"],
                                    "decode_ms": rv["dec_ms"], "status": rv["status"]}
+        # the same decoders on the model with bf16-valued streamed weights, stored as bf16:
+        # another model (its tokens differ from the fp32 model's), reported beside, never as value
+        import oracle as _oracle
+        for v in ("frame", "label", "tdt"):
+            rv = run_variant(v, max(3, args.steps // 2), 2, bf16_weights=True)
+            wv = rv["w"]
+            ref = _oracle.decode(_oracle.LstmNet(wv.model), wv.enc_out, wv.enc_len, wv.max_symbols,
+                                 "seq", n_threads=min(16, os.cpu_count() or 1))
+            same = sum(int(np.array_equal(ref.tokens[b], rv["tokens"][b])) for b in range(wv.B))
+            line["variants"][v + "_bf16_weights"] = {
+                "frames_per_s": wv.frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
+                "status": rv["status"], "rows_token_identical_to_oracle_on_same_model": same}
     if args.sweep:
         # batch-size and input-pattern sweep: how the two schedules take a slow row, the
         # alternating batch and an input that emits max_symbols labels on every frame

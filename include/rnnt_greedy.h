@@ -112,9 +112,24 @@ typedef struct rnnt_stats {
 } rnnt_stats;
 
 /*
+ * Engine flags.  RNNT_FLAG_BF16_WEIGHTS: keep the weights that are streamed at
+ * every step (W_hh of every layer, W_ih of the layers above the first, W_pred,
+ * W_out) as bf16 in the engine's packed copy, half the bytes per step.  The
+ * storage is lossless or refused: every one of those weights must already be
+ * a bf16 value (low 16 bits of the float zero), otherwise create returns
+ * RNNT_ERR_SHAPE; the arithmetic stays fp32 (a stored weight is widened before
+ * use), so the results are those of the fp32 engine on the same model up to
+ * summation order.  The embedding, W_ih of the first layer, W_enc and all
+ * biases may hold any fp32 values.  The paper's experiments run bf16 models
+ * (section on the experimental set-up); this is the storage half of that.
+ */
+#define RNNT_FLAG_BF16_WEIGHTS 1
+
+/*
  * Create an engine for up to max_B utterances of up to max_T frames.
  * Copies and repacks the weights on the current device, allocates the
  * workspace (projected frames [max_B, max_T, J], state, exchange buffers).
+ * flags: 0 or RNNT_FLAG_BF16_WEIGHTS; other bits are RNNT_ERR_SHAPE.
  * Synchronous.  *out is set only on success.
  */
 int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T,

@@ -6,6 +6,7 @@ C names and only marshal arguments; every step of the decode runs in the HIP
 kernels.  There is no fallback: importing fails if the library is not built.
 """
 from .binding import (  # noqa: F401
+    RNNT_FLAG_BF16_WEIGHTS,
     Engine,
     RnntError,
     RnntStats,

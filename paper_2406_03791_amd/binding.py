@@ -21,6 +21,9 @@ EXPORTS = (
 )
 
 
+RNNT_FLAG_BF16_WEIGHTS = 1
+
+
 class RnntError(RuntimeError):
     def __init__(self, code: int, text: str):
         super().__init__(f"rnnt_greedy error {code}: {text}")
@@ -193,7 +196,7 @@ class Engine:
     Holds no decode logic: each method forwards to the C entry point of the
     same name."""
 
-    def __init__(self, model, max_B: int, max_T: int, device: str = "cuda:0"):
+    def __init__(self, model, max_B: int, max_T: int, device: str = "cuda:0", flags: int = 0):
         import torch
         self.torch = torch
         self.device = torch.device(device)
@@ -201,7 +204,7 @@ class Engine:
         self.weights = {k: torch.from_numpy(v).to(self.device).contiguous()
                         for k, v in model.arrays().items()}
         torch.cuda.synchronize(self.device)
-        self.handle = rnnt_engine_create(self.dims, self.weights, max_B, max_T)
+        self.handle = rnnt_engine_create(self.dims, self.weights, max_B, max_T, flags)
 
     def close(self) -> None:
         if getattr(self, "handle", None):

@@ -9,7 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip",
            "decode_f1.hip", "decode_f2.hip", "decode_f4.hip",
-           "decode_l1.hip", "decode_l2.hip", "decode_l4.hip"]
+           "decode_l1.hip", "decode_l2.hip", "decode_l4.hip",
+           "decode_f1b.hip", "decode_f2b.hip", "decode_f4b.hip",
+           "decode_l1b.hip", "decode_l2b.hip", "decode_l4b.hip"]
 LIB = os.path.join(HERE, "librnnt_greedy.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 FLAGS = ((["-DRNNT_PROFILE"] if os.environ.get("RNNT_PROFILE") else []) +

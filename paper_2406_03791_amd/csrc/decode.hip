@@ -4,12 +4,15 @@
 
 namespace rnnt {
 
-hipError_t launch_decode_f1(const DecodeParams &p, int rgj, hipStream_t stream);
-hipError_t launch_decode_f2(const DecodeParams &p, int rgj, hipStream_t stream);
-hipError_t launch_decode_f4(const DecodeParams &p, int rgj, hipStream_t stream);
-hipError_t launch_decode_l1(const DecodeParams &p, int rgj, hipStream_t stream);
-hipError_t launch_decode_l2(const DecodeParams &p, int rgj, hipStream_t stream);
-hipError_t launch_decode_l4(const DecodeParams &p, int rgj, hipStream_t stream);
+#define RNNT_DECLARE_LAUNCH(name) \
+    hipError_t name(const DecodeParams &p, int rgj, hipStream_t stream)
+RNNT_DECLARE_LAUNCH(launch_decode_f1); RNNT_DECLARE_LAUNCH(launch_decode_f2);
+RNNT_DECLARE_LAUNCH(launch_decode_f4); RNNT_DECLARE_LAUNCH(launch_decode_l1);
+RNNT_DECLARE_LAUNCH(launch_decode_l2); RNNT_DECLARE_LAUNCH(launch_decode_l4);
+RNNT_DECLARE_LAUNCH(launch_decode_f1b); RNNT_DECLARE_LAUNCH(launch_decode_f2b);
+RNNT_DECLARE_LAUNCH(launch_decode_f4b); RNNT_DECLARE_LAUNCH(launch_decode_l1b);
+RNNT_DECLARE_LAUNCH(launch_decode_l2b); RNNT_DECLARE_LAUNCH(launch_decode_l4b);
+#undef RNNT_DECLARE_LAUNCH
 
 // Clears what must start at zero for a call: barrier counters, abort flag, status, stats and
 // the tagged argmax partials and row states (a tag left by the previous call must not look
@@ -45,14 +48,14 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     const int rows_j = (rows + p.groups - 1) / p.groups;
     const int samples = rows_j * p.lookahead;
     const int rgj = samples <= 4 ? 1 : (samples <= 8 ? 2 : (samples <= 16 ? 4 : 8));
-    if (p.variant == kFrameLooping) {
-        if (rg <= 1) return launch_decode_f1(p, rgj, stream);
-        if (rg <= 2) return launch_decode_f2(p, rgj, stream);
-        return launch_decode_f4(p, rgj, stream);
-    }
-    if (rg <= 1) return launch_decode_l1(p, rgj, stream);
-    if (rg <= 2) return launch_decode_l2(p, rgj, stream);
-    return launch_decode_l4(p, rgj, stream);
+    const int rgi = rg <= 1 ? 0 : (rg <= 2 ? 1 : 2);
+    typedef hipError_t (*Launch)(const DecodeParams &, int, hipStream_t);
+    static const Launch table[2][2][3] = {
+        {{launch_decode_f1, launch_decode_f2, launch_decode_f4},
+         {launch_decode_l1, launch_decode_l2, launch_decode_l4}},
+        {{launch_decode_f1b, launch_decode_f2b, launch_decode_f4b},
+         {launch_decode_l1b, launch_decode_l2b, launch_decode_l4b}}};
+    return table[p.wt == kWeightBf16 ? 1 : 0][p.variant == kFrameLooping ? 0 : 1][rgi](p, rgj, stream);
 }
 
 }  // namespace rnnt

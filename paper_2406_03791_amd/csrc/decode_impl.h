@@ -222,7 +222,10 @@ __device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const Sta
 //   x            LDS, rows `xstride` floats apart; input vector `inp` of a group
 //                starts `x_inp_stride` floats further (inp = group / groups_per_inp)
 //   red_aliases_x  the results overwrite x (only valid with a single slot)
-template <int RG, int AH, bool NT>
+// WT: how the packed weights are stored.  kWeightF32: a load carries four weights.
+// kWeightBf16: a load carries eight bf16 weights, used as two half-steps of four; a bf16
+// weight becomes its fp32 value by a shift, the products and sums are fp32 as before.
+template <int RG, int WT, int AH, bool NT>
 __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int rank, int n_tasks,
                                           WeightStream<AH, NT> &ws, const float *x, int xstride,
                                           int x_inp_stride, int groups_per_inp, float *red,
@@ -236,7 +239,9 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
         const bool live = ws.live;
         const int g = live ? task / sd.nks : 0;
         const int ks = live ? task - g * sd.nks : 0;
-        const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * 4;
+        constexpr int KPER = WT == kWeightBf16 ? 8 : 4;
+        constexpr int HALVES = KPER / 4;
+        const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * KPER;
         v4f acc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){0.f, 0.f, 0.f, 0.f};
@@ -257,23 +262,35 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
                 if (i < sd.nsteps) {
 #pragma unroll
                     for (int u = 0; u < kStepUnroll; ++u) {
-                        // the row is 4 floats longer than kpad, so the read past the last
-                        // step stays inside it
+                        const float4 raw = ws.q[a][u];
 #pragma unroll
-                        for (int rg = 0; rg < RG; ++rg)
-                            xb[rg] = *reinterpret_cast<const float4 *>(xr + rg * 4 * xstride +
-                                                                       (i + u + 1) * 4);
-                        const float4 wv = ws.q[a][u];
+                        for (int h = 0; h < HALVES; ++h) {
+                            // the row is 4 floats longer than kpad, so the read past the
+                            // last step stays inside it
 #pragma unroll
-                        for (int rg = 0; rg < RG; ++rg) {
-                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].x, wv.x, acc[rg], 0, 0, 0);
-                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].y, wv.y, acc[rg], 0, 0, 0);
-                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].z, wv.z, acc[rg], 0, 0, 0);
-                            acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].w, wv.w, acc[rg], 0, 0, 0);
+                            for (int rg = 0; rg < RG; ++rg)
+                                xb[rg] = *reinterpret_cast<const float4 *>(
+                                    xr + rg * 4 * xstride + ((i + u) * HALVES + h + 1) * 4);
+                            float4 wv;
+                            if (WT == kWeightBf16) {
+                                const unsigned lo = __float_as_uint(h == 0 ? raw.x : raw.z);
+                                const unsigned hi = __float_as_uint(h == 0 ? raw.y : raw.w);
+                                wv = make_float4(__uint_as_float(lo << 16), __uint_as_float(lo & 0xffff0000u),
+                                                 __uint_as_float(hi << 16), __uint_as_float(hi & 0xffff0000u));
+                            } else {
+                                wv = raw;
+                            }
+#pragma unroll
+                            for (int rg = 0; rg < RG; ++rg) {
+                                acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].x, wv.x, acc[rg], 0, 0, 0);
+                                acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].y, wv.y, acc[rg], 0, 0, 0);
+                                acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].z, wv.z, acc[rg], 0, 0, 0);
+                                acc[rg] = __builtin_amdgcn_mfma_f32_4x4x1f32(xa[rg].w, wv.w, acc[rg], 0, 0, 0);
+                            }
+#pragma unroll
+                            for (int rg = 0; rg < RG; ++rg) xa[rg] = xb[rg];
+                            __builtin_amdgcn_sched_barrier(0);
                         }
-#pragma unroll
-                        for (int rg = 0; rg < RG; ++rg) xa[rg] = xb[rg];
-                        __builtin_amdgcn_sched_barrier(0);
                     }
                     if (live && i + kAhead * kStepUnroll < sd.nsteps) {
 #pragma unroll
@@ -382,7 +399,7 @@ __device__ __forceinline__ void lstm_point(float gi, float gf, float gg, float g
 
 // One prediction-network step for all rows of the team, from (last, committed
 // state) to the candidate state and q = W_pred h'_top + b_pred.
-template <int RG>
+template <int RG, int WT>
 __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg &w0, Sync &sy, const Lds &l)
 {
     const Wg w = rederive(w0);
@@ -407,7 +424,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         if (layer == 0)
             pre = *reinterpret_cast<const float4 *>(p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
     }
-    run_stage<RG>(p.st0, w, w.rank, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
+    run_stage<RG, WT>(p.st0, w, w.rank, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
                   l.red, false);
     // the next stage's weights start moving while this one finishes and the team meets
     const int ng_all_p = (p.J + 3) / 4;
@@ -449,7 +466,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
         __syncthreads();
         PROF_MARK(w, 4);
-        run_stage<RG>(sd, w, w.rank, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        run_stage<RG, WT>(sd, w, w.rank, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
         if (layer + 1 < kMaxLayers && layer + 1 < p.L)
             stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
                          nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks, 0);
@@ -477,7 +494,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows(p, w, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
         __syncthreads();
         PROF_MARK(w, 8);
-        run_stage<RG>(p.spred, w, w.rank, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        run_stage<RG, WT>(p.spred, w, w.rank, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
         __syncthreads();
         PROF_MARK(w, 9);
         for (int e = w.tid; e < ng * c.R; e += kThreads) {
@@ -565,7 +582,7 @@ __device__ __forceinline__ unsigned long long wait_partial(const DecodeParams &p
 // Joint network + argmax for the c.ns samples listed in c.s_row / c.s_frame /
 // c.s_valid.  Leaves c.s_k, c.s_v (token argmax and its logit) and c.s_d
 // (duration index) for every valid sample.
-template <int RG>
+template <int RG, int WT>
 __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, Sync &sy, const Lds &l, int parity)
 {
     const Wg w = rederive(w0);
@@ -654,7 +671,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
     // with one slot the partial sums may overwrite z once every wave is done with it
     const bool alias = p.sjoint.slots == 1;
     float *red = alias ? l.xz : l.red;
-    run_stage<RG>(p.sjoint, w, w.jrank, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias);
+    run_stage<RG, WT>(p.sjoint, w, w.jrank, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias);
     __syncthreads();
     PROF_MARK(w, 14);
     // Per sample, this rank's best token column and best duration column.  GP
@@ -765,8 +782,9 @@ __device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, int
 }
 
 // RG: row groups (of 4) of a team in the prediction stages; RGJ: row groups a joint step is
-// laid out for (its samples never exceed 4 * RGJ); VARIANT: which loop nest.
-template <int RG, int RGJ, int VARIANT>
+// laid out for (its samples never exceed 4 * RGJ); VARIANT: which loop nest; WT: storage of
+// the packed weights.
+template <int RG, int RGJ, int VARIANT, int WT>
 __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 {
     extern __shared__ __align__(16) float dyn_lds[];
@@ -890,7 +908,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 if (need_pred) {
                     // g, hidden_prime = prediction(last_label, hidden); skipped when neither
                     // input changed since the last evaluation (same result)
-                    ok = prediction_step<RG>(p, w, sy, l);
+                    ok = prediction_step<RG, WT>(p, w, sy, l);
                     if (!ok) break;
                     ++n_pred;
                     need_pred = false;
@@ -909,7 +927,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                     }
                     if (w.tid == 0) c.ns = R * n_ahead;
                     __syncthreads();
-                    ok = joint_step<RGJ>(p, w, sy, l, parity);      // logp = joint(f, g); k, v = logp.max()
+                    ok = joint_step<RGJ, WT>(p, w, sy, l, parity);      // logp = joint(f, g); k, v = logp.max()
                     if (!ok) break;
                     parity ^= 1; ++n_joint; n_samples += R * n_ahead;
                     win0 = time_idx; win_n = n_ahead;
@@ -949,7 +967,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         while (ok && any_active) {
             ++outer;
             if (need_pred) {
-                ok = prediction_step<RG>(p, w, sy, l);
+                ok = prediction_step<RG, WT>(p, w, sy, l);
                 if (!ok) break;
                 ++n_pred;
             }
@@ -975,7 +993,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 }
                 if (w.tid == 0) c.ns = rj * la;
                 __syncthreads();
-                ok = joint_step<RGJ>(p, w, sy, l, parity);
+                ok = joint_step<RGJ, WT>(p, w, sy, l, parity);
                 if (!ok) break;
                 parity ^= 1; ++n_joint;
                 if (w.tid < rj && c.searching[g + w.tid * G]) {
@@ -1089,10 +1107,10 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 }
 
 
-template <int RG, int RGJ, int VARIANT>
+template <int RG, int RGJ, int VARIANT, int WT>
 hipError_t launch_one(const DecodeParams &p, hipStream_t stream)
 {
-    const void *fn = reinterpret_cast<const void *>(&decode_kernel<RG, RGJ, VARIANT>);
+    const void *fn = reinterpret_cast<const void *>(&decode_kernel<RG, RGJ, VARIANT, WT>);
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_bytes);
     if (e != hipSuccess) return e;
     DecodeParams pc = p;
@@ -1113,14 +1131,14 @@ hipError_t launch_one(const DecodeParams &p, hipStream_t stream)
 
 // Launch for one loop nest and one prediction row-group count; rgj (1, 2, 4 or 8) picks the
 // joint-step layout.
-template <int RG, int VARIANT>
+template <int RG, int VARIANT, int WT>
 hipError_t launch_variant(const DecodeParams &p, int rgj, hipStream_t stream)
 {
     switch (rgj) {
-    case 1: return launch_one<RG, 1, VARIANT>(p, stream);
-    case 2: return launch_one<RG, 2, VARIANT>(p, stream);
-    case 4: return launch_one<RG, 4, VARIANT>(p, stream);
-    default: return launch_one<RG, 8, VARIANT>(p, stream);
+    case 1: return launch_one<RG, 1, VARIANT, WT>(p, stream);
+    case 2: return launch_one<RG, 2, VARIANT, WT>(p, stream);
+    case 4: return launch_one<RG, 4, VARIANT, WT>(p, stream);
+    default: return launch_one<RG, 8, VARIANT, WT>(p, stream);
     }
 }
 

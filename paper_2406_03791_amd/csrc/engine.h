@@ -12,7 +12,7 @@ enum Variant { kFrameLooping = 0, kLabelLooping = 1, kTdtLabelLooping = 2 };
 
 // Packed weights of one dense stage on the device.
 struct StageDev {
-    const float4 *w;       // [rank][slot][wave][step][lane]
+    const float4 *w;       // [rank][slot][wave][step][lane], 16 bytes each: 4 fp32 or 8 bf16 weights
     int nks, nsteps, slots, kpad;
     long long rank_stride; // float4 elements per rank
 };
@@ -25,6 +25,7 @@ struct DecodeParams {
     int F, E, H, L, J, V1, D, blank, NOUT;
     int durations[kMaxDur];
     int B, T, S, cap, variant;
+    int wt;                 // WeightType of the packed stages
     int n_teams, team_size, lookahead;
     int search_steps;       // label looping: joint steps per search before the next prediction step (0: no limit)
     int groups, jteam_size; // joint groups per team and work-groups per joint group

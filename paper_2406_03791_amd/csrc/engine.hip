@@ -76,6 +76,7 @@ struct rnnt_engine {
     int n_wg = 0;          // work-groups the device can keep resident (one per CU)
     int lookahead = 0;
     int search_steps = 0;  // 0: chosen per call, -1: no limit, > 0: as given
+    int wt = kWeightF32;   // storage of the packed (streamed) weights
     // host copies of the weights that get repacked when the team layout changes
     std::vector<std::vector<float>> w_ih, w_hh;
     std::vector<float> w_pred, w_out;
@@ -93,11 +94,20 @@ struct rnnt_engine {
 
 namespace {
 
+// bf16 code of a float that is exactly representable in bf16 (the engine checks that first).
+inline uint16_t bf16_bits(float v)
+{
+    uint32_t u;
+    std::memcpy(&u, &v, sizeof u);
+    return (uint16_t)(u >> 16);
+}
+
 int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups,
                  const std::function<const float *(int, int, int)> &row_of)
 {
     const StagePlan &pl = ps.plan;
-    std::vector<float> host((size_t)ts * pl.rank_stride * 4, 0.f);
+    // 16 bytes per (rank, slot, wave, step, lane): 4 floats or 8 bf16 codes
+    std::vector<uint32_t> host((size_t)ts * pl.rank_stride * 4, 0u);
     for (int rank = 0; rank < ts; ++rank) {
         const int ntask = ngroups(rank) * pl.nks;
         for (int slot = 0; slot < pl.slots; ++slot)
@@ -109,17 +119,23 @@ int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups
                     const float *row = row_of(rank, g, lane & 3);
                     if (!row) continue;
                     for (int step = 0; step < pl.nsteps; ++step) {
-                        float *dst = host.data() +
-                                     ((size_t)rank * pl.rank_stride +
-                                      ((size_t)(slot * kWaves + wave) * pl.nsteps + step) * 64 + lane) * 4;
-                        const int k0 = (ks * pl.nsteps + step) * 4;
-                        for (int c = 0; c < 4; ++c)
-                            if (k0 + c < pl.K) dst[c] = row[k0 + c];
+                        uint32_t *dst = host.data() +
+                                        ((size_t)rank * pl.rank_stride +
+                                         ((size_t)(slot * kWaves + wave) * pl.nsteps + step) * 64 + lane) * 4;
+                        const int k0 = (ks * pl.nsteps + step) * pl.kper;
+                        if (pl.kper == 4) {
+                            for (int c = 0; c < 4; ++c)
+                                if (k0 + c < pl.K) std::memcpy(dst + c, row + k0 + c, 4);
+                        } else {
+                            for (int c = 0; c < 8; ++c)
+                                if (k0 + c < pl.K)
+                                    dst[c >> 1] |= (uint32_t)bf16_bits(row[k0 + c]) << (16 * (c & 1));
+                        }
                     }
                 }
     }
-    HIP_TRY(ps.w.alloc(host.size() * sizeof(float)));
-    HIP_TRY(hipMemcpy(ps.w.p, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY(ps.w.alloc(host.size() * sizeof(uint32_t)));
+    HIP_TRY(hipMemcpy(ps.w.p, host.data(), host.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     return RNNT_OK;
 }
 
@@ -145,10 +161,10 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         gp_max = std::max(gp_max, gp_of(r));
     }
     for (int r = 0; r < tj; ++r) gj_max = std::max(gj_max, gj_of(r));
-    t.st0.plan = make_stage_plan(H, L * nu_max);
-    for (int l = 1; l < L; ++l) t.stl[l].plan = make_stage_plan(H, nu_max);
-    t.spred.plan = make_stage_plan(H, gp_max);
-    t.sjoint.plan = make_stage_plan(J, gj_max);
+    t.st0.plan = make_stage_plan(H, L * nu_max, e->wt);
+    for (int l = 1; l < L; ++l) t.stl[l].plan = make_stage_plan(H, nu_max, e->wt);
+    t.spred.plan = make_stage_plan(H, gp_max, e->wt);
+    t.sjoint.plan = make_stage_plan(J, gj_max, e->wt);
 
     // LDS layout
     int kpad = std::max({t.st0.plan.kpad, t.spred.plan.kpad, t.sjoint.plan.kpad});
@@ -337,6 +353,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
         const char *v = std::getenv("RNNT_SERPENTINE");
         p.serpentine = v ? (v[0] == '1') : 1;
     }
+    p.wt = e->wt;
     p.lookahead = effective_lookahead(e, t, B);
     p.search_steps = effective_search_steps(e, t, B);
     p.xstride = t.xstride; p.nu_max = t.nu_max; p.gj_max = t.gj_max;
@@ -374,8 +391,8 @@ extern "C" {
 int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T, int32_t flags,
                        rnnt_engine **out)
 {
-    (void)flags;
     if (!desc || !out) return RNNT_ERR_NULL;
+    if (flags & ~RNNT_FLAG_BF16_WEIGHTS) return RNNT_ERR_SHAPE;
     const rnnt_model_desc &d = *desc;
     if (!d.emb || !d.w_ih || !d.w_hh || !d.b_ih || !d.b_hh || !d.w_enc || !d.b_enc || !d.w_pred ||
         !d.b_pred || !d.w_out || !d.b_out)
@@ -406,6 +423,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     for (int i = 0; i < d.D; ++i) e->durations[i] = d.durations[i];
     e->NOUT = d.V1 + d.D;
     e->max_B = max_B; e->max_T = max_T;
+    e->wt = (flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32;
     e->n_wg = (prop.multiProcessorCount / 32) * 32;   // every layout divides it
     if (e->n_wg < 32) return RNNT_ERR_UNSUPPORTED;
 
@@ -425,6 +443,20 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     }
     if ((rc = fetch(e->w_pred, d.w_pred, J * H))) return rc;
     if ((rc = fetch(e->w_out, d.w_out, (size_t)e->NOUT * J))) return rc;
+    if (e->wt == kWeightBf16) {
+        // compact storage is lossless or refused: every streamed weight must be a bf16 value
+        auto is_bf16 = [](const std::vector<float> &v) {
+            for (float x : v) {
+                uint32_t u;
+                std::memcpy(&u, &x, sizeof u);
+                if (u & 0xffffu) return false;
+            }
+            return true;
+        };
+        bool ok = is_bf16(e->w_pred) && is_bf16(e->w_out);
+        for (int l = 0; l < d.L; ++l) ok = ok && is_bf16(e->w_hh[l]) && (l == 0 || is_bf16(e->w_ih[l]));
+        if (!ok) return RNNT_ERR_SHAPE;
+    }
 
     auto clone = [&](DevBuf &dst, const float *src, size_t n) -> int {
         HIP_TRY(dst.alloc(n * sizeof(float)));

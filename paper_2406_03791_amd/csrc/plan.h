@@ -25,7 +25,12 @@ constexpr int kMaxLayers = 4;
 constexpr int kMaxDur = 8;
 constexpr int kMaxRows = 16;         // utterances per team
 constexpr int kMaxSamples = 32;      // (utterance, frame) pairs per joint step
-constexpr int kStepUnroll = 4;       // K steps (of 4 floats) per software-pipeline batch
+constexpr int kStepUnroll = 4;       // weight loads (16 bytes per lane) per software-pipeline batch
+
+// Storage of the packed weights: fp32 (4 K values per 16-byte load) or bf16 (8 per load).
+// The arithmetic is fp32 either way: a bf16 weight is widened before it is used.
+enum WeightType { kWeightF32 = 0, kWeightBf16 = 1 };
+RNNT_HD inline int k_per_load(int wt) { return wt == kWeightBf16 ? 8 : 4; }
 
 // Contiguous share of n items owned by `rank` out of `ts`.
 RNNT_HD inline int range_lo(int rank, int ts, int n) { return (int)(((int64_t)rank * n) / ts); }
@@ -34,20 +39,22 @@ RNNT_HD inline int range_hi(int rank, int ts, int n) { return (int)(((int64_t)(r
 struct StagePlan {
     int K;          // input length in floats
     int nks;        // K slices per group
-    int nsteps;     // float4 steps per task (multiple of kStepUnroll)
+    int nsteps;     // 16-byte loads per lane and task (multiple of kStepUnroll)
     int slots;      // passes over the 128 blocks
-    int kpad;       // nks * nsteps * 4: padded input length
-    int64_t rank_stride;   // float4 elements of packed weights per rank
+    int kper;       // K values per load (4: fp32 weights, 8: bf16 weights)
+    int kpad;       // nks * nsteps * kper: padded input length
+    int64_t rank_stride;   // 16-byte elements of packed weights per rank
 };
 
 // groups_max: largest number of groups any rank owns in this stage.
 // Picks the number of K slices that fills the 128 blocks best while keeping the
 // zero padding of K (slices are whole multiples of kStepUnroll steps) below 1/8.
-inline StagePlan make_stage_plan(int K, int groups_max)
+inline StagePlan make_stage_plan(int K, int groups_max, int wt = kWeightF32)
 {
     StagePlan p{};
     p.K = K;
-    const int k4 = (K + 3) / 4;
+    p.kper = k_per_load(wt);
+    const int k4 = (K + p.kper - 1) / p.kper;      // loads needed to cover K
     if (groups_max < 1) groups_max = 1;
     auto steps_for = [&](int nks) {
         int n = (k4 + nks - 1) / nks;
@@ -70,7 +77,7 @@ inline StagePlan make_stage_plan(int K, int groups_max)
         p.slots = (groups_max + kBlocksPerWg - 1) / kBlocksPerWg;
     }
     p.nsteps = steps_for(p.nks);
-    p.kpad = p.nks * p.nsteps * 4;
+    p.kpad = p.nks * p.nsteps * p.kper;
     p.rank_stride = (int64_t)p.slots * kWaves * p.nsteps * 64;
     return p;
 }

@@ -19,6 +19,8 @@ from .workloads import (
     make_inputs,
     make_workload,
     param_count,
+    round_to_bf16,
+    with_bf16_streamed_weights,
 )
 
 from .adversarial import PATTERNS, emit_mask, make_adversarial, steer_frames
@@ -28,4 +30,5 @@ __all__ = [
     "Stream", "uniform", "normal", "randint",
     "ModelDims", "Model", "Workload", "CONFIGS",
     "make_model", "make_inputs", "make_workload", "param_count",
+    "round_to_bf16", "with_bf16_streamed_weights",
 ]

@@ -242,3 +242,22 @@ def make_workload(cfg: int, *, B: Optional[int] = None, pad: str = "normal",
     enc_out = np.concatenate(blocks_x, axis=0)[:want_B].copy()
     enc_len = np.concatenate(blocks_len, axis=0)[:want_B].copy()
     return Workload(c["name"], c["variant"], model, enc_out, enc_len, c["S"])
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """float32 array with every value rounded to the nearest bf16 value (ties to even) and
+    stored as float32 again."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return r.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def with_bf16_streamed_weights(model: Model) -> Model:
+    """A copy of `model` whose per-step streamed matrices (W_hh of every layer, W_ih of the
+    layers above the first, W_pred, W_out) hold bf16 values; everything else is unchanged.
+    This is the model a bf16 checkpoint would give for those matrices; both the oracle and the
+    engine take it as their fp32 input."""
+    w_ih = [w if l == 0 else round_to_bf16(w) for l, w in enumerate(model.w_ih)]
+    w_hh = [round_to_bf16(w) for w in model.w_hh]
+    return replace(model, w_ih=w_ih, w_hh=w_hh, w_pred=round_to_bf16(model.w_pred),
+                   w_out=round_to_bf16(model.w_out))

@@ -49,7 +49,8 @@ def test_status_strings_and_null_checks_need_no_gpu():
 
 def test_stage_planner_covers_k_and_fits_the_blocks():
     """Host logic of the weight packer, re-stated: every (groups, K) choice must
-    cover K with nks slices of nsteps float4 steps and fit the blocks of a slot."""
+    cover K with nks slices of nsteps 16-byte loads (4 fp32 or 8 bf16 weights each) and fit
+    the blocks of a slot."""
     import subprocess
     import tempfile
     src = r'''
@@ -57,10 +58,12 @@ def test_stage_planner_covers_k_and_fits_the_blocks():
 #include <cstdio>
 int main() {
   int bad = 0;
+  for (int wt = 0; wt < 2; ++wt)
   for (int K = 4; K <= 2048; K += 4)
     for (int g = 1; g <= 300; g += (g < 40 ? 1 : 13)) {
-      rnnt::StagePlan p = rnnt::make_stage_plan(K, g);
-      if (p.kpad < K || p.kpad != p.nks * p.nsteps * 4 || p.nsteps % rnnt::kStepUnroll) bad++;
+      rnnt::StagePlan p = rnnt::make_stage_plan(K, g, wt);
+      if (p.kper != (wt ? 8 : 4)) bad++;
+      if (p.kpad < K || p.kpad != p.nks * p.nsteps * p.kper || p.nsteps % rnnt::kStepUnroll) bad++;
       if (g * p.nks > rnnt::kBlocksPerWg * p.slots) bad++;
       if (p.slots > 1 && p.nks != 1) bad++;
     }

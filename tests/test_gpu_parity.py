@@ -254,3 +254,28 @@ def test_adversarial_batches(pkg):
             ref, got, stats = check(pkg, w, variant, f"adv/{pat}", engine=eng)
             assert ref.tok_len.tolist() == want.tolist()
             assert [len(t) for t in got["tokens"]] == want.tolist()
+
+
+def test_bf16_weight_storage(pkg):
+    """Engine with the streamed weights kept as bf16 (lossless storage of a model whose streamed
+    matrices hold bf16 values) against the oracle on that same model; a model with other values
+    is refused.  Also logs how many rows differ from the decode of the unrounded model."""
+    import dataclasses
+    for cfg, variants, kw in [(3, ("frame", "label"), dict(B=6, T=120, len_lo=40, len_hi=120)),
+                              (4, ("tdt",), dict(B=6, T=120, len_lo=40, len_hi=120)),
+                              (1, ("frame", "label"), {})]:
+        w32 = synth.make_workload(cfg, pad="nan", **kw)
+        with pytest.raises(pkg.RnntError) as err:
+            pkg.Engine(w32.model, w32.B, w32.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS)
+        assert err.value.code == -2
+        w = dataclasses.replace(w32, model=synth.with_bf16_streamed_weights(w32.model))
+        eng = pkg.Engine(w.model, w.B, w.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS)
+        ref32 = oracle.decode(oracle.LstmNet(w32.model), w32.enc_out, w32.enc_len, w32.max_symbols,
+                              "seq", n_threads=N_THREADS)
+        for variant in variants:
+            ref, got, _ = check(pkg, w, variant, f"cfg{cfg}/bf16w", engine=eng)
+            moved = sum(int(not np.array_equal(ref.tokens[b], ref32.tokens[b])) for b in range(w.B))
+            log(f"  rows whose tokens differ from the fp32 model's: {moved}/{w.B}")
+        eng.close()
+    with pytest.raises(pkg.RnntError):
+        pkg.Engine(w32.model, w32.B, w32.T, flags=2)

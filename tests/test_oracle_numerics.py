@@ -305,3 +305,16 @@ def test_stored_oracle_tokens_are_reproduced():
         stored = json.load(fh)
     for name, case in mg.CASES.items():
         assert mg.run(case) == stored[name], name
+
+
+def test_bf16_rounding_of_inputs_matches_torch():
+    """synth.round_to_bf16 is round-to-nearest-even to bf16, as torch's conversion."""
+    x = synth.normal(77, 1, (4096,)).astype(np.float32) * np.float32(0.1)
+    x[:4] = [0.0, -0.0, 1.00390625, 3.0e38]
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(synth.round_to_bf16(x), want)
+    m = synth.make_workload(0).model
+    r = synth.with_bf16_streamed_weights(m)
+    assert np.array_equal(r.emb, m.emb) and np.array_equal(r.w_ih[0], m.w_ih[0])
+    assert not np.array_equal(r.w_out, m.w_out)
+    assert np.all(r.w_out.view(np.uint32) & 0xFFFF == 0) and np.all(r.w_hh[0].view(np.uint32) & 0xFFFF == 0)
