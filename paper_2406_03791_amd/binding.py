@@ -76,6 +76,12 @@ def load_library():
             raise ImportError(
                 f"{path} is missing: build it with `python -m paper_2406_03791_amd.build` "
                 "(there is no fallback path)")
+        # PyTorch ships its own HIP runtime; it has to be in the process before this library
+        # pulls in the system one, or the two runtimes disagree about the device.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = C.CDLL(path)
         dec_args = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                     C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
