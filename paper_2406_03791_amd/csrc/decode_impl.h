@@ -970,6 +970,12 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 ok = prediction_step<RG, WT>(p, w, sy, l);
                 if (!ok) break;
                 ++n_pred;
+            } else {
+                // Every iteration meets the whole team once, here or inside the prediction
+                // step: no work-group can then be more than one iteration behind another, which
+                // is what the two parity slots of the row-state exchange below rely on.
+                ok = team_barrier(p, w, sy);
+                if (!ok) break;
             }
             if (w.tid < R) { c.searching[w.tid] = (w.tid % G == g) && c.active[w.tid]; c.emitted[w.tid] = 0; }
             __syncthreads();
@@ -1041,8 +1047,9 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                                              ((unsigned)c.sel[r] << 16) | ((unsigned)c.active[r] << 17) |
                                              ((unsigned)c.emitted[r] << 18);
                     // two slots per row, by parity of the iteration: a group that runs ahead
-                    // writes the other slot, and cannot reach this one again before every group
-                    // has published for the iteration in between, that is, after reading this one
+                    // writes the other slot, and reaches this one again only two iterations
+                    // later, after a team-wide meeting that every work-group enters only when
+                    // it has read this one
                     xstore64(p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r,
                              ((unsigned long long)outer << 32) | payload);
                 }
