@@ -55,6 +55,7 @@ class _DecodeIO(C.Structure):
         ("stat_outer", C.c_int64), ("stat_inner", C.c_int64),
         ("stat_pred", C.c_int64), ("stat_pred_rows", C.c_int64),
         ("stat_joint_rows", C.c_int64),
+        ("logps", C.c_void_p),
     ]
 
 
@@ -174,7 +175,8 @@ class Records:
 class Decoded:
     tokens: List[np.ndarray]
     frames: List[np.ndarray]
-    scores: List[np.ndarray]
+    scores: List[np.ndarray]       # maximum token logit of each emission
+    logps: List[np.ndarray]        # its log-softmax value over the token columns
     durs: List[np.ndarray]
     tok_len: np.ndarray
     status: int
@@ -202,6 +204,7 @@ def decode(net: Net, enc_out: np.ndarray, enc_len: np.ndarray, max_symbols: int,
     i32 = lambda *s: np.zeros(s, dtype=np.int32)
     rl = lambda *s: np.zeros(s, dtype=net.dtype)
     tokens, frames, scores, durs = i32(B, cap), i32(B, cap), rl(B, cap), i32(B, cap)
+    logps = rl(B, cap)
     tok_len = i32(B)
     io = _DecodeIO()
     io.B, io.T, io.S, io.cap, io.rec_cap = B, T, S, cap, rec_cap
@@ -209,6 +212,7 @@ def decode(net: Net, enc_out: np.ndarray, enc_len: np.ndarray, max_symbols: int,
     io.x, io.len = _ptr(x), _ptr(ln)
     io.tokens, io.frames, io.scores = _ptr(tokens), _ptr(frames), _ptr(scores)
     io.durs, io.tok_len = _ptr(durs), _ptr(tok_len)
+    io.logps = _ptr(logps)
     recs = None
     if record:
         recs = dict(t=i32(B, rec_cap), u=i32(B, rec_cap), k=i32(B, rec_cap),
@@ -227,6 +231,7 @@ def decode(net: Net, enc_out: np.ndarray, enc_len: np.ndarray, max_symbols: int,
         tokens=[tokens[b, :n[b]].copy() for b in range(B)],
         frames=[frames[b, :n[b]].copy() for b in range(B)],
         scores=[scores[b, :n[b]].copy() for b in range(B)],
+        logps=[logps[b, :n[b]].copy() for b in range(B)],
         durs=[durs[b, :n[b]].copy() for b in range(B)],
         tok_len=tok_len.copy(), status=int(io.status),
         stats=dict(outer=int(io.stat_outer), inner=int(io.stat_inner),

@@ -315,6 +315,9 @@ typedef struct {
     int64_t stat_pred;       /* batched prediction-network calls               */
     int64_t stat_pred_rows;  /* utterance-level prediction evaluations         */
     int64_t stat_joint_rows; /* utterance-level joint evaluations              */
+    real *logps;           /* [B][cap]  log-softmax value of each emitted label */
+                           /* over the token columns: the v of Algorithm 1's    */
+                           /* k, v = logp.max() (may be NULL)                   */
 } decode_io;
 
 /* argmax over v[lo..hi) with the lowest index winning ties; *margin is the   */
@@ -333,6 +336,15 @@ static int argmax_margin(const real *v, int lo, int hi, real *top, real *margin)
     return k;
 }
 
+/* log_softmax(v[0..n))[k] for the k holding the maximum `top`: the sum runs in  */
+/* index order in double precision.                                           */
+static real log_prob_of_top(const real *v, int n, real top)
+{
+    double s = 0.0;
+    for (int j = 0; j < n; ++j) s += exp((double)v[j] - (double)top);
+    return (real)(-log(s));
+}
+
 static int clamp_len(const decode_io *io, int b, int32_t *status)
 {
     int n = io->len[b];
@@ -341,7 +353,7 @@ static int clamp_len(const decode_io *io, int b, int32_t *status)
     return n;
 }
 
-static void emit(decode_io *io, int b, int k, int t, real v, int dval,
+static void emit(decode_io *io, int b, int k, int t, real v, real lp, int dval,
                  int32_t *status)
 {
     const int n = io->tok_len[b];
@@ -350,6 +362,7 @@ static void emit(decode_io *io, int b, int k, int t, real v, int dval,
         io->tokens[o] = k;
         if (io->frames) io->frames[o] = t;
         if (io->scores) io->scores[o] = v;
+        if (io->logps) io->logps[o] = lp;
         if (io->durs) io->durs[o] = dval;
     } else {
         *status |= ORC_STATUS_OVERFLOW;
@@ -383,6 +396,7 @@ static void clear_outputs(decode_io *io)
             io->tokens[o] = -1;
             if (io->frames) io->frames[o] = -1;
             if (io->scores) io->scores[o] = (real)0;
+            if (io->logps) io->logps[o] = (real)0;
             if (io->durs) io->durs[o] = -1;
         }
     }
@@ -438,6 +452,7 @@ int orc_decode_frame_looping(const net_t *net, decode_io *io)
     int *k = (int *)malloc(sizeof(int) * (size_t)B);
     real *v = (real *)malloc(sizeof(real) * (size_t)B);
     real *mg = (real *)malloc(sizeof(real) * (size_t)B);
+    real *lp = (real *)calloc((size_t)B, sizeof(real));
     unsigned char *blank_mask = (unsigned char *)malloc((size_t)B);
     unsigned char *was_masked = (unsigned char *)malloc((size_t)B);
     int max_out_len = 0;
@@ -467,6 +482,7 @@ int orc_decode_frame_looping(const net_t *net, decode_io *io)
                 net->joint(net, cache_get(&fc, b, time_idx), g + (size_t)b * GS, logp);
                 /* k, v = logp.max()                                           */
                 k[b] = argmax_margin(logp, 0, net->V1, &v[b], &mg[b]);
+                if (io->logps) lp[b] = log_prob_of_top(logp, net->V1, v[b]);
                 io->stat_pred_rows++; io->stat_joint_rows++;
             }
             for (int b = 0; b < B; ++b) {
@@ -475,7 +491,7 @@ int orc_decode_frame_looping(const net_t *net, decode_io *io)
                 blank_mask[b] = blank_mask[b] || (k[b] == blank_index);
                 if (!blank_mask[b]) {
                     /* save k and v; masked select of last_label and hidden    */
-                    emit(io, b, k[b], time_idx, v[b], 0, &status);
+                    emit(io, b, k[b], time_idx, v[b], lp[b], 0, &status);
                     last_label[b] = k[b];
                     memcpy(hidden + (size_t)b * SS, hidden_prime + (size_t)b * SS,
                            sizeof(real) * (size_t)SS);
@@ -488,7 +504,7 @@ int orc_decode_frame_looping(const net_t *net, decode_io *io)
     }
     io->status = status;
     free(hidden); free(hidden_prime); free(g); free(logp); free(last_label);
-    free(out_len); free(k); free(v); free(mg); free(blank_mask); free(was_masked);
+    free(out_len); free(k); free(v); free(mg); free(lp); free(blank_mask); free(was_masked);
     cache_free(&fc);
     return 0;
 }
@@ -515,6 +531,7 @@ int orc_decode_label_looping(const net_t *net, decode_io *io)
     int *n = (int *)calloc((size_t)B, sizeof(int));
     int *k = (int *)malloc(sizeof(int) * (size_t)B);
     int *d = (int *)calloc((size_t)B, sizeof(int));
+    real *lp = (real *)calloc((size_t)B, sizeof(real));
     real *v = (real *)malloc(sizeof(real) * (size_t)B);
     unsigned char *active = (unsigned char *)malloc((size_t)B);
     unsigned char *searching = (unsigned char *)malloc((size_t)B);
@@ -552,6 +569,7 @@ int orc_decode_label_looping(const net_t *net, decode_io *io)
                 io->stat_joint_rows++;
                 real mg, dmg = 0, dv;
                 k[b] = argmax_margin(logits, 0, V1, &v[b], &mg);
+                if (io->logps) lp[b] = log_prob_of_top(logits, V1, v[b]);
                 int dval = 0;
                 if (D > 0) {
                     const int di = argmax_margin(logits, V1, V1 + D, &dv, &dmg) - V1;
@@ -569,7 +587,7 @@ int orc_decode_label_looping(const net_t *net, decode_io *io)
         any_active = 0;
         for (int b = 0; b < B; ++b) {
             if (!active[b]) continue;
-            emit(io, b, k[b], t[b], v[b], d[b], &status);
+            emit(io, b, k[b], t[b], v[b], lp[b], d[b], &status);
             last[b] = k[b];
             memcpy(state + (size_t)b * SS, state_prime + (size_t)b * SS,
                    sizeof(real) * (size_t)SS);
@@ -585,7 +603,7 @@ int orc_decode_label_looping(const net_t *net, decode_io *io)
     }
     io->status = status;
     free(state); free(state_prime); free(g); free(logits); free(last); free(len);
-    free(t); free(n); free(k); free(d); free(v); free(active); free(searching);
+    free(t); free(n); free(k); free(d); free(v); free(lp); free(active); free(searching);
     cache_free(&fc);
     return 0;
 }
@@ -622,7 +640,7 @@ static void decode_one(const net_t *net, decode_io *io, int b, int32_t *status,
             t += (D > 0 && dval > 1) ? dval : 1;
             n = 0;
         } else {
-            emit(io, b, k, t, v, dval, status);
+            emit(io, b, k, t, v, io->logps ? log_prob_of_top(logits, V1, v) : (real)0, dval, status);
             last = k;
             memcpy(state, state_prime, sizeof(real) * (size_t)SS);
             if (D > 0 && dval > 0) { t += dval; n = 0; }

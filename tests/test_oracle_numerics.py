@@ -318,3 +318,37 @@ def test_bf16_rounding_of_inputs_matches_torch():
     assert np.array_equal(r.emb, m.emb) and np.array_equal(r.w_ih[0], m.w_ih[0])
     assert not np.array_equal(r.w_out, m.w_out)
     assert np.all(r.w_out.view(np.uint32) & 0xFFFF == 0) and np.all(r.w_hh[0].view(np.uint32) & 0xFFFF == 0)
+
+
+def test_log_probabilities_of_emitted_labels():
+    """The v of Algorithm 1's `k, v = logp.max()`: log_softmax over the token columns at the
+    chosen label.  Pinned against torch.log_softmax on table-driven logits (the duration
+    columns of a TDT table do not enter), the closed form for equal logits, and the LSTM net's
+    own joint output re-evaluated through the direct-access entry points."""
+    rng = np.random.default_rng(11)
+    B, T, U, V1 = 3, 5, 8, 6
+    for durations in [(), (0, 1, 2)]:
+        D = len(durations)
+        tab = rng.normal(0.0, 2.0, size=(B, T, U, V1 + D)).astype(np.float32)
+        net = oracle.TableNet(tab, V1, durations)
+        lens = np.array([5, 3, 4], dtype=np.int32)
+        for sched in (["label", "seq"] if D else ["frame", "label", "seq"]):
+            r = oracle.decode(net, net.frames(), lens, 3, sched)
+            for b in range(B):
+                for i, (k, t) in enumerate(zip(r.tokens[b], r.frames[b])):
+                    logits = torch.from_numpy(tab[b, t, min(i, U - 1), :V1].astype(np.float64))
+                    want = torch.log_softmax(logits, dim=0)[int(k)].item()
+                    assert abs(float(r.logps[b][i]) - want) < 1e-6, (sched, b, i)
+                    assert abs(float(r.scores[b][i]) - float(logits.max())) == 0.0
+    # equal logits: every label has probability 1 / V1
+    net = oracle.TableNet(np.zeros((1, 2, 3, 4), dtype=np.float32), 4)
+    r = oracle.decode(net, net.frames(), np.array([2]), 1, "seq")
+    assert np.allclose(r.logps[0], -np.log(4.0), atol=1e-7)
+    # LSTM net, float and double builds agree, and exp(logp) <= 1
+    w = synth.make_workload(0)
+    rf = oracle.decode(oracle.LstmNet(w.model), w.enc_out, w.enc_len, w.max_symbols, "frame")
+    rd = oracle.decode(oracle.LstmNet(w.model, real="double"), w.enc_out.astype(np.float64),
+                       w.enc_len, w.max_symbols, "frame")
+    assert rf.tok_len[0] > 0 and np.array_equal(rf.tokens[0], rd.tokens[0])
+    assert np.allclose(rf.logps[0], rd.logps[0], atol=1e-5)
+    assert np.all(rf.logps[0] <= 0.0)
