@@ -126,7 +126,7 @@ def main() -> int:
                                                "launches": 4}}))
         return 0
 
-    def run_variant(variant, steps, warmup, bf16_weights=False):
+    def run_variant(variant, steps, warmup, bf16_weights=False, logp=False):
         cfg = {"frame": 2, "label": 3, "tdt": 4}[variant]
         w = synth.make_workload(cfg, B=args.batch)
         if bf16_weights:
@@ -139,12 +139,12 @@ def main() -> int:
         ln = torch.from_numpy(w.enc_len).cuda()
         out = eng.alloc_outputs(w.B, w.T * w.max_symbols)
         for _ in range(warmup):
-            eng.decode(variant, enc, ln, w.max_symbols, out=out)
+            eng.decode(variant, enc, ln, w.max_symbols, out=out, logp=logp)
         torch.cuda.synchronize()
         dec_ms, proj_ms = [], []
         t0 = time.perf_counter()
         for _ in range(steps):
-            eng.decode(variant, enc, ln, w.max_symbols, out=out)
+            eng.decode(variant, enc, ln, w.max_symbols, out=out, logp=logp)
             # the stats call waits for the device: each step is timed on its own events
             st = eng.stats()
             dec_ms.append(st["decode_ms"])
@@ -204,6 +204,11 @@ def main() -> int:
             rv = run_variant(v, max(3, args.steps // 2), 2)
             line["variants"][v] = {"frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"],
                                    "decode_ms": rv["dec_ms"], "status": rv["status"]}
+        # label looping that also returns the log-probability of every label (fused log-sum-exp)
+        rv = run_variant("label", max(3, args.steps // 2), 2, logp=True)
+        line["variants"]["label_with_logp"] = {
+            "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
+            "status": rv["status"]}
         # the same decoders on the model with bf16-valued streamed weights, stored as bf16:
         # another model (its tokens differ from the fp32 model's), reported beside, never as value
         import oracle as _oracle

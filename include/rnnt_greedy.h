@@ -223,6 +223,18 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out);
 int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_groups,
                           int32_t lookahead, int32_t search_steps);
 
+/*
+ * Optional extra output of the decode calls that follow: logp_out, a DEVICE
+ * buffer [B, cap] laid out like tokens_out, receives for every emitted label
+ * its log-softmax value over the V1 token columns -- the v of Algorithm 1's
+ * "k, v = logp.max()" (logit_out carries the maximum before the softmax).  The
+ * log-sum-exp is fused into the argmax exchange of the joint step; nothing is
+ * computed while no buffer is set.  NULL switches it off again.  The caller
+ * owns the buffer and keeps it alive (cap as in the decode call) until the
+ * calls that use it have finished.  Entries beyond tok_len are 0.
+ */
+int rnnt_engine_set_logp_output(rnnt_engine *eng, float *logp_out);
+
 /* Text for a return code; for RNNT_ERR_HIP includes the last HIP error text. */
 const char *rnnt_status_string(int code);
 

@@ -18,6 +18,7 @@ EXPORTS = (
     "rnnt_engine_create", "rnnt_engine_destroy", "rnnt_greedy_decode",
     "rnnt_label_looping_decode", "tdt_label_looping_decode", "rnnt_encoder_projection",
     "rnnt_engine_status", "rnnt_engine_stats", "rnnt_engine_configure", "rnnt_status_string",
+    "rnnt_engine_set_logp_output",
 )
 
 
@@ -96,6 +97,7 @@ def load_library():
         lib.rnnt_engine_status.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
         lib.rnnt_engine_stats.argtypes = [C.c_void_p, C.POINTER(RnntStats)]
         lib.rnnt_engine_configure.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        lib.rnnt_engine_set_logp_output.argtypes = [C.c_void_p, C.c_void_p]
         lib.rnnt_status_string.argtypes = [C.c_int]
         lib.rnnt_status_string.restype = C.c_char_p
         for name in EXPORTS:
@@ -143,6 +145,10 @@ def rnnt_engine_create(dims, weights: dict, max_B: int, max_T: int, flags: int =
 
 def rnnt_engine_destroy(eng) -> None:
     _check(load_library().rnnt_engine_destroy(eng))
+
+
+def rnnt_engine_set_logp_output(eng, logp_out) -> None:
+    _check(load_library().rnnt_engine_set_logp_output(eng, _p(logp_out)))
 
 
 def rnnt_engine_configure(eng, n_teams: int = 0, joint_groups: int = 0, lookahead: int = 0,
@@ -239,14 +245,18 @@ class Engine:
         return out
 
     def decode(self, variant: str, enc_out, enc_len, max_symbols: int, out=None,
-               cap: Optional[int] = None):
+               cap: Optional[int] = None, logp: bool = False):
         """enc_out [B,T,F] fp32 and enc_len [B] int32 device tensors.  Queues the
-        decode on the current stream and returns the output tensors (device)."""
+        decode on the current stream and returns the output tensors (device).
+        logp=True also asks for the log-probabilities (out["logps"])."""
         B, T = int(enc_out.shape[0]), int(enc_out.shape[1])
         if cap is None:
             cap = T * max_symbols
         if out is None:
             out = self.alloc_outputs(B, cap)
+        if logp and "logps" not in out:
+            out["logps"] = self.torch.empty((B, cap), dtype=self.torch.float32, device=self.device)
+        rnnt_engine_set_logp_output(self.handle, out["logps"] if logp else None)
         stream = self.torch.cuda.current_stream(self.device).cuda_stream
         common = (self.handle, enc_out, enc_len, B, T, max_symbols, out["tokens"], out["tok_len"],
                   cap, out["frames"], out["logits"])

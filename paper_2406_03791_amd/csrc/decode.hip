@@ -19,13 +19,14 @@ RNNT_DECLARE_LAUNCH(launch_decode_l2b); RNNT_DECLARE_LAUNCH(launch_decode_l4b);
 // current).
 __global__ void reset_kernel(unsigned *bar, int n_bar, unsigned *abort_flag, int *status,
                              long long *stats, int n_stats, unsigned long long *part,
-                             unsigned long long *dpart, int n_part, unsigned long long *rowx,
+                             unsigned long long *dpart, unsigned long long *lpart, int n_part,
+                             unsigned long long *rowx,
                              int n_rowx)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_bar) bar[i] = 0u;
     if (i < n_stats) stats[i] = 0;
-    if (i < n_part) { part[i] = 0ull; dpart[i] = 0ull; }
+    if (i < n_part) { part[i] = 0ull; dpart[i] = 0ull; lpart[i] = 0ull; }
     if (i < n_rowx) rowx[i] = 0ull;
     if (i == 0) { *abort_flag = 0u; *status = 0; }
 }
@@ -37,7 +38,7 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     int n = n_bar > n_stats ? n_bar : n_stats;
     n = n > n_part ? n : n_part;
     hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.bar, n_bar,
-                       p.abort_flag, p.status, p.stats, n_stats, p.part, p.dpart, n_part, p.rowx,
+                       p.abort_flag, p.status, p.stats, n_stats, p.part, p.dpart, p.lpart, n_part, p.rowx,
                        p.n_teams * 2 * kMaxRows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

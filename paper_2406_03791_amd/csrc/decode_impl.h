@@ -27,10 +27,10 @@ struct Ctl {
     int cnt[kMaxRows], sel[kMaxRows], active[kMaxRows], searching[kMaxRows], mask[kMaxRows];
     int hold_k[kMaxRows], hold_d[kMaxRows];
     int emitted[kMaxRows];         // label looping: the row emitted in the current outer iteration
-    float hold_v[kMaxRows];
+    float hold_v[kMaxRows], hold_lp[kMaxRows];
     int s_row[kMaxSamples], s_frame[kMaxSamples], s_valid[kMaxSamples];
     int s_k[kMaxSamples], s_d[kMaxSamples];
-    float s_v[kMaxSamples];
+    float s_v[kMaxSamples], s_lp[kMaxSamples];   // maximum logit and its log-softmax value
     int R, ns, any, bar_ok, committed;
     int st_clamped, st_overflow;   // set to 1 by any thread (same value from all writers)
     int durations[kMaxDur];
@@ -708,12 +708,30 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
                 const int oj = __shfl_xor(di, off);
                 if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
             }
+            // log-softmax of the maximum, first half: this rank's sum of exp(logit - its own
+            // maximum) over its token columns (asked for only when the caller wants scores)
+            float se = 0.f;
+            if (p.logps) {
+                if (s < ns) {
+                    for (int g = gl; g < ng; g += gp) {
+                        float a[4];
+                        reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int col = (g0 + g) * 4 + j;
+                            if (col < p.V1) se += expf(a[j] + l.b_out[g * 4 + j] - bv);
+                        }
+                    }
+                }
+                for (int off = 1; off < gp; off <<= 1) se += __shfl_xor(se, off);
+            }
             if (s < ns && gl == 0) {
                 const long long o =
                     (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) *
                         p.jteam_size + w.jrank;
                 xstore64(p.part + o, pack_cand(bv, bi, tag));
                 if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di, tag));
+                if (p.logps) xstore64(p.lpart + o, pack_cand(se, 0, tag));
             }
         }
     }
@@ -724,6 +742,9 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
         const int s = w.tid / LPS, sub = w.tid % LPS;
         float bv = -INFINITY, dv = -INFINITY;
         int bi = 0x7fffffff, di = 0x7fffffff;
+        // second half of the log-softmax: sum over the ranks of se_r * exp(m_r - M), kept as
+        // (running maximum lm, sum ls relative to it)
+        float lm = -INFINITY, ls = 0.f;
         if (s < ns && c.s_valid[s]) {
             const long long o =
                 (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) * p.jteam_size;
@@ -732,6 +753,12 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
                 const float v = __uint_as_float((unsigned)(pk >> 32));
                 const int i = (int)(pk & 0xffffu);
                 if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+                if (p.logps) {
+                    const unsigned long long lk = wait_partial(p, sy, p.lpart + o + r, tag);
+                    const float se = __uint_as_float((unsigned)(lk >> 32));
+                    if (v > lm) { ls = ls * expf(lm - v) + se; lm = v; }
+                    else if (v > -INFINITY) ls += se * expf(v - lm);
+                }
                 if (p.D > 0) {
                     const unsigned long long dk = wait_partial(p, sy, p.dpart + o + r, tag);
                     const float d = __uint_as_float((unsigned)(dk >> 32));
@@ -748,11 +775,18 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
             const float od = __shfl_xor(dv, off, LPS);
             const int oj = __shfl_xor(di, off, LPS);
             if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
+            if (p.logps) {
+                const float om = __shfl_xor(lm, off, LPS);
+                const float os = __shfl_xor(ls, off, LPS);
+                if (om > lm) { ls = ls * expf(lm - om) + os; lm = om; }
+                else if (om > -INFINITY) ls += os * expf(om - lm);
+            }
         }
         if (s < ns && sub == 0) {
             // no finite logit (NaN input inside enc_len): fall back to blank, never index out of range
             if ((unsigned)bi >= (unsigned)p.V1) bi = p.blank;
             c.s_k[s] = bi; c.s_v[s] = bv; c.s_d[s] = (p.D > 0 && di < p.D) ? di : 0;
+            c.s_lp[s] = p.logps ? -logf(ls) : 0.f;      // the maximum is its own reference: logit - lm = 0
         }
     }
     __syncthreads();
@@ -762,7 +796,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
 
 // Row r emits label k at frame t (rank 0 writes the outputs).
 __device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, int r, int k,
-                                         int t, float v, int dval)
+                                         int t, float v, float lp, int dval)
 {
     const int n = c.cnt[r];
     if (w.jrank == 0) {
@@ -771,6 +805,7 @@ __device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, int
             p.tokens[o] = k;
             if (p.frames) p.frames[o] = t;
             if (p.logits) p.logits[o] = v;
+            if (p.logps) p.logps[o] = lp;
             if (p.durs) p.durs[o] = dval;
         } else {
             c.st_overflow = 1;
@@ -878,6 +913,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             p.tokens[o + i] = -1;
             if (p.frames) p.frames[o + i] = -1;
             if (p.logits) p.logits[o + i] = 0.f;
+            if (p.logps) p.logps[o + i] = 0.f;
             if (p.durs) p.durs[o + i] = -1;
         }
     }
@@ -938,7 +974,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                         if (c.mask[r]) continue;
                         const int k = c.s_k[off * R + r];
                         if (k == p.blank) { c.mask[r] = 1; }          // blank_mask |= (k == blank)
-                        else { emit_row(p, w, r, k, time_idx, c.s_v[off * R + r], 0); any = 1; }
+                        else { emit_row(p, w, r, k, time_idx, c.s_v[off * R + r], c.s_lp[off * R + r], 0); any = 1; }
                     }
                     c.any = any;
                 }
@@ -1014,7 +1050,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                             c.n[r] = 0;
                         } else {
                             found = 1;
-                            c.hold_k[r] = k; c.hold_v[r] = c.s_v[s]; c.hold_d[r] = dval;
+                            c.hold_k[r] = k; c.hold_v[r] = c.s_v[s]; c.hold_lp[r] = c.s_lp[s]; c.hold_d[r] = dval;
                             break;
                         }
                     }
@@ -1032,7 +1068,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             if (w.tid < rj && c.active[g + w.tid * G] && !c.searching[g + w.tid * G]) {
                 const int r = g + w.tid * G;
                 const int dval = c.hold_d[r];
-                emit_row(p, w, r, c.hold_k[r], c.t[r], c.hold_v[r], dval);
+                emit_row(p, w, r, c.hold_k[r], c.t[r], c.hold_v[r], c.hold_lp[r], dval);
                 if (tdt && dval > 0) { c.t[r] += dval; c.n[r] = 0; }
                 else { c.n[r] += 1; if (c.n[r] == p.S) { c.t[r] += 1; c.n[r] = 0; } }
                 c.active[r] = c.t[r] < c.len[r];

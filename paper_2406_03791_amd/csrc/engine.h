@@ -44,6 +44,7 @@ struct DecodeParams {
     const int *enc_len;     // [B]
     const float *P;         // [B, T, J] projected frames
     int *tokens; int *tok_len; int *frames; float *logits; int *durs;
+    float *logps;           // [B, cap] log-softmax value of each emitted label, or NULL
     StageDev st0;                 // recurrent (h) parts of all layers
     StageDev stl[kMaxLayers];     // input parts of layers 1..L-1 (index = layer)
     StageDev spred;               // prediction-side joint projection
@@ -57,6 +58,7 @@ struct DecodeParams {
     float *qbuf;                  // [n_teams][kMaxRows][J]
     unsigned long long *part;     // [n_teams * groups][2][kMaxSamples][jteam_size] token partial argmax
     unsigned long long *dpart;    // same for durations
+    unsigned long long *lpart;    // same layout: a rank's sum of exp(logit - its maximum)
     unsigned long long *rowx;     // [n_teams][2][kMaxRows]: row state published by the owning joint group
     unsigned *bar;                // [n_teams * 32]: one counter per team, 128 B apart
     unsigned *abort_flag;

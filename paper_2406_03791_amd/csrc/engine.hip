@@ -61,7 +61,7 @@ struct PackedStage {
 struct TeamConfig {
     int n_teams = 0, team_size = 0, groups = 1, jteam_size = 0;
     PackedStage st0, stl[kMaxLayers], spred, sjoint;
-    DevBuf hbuf, qbuf, part, dpart, rowx, bar, stats, xcc;
+    DevBuf hbuf, qbuf, part, dpart, lpart, rowx, bar, stats, xcc;
     int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
     int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
     int q_in_lds = 0, qstride = 0;
@@ -77,6 +77,7 @@ struct rnnt_engine {
     int lookahead = 0;
     int search_steps = 0;  // 0: chosen per call, -1: no limit, > 0: as given
     int wt = kWeightF32;   // storage of the packed (streamed) weights
+    float *logp_out = nullptr;   // caller's [B, cap] buffer for log-probabilities, or none
     // host copies of the weights that get repacked when the team layout changes
     std::vector<std::vector<float>> w_ih, w_hh;
     std::vector<float> w_pred, w_out;
@@ -233,6 +234,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     HIP_TRY(t.qbuf.alloc((size_t)n_teams * kMaxRows * J * sizeof(float)));
     HIP_TRY(t.part.alloc(n_part * sizeof(unsigned long long)));
     HIP_TRY(t.dpart.alloc(n_part * sizeof(unsigned long long)));
+    HIP_TRY(t.lpart.alloc(n_part * sizeof(unsigned long long)));
     HIP_TRY(t.rowx.alloc((size_t)n_teams * 2 * kMaxRows * sizeof(unsigned long long)));
     HIP_TRY(t.bar.alloc((size_t)n_teams * 32 * sizeof(unsigned)));
     HIP_TRY(t.stats.alloc((size_t)n_teams * kStatStride * sizeof(long long)));
@@ -365,6 +367,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.enc_len = enc_len; p.P = e->P.as<float>();
     p.tokens = tokens_out; p.tok_len = tok_len_out; p.frames = frames_out; p.logits = logit_out;
     p.durs = durs_out;
+    p.logps = e->logp_out;
     p.st0 = dev_stage(t.st0);
     for (int l = 1; l < d.L; ++l) p.stl[l] = dev_stage(t.stl[l]);
     p.spred = dev_stage(t.spred);
@@ -373,6 +376,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.b_pred = e->b_pred.as<float>(); p.b_out = e->b_out.as<float>();
     p.hbuf = t.hbuf.as<float>(); p.qbuf = t.qbuf.as<float>();
     p.part = t.part.as<unsigned long long>(); p.dpart = t.dpart.as<unsigned long long>();
+    p.lpart = t.lpart.as<unsigned long long>();
     p.rowx = t.rowx.as<unsigned long long>();
     p.bar = t.bar.as<unsigned>(); p.abort_flag = e->abort_flag.as<unsigned>();
     p.status = e->status.as<int>(); p.stats = t.stats.as<long long>(); p.xcc = t.xcc.as<int>();
@@ -515,6 +519,13 @@ int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_group
     }
     eng->lookahead = lookahead;
     eng->search_steps = search_steps;
+    return RNNT_OK;
+}
+
+int rnnt_engine_set_logp_output(rnnt_engine *eng, float *logp_out)
+{
+    if (!eng) return RNNT_ERR_NULL;
+    eng->logp_out = logp_out;
     return RNNT_OK;
 }
 

@@ -25,6 +25,8 @@ def to_lists(out, B):
     res = dict(tok_len=tok_len, tokens=cut("tokens"), frames=cut("frames"), logits=cut("logits"),
                raw_tokens=out["tokens"].cpu().numpy())
     res["durs"] = cut("durs") if "durs" in out else [np.zeros(n[b], np.int32) for b in range(B)]
+    if "logps" in out:
+        res["logps"] = cut("logps")
     return res
 
 
@@ -43,6 +45,11 @@ def compare(w, net, ref, got, S, check_fill=True):
             tol = LOGIT_RTOL * np.maximum(1.0, np.abs(rv))
             assert np.all(np.abs(rv - gv) <= tol), (
                 f"row {b}: logits differ by {np.max(np.abs(rv - gv)):.3e}")
+            if "logps" in got:
+                rl, gl = ref.logps[b].astype(np.float64), got["logps"][b].astype(np.float64)
+                tol = LOGIT_RTOL * np.maximum(1.0, np.abs(rl))
+                assert np.all(np.abs(rl - gl) <= tol), (
+                    f"row {b}: log-probabilities differ by {np.max(np.abs(rl - gl)):.3e}")
         else:
             f = oracle.follow(net, w.enc_out[b], int(w.enc_len[b]), S, got["tokens"][b],
                               got["frames"][b], got["durs"][b] if w.model.dims.D else None)

@@ -42,24 +42,24 @@ def engine_for(pkg, key, model, max_B, max_T):
     return _ENGINES[k]
 
 
-def run_gpu(eng, w, variant, S, cap=None, pad_nan=True):
+def run_gpu(eng, w, variant, S, cap=None, pad_nan=True, logp=False):
     x = w.enc_out.copy()
     if pad_nan:
         for b in range(w.B):
             x[b, max(0, min(int(w.enc_len[b]), w.T)):, :] = np.nan
     enc = torch.from_numpy(x).cuda().contiguous()
     ln = torch.from_numpy(w.enc_len.astype(np.int32)).cuda()
-    out = eng.decode(variant, enc, ln, S, cap=cap)
+    out = eng.decode(variant, enc, ln, S, cap=cap, logp=logp)
     torch.cuda.synchronize()
     return to_lists(out, w.B), eng.status(), eng.stats()
 
 
-def check(pkg, w, variant, key, S=None, max_B=None, engine=None, expect_status=0):
+def check(pkg, w, variant, key, S=None, max_B=None, engine=None, expect_status=0, logp=False):
     S = w.max_symbols if S is None else S
     eng = engine or engine_for(pkg, key, w.model, max_B or w.B, w.T)
     net = oracle.LstmNet(w.model)
     ref = oracle.decode(net, w.enc_out, w.enc_len, S, "seq", n_threads=N_THREADS)
-    got, status, stats = run_gpu(eng, w, variant, S)
+    got, status, stats = run_gpu(eng, w, variant, S, logp=logp)
     log(f"[{key}/{variant}] B={w.B} T={w.T} S={S} tokens={int(ref.tok_len.sum())} "
         f"status={status} stats={stats}")
     assert status == expect_status
@@ -279,3 +279,23 @@ def test_bf16_weight_storage(pkg):
         eng.close()
     with pytest.raises(pkg.RnntError):
         pkg.Engine(w32.model, w32.B, w32.T, flags=2)
+
+
+def test_log_probabilities(pkg):
+    """The optional log-softmax output (fused log-sum-exp over the ranks) against the oracle's,
+    for the three decoders, with and without joint groups; asking for it changes no token, and
+    a later call without it leaves the buffer alone."""
+    for cfg, variants, kw in [(1, ("frame", "label"), {}),
+                              (3, ("frame", "label"), dict(B=9, T=100, len_lo=30, len_hi=100)),
+                              (4, ("tdt",), dict(B=9, T=100, len_lo=30, len_hi=100))]:
+        w = synth.make_workload(cfg, pad="nan", **kw)
+        eng = pkg.Engine(w.model, w.B, w.T)
+        for variant in variants:
+            for n_teams, groups in [(0, 0), (8, 1), (2, 4)]:
+                eng.configure(n_teams=n_teams, joint_groups=groups)
+                _, got, _ = check(pkg, w, variant, f"cfg{cfg}/logp teams={n_teams}/{groups}",
+                                  engine=eng, logp=True)
+                assert all(np.all(x <= 1e-6) for x in got["logps"])
+                _, plain, _ = check(pkg, w, variant, f"cfg{cfg}/no logp", engine=eng)
+                assert np.array_equal(plain["raw_tokens"], got["raw_tokens"])
+        eng.close()
