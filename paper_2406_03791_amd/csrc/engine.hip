@@ -307,6 +307,7 @@ int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
 // have their label; single-row groups of a team with four or more rows stop after two.
 int effective_search_steps(const rnnt_engine *e, const TeamConfig &t, int B)
 {
+    if (&t == &e->frame_cfg) return 0;      // Algorithm 1 has no label search
     if (e->search_steps < 0) return 0;
     if (e->search_steps > 0) return e->search_steps;
     const int rows_team = (B + t.n_teams - 1) / t.n_teams;
@@ -351,10 +352,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.B = B; p.T = T; p.S = S; p.cap = cap; p.variant = variant;
     p.n_teams = t.n_teams; p.team_size = t.team_size;
     p.groups = t.groups; p.jteam_size = t.jteam_size;
-    {
-        const char *v = std::getenv("RNNT_SERPENTINE");
-        p.serpentine = v ? (v[0] == '1') : 1;
-    }
+    p.serpentine = 1;
     p.wt = e->wt;
     p.lookahead = effective_lookahead(e, t, B);
     p.search_steps = effective_search_steps(e, t, B);
@@ -615,6 +613,7 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
         }
         if (i < std::min(eng->last_B, t->n_teams)) out->xcd_mismatch += mixed;
     }
+    // phase timers of a library built with -DRNNT_PROFILE, printed on request
     if (const char *dump = std::getenv("RNNT_DUMP_PHASES")) {
         if (dump[0] == '1') {
             for (int i = 0; i < t->n_teams; ++i) {
