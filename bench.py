@@ -91,6 +91,8 @@ def main() -> int:
     ap.add_argument("--variant", default="frame", choices=["frame", "label", "tdt"])
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="time the chosen decoder only (profiler runs: one decode kernel per trace)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead of the decode: under rocprofv3 "
                          "--pmc it gives the FETCH_SIZE / WRITE_SIZE reading for a known traffic")
@@ -98,7 +100,8 @@ def main() -> int:
                     help="also time Algorithm 1 and label looping over batch sizes 1..128 on the "
                          "typical workload and on the adversarial batches; listed under 'sweep'")
     ap.add_argument("--all-variants", action="store_true",
-                    help="also time the other decoders and list them under 'variants'")
+                    help="also time label looping with log-probabilities and the three decoders "
+                         "with bf16-stored weights, listed under 'variants'")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the batch shards with no exchange; "
@@ -196,14 +199,16 @@ def main() -> int:
                      "gpu_busy_frac": (r["dec_ms"] + r["proj_ms"]) / ms_per_step,
                      "us_per_lockstep_frame": 1e3 * ms_per_step / int(w.enc_len.max())},
     }
+    # the other decoders on their configurations (label looping decodes config 2's inputs and
+    # emits the same tokens; TDT is config 4's model): always listed beside the headline
+    line["variants"] = {}
+    for v in ("frame", "label", "tdt"):
+        if v == args.variant or args.no_variants:
+            continue
+        rv = run_variant(v, max(3, args.steps // 2), 2)
+        line["variants"][v] = {"frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"],
+                               "decode_ms": rv["dec_ms"], "status": rv["status"]}
     if args.all_variants:
-        line["variants"] = {}
-        for v in ("frame", "label", "tdt"):
-            if v == args.variant:
-                continue
-            rv = run_variant(v, max(3, args.steps // 2), 2)
-            line["variants"][v] = {"frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"],
-                                   "decode_ms": rv["dec_ms"], "status": rv["status"]}
         # label looping that also returns the log-probability of every label (fused log-sum-exp)
         rv = run_variant("label", max(3, args.steps // 2), 2, logp=True)
         line["variants"]["label_with_logp"] = {
