@@ -306,7 +306,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
 #pragma unroll
             for (int rg = 0; rg < RG; ++rg) {
                 float4 o = make_float4(acc[rg][0], acc[rg][1], acc[rg][2], acc[rg][3]);
-                *reinterpret_cast<float4 *>(red + ((task * RG + rg) * 4 + r4) * 4) = o;
+                *reinterpret_cast<float4 *>(red + task * red_task_stride(RG) + (rg * 4 + r4) * 4) = o;
             }
         }
     }
@@ -317,11 +317,11 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
 template <int RG>
 __device__ __forceinline__ void reduce_tasks4(const float *red, int nks, int g, int row, float (&a)[4])
 {
-    const float *src = red + ((g * nks * RG + (row >> 2)) * 4) * 4 + (row & 3);
+    const float *src = red + g * nks * red_task_stride(RG) + (row >> 2) * 16 + (row & 3);
     a[0] = a[1] = a[2] = a[3] = 0.f;
 #pragma unroll 4
     for (int ks = 0; ks < nks; ++ks) {
-        const float *q = src + ks * RG * 16;
+        const float *q = src + ks * red_task_stride(RG);
         a[0] += q[0]; a[1] += q[4]; a[2] += q[8]; a[3] += q[12];
     }
 }

@@ -174,7 +174,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     const int rgp = (rows_max + 3) / 4, rows_pad = rgp * 4;
     const int rgj = kMaxSamples / 4;
     auto red_need = [&](const StagePlan &pl, int grp, int rg) {
-        return std::min(grp * pl.nks, kBlocksPerWg * pl.slots) * rg * 16;
+        return std::min(grp * pl.nks, kBlocksPerWg * pl.slots) * red_task_stride(rg);
     };
     int xz = std::max(L * rows_pad * xstride, kMaxSamples * xstride);
     int red = red_need(t.st0.plan, L * nu_max, rgp);

@@ -32,6 +32,14 @@ constexpr int kStepUnroll = 4;       // weight loads (16 bytes per lane) per sof
 enum WeightType { kWeightF32 = 0, kWeightBf16 = 1 };
 RNNT_HD inline int k_per_load(int wt) { return wt == kWeightBf16 ? 8 : 4; }
 
+// Floats between the partial sums of consecutive tasks in LDS: 16 per row group plus a pad that
+// spreads the readers (one lane per output group, so a stride of whole multiples of 16 floats
+// would put all of them on two banks).
+#ifndef RNNT_RED_PAD
+#define RNNT_RED_PAD 4
+#endif
+RNNT_HD inline int red_task_stride(int rg) { return rg * 16 + RNNT_RED_PAD; }
+
 // Contiguous share of n items owned by `rank` out of `ts`.
 RNNT_HD inline int range_lo(int rank, int ts, int n) { return (int)(((int64_t)rank * n) / ts); }
 RNNT_HD inline int range_hi(int rank, int ts, int n) { return (int)(((int64_t)(rank + 1) * n) / ts); }
