@@ -299,3 +299,16 @@ def test_log_probabilities(pkg):
                 _, plain, _ = check(pkg, w, variant, f"cfg{cfg}/no logp", engine=eng)
                 assert np.array_equal(plain["raw_tokens"], got["raw_tokens"])
         eng.close()
+
+
+def test_full_size_label_looping_with_scores_and_bf16_storage(pkg):
+    """Config 3 at its full size, in the launch configuration bench.py times: label looping with
+    the log-probability output, and the same on the bf16-valued model stored as bf16."""
+    import dataclasses
+    w = synth.make_workload(3, pad="nan")
+    check(pkg, w, "label", "cfg3/full/logp", logp=True)
+    wb = dataclasses.replace(w, model=synth.with_bf16_streamed_weights(w.model))
+    eng = pkg.Engine(wb.model, wb.B, wb.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS)
+    check(pkg, wb, "label", "cfg3/full/bf16w", engine=eng, logp=True)
+    check(pkg, wb, "frame", "cfg2/full/bf16w", engine=eng)
+    eng.close()
