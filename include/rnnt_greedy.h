@@ -130,6 +130,10 @@ typedef struct rnnt_stats {
  * Copies and repacks the weights on the current device, allocates the
  * workspace (projected frames [max_B, max_T, J], state, exchange buffers).
  * flags: 0 or RNNT_FLAG_BF16_WEIGHTS; other bits are RNNT_ERR_SHAPE.
+ * A team of work-groups holds at most 16 utterances and its state has to fit
+ * the compute units' local memory: with the Parakeet shape on 256 compute
+ * units max_B up to 256 is accepted, a larger one returns
+ * RNNT_ERR_UNSUPPORTED (decode a larger batch in several calls).
  * Synchronous.  *out is set only on success.
  */
 int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T,

@@ -193,6 +193,18 @@ def test_host_side_errors(pkg):
     with pytest.raises(pkg.RnntError) as ei:
         pkg.tdt_label_looping_decode(**args())
     assert ei.value.code == -3
+    # a batch too large for the team layouts is refused when the engine is created
+    w2 = synth.make_workload(2, B=1, T=8, len_lo=8, len_hi=8)
+    with pytest.raises(pkg.RnntError) as ei:
+        pkg.Engine(w2.model, 1024, 8)
+    assert ei.value.code == -5
+
+
+def test_max_batch_of_the_parakeet_shape(pkg):
+    # 256 utterances: 8 rows per team in frame looping, 16 in label looping
+    w = synth.make_workload(2, pad="nan", B=256, T=40, len_lo=10, len_hi=40)
+    check(pkg, w, "frame", "parakeet256")
+    check(pkg, w, "label", "parakeet256")
 
 
 def test_cfg2_cut_and_tdt_cut(pkg):
