@@ -290,6 +290,19 @@ def main() -> int:
                                           f"{passes} times, per-utterance decode, one utterance "
                                           f"per thread, {dt:.2f} s wall in total",
                                 "rows_token_identical_to_gpu": same}
+        # one thread: the literal schedule of the timed decoder and the per-utterance
+        # schedule, on the two shortest utterances of the batch
+        nb = min(2, w.B)
+        pick = np.argsort(w.enc_len, kind="stable")[:nb]
+        xs, ls = np.ascontiguousarray(w.enc_out[pick]), np.ascontiguousarray(w.enc_len[pick])
+        literal = {"frame": "frame", "label": "label", "tdt": "tdt"}[args.variant]
+        one = {}
+        for name, s in (("literal_schedule", literal), ("per_utterance", "seq")):
+            t0 = time.perf_counter()
+            oracle.decode(net, xs, ls, w.max_symbols, s, n_threads=1)
+            one[name] = int(ls.sum()) / (time.perf_counter() - t0)
+        line["cpu_baseline"]["one_thread"] = dict(
+            one, unit="frames/s", sample=f"the {nb} shortest utterances ({int(ls.sum())} frames)")
     print(json.dumps(line))
     return 0
 

@@ -239,6 +239,28 @@ int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_group
  */
 int rnnt_engine_set_logp_output(rnnt_engine *eng, float *logp_out);
 
+/*
+ * Early return of finished utterances.  A batched decoder normally hands back
+ * nothing before its slowest utterance is done (the paper's discussion of the
+ * experiments names this as the price of batching); here utterances are
+ * decoded independently inside one kernel, so each one's results are final
+ * long before the call ends.
+ *
+ * done: [B] int32 the decode calls that follow write to, or NULL to switch the
+ * flags off.  The caller sets done[0..B) to 0 before a call; the library only
+ * ever stores 1.  As soon as utterance b has its last label, tok_len_out[b]
+ * and the utterance's rows of every output buffer (fill beyond tok_len
+ * included) are written and released at system scope, then done[b] = 1 is
+ * stored.  A host thread that is to read results while the call still runs
+ * passes pinned host memory (hipHostMalloc) for done and for the output
+ * buffers, polls done[b] and reads row b once it sees 1; with device memory the
+ * flags only order the outputs for other device-side readers.  When the call
+ * has completed every flag is 1 unless the device status reports an aborted
+ * call; the status word, not the flags, says whether results are valid.
+ * The caller owns the array and keeps it alive until the calls have finished.
+ */
+int rnnt_engine_set_done_flags(rnnt_engine *eng, int32_t *done);
+
 /* Text for a return code; for RNNT_ERR_HIP includes the last HIP error text. */
 const char *rnnt_status_string(int code);
 

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     rnnt_engine_create,
     rnnt_engine_destroy,
     rnnt_engine_set_logp_output,
+    rnnt_engine_set_done_flags,
     rnnt_engine_stats,
     rnnt_engine_status,
     rnnt_greedy_decode,

@@ -19,6 +19,7 @@ EXPORTS = (
     "rnnt_label_looping_decode", "tdt_label_looping_decode", "rnnt_encoder_projection",
     "rnnt_engine_status", "rnnt_engine_stats", "rnnt_engine_configure", "rnnt_status_string",
     "rnnt_engine_set_logp_output",
+    "rnnt_engine_set_done_flags",
 )
 
 
@@ -98,6 +99,7 @@ def load_library():
         lib.rnnt_engine_stats.argtypes = [C.c_void_p, C.POINTER(RnntStats)]
         lib.rnnt_engine_configure.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         lib.rnnt_engine_set_logp_output.argtypes = [C.c_void_p, C.c_void_p]
+        lib.rnnt_engine_set_done_flags.argtypes = [C.c_void_p, C.c_void_p]
         lib.rnnt_status_string.argtypes = [C.c_int]
         lib.rnnt_status_string.restype = C.c_char_p
         for name in EXPORTS:
@@ -149,6 +151,10 @@ def rnnt_engine_destroy(eng) -> None:
 
 def rnnt_engine_set_logp_output(eng, logp_out) -> None:
     _check(load_library().rnnt_engine_set_logp_output(eng, _p(logp_out)))
+
+
+def rnnt_engine_set_done_flags(eng, done) -> None:
+    _check(load_library().rnnt_engine_set_done_flags(eng, _p(done)))
 
 
 def rnnt_engine_configure(eng, n_teams: int = 0, joint_groups: int = 0, lookahead: int = 0,
@@ -233,9 +239,11 @@ class Engine:
                   search_steps: int = 0) -> None:
         rnnt_engine_configure(self.handle, n_teams, joint_groups, lookahead, search_steps)
 
-    def alloc_outputs(self, B: int, cap: int):
+    def alloc_outputs(self, B: int, cap: int, pinned: bool = False):
+        """Output tensors on the device, or (pinned=True) in pinned host memory,
+        which a host thread can read while a decode call runs."""
         t = self.torch
-        kw = dict(device=self.device)
+        kw = dict(pin_memory=True) if pinned else dict(device=self.device)
         out = dict(tokens=t.empty((B, cap), dtype=t.int32, **kw),
                    tok_len=t.empty((B,), dtype=t.int32, **kw),
                    frames=t.empty((B, cap), dtype=t.int32, **kw),
@@ -245,10 +253,11 @@ class Engine:
         return out
 
     def decode(self, variant: str, enc_out, enc_len, max_symbols: int, out=None,
-               cap: Optional[int] = None, logp: bool = False):
+               cap: Optional[int] = None, logp: bool = False, done=None):
         """enc_out [B,T,F] fp32 and enc_len [B] int32 device tensors.  Queues the
         decode on the current stream and returns the output tensors (device).
-        logp=True also asks for the log-probabilities (out["logps"])."""
+        logp=True also asks for the log-probabilities (out["logps"]); done is an
+        int32 [B] tensor of completion flags the caller has zeroed."""
         B, T = int(enc_out.shape[0]), int(enc_out.shape[1])
         if cap is None:
             cap = T * max_symbols
@@ -257,6 +266,7 @@ class Engine:
         if logp and "logps" not in out:
             out["logps"] = self.torch.empty((B, cap), dtype=self.torch.float32, device=self.device)
         rnnt_engine_set_logp_output(self.handle, out["logps"] if logp else None)
+        rnnt_engine_set_done_flags(self.handle, done)
         stream = self.torch.cuda.current_stream(self.device).cuda_stream
         common = (self.handle, enc_out, enc_len, B, T, max_symbols, out["tokens"], out["tok_len"],
                   cap, out["frames"], out["logits"])

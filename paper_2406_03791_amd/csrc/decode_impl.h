@@ -816,6 +816,17 @@ __device__ __forceinline__ void emit_row(const DecodeParams &p, const Wg &w, int
     c.sel[r] ^= 1;     // the candidate state becomes the state
 }
 
+// Row r has its last label: publish its count and, when the caller asked for completion
+// flags, make everything written for the utterance visible outside the device before the
+// flag is raised.  Called by the thread that wrote the row's outputs, or after a
+// work-group barrier behind that thread.
+__device__ __forceinline__ void finish_row(const DecodeParams &p, int r)
+{
+    const int b = c.b[r];
+    p.tok_len[b] = c.cnt[r];
+    if (p.done) __hip_atomic_store(p.done + b, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // RG: row groups (of 4) of a team in the prediction stages; RGJ: row groups a joint step is
 // laid out for (its samples never exceed 4 * RGJ); VARIANT: which loop nest; WT: storage of
 // the packed weights.
@@ -918,6 +929,8 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         }
     }
     if (!team_barrier(p, w, sy)) return;
+    // empty utterances are complete from the start
+    if (w.jrank == 0 && w.tid < R && w.tid % p.groups == w.jg && !c.active[w.tid]) finish_row(p, w.tid);
 
     long long n_pred = 0, n_joint = 0, n_samples = 0;
     int parity = 0;
@@ -936,7 +949,11 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         bool need_pred = true;     // nothing computed yet for (last_label, hidden)
         int win0 = 0, win_n = 0;   // frames [win0, win0 + win_n) have results for the current g
         for (int time_idx = 0; ok && time_idx < max_out_len; ++time_idx) {
-            if (w.tid < R) c.mask[w.tid] = time_idx >= c.len[w.tid];   // blank_mask
+            if (w.tid < R) {
+                c.mask[w.tid] = time_idx >= c.len[w.tid];   // blank_mask
+                // a row whose frames have run out is complete although the team goes on
+                if (w.rank == 0 && time_idx == c.len[w.tid] && time_idx > 0) finish_row(p, w.tid);
+            }
             int symbols_added = 0;
             bool not_blank = true;
             __syncthreads();
@@ -1056,7 +1073,10 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                     }
                     c.t[r] += pos;
                     if (found) c.searching[r] = 0;
-                    else if (c.t[r] >= c.len[r]) { c.searching[r] = 0; c.active[r] = 0; }
+                    else if (c.t[r] >= c.len[r]) {
+                        c.searching[r] = 0; c.active[r] = 0;
+                        if (w.jrank == 0) finish_row(p, r);
+                    }
                 }
                 __syncthreads();
                 any_searching = false;
@@ -1073,6 +1093,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 else { c.n[r] += 1; if (c.n[r] == p.S) { c.t[r] += 1; c.n[r] = 0; } }
                 c.active[r] = c.t[r] < c.len[r];
                 c.emitted[r] = 1;
+                if (!c.active[r] && w.jrank == 0) finish_row(p, r);
             }
             __syncthreads();
             if (G > 1) {
@@ -1131,7 +1152,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     }
     // epilogue
     __syncthreads();
-    if (w.jrank == 0 && w.tid < R && w.tid % p.groups == w.jg) p.tok_len[c.b[w.tid]] = c.cnt[w.tid];
+    if (w.jrank == 0 && w.tid < R && w.tid % p.groups == w.jg) finish_row(p, w.tid);
     if (w.jrank == 0 && w.tid == 0) {
         int st = (c.st_clamped ? 1 : 0) | (c.st_overflow ? 2 : 0);
         if (!ok) st |= 4;

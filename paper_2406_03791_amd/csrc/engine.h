@@ -45,6 +45,7 @@ struct DecodeParams {
     const float *P;         // [B, T, J] projected frames
     int *tokens; int *tok_len; int *frames; float *logits; int *durs;
     float *logps;           // [B, cap] log-softmax value of each emitted label, or NULL
+    int *done;              // [B] set to 1 once an utterance's outputs are final, or NULL
     StageDev st0;                 // recurrent (h) parts of all layers
     StageDev stl[kMaxLayers];     // input parts of layers 1..L-1 (index = layer)
     StageDev spred;               // prediction-side joint projection

@@ -78,6 +78,7 @@ struct rnnt_engine {
     int search_steps = 0;  // 0: chosen per call, -1: no limit, > 0: as given
     int wt = kWeightF32;   // storage of the packed (streamed) weights
     float *logp_out = nullptr;   // caller's [B, cap] buffer for log-probabilities, or none
+    int32_t *done = nullptr;     // caller's [B] completion flags, or none
     // host copies of the weights that get repacked when the team layout changes
     std::vector<std::vector<float>> w_ih, w_hh;
     std::vector<float> w_pred, w_out;
@@ -366,6 +367,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.tokens = tokens_out; p.tok_len = tok_len_out; p.frames = frames_out; p.logits = logit_out;
     p.durs = durs_out;
     p.logps = e->logp_out;
+    p.done = e->done;
     p.st0 = dev_stage(t.st0);
     for (int l = 1; l < d.L; ++l) p.stl[l] = dev_stage(t.stl[l]);
     p.spred = dev_stage(t.spred);
@@ -524,6 +526,13 @@ int rnnt_engine_set_logp_output(rnnt_engine *eng, float *logp_out)
 {
     if (!eng) return RNNT_ERR_NULL;
     eng->logp_out = logp_out;
+    return RNNT_OK;
+}
+
+int rnnt_engine_set_done_flags(rnnt_engine *eng, int32_t *done)
+{
+    if (!eng) return RNNT_ERR_NULL;
+    eng->done = done;
     return RNNT_OK;
 }
 

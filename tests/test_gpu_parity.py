@@ -49,8 +49,10 @@ def run_gpu(eng, w, variant, S, cap=None, pad_nan=True, logp=False):
             x[b, max(0, min(int(w.enc_len[b]), w.T)):, :] = np.nan
     enc = torch.from_numpy(x).cuda().contiguous()
     ln = torch.from_numpy(w.enc_len.astype(np.int32)).cuda()
-    out = eng.decode(variant, enc, ln, S, cap=cap, logp=logp)
+    done = torch.zeros(w.B, dtype=torch.int32, device="cuda")
+    out = eng.decode(variant, enc, ln, S, cap=cap, logp=logp, done=done)
     torch.cuda.synchronize()
+    assert bool((done == 1).all()), "every utterance is flagged complete when the call has ended"
     return to_lists(out, w.B), eng.status(), eng.stats()
 
 
@@ -266,6 +268,46 @@ def test_adversarial_batches(pkg):
             ref, got, stats = check(pkg, w, variant, f"adv/{pat}", engine=eng)
             assert ref.tok_len.tolist() == want.tolist()
             assert [len(t) for t in got["tokens"]] == want.tolist()
+
+
+def test_finished_utterances_are_flagged_while_the_call_runs(pkg):
+    # Row 0 emits max_symbols labels on every frame, the other rows only blanks: their
+    # results must be readable from pinned host memory, and right, long before row 0 is done.
+    import time
+    w = synth.make_adversarial("one_slow_row", cfg=2, B=8, T=60)
+    net = oracle.LstmNet(w.model)
+    ref = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "seq", n_threads=N_THREADS)
+    eng = engine_for(pkg, "parakeet_slow_row", w.model, w.B, w.T)
+    enc = torch.from_numpy(w.enc_out).cuda()
+    ln = torch.from_numpy(w.enc_len).cuda()
+    cap = w.T * w.max_symbols
+    for variant in ("label", "frame"):
+        out = eng.alloc_outputs(w.B, cap, pinned=True)
+        done = torch.zeros(w.B, dtype=torch.int32, pin_memory=True)
+        flags, lens, toks = done.numpy(), out["tok_len"].numpy(), out["tokens"].numpy()
+        stream, end = torch.cuda.Stream(), torch.cuda.Event()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            eng.decode(variant, enc, ln, w.max_symbols, out=out, done=done)
+            end.record()
+        seen = {}
+        deadline = time.monotonic() + 30.0
+        while len(seen) < w.B and time.monotonic() < deadline:
+            for b in range(w.B):
+                if b not in seen and flags[b] == 1:
+                    running = not end.query()      # asked after the flag was seen
+                    n = int(lens[b])
+                    seen[b] = (running, toks[b, :min(n, cap)].copy())
+        stream.synchronize()
+        assert eng.status() == 0
+        assert sorted(seen) == list(range(w.B))
+        early = [b for b in seen if seen[b][0]]
+        log(f"[slow row/{variant}] flagged while the kernel ran: rows {early}; "
+            f"tokens per row {[len(seen[b][1]) for b in range(w.B)]}")
+        for b in range(w.B):
+            assert np.array_equal(seen[b][1], ref.tokens[b]), (variant, b)
+        assert any(b != 0 for b in early)
+        assert len(ref.tokens[0]) == w.T * w.max_symbols
 
 
 def test_bf16_weight_storage(pkg):
