@@ -114,7 +114,7 @@ def main() -> int:
                          "typical workload and on the adversarial batches; listed under 'sweep'")
     ap.add_argument("--all-variants", action="store_true",
                     help="also time label looping with log-probabilities and the three decoders "
-                         "with bf16-stored weights, listed under 'variants'")
+                         "with bf16-stored and 8-bit (e4m3) stored weights, listed under 'variants'")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the batch shards with no exchange; "
@@ -142,15 +142,20 @@ def main() -> int:
                                                "launches": 4}}))
         return 0
 
-    def run_variant(variant, steps, warmup, bf16_weights=False, logp=False):
+    def run_variant(variant, steps, warmup, storage="fp32", logp=False):
         cfg = {"frame": 2, "label": 3, "tdt": 4}[variant]
         w = synth.make_workload(cfg, B=args.batch)
-        if bf16_weights:
-            # the model a bf16 checkpoint would give for the streamed matrices, kept as bf16 by
-            # the engine (lossless); fp32 arithmetic, checked against the oracle on that model
+        flags = 0
+        if storage != "fp32":
+            # the model a bf16 / 8-bit e4m3 checkpoint would give for the streamed matrices, kept
+            # in that format by the engine (lossless); fp32 arithmetic, checked against the
+            # oracle on that model
             import dataclasses
-            w = dataclasses.replace(w, model=synth.with_bf16_streamed_weights(w.model))
-        eng = pkg.Engine(w.model, w.B, w.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS if bf16_weights else 0)
+            transform, flags = {
+                "bf16": (synth.with_bf16_streamed_weights, pkg.RNNT_FLAG_BF16_WEIGHTS),
+                "fp8": (synth.with_fp8_streamed_weights, pkg.RNNT_FLAG_FP8_WEIGHTS)}[storage]
+            w = dataclasses.replace(w, model=transform(w.model))
+        eng = pkg.Engine(w.model, w.B, w.T, flags=flags)
         enc = torch.from_numpy(w.enc_out).cuda().contiguous()
         ln = torch.from_numpy(w.enc_len).cuda()
         out = eng.alloc_outputs(w.B, w.T * w.max_symbols)
@@ -231,17 +236,20 @@ def main() -> int:
         line["variants"]["label_with_logp"] = {
             "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
             "status": rv["status"]}
-        # the same decoders on the model with bf16-valued streamed weights, stored as bf16:
-        # another model (its tokens differ from the fp32 model's), reported beside, never as value
+        # the same decoders on the models with bf16-valued / e4m3-valued streamed weights, stored
+        # in that format: other models (their tokens differ from the fp32 model's), reported
+        # beside, never as value
         import oracle as _oracle
-        for v in ("frame", "label", "tdt"):
-            rv = run_variant(v, max(3, args.steps // 2), 2, bf16_weights=True)
+        for v, storage in [(v, s) for s in ("bf16", "fp8") for v in ("frame", "label", "tdt")]:
+            rv = run_variant(v, max(3, args.steps // 2), 2, storage=storage)
             wv = rv["w"]
             ref = _oracle.decode(_oracle.LstmNet(wv.model), wv.enc_out, wv.enc_len, wv.max_symbols,
                                  "seq", n_threads=min(16, os.cpu_count() or 1))
             same = sum(int(np.array_equal(ref.tokens[b], rv["tokens"][b])) for b in range(wv.B))
-            line["variants"][v + "_bf16_weights"] = {
+            line["variants"][f"{v}_{storage}_weights"] = {
                 "frames_per_s": wv.frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
+                "max_pred_steps": rv["stats"]["max_pred_steps"],
+                "max_joint_steps": rv["stats"]["max_joint_steps"], "tokens": int(rv["tok_len"].sum()),
                 "status": rv["status"], "rows_token_identical_to_oracle_on_same_model": same}
     if args.sweep:
         # batch-size and input-pattern sweep: how the two schedules take a slow row, the

@@ -126,10 +126,23 @@ typedef struct rnnt_stats {
 #define RNNT_FLAG_BF16_WEIGHTS 1
 
 /*
+ * rnnt_engine_create flag: the same matrices are kept as 8-bit floats in the
+ * OCP e4m3 format (1 sign, 4 exponent, 3 mantissa bits; largest value 448, no
+ * scale factors), a quarter of the fp32 bytes per step.  Lossless or refused
+ * like the bf16 flag: every streamed weight must be an e4m3 value or create
+ * returns RNNT_ERR_SHAPE; the arithmetic stays fp32.  Weight-only 8-bit storage
+ * is the direction the paper's conclusion names for the next speed-up (there
+ * for the encoder's products).  The two storage flags exclude each other
+ * (RNNT_ERR_SHAPE).
+ */
+#define RNNT_FLAG_FP8_WEIGHTS 2
+
+/*
  * Create an engine for up to max_B utterances of up to max_T frames.
  * Copies and repacks the weights on the current device, allocates the
  * workspace (projected frames [max_B, max_T, J], state, exchange buffers).
- * flags: 0 or RNNT_FLAG_BF16_WEIGHTS; other bits are RNNT_ERR_SHAPE.
+ * flags: 0, RNNT_FLAG_BF16_WEIGHTS or RNNT_FLAG_FP8_WEIGHTS; other bits are
+ * RNNT_ERR_SHAPE.
  * A team of work-groups holds at most 16 utterances and its state has to fit
  * the compute units' local memory: with the Parakeet shape on 256 compute
  * units max_B up to 256 is accepted, a larger one returns

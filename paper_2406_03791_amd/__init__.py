@@ -7,6 +7,7 @@ kernels.  There is no fallback: importing fails if the library is not built.
 """
 from .binding import (  # noqa: F401
     RNNT_FLAG_BF16_WEIGHTS,
+    RNNT_FLAG_FP8_WEIGHTS,
     Engine,
     RnntError,
     RnntStats,

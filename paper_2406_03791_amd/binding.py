@@ -24,6 +24,7 @@ EXPORTS = (
 
 
 RNNT_FLAG_BF16_WEIGHTS = 1
+RNNT_FLAG_FP8_WEIGHTS = 2
 
 
 class RnntError(RuntimeError):

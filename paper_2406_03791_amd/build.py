@@ -11,7 +11,9 @@ SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip",
            "decode_f1.hip", "decode_f2.hip", "decode_f4.hip",
            "decode_l1.hip", "decode_l2.hip", "decode_l4.hip",
            "decode_f1b.hip", "decode_f2b.hip", "decode_f4b.hip",
-           "decode_l1b.hip", "decode_l2b.hip", "decode_l4b.hip"]
+           "decode_l1b.hip", "decode_l2b.hip", "decode_l4b.hip",
+           "decode_f1e.hip", "decode_f2e.hip", "decode_f4e.hip",
+           "decode_l1e.hip", "decode_l2e.hip", "decode_l4e.hip"]
 LIB = os.path.join(HERE, "librnnt_greedy.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 FLAGS = ((["-DRNNT_PROFILE"] if os.environ.get("RNNT_PROFILE") else []) +

@@ -12,6 +12,9 @@ RNNT_DECLARE_LAUNCH(launch_decode_l2); RNNT_DECLARE_LAUNCH(launch_decode_l4);
 RNNT_DECLARE_LAUNCH(launch_decode_f1b); RNNT_DECLARE_LAUNCH(launch_decode_f2b);
 RNNT_DECLARE_LAUNCH(launch_decode_f4b); RNNT_DECLARE_LAUNCH(launch_decode_l1b);
 RNNT_DECLARE_LAUNCH(launch_decode_l2b); RNNT_DECLARE_LAUNCH(launch_decode_l4b);
+RNNT_DECLARE_LAUNCH(launch_decode_f1e); RNNT_DECLARE_LAUNCH(launch_decode_f2e);
+RNNT_DECLARE_LAUNCH(launch_decode_f4e); RNNT_DECLARE_LAUNCH(launch_decode_l1e);
+RNNT_DECLARE_LAUNCH(launch_decode_l2e); RNNT_DECLARE_LAUNCH(launch_decode_l4e);
 #undef RNNT_DECLARE_LAUNCH
 
 // Clears what must start at zero for a call: barrier counters, abort flag, status, stats and
@@ -51,12 +54,15 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     const int rgj = samples <= 4 ? 1 : (samples <= 8 ? 2 : (samples <= 16 ? 4 : 8));
     const int rgi = rg <= 1 ? 0 : (rg <= 2 ? 1 : 2);
     typedef hipError_t (*Launch)(const DecodeParams &, int, hipStream_t);
-    static const Launch table[2][2][3] = {
+    static const Launch table[3][2][3] = {
         {{launch_decode_f1, launch_decode_f2, launch_decode_f4},
          {launch_decode_l1, launch_decode_l2, launch_decode_l4}},
         {{launch_decode_f1b, launch_decode_f2b, launch_decode_f4b},
-         {launch_decode_l1b, launch_decode_l2b, launch_decode_l4b}}};
-    return table[p.wt == kWeightBf16 ? 1 : 0][p.variant == kFrameLooping ? 0 : 1][rgi](p, rgj, stream);
+         {launch_decode_l1b, launch_decode_l2b, launch_decode_l4b}},
+        {{launch_decode_f1e, launch_decode_f2e, launch_decode_f4e},
+         {launch_decode_l1e, launch_decode_l2e, launch_decode_l4e}}};
+    if (p.wt < 0 || p.wt > 2) return hipErrorInvalidValue;
+    return table[p.wt][p.variant == kFrameLooping ? 0 : 1][rgi](p, rgj, stream);
 }
 
 }  // namespace rnnt

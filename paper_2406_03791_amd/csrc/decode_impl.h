@@ -21,6 +21,7 @@ namespace rnnt {
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 
 struct Ctl {
     int b[kMaxRows], len[kMaxRows], t[kMaxRows], n[kMaxRows], last[kMaxRows];
@@ -223,8 +224,9 @@ __device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const Sta
 //                starts `x_inp_stride` floats further (inp = group / groups_per_inp)
 //   red_aliases_x  the results overwrite x (only valid with a single slot)
 // WT: how the packed weights are stored.  kWeightF32: a load carries four weights.
-// kWeightBf16: a load carries eight bf16 weights, used as two half-steps of four; a bf16
+// kWeightBf16: a load carries eight bf16 weights, used as two part-steps of four; a bf16
 // weight becomes its fp32 value by a shift, the products and sums are fp32 as before.
+// kWeightFp8: sixteen e4m3 weights, four part-steps; one conversion instruction widens two.
 template <int RG, int WT, int AH, bool NT>
 __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int rank, int n_tasks,
                                           WeightStream<AH, NT> &ws, const float *x, int xstride,
@@ -239,7 +241,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
         const bool live = ws.live;
         const int g = live ? task / sd.nks : 0;
         const int ks = live ? task - g * sd.nks : 0;
-        constexpr int KPER = WT == kWeightBf16 ? 8 : 4;
+        constexpr int KPER = WT == kWeightFp8 ? 16 : (WT == kWeightBf16 ? 8 : 4);
         constexpr int HALVES = KPER / 4;
         const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * KPER;
         v4f acc[RG];
@@ -277,6 +279,11 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
                                 const unsigned hi = __float_as_uint(h == 0 ? raw.y : raw.w);
                                 wv = make_float4(__uint_as_float(lo << 16), __uint_as_float(lo & 0xffff0000u),
                                                  __uint_as_float(hi << 16), __uint_as_float(hi & 0xffff0000u));
+                            } else if (WT == kWeightFp8) {
+                                const int word = (int)__float_as_uint(h == 0 ? raw.x : (h == 1 ? raw.y : (h == 2 ? raw.z : raw.w)));
+                                const v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(word, false);
+                                const v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8(word, true);
+                                wv = make_float4(lo[0], lo[1], hi[0], hi[1]);
                             } else {
                                 wv = raw;
                             }

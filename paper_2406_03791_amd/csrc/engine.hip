@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -104,11 +105,35 @@ inline uint16_t bf16_bits(float v)
     return (uint16_t)(u >> 16);
 }
 
+// OCP e4m3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, largest
+// finite value 448) of a float, if the float is one of its values.
+inline bool e4m3_bits(float v, uint8_t *code)
+{
+    uint32_t u;
+    std::memcpy(&u, &v, sizeof u);
+    const uint32_t sign = (u >> 31) << 7, expo = (u >> 23) & 0xffu, mant = u & 0x7fffffu;
+    if ((u & 0x7fffffffu) == 0) { *code = (uint8_t)sign; return true; }
+    if (expo == 0xffu || expo == 0) return false;           // not finite, or an fp32 subnormal
+    const int e = (int)expo - 127;
+    if (e >= -6) {                                          // e4m3 normal
+        if (e > 8 || (mant & 0xfffffu) != 0) return false;
+        const uint32_t m = mant >> 20;
+        if (e == 8 && m == 7) return false;                 // that code is NaN
+        *code = (uint8_t)(sign | ((uint32_t)(e + 7) << 3) | m);
+        return true;
+    }
+    const float t = std::fabs(v) * 512.0f;                  // e4m3 subnormals are m * 2^-9, m = 1..7
+    const int m = (int)t;
+    if ((float)m != t || m < 1 || m > 7) return false;
+    *code = (uint8_t)(sign | (uint32_t)m);
+    return true;
+}
+
 int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups,
                  const std::function<const float *(int, int, int)> &row_of)
 {
     const StagePlan &pl = ps.plan;
-    // 16 bytes per (rank, slot, wave, step, lane): 4 floats or 8 bf16 codes
+    // 16 bytes per (rank, slot, wave, step, lane): 4 floats, 8 bf16 codes or 16 e4m3 codes
     std::vector<uint32_t> host((size_t)ts * pl.rank_stride * 4, 0u);
     for (int rank = 0; rank < ts; ++rank) {
         const int ntask = ngroups(rank) * pl.nks;
@@ -128,10 +153,17 @@ int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups
                         if (pl.kper == 4) {
                             for (int c = 0; c < 4; ++c)
                                 if (k0 + c < pl.K) std::memcpy(dst + c, row + k0 + c, 4);
-                        } else {
+                        } else if (pl.kper == 8) {
                             for (int c = 0; c < 8; ++c)
                                 if (k0 + c < pl.K)
                                     dst[c >> 1] |= (uint32_t)bf16_bits(row[k0 + c]) << (16 * (c & 1));
+                        } else {
+                            for (int c = 0; c < 16; ++c)
+                                if (k0 + c < pl.K) {
+                                    uint8_t code = 0;
+                                    e4m3_bits(row[k0 + c], &code);   // checked when the engine was created
+                                    dst[c >> 2] |= (uint32_t)code << (8 * (c & 3));
+                                }
                         }
                     }
                 }
@@ -396,7 +428,8 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
                        rnnt_engine **out)
 {
     if (!desc || !out) return RNNT_ERR_NULL;
-    if (flags & ~RNNT_FLAG_BF16_WEIGHTS) return RNNT_ERR_SHAPE;
+    if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS)) return RNNT_ERR_SHAPE;
+    if ((flags & RNNT_FLAG_BF16_WEIGHTS) && (flags & RNNT_FLAG_FP8_WEIGHTS)) return RNNT_ERR_SHAPE;
     const rnnt_model_desc &d = *desc;
     if (!d.emb || !d.w_ih || !d.w_hh || !d.b_ih || !d.b_hh || !d.w_enc || !d.b_enc || !d.w_pred ||
         !d.b_pred || !d.w_out || !d.b_out)
@@ -427,7 +460,8 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     for (int i = 0; i < d.D; ++i) e->durations[i] = d.durations[i];
     e->NOUT = d.V1 + d.D;
     e->max_B = max_B; e->max_T = max_T;
-    e->wt = (flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32;
+    e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8
+                                            : ((flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32);
     e->n_wg = (prop.multiProcessorCount / 32) * 32;   // every layout divides it
     if (e->n_wg < 32) return RNNT_ERR_UNSUPPORTED;
 
@@ -459,6 +493,17 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         };
         bool ok = is_bf16(e->w_pred) && is_bf16(e->w_out);
         for (int l = 0; l < d.L; ++l) ok = ok && is_bf16(e->w_hh[l]) && (l == 0 || is_bf16(e->w_ih[l]));
+        if (!ok) return RNNT_ERR_SHAPE;
+    }
+    if (e->wt == kWeightFp8) {
+        auto is_e4m3 = [](const std::vector<float> &v) {
+            uint8_t code;
+            for (float x : v)
+                if (!e4m3_bits(x, &code)) return false;
+            return true;
+        };
+        bool ok = is_e4m3(e->w_pred) && is_e4m3(e->w_out);
+        for (int l = 0; l < d.L; ++l) ok = ok && is_e4m3(e->w_hh[l]) && (l == 0 || is_e4m3(e->w_ih[l]));
         if (!ok) return RNNT_ERR_SHAPE;
     }
 

@@ -27,10 +27,11 @@ constexpr int kMaxRows = 16;         // utterances per team
 constexpr int kMaxSamples = 32;      // (utterance, frame) pairs per joint step
 constexpr int kStepUnroll = 4;       // weight loads (16 bytes per lane) per software-pipeline batch
 
-// Storage of the packed weights: fp32 (4 K values per 16-byte load) or bf16 (8 per load).
-// The arithmetic is fp32 either way: a bf16 weight is widened before it is used.
-enum WeightType { kWeightF32 = 0, kWeightBf16 = 1 };
-RNNT_HD inline int k_per_load(int wt) { return wt == kWeightBf16 ? 8 : 4; }
+// Storage of the packed weights: fp32 (4 K values per 16-byte load), bf16 (8 per load) or
+// fp8 in the OCP e4m3 format (16 per load).  The arithmetic is fp32 in every case: a stored
+// weight is widened before it is used.
+enum WeightType { kWeightF32 = 0, kWeightBf16 = 1, kWeightFp8 = 2 };
+RNNT_HD inline int k_per_load(int wt) { return wt == kWeightFp8 ? 16 : (wt == kWeightBf16 ? 8 : 4); }
 
 // Floats between the partial sums of consecutive tasks in LDS: 16 per row group plus a pad that
 // spreads the readers (one lane per output group, so a stride of whole multiples of 16 floats
@@ -49,7 +50,7 @@ struct StagePlan {
     int nks;        // K slices per group
     int nsteps;     // 16-byte loads per lane and task (multiple of kStepUnroll)
     int slots;      // passes over the 128 blocks
-    int kper;       // K values per load (4: fp32 weights, 8: bf16 weights)
+    int kper;       // K values per load (4: fp32 weights, 8: bf16, 16: fp8)
     int kpad;       // nks * nsteps * kper: padded input length
     int64_t rank_stride;   // 16-byte elements of packed weights per rank
 };

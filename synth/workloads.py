@@ -252,12 +252,33 @@ def round_to_bf16(a: np.ndarray) -> np.ndarray:
     return r.astype(np.uint32).view(np.float32).reshape(a.shape)
 
 
+def round_to_e4m3(a: np.ndarray) -> np.ndarray:
+    """float32 array with every value rounded to the nearest value of the 8-bit OCP e4m3
+    format (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; subnormals are multiples of
+    2^-9; largest value 448, larger inputs saturate), ties to even, stored as float32."""
+    x = np.ascontiguousarray(a, dtype=np.float32).astype(np.float64)
+    mag = np.minimum(np.abs(x), 448.0)
+    _, e = np.frexp(mag)                       # mag = m * 2^e, 0.5 <= m < 1
+    quantum = np.ldexp(1.0, np.maximum(e - 1, -6) - 3)
+    r = np.minimum(np.rint(mag / quantum) * quantum, 448.0)
+    return np.copysign(r, x).astype(np.float32).reshape(a.shape)
+
+
+def _with_streamed_weights(model: Model, f) -> Model:
+    w_ih = [w if l == 0 else f(w) for l, w in enumerate(model.w_ih)]
+    w_hh = [f(w) for w in model.w_hh]
+    return replace(model, w_ih=w_ih, w_hh=w_hh, w_pred=f(model.w_pred), w_out=f(model.w_out))
+
+
+def with_fp8_streamed_weights(model: Model) -> Model:
+    """Like with_bf16_streamed_weights, with e4m3 values: the model an 8-bit weight-only
+    checkpoint (without scale factors) would give for the streamed matrices."""
+    return _with_streamed_weights(model, round_to_e4m3)
+
+
 def with_bf16_streamed_weights(model: Model) -> Model:
     """A copy of `model` whose per-step streamed matrices (W_hh of every layer, W_ih of the
     layers above the first, W_pred, W_out) hold bf16 values; everything else is unchanged.
     This is the model a bf16 checkpoint would give for those matrices; both the oracle and the
     engine take it as their fp32 input."""
-    w_ih = [w if l == 0 else round_to_bf16(w) for l, w in enumerate(model.w_ih)]
-    w_hh = [round_to_bf16(w) for w in model.w_hh]
-    return replace(model, w_ih=w_ih, w_hh=w_hh, w_pred=round_to_bf16(model.w_pred),
-                   w_out=round_to_bf16(model.w_out))
+    return _with_streamed_weights(model, round_to_bf16)

@@ -58,11 +58,11 @@ def test_stage_planner_covers_k_and_fits_the_blocks():
 #include <cstdio>
 int main() {
   int bad = 0;
-  for (int wt = 0; wt < 2; ++wt)
+  for (int wt = 0; wt < 3; ++wt)
   for (int K = 4; K <= 2048; K += 4)
     for (int g = 1; g <= 300; g += (g < 40 ? 1 : 13)) {
       rnnt::StagePlan p = rnnt::make_stage_plan(K, g, wt);
-      if (p.kper != (wt ? 8 : 4)) bad++;
+      if (p.kper != (4 << wt)) bad++;
       if (p.kpad < K || p.kpad != p.nks * p.nsteps * p.kper || p.nsteps % rnnt::kStepUnroll) bad++;
       if (g * p.nks > rnnt::kBlocksPerWg * p.slots) bad++;
       if (p.slots > 1 && p.nks != 1) bad++;

@@ -310,29 +310,37 @@ def test_finished_utterances_are_flagged_while_the_call_runs(pkg):
         assert len(ref.tokens[0]) == w.T * w.max_symbols
 
 
-def test_bf16_weight_storage(pkg):
-    """Engine with the streamed weights kept as bf16 (lossless storage of a model whose streamed
-    matrices hold bf16 values) against the oracle on that same model; a model with other values
-    is refused.  Also logs how many rows differ from the decode of the unrounded model."""
+def test_compact_weight_storage(pkg):
+    """Engines with the streamed weights kept as bf16 or as 8-bit e4m3 (lossless storage of a
+    model whose streamed matrices hold such values) against the oracle on that same model; a
+    model with other values is refused.  Also logs how many rows differ from the decode of the
+    unrounded model."""
     import dataclasses
+    kinds = [("bf16w", pkg.RNNT_FLAG_BF16_WEIGHTS, synth.with_bf16_streamed_weights),
+             ("fp8w", pkg.RNNT_FLAG_FP8_WEIGHTS, synth.with_fp8_streamed_weights)]
     for cfg, variants, kw in [(3, ("frame", "label"), dict(B=6, T=120, len_lo=40, len_hi=120)),
                               (4, ("tdt",), dict(B=6, T=120, len_lo=40, len_hi=120)),
                               (1, ("frame", "label"), {})]:
         w32 = synth.make_workload(cfg, pad="nan", **kw)
-        with pytest.raises(pkg.RnntError) as err:
-            pkg.Engine(w32.model, w32.B, w32.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS)
-        assert err.value.code == -2
-        w = dataclasses.replace(w32, model=synth.with_bf16_streamed_weights(w32.model))
-        eng = pkg.Engine(w.model, w.B, w.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS)
         ref32 = oracle.decode(oracle.LstmNet(w32.model), w32.enc_out, w32.enc_len, w32.max_symbols,
                               "seq", n_threads=N_THREADS)
-        for variant in variants:
-            ref, got, _ = check(pkg, w, variant, f"cfg{cfg}/bf16w", engine=eng)
-            moved = sum(int(not np.array_equal(ref.tokens[b], ref32.tokens[b])) for b in range(w.B))
-            log(f"  rows whose tokens differ from the fp32 model's: {moved}/{w.B}")
-        eng.close()
-    with pytest.raises(pkg.RnntError):
-        pkg.Engine(w32.model, w32.B, w32.T, flags=2)
+        for name, flag, transform in kinds:
+            with pytest.raises(pkg.RnntError) as err:
+                pkg.Engine(w32.model, w32.B, w32.T, flags=flag)
+            assert err.value.code == -2
+            w = dataclasses.replace(w32, model=transform(w32.model))
+            eng = pkg.Engine(w.model, w.B, w.T, flags=flag)
+            for variant in variants:
+                ref, got, _ = check(pkg, w, variant, f"cfg{cfg}/{name}", engine=eng)
+                moved = sum(int(not np.array_equal(ref.tokens[b], ref32.tokens[b])) for b in range(w.B))
+                log(f"  rows whose tokens differ from the fp32 model's: {moved}/{w.B}")
+            eng.close()
+    # unknown flag bits and both storage flags at once are refused
+    w8 = dataclasses.replace(w32, model=synth.with_fp8_streamed_weights(w32.model))
+    for flags in (4, pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS):
+        with pytest.raises(pkg.RnntError) as err:
+            pkg.Engine(w8.model, w8.B, w8.T, flags=flags)
+        assert err.value.code == -2
 
 
 def test_log_probabilities(pkg):
@@ -355,9 +363,10 @@ def test_log_probabilities(pkg):
         eng.close()
 
 
-def test_full_size_label_looping_with_scores_and_bf16_storage(pkg):
+def test_full_size_label_looping_with_scores_and_compact_storage(pkg):
     """Config 3 at its full size, in the launch configuration bench.py times: label looping with
-    the log-probability output, and the same on the bf16-valued model stored as bf16."""
+    the log-probability output, and the same on the bf16-valued model stored as bf16 and the
+    e4m3-valued model stored as e4m3."""
     import dataclasses
     w = synth.make_workload(3, pad="nan")
     check(pkg, w, "label", "cfg3/full/logp", logp=True)
@@ -365,4 +374,9 @@ def test_full_size_label_looping_with_scores_and_bf16_storage(pkg):
     eng = pkg.Engine(wb.model, wb.B, wb.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS)
     check(pkg, wb, "label", "cfg3/full/bf16w", engine=eng, logp=True)
     check(pkg, wb, "frame", "cfg2/full/bf16w", engine=eng)
+    eng.close()
+    w8 = dataclasses.replace(w, model=synth.with_fp8_streamed_weights(w.model))
+    eng = pkg.Engine(w8.model, w8.B, w8.T, flags=pkg.RNNT_FLAG_FP8_WEIGHTS)
+    check(pkg, w8, "label", "cfg3/full/fp8w", engine=eng, logp=True)
+    check(pkg, w8, "frame", "cfg2/full/fp8w", engine=eng)
     eng.close()

@@ -320,6 +320,26 @@ def test_bf16_rounding_of_inputs_matches_torch():
     assert np.all(r.w_out.view(np.uint32) & 0xFFFF == 0) and np.all(r.w_hh[0].view(np.uint32) & 0xFFFF == 0)
 
 
+def test_e4m3_rounding_of_inputs_matches_torch():
+    """synth.round_to_e4m3 rounds to the nearest 8-bit e4m3 value (ties to even, saturating at
+    448), as torch's float8_e4m3fn conversion does inside that range; the 254 finite codes are
+    fixed points."""
+    x = np.concatenate([synth.normal(78, 1, (4096,)) * 0.1, synth.normal(78, 2, (4096,)) * 30.0,
+                        synth.uniform(78, 3, (2048,), -0.01, 0.01)]).astype(np.float32)
+    x[:10] = [0.0, -0.0, 448.0, -448.0, 2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -10, 2.0 ** -6, 0.0625 + 2.0 ** -8, 440.0]
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).to(torch.float32).numpy()
+    got = synth.round_to_e4m3(x)
+    assert np.array_equal(got, want) and np.array_equal(np.signbit(got), np.signbit(want))
+    assert synth.round_to_e4m3(np.array([1000.0, -465.0], np.float32)).tolist() == [448.0, -448.0]
+    codes = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    finite = codes[np.isfinite(codes)]
+    assert finite.size == 254 and np.array_equal(synth.round_to_e4m3(finite), finite)
+    m = synth.make_workload(0).model
+    r = synth.with_fp8_streamed_weights(m)
+    assert np.array_equal(r.emb, m.emb) and np.array_equal(r.w_ih[0], m.w_ih[0])
+    assert np.array_equal(synth.round_to_e4m3(r.w_out), r.w_out) and not np.array_equal(r.w_out, m.w_out)
+
+
 def test_log_probabilities_of_emitted_labels():
     """The v of Algorithm 1's `k, v = logp.max()`: log_softmax over the token columns at the
     chosen label.  Pinned against torch.log_softmax on table-driven logits (the duration
