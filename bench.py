@@ -25,14 +25,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(dims, B, variant, enc_len, tok_frames, S):
+def algorithmic_bytes(dims, B, variant, enc_len, tok_frames, S, wbytes=4):
     """Bytes the method must touch per launch: every weight once per batched
     step of the schedule (Algorithm 1 / label looping run on the whole batch),
     recurrent state read and written, embedding and projected-frame rows."""
     H, L, J, E, nout = dims.H, dims.L, dims.J, dims.E, dims.n_out
-    lstm_w = sum(4 * H * ((E if l == 0 else H) + H) + 8 * H for l in range(L))
-    pred_bytes = 4 * (lstm_w + J * H + J) + 4 * (2 * L * 2 * B * H) + 4 * B * E
-    joint_bytes = 4 * (nout * J + nout) + 4 * B * J
+    # matrices in their stored width (layer 0's input weights are never stored compactly),
+    # biases, state and gathered rows in fp32
+    lstm_w = sum(4 * H * (4 * E if l == 0 else wbytes * H) + 4 * H * wbytes * H + 4 * 8 * H
+                 for l in range(L))
+    pred_bytes = lstm_w + wbytes * J * H + 4 * J + 4 * (2 * L * 2 * B * H) + 4 * B * E
+    joint_bytes = wbytes * nout * J + 4 * nout + 4 * B * J
     counts = [np.bincount(f, minlength=int(n))[:int(n)] if int(n) else np.zeros(0, int)
               for f, n in zip(tok_frames, enc_len)]
     tok = np.array([len(f) for f in tok_frames])
@@ -55,7 +58,7 @@ def algorithmic_bytes(dims, B, variant, enc_len, tok_frames, S):
             pred_steps * pred_flops + joint_steps * joint_flops)
 
 
-def issued_weight_bytes(dims, stats):
+def issued_weight_bytes(dims, stats, bytes_per_weight=4):
     """Bytes of the steps the device ran, from its own step counters: every prediction
     step of a team streams the recurrent and upper-layer LSTM weights and W_pred (layer 0's
     input weights are folded into a table and never stream), every joint step of a joint
@@ -63,8 +66,8 @@ def issued_weight_bytes(dims, stats):
     groups are taken to be alike.  Part of it is served by the L2 of an XCD that several
     teams share, so the profiled HBM traffic is lower."""
     H, L, J = dims.H, dims.L, dims.J
-    pred = 4 * (sum(4 * H * (H + (H if l else 0)) for l in range(L)) + J * H)
-    joint = 4 * dims.n_out * J
+    pred = bytes_per_weight * (sum(4 * H * (H + (H if l else 0)) for l in range(L)) + J * H)
+    joint = bytes_per_weight * dims.n_out * J
     return stats["pred_steps"] * pred + stats["joint_steps"] * stats["joint_groups"] * joint
 
 
@@ -103,6 +106,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--variant", default="frame", choices=["frame", "label", "tdt"])
     ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--storage", default="fp32", choices=["fp32", "bf16", "fp8"],
+                    help="storage of the streamed weights for the timed decoder; bf16 / fp8 decode "
+                         "another model (the one with weights rounded to that format), so their "
+                         "figures stand beside the fp32 headline, never for it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
                     help="time the chosen decoder only (profiler runs: one decode kernel per trace)")
@@ -182,16 +189,18 @@ def main() -> int:
         eng.close()
         return res
 
-    r = run_variant(args.variant, args.steps, args.warmup)
+    r = run_variant(args.variant, args.steps, args.warmup, storage=args.storage)
     w = r["w"]
     n_frames = w.frames
     ms_per_step = 1e3 * r["wall"] / r["steps"]
     value = n_frames * r["steps"] / r["wall"]
     alg_bytes, pred_steps, joint_steps, alg_flops = algorithmic_bytes(
-        w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols)
+        w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols,
+        {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage])
     # numerator of the roofline: the bytes of the steps the device counted (every team step
     # touches its streamed weights once); the batched schedule's figure is listed beside it
-    step_bytes = issued_weight_bytes(w.model.dims, r["stats"])
+    step_bytes = issued_weight_bytes(w.model.dims, r["stats"],
+                                     {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage])
     achieved = step_bytes / (r["dec_ms"] * 1e-3) / 1e9
     line = {
         "metric": "encoder frames decoded/sec, Parakeet-1.1B decoder shape, B=32",
@@ -201,14 +210,18 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"config {dict(frame=2, label=3, tdt=4)[args.variant]}: "
                                f"{w.name}, B={w.B}, T<={w.T}, frames={n_frames}, "
-                               f"max_symbols={w.max_symbols}, variant={args.variant}",
+                               f"max_symbols={w.max_symbols}, variant={args.variant}" +
+                               ("" if args.storage == "fp32" else
+                                f", streamed weights rounded to and stored as {args.storage} "
+                                f"(another model than the headline's; fp32 arithmetic)"),
                    "tokens": int(r["tok_len"].sum()), "device_status": r["status"],
                    "kernel_ms": {"decode": r["dec_ms"], "decode_min": r["dec_ms_min"],
                                  "encoder_projection": r["proj_ms"]},
                    "engine": r["stats"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": profiled_traffic(args.variant) if args.batch == 32 else None,
+                     "traffic": (profiled_traffic(args.variant)
+                                 if args.batch == 32 and args.storage == "fp32" else None),
                      "kernel": "decode_kernel", "algorithmic_bytes": step_bytes,
                      "bytes_from": "measured team steps x weights streamed per step",
                      "batched_schedule": {"prediction_steps": pred_steps, "joint_steps": joint_steps,
