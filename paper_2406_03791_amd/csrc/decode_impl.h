@@ -1103,6 +1103,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 if (!c.active[r] && w.jrank == 0) finish_row(p, r);
             }
             __syncthreads();
+            PROF_MARK(w, 16);
             if (G > 1) {
                 // tell the other groups about this group's rows, learn about theirs
                 if (w.jrank == 0 && w.tid < rj) {
@@ -1148,6 +1149,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 __syncthreads();
                 ok = c.bar_ok != 0;
             }
+            PROF_MARK(w, 19);
             any_active = false;
             need_pred = false;
             for (int r = 0; r < R; ++r) {
