@@ -330,6 +330,10 @@ int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
     const int rows = std::max(1, (rows_team + t.groups - 1) / t.groups);
     int la = e->lookahead > 0 ? e->lookahead : 8;
     if (e->lookahead == 0 && &t == &e->frame_cfg) la = std::min(8, std::max(1, 16 / rows));
+    // label looping with one utterance per joint group on the 64-work-group teams of the small
+    // batches: a joint step is cheap next to its fixed cost, 16 frames per step measured 4-9 %
+    // faster than 8 (no gain on the smaller teams of larger batches)
+    if (e->lookahead == 0 && &t != &e->frame_cfg && rows == 1 && t.team_size >= 64) la = 16;
     if (la * rows > kMaxSamples) la = std::max(1, kMaxSamples / rows);
     return la;
 }
