@@ -120,8 +120,9 @@ def main() -> int:
                     help="also time Algorithm 1 and label looping over batch sizes 1..128 on the "
                          "typical workload and on the adversarial batches; listed under 'sweep'")
     ap.add_argument("--all-variants", action="store_true",
-                    help="also time label looping with log-probabilities and the three decoders "
-                         "with bf16-stored and 8-bit (e4m3) stored weights, listed under 'variants'")
+                    help="also time label looping with log-probabilities, the single-layer second "
+                         "workload and the three decoders with bf16-stored and 8-bit (e4m3) stored "
+                         "weights, listed under 'variants'")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the batch shards with no exchange; "
@@ -149,8 +150,8 @@ def main() -> int:
                                                "launches": 4}}))
         return 0
 
-    def run_variant(variant, steps, warmup, storage="fp32", logp=False):
-        cfg = {"frame": 2, "label": 3, "tdt": 4}[variant]
+    def run_variant(variant, steps, warmup, storage="fp32", logp=False, cfg=None):
+        cfg = {"frame": 2, "label": 3, "tdt": 4}[variant] if cfg is None else cfg
         w = synth.make_workload(cfg, B=args.batch)
         flags = 0
         if storage != "fp32":
@@ -249,6 +250,12 @@ def main() -> int:
         line["variants"]["label_with_logp"] = {
             "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
             "status": rv["status"]}
+        # second workload: the single-layer model that stands in for the paper's smaller one
+        for v in ("frame", "label"):
+            rv = run_variant(v, max(3, args.steps // 2), 2, cfg=5)
+            line["variants"][v + "_small_model"] = {
+                "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
+                "frames": rv["w"].frames, "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
         # the same decoders on the models with bf16-valued / e4m3-valued streamed weights, stored
         # in that format: other models (their tokens differ from the fp32 model's), reported
         # beside, never as value

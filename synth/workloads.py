@@ -206,6 +206,12 @@ CONFIGS = {
     4: dict(name="tdt_label", variant="tdt", seed=4, dims=_TDT,
             B=32, T=500, len_lo=200, len_hi=500, sort_desc=True, S=10,
             model_kw=dict(blank_bias=7.71, tie=(5.0, 2.0, 5.0))),
+    # Second workload: the smaller model of the paper's results table.  The paper does not give
+    # its decoder's shape; a single LSTM layer at the same widths is this build's guess.
+    5: dict(name="small_model_label", variant="label", seed=5,
+            dims=replace(_PARAKEET, L=1),
+            B=32, T=500, len_lo=200, len_hi=500, sort_desc=True, S=10,
+            model_kw=dict(blank_bias=8.73, tie=(5.0, 2.0, 5.0))),
 }
 
 

@@ -241,6 +241,13 @@ def test_cfg4_tdt_full(pkg):
     check(pkg, w, "tdt", "tdt")
 
 
+def test_cfg5_second_workload_single_layer_model(pkg):
+    # the smaller model's shape (a guess: one LSTM layer at the Parakeet widths), full size
+    w = synth.make_workload(5, pad="nan")
+    check(pkg, w, "label", "small_model")
+    check(pkg, w, "frame", "small_model")
+
+
 def test_repeat_and_permutation_invariance(pkg):
     w = synth.make_workload(2, pad="nan", B=8, T=60, len_lo=20, len_hi=60)
     eng = engine_for(pkg, "parakeet8", w.model, 8, 60)

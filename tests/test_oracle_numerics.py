@@ -153,6 +153,7 @@ def check_invariants(w, r, S):
     (1, {}),
     (2, dict(B=6, T=40, len_lo=15, len_hi=40)),
     (4, dict(B=6, T=60, len_lo=20, len_hi=60)),
+    (5, dict(B=6, T=40, len_lo=15, len_hi=40)),
 ])
 def test_schedules_agree_bit_for_bit(cfg, kw):
     """Frame looping, label looping and the per-utterance decode give identical
