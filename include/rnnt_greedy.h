@@ -20,7 +20,9 @@
  *   - Decode calls only enqueue work on `stream` and return; they never wait
  *     for the device and never read device memory from the host.
  *   - One engine serves one call at a time (shared workspace): calls on the
- *     same engine must be ordered by the caller (same stream or events).
+ *     same engine must be ordered by the caller (same stream or events).  A
+ *     decode launch occupies every compute unit, so calls of different engines
+ *     gain nothing from running on different streams; order them too.
  *   - Return value: RNNT_OK (0) or a negative RNNT_ERR_* code, detected on the
  *     host before anything is queued.  Conditions only the device can see are
  *     reported through rnnt_engine_status().
