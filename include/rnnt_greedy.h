@@ -102,7 +102,7 @@ typedef struct rnnt_stats {
     int32_t n_teams;          /* work-group teams used by the call               */
     int32_t team_size;        /* work-groups per team                            */
     int32_t lookahead;        /* frames examined per utterance per joint step    */
-    int32_t xcd_mismatch;     /* teams whose work-groups were not on one XCD     */
+    int32_t xcd_mismatch;     /* work-groups not on the XCD their weights are on */
     int32_t joint_groups;     /* groups per team that search for labels on their */
                               /* own (1 = the whole team together)               */
     int32_t search_steps;     /* joint steps a label search may take before the  */

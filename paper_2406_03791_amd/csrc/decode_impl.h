@@ -843,7 +843,8 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     extern __shared__ __align__(16) float dyn_lds[];
     Wg w;
     w.tid = threadIdx.x; w.lane = w.tid & 63; w.wave = w.tid >> 6;
-    w.team = blockIdx.x % p.n_teams; w.rank = blockIdx.x / p.n_teams;
+    if (p.spread) { w.rank = blockIdx.x % p.team_size; w.team = blockIdx.x / p.team_size; }
+    else { w.team = blockIdx.x % p.n_teams; w.rank = blockIdx.x / p.n_teams; }
     w.jg = w.rank / p.jteam_size; w.jrank = w.rank - w.jg * p.jteam_size;
     Sync sy;
     sy.epoch = 0; sy.jepoch = 0; sy.polls = 0;
@@ -862,7 +863,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 
     if (w.tid == 0) {
         // XCC_ID hardware register, bits [3:0]
-        p.xcc[blockIdx.x] = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
+        p.xcc[w.rank * p.n_teams + w.team] = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
     }
     // Rows of this team.  Utterances are ranked by length (longest first, ties by index)
     // and dealt to the teams in serpentine order (0..n-1, n-1..0, ...), so that the sums of

@@ -362,6 +362,15 @@ StageDev dev_stage(const PackedStage &ps)
     return s;
 }
 
+// Which work-group is which rank of which team.  Work-groups are dispatched to the 8 XCDs
+// round-robin, and every XCD has its own 4 MB L2.  With rank = index % team_size the ranks
+// r, r + 8, ... of every team share an XCD, so that XCD only ever reads its eighth of the
+// packed weights (3 MB in fp32) and keeps it in its L2: the weight streams of all teams then
+// come from L2 instead of the fabric.  The teams' exchanges cross XCDs, which costs little,
+// because exchange data bypasses the L2s in any case.  Needs a team size that is a multiple
+// of 8; otherwise team = index % n_teams, which keeps a team on as few XCDs as possible.
+bool spread_layout(const TeamConfig &t) { return t.team_size % 8 == 0; }
+
 int check_call(rnnt_engine *e, const float *enc_out, const int32_t *enc_len, int32_t B, int32_t T,
                int32_t max_symbols, int32_t *tokens_out, int32_t *tok_len_out, int32_t cap)
 {
@@ -390,6 +399,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.n_teams = t.n_teams; p.team_size = t.team_size;
     p.groups = t.groups; p.jteam_size = t.jteam_size;
     p.serpentine = 1;
+    p.spread = spread_layout(t) ? 1 : 0;
     p.wt = e->wt;
     p.lookahead = effective_lookahead(e, t, B);
     p.search_steps = effective_search_steps(e, t, B);
@@ -662,14 +672,16 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
         out->barrier_polls += s[kStatPolls];
         out->max_pred_steps = std::max<int64_t>(out->max_pred_steps, s[kStatPred]);
         out->max_joint_steps = std::max<int64_t>(out->max_joint_steps, s[kStatJoint]);
-        // work-group b belongs to team b % n_teams
-        int first = -1, mixed = 0;
+        if (i >= std::min(eng->last_B, t->n_teams)) continue;   // the team had no utterance and left at once
+        // Work-groups whose XCD is not the one their rank's weight slice is kept on: rank r of
+        // every team is meant to sit on the XCD of rank r % 8 of the first team (layouts whose
+        // teams are not multiples of 8 keep a team on one XCD instead).
         for (int r = 0; r < t->team_size; ++r) {
             const int id = xcc[(size_t)r * t->n_teams + i];
-            if (first < 0) first = id;
-            else if (id != first) mixed = 1;
+            const int want = spread_layout(*t) ? xcc[(size_t)(r % 8) * t->n_teams]
+                                               : xcc[(size_t)i];
+            out->xcd_mismatch += id != want;
         }
-        if (i < std::min(eng->last_B, t->n_teams)) out->xcd_mismatch += mixed;
     }
     // phase timers of a library built with -DRNNT_PROFILE, printed on request
     if (const char *dump = std::getenv("RNNT_DUMP_PHASES")) {
