@@ -195,35 +195,44 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         gp_max = std::max(gp_max, gp_of(r));
     }
     for (int r = 0; r < tj; ++r) gj_max = std::max(gj_max, gj_of(r));
-    t.st0.plan = make_stage_plan(H, L * nu_max, e->wt);
-    for (int l = 1; l < L; ++l) t.stl[l].plan = make_stage_plan(H, nu_max, e->wt);
-    t.spred.plan = make_stage_plan(H, gp_max, e->wt);
-    t.sjoint.plan = make_stage_plan(J, gj_max, e->wt);
-
-    // LDS layout
-    int kpad = std::max({t.st0.plan.kpad, t.spred.plan.kpad, t.sjoint.plan.kpad});
-    for (int l = 1; l < L; ++l) kpad = std::max(kpad, t.stl[l].plan.kpad);
-    const int xstride = kpad + 4;
+    // Stage plans and LDS layout.  Stages with more groups than blocks are first planned with K
+    // slices over several passes (best use of the blocks); if the partial sums of such a plan do
+    // not fit the LDS, they fall back to unsliced tasks.
     const int rgp = (rows_max + 3) / 4, rows_pad = rgp * 4;
     const int rgj = kMaxSamples / 4;
-    auto red_need = [&](const StagePlan &pl, int grp, int rg) {
-        return std::min(grp * pl.nks, kBlocksPerWg * pl.slots) * red_task_stride(rg);
-    };
-    int xz = std::max(L * rows_pad * xstride, kMaxSamples * xstride);
-    int red = red_need(t.st0.plan, L * nu_max, rgp);
-    for (int l = 1; l < L; ++l) red = std::max(red, red_need(t.stl[l].plan, nu_max, rgp));
-    red = std::max(red, red_need(t.spred.plan, gp_max, rgp));
-    if (t.sjoint.plan.slots == 1) xz = std::max(xz, red_need(t.sjoint.plan, gj_max, rgj));
-    else red = std::max(red, red_need(t.sjoint.plan, gj_max, rgj));
     int off = 0;
     auto take = [&](int n) { int o = off; off += (n + 3) & ~3; return o; };
-    t.lds_xz = take(xz);
-    t.lds_red = take(red);
-    t.rcap = rows_max;
-    t.lds_c = take(L * 2 * nu_max * rows_max);
-    t.lds_part = take(L * nu_max * rows_max * 4);
-    t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
-    if ((unsigned)off * 4u + (unsigned)kStaticLds > (unsigned)kLdsBytes) return RNNT_ERR_UNSUPPORTED;
+    int xstride = 0;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        const bool single = attempt == 1;
+        t.st0.plan = make_stage_plan(H, L * nu_max, e->wt, single);
+        for (int l = 1; l < L; ++l) t.stl[l].plan = make_stage_plan(H, nu_max, e->wt, single);
+        t.spred.plan = make_stage_plan(H, gp_max, e->wt, single);
+        t.sjoint.plan = make_stage_plan(J, gj_max, e->wt, single);
+        int kpad = std::max({t.st0.plan.kpad, t.spred.plan.kpad, t.sjoint.plan.kpad});
+        for (int l = 1; l < L; ++l) kpad = std::max(kpad, t.stl[l].plan.kpad);
+        xstride = kpad + 4;
+        auto red_need = [&](const StagePlan &pl, int grp, int rg) {
+            return std::min(grp * pl.nks, kBlocksPerWg * pl.slots) * red_task_stride(rg);
+        };
+        int xz = std::max(L * rows_pad * xstride, kMaxSamples * xstride);
+        int red = red_need(t.st0.plan, L * nu_max, rgp);
+        for (int l = 1; l < L; ++l) red = std::max(red, red_need(t.stl[l].plan, nu_max, rgp));
+        red = std::max(red, red_need(t.spred.plan, gp_max, rgp));
+        if (t.sjoint.plan.slots == 1) xz = std::max(xz, red_need(t.sjoint.plan, gj_max, rgj));
+        else red = std::max(red, red_need(t.sjoint.plan, gj_max, rgj));
+        off = 0;
+        t.lds_xz = take(xz);
+        t.lds_red = take(red);
+        t.rcap = rows_max;
+        t.lds_c = take(L * 2 * nu_max * rows_max);
+        t.lds_part = take(L * nu_max * rows_max * 4);
+        t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
+        // room for a joint group's q rows as well (needed by joint groups, see below)
+        const int q_need = groups > 1 ? ((rows_max + groups - 1) / groups) * ((J + 3) & ~3) : 0;
+        if ((unsigned)(off + q_need) * 4u + (unsigned)kStaticLds <= (unsigned)kLdsBytes) break;
+        if (single) return RNNT_ERR_UNSUPPORTED;
+    }
     // q of the team's rows stays in LDS between joint steps when there is room
     t.qstride = (J + 3) & ~3;
     const int q_rows = (rows_max + groups - 1) / groups;   // a joint group keeps its own rows only

@@ -55,10 +55,20 @@ struct StagePlan {
     int64_t rank_stride;   // 16-byte elements of packed weights per rank
 };
 
+// Steps a pass over the blocks costs beyond its loads (the partial sums are written out and the
+// next pass's tasks are set up), in units of one load step: the weight given to the number of
+// passes when the K slicing is chosen.
+constexpr int kPassOverheadSteps = 8;
+
 // groups_max: largest number of groups any rank owns in this stage.
-// Picks the number of K slices that fills the 128 blocks best while keeping the
-// zero padding of K (slices are whole multiples of kStepUnroll steps) below 1/8.
-inline StagePlan make_stage_plan(int K, int groups_max, int wt = kWeightF32)
+// Picks the number of K slices per group: groups_max * nks tasks run in passes ("slots") of
+// kBlocksPerWg tasks, a pass takes as long as its nsteps loads, so the choice minimises
+// slots * (nsteps + overhead) while the zero padding of K (slices are whole multiples of
+// kStepUnroll steps) stays below 1/8.  Ties go to fewer slices (fewer partial sums to add).
+// single_pass_only restricts stages with more groups than blocks to unsliced tasks, which
+// needs the least LDS for partial sums (the engine falls back to it when LDS is short).
+inline StagePlan make_stage_plan(int K, int groups_max, int wt = kWeightF32,
+                                 bool single_pass_only = false)
 {
     StagePlan p{};
     p.K = K;
@@ -69,22 +79,20 @@ inline StagePlan make_stage_plan(int K, int groups_max, int wt = kWeightF32)
         int n = (k4 + nks - 1) / nks;
         return ((n + kStepUnroll - 1) / kStepUnroll) * kStepUnroll;
     };
-    if (groups_max <= kBlocksPerWg) {
-        int cap = kBlocksPerWg / groups_max;
-        const int cap_k = k4 / kStepUnroll > 0 ? k4 / kStepUnroll : 1;
-        if (cap > cap_k) cap = cap_k;
-        if (cap < 1) cap = 1;
-        int best = 1;
-        for (int nks = cap; nks >= 1; --nks) {
-            const int kpad4 = nks * steps_for(nks);
-            if (kpad4 * 8 <= k4 * 9 || nks == 1) { best = nks; break; }
-        }
-        p.nks = best;
-        p.slots = 1;
-    } else {
-        p.nks = 1;
-        p.slots = (groups_max + kBlocksPerWg - 1) / kBlocksPerWg;
+    const int cap_k = k4 / kStepUnroll > 0 ? k4 / kStepUnroll : 1;
+    int best = 1;
+    long best_cost = -1;
+    for (int nks = 1; nks <= cap_k; ++nks) {
+        const int tasks = groups_max * nks;
+        if (single_pass_only && nks > 1 && tasks > kBlocksPerWg) break;
+        const int kpad4 = nks * steps_for(nks);
+        if (nks > 1 && kpad4 * 8 > k4 * 9) continue;
+        const int slots = (tasks + kBlocksPerWg - 1) / kBlocksPerWg;
+        const long cost = (long)slots * (steps_for(nks) + kPassOverheadSteps);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = nks; }
     }
+    p.nks = best;
+    p.slots = (groups_max * best + kBlocksPerWg - 1) / kBlocksPerWg;
     p.nsteps = steps_for(p.nks);
     p.kpad = p.nks * p.nsteps * p.kper;
     p.rank_stride = (int64_t)p.slots * kWaves * p.nsteps * 64;

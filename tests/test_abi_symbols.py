@@ -49,8 +49,9 @@ def test_status_strings_and_null_checks_need_no_gpu():
 
 def test_stage_planner_covers_k_and_fits_the_blocks():
     """Host logic of the weight packer, re-stated: every (groups, K) choice must
-    cover K with nks slices of nsteps 16-byte loads (4 fp32 or 8 bf16 weights each) and fit
-    the blocks of a slot."""
+    cover K with nks slices of nsteps 16-byte loads (4 fp32, 8 bf16 or 16 e4m3 weights each),
+    fill its passes over the blocks without an empty one, keep the zero padding small, and
+    never cost more passes-times-steps than the unsliced fallback."""
     import subprocess
     import tempfile
     src = r'''
@@ -65,7 +66,13 @@ int main() {
       if (p.kper != (4 << wt)) bad++;
       if (p.kpad < K || p.kpad != p.nks * p.nsteps * p.kper || p.nsteps % rnnt::kStepUnroll) bad++;
       if (g * p.nks > rnnt::kBlocksPerWg * p.slots) bad++;
-      if (p.slots > 1 && p.nks != 1) bad++;
+      if (g * p.nks <= rnnt::kBlocksPerWg * (p.slots - 1)) bad++;          // no empty pass
+      if (p.nks > 1 && (p.kpad - K) * 8 > K + 8 * p.kper * rnnt::kStepUnroll) bad++;   // padding stays small
+      // the fallback for a short LDS: more groups than blocks means unsliced tasks
+      rnnt::StagePlan q = rnnt::make_stage_plan(K, g, wt, true);
+      if (q.kpad < K || g * q.nks > rnnt::kBlocksPerWg * q.slots) bad++;
+      if (q.slots > 1 && q.nks != 1) bad++;
+      if (q.slots * (q.nsteps + rnnt::kPassOverheadSteps) < p.slots * (p.nsteps + rnnt::kPassOverheadSteps)) bad++;
     }
   std::printf("%d\n", bad);
   return bad != 0;
