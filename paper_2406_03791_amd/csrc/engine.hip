@@ -293,28 +293,28 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     return RNNT_OK;
 }
 
-// Default team layouts, chosen from measurements on MI355X.
+// Default team layouts, chosen from measurements on MI355X (all with the rank-to-XCD mapping
+// of spread_layout, so the size of a team does not change where its weights are read from).
 //   Algorithm 1: one utterance per team while the teams keep at least 8 work-groups (no
 //   lock-step waiting between utterances, and a prediction step per label of one utterance
-//   only): 4, 8, 16 or 32 teams; beyond 32 utterances the teams take several rows each.
-//   Up to 8 utterances (label looping) or 4 (Algorithm 1) teams of 64 work-groups on two
-//   XCDs are faster than idle XCDs, although their exchange crosses the fabric.
+//   only): 8, 16 or 32 teams; beyond 32 utterances the teams take several rows each.
+//   Label looping: 8 teams of 32 up to 16 utterances, 16 teams of 16 beyond; two joint groups
+//   per team from 9 utterances on.  (Teams of 64 were only faster while a team had to sit on
+//   its own XCDs.)
 int default_layouts(rnnt_engine *e)
 {
     const int max_B = e->max_B;
-    int nf = max_B <= 4 ? 4 : (max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32));
+    int nf = max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32);
     while (nf > 1 && e->n_wg % nf != 0) nf /= 2;
     while ((max_B + nf - 1) / nf > kMaxRows) nf *= 2;
     int rc = plan_and_pack(e, e->frame_cfg, nf, 1);
     if (rc) return rc;
-    int nl = max_B <= 8 ? 4 : (max_B <= 48 ? 8 : 16);
+    int nl = max_B <= 16 ? 8 : 16;
     while (nl > 1 && e->n_wg % nl != 0) nl /= 2;
     while ((max_B + nl - 1) / nl > kMaxRows) nl *= 2;
     const int rows = (max_B + nl - 1) / nl;
-    const int ts = e->n_wg / nl, min_group = max_B > 64 ? 4 : 8;
-    int groups = 1;
-    while (groups * 2 <= rows && ts % (groups * 2) == 0 && ts / (groups * 2) >= min_group)
-        groups *= 2;
+    const int ts = e->n_wg / nl;
+    int groups = (max_B > 8 && rows >= 2 && ts % 2 == 0 && ts / 2 >= 8) ? 2 : 1;
     rc = plan_and_pack(e, e->label_cfg, nl, groups);
     while (rc == RNNT_ERR_UNSUPPORTED && groups > 1) {
         groups /= 2;
@@ -339,10 +339,10 @@ int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
     const int rows = std::max(1, (rows_team + t.groups - 1) / t.groups);
     int la = e->lookahead > 0 ? e->lookahead : 8;
     if (e->lookahead == 0 && &t == &e->frame_cfg) la = std::min(8, std::max(1, 16 / rows));
-    // label looping with one utterance per joint group on the 64-work-group teams of the small
-    // batches: a joint step is cheap next to its fixed cost, 16 frames per step measured 4-9 %
-    // faster than 8 (no gain on the smaller teams of larger batches)
-    if (e->lookahead == 0 && &t != &e->frame_cfg && rows == 1 && t.team_size >= 64) la = 16;
+    // label looping of one or two utterances: most of the device idles, a joint step is cheap
+    // next to its fixed cost, and 16 frames per step measured 2-3 % faster than 8 (slower from
+    // four utterances on)
+    if (e->lookahead == 0 && &t != &e->frame_cfg && B <= 2) la = 16;
     if (la * rows > kMaxSamples) la = std::max(1, kMaxSamples / rows);
     return la;
 }
