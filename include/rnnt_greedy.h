@@ -228,9 +228,9 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out);
  * chosen from max_B).  joint_groups (needs n_teams > 0): joint groups per team
  * in the label-looping calls, 0 or 1 = none; Algorithm 1 always runs plain
  * teams.  lookahead: frames examined per utterance per joint step (0 = default:
- * 8 in the label-looping calls, 16 where a joint group of a 64-work-group team
- * holds one utterance (batches up to 8); up to 8 with at most 16 samples per
- * step in Algorithm 1; 1 = one frame per step).  search_steps: joint steps a search of
+ * 8 in the label-looping calls, 16 when a call has one or two utterances; up
+ * to 8 with at most 16 samples per step in Algorithm 1; 1 = one frame per
+ * step).  search_steps: joint steps a search of
  * the label-looping calls may take before the team runs its next prediction
  * step for the rows that have their label (0 = chosen per call from the rows
  * per team, -1 = no limit).  None of the knobs changes a token.

@@ -58,7 +58,10 @@ struct StagePlan {
 // Steps a pass over the blocks costs beyond its loads (the partial sums are written out and the
 // next pass's tasks are set up), in units of one load step: the weight given to the number of
 // passes when the K slicing is chosen.
-constexpr int kPassOverheadSteps = 8;
+#ifndef RNNT_PASS_OVERHEAD
+#define RNNT_PASS_OVERHEAD 8
+#endif
+constexpr int kPassOverheadSteps = RNNT_PASS_OVERHEAD;
 
 // groups_max: largest number of groups any rank owns in this stage.
 // Picks the number of K slices per group: groups_max * nks tasks run in passes ("slots") of
