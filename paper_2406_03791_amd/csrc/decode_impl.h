@@ -203,16 +203,18 @@ __device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const Sta
                                              int rank, int n_tasks, int slot)
 {
     constexpr int kAhead = AH;
+    // a wave's passes ("slots") follow each other in memory, so its whole stage is one
+    // contiguous run of slots * nsteps loads per lane
     ws.task = slot * kBlocksPerWg + w.wave * 16 + (w.lane >> 2);
     ws.live = ws.task < n_tasks;
     ws.wp = sd.w + (long long)rank * sd.rank_stride +
-            ((long long)(slot * kWaves + w.wave) * sd.nsteps) * 64 + w.lane;
+            ((long long)(w.wave * sd.slots + slot) * sd.nsteps) * 64 + w.lane;
 #pragma unroll
     for (int a = 0; a < kAhead; ++a)
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
             const int step = a * kStepUnroll + u;
-            ws.q[a][u] = (ws.live && step < sd.nsteps) ? load_weight<NT>(ws.wp + step * 64)
+            ws.q[a][u] = (ws.live && step < sd.nsteps * sd.slots) ? load_weight<NT>(ws.wp + step * 64)
                                                        : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 }
@@ -234,11 +236,18 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
                                           bool red_aliases_x)
 {
     constexpr int kAhead = AH;
+    // two batches in flight: the hand-over of the batches at a pass boundary below is written
+    // for that depth (deeper windows measured slower in every layout)
+    static_assert(AH == 2, "run_stage: the pass boundary assumes two batches in flight");
     const int r4 = w.lane & 3;
+    // The loads run through the passes without a break: a lane that has a task in the first
+    // pass keeps loading to the end of the stage (a pass in which it has none reads the zero
+    // padding of the packed weights), so the pipeline is never empty between passes.
+    const bool stream_live = ws.live;
+    int left = sd.slots * sd.nsteps;                 // loads from the start of this pass to the end
     for (int slot = 0; slot < sd.slots; ++slot) {
-        if (slot > 0) stream_begin(ws, sd, w, rank, n_tasks, slot);
         const int task = ws.task;
-        const bool live = ws.live;
+        const bool live = task < n_tasks;
         const int g = live ? task / sd.nks : 0;
         const int ks = live ? task - g * sd.nks : 0;
         constexpr int KPER = WT == kWeightFp8 ? 16 : (WT == kWeightBf16 ? 8 : 4);
@@ -299,7 +308,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
                             __builtin_amdgcn_sched_barrier(0);
                         }
                     }
-                    if (live && i + kAhead * kStepUnroll < sd.nsteps) {
+                    if (stream_live && i + kAhead * kStepUnroll < left) {
 #pragma unroll
                         for (int u = 0; u < kStepUnroll; ++u)
                             ws.q[a][u] = load_weight<NT>(ws.wp + (i + kAhead * kStepUnroll + u) * 64);
@@ -314,6 +323,18 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
             for (int rg = 0; rg < RG; ++rg) {
                 float4 o = make_float4(acc[rg][0], acc[rg][1], acc[rg][2], acc[rg][3]);
                 *reinterpret_cast<float4 *>(red + task * red_task_stride(RG) + (rg * 4 + r4) * 4) = o;
+            }
+        }
+        // next pass: same blocks, next kBlocksPerWg tasks.  A batch holds the steps it was
+        // refilled with two batches earlier, so when a pass ends on an odd batch the two
+        // batches change roles.
+        ws.task = task + kBlocksPerWg;
+        ws.wp += sd.nsteps * 64;
+        left -= sd.nsteps;
+        if ((sd.nsteps & kStepUnroll) && slot + 1 < sd.slots) {
+#pragma unroll
+            for (int u = 0; u < kStepUnroll; ++u) {
+                const float4 t_ = ws.q[0][u]; ws.q[0][u] = ws.q[1][u]; ws.q[1][u] = t_;
             }
         }
     }

@@ -133,7 +133,7 @@ int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups
                  const std::function<const float *(int, int, int)> &row_of)
 {
     const StagePlan &pl = ps.plan;
-    // 16 bytes per (rank, slot, wave, step, lane): 4 floats, 8 bf16 codes or 16 e4m3 codes
+    // 16 bytes per (rank, wave, slot, step, lane): 4 floats, 8 bf16 codes or 16 e4m3 codes
     std::vector<uint32_t> host((size_t)ts * pl.rank_stride * 4, 0u);
     for (int rank = 0; rank < ts; ++rank) {
         const int ntask = ngroups(rank) * pl.nks;
@@ -148,7 +148,7 @@ int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups
                     for (int step = 0; step < pl.nsteps; ++step) {
                         uint32_t *dst = host.data() +
                                         ((size_t)rank * pl.rank_stride +
-                                         ((size_t)(slot * kWaves + wave) * pl.nsteps + step) * 64 + lane) * 4;
+                                         ((size_t)(wave * pl.slots + slot) * pl.nsteps + step) * 64 + lane) * 4;
                         const int k0 = (ks * pl.nsteps + step) * pl.kper;
                         if (pl.kper == 4) {
                             for (int c = 0; c < 4; ++c)
