@@ -12,7 +12,7 @@ enum Variant { kFrameLooping = 0, kLabelLooping = 1, kTdtLabelLooping = 2 };
 
 // Packed weights of one dense stage on the device.
 struct StageDev {
-    const float4 *w;       // [rank][slot][wave][step][lane], 16 bytes each: 4 fp32 or 8 bf16 weights
+    const float4 *w;       // [rank][wave][slot][step][lane], 16 bytes each: 4 fp32, 8 bf16 or 16 e4m3 weights
     int nks, nsteps, slots, kpad;
     long long rank_stride; // float4 elements per rank
 };
