@@ -978,6 +978,27 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         bool need_pred = true;     // nothing computed yet for (last_label, hidden)
         int win0 = 0, win_n = 0;   // frames [win0, win0 + win_n) have results for the current g
         for (int time_idx = 0; ok && time_idx < max_out_len; ++time_idx) {
+            // Frames the window already covers and on which every row produced a blank change
+            // nothing but the frame index: they are passed over in one go (each would run the
+            // inner loop once, find all blank and leave).  Every thread reads the same results
+            // and takes the same decision.
+            if (!need_pred && time_idx > win0 && time_idx < win0 + win_n) {
+                int f = time_idx;
+                for (; f < win0 + win_n; ++f) {
+                    bool all_blank = true;
+                    for (int r = 0; r < R; ++r)
+                        if (f < c.len[r] && c.s_k[(f - win0) * R + r] != p.blank) all_blank = false;
+                    if (!all_blank) break;
+                }
+                if (f > time_idx) {
+                    // rows whose frames ran out on the way are complete
+                    if (w.rank == 0 && w.tid < R && c.len[w.tid] >= time_idx && c.len[w.tid] < f &&
+                        c.len[w.tid] > 0)
+                        finish_row(p, w.tid);
+                    time_idx = f;
+                    if (time_idx >= max_out_len) break;
+                }
+            }
             if (w.tid < R) {
                 c.mask[w.tid] = time_idx >= c.len[w.tid];   // blank_mask
                 // a row whose frames have run out is complete although the team goes on
