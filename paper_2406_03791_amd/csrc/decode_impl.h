@@ -239,6 +239,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
     // two batches in flight: the hand-over of the batches at a pass boundary below is written
     // for that depth (deeper windows measured slower in every layout)
     static_assert(AH == 2, "run_stage: the pass boundary assumes two batches in flight");
+    static_assert(kMaxSamples <= 64, "the samples of a joint step are set up by one wave");
     const int r4 = w.lane & 3;
     // The loads run through the passes without a break: a lane that has a task in the first
     // pass keeps loading to the end of the stage (a pass in which it has none reads the zero
@@ -1099,6 +1100,9 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                         valid = c.searching[row] && fr < c.len[row];
                     }
                     c.s_row[s] = row; c.s_frame[s] = fr; c.s_valid[s] = valid;
+                    // statistics: the samples are all in the first wave, thread 0 keeps the count
+                    const unsigned long long vmask = __ballot(valid != 0);
+                    if (w.tid == 0) n_samples += __popcll(vmask);
                 }
                 if (w.tid == 0) c.ns = rj * la;
                 __syncthreads();
@@ -1131,7 +1135,6 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 __syncthreads();
                 any_searching = false;
                 for (int j = 0; j < rj; ++j) any_searching = any_searching || c.searching[g + j * G];
-                for (int s = 0; s < rj * la; ++s) n_samples += c.s_valid[s];
                 __syncthreads();
             }
             if (!ok) break;
