@@ -44,7 +44,7 @@ def _np_real(real: str):
 class _DecodeIO(C.Structure):
     _fields_ = [
         ("B", C.c_int32), ("T", C.c_int32), ("S", C.c_int32), ("cap", C.c_int32),
-        ("rec_cap", C.c_int32), ("eval_masked", C.c_int32),
+        ("rec_cap", C.c_int32), ("skip_masked", C.c_int32),
         ("n_threads", C.c_int32), ("status", C.c_int32),
         ("x", C.c_void_p), ("len", C.c_void_p),
         ("tokens", C.c_void_p), ("frames", C.c_void_p), ("scores", C.c_void_p),
@@ -191,7 +191,10 @@ _SCHEDULES = {"frame": "orc_decode_frame_looping", "label": "orc_decode_label_lo
 
 def decode(net: Net, enc_out: np.ndarray, enc_len: np.ndarray, max_symbols: int,
            schedule: str = "seq", *, cap: Optional[int] = None, record: bool = False,
-           n_threads: int = 1, eval_masked: bool = False) -> Decoded:
+           n_threads: int = 1, skip_masked: bool = False) -> Decoded:
+    """schedule 'frame' is Algorithm 1 as written: both networks run for every row at every
+    inner step.  skip_masked=True passes over rows that are already masked (same outputs,
+    pinned by tests; only for timing large batches)."""
     x = np.ascontiguousarray(enc_out, dtype=net.dtype)
     B, T = int(x.shape[0]), int(x.shape[1])
     assert x.shape[2] == net.x_size
@@ -208,7 +211,7 @@ def decode(net: Net, enc_out: np.ndarray, enc_len: np.ndarray, max_symbols: int,
     tok_len = i32(B)
     io = _DecodeIO()
     io.B, io.T, io.S, io.cap, io.rec_cap = B, T, S, cap, rec_cap
-    io.eval_masked, io.n_threads = int(eval_masked), int(n_threads)
+    io.skip_masked, io.n_threads = int(skip_masked), int(n_threads)
     io.x, io.len = _ptr(x), _ptr(ln)
     io.tokens, io.frames, io.scores = _ptr(tokens), _ptr(frames), _ptr(scores)
     io.durs, io.tok_len = _ptr(durs), _ptr(tok_len)

@@ -8,7 +8,10 @@
  *
  * What it follows (paper = "Speed of Light Exact Greedy Decoding for RNN-T
  * Speech Recognition Models on GPU"):
- *   - decode_frame_looping : Algorithm 1, statement by statement.
+ *   - decode_frame_looping : Algorithm 1 in its own order: lock-step frames, an
+ *                            inner loop of at most max_symbols batched steps,
+ *                            both networks run for the whole batch at every
+ *                            step, sticky blank mask, masked state update.
  *   - decode_label_looping : the label-looping schedule described at the end of
  *                            the Related Work section (batch elements advance
  *                            their own frame index); with a duration head it is
@@ -23,8 +26,10 @@
  * The paper leaves prediction() and joint() abstract.  Here prediction() is an
  * embedding plus L stacked LSTM cells (standard equations) whose top hidden
  * vector is g, and joint(f, g) = W_out relu(W_enc f + b_enc + W_pred g + b_pred)
- * + b_out.  No log-softmax is applied: argmax is invariant under it and the
- * saved score v is the raw maximum logit.
+ * + b_out.  The argmax is taken on the logits (a log-softmax would not change
+ * it); each emission keeps the raw maximum logit (scores) and, when asked
+ * for, its log-softmax value over the token columns (logps), which is the
+ * score Algorithm 1 saves.
  *
  * Arithmetic: every dot product is accumulated one term at a time in index
  * order, in the type REAL (float by default, double with -DREAL=double; build
@@ -34,8 +39,10 @@
  * each output still sums its terms in the same order.
  *
  * The encoder-side term W_enc f + b_enc depends only on (utterance, frame), so
- * it is computed the first time a frame is used and kept; re-computing it at
- * every inner step would give the same bits.
+ * the batched schedules compute it the first time a frame is used and keep it;
+ * re-computing it at every inner step gives the same bits (the per-utterance
+ * definition does recompute it per frame, and the schedules are tested to agree
+ * with it bit for bit).
  *
  * Pins (tests/test_oracle_*.py): hand-traced lattices, brute force over all
  * tiny argmax tables against a pure-Python lattice walk, all-blank and
@@ -295,7 +302,10 @@ int orc_real_size(void) { return (int)sizeof(real); }
 /* ------------------------------------------------------------------------ */
 typedef struct {
     int32_t B, T, S, cap, rec_cap;
-    int32_t eval_masked;   /* frame looping: also evaluate rows already masked */
+    int32_t skip_masked;   /* frame looping: 0 = every row runs both networks at  */
+                           /* every inner step, as Algorithm 1 does; 1 = rows that */
+                           /* are already masked are passed over (a shortcut whose */
+                           /* equality with the literal form is pinned by tests)   */
     int32_t n_threads;     /* sequential decode: utterances in parallel        */
     int32_t status;        /* out: ORC_STATUS_* bits                           */
     const real *x;         /* [B][T][x_size]                                   */
@@ -465,38 +475,45 @@ int orc_decode_frame_looping(const net_t *net, decode_io *io)
         io->stat_outer++;
         int not_blank = 1;
         int symbols_added = 0;
+        /* rows whose frames have run out take no further part in this frame  */
         for (int b = 0; b < B; ++b) blank_mask[b] = (time_idx >= out_len[b]);
         while (not_blank && symbols_added < io->S) {
             io->stat_inner++; io->stat_pred++;
+            /* Both networks run for the whole batch, masked rows included     */
+            /* (their frame may be padding; whatever they produce is dropped   */
+            /* by the masked updates below).                                   */
             for (int b = 0; b < B; ++b) {
                 was_masked[b] = blank_mask[b];
-                if (blank_mask[b] && !io->eval_masked) {
-                    /* k and hidden_prime of a masked row are discarded below. */
+                if (blank_mask[b] && io->skip_masked) {
                     k[b] = blank_index; v[b] = 0; mg[b] = 0;
                     continue;
                 }
-                /* g, hidden_prime = prediction(last_label, hidden)            */
+                /* prediction network on (last label, state): output g and the */
+                /* candidate state                                             */
                 net->pred(net, last_label[b], hidden + (size_t)b * SS,
                           hidden_prime + (size_t)b * SS, g + (size_t)b * GS);
-                /* logp = joint(f, g) with f = x[:, time_idx]                  */
+                /* joint network on this frame and g, then the best label and  */
+                /* its score                                                   */
                 net->joint(net, cache_get(&fc, b, time_idx), g + (size_t)b * GS, logp);
-                /* k, v = logp.max()                                           */
                 k[b] = argmax_margin(logp, 0, net->V1, &v[b], &mg[b]);
                 if (io->logps) lp[b] = log_prob_of_top(logp, net->V1, v[b]);
                 io->stat_pred_rows++; io->stat_joint_rows++;
             }
             for (int b = 0; b < B; ++b) {
                 if (!was_masked[b]) record(io, b, time_idx, k[b], v[b], mg[b], 0, 0, &status);
-                /* blank_mask = blank_mask || (k == blank_index)               */
+                /* a row that produced a blank is masked for the rest of the   */
+                /* frame; the mask is sticky                                   */
                 blank_mask[b] = blank_mask[b] || (k[b] == blank_index);
                 if (!blank_mask[b]) {
-                    /* save k and v; masked select of last_label and hidden    */
+                    /* unmasked rows keep their label and score, and take the  */
+                    /* label and the candidate state as their new state        */
                     emit(io, b, k[b], time_idx, v[b], lp[b], 0, &status);
                     last_label[b] = k[b];
                     memcpy(hidden + (size_t)b * SS, hidden_prime + (size_t)b * SS,
                            sizeof(real) * (size_t)SS);
                 }
             }
+            /* the inner loop goes on while some row is unmasked               */
             not_blank = 0;
             for (int b = 0; b < B; ++b) if (!blank_mask[b]) not_blank = 1;
             symbols_added += 1;

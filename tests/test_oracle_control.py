@@ -56,6 +56,17 @@ def test_hand_traced_cases(case):
                 assert r.durs[b].tolist() == case["durs"][b], (sched, b)
             assert len(r.records.k[b]) == case["joint_evals"][b], (sched, b)
         assert r.status == 0
+    if not dur:
+        # Algorithm 1 as written (every row evaluated at every inner step) and the form that
+        # passes over masked rows give the same outputs and the same records
+        lit = oracle.decode(net, net.frames(), np.array(case["len"]), S, "frame", record=True)
+        skp = oracle.decode(net, net.frames(), np.array(case["len"]), S, "frame", record=True,
+                            skip_masked=True)
+        assert np.array_equal(lit.raw_tokens, skp.raw_tokens)
+        for b in range(B):
+            assert np.array_equal(lit.frames[b], skp.frames[b])
+            assert np.array_equal(lit.records.k[b], skp.records.k[b])
+        assert lit.stats["pred_rows"] == lit.stats["inner"] * B >= skp.stats["pred_rows"]
 
 
 def lattice_walk(choice, dur_choice, durations, length, S, blank):

@@ -168,15 +168,26 @@ def test_schedules_agree_bit_for_bit(cfg, kw):
 
 
 def test_frame_looping_masked_rows_do_not_matter():
-    """Algorithm 1 also runs the networks on rows that are already masked;
-    their results are discarded, so evaluating them changes nothing."""
-    w = synth.make_workload(1, pad="normal", T=60, len_lo=20, len_hi=60)
-    net = oracle.LstmNet(w.model)
-    a = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "frame", record=True)
-    b = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "frame", record=True,
-                      eval_masked=True)
-    assert_same(a, b)
-    assert b.stats["pred_rows"] == b.stats["inner"] * w.B > a.stats["pred_rows"]
+    """Algorithm 1 runs both networks for the whole batch at every inner step, rows that are
+    already masked included (the oracle's default); their results are discarded, so passing
+    over them (skip_masked, used where a large batch has to be timed) changes nothing: same
+    tokens, frames, scores bit for bit and the same records, on the small model, on a cut of
+    the two-layer Parakeet-shaped model and with padding frames that hold NaN."""
+    for cfg, kw in [(1, dict(pad="normal", T=60, len_lo=20, len_hi=60)),
+                    (2, dict(pad="nan", B=5, T=40, len_lo=12, len_hi=40)),
+                    (1, dict(pad="nan", T=30, len_lo=0, len_hi=30))]:
+        w = synth.make_workload(cfg, **kw)
+        net = oracle.LstmNet(w.model)
+        a = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "frame", record=True)
+        b = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "frame", record=True,
+                          skip_masked=True)
+        assert_same(a, b)
+        for i in range(w.B):
+            assert np.array_equal(a.records.k[i], b.records.k[i])
+            assert np.array_equal(a.records.t[i], b.records.t[i])
+        # the literal form really evaluates every row at every inner step
+        assert a.stats["pred_rows"] == a.stats["inner"] * w.B > b.stats["pred_rows"]
+        assert a.stats["inner"] == b.stats["inner"]
 
 
 def test_batch_row_equals_single_utterance_and_permutation():
@@ -290,6 +301,74 @@ def test_follow_reports_departures():
     fr = r.frames[b].copy()
     fr[-1] = w.enc_len[b] + 3
     assert oracle.follow(net, w.enc_out[b], w.enc_len[b], w.max_symbols, r.tokens[b], fr).departures == -1
+
+
+def test_follow_reports_tdt_departures():
+    """Follow mode on a token-and-duration model: the oracle's own hypothesis has no departure;
+    an altered token is reported with the oracle's label and the right gap; an altered duration
+    is reported as column V1 + index with the gap between the two duration logits; a duration
+    value the model does not have makes the hypothesis impossible."""
+    w = synth.make_workload(4, pad="nan", B=4, T=60, len_lo=30, len_hi=60)
+    net = oracle.LstmNet(w.model)
+    V1, durations = w.model.dims.V1, list(w.model.dims.durations)
+    r = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "seq", record=True)
+    b = int(np.argmax(r.tok_len))
+    n = int(r.tok_len[b])
+    assert n >= 4
+    args = (net, w.enc_out[b], int(w.enc_len[b]), w.max_symbols)
+    ok = oracle.follow(*args, r.tokens[b], r.frames[b], r.durs[b])
+    assert ok.departures == 0 and ok.worst_gap == 0.0
+
+    def logits_at(u):
+        """Logits of the evaluation that emitted label u, recomputed through the sub-network
+        calls (prediction steps along the first u labels, joint at the label's frame)."""
+        state = np.zeros(net.state_size, dtype=np.float32)
+        g, cand = net.pred(net.blank, state)
+        for i in range(u):
+            g, cand = net.pred(int(r.tokens[b][i]), cand)
+        return net.joint(net.prep(w.enc_out[b, int(r.frames[b][u])]), g)
+
+    # 1. a token altered: first departure at that label, the oracle's label as `want`
+    u = 1
+    lg = logits_at(u)
+    assert int(np.argmax(lg[:V1])) == int(r.tokens[b][u])
+    toks = r.tokens[b].copy()
+    toks[u] = (int(toks[u]) + 3) % (V1 - 1)
+    bad = oracle.follow(*args, toks, r.frames[b], r.durs[b])
+    assert bad.departures >= 1
+    first = bad.where[0]
+    assert (first["u"], first["t"]) == (u, int(r.frames[b][u]))
+    assert first["want"] == int(r.tokens[b][u]) and first["got"] == int(toks[u])
+    assert abs(first["gap"] - float(lg[:V1].max() - lg[toks[u]])) < 1e-6
+    assert bad.worst_gap >= first["gap"] > 0
+
+    # 2. a duration altered on the last label (no later label's frame index contradicts the
+    # new landing frame; the blanks after it may still give further departures)
+    u = n - 1
+    lg = logits_at(u)
+    di = int(np.argmax(lg[V1:]))
+    assert durations[di] == int(r.durs[b][u])
+    gi = (di + 1) % len(durations)
+    durs = r.durs[b].copy()
+    durs[u] = durations[gi]
+    bad = oracle.follow(*args, r.tokens[b], r.frames[b], durs)
+    assert bad.departures >= 1
+    rep = bad.where[0]
+    assert (rep["u"], rep["want"], rep["got"]) == (u, V1 + di, V1 + gi)
+    assert abs(rep["gap"] - float(lg[V1 + di] - lg[V1 + gi])) < 1e-6
+    assert bad.worst_gap >= rep["gap"] > 0
+
+    # 3. a duration the model does not have: no walk produces it
+    durs = r.durs[b].copy()
+    durs[0] = 7
+    assert oracle.follow(*args, r.tokens[b], r.frames[b], durs).departures == -1
+    # 4. a duration altered in the middle moves the walk off the hypothesis' later frames
+    # unless the frames follow: a skipped frame index makes the rest unreachable
+    if n >= 3:
+        durs = r.durs[b].copy()
+        durs[0] = durations[-1] + 0 if int(durs[0]) != durations[-1] else durations[0]
+        res = oracle.follow(*args, r.tokens[b], r.frames[b], durs)
+        assert res.departures != 0
 
 
 def test_stored_oracle_tokens_are_reproduced():
