@@ -48,11 +48,14 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     // kernels are instantiated per loop nest, per row-group count of the prediction stages
     // and per row-group count of the joint step
     const int rows = (p.B + p.n_teams - 1) / p.n_teams;
-    const int rg = (rows + 3) / 4;
+    const int rg = pred_row_groups(rows);
     const int rows_j = (rows + p.groups - 1) / p.groups;
     const int samples = rows_j * p.lookahead;
-    const int rgj = samples <= 4 ? 1 : (samples <= 8 ? 2 : (samples <= 16 ? 4 : 8));
+    const int rgj = joint_row_groups(samples);
     const int rgi = rg <= 1 ? 0 : (rg <= 2 ? 1 : 2);
+    // the LDS layout of the call was planned for rg_planned / kMaxSamples row groups: an instance
+    // that assumes more would write outside its regions
+    if (rows > kMaxRows || rg > p.rg_planned || samples > kMaxSamples) return hipErrorInvalidValue;
     typedef hipError_t (*Launch)(const DecodeParams &, int, hipStream_t);
     static const Launch table[3][2][3] = {
         {{launch_decode_f1, launch_decode_f2, launch_decode_f4},

@@ -572,9 +572,15 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
 }
 
 // An argmax partial as exchanged between the ranks of a team: logit bits, a 16-bit tag (the
-// joint step it belongs to) and a 16-bit column index.  Readers poll a slot until its tag is
-// the current step's, so the exchange needs no separate barrier; a slot is rewritten every
-// second step (two parities), so a stale tag can never equal the current one.
+// joint step it belongs to, modulo 65536) and a 16-bit column index.  Readers poll a slot until
+// its tag is the current step's, so the exchange needs no separate barrier.  Why a stale tag
+// can never equal the current one, however many joint steps a call takes: the slots of a step
+// are chosen by the parity of the step number, every rank rewrites all slots s < ns of that
+// parity at every such step (valid sample or not), readers read only slots s < ns, and ns never
+// grows during a call (label looping keeps it constant, Algorithm 1 shrinks it on the last
+// frames only).  So what a reader can find in a slot is the current step's word or the one
+// written two steps earlier, whose tag differs by 2 modulo 65536; the value 0 the reset kernel
+// leaves is only ever found before step 1 or 2 has been written, and those tags are 1 and 2.
 __device__ __forceinline__ unsigned long long pack_cand(float v, int idx, unsigned tag)
 {
     return ((unsigned long long)__float_as_uint(v) << 32) | ((tag & 0xffffu) << 16) |
@@ -947,10 +953,15 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         const int r = rem / nu, u = rem - r * nu;
         xstore(h_slot(p, w.team, 0, layer, r) + u0 + u, 0.f);
     }
-    // output fill: every rank clears a share of its team's rows
-    for (int r = 0; r < R; ++r) {
+    // Output fill.  A row's outputs are only ever written by one work-group, the one that
+    // will emit the row's labels (first rank of the row's joint group): the work-groups of a
+    // team sit on different XCDs, whose L2s are not coherent with each other for plain stores,
+    // so a fill written by another work-group could reach memory after the labels it was
+    // meant to precede.  Within a work-group the barrier below orders fill and labels.
+    for (int r = w.jg; r < R; r += p.groups) {
+        if (w.jrank != 0) break;
         const long long o = (long long)c.b[r] * p.cap;
-        for (int i = w.rank * kThreads + w.tid; i < p.cap; i += p.team_size * kThreads) {
+        for (int i = w.tid; i < p.cap; i += kThreads) {
             p.tokens[o + i] = -1;
             if (p.frames) p.frames[o + i] = -1;
             if (p.logits) p.logits[o + i] = 0.f;
@@ -958,13 +969,13 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             if (p.durs) p.durs[o + i] = -1;
         }
     }
-    if (!team_barrier(p, w, sy)) return;
+    // a failed first barrier skips the loops and reaches the epilogue, which reports it
+    bool ok = team_barrier(p, w, sy);
     // empty utterances are complete from the start
-    if (w.jrank == 0 && w.tid < R && w.tid % p.groups == w.jg && !c.active[w.tid]) finish_row(p, w.tid);
+    if (ok && w.jrank == 0 && w.tid < R && w.tid % p.groups == w.jg && !c.active[w.tid]) finish_row(p, w.tid);
 
     long long n_pred = 0, n_joint = 0, n_samples = 0;
     int parity = 0;
-    bool ok = true;
 
     if constexpr (VARIANT == kFrameLooping) {
         // Algorithm 1 on this team's rows.  A joint step also evaluates the next frames of

@@ -38,6 +38,7 @@ struct DecodeParams {
     // dynamic LDS layout, offsets in floats
     int lds_xz, lds_red, lds_c, lds_part, lds_bias, lds_q;
     int rcap;               // rows the LDS state buffers are laid out for (>= rows of any team)
+    int rg_planned;         // row groups the activation rows and partial sums in LDS are sized for
     int q_in_lds;           // q = W_pred h + b_pred of the team's rows is kept in LDS
     int qstride;            // floats per q row in LDS
     unsigned lds_bytes;

@@ -59,14 +59,34 @@ struct PackedStage {
 // made of `groups` joint groups of `jteam_size` work-groups, each of which owns a share of the
 // team's utterances and searches for their next labels on its own.  groups == 1 is the plain
 // arrangement (Algorithm 1 always uses it: its lock-step covers the whole team).
+// Device memory a decode call works in besides its inputs, its outputs and the packed weights:
+// the projected frames and what the teams exchange.  An engine owns one such set per team
+// layout (allocated when the layout is planned); the entry point that allocates nothing carves
+// the same set out of a static scratch array instead.
+struct Workspace {
+    float *P = nullptr;                 // [B, T, J] projected frames
+    float *hbuf = nullptr, *qbuf = nullptr;
+    unsigned long long *part = nullptr, *dpart = nullptr, *lpart = nullptr, *rowx = nullptr;
+    unsigned *bar = nullptr, *abort_flag = nullptr;
+    int *status = nullptr, *xcc = nullptr;
+    long long *stats = nullptr;
+};
+
+// Bytes of each part of the team workspace for a layout (everything but P).
+struct WorkspaceSizes {
+    size_t hbuf, qbuf, part, rowx, bar, stats, xcc;
+};
+
 struct TeamConfig {
     int n_teams = 0, team_size = 0, groups = 1, jteam_size = 0;
     PackedStage st0, stl[kMaxLayers], spred, sjoint;
     DevBuf hbuf, qbuf, part, dpart, lpart, rowx, bar, stats, xcc;
+    Workspace ws;          // the buffers above plus the engine's P, abort flag and status word
     int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
     int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
     int q_in_lds = 0, qstride = 0;
     int rcap = 0;
+    int rg_planned = 0;
     unsigned lds_bytes = 0;
 };
 
@@ -89,6 +109,7 @@ struct rnnt_engine {
     TeamConfig frame_cfg;   // Algorithm 1
     TeamConfig label_cfg;   // label looping, RNN-T and TDT
     const TeamConfig *last_cfg = nullptr;
+    Workspace last_ws;      // where the last call kept its status word and statistics
     int last_B = 0;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before projection, before decode, after
     bool timed = false;
@@ -173,6 +194,20 @@ int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups
     return RNNT_OK;
 }
 
+WorkspaceSizes workspace_sizes(int n_teams, int ts, int groups, int L, int H, int J)
+{
+    WorkspaceSizes z;
+    const int tj = ts / groups;
+    z.hbuf = (size_t)n_teams * 2 * L * kMaxRows * H * sizeof(float);
+    z.qbuf = (size_t)n_teams * kMaxRows * J * sizeof(float);
+    z.part = (size_t)n_teams * groups * 2 * kMaxSamples * tj * sizeof(unsigned long long);
+    z.rowx = (size_t)n_teams * 2 * kMaxRows * sizeof(unsigned long long);
+    z.bar = (size_t)n_teams * 32 * sizeof(unsigned);
+    z.stats = (size_t)n_teams * kStatStride * sizeof(long long);
+    z.xcc = (size_t)n_teams * ts * sizeof(int);
+    return z;
+}
+
 // Choose the stage plans and the LDS layout for `n_teams` teams of `groups` joint groups and
 // upload the repacked weights.  Synchronous.
 int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
@@ -198,7 +233,9 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     // Stage plans and LDS layout.  Stages with more groups than blocks are first planned with K
     // slices over several passes (best use of the blocks); if the partial sums of such a plan do
     // not fit the LDS, they fall back to unsliced tasks.
-    const int rgp = (rows_max + 3) / 4, rows_pad = rgp * 4;
+    // the prediction kernels exist for 1, 2 and 4 row groups (pred_row_groups): the layout is
+    // sized for the instance that will run, not for the rows alone
+    const int rgp = pred_row_groups(rows_max), rows_pad = rgp * 4;
     const int rgj = kMaxSamples / 4;
     int off = 0;
     auto take = [&](int n) { int o = off; off += (n + 3) & ~3; return o; };
@@ -225,6 +262,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         t.lds_xz = take(xz);
         t.lds_red = take(red);
         t.rcap = rows_max;
+        t.rg_planned = rgp;
         t.lds_c = take(L * 2 * nu_max * rows_max);
         t.lds_part = take(L * nu_max * rows_max * 4);
         t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
@@ -271,25 +309,32 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     if (rc) return rc;
 
     // team workspace
-    const size_t n_part = (size_t)n_teams * groups * 2 * kMaxSamples * tj;
-    HIP_TRY(t.hbuf.alloc((size_t)n_teams * 2 * L * kMaxRows * H * sizeof(float)));
-    HIP_TRY(t.qbuf.alloc((size_t)n_teams * kMaxRows * J * sizeof(float)));
-    HIP_TRY(t.part.alloc(n_part * sizeof(unsigned long long)));
-    HIP_TRY(t.dpart.alloc(n_part * sizeof(unsigned long long)));
-    HIP_TRY(t.lpart.alloc(n_part * sizeof(unsigned long long)));
-    HIP_TRY(t.rowx.alloc((size_t)n_teams * 2 * kMaxRows * sizeof(unsigned long long)));
-    HIP_TRY(t.bar.alloc((size_t)n_teams * 32 * sizeof(unsigned)));
-    HIP_TRY(t.stats.alloc((size_t)n_teams * kStatStride * sizeof(long long)));
-    HIP_TRY(t.xcc.alloc((size_t)n_teams * ts * sizeof(int)));
-    HIP_TRY(hipMemset(t.hbuf.p, 0, (size_t)n_teams * 2 * L * kMaxRows * H * sizeof(float)));
-    HIP_TRY(hipMemset(t.qbuf.p, 0, (size_t)n_teams * kMaxRows * J * sizeof(float)));
-    HIP_TRY(hipMemset(t.stats.p, 0, (size_t)n_teams * kStatStride * sizeof(long long)));
-    HIP_TRY(hipMemset(t.xcc.p, 0, (size_t)n_teams * ts * sizeof(int)));
+    const WorkspaceSizes z = workspace_sizes(n_teams, ts, groups, L, H, J);
+    HIP_TRY(t.hbuf.alloc(z.hbuf));
+    HIP_TRY(t.qbuf.alloc(z.qbuf));
+    HIP_TRY(t.part.alloc(z.part));
+    HIP_TRY(t.dpart.alloc(z.part));
+    HIP_TRY(t.lpart.alloc(z.part));
+    HIP_TRY(t.rowx.alloc(z.rowx));
+    HIP_TRY(t.bar.alloc(z.bar));
+    HIP_TRY(t.stats.alloc(z.stats));
+    HIP_TRY(t.xcc.alloc(z.xcc));
+    HIP_TRY(hipMemset(t.hbuf.p, 0, z.hbuf));
+    HIP_TRY(hipMemset(t.qbuf.p, 0, z.qbuf));
+    HIP_TRY(hipMemset(t.stats.p, 0, z.stats));
+    HIP_TRY(hipMemset(t.xcc.p, 0, z.xcc));
     HIP_TRY(hipDeviceSynchronize());
     t.n_teams = n_teams;
     t.team_size = ts;
     t.groups = groups;
     t.jteam_size = tj;
+    t.ws.P = e->P.as<float>();
+    t.ws.abort_flag = e->abort_flag.as<unsigned>();
+    t.ws.status = e->status.as<int>();
+    t.ws.hbuf = t.hbuf.as<float>(); t.ws.qbuf = t.qbuf.as<float>();
+    t.ws.part = t.part.as<unsigned long long>(); t.ws.dpart = t.dpart.as<unsigned long long>();
+    t.ws.lpart = t.lpart.as<unsigned long long>(); t.ws.rowx = t.rowx.as<unsigned long long>();
+    t.ws.bar = t.bar.as<unsigned>(); t.ws.stats = t.stats.as<long long>(); t.ws.xcc = t.xcc.as<int>();
     return RNNT_OK;
 }
 
@@ -392,13 +437,15 @@ int check_call(rnnt_engine *e, const float *enc_out, const int32_t *enc_len, int
 
 int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t *enc_len, int32_t B,
                int32_t T, int32_t S, int32_t *tokens_out, int32_t *tok_len_out, int32_t cap,
-               int32_t *frames_out, float *logit_out, int32_t *durs_out, hipStream_t stream)
+               int32_t *frames_out, float *logit_out, int32_t *durs_out, hipStream_t stream,
+               const Workspace *static_ws = nullptr)
 {
     const rnnt_model_desc &d = e->d;
     const TeamConfig &t = variant == kFrameLooping ? e->frame_cfg : e->label_cfg;
+    const Workspace &ws = static_ws ? *static_ws : t.ws;
     HIP_TRY(hipEventRecord(e->ev[0], stream));
     HIP_TRY(launch_encoder_projection(enc_out, enc_len, e->w_enc.as<float>(), e->b_enc.as<float>(),
-                                      e->P.as<float>(), B, T, d.F, d.J, stream));
+                                      ws.P, B, T, d.F, d.J, stream));
     HIP_TRY(hipEventRecord(e->ev[1], stream));
     DecodeParams p{};
     p.F = d.F; p.E = d.E; p.H = d.H; p.L = d.L; p.J = d.J; p.V1 = d.V1; p.D = d.D;
@@ -417,8 +464,9 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
     p.lds_q = t.lds_q; p.q_in_lds = t.q_in_lds; p.qstride = t.qstride;
     p.rcap = t.rcap;
+    p.rg_planned = t.rg_planned;
     p.spin_limit = 1u << 22;
-    p.enc_len = enc_len; p.P = e->P.as<float>();
+    p.enc_len = enc_len; p.P = ws.P;
     p.tokens = tokens_out; p.tok_len = tok_len_out; p.frames = frames_out; p.logits = logit_out;
     p.durs = durs_out;
     p.logps = e->logp_out;
@@ -429,14 +477,13 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.sjoint = dev_stage(t.sjoint);
     p.T0 = e->T0.as<float>(); p.bias_l = e->bias_l.as<float>();
     p.b_pred = e->b_pred.as<float>(); p.b_out = e->b_out.as<float>();
-    p.hbuf = t.hbuf.as<float>(); p.qbuf = t.qbuf.as<float>();
-    p.part = t.part.as<unsigned long long>(); p.dpart = t.dpart.as<unsigned long long>();
-    p.lpart = t.lpart.as<unsigned long long>();
-    p.rowx = t.rowx.as<unsigned long long>();
-    p.bar = t.bar.as<unsigned>(); p.abort_flag = e->abort_flag.as<unsigned>();
-    p.status = e->status.as<int>(); p.stats = t.stats.as<long long>(); p.xcc = t.xcc.as<int>();
+    p.hbuf = ws.hbuf; p.qbuf = ws.qbuf;
+    p.part = ws.part; p.dpart = ws.dpart; p.lpart = ws.lpart; p.rowx = ws.rowx;
+    p.bar = ws.bar; p.abort_flag = ws.abort_flag;
+    p.status = ws.status; p.stats = ws.stats; p.xcc = ws.xcc;
     e->last_B = B;
     e->last_cfg = &t;
+    e->last_ws = ws;
     HIP_TRY(launch_decode(p, stream));
     HIP_TRY(hipEventRecord(e->ev[2], stream));
     e->timed = true;
@@ -576,6 +623,8 @@ int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_group
     if (search_steps < -1) return RNNT_ERR_SHAPE;
     HIP_TRY(hipDeviceSynchronize());
     if (n_teams > 0) {
+        eng->last_cfg = nullptr;      // the workspace the last call's statistics live in goes away
+        eng->last_ws = Workspace();
         // plain teams for Algorithm 1; the label-looping decoders split each team further
         if (eng->n_wg % n_teams != 0) return RNNT_ERR_SHAPE;
         int rc = plan_and_pack(eng, eng->frame_cfg, n_teams, 1);
@@ -658,7 +707,8 @@ int rnnt_engine_status(rnnt_engine *eng, int32_t *status_out)
 {
     if (!eng || !status_out) return RNNT_ERR_NULL;
     HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpy(status_out, eng->status.p, sizeof(int), hipMemcpyDeviceToHost));
+    const int *src = eng->last_ws.status ? eng->last_ws.status : eng->status.as<int>();
+    HIP_TRY(hipMemcpy(status_out, src, sizeof(int), hipMemcpyDeviceToHost));
     return RNNT_OK;
 }
 
@@ -671,8 +721,8 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
     if (!t) return RNNT_OK;
     std::vector<long long> st((size_t)t->n_teams * kStatStride);
     std::vector<int> xcc((size_t)t->n_teams * t->team_size);
-    HIP_TRY(hipMemcpy(st.data(), t->stats.p, st.size() * sizeof(long long), hipMemcpyDeviceToHost));
-    HIP_TRY(hipMemcpy(xcc.data(), t->xcc.p, xcc.size() * sizeof(int), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(st.data(), eng->last_ws.stats, st.size() * sizeof(long long), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(xcc.data(), eng->last_ws.xcc, xcc.size() * sizeof(int), hipMemcpyDeviceToHost));
     for (int i = 0; i < t->n_teams; ++i) {
         const long long *s = st.data() + (size_t)i * kStatStride;
         out->pred_steps += s[kStatPred];

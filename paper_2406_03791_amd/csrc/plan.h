@@ -41,6 +41,20 @@ RNNT_HD inline int k_per_load(int wt) { return wt == kWeightFp8 ? 16 : (wt == kW
 #endif
 RNNT_HD inline int red_task_stride(int rg) { return rg * 16 + RNNT_RED_PAD; }
 
+// Row groups (of 4 rows) the prediction stages of a team with `rows` utterances are compiled
+// for: the kernels are instantiated for 1, 2 and 4 groups.  The LDS layout (activation rows,
+// stride of the partial sums) has to be sized for this number, not for ceil(rows / 4).
+RNNT_HD inline int pred_row_groups(int rows)
+{
+    const int rg = (rows + 3) / 4;
+    return rg <= 1 ? 1 : (rg <= 2 ? 2 : 4);
+}
+// Row groups a joint step of `samples` (utterance, frame) pairs is compiled for: 1, 2, 4 or 8.
+RNNT_HD inline int joint_row_groups(int samples)
+{
+    return samples <= 4 ? 1 : (samples <= 8 ? 2 : (samples <= 16 ? 4 : 8));
+}
+
 // Contiguous share of n items owned by `rank` out of `ts`.
 RNNT_HD inline int range_lo(int rank, int ts, int n) { return (int)(((int64_t)rank * n) / ts); }
 RNNT_HD inline int range_hi(int rank, int ts, int n) { return (int)(((int64_t)(rank + 1) * n) / ts); }
