@@ -46,7 +46,9 @@ enum {
     RNNT_ERR_SHAPE = -2,       /* a dimension or count is out of range         */
     RNNT_ERR_VARIANT = -3,     /* RNN-T call on a TDT engine or the reverse    */
     RNNT_ERR_HIP = -4,         /* a HIP runtime call failed                    */
-    RNNT_ERR_UNSUPPORTED = -5  /* the device or the model does not fit         */
+    RNNT_ERR_UNSUPPORTED = -5, /* the device or the model does not fit         */
+    RNNT_ERR_SCRATCH = -6      /* rnnt_label_looping_decode_noalloc: the call  */
+                               /* needs more than the static scratch array     */
 };
 
 /* Bits of the device status word (rnnt_engine_status). */
@@ -191,6 +193,31 @@ int rnnt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int3
                               int32_t B, int32_t T, int32_t max_symbols,
                               int32_t *tokens_out, int32_t *tok_len_out, int32_t cap,
                               int32_t *frames_out, float *logit_out, rnnt_stream_t stream);
+
+/*
+ * rnnt_label_looping_decode for callers that cannot allocate device memory or
+ * have it allocated on their behalf: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * outputs, same errors.  The call's scratch -- the projected frames
+ * [B, T, J] and what the teams exchange -- does not come from the engine's
+ * workspace but from one array of RNNT_NOALLOC_SCRATCH_BYTES bytes that the
+ * library holds as a static device object on every device it runs on, until
+ * the process ends.  The entry point calls no hipMalloc, hipFree or other
+ * allocating routine; the engine (its packed weights) is created beforehand.
+ * A call that needs more (roughly B * T * J * 4 bytes plus 5 MiB at the
+ * Parakeet shape) returns RNNT_ERR_SCRATCH and queues nothing.
+ * All calls on one device share the array, which keeps the last call's
+ * contents (the call clears what must start at zero): calls through this entry
+ * point that overlap on one device race, whatever engines and streams they use;
+ * order them.  rnnt_engine_status / rnnt_engine_stats report on such a call
+ * until the next call on the engine.
+ */
+#define RNNT_NOALLOC_SCRATCH_BYTES (32u << 20)
+int rnnt_label_looping_decode_noalloc(rnnt_engine *eng, const float *enc_out,
+                                      const int32_t *enc_len, int32_t B, int32_t T,
+                                      int32_t max_symbols, int32_t *tokens_out,
+                                      int32_t *tok_len_out, int32_t cap, int32_t *frames_out,
+                                      float *logit_out, rnnt_stream_t stream);
 
 /*
  * Label-looping decoding of a token-and-duration transducer (the TDT rows of

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     rnnt_engine_status,
     rnnt_greedy_decode,
     rnnt_label_looping_decode,
+    rnnt_label_looping_decode_noalloc,
     rnnt_status_string,
     tdt_label_looping_decode,
 )

@@ -20,6 +20,7 @@ EXPORTS = (
     "rnnt_engine_status", "rnnt_engine_stats", "rnnt_engine_configure", "rnnt_status_string",
     "rnnt_engine_set_logp_output",
     "rnnt_engine_set_done_flags",
+    "rnnt_label_looping_decode_noalloc",
 )
 
 
@@ -93,6 +94,7 @@ def load_library():
         lib.rnnt_engine_destroy.argtypes = [C.c_void_p]
         lib.rnnt_greedy_decode.argtypes = dec_args + [C.c_void_p]
         lib.rnnt_label_looping_decode.argtypes = dec_args + [C.c_void_p]
+        lib.rnnt_label_looping_decode_noalloc.argtypes = dec_args + [C.c_void_p]
         lib.tdt_label_looping_decode.argtypes = dec_args + [C.c_void_p, C.c_void_p]
         lib.rnnt_encoder_projection.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                                 C.c_int32, C.c_void_p, C.c_void_p]
@@ -185,6 +187,13 @@ def rnnt_label_looping_decode(eng, enc_out, enc_len, B, T, max_symbols, tokens_o
             tokens_out, tok_len_out, cap, frames_out, logit_out, [], stream)
 
 
+def rnnt_label_looping_decode_noalloc(eng, enc_out, enc_len, B, T, max_symbols, tokens_out,
+                                      tok_len_out, cap, frames_out=None, logit_out=None,
+                                      stream: int = 0) -> None:
+    _decode(load_library().rnnt_label_looping_decode_noalloc, eng, enc_out, enc_len, B, T,
+            max_symbols, tokens_out, tok_len_out, cap, frames_out, logit_out, [], stream)
+
+
 def tdt_label_looping_decode(eng, enc_out, enc_len, B, T, max_symbols, tokens_out, tok_len_out,
                              cap, frames_out=None, logit_out=None, durations_out=None,
                              stream: int = 0) -> None:
@@ -275,6 +284,8 @@ class Engine:
             rnnt_greedy_decode(*common, stream=stream)
         elif variant == "label":
             rnnt_label_looping_decode(*common, stream=stream)
+        elif variant == "label_noalloc":
+            rnnt_label_looping_decode_noalloc(*common, stream=stream)
         elif variant == "tdt":
             tdt_label_looping_decode(*common, durations_out=out["durs"], stream=stream)
         else:

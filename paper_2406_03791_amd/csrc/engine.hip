@@ -37,6 +37,12 @@ int hip_fail(hipError_t e, const char *what)
 constexpr int kLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit
 constexpr int kStaticLds = 3072;        // kept free for the kernel's static LDS (control block)
 
+// Scratch of the entry point that allocates nothing (rnnt_label_looping_decode_noalloc): the
+// projected frames and the team workspace of one call.  One copy per device, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress: the address
+// kernels and copies use is the one that call returns (rnnt_engine::scratch).
+static __device__ __align__(256) unsigned char scratch[RNNT_NOALLOC_SCRATCH_BYTES];
+
 struct DevBuf {
     void *p = nullptr;
     ~DevBuf() { if (p) (void)hipFree(p); }
@@ -62,7 +68,7 @@ struct PackedStage {
 // Device memory a decode call works in besides its inputs, its outputs and the packed weights:
 // the projected frames and what the teams exchange.  An engine owns one such set per team
 // layout (allocated when the layout is planned); the entry point that allocates nothing carves
-// the same set out of a static scratch array instead.
+// the same set out of the library's static scratch array instead.
 struct Workspace {
     float *P = nullptr;                 // [B, T, J] projected frames
     float *hbuf = nullptr, *qbuf = nullptr;
@@ -111,6 +117,7 @@ struct rnnt_engine {
     const TeamConfig *last_cfg = nullptr;
     Workspace last_ws;      // where the last call kept its status word and statistics
     int last_B = 0;
+    void *scratch = nullptr;   // device address of the library's static scratch array on the engine's device
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before projection, before decode, after
     bool timed = false;
     ~rnnt_engine() { for (auto &x : ev) if (x) (void)hipEventDestroy(x); }
@@ -591,6 +598,8 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     HIP_TRY(e->T0.alloc((size_t)d.V1 * H * 4 * sizeof(float)));
     HIP_TRY(launch_fold_embedding(d.emb, d.w_ih[0], d.b_ih[0], d.b_hh[0], e->T0.as<float>(), d.V1,
                                   d.E, d.H, nullptr));
+    // this device's copy of the static scratch array (each device has its own, at its own address)
+    HIP_TRY(hipGetSymbolAddress(&e->scratch, HIP_SYMBOL(scratch)));
     HIP_TRY(e->P.alloc((size_t)max_B * max_T * J * sizeof(float)));
     HIP_TRY(e->abort_flag.alloc(sizeof(unsigned)));
     HIP_TRY(e->status.alloc(sizeof(int)));
@@ -676,6 +685,46 @@ int rnnt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int3
     return run_decode(eng, kLabelLooping, enc_out, enc_len, B, T, max_symbols, tokens_out,
                       tok_len_out, cap, frames_out, logit_out, nullptr,
                       static_cast<hipStream_t>(stream));
+}
+
+int rnnt_label_looping_decode_noalloc(rnnt_engine *eng, const float *enc_out, const int32_t *enc_len,
+                                      int32_t B, int32_t T, int32_t max_symbols, int32_t *tokens_out,
+                                      int32_t *tok_len_out, int32_t cap, int32_t *frames_out,
+                                      float *logit_out, rnnt_stream_t stream)
+{
+    int rc = check_call(eng, enc_out, enc_len, B, T, max_symbols, tokens_out, tok_len_out, cap);
+    if (rc) return rc;
+    if (eng->d.D != 0) return RNNT_ERR_VARIANT;
+    if (!eng->scratch) return RNNT_ERR_UNSUPPORTED;
+    // carve the call's workspace out of the static array, every part 256-byte aligned
+    const TeamConfig &t = eng->label_cfg;
+    const WorkspaceSizes z = workspace_sizes(t.n_teams, t.team_size, t.groups, eng->d.L, eng->d.H, eng->d.J);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
+    const size_t o_P = take((size_t)B * T * eng->d.J * sizeof(float));
+    const size_t o_h = take(z.hbuf), o_q = take(z.qbuf), o_p = take(z.part), o_d = take(z.part);
+    const size_t o_l = take(z.part), o_r = take(z.rowx), o_b = take(z.bar), o_s = take(z.stats);
+    const size_t o_x = take(z.xcc), o_a = take(sizeof(unsigned)), o_st = take(sizeof(int));
+    if (off > (size_t)RNNT_NOALLOC_SCRATCH_BYTES) return RNNT_ERR_SCRATCH;
+    unsigned char *base = static_cast<unsigned char *>(eng->scratch);
+    Workspace ws;
+    ws.P = reinterpret_cast<float *>(base + o_P);
+    ws.hbuf = reinterpret_cast<float *>(base + o_h);
+    ws.qbuf = reinterpret_cast<float *>(base + o_q);
+    ws.part = reinterpret_cast<unsigned long long *>(base + o_p);
+    ws.dpart = reinterpret_cast<unsigned long long *>(base + o_d);
+    ws.lpart = reinterpret_cast<unsigned long long *>(base + o_l);
+    ws.rowx = reinterpret_cast<unsigned long long *>(base + o_r);
+    ws.bar = reinterpret_cast<unsigned *>(base + o_b);
+    ws.stats = reinterpret_cast<long long *>(base + o_s);
+    ws.xcc = reinterpret_cast<int *>(base + o_x);
+    ws.abort_flag = reinterpret_cast<unsigned *>(base + o_a);
+    ws.status = reinterpret_cast<int *>(base + o_st);
+    // the reset kernel the decode launch starts with clears the counters, flags, tags and
+    // statistics the previous call left; the decode kernel zeroes the state rows it reads
+    return run_decode(eng, kLabelLooping, enc_out, enc_len, B, T, max_symbols, tokens_out,
+                      tok_len_out, cap, frames_out, logit_out, nullptr,
+                      static_cast<hipStream_t>(stream), &ws);
 }
 
 int tdt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int32_t *enc_len,
@@ -779,6 +828,7 @@ const char *rnnt_status_string(int code)
     case RNNT_ERR_VARIANT: return "RNN-T call on a TDT engine or TDT call on an RNN-T engine";
     case RNNT_ERR_HIP: return g_hip_error.empty() ? "HIP runtime error" : g_hip_error.c_str();
     case RNNT_ERR_UNSUPPORTED: return "the device or the model shape is not supported";
+    case RNNT_ERR_SCRATCH: return "the call needs more scratch than the static array holds (RNNT_NOALLOC_SCRATCH_BYTES)";
     default: return "unknown status code";
     }
 }
