@@ -142,11 +142,31 @@ typedef struct rnnt_stats {
 #define RNNT_FLAG_FP8_WEIGHTS 2
 
 /*
+ * rnnt_engine_create flag: launch the decode kernel with an ordinary launch
+ * instead of a cooperative one.  The kernel's teams synchronise among
+ * themselves, which needs all work-groups resident at once; the cooperative
+ * launch guarantees that, an ordinary launch of one work-group per compute
+ * unit has it on a device that runs nothing else (every wait in the kernel is
+ * bounded, so a call that does not get it ends with RNNT_DEV_ABORTED instead
+ * of hanging).  For profiling runs: a process that has run a cooperative
+ * launch under rocprofv3's kernel trace has been seen to crash in its exit
+ * handlers.  May be combined with a storage flag.
+ */
+#define RNNT_FLAG_PLAIN_LAUNCH 4
+
+/*
  * Create an engine for up to max_B utterances of up to max_T frames.
  * Copies and repacks the weights on the current device, allocates the
  * workspace (projected frames [max_B, max_T, J], state, exchange buffers).
- * flags: 0, RNNT_FLAG_BF16_WEIGHTS or RNNT_FLAG_FP8_WEIGHTS; other bits are
- * RNNT_ERR_SHAPE.
+ * flags: 0 or one of RNNT_FLAG_BF16_WEIGHTS / RNNT_FLAG_FP8_WEIGHTS, optionally
+ * with RNNT_FLAG_PLAIN_LAUNCH; other bits are RNNT_ERR_SHAPE.
+ * Limits of this implementation, checked here before anything is allocated
+ * (RNNT_ERR_UNSUPPORTED): F must be a multiple of 16 (K tile of the projection
+ * GEMM); V1 at most 65 535 (the argmax exchange carries a 16-bit column index);
+ * the device must support cooperative launches.  1 <= L <= 4, D <= 8, blank in
+ * [0, V1) and positive sizes are RNNT_ERR_SHAPE.
+ * The two bias vectors of an LSTM layer are added once on the host while the
+ * weights are repacked (b_ih + b_hh in fp32).
  * A team of work-groups holds at most 16 utterances and its state has to fit
  * the compute units' local memory: with the Parakeet shape on 256 compute
  * units max_B up to 256 is accepted, a larger one returns
@@ -164,8 +184,10 @@ int rnnt_engine_destroy(rnnt_engine *eng);
  * frames shared by the utterances of a team, an inner loop of at most
  * max_symbols steps that ends when every utterance has produced a blank.
  *
- *   enc_out     [B, T, F]   encoder output; frames t >= enc_len[b] are padding
- *                           and may hold anything, NaN included
+ *   enc_out     [B, T, F]   encoder output, 16-byte aligned (the projection
+ *                           kernel loads four floats at a time; any other
+ *                           address is RNNT_ERR_SHAPE); frames t >= enc_len[b]
+ *                           are padding and may hold anything, NaN included
  *   enc_len     [B]         valid frames per utterance; values outside [0, T]
  *                           are clamped on the device (RNNT_DEV_LEN_CLAMPED)
  *   tokens_out  [B, cap]    emitted labels in order; entries at and beyond
@@ -303,6 +325,16 @@ int rnnt_engine_set_logp_output(rnnt_engine *eng, float *logp_out);
  * The caller owns the array and keeps it alive until the calls have finished.
  */
 int rnnt_engine_set_done_flags(rnnt_engine *eng, int32_t *done);
+
+/*
+ * Phase timers of the last decode call, for libraries built with
+ * -DRNNT_PROFILE (RNNT_PROFILE=1 in the environment of build.py): microseconds
+ * rank 0 of `team` spent in each phase of the prediction and joint steps, as
+ * many as n (at most 24) into the HOST array us_out.  The phases are listed in
+ * bench.py (--phases).  An ordinary build returns RNNT_ERR_UNSUPPORTED.  Waits
+ * for the device.
+ */
+int rnnt_engine_phase_timers(rnnt_engine *eng, int32_t team, double *us_out, int32_t n);
 
 /* Text for a return code; for RNNT_ERR_HIP includes the last HIP error text. */
 const char *rnnt_status_string(int code);

@@ -8,6 +8,7 @@ kernels.  There is no fallback: importing fails if the library is not built.
 from .binding import (  # noqa: F401
     RNNT_FLAG_BF16_WEIGHTS,
     RNNT_FLAG_FP8_WEIGHTS,
+    RNNT_FLAG_PLAIN_LAUNCH,
     Engine,
     RnntError,
     RnntStats,
@@ -19,6 +20,7 @@ from .binding import (  # noqa: F401
     rnnt_engine_destroy,
     rnnt_engine_set_logp_output,
     rnnt_engine_set_done_flags,
+    rnnt_engine_phase_timers,
     rnnt_engine_stats,
     rnnt_engine_status,
     rnnt_greedy_decode,

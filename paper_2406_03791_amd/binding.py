@@ -21,11 +21,13 @@ EXPORTS = (
     "rnnt_engine_set_logp_output",
     "rnnt_engine_set_done_flags",
     "rnnt_label_looping_decode_noalloc",
+    "rnnt_engine_phase_timers",
 )
 
 
 RNNT_FLAG_BF16_WEIGHTS = 1
 RNNT_FLAG_FP8_WEIGHTS = 2
+RNNT_FLAG_PLAIN_LAUNCH = 4
 
 
 class RnntError(RuntimeError):
@@ -103,6 +105,7 @@ def load_library():
         lib.rnnt_engine_configure.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         lib.rnnt_engine_set_logp_output.argtypes = [C.c_void_p, C.c_void_p]
         lib.rnnt_engine_set_done_flags.argtypes = [C.c_void_p, C.c_void_p]
+        lib.rnnt_engine_phase_timers.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_int32]
         lib.rnnt_status_string.argtypes = [C.c_int]
         lib.rnnt_status_string.restype = C.c_char_p
         for name in EXPORTS:
@@ -213,6 +216,13 @@ def rnnt_engine_status(eng) -> int:
     return int(out.value)
 
 
+def rnnt_engine_phase_timers(eng, team: int, n: int = 24):
+    """Microseconds per phase for rank 0 of `team` (profile builds only)."""
+    out = (C.c_double * n)()
+    _check(load_library().rnnt_engine_phase_timers(eng, int(team), out, int(n)))
+    return [float(v) for v in out]
+
+
 def rnnt_engine_stats(eng) -> RnntStats:
     out = RnntStats()
     _check(load_library().rnnt_engine_stats(eng, C.byref(out)))
@@ -304,3 +314,6 @@ class Engine:
 
     def stats(self) -> dict:
         return rnnt_engine_stats(self.handle).as_dict()
+
+    def phase_timers(self, team: int, n: int = 24):
+        return rnnt_engine_phase_timers(self.handle, team, n)

@@ -7,13 +7,11 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip",
-           "decode_f1.hip", "decode_f2.hip", "decode_f4.hip",
-           "decode_l1.hip", "decode_l2.hip", "decode_l4.hip",
-           "decode_f1b.hip", "decode_f2b.hip", "decode_f4b.hip",
-           "decode_l1b.hip", "decode_l2b.hip", "decode_l4b.hip",
-           "decode_f1e.hip", "decode_f2e.hip", "decode_f4e.hip",
-           "decode_l1e.hip", "decode_l2e.hip", "decode_l4e.hip"]
+SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip"]
+# the decode kernel is instantiated in one unit per (loop nest, row groups, weight storage),
+# all compiled from decode_inst.hip, so that the instances build in parallel
+INSTANCES = [(nest, rg, wt) for wt in ("f32", "bf16", "fp8") for nest in ("f", "l")
+             for rg in (1, 2, 4)]
 LIB = os.path.join(HERE, "librnnt_greedy.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 FLAGS = ((["-DRNNT_PROFILE"] if os.environ.get("RNNT_PROFILE") else []) +
@@ -30,16 +28,21 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
 
     os.makedirs(OBJ_DIR, exist_ok=True)
 
-    def compile_one(src: str) -> str:
-        obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-        cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    def compile_one(job) -> str:
+        src, name, defs = job
+        obj = os.path.join(OBJ_DIR, name + ".o")
+        cmd = ["hipcc", *FLAGS, *defs, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
         return obj
 
+    jobs_ = [("decode_inst.hip", f"decode_{nest}{rg}_{wt}",
+              [f"-DRNNT_INST_NEST={nest}", f"-DRNNT_INST_RG={rg}", f"-DRNNT_INST_WT={wt}"])
+             for nest, rg, wt in INSTANCES]
+    jobs_ += [(src, src.replace(".hip", ""), []) for src in SOURCES]
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, os.cpu_count() or 1))) as pool:
-        objs = list(pool.map(compile_one, SOURCES))
+        objs = list(pool.map(compile_one, jobs_))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -4,17 +4,15 @@
 
 namespace rnnt {
 
+// launch_decode_<nest><row groups>_<storage>: one per instantiation unit (decode_inst.hip)
 #define RNNT_DECLARE_LAUNCH(name) \
     hipError_t name(const DecodeParams &p, int rgj, hipStream_t stream)
-RNNT_DECLARE_LAUNCH(launch_decode_f1); RNNT_DECLARE_LAUNCH(launch_decode_f2);
-RNNT_DECLARE_LAUNCH(launch_decode_f4); RNNT_DECLARE_LAUNCH(launch_decode_l1);
-RNNT_DECLARE_LAUNCH(launch_decode_l2); RNNT_DECLARE_LAUNCH(launch_decode_l4);
-RNNT_DECLARE_LAUNCH(launch_decode_f1b); RNNT_DECLARE_LAUNCH(launch_decode_f2b);
-RNNT_DECLARE_LAUNCH(launch_decode_f4b); RNNT_DECLARE_LAUNCH(launch_decode_l1b);
-RNNT_DECLARE_LAUNCH(launch_decode_l2b); RNNT_DECLARE_LAUNCH(launch_decode_l4b);
-RNNT_DECLARE_LAUNCH(launch_decode_f1e); RNNT_DECLARE_LAUNCH(launch_decode_f2e);
-RNNT_DECLARE_LAUNCH(launch_decode_f4e); RNNT_DECLARE_LAUNCH(launch_decode_l1e);
-RNNT_DECLARE_LAUNCH(launch_decode_l2e); RNNT_DECLARE_LAUNCH(launch_decode_l4e);
+#define RNNT_DECLARE_NEST(wt)                                                            \
+    RNNT_DECLARE_LAUNCH(launch_decode_f1_##wt); RNNT_DECLARE_LAUNCH(launch_decode_f2_##wt); \
+    RNNT_DECLARE_LAUNCH(launch_decode_f4_##wt); RNNT_DECLARE_LAUNCH(launch_decode_l1_##wt); \
+    RNNT_DECLARE_LAUNCH(launch_decode_l2_##wt); RNNT_DECLARE_LAUNCH(launch_decode_l4_##wt)
+RNNT_DECLARE_NEST(f32); RNNT_DECLARE_NEST(bf16); RNNT_DECLARE_NEST(fp8);
+#undef RNNT_DECLARE_NEST
 #undef RNNT_DECLARE_LAUNCH
 
 // Clears what must start at zero for a call: barrier counters, abort flag, status, stats and
@@ -58,12 +56,12 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     if (rows > kMaxRows || rg > p.rg_planned || samples > kMaxSamples) return hipErrorInvalidValue;
     typedef hipError_t (*Launch)(const DecodeParams &, int, hipStream_t);
     static const Launch table[3][2][3] = {
-        {{launch_decode_f1, launch_decode_f2, launch_decode_f4},
-         {launch_decode_l1, launch_decode_l2, launch_decode_l4}},
-        {{launch_decode_f1b, launch_decode_f2b, launch_decode_f4b},
-         {launch_decode_l1b, launch_decode_l2b, launch_decode_l4b}},
-        {{launch_decode_f1e, launch_decode_f2e, launch_decode_f4e},
-         {launch_decode_l1e, launch_decode_l2e, launch_decode_l4e}}};
+        {{launch_decode_f1_f32, launch_decode_f2_f32, launch_decode_f4_f32},
+         {launch_decode_l1_f32, launch_decode_l2_f32, launch_decode_l4_f32}},
+        {{launch_decode_f1_bf16, launch_decode_f2_bf16, launch_decode_f4_bf16},
+         {launch_decode_l1_bf16, launch_decode_l2_bf16, launch_decode_l4_bf16}},
+        {{launch_decode_f1_fp8, launch_decode_f2_fp8, launch_decode_f4_fp8},
+         {launch_decode_l1_fp8, launch_decode_l2_fp8, launch_decode_l4_fp8}}};
     if (p.wt < 0 || p.wt > 2) return hipErrorInvalidValue;
     return table[p.wt][p.variant == kFrameLooping ? 0 : 1][rgi](p, rgj, stream);
 }

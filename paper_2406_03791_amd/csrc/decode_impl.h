@@ -13,8 +13,6 @@
 // joint groups inside a team: the team runs the prediction network for all its
 // rows together, the groups search for the labels of their own rows on their own.
 #pragma once
-#include <cstdlib>
-
 #include "engine.h"
 
 namespace rnnt {
@@ -81,25 +79,6 @@ struct Sync {
     long long polls;
 };
 
-// A copy of the work-group coordinates for one phase of a step.  Making the copy opaque to the
-// optimiser (an empty asm on tid, team and rank) keeps the phase's indices and addresses from
-// being hoisted out of the decode loops and cuts the kernel from ~250 to ~165 VGPRs, but it
-// measured 5 % slower on MI355X (the hoisted values save more than the registers cost at two
-// waves per SIMD), so the copy is a plain one unless the library is built with
-// -DRNNT_REDERIVE=1.
-#ifndef RNNT_REDERIVE
-#define RNNT_REDERIVE 0
-#endif
-__device__ __forceinline__ Wg rederive(const Wg &a)
-{
-    Wg b = a;
-#if RNNT_REDERIVE
-    asm volatile("" : "+v"(b.tid), "+s"(b.team), "+s"(b.rank));
-    b.lane = b.tid & 63; b.wave = b.tid >> 6;
-#endif
-    return b;
-}
-
 // Phase timers (100 MHz wall clock), compiled in only for profiling builds.
 #ifdef RNNT_PROFILE
 __shared__ long long g_prof[24];
@@ -158,51 +137,22 @@ __device__ __forceinline__ bool team_barrier(const DecodeParams &p, const Wg &w,
 
 // The packed weights of a stage are a fixed stream per lane, independent of the
 // data, so their loads can start before the stage's input is there: kAhead
-// batches of kStepUnroll float4 steps are kept in flight in registers.
-#ifndef RNNT_NT_PRED
-#define RNNT_NT_PRED 0
-#endif
-#ifndef RNNT_NT_JOINT
-#define RNNT_NT_JOINT 0
-#endif
-#ifndef RNNT_AHEAD_PRED
-#define RNNT_AHEAD_PRED 2
-#endif
-#ifndef RNNT_AHEAD_JOINT
-#define RNNT_AHEAD_JOINT 2
-#endif
-constexpr int kAheadPred = RNNT_AHEAD_PRED;     // prediction stages: pure streaming, few accumulators
-constexpr int kAheadJoint = RNNT_AHEAD_JOINT;   // joint stage: 8 row groups of accumulators are live too
+// batches of kStepUnroll float4 steps are kept in flight in registers.  (Deeper windows and
+// non-temporal loads both measured slower on MI355X: a wave's loads return in order, so the
+// exchange loads behind a longer window wait longer, and the teams of an XCD profit from
+// each other's L2 lines.)
+constexpr int kAhead = 2;
 
-// Optional non-temporal weight loads (-DRNNT_NT_PRED=1, -DRNNT_NT_JOINT=1).  Measured on MI355X
-// they are slower (by a third where the teams of an XCD stream the same packed weights and
-// profit from each other's L2 lines), so every stream uses ordinary loads by default.  Deeper
-// windows (-DRNNT_AHEAD_PRED, -DRNNT_AHEAD_JOINT) measured slower too: a wave's loads return
-// in order, so the exchange loads behind a longer window wait longer.
-template <bool NT>
-__device__ __forceinline__ float4 load_weight(const float4 *p)
-{
-    if (NT) {
-        // one 16-byte load marked non-temporal (streaming): the line is not kept in L2
-        const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
-        return make_float4(v[0], v[1], v[2], v[3]);
-    }
-    return *p;
-}
-
-template <int AH, bool NT>
 struct WeightStream {
     const float4 *wp;
     int task;
     bool live;
-    float4 q[AH][kStepUnroll];
+    float4 q[kAhead][kStepUnroll];
 };
 
-template <int AH, bool NT>
-__device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const StageDev &sd, const Wg &w,
+__device__ __forceinline__ void stream_begin(WeightStream &ws, const StageDev &sd, const Wg &w,
                                              int rank, int n_tasks, int slot)
 {
-    constexpr int kAhead = AH;
     // a wave's passes ("slots") follow each other in memory, so its whole stage is one
     // contiguous run of slots * nsteps loads per lane
     ws.task = slot * kBlocksPerWg + w.wave * 16 + (w.lane >> 2);
@@ -214,7 +164,7 @@ __device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const Sta
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
             const int step = a * kStepUnroll + u;
-            ws.q[a][u] = (ws.live && step < sd.nsteps * sd.slots) ? load_weight<NT>(ws.wp + step * 64)
+            ws.q[a][u] = (ws.live && step < sd.nsteps * sd.slots) ? *(ws.wp + step * 64)
                                                        : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 }
@@ -229,16 +179,15 @@ __device__ __forceinline__ void stream_begin(WeightStream<AH, NT> &ws, const Sta
 // kWeightBf16: a load carries eight bf16 weights, used as two part-steps of four; a bf16
 // weight becomes its fp32 value by a shift, the products and sums are fp32 as before.
 // kWeightFp8: sixteen e4m3 weights, four part-steps; one conversion instruction widens two.
-template <int RG, int WT, int AH, bool NT>
+template <int RG, int WT>
 __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int rank, int n_tasks,
-                                          WeightStream<AH, NT> &ws, const float *x, int xstride,
+                                          WeightStream &ws, const float *x, int xstride,
                                           int x_inp_stride, int groups_per_inp, float *red,
                                           bool red_aliases_x)
 {
-    constexpr int kAhead = AH;
     // two batches in flight: the hand-over of the batches at a pass boundary below is written
-    // for that depth (deeper windows measured slower in every layout)
-    static_assert(AH == 2, "run_stage: the pass boundary assumes two batches in flight");
+    // for that depth
+    static_assert(kAhead == 2, "run_stage: the pass boundary assumes two batches in flight");
     static_assert(kMaxSamples <= 64, "the samples of a joint step are set up by one wave");
     const int r4 = w.lane & 3;
     // The loads run through the passes without a break: a lane that has a task in the first
@@ -312,7 +261,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
                     if (stream_live && i + kAhead * kStepUnroll < left) {
 #pragma unroll
                         for (int u = 0; u < kStepUnroll; ++u)
-                            ws.q[a][u] = load_weight<NT>(ws.wp + (i + kAhead * kStepUnroll + u) * 64);
+                            ws.q[a][u] = *(ws.wp + (i + kAhead * kStepUnroll + u) * 64);
                     }
                 }
             }
@@ -429,15 +378,14 @@ __device__ __forceinline__ void lstm_point(float gi, float gf, float gg, float g
 // One prediction-network step for all rows of the team, from (last, committed
 // state) to the candidate state and q = W_pred h'_top + b_pred.
 template <int RG, int WT>
-__device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg &w0, Sync &sy, const Lds &l)
+__device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l)
 {
-    const Wg w = rederive(w0);
     const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
     const int rows_pad = RG * 4;
     const int inp_stride = rows_pad * p.xstride;
     // stage 0: recurrent parts of every layer, layer 0 completes
     PROF_MARK(w, 18);
-    WeightStream<kAheadPred, RNNT_NT_PRED != 0> ws;
+    WeightStream ws;
     stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks, 0);
     for (int layer = 0; layer < p.L; ++layer)
         fill_rows(p, w, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
@@ -618,9 +566,8 @@ __device__ __forceinline__ unsigned long long wait_partial(const DecodeParams &p
 // c.s_valid.  Leaves c.s_k, c.s_v (token argmax and its logit) and c.s_d
 // (duration index) for every valid sample.
 template <int RG, int WT>
-__device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, Sync &sy, const Lds &l, int parity)
+__device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l, int parity)
 {
-    const Wg w = rederive(w0);
     const int ns = c.ns;
     const int rows_pad = RG * 4;
     const int kpad = p.sjoint.kpad;
@@ -631,7 +578,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w0, 
     const int g0 = range_lo(w.jrank, p.jteam_size, ng_all);
     const int ng = range_hi(w.jrank, p.jteam_size, ng_all) - g0;
     PROF_MARK(w, 18);
-    WeightStream<kAheadJoint, RNNT_NT_JOINT != 0> ws;
+    WeightStream ws;
     // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time; the loads of a
     // batch are all issued before the first use.  The first batch of gathers goes out before
     // the weight stream begins: a wave's loads return in order, and z is needed first.
@@ -1246,16 +1193,11 @@ hipError_t launch_one(const DecodeParams &p, hipStream_t stream)
     DecodeParams pc = p;
     void *args[] = {&pc};
     // The cooperative launch guarantees that all work-groups are resident together, which
-    // the team barriers rely on.  RNNT_PLAIN_LAUNCH=1 uses an ordinary launch instead (the
-    // grid is one work-group per compute unit, so on an otherwise idle device it is
-    // resident too, and every wait in the kernel is bounded): rocprofv3 crashes at process
-    // exit after a cooperative launch was traced.
-    static const bool plain = [] {
-        const char *v = std::getenv("RNNT_PLAIN_LAUNCH");
-        return v && v[0] == '1';
-    }();
+    // the team barriers rely on.  An engine created with RNNT_FLAG_PLAIN_LAUNCH uses an
+    // ordinary launch instead (the grid is one work-group per compute unit, so on an
+    // otherwise idle device it is resident too, and every wait in the kernel is bounded).
     const dim3 grid(p.n_teams * p.team_size), block(kThreads);
-    if (plain) return hipLaunchKernel(fn, grid, block, args, p.lds_bytes, stream);
+    if (p.plain_launch) return hipLaunchKernel(fn, grid, block, args, p.lds_bytes, stream);
     return hipLaunchCooperativeKernel(fn, grid, block, args, p.lds_bytes, stream);
 }
 

@@ -29,6 +29,7 @@ struct DecodeParams {
     int n_teams, team_size, lookahead;
     int search_steps;       // label looping: joint steps per search before the next prediction step (0: no limit)
     int groups, jteam_size; // joint groups per team and work-groups per joint group
+    int plain_launch;       // ordinary instead of cooperative launch (engine flag)
     int spread;             // work-group i is rank i % team_size of team i / team_size (else team i % n_teams, rank i / n_teams)
     int serpentine;         // deal length-ranked utterances to teams 0..n-1, n-1..0, ... (else 0..n-1, 0..n-1)
     int xstride;            // floats per activation row in LDS

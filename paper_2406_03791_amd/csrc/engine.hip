@@ -1,13 +1,14 @@
 // Host side of the C ABI declared in include/rnnt_greedy.h: argument checks,
-// weight repacking, workspace, launches.  Nothing here computes any part of the
-// decode; every step of the path runs in the kernels.
+// weight repacking, workspace, launches.  Every step of the decode runs in the kernels; the
+// only arithmetic on the host is done once per engine, on weights: the two LSTM bias vectors
+// of a layer are added (b_ih + b_hh, one fp32 addition per gate, the order the oracle adds
+// them in) while the weights are repacked.
 #include "../../include/rnnt_greedy.h"
 
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cmath>
-#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <functional>
@@ -15,6 +16,7 @@
 #include <vector>
 
 #include "engine.h"
+#include "pack.h"
 
 using namespace rnnt;
 
@@ -104,6 +106,7 @@ struct rnnt_engine {
     int lookahead = 0;
     int search_steps = 0;  // 0: chosen per call, -1: no limit, > 0: as given
     int wt = kWeightF32;   // storage of the packed (streamed) weights
+    bool plain_launch = false;   // RNNT_FLAG_PLAIN_LAUNCH
     float *logp_out = nullptr;   // caller's [B, cap] buffer for log-probabilities, or none
     int32_t *done = nullptr;     // caller's [B] completion flags, or none
     // host copies of the weights that get repacked when the team layout changes
@@ -125,77 +128,10 @@ struct rnnt_engine {
 
 namespace {
 
-// bf16 code of a float that is exactly representable in bf16 (the engine checks that first).
-inline uint16_t bf16_bits(float v)
-{
-    uint32_t u;
-    std::memcpy(&u, &v, sizeof u);
-    return (uint16_t)(u >> 16);
-}
-
-// OCP e4m3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, largest
-// finite value 448) of a float, if the float is one of its values.
-inline bool e4m3_bits(float v, uint8_t *code)
-{
-    uint32_t u;
-    std::memcpy(&u, &v, sizeof u);
-    const uint32_t sign = (u >> 31) << 7, expo = (u >> 23) & 0xffu, mant = u & 0x7fffffu;
-    if ((u & 0x7fffffffu) == 0) { *code = (uint8_t)sign; return true; }
-    if (expo == 0xffu || expo == 0) return false;           // not finite, or an fp32 subnormal
-    const int e = (int)expo - 127;
-    if (e >= -6) {                                          // e4m3 normal
-        if (e > 8 || (mant & 0xfffffu) != 0) return false;
-        const uint32_t m = mant >> 20;
-        if (e == 8 && m == 7) return false;                 // that code is NaN
-        *code = (uint8_t)(sign | ((uint32_t)(e + 7) << 3) | m);
-        return true;
-    }
-    const float t = std::fabs(v) * 512.0f;                  // e4m3 subnormals are m * 2^-9, m = 1..7
-    const int m = (int)t;
-    if ((float)m != t || m < 1 || m > 7) return false;
-    *code = (uint8_t)(sign | (uint32_t)m);
-    return true;
-}
-
 int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups,
                  const std::function<const float *(int, int, int)> &row_of)
 {
-    const StagePlan &pl = ps.plan;
-    // 16 bytes per (rank, wave, slot, step, lane): 4 floats, 8 bf16 codes or 16 e4m3 codes
-    std::vector<uint32_t> host((size_t)ts * pl.rank_stride * 4, 0u);
-    for (int rank = 0; rank < ts; ++rank) {
-        const int ntask = ngroups(rank) * pl.nks;
-        for (int slot = 0; slot < pl.slots; ++slot)
-            for (int wave = 0; wave < kWaves; ++wave)
-                for (int lane = 0; lane < 64; ++lane) {
-                    const int task = slot * kBlocksPerWg + wave * 16 + (lane >> 2);
-                    if (task >= ntask) continue;
-                    const int g = task / pl.nks, ks = task % pl.nks;
-                    const float *row = row_of(rank, g, lane & 3);
-                    if (!row) continue;
-                    for (int step = 0; step < pl.nsteps; ++step) {
-                        uint32_t *dst = host.data() +
-                                        ((size_t)rank * pl.rank_stride +
-                                         ((size_t)(wave * pl.slots + slot) * pl.nsteps + step) * 64 + lane) * 4;
-                        const int k0 = (ks * pl.nsteps + step) * pl.kper;
-                        if (pl.kper == 4) {
-                            for (int c = 0; c < 4; ++c)
-                                if (k0 + c < pl.K) std::memcpy(dst + c, row + k0 + c, 4);
-                        } else if (pl.kper == 8) {
-                            for (int c = 0; c < 8; ++c)
-                                if (k0 + c < pl.K)
-                                    dst[c >> 1] |= (uint32_t)bf16_bits(row[k0 + c]) << (16 * (c & 1));
-                        } else {
-                            for (int c = 0; c < 16; ++c)
-                                if (k0 + c < pl.K) {
-                                    uint8_t code = 0;
-                                    e4m3_bits(row[k0 + c], &code);   // checked when the engine was created
-                                    dst[c >> 2] |= (uint32_t)code << (8 * (c & 3));
-                                }
-                        }
-                    }
-                }
-    }
+    const std::vector<uint32_t> host = pack_stage(ps.plan, ts, ngroups, row_of);
     HIP_TRY(ps.w.alloc(host.size() * sizeof(uint32_t)));
     HIP_TRY(hipMemcpy(ps.w.p, host.data(), host.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     return RNNT_OK;
@@ -463,6 +399,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.groups = t.groups; p.jteam_size = t.jteam_size;
     p.serpentine = 1;
     p.spread = spread_layout(t) ? 1 : 0;
+    p.plain_launch = e->plain_launch ? 1 : 0;
     p.wt = e->wt;
     p.lookahead = effective_lookahead(e, t, B);
     p.search_steps = effective_search_steps(e, t, B);
@@ -505,7 +442,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
                        rnnt_engine **out)
 {
     if (!desc || !out) return RNNT_ERR_NULL;
-    if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS)) return RNNT_ERR_SHAPE;
+    if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_PLAIN_LAUNCH)) return RNNT_ERR_SHAPE;
     if ((flags & RNNT_FLAG_BF16_WEIGHTS) && (flags & RNNT_FLAG_FP8_WEIGHTS)) return RNNT_ERR_SHAPE;
     const rnnt_model_desc &d = *desc;
     if (!d.emb || !d.w_ih || !d.w_hh || !d.b_ih || !d.b_hh || !d.w_enc || !d.b_enc || !d.w_pred ||
@@ -539,6 +476,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     e->max_B = max_B; e->max_T = max_T;
     e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8
                                             : ((flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32);
+    e->plain_launch = (flags & RNNT_FLAG_PLAIN_LAUNCH) != 0;
     e->n_wg = (prop.multiProcessorCount / 32) * 32;   // every layout divides it
     if (e->n_wg < 32) return RNNT_ERR_UNSUPPORTED;
 
@@ -791,22 +729,6 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
             out->xcd_mismatch += id != want;
         }
     }
-    // phase timers of a library built with -DRNNT_PROFILE, printed on request
-    if (const char *dump = std::getenv("RNNT_DUMP_PHASES")) {
-        if (dump[0] == '1') {
-            for (int i = 0; i < t->n_teams; ++i) {
-                const long long *s = st.data() + (size_t)i * kStatStride;
-                std::fprintf(stderr, "team %d: %lld prediction steps, %lld joint steps; rank 0 phase timers (us):",
-                             i, s[kStatPred], s[kStatJoint]);
-                double tot = 0;
-                for (int k = 0; k < 20; ++k) {
-                    std::fprintf(stderr, " %d:%.0f", k, s[kStatCount + k] * 0.01);
-                    tot += s[kStatCount + k] * 0.01;
-                }
-                std::fprintf(stderr, " total:%.0f\n", tot);
-            }
-        }
-    }
     out->n_teams = t->n_teams;
     out->team_size = t->team_size;
     out->joint_groups = t->groups;
@@ -817,6 +739,24 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
         HIP_TRY(hipEventElapsedTime(&out->decode_ms, eng->ev[1], eng->ev[2]));
     }
     return RNNT_OK;
+}
+
+int rnnt_engine_phase_timers(rnnt_engine *eng, int32_t team, double *us_out, int32_t n)
+{
+    if (!eng || !us_out) return RNNT_ERR_NULL;
+#ifdef RNNT_PROFILE
+    const TeamConfig *t = eng->last_cfg;
+    if (!t || team < 0 || team >= t->n_teams || n < 0) return RNNT_ERR_SHAPE;
+    HIP_TRY(hipDeviceSynchronize());
+    long long raw[kStatProf];
+    HIP_TRY(hipMemcpy(raw, eng->last_ws.stats + (size_t)team * kStatStride + kStatCount, sizeof raw,
+                      hipMemcpyDeviceToHost));
+    for (int i = 0; i < n; ++i) us_out[i] = i < kStatProf ? raw[i] * 0.01 : 0.0;   // 100 MHz clock
+    return RNNT_OK;
+#else
+    (void)team; (void)n;
+    return RNNT_ERR_UNSUPPORTED;
+#endif
 }
 
 const char *rnnt_status_string(int code)

@@ -1,0 +1,93 @@
+// Host-side repacking of a dense stage's weights into the order the decode kernel streams
+// them in (see plan.h for the task decomposition).  No device code and no HIP calls here, so
+// that the packer can be built and run under host sanitizers on its own.
+#pragma once
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <functional>
+#include <vector>
+
+#include "plan.h"
+
+namespace rnnt {
+
+// bf16 code of a float that is exactly representable in bf16 (the engine checks that first).
+inline uint16_t bf16_bits(float v)
+{
+    uint32_t u;
+    std::memcpy(&u, &v, sizeof u);
+    return (uint16_t)(u >> 16);
+}
+
+// OCP e4m3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, largest
+// finite value 448) of a float, if the float is one of its values.
+inline bool e4m3_bits(float v, uint8_t *code)
+{
+    uint32_t u;
+    std::memcpy(&u, &v, sizeof u);
+    const uint32_t sign = (u >> 31) << 7, expo = (u >> 23) & 0xffu, mant = u & 0x7fffffu;
+    if ((u & 0x7fffffffu) == 0) { *code = (uint8_t)sign; return true; }
+    if (expo == 0xffu || expo == 0) return false;           // not finite, or an fp32 subnormal
+    const int e = (int)expo - 127;
+    if (e >= -6) {                                          // e4m3 normal
+        if (e > 8 || (mant & 0xfffffu) != 0) return false;
+        const uint32_t m = mant >> 20;
+        if (e == 8 && m == 7) return false;                 // that code is NaN
+        *code = (uint8_t)(sign | ((uint32_t)(e + 7) << 3) | m);
+        return true;
+    }
+    const float t = std::fabs(v) * 512.0f;                  // e4m3 subnormals are m * 2^-9, m = 1..7
+    const int m = (int)t;
+    if ((float)m != t || m < 1 || m > 7) return false;
+    *code = (uint8_t)(sign | (uint32_t)m);
+    return true;
+}
+
+// The packed image of one stage: 16 bytes per (rank, wave, slot, step, lane) holding 4 floats,
+// 8 bf16 codes or 16 e4m3 codes of consecutive K for the output column the lane owns.
+//   ngroups(rank)        output groups (of 4 columns) the rank owns
+//   row_of(rank, g, j)   the weight row (length plan.K) of column j of the rank's group g, or
+//                        nullptr for a column beyond the matrix (stays zero)
+inline std::vector<uint32_t> pack_stage(const StagePlan &pl, int ts,
+                                        const std::function<int(int)> &ngroups,
+                                        const std::function<const float *(int, int, int)> &row_of)
+{
+    std::vector<uint32_t> host((size_t)ts * pl.rank_stride * 4, 0u);
+    for (int rank = 0; rank < ts; ++rank) {
+        const int ntask = ngroups(rank) * pl.nks;
+        for (int slot = 0; slot < pl.slots; ++slot)
+            for (int wave = 0; wave < kWaves; ++wave)
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int task = slot * kBlocksPerWg + wave * 16 + (lane >> 2);
+                    if (task >= ntask) continue;
+                    const int g = task / pl.nks, ks = task % pl.nks;
+                    const float *row = row_of(rank, g, lane & 3);
+                    if (!row) continue;
+                    for (int step = 0; step < pl.nsteps; ++step) {
+                        uint32_t *dst = host.data() +
+                                        ((size_t)rank * pl.rank_stride +
+                                         ((size_t)(wave * pl.slots + slot) * pl.nsteps + step) * 64 + lane) * 4;
+                        const int k0 = (ks * pl.nsteps + step) * pl.kper;
+                        if (pl.kper == 4) {
+                            for (int c = 0; c < 4; ++c)
+                                if (k0 + c < pl.K) std::memcpy(dst + c, row + k0 + c, 4);
+                        } else if (pl.kper == 8) {
+                            for (int c = 0; c < 8; ++c)
+                                if (k0 + c < pl.K)
+                                    dst[c >> 1] |= (uint32_t)bf16_bits(row[k0 + c]) << (16 * (c & 1));
+                        } else {
+                            for (int c = 0; c < 16; ++c)
+                                if (k0 + c < pl.K) {
+                                    uint8_t code = 0;
+                                    e4m3_bits(row[k0 + c], &code);   // checked when the engine was created
+                                    dst[c >> 2] |= (uint32_t)code << (8 * (c & 3));
+                                }
+                        }
+                    }
+                }
+    }
+    return host;
+}
+
+}  // namespace rnnt

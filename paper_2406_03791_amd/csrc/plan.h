@@ -36,10 +36,7 @@ RNNT_HD inline int k_per_load(int wt) { return wt == kWeightFp8 ? 16 : (wt == kW
 // Floats between the partial sums of consecutive tasks in LDS: 16 per row group plus a pad that
 // spreads the readers (one lane per output group, so a stride of whole multiples of 16 floats
 // would put all of them on two banks).
-#ifndef RNNT_RED_PAD
-#define RNNT_RED_PAD 4
-#endif
-RNNT_HD inline int red_task_stride(int rg) { return rg * 16 + RNNT_RED_PAD; }
+RNNT_HD inline int red_task_stride(int rg) { return rg * 16 + 4; }
 
 // Row groups (of 4 rows) the prediction stages of a team with `rows` utterances are compiled
 // for: the kernels are instantiated for 1, 2 and 4 groups.  The LDS layout (activation rows,
@@ -72,10 +69,7 @@ struct StagePlan {
 // Steps a pass over the blocks costs beyond its loads (the partial sums are written out and the
 // next pass's tasks are set up), in units of one load step: the weight given to the number of
 // passes when the K slicing is chosen.
-#ifndef RNNT_PASS_OVERHEAD
-#define RNNT_PASS_OVERHEAD 8
-#endif
-constexpr int kPassOverheadSteps = RNNT_PASS_OVERHEAD;
+constexpr int kPassOverheadSteps = 8;
 
 // groups_max: largest number of groups any rank owns in this stage.
 // Picks the number of K slices per group: groups_max * nks tasks run in passes ("slots") of

@@ -1,0 +1,92 @@
+// Host-only check of the stage planner and the weight packer (csrc/plan.h, csrc/pack.h), meant
+// to be built with AddressSanitizer and UndefinedBehaviorSanitizer and run by the CPU test
+// suite.  For a sweep of shapes and the three weight storages it packs a matrix whose entry
+// (col, k) encodes its own position, then walks the packed image the way the kernel's lanes
+// do and checks that every (col, k) of the matrix turns up exactly once, at the place the
+// plan says, and that everything else is zero.  Also checks e4m3_bits on all 256 codes.
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "pack.h"
+
+using namespace rnnt;
+
+static float e4m3_value(int code)
+{
+    const int s = code >> 7, e = (code >> 3) & 15, m = code & 7;
+    float v = e == 0 ? std::ldexp((float)m, -9) : std::ldexp(1.0f + m / 8.0f, e - 7);
+    return s ? -v : v;
+}
+
+int main()
+{
+    long checked = 0;
+    // e4m3: every finite code is a fixed point; the two NaN codes and values in between are refused
+    for (int code = 0; code < 256; ++code) {
+        if ((code & 0x7f) == 0x7f) continue;
+        uint8_t back = 0xff;
+        if (!e4m3_bits(e4m3_value(code), &back) || back != code) { std::printf("e4m3 code %d\n", code); return 1; }
+    }
+    uint8_t tmp;
+    if (e4m3_bits(0.3f, &tmp) || e4m3_bits(449.0f, &tmp) || e4m3_bits(480.0f, &tmp) ||
+        e4m3_bits(1e-9f, &tmp) || e4m3_bits(INFINITY, &tmp) || e4m3_bits(NAN, &tmp)) {
+        std::printf("e4m3 accepted a value outside the format\n");
+        return 1;
+    }
+    for (int wt = 0; wt < 3; ++wt)
+        for (int ts : {1, 3, 8, 32})
+            for (int K : {4, 20, 64, 100, 640})
+                for (int N : {1, 7, 64, 257, 1030}) {
+                    const int ng_all = (N + 3) / 4;
+                    auto ng_of = [&](int r) { return range_hi(r, ts, ng_all) - range_lo(r, ts, ng_all); };
+                    int gmax = 0;
+                    for (int r = 0; r < ts; ++r) gmax = std::max(gmax, ng_of(r));
+                    const StagePlan pl = make_stage_plan(K, gmax, wt);
+                    // values: small integers that are exact in every storage (e4m3 holds 0..15 exactly)
+                    std::vector<float> W((size_t)N * K);
+                    for (int c = 0; c < N; ++c)
+                        for (int k = 0; k < K; ++k) W[(size_t)c * K + k] = (float)(1 + (c * 7 + k * 3) % 15);
+                    const std::vector<uint32_t> img = pack_stage(
+                        pl, ts, ng_of, [&](int r, int g, int j) -> const float * {
+                            const int col = (range_lo(r, ts, ng_all) + g) * 4 + j;
+                            return col < N ? W.data() + (size_t)col * K : nullptr;
+                        });
+                    if (img.size() != (size_t)ts * pl.rank_stride * 4) { std::printf("size\n"); return 1; }
+                    std::vector<int> seen((size_t)N * K, 0);
+                    for (int rank = 0; rank < ts; ++rank)
+                        for (int wave = 0; wave < kWaves; ++wave)
+                            for (int slot = 0; slot < pl.slots; ++slot)
+                                for (int step = 0; step < pl.nsteps; ++step)
+                                    for (int lane = 0; lane < 64; ++lane) {
+                                        const uint32_t *q = img.data() + ((size_t)rank * pl.rank_stride +
+                                            ((size_t)(wave * pl.slots + slot) * pl.nsteps + step) * 64 + lane) * 4;
+                                        const int task = slot * kBlocksPerWg + wave * 16 + (lane >> 2);
+                                        const int g = task / pl.nks, ks = task % pl.nks;
+                                        const int col = (range_lo(rank, ts, ng_all) + g) * 4 + (lane & 3);
+                                        for (int c = 0; c < pl.kper; ++c) {
+                                            float v;
+                                            if (pl.kper == 4) { std::memcpy(&v, q + c, 4); }
+                                            else if (pl.kper == 8) {
+                                                const uint32_t bits = ((q[c >> 1] >> (16 * (c & 1))) & 0xffffu) << 16;
+                                                std::memcpy(&v, &bits, 4);
+                                            } else {
+                                                v = e4m3_value((q[c >> 2] >> (8 * (c & 3))) & 0xff);
+                                            }
+                                            const int k = (ks * pl.nsteps + step) * pl.kper + c;
+                                            const bool real_cell = task < ng_of(rank) * pl.nks && col < N && k < K;
+                                            if (!real_cell) {
+                                                if (v != 0.0f) { std::printf("padding not zero\n"); return 1; }
+                                                continue;
+                                            }
+                                            if (v != W[(size_t)col * K + k]) { std::printf("wrong value\n"); return 1; }
+                                            seen[(size_t)col * K + k]++;
+                                            ++checked;
+                                        }
+                                    }
+                    for (int v : seen)
+                        if (v != 1) { std::printf("wt %d ts %d K %d N %d: a weight appears %d times\n", wt, ts, K, N, v); return 1; }
+                }
+    std::printf("ok %ld\n", checked);
+    return 0;
+}

@@ -47,6 +47,44 @@ def test_status_strings_and_null_checks_need_no_gpu():
     assert lib.rnnt_engine_status(None, ctypes.byref(st)) == -1
 
 
+def test_create_refuses_unsupported_shapes_before_touching_the_device():
+    """The limits the header documents for rnnt_engine_create are checked on the host before any
+    HIP call: F not a multiple of 16 and V1 above 65 535 are RNNT_ERR_UNSUPPORTED, a layer count
+    or a blank index out of range and unknown flag bits are RNNT_ERR_SHAPE.  The weight pointers
+    are never dereferenced on these paths, so dummies do."""
+    import paper_2406_03791_amd as pkg
+    from paper_2406_03791_amd.binding import _ModelDesc
+    lib = pkg.load_library()
+
+    def create(flags=0, **dims):
+        d = _ModelDesc()
+        base = dict(F=64, E=8, H=8, L=1, J=8, V1=5, blank=4, D=0)
+        base.update(dims)
+        for k, v in base.items():
+            setattr(d, k, v)
+        L = max(1, min(int(base["L"]), 8))
+        fake = (ctypes.c_void_p * L)(*([0x1000] * L))
+        for key in ("w_ih", "w_hh", "b_ih", "b_hh"):
+            setattr(d, key, ctypes.cast(fake, ctypes.POINTER(ctypes.c_void_p)))
+        for key in ("emb", "w_enc", "b_enc", "w_pred", "b_pred", "w_out", "b_out"):
+            setattr(d, key, 0x1000)
+        dur = (ctypes.c_int32 * 8)(0, 1, 2, 3, 4, 5, 6, 7)
+        d.durations = ctypes.cast(dur, ctypes.POINTER(ctypes.c_int32))
+        out = ctypes.c_void_p()
+        return lib.rnnt_engine_create(ctypes.byref(d), 1, 1, flags, ctypes.byref(out))
+
+    assert create(F=17) == -5
+    assert create(F=24) == -5
+    assert create(V1=65536, blank=0) == -5
+    assert create(L=0) == -2 and create(L=5) == -2
+    assert create(blank=5) == -2 and create(blank=-1) == -2
+    assert create(D=9) == -2
+    assert create(flags=8) == -2
+    assert create(flags=pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS) == -2
+    assert "not supported" in pkg.rnnt_status_string(-5)
+    assert "scratch" in pkg.rnnt_status_string(-6)
+
+
 def test_stage_planner_covers_k_and_fits_the_blocks():
     """Host logic of the weight packer, re-stated: every (groups, K) choice must
     cover K with nks slices of nsteps 16-byte loads (4 fp32, 8 bf16 or 16 e4m3 weights each),

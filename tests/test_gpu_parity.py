@@ -196,6 +196,17 @@ def test_host_side_errors(pkg):
     with pytest.raises(pkg.RnntError) as ei:
         pkg.tdt_label_looping_decode(**args())
     assert ei.value.code == -3
+    # enc_out must be 16-byte aligned: a view that starts one float into a buffer is refused
+    flat = torch.zeros(enc.numel() + 4, dtype=torch.float32, device="cuda")
+    shifted = flat[1:1 + enc.numel()].view(enc.shape)
+    assert shifted.data_ptr() % 16 != 0
+    for fn in (pkg.rnnt_greedy_decode, pkg.rnnt_label_looping_decode, pkg.rnnt_label_looping_decode_noalloc):
+        with pytest.raises(pkg.RnntError) as ei:
+            fn(**args(enc_out=shifted))
+        assert ei.value.code == -2
+    with pytest.raises(pkg.RnntError) as ei:
+        pkg.rnnt_encoder_projection(eng.handle, shifted, ln, 1, w.T, torch.zeros(1, w.T, 64, device="cuda"))
+    assert ei.value.code == -2
     # a batch too large for the team layouts is refused when the engine is created
     w2 = synth.make_workload(2, B=1, T=8, len_lo=8, len_hi=8)
     with pytest.raises(pkg.RnntError) as ei:
@@ -345,7 +356,7 @@ def test_compact_weight_storage(pkg):
             eng.close()
     # unknown flag bits and both storage flags at once are refused
     w8 = dataclasses.replace(w32, model=synth.with_fp8_streamed_weights(w32.model))
-    for flags in (4, pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS):
+    for flags in (8, pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS):
         with pytest.raises(pkg.RnntError) as err:
             pkg.Engine(w8.model, w8.B, w8.T, flags=flags)
         assert err.value.code == -2
