@@ -110,6 +110,9 @@ def main() -> int:
                     help="storage of the streamed weights for the timed decoder; bf16 / fp8 decode "
                          "another model (the one with weights rounded to that format), so their "
                          "figures stand beside the fp32 headline, never for it")
+    ap.add_argument("--plain-launch", action="store_true",
+                    help="create the engines with RNNT_FLAG_PLAIN_LAUNCH (ordinary instead of "
+                         "cooperative launch): for runs under rocprofv3, see the header")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
                     help="time the chosen decoder only (profiler runs: one decode kernel per trace)")
@@ -163,6 +166,8 @@ def main() -> int:
                 "bf16": (synth.with_bf16_streamed_weights, pkg.RNNT_FLAG_BF16_WEIGHTS),
                 "fp8": (synth.with_fp8_streamed_weights, pkg.RNNT_FLAG_FP8_WEIGHTS)}[storage]
             w = dataclasses.replace(w, model=transform(w.model))
+        if args.plain_launch:
+            flags |= pkg.RNNT_FLAG_PLAIN_LAUNCH
         eng = pkg.Engine(w.model, w.B, w.T, flags=flags)
         enc = torch.from_numpy(w.enc_out).cuda().contiguous()
         ln = torch.from_numpy(w.enc_len).cuda()

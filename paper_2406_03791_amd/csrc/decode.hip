@@ -21,15 +21,18 @@ RNNT_DECLARE_NEST(f32); RNNT_DECLARE_NEST(bf16); RNNT_DECLARE_NEST(fp8);
 __global__ void reset_kernel(unsigned *bar, int n_bar, unsigned *abort_flag, int *status,
                              long long *stats, int n_stats, unsigned long long *part,
                              unsigned long long *dpart, unsigned long long *lpart, int n_part,
-                             unsigned long long *rowx,
-                             int n_rowx)
+                             unsigned long long *rowx, int n_rowx, unsigned long long *xh, int n_xh,
+                             unsigned long long *xq, int n_xq)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_bar) bar[i] = 0u;
-    if (i < n_stats) stats[i] = 0;
-    if (i < n_part) { part[i] = 0ull; dpart[i] = 0ull; lpart[i] = 0ull; }
-    if (i < n_rowx) rowx[i] = 0ull;
-    if (i == 0) { *abort_flag = 0u; *status = 0; }
+    const int i0 = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i0 < n_bar) bar[i0] = 0u;
+    if (i0 < n_stats) stats[i0] = 0;
+    if (i0 < n_part) { part[i0] = 0ull; dpart[i0] = 0ull; lpart[i0] = 0ull; }
+    if (i0 < n_rowx) rowx[i0] = 0ull;
+    if (i0 == 0) { *abort_flag = 0u; *status = 0; }
+    // the tagged hidden-vector and q words (the larger arrays): grid-stride
+    for (int i = i0; i < n_xh; i += gridDim.x * blockDim.x) xh[i] = 0ull;
+    for (int i = i0; i < n_xq; i += gridDim.x * blockDim.x) xq[i] = 0ull;
 }
 
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
@@ -38,9 +41,13 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     const int n_part = p.n_teams * p.groups * 2 * kMaxSamples * p.jteam_size;
     int n = n_bar > n_stats ? n_bar : n_stats;
     n = n > n_part ? n : n_part;
-    hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.bar, n_bar,
+    const int n_xh = p.fast_pred ? p.n_teams * p.L * kMaxRows * p.H : 0;
+    const int n_xq = p.fast_pred ? p.n_teams * kMaxRows * p.J : 0;
+    int blocks = (n + 255) / 256;
+    if (p.fast_pred && blocks < 256) blocks = 256;
+    hipLaunchKernelGGL(reset_kernel, dim3(blocks), dim3(256), 0, stream, p.bar, n_bar,
                        p.abort_flag, p.status, p.stats, n_stats, p.part, p.dpart, p.lpart, n_part, p.rowx,
-                       p.n_teams * 2 * kMaxRows);
+                       p.n_teams * 2 * kMaxRows, p.xh, n_xh, p.xq, n_xq);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // kernels are instantiated per loop nest, per row-group count of the prediction stages
@@ -51,9 +58,9 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     const int samples = rows_j * p.lookahead;
     const int rgj = joint_row_groups(samples);
     const int rgi = rg <= 1 ? 0 : (rg <= 2 ? 1 : 2);
-    // the LDS layout of the call was planned for rg_planned / kMaxSamples row groups: an instance
+    // the LDS layout of the call was planned for rg_planned row groups and samples_cap samples: an instance
     // that assumes more would write outside its regions
-    if (rows > kMaxRows || rg > p.rg_planned || samples > kMaxSamples) return hipErrorInvalidValue;
+    if (rows > kMaxRows || rg > p.rg_planned || samples > p.samples_cap) return hipErrorInvalidValue;
     typedef hipError_t (*Launch)(const DecodeParams &, int, hipStream_t);
     static const Launch table[3][2][3] = {
         {{launch_decode_f1_f32, launch_decode_f2_f32, launch_decode_f4_f32},

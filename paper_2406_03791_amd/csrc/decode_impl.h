@@ -31,6 +31,7 @@ struct Ctl {
     int s_k[kMaxSamples], s_d[kMaxSamples];
     float s_v[kMaxSamples], s_lp[kMaxSamples];   // maximum logit and its log-softmax value
     int R, ns, any, bar_ok, committed;
+    int f_any_active, f_need_pred, f_any_searching;   // loop decisions of the control wave
     int st_clamped, st_overflow;   // set to 1 by any thread (same value from all writers)
     int durations[kMaxDur];
 };
@@ -76,6 +77,7 @@ struct Wg {
 struct Sync {
     unsigned epoch;      // team barriers passed
     unsigned jepoch;     // joint steps taken by the team: tags the exchanged argmax partials
+    unsigned pepoch;     // prediction steps taken by the team: tags the exchanged hidden vectors
     long long polls;
 };
 
@@ -144,29 +146,30 @@ __device__ __forceinline__ bool team_barrier(const DecodeParams &p, const Wg &w,
 constexpr int kAhead = 2;
 
 struct WeightStream {
-    const float4 *wp;
+    const float4 *base;   // this wave's run of the current pass (uniform over the wave)
+    int lane_off;         // the lane's float4 inside a step's 64
     int task;
-    bool live;
     float4 q[kAhead][kStepUnroll];
 };
 
+// Start the weight stream of a stage for this wave: the first kAhead batches go out.  Every
+// lane loads, also one without a task: it reads along with lane (lane & 3) of the wave's first
+// block, which costs no extra traffic, and its products are never stored.  That keeps the
+// loads free of per-lane conditions.  The packed buffers end in a few steps of padding, so a
+// short stage's second batch may read past its last step.
 __device__ __forceinline__ void stream_begin(WeightStream &ws, const StageDev &sd, const Wg &w,
-                                             int rank, int n_tasks, int slot)
+                                             int rank, int n_tasks)
 {
     // a wave's passes ("slots") follow each other in memory, so its whole stage is one
     // contiguous run of slots * nsteps loads per lane
-    ws.task = slot * kBlocksPerWg + w.wave * 16 + (w.lane >> 2);
-    ws.live = ws.task < n_tasks;
-    ws.wp = sd.w + (long long)rank * sd.rank_stride +
-            ((long long)(w.wave * sd.slots + slot) * sd.nsteps) * 64 + w.lane;
+    ws.task = w.wave * 16 + (w.lane >> 2);
+    ws.lane_off = ws.task < n_tasks ? w.lane : (w.lane & 3);
+    ws.base = sd.w + (long long)rank * sd.rank_stride + ((long long)(w.wave * sd.slots) * sd.nsteps) * 64;
 #pragma unroll
     for (int a = 0; a < kAhead; ++a)
 #pragma unroll
-        for (int u = 0; u < kStepUnroll; ++u) {
-            const int step = a * kStepUnroll + u;
-            ws.q[a][u] = (ws.live && step < sd.nsteps * sd.slots) ? *(ws.wp + step * 64)
-                                                       : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int u = 0; u < kStepUnroll; ++u)
+            ws.q[a][u] = ws.base[ws.lane_off + (a * kStepUnroll + u) * 64];
 }
 
 // One dense stage for this rank:  red[task][rg][col][row] = sum over the task's
@@ -179,21 +182,22 @@ __device__ __forceinline__ void stream_begin(WeightStream &ws, const StageDev &s
 // kWeightBf16: a load carries eight bf16 weights, used as two part-steps of four; a bf16
 // weight becomes its fp32 value by a shift, the products and sums are fp32 as before.
 // kWeightFp8: sixteen e4m3 weights, four part-steps; one conversion instruction widens two.
+//   bias         LDS, the rank's slice of the stage's bias vector (4 per group), or nullptr:
+//                the accumulators of a group's first K slice start from it, as the sum the
+//                oracle forms does
 template <int RG, int WT>
-__device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int rank, int n_tasks,
+__device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n_tasks,
                                           WeightStream &ws, const float *x, int xstride,
                                           int x_inp_stride, int groups_per_inp, float *red,
-                                          bool red_aliases_x)
+                                          bool red_aliases_x, const float *bias = nullptr)
 {
     // two batches in flight: the hand-over of the batches at a pass boundary below is written
     // for that depth
     static_assert(kAhead == 2, "run_stage: the pass boundary assumes two batches in flight");
     static_assert(kMaxSamples <= 64, "the samples of a joint step are set up by one wave");
     const int r4 = w.lane & 3;
-    // The loads run through the passes without a break: a lane that has a task in the first
-    // pass keeps loading to the end of the stage (a pass in which it has none reads the zero
-    // padding of the packed weights), so the pipeline is never empty between passes.
-    const bool stream_live = ws.live;
+    // The loads run through the passes without a break (a lane without a task in a pass reads
+    // the zero padding of the packed weights), so the pipeline is never empty between passes.
     int left = sd.slots * sd.nsteps;                 // loads from the start of this pass to the end
     for (int slot = 0; slot < sd.slots; ++slot) {
         const int task = ws.task;
@@ -203,9 +207,11 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
         constexpr int KPER = WT == kWeightFp8 ? 16 : (WT == kWeightBf16 ? 8 : 4);
         constexpr int HALVES = KPER / 4;
         const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * KPER;
+        // lane r4 of a block accumulates output column r4 of the group for the block's four rows
+        const float b0 = (bias && live && ks == 0) ? bias[g * 4 + r4] : 0.f;
         v4f acc[RG];
 #pragma unroll
-        for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){0.f, 0.f, 0.f, 0.f};
+        for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){b0, b0, b0, b0};
         // activations of the step after the current one are fetched from LDS while the
         // current step's MFMAs issue; the scheduling barriers keep the compiler from
         // hoisting more LDS reads than that (they would occupy hundreds of registers)
@@ -258,10 +264,10 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
                             __builtin_amdgcn_sched_barrier(0);
                         }
                     }
-                    if (stream_live && i + kAhead * kStepUnroll < left) {
+                    if (i + kAhead * kStepUnroll < left) {
 #pragma unroll
                         for (int u = 0; u < kStepUnroll; ++u)
-                            ws.q[a][u] = *(ws.wp + (i + kAhead * kStepUnroll + u) * 64);
+                            ws.q[a][u] = ws.base[ws.lane_off + (i + kAhead * kStepUnroll + u) * 64];
                     }
                 }
             }
@@ -279,7 +285,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int r
         // refilled with two batches earlier, so when a pass ends on an odd batch the two
         // batches change roles.
         ws.task = task + kBlocksPerWg;
-        ws.wp += sd.nsteps * 64;
+        ws.base += sd.nsteps * 64;
         left -= sd.nsteps;
         if ((sd.nsteps & kStepUnroll) && slot + 1 < sd.slots) {
 #pragma unroll
@@ -307,7 +313,7 @@ __device__ __forceinline__ void reduce_tasks4(const float *red, int nks, int g, 
 __device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
 
 struct Lds {
-    float *xz, *red, *c, *part, *q;
+    float *xz, *red, *c, *part, *q, *hc;
     float *b_pred, *b_out, *b_lstm;   // this rank's slices of the bias vectors
 };
 
@@ -375,18 +381,234 @@ __device__ __forceinline__ void lstm_point(float gi, float gf, float gg, float g
     h_new = o_ * tanhf(c_new);
 }
 
+// value of the lane a DPP control pairs the caller with
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    const int i = (int)__float_as_uint(v);
+    return __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, false));
+}
+
+// ---- prediction step for teams of up to four utterances --------------------------------
+// Same arithmetic as prediction_step below, with two changes in how the hidden vectors
+// travel.  (1) Every work-group keeps a copy of all hidden vectors of the team's rows in its
+// LDS (committed and candidate, per layer): it reads every candidate vector anyway, as the
+// input of the next stage, so the recurrent stage of the next step reads nothing from memory.
+// (2) The exchanged values carry their step number: a work-group writes its slice as 64-bit
+// words (step tag, float bits) and the readers poll the words themselves until the tag is the
+// current step's, so a stage needs no barrier and no second round trip for the data.  A word
+// is rewritten once per step, and nobody can reach step n + 1's store of a word before every
+// work-group has read step n's (the stores of a stage need the complete input of the stage
+// before, which needs every work-group's stores of that stage, made after its reads of the
+// step before); the reset kernel clears the words, so a tag left by an earlier call is never
+// current.
+template <int NW>
+__device__ __forceinline__ bool poll_words(const DecodeParams &p, Sync &sy, const unsigned long long *const (&src)[NW],
+                                           unsigned tag, unsigned long long (&v)[NW])
+{
+    unsigned spins = 0;
+    bool ok = true;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) v[i] = src[i] ? xload64(src[i]) : ((unsigned long long)tag << 32);
+    for (;;) {
+        bool all = true;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) all = all && (unsigned)(v[i] >> 32) == tag;
+        if (all) break;
+        ++spins;
+        if ((spins & 127u) == 0 &&
+            __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            ok = false;
+            break;
+        }
+        if (spins > p.spin_limit) {
+            __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = false;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+        for (int i = 0; i < NW; ++i)
+            if ((unsigned)(v[i] >> 32) != tag) v[i] = xload64(src[i]);
+    }
+    sy.polls += spins;
+    if (!ok) c.bar_ok = 0;
+    return ok;
+}
+
+__device__ __forceinline__ unsigned long long tagged(float v, unsigned tag)
+{
+    return ((unsigned long long)tag << 32) | __float_as_uint(v);
+}
+
+// value of lane `Q` of the caller's quad (four adjacent lanes)
+template <int Q>
+__device__ __forceinline__ float quad_lane(float v) { return dpp_f32<Q * 0x55>(v); }
+
+template <int WT>
+__device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l)
+{
+    constexpr int RG = 1;
+    constexpr int KI = 2;                       // 64-bit words per row a thread polls: H, J <= 1024
+    const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
+    const int xs = p.xstride, R = c.R;
+    sy.pepoch += 1;
+    const unsigned tag = sy.pepoch;
+    const int r4 = w.lane & 3;
+    const int selr = r4 < R ? c.sel[r4] : 0;    // rows beyond R stay zero in either copy
+    float *hc = l.hc;                           // [2 selectors][L][4 rows][xs]
+    const long long lay_stride = 4 * xs;
+    // Candidate hidden vectors of layer `lay`, all rows: wait for every word, keep them in LDS.
+    auto receive_h = [&](int lay) -> bool {
+        const unsigned long long *base = p.xh + (((long long)w.team * p.L + lay) * kMaxRows) * p.H;
+        const unsigned long long *src[4 * KI];
+        unsigned long long v[4 * KI];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const int k = w.tid + i * kThreads;
+                src[r * KI + i] = (r < R && k < p.H) ? base + (long long)r * p.H + k : nullptr;
+            }
+        if (!poll_words<4 * KI>(p, sy, src, tag, v)) return false;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const int k = w.tid + i * kThreads;
+                if (r < R && k < p.H)
+                    hc[(((c.sel[r] ^ 1) * p.L + lay) * 4 + r) * xs + k] = __uint_as_float((unsigned)v[r * KI + i]);
+            }
+        return true;
+    };
+    // LSTM cell of (layer, unit u, row r) on the four lanes of a quad: lane j holds the
+    // pre-activation of gate j (input, forget, cell, output)
+    auto cell = [&](int layer, int u, int r, int j, float pre) {
+        const float act = j == 2 ? tanhf(pre) : sigmoidf_(pre);
+        const float i_ = quad_lane<0>(act), f_ = quad_lane<1>(act), g_ = quad_lane<2>(act), o_ = quad_lane<3>(act);
+        if (j == 0) {
+            const float cn = f_ * *c_slot(p, l, layer, c.sel[r], u, r) + i_ * g_;
+            const float hn = o_ * tanhf(cn);
+            *c_slot(p, l, layer, c.sel[r] ^ 1, u, r) = cn;
+            xstore64(p.xh + (((long long)w.team * p.L + layer) * kMaxRows + r) * p.H + u0 + u, tagged(hn, tag));
+        }
+    };
+    PROF_MARK(w, 18);
+    // stage 0: recurrent parts of every layer from the committed vectors in LDS
+    WeightStream ws;
+    stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks);
+    PROF_MARK(w, 0);
+    run_stage<RG, WT>(p.st0, w, p.L * nu * p.st0.nks, ws, hc + (long long)selr * p.L * lay_stride, xs,
+                      (int)lay_stride, nu > 0 ? nu : 1, l.red, false);
+    const int ng_all_p = (p.J + 3) / 4;
+    const int gp0 = range_lo(w.rank, p.team_size, ng_all_p);
+    const int ngp = range_hi(w.rank, p.team_size, ng_all_p) - gp0;
+    if (p.L > 1) stream_begin(ws, p.stl[1], w, w.rank, nu * p.stl[1].nks);
+    else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks);
+    __syncthreads();
+    PROF_MARK(w, 1);
+    for (int e4 = w.tid; e4 < p.L * nu * R * 4; e4 += kThreads) {
+        const int e = e4 >> 2, j = e4 & 3;
+        const int layer = e / (nu * R);
+        const int rem = e - layer * nu * R;
+        const int u = rem / R, r = rem - u * R;
+        const float *src = l.red + (layer * nu + u) * p.st0.nks * red_task_stride(RG) + j * 4 + r;
+        float a = 0.f;
+        for (int ks = 0; ks < p.st0.nks; ++ks) a += src[ks * red_task_stride(RG)];
+        if (layer == 0) {
+            a += p.T0[((long long)c.last[r] * p.H + (u0 + u)) * 4 + j];
+            cell(0, u, r, j, a);
+        } else {
+            l.part[((layer * p.nu_max + u) * p.rcap + r) * 4 + j] = a + l.b_lstm[(layer * p.nu_max + u) * 4 + j];
+        }
+    }
+    PROF_MARK(w, 2);
+    // stages 1..L-1: input part of layer `layer` from the candidate h of the layer below
+#pragma unroll
+    for (int layer = 1; layer < kMaxLayers; ++layer) {
+        if (layer >= p.L) break;
+        const StageDev &sd = p.stl[layer];
+        if (!receive_h(layer - 1)) return false;
+        __syncthreads();
+        PROF_MARK(w, 4);
+        run_stage<RG, WT>(sd, w, nu * sd.nks, ws, hc + ((long long)(selr ^ 1) * p.L + (layer - 1)) * lay_stride, xs,
+                          0, 1 << 30, l.red, false);
+        if (layer + 1 < kMaxLayers && layer + 1 < p.L)
+            stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
+                         nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks);
+        else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks);
+        __syncthreads();
+        PROF_MARK(w, 5);
+        for (int e4 = w.tid; e4 < nu * R * 4; e4 += kThreads) {
+            const int e = e4 >> 2, j = e4 & 3;
+            const int u = e / R, r = e - u * R;
+            const float *src = l.red + u * sd.nks * red_task_stride(RG) + j * 4 + r;
+            float a = 0.f;
+            for (int ks = 0; ks < sd.nks; ++ks) a += src[ks * red_task_stride(RG)];
+            a += l.part[((layer * p.nu_max + u) * p.rcap + r) * 4 + j];
+            cell(layer, u, r, j, a);
+        }
+        PROF_MARK(w, 6);
+    }
+    // prediction-side joint projection
+    if (!receive_h(p.L - 1)) return false;
+    __syncthreads();
+    PROF_MARK(w, 8);
+    run_stage<RG, WT>(p.spred, w, ngp * p.spred.nks, ws, hc + ((long long)(selr ^ 1) * p.L + (p.L - 1)) * lay_stride,
+                      xs, 0, 1 << 30, l.red, false);
+    __syncthreads();
+    PROF_MARK(w, 9);
+    for (int e4 = w.tid; e4 < ngp * R * 4; e4 += kThreads) {
+        const int e = e4 >> 2, j = e4 & 3;
+        const int g = e / R, r = e - g * R;
+        const float *src = l.red + g * p.spred.nks * red_task_stride(RG) + j * 4 + r;
+        float a = 0.f;
+        for (int ks = 0; ks < p.spred.nks; ++ks) a += src[ks * red_task_stride(RG)];
+        const int col = (gp0 + g) * 4 + j;
+        if (col < p.J)
+            xstore64(p.xq + ((long long)w.team * kMaxRows + r) * p.J + col, tagged(a + l.b_pred[g * 4 + j], tag));
+    }
+    PROF_MARK(w, 10);
+    {
+        // q of the rows this joint group searches for
+        const unsigned long long *src[4 * KI];
+        unsigned long long v[4 * KI];
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const int r = w.jg + i4 * p.groups, k = w.tid + i * kThreads;
+                src[i4 * KI + i] = (r < R && k < p.J) ? p.xq + ((long long)w.team * kMaxRows + r) * p.J + k : nullptr;
+            }
+        if (!poll_words<4 * KI>(p, sy, src, tag, v)) return false;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const int r = w.jg + i4 * p.groups, k = w.tid + i * kThreads;
+                if (r < R && k < p.J) l.q[i4 * p.qstride + k] = __uint_as_float((unsigned)v[i4 * KI + i]);
+            }
+    }
+    __syncthreads();
+    PROF_MARK(w, 12);
+    return c.bar_ok != 0;
+}
+
 // One prediction-network step for all rows of the team, from (last, committed
 // state) to the candidate state and q = W_pred h'_top + b_pred.
 template <int RG, int WT>
 __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l)
 {
+    if constexpr (RG == 1) {
+        if (p.fast_pred) return prediction_step_fast<WT>(p, w, sy, l);
+    }
     const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
     const int rows_pad = RG * 4;
     const int inp_stride = rows_pad * p.xstride;
     // stage 0: recurrent parts of every layer, layer 0 completes
     PROF_MARK(w, 18);
     WeightStream ws;
-    stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks, 0);
+    stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks);
     for (int layer = 0; layer < p.L; ++layer)
         fill_rows(p, w, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
     __syncthreads();
@@ -401,14 +623,14 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         if (layer == 0)
             pre = *reinterpret_cast<const float4 *>(p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
     }
-    run_stage<RG, WT>(p.st0, w, w.rank, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
+    run_stage<RG, WT>(p.st0, w, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
                   l.red, false);
     // the next stage's weights start moving while this one finishes and the team meets
     const int ng_all_p = (p.J + 3) / 4;
     const int gp0 = range_lo(w.rank, p.team_size, ng_all_p);
     const int ngp = range_hi(w.rank, p.team_size, ng_all_p) - gp0;
-    if (p.L > 1) stream_begin(ws, p.stl[1], w, w.rank, nu * p.stl[1].nks, 0);
-    else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks, 0);
+    if (p.L > 1) stream_begin(ws, p.stl[1], w, w.rank, nu * p.stl[1].nks);
+    else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks);
     __syncthreads();
     PROF_MARK(w, 1);
     for (int e = w.tid; e < p.L * nu * c.R; e += kThreads) {
@@ -443,11 +665,11 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
         __syncthreads();
         PROF_MARK(w, 4);
-        run_stage<RG, WT>(sd, w, w.rank, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        run_stage<RG, WT>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
         if (layer + 1 < kMaxLayers && layer + 1 < p.L)
             stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
-                         nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks, 0);
-        else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks, 0);
+                         nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks);
+        else stream_begin(ws, p.spred, w, w.rank, ngp * p.spred.nks);
         __syncthreads();
         PROF_MARK(w, 5);
         for (int e = w.tid; e < nu * c.R; e += kThreads) {
@@ -471,7 +693,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows(p, w, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
         __syncthreads();
         PROF_MARK(w, 8);
-        run_stage<RG, WT>(p.spred, w, w.rank, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        run_stage<RG, WT>(p.spred, w, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
         __syncthreads();
         PROF_MARK(w, 9);
         for (int e = w.tid; e < ng * c.R; e += kThreads) {
@@ -519,8 +741,60 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
     return true;
 }
 
-// An argmax partial as exchanged between the ranks of a team: logit bits, a 16-bit tag (the
-// joint step it belongs to, modulo 65536) and a 16-bit column index.  Readers poll a slot until
+// ---- argmax candidates as 64-bit keys -------------------------------------------------
+// A candidate (logit v, column idx) is packed so that an unsigned comparison orders by value
+// first and, among equal values, by the lower column: high word = the float's bits mapped to
+// an order-preserving unsigned (-0 is made +0 first), low 16 bits = 0xffff - idx.  Bits 16-31
+// carry the step tag while a key travels between work-groups and are zero otherwise.  Logits
+// have to be finite (a NaN would order above every number).
+__device__ __forceinline__ unsigned long long make_key(float v, int idx)
+{
+    const unsigned u = __float_as_uint(v + 0.0f);
+    const unsigned o = u ^ ((unsigned)((int)u >> 31) | 0x80000000u);
+    return ((unsigned long long)o << 32) | (unsigned)(0xffff - idx);
+}
+__device__ __forceinline__ float key_value(unsigned long long k)
+{
+    const unsigned o = (unsigned)(k >> 32);
+    return __uint_as_float(o ^ ((o >> 31) ? 0x80000000u : 0xffffffffu));
+}
+__device__ __forceinline__ int key_index(unsigned long long k) { return 0xffff - (int)(k & 0xffffu); }
+
+// max of the keys of a lane and of the lane a DPP control pairs it with
+// (0xB1: lane ^ 1, 0x4E: lane ^ 2, 0x141: mirror within 8 lanes, 0x140: mirror within 16)
+template <int CTRL>
+__device__ __forceinline__ unsigned long long key_max_dpp(unsigned long long k)
+{
+    const int lo = (int)(unsigned)k, hi = (int)(unsigned)(k >> 32);
+    const int olo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
+    const int ohi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+    const unsigned long long o = ((unsigned long long)(unsigned)ohi << 32) | (unsigned)olo;
+    return o > k ? o : k;
+}
+// max over groups of 8 (all 8 lanes get it) or 16 adjacent lanes
+__device__ __forceinline__ unsigned long long key_max8(unsigned long long k)
+{
+    k = key_max_dpp<0xB1>(k); k = key_max_dpp<0x4E>(k); return key_max_dpp<0x141>(k);
+}
+__device__ __forceinline__ unsigned long long key_max16(unsigned long long k)
+{
+    return key_max_dpp<0x140>(key_max8(k));
+}
+// log-sum-exp pairs (maximum m, sum s of exp(x - m)) combined the same way
+__device__ __forceinline__ void lse_merge(float &m, float &s, float om, float os)
+{
+    if (om > m) { s = s * expf(m - om) + os; m = om; }
+    else if (om > -INFINITY) s += os * expf(om - m);
+}
+template <int CTRL>
+__device__ __forceinline__ void lse_merge_dpp(float &m, float &s)
+{
+    const float om = dpp_f32<CTRL>(m), os = dpp_f32<CTRL>(s);
+    lse_merge(m, s, om, os);
+}
+
+// An argmax partial as exchanged between the ranks of a joint group: a key with the 16-bit tag
+// (the joint step it belongs to, modulo 65536) in bits 16-31.  Readers poll a slot until
 // its tag is the current step's, so the exchange needs no separate barrier.  Why a stale tag
 // can never equal the current one, however many joint steps a call takes: the slots of a step
 // are chosen by the parity of the step number, every rank rewrites all slots s < ns of that
@@ -529,21 +803,30 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
 // frames only).  So what a reader can find in a slot is the current step's word or the one
 // written two steps earlier, whose tag differs by 2 modulo 65536; the value 0 the reset kernel
 // leaves is only ever found before step 1 or 2 has been written, and those tags are 1 and 2.
-__device__ __forceinline__ unsigned long long pack_cand(float v, int idx, unsigned tag)
+__device__ __forceinline__ unsigned long long with_tag(unsigned long long key, unsigned tag)
 {
-    return ((unsigned long long)__float_as_uint(v) << 32) | ((tag & 0xffffu) << 16) |
-           ((unsigned)idx & 0xffffu);
+    return key | ((unsigned long long)(tag & 0xffffu) << 16);
+}
+__device__ __forceinline__ bool has_tag(unsigned long long word, unsigned tag)
+{
+    return (unsigned)((word >> 16) & 0xffffu) == (tag & 0xffffu);
 }
 
-// Poll one partial until it carries `tag`.  Bounded: gives up (and raises the abort flag) after
-// spin_limit polls or when another work-group has raised it.
-__device__ __forceinline__ unsigned long long wait_partial(const DecodeParams &p, Sync &sy,
-                                                           const unsigned long long *slot,
-                                                           unsigned tag)
+// Read up to four tagged words (slots base[r0], base[r0 + stride], ...; n of them) with all
+// loads in flight together, polling again only for those that are not there yet.  Bounded:
+// gives up (and raises the abort flag) after spin_limit polls or when another work-group has
+// raised it.  Tags are stripped from what is returned.
+__device__ __forceinline__ void wait_words4(const DecodeParams &p, Sync &sy, const unsigned long long *base,
+                                            int stride, int n, unsigned tag, unsigned long long (&out)[4])
 {
     unsigned spins = 0;
-    unsigned long long v = xload64(slot);
-    while ((unsigned)((v >> 16) & 0xffffu) != (tag & 0xffffu)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = i < n ? xload64(base + i * stride) : 0ull;
+    for (;;) {
+        bool all = true;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) all = all && (i >= n || has_tag(out[i], tag));
+        if (all) break;
         ++spins;
         if ((spins & 127u) == 0 &&
             __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
@@ -556,218 +839,261 @@ __device__ __forceinline__ unsigned long long wait_partial(const DecodeParams &p
             break;
         }
         __builtin_amdgcn_s_sleep(1);
-        v = xload64(slot);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i < n && !has_tag(out[i], tag)) out[i] = xload64(base + i * stride);
     }
     sy.polls += spins;
-    return v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] &= ~0xffff0000ull;
 }
 
 // Joint network + argmax for the c.ns samples listed in c.s_row / c.s_frame /
 // c.s_valid.  Leaves c.s_k, c.s_v (token argmax and its logit) and c.s_d
 // (duration index) for every valid sample.
 template <int RG, int WT>
-__device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l, int parity)
+__device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l)
 {
     const int ns = c.ns;
     const int rows_pad = RG * 4;
     const int kpad = p.sjoint.kpad;
     sy.jepoch += 1;
     const unsigned tag = sy.jepoch;
-    parity = (int)(tag & 1u);
+    const int parity = (int)(tag & 1u);
     const int ng_all = (p.NOUT + 3) / 4;
     const int g0 = range_lo(w.jrank, p.jteam_size, ng_all);
     const int ng = range_hi(w.jrank, p.jteam_size, ng_all) - g0;
     PROF_MARK(w, 18);
+    // z = relu(P[b, frame] + q[row]) for every sample.  Wave v builds the samples v, v + 8, ...,
+    // so a sample's row addresses are uniform over the wave; a lane takes four floats at k = 4 *
+    // (lane, lane + 64, lane + 128).  The loads of the projected frames go out first, then the
+    // first two batches of the weight stream (a wave's loads return in order and z is needed
+    // first), then z is formed and written to LDS.
     WeightStream ws;
-    // z = relu(P[b, frame] + q[row]) for every sample, four floats at a time; the loads of a
-    // batch are all issued before the first use.  The first batch of gathers goes out before
-    // the weight stream begins: a wave's loads return in order, and z is needed first.
     {
-        constexpr int NB = 6;
-        const int k4n = kpad >> 2;
-        const int total = rows_pad * k4n;
+        const int k4n = kpad >> 2;                 // float4 per z row, zero padding included
+        const int j4 = p.J >> 2;                   // whole float4 of a row
         const bool vec = (p.J & 3) == 0;
-        auto gather = [&](int base, float4 (&pe)[NB]) {
+        constexpr int SPW = (RG * 4 + kWaves - 1) / kWaves;    // samples per wave
+        float4 pe[SPW][3];
+        int valid[SPW], qoff[SPW];
 #pragma unroll
-            for (int u = 0; u < NB; ++u) {
-                const int idx = base + u * kThreads;
-                pe[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (idx < total) {
-                    const int s = idx / k4n, k = (idx - s * k4n) * 4;
-                    if (s < ns && k < p.J && c.s_valid[s]) {
-                        const int r = c.s_row[s];
-                        const float *pr = p.P + ((long long)c.b[r] * p.T + c.s_frame[s]) * p.J + k;
-                        if (vec) {
-                            pe[u] = *reinterpret_cast<const float4 *>(pr);
-                        } else {
-                            pe[u].x = pr[0];
-                            if (k + 1 < p.J) pe[u].y = pr[1];
-                            if (k + 2 < p.J) pe[u].z = pr[2];
-                            if (k + 3 < p.J) pe[u].w = pr[3];
-                        }
+        for (int i = 0; i < SPW; ++i) {
+            const int s = w.wave + i * kWaves;
+            valid[i] = 0; qoff[i] = 0;
+#pragma unroll
+            for (int u = 0; u < 3; ++u) pe[i][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (s < ns) valid[i] = __builtin_amdgcn_readfirstlane(c.s_valid[s]);
+            if (valid[i]) {
+                const int r = __builtin_amdgcn_readfirstlane(c.s_row[s]);
+                const int fr = __builtin_amdgcn_readfirstlane(c.s_frame[s]);
+                const int b = __builtin_amdgcn_readfirstlane(c.b[r]);
+                qoff[i] = p.q_in_lds ? (r / p.groups) * p.qstride : r;
+                const float *pr = p.P + ((long long)b * p.T + fr) * p.J;
+                if (vec) {
+#pragma unroll
+                    for (int u = 0; u < 3; ++u) {
+                        const int k4 = w.lane + 64 * u;
+                        if (64 * u < j4)       // uniform; lanes past the row read its first float4
+                            pe[i][u] = reinterpret_cast<const float4 *>(pr)[k4 < j4 ? k4 : 0];
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 3; ++u) {
+                        const int k = (w.lane + 64 * u) * 4;
+                        if (k < p.J) pe[i][u].x = pr[k];
+                        if (k + 1 < p.J) pe[i][u].y = pr[k + 1];
+                        if (k + 2 < p.J) pe[i][u].z = pr[k + 2];
+                        if (k + 3 < p.J) pe[i][u].w = pr[k + 3];
                     }
                 }
             }
-        };
-        auto combine = [&](int base, const float4 (&pe)[NB]) {
-#pragma unroll
-            for (int u = 0; u < NB; ++u) {
-                const int idx = base + u * kThreads;
-                if (idx < total) {
-                    const int s = idx / k4n, k = (idx - s * k4n) * 4;
-                    float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (s < ns && k < p.J && c.s_valid[s]) {
-                        const int r = c.s_row[s];
-                        float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (p.q_in_lds) {
-                            qv = *reinterpret_cast<const float4 *>(l.q + (r / p.groups) * p.qstride + k);
-                        } else {
-                            const float *qr = p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k;
-                            qv.x = xload(qr);
-                            if (k + 1 < p.J) qv.y = xload(qr + 1);
-                            if (k + 2 < p.J) qv.z = xload(qr + 2);
-                            if (k + 3 < p.J) qv.w = xload(qr + 3);
-                        }
-                        z.x = fmaxf(pe[u].x + qv.x, 0.f);
-                        if (k + 1 < p.J) z.y = fmaxf(pe[u].y + qv.y, 0.f);
-                        if (k + 2 < p.J) z.z = fmaxf(pe[u].z + qv.z, 0.f);
-                        if (k + 3 < p.J) z.w = fmaxf(pe[u].w + qv.w, 0.f);
-                    }
-                    *reinterpret_cast<float4 *>(l.xz + s * p.xstride + k) = z;
-                }
-            }
-        };
-        float4 pe[NB];
-        gather(w.tid, pe);
-        __builtin_amdgcn_sched_barrier(0);
-        stream_begin(ws, p.sjoint, w, w.jrank, ng * p.sjoint.nks, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        combine(w.tid, pe);
-        for (int base = w.tid + NB * kThreads; base < total; base += NB * kThreads) {
-            gather(base, pe);
-            combine(base, pe);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        stream_begin(ws, p.sjoint, w, w.jrank, ng * p.sjoint.nks);
+        __builtin_amdgcn_sched_barrier(0);
+        PROF_MARK(w, 22);
+#pragma unroll
+        for (int i = 0; i < SPW; ++i) {
+            const int s = w.wave + i * kWaves;
+            if (s >= rows_pad) break;
+            float *zrow = l.xz + s * p.xstride;
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                const int k4 = w.lane + 64 * u;
+                if (k4 >= k4n) break;
+                const int k = k4 * 4;
+                float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (valid[i] && k < p.J) {
+                    float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (p.q_in_lds) {
+                        qv = *reinterpret_cast<const float4 *>(l.q + qoff[i] + k);
+                    } else {
+                        const float *qr = p.qbuf + ((long long)w.team * kMaxRows + qoff[i]) * p.J + k;
+                        qv.x = xload(qr);
+                        if (k + 1 < p.J) qv.y = xload(qr + 1);
+                        if (k + 2 < p.J) qv.z = xload(qr + 2);
+                        if (k + 3 < p.J) qv.w = xload(qr + 3);
+                    }
+                    z.x = fmaxf(pe[i][u].x + qv.x, 0.f);
+                    if (k + 1 < p.J) z.y = fmaxf(pe[i][u].y + qv.y, 0.f);
+                    if (k + 2 < p.J) z.z = fmaxf(pe[i][u].z + qv.z, 0.f);
+                    if (k + 3 < p.J) z.w = fmaxf(pe[i][u].w + qv.w, 0.f);
+                }
+                *reinterpret_cast<float4 *>(zrow + k) = z;
+            }
+            // joint layers wider than 768: the rest of the row, loaded where it is used
+            for (int k4 = w.lane + 192; k4 < k4n; k4 += 64) {
+                const int k = k4 * 4;
+                float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (valid[i] && k < p.J) {
+                    const int sidx = w.wave + i * kWaves;
+                    const int r = c.s_row[sidx];
+                    const float *pr = p.P + ((long long)c.b[r] * p.T + c.s_frame[sidx]) * p.J + k;
+                    const float *qr = p.qbuf + ((long long)w.team * kMaxRows + r) * p.J + k;
+                    float pv[4], qv[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        pv[j] = k + j < p.J ? pr[j] : 0.f;
+                        qv[j] = k + j >= p.J ? 0.f : (p.q_in_lds ? l.q[qoff[i] + k + j] : xload(qr + j));
+                    }
+                    z = make_float4(fmaxf(pv[0] + qv[0], 0.f), k + 1 < p.J ? fmaxf(pv[1] + qv[1], 0.f) : 0.f,
+                                    k + 2 < p.J ? fmaxf(pv[2] + qv[2], 0.f) : 0.f,
+                                    k + 3 < p.J ? fmaxf(pv[3] + qv[3], 0.f) : 0.f);
+                }
+                *reinterpret_cast<float4 *>(zrow + k) = z;
+            }
+        }
+        PROF_MARK(w, 23);
     }
     __syncthreads();
     PROF_MARK(w, 13);
-    // with one slot the partial sums may overwrite z once every wave is done with it
+    // with one slot the partial sums may overwrite z once every wave is done with it; the
+    // output bias goes into the accumulators of every group's first K slice
     const bool alias = p.sjoint.slots == 1;
     float *red = alias ? l.xz : l.red;
-    run_stage<RG, WT>(p.sjoint, w, w.jrank, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias);
+    run_stage<RG, WT>(p.sjoint, w, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias, l.b_out);
     __syncthreads();
     PROF_MARK(w, 14);
-    // Per sample, this rank's best token column and best duration column.  GP
-    // adjacent lanes share a sample and each takes the groups gl, gl + GP, ...;
-    // groups ascend with the lane, so a strict > keeps the lowest index.
+    // Per sample, this rank's best token column and best duration column, in two steps through
+    // LDS.  First one thread per (sample, group of four columns): the K-slice partials are
+    // added and the best of the four columns becomes a key.  The keys go where nothing is
+    // live: into the partial-sum region when the sums sit in the z rows, else into the z rows.
+    unsigned long long *cand = reinterpret_cast<unsigned long long *>(alias ? l.red : l.xz);
+    unsigned long long *cand_d = cand + ns * ng;
+    float *rank_max = reinterpret_cast<float *>(cand + 2 * ns * ng);      // [ns], for the scores
     {
-        int gp = 1;
-        while (gp < ng && gp < 64) gp <<= 1;
-        for (int base = 0; base < ns * gp; base += kThreads) {
-            const int e = base + w.tid;
-            const int s = e / gp, gl = e - s * gp;
-            float bv = -INFINITY, dv = -INFINITY;
-            int bi = 0x7fffffff, di = 0x7fffffff;
-            if (s < ns) {
-                for (int g = gl; g < ng; g += gp) {
-                    float a[4];
-                    reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
+        int nsp = 1, lg = 0;
+        while (nsp < ns) { nsp <<= 1; ++lg; }
+        const int s = w.tid & (nsp - 1);
+        for (int g = w.tid >> lg; g < ng; g += kThreads >> lg) {
+            if (s >= ns) continue;
+            float a[4];
+            reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
+            unsigned long long kt = 0ull, kd = 0ull;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int col = (g0 + g) * 4 + j;
-                        if (col < p.NOUT) {
-                            const float v = a[j] + l.b_out[g * 4 + j];
-                            if (col < p.V1) { if (v > bv) { bv = v; bi = col; } }
-                            else { if (v > dv) { dv = v; di = col - p.V1; } }
-                        }
-                    }
-                }
+            for (int j = 0; j < 4; ++j) {
+                const int col = (g0 + g) * 4 + j;
+                if (col < p.V1) { const unsigned long long k = make_key(a[j], col); kt = k > kt ? k : kt; }
+                else if (col < p.NOUT) { const unsigned long long k = make_key(a[j], col - p.V1); kd = k > kd ? k : kd; }
             }
-            for (int off = 1; off < gp; off <<= 1) {
-                const float ov = __shfl_xor(bv, off);
-                const int oi = __shfl_xor(bi, off);
-                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-                const float od = __shfl_xor(dv, off);
-                const int oj = __shfl_xor(di, off);
-                if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
+            cand[s * ng + g] = kt;
+            if (p.D > 0) cand_d[s * ng + g] = kd;
+        }
+    }
+    __syncthreads();
+    PROF_MARK(w, 20);
+    // then eight adjacent lanes per sample scan the groups and publish the rank's partial
+    if (w.wave * 8 < ns) {
+        const int s = w.tid >> 3, sub = w.tid & 7;
+        unsigned long long kt = 0ull, kd = 0ull;
+        if (s < ns)
+            for (int g = sub; g < ng; g += 8) {
+                const unsigned long long k = cand[s * ng + g];
+                kt = k > kt ? k : kt;
+                if (p.D > 0) { const unsigned long long d = cand_d[s * ng + g]; kd = d > kd ? d : kd; }
             }
-            // log-softmax of the maximum, first half: this rank's sum of exp(logit - its own
-            // maximum) over its token columns (asked for only when the caller wants scores)
+        kt = key_max8(kt);
+        if (p.D > 0) kd = key_max8(kd);
+        if (s < ns && sub == 0) {
+            const long long o =
+                (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) * p.jteam_size + w.jrank;
+            xstore64(p.part + o, with_tag(kt, tag));
+            if (p.D > 0) xstore64(p.dpart + o, with_tag(kd, tag));
+            if (p.logps) rank_max[s] = kt ? key_value(kt) : -INFINITY;
+        }
+    }
+    if (p.logps) {
+        // log-softmax of the maximum, first half: this rank's sum of exp(logit - its own maximum)
+        // over its token columns (asked for only when the caller wants scores)
+        __syncthreads();
+        float *se_part = rank_max + kMaxSamples;          // [ns][ng]
+        int nsp = 1, lg = 0;
+        while (nsp < ns) { nsp <<= 1; ++lg; }
+        const int s = w.tid & (nsp - 1);
+        for (int g = w.tid >> lg; g < ng; g += kThreads >> lg) {
+            if (s >= ns) continue;
+            float a[4], se = 0.f;
+            reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((g0 + g) * 4 + j < p.V1) se += expf(a[j] - rank_max[s]);
+            se_part[s * ng + g] = se;
+        }
+        __syncthreads();
+        if (w.tid < ns) {
             float se = 0.f;
-            if (p.logps) {
-                if (s < ns) {
-                    for (int g = gl; g < ng; g += gp) {
-                        float a[4];
-                        reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int col = (g0 + g) * 4 + j;
-                            if (col < p.V1) se += expf(a[j] + l.b_out[g * 4 + j] - bv);
-                        }
-                    }
-                }
-                for (int off = 1; off < gp; off <<= 1) se += __shfl_xor(se, off);
-            }
-            if (s < ns && gl == 0) {
-                const long long o =
-                    (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) *
-                        p.jteam_size + w.jrank;
-                xstore64(p.part + o, pack_cand(bv, bi, tag));
-                if (p.D > 0) xstore64(p.dpart + o, pack_cand(dv, di, tag));
-                if (p.logps) xstore64(p.lpart + o, pack_cand(se, 0, tag));
-            }
+            for (int g = 0; g < ng; ++g) se += se_part[w.tid * ng + g];
+            const long long o =
+                (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + w.tid) * p.jteam_size + w.jrank;
+            // the sum travels as a float in the high word (it is positive: no key order needed)
+            xstore64(p.lpart + o, with_tag((unsigned long long)__float_as_uint(se) << 32, tag));
         }
     }
     PROF_MARK(w, 15);
-    // final argmax over the ranks, a few adjacent lanes per sample
-    {
-        constexpr int LPS = kThreads / kMaxSamples;   // lanes per sample
-        const int s = w.tid / LPS, sub = w.tid % LPS;
-        float bv = -INFINITY, dv = -INFINITY;
-        int bi = 0x7fffffff, di = 0x7fffffff;
-        // second half of the log-softmax: sum over the ranks of se_r * exp(m_r - M), kept as
-        // (running maximum lm, sum ls relative to it)
+    // final argmax over the ranks: sixteen adjacent lanes per sample, each with up to four
+    // ranks' partials in flight at a time
+    if (w.wave * 4 < ns) {
+        const int s = w.tid >> 4, sub = w.tid & 15;
+        const bool mine = s < ns && c.s_valid[s];
+        unsigned long long kt = 0ull, kd = 0ull;
         float lm = -INFINITY, ls = 0.f;
-        if (s < ns && c.s_valid[s]) {
+        if (mine) {
             const long long o =
                 (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) * p.jteam_size;
-            for (int r = sub; r < p.jteam_size; r += LPS) {
-                const unsigned long long pk = wait_partial(p, sy, p.part + o + r, tag);
-                const float v = __uint_as_float((unsigned)(pk >> 32));
-                const int i = (int)(pk & 0xffffu);
-                if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+            for (int r0 = sub; r0 < p.jteam_size; r0 += 64) {
+                const int n = min(4, (p.jteam_size - r0 + 15) >> 4);
+                unsigned long long wd[4];
+                wait_words4(p, sy, p.part + o + r0, 16, n, tag, wd);
                 if (p.logps) {
-                    const unsigned long long lk = wait_partial(p, sy, p.lpart + o + r, tag);
-                    const float se = __uint_as_float((unsigned)(lk >> 32));
-                    if (v > lm) { ls = ls * expf(lm - v) + se; lm = v; }
-                    else if (v > -INFINITY) ls += se * expf(v - lm);
-                }
-                if (p.D > 0) {
-                    const unsigned long long dk = wait_partial(p, sy, p.dpart + o + r, tag);
-                    const float d = __uint_as_float((unsigned)(dk >> 32));
-                    const int j = (int)(dk & 0xffffu);
-                    if (d > dv || (d == dv && j < di)) { dv = d; di = j; }
-                }
-            }
-        }
+                    unsigned long long wl[4];
+                    wait_words4(p, sy, p.lpart + o + r0, 16, n, tag, wl);
 #pragma unroll
-        for (int off = LPS / 2; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, LPS);
-            const int oi = __shfl_xor(bi, off, LPS);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-            const float od = __shfl_xor(dv, off, LPS);
-            const int oj = __shfl_xor(di, off, LPS);
-            if (od > dv || (od == dv && oj < di)) { dv = od; di = oj; }
-            if (p.logps) {
-                const float om = __shfl_xor(lm, off, LPS);
-                const float os = __shfl_xor(ls, off, LPS);
-                if (om > lm) { ls = ls * expf(lm - om) + os; lm = om; }
-                else if (om > -INFINITY) ls += os * expf(om - lm);
+                    for (int i = 0; i < 4; ++i)
+                        if (i < n && wd[i]) lse_merge(lm, ls, key_value(wd[i]), __uint_as_float((unsigned)(wl[i] >> 32)));
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) kt = wd[i] > kt ? wd[i] : kt;
+                if (p.D > 0) {
+                    wait_words4(p, sy, p.dpart + o + r0, 16, n, tag, wd);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) kd = wd[i] > kd ? wd[i] : kd;
+                }
             }
         }
-        if (s < ns && sub == 0) {
-            // no finite logit (NaN input inside enc_len): fall back to blank, never index out of range
+        kt = key_max16(kt);
+        if (p.D > 0) kd = key_max16(kd);
+        if (p.logps) {
+            lse_merge_dpp<0xB1>(lm, ls); lse_merge_dpp<0x4E>(lm, ls);
+            lse_merge_dpp<0x141>(lm, ls); lse_merge_dpp<0x140>(lm, ls);
+        }
+        if (mine && sub == 0) {
+            // no candidate at all cannot happen (every rank owns at least one token column or
+            // publishes key 0, and rank 0 always owns column 0); keep the index in range anyway
+            int bi = kt ? key_index(kt) : p.blank;
             if ((unsigned)bi >= (unsigned)p.V1) bi = p.blank;
-            c.s_k[s] = bi; c.s_v[s] = bv; c.s_d[s] = (p.D > 0 && di < p.D) ? di : 0;
+            const int di = (p.D > 0 && kd) ? key_index(kd) : 0;
+            c.s_k[s] = bi; c.s_v[s] = key_value(kt); c.s_d[s] = di < p.D ? di : 0;
             c.s_lp[s] = p.logps ? -logf(ls) : 0.f;      // the maximum is its own reference: logit - lm = 0
         }
     }
@@ -817,12 +1143,15 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 {
     extern __shared__ __align__(16) float dyn_lds[];
     Wg w;
-    w.tid = threadIdx.x; w.lane = w.tid & 63; w.wave = w.tid >> 6;
+    w.tid = threadIdx.x; w.lane = w.tid & 63;
+    // the wave index is the same for all lanes: telling the compiler keeps everything derived
+    // from it (task numbers, stream addresses) in scalar registers
+    w.wave = __builtin_amdgcn_readfirstlane(w.tid >> 6);
     if (p.spread) { w.rank = blockIdx.x % p.team_size; w.team = blockIdx.x / p.team_size; }
     else { w.team = blockIdx.x % p.n_teams; w.rank = blockIdx.x / p.n_teams; }
     w.jg = w.rank / p.jteam_size; w.jrank = w.rank - w.jg * p.jteam_size;
     Sync sy;
-    sy.epoch = 0; sy.jepoch = 0; sy.polls = 0;
+    sy.epoch = 0; sy.jepoch = 0; sy.pepoch = 0; sy.polls = 0;
 #ifdef RNNT_PROFILE
     if (w.tid == 0) {
         for (int i = 0; i < 24; ++i) g_prof[i] = 0;
@@ -831,7 +1160,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 #endif
     Lds l;
     l.xz = dyn_lds + p.lds_xz; l.red = dyn_lds + p.lds_red; l.c = dyn_lds + p.lds_c;
-    l.part = dyn_lds + p.lds_part; l.q = dyn_lds + p.lds_q;
+    l.part = dyn_lds + p.lds_part; l.q = dyn_lds + p.lds_q; l.hc = dyn_lds + p.lds_hc;
     l.b_pred = dyn_lds + p.lds_bias;
     l.b_out = l.b_pred + 4 * p.gp_max;
     l.b_lstm = l.b_out + 4 * p.gj_max;
@@ -895,6 +1224,8 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     // zero state: c of both selectors, committed h of this rank's units
     const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
     for (int i = w.tid; i < p.L * 2 * p.nu_max * p.rcap; i += kThreads) l.c[i] = 0.f;
+    if (p.fast_pred)     // the LDS copies of the hidden vectors: zero state, zero rows beyond R, zero K padding
+        for (int i = w.tid; i < 2 * p.L * 4 * p.xstride; i += kThreads) l.hc[i] = 0.f;
     for (int i = w.tid; i < p.L * R * nu; i += kThreads) {
         const int layer = i / (R * nu), rem = i - layer * R * nu;
         const int r = rem / nu, u = rem - r * nu;
@@ -922,7 +1253,6 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     if (ok && w.jrank == 0 && w.tid < R && w.tid % p.groups == w.jg && !c.active[w.tid]) finish_row(p, w.tid);
 
     long long n_pred = 0, n_joint = 0, n_samples = 0;
-    int parity = 0;
 
     if constexpr (VARIANT == kFrameLooping) {
         // Algorithm 1 on this team's rows.  A joint step also evaluates the next frames of
@@ -989,9 +1319,9 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                     }
                     if (w.tid == 0) c.ns = R * n_ahead;
                     __syncthreads();
-                    ok = joint_step<RGJ, WT>(p, w, sy, l, parity);      // logp = joint(f, g); k, v = logp.max()
+                    ok = joint_step<RGJ, WT>(p, w, sy, l);
                     if (!ok) break;
-                    parity ^= 1; ++n_joint; n_samples += R * n_ahead;
+                    ++n_joint; n_samples += R * n_ahead;
                     win0 = time_idx; win_n = n_ahead;
                 }
                 if (w.tid == 0) {
@@ -1023,12 +1353,29 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         if (rj > 0 && la * rj > RGJ * 4) la = RGJ * 4 / rj;   // the host sized RGJ for lookahead * rows
         if (la < 1) la = 1;
         unsigned outer = 0;
-        bool any_active = false;
-        for (int r = 0; r < R; ++r) any_active = any_active || c.active[r];
-        bool need_pred = true;
-        while (ok && any_active) {
+        // The loop control runs in the first wave only (lane j looks after the group's row j),
+        // between two work-group barriers; the other waves read its decisions from c.f_*.
+        // Samples of the next joint step: `la` consecutive frames of every searching row.
+        auto set_up_samples = [&]() {
+            const int s = w.lane, j = s / la, i = s - j * la;
+            int valid = 0, fr = 0, row = 0;
+            if (s < kMaxSamples && j < rj) {
+                row = g + j * G; fr = c.t[row] + i;
+                valid = c.searching[row] && fr < c.len[row];
+            }
+            if (s < kMaxSamples) { c.s_row[s] = row; c.s_frame[s] = fr; c.s_valid[s] = valid; }
+            const unsigned long long vmask = __ballot(valid != 0);
+            if (w.lane == 0) { c.ns = rj * la; n_samples += __popcll(vmask); }
+        };
+        if (w.wave == 0) {
+            int act = 0;
+            if (w.lane < R) act = c.active[w.lane];
+            if (w.lane == 0) { c.f_any_active = __ballot(act != 0) != 0ull; c.f_need_pred = 1; }
+        }
+        __syncthreads();
+        while (ok && c.f_any_active) {
             ++outer;
-            if (need_pred) {
+            if (c.f_need_pred) {
                 ok = prediction_step<RG, WT>(p, w, sy, l);
                 if (!ok) break;
                 ++n_pred;
@@ -1039,128 +1386,126 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 ok = team_barrier(p, w, sy);
                 if (!ok) break;
             }
-            if (w.tid < R) { c.searching[w.tid] = (w.tid % G == g) && c.active[w.tid]; c.emitted[w.tid] = 0; }
-            __syncthreads();
-            bool any_searching = false;
-            for (int j = 0; j < rj; ++j) any_searching = any_searching || c.searching[g + j * G];
             // A search is cut off after search_steps joint steps (0: never): rows that have
             // found their label go on to the next prediction step instead of waiting for a row
             // in a long run of blanks; that row keeps its state through the step (prediction()
             // of unchanged inputs gives the same g) and searches on afterwards.  When no row
             // of the team emitted, nothing changed and the prediction step is skipped.
             int steps_left = p.search_steps > 0 ? p.search_steps : 0x7fffffff;
-            while (ok && any_searching && steps_left-- > 0) {
-                if (w.tid < kMaxSamples) {
-                    const int s = w.tid, j = s / la, i = s - j * la;
-                    int valid = 0, fr = 0, row = 0;
-                    if (j < rj) {
-                        row = g + j * G; fr = c.t[row] + i;
-                        valid = c.searching[row] && fr < c.len[row];
-                    }
-                    c.s_row[s] = row; c.s_frame[s] = fr; c.s_valid[s] = valid;
-                    // statistics: the samples are all in the first wave, thread 0 keeps the count
-                    const unsigned long long vmask = __ballot(valid != 0);
-                    if (w.tid == 0) n_samples += __popcll(vmask);
+            if (w.wave == 0) {
+                int searching = 0;
+                if (w.lane < R) {
+                    searching = (w.lane % G == g) && c.active[w.lane];
+                    c.searching[w.lane] = searching; c.emitted[w.lane] = 0;
                 }
-                if (w.tid == 0) c.ns = rj * la;
-                __syncthreads();
-                ok = joint_step<RGJ, WT>(p, w, sy, l, parity);
+                const bool any = __ballot(searching != 0) != 0ull;
+                if (w.lane == 0) c.f_any_searching = any;
+                if (any) set_up_samples();
+            }
+            __syncthreads();
+            while (ok && c.f_any_searching && steps_left-- > 0) {
+                ok = joint_step<RGJ, WT>(p, w, sy, l);
                 if (!ok) break;
-                parity ^= 1; ++n_joint;
-                if (w.tid < rj && c.searching[g + w.tid * G]) {
-                    const int j = w.tid, r = g + j * G;
-                    int pos = 0, found = 0;
-                    while (pos < la && c.t[r] + pos < c.len[r]) {
-                        const int s = j * la + pos;
-                        const int k = c.s_k[s];
-                        const int dval = tdt ? c.durations[c.s_d[s]] : 0;
-                        if (k == p.blank) {
-                            pos += tdt ? max(dval, 1) : 1;
-                            c.n[r] = 0;
-                        } else {
-                            found = 1;
-                            c.hold_k[r] = k; c.hold_v[r] = c.s_v[s]; c.hold_lp[r] = c.s_lp[s]; c.hold_d[r] = dval;
-                            break;
+                ++n_joint;
+                if (w.wave == 0) {
+                    // lane j walks the results of the group's row j in frame order
+                    int still = 0;
+                    if (w.lane < rj && c.searching[g + w.lane * G]) {
+                        const int j = w.lane, r = g + j * G;
+                        int pos = 0, found = 0;
+                        while (pos < la && c.t[r] + pos < c.len[r]) {
+                            const int s = j * la + pos;
+                            const int k = c.s_k[s];
+                            const int dval = tdt ? c.durations[c.s_d[s]] : 0;
+                            if (k == p.blank) {
+                                pos += tdt ? max(dval, 1) : 1;
+                                c.n[r] = 0;
+                            } else {
+                                found = 1;
+                                c.hold_k[r] = k; c.hold_v[r] = c.s_v[s]; c.hold_lp[r] = c.s_lp[s]; c.hold_d[r] = dval;
+                                break;
+                            }
+                        }
+                        c.t[r] += pos;
+                        still = 1;
+                        if (found) { c.searching[r] = 0; still = 0; }
+                        else if (c.t[r] >= c.len[r]) {
+                            c.searching[r] = 0; c.active[r] = 0; still = 0;
+                            if (w.jrank == 0) finish_row(p, r);
                         }
                     }
-                    c.t[r] += pos;
-                    if (found) c.searching[r] = 0;
-                    else if (c.t[r] >= c.len[r]) {
-                        c.searching[r] = 0; c.active[r] = 0;
-                        if (w.jrank == 0) finish_row(p, r);
-                    }
+                    const bool any = __ballot(still != 0) != 0ull;
+                    if (w.lane == 0) c.f_any_searching = any;
+                    if (any && steps_left > 0) set_up_samples();
                 }
-                __syncthreads();
-                any_searching = false;
-                for (int j = 0; j < rj; ++j) any_searching = any_searching || c.searching[g + j * G];
                 __syncthreads();
             }
             if (!ok) break;
-            if (w.tid < rj && c.active[g + w.tid * G] && !c.searching[g + w.tid * G]) {
-                const int r = g + w.tid * G;
-                const int dval = c.hold_d[r];
-                emit_row(p, w, r, c.hold_k[r], c.t[r], c.hold_v[r], c.hold_lp[r], dval);
-                if (tdt && dval > 0) { c.t[r] += dval; c.n[r] = 0; }
-                else { c.n[r] += 1; if (c.n[r] == p.S) { c.t[r] += 1; c.n[r] = 0; } }
-                c.active[r] = c.t[r] < c.len[r];
-                c.emitted[r] = 1;
-                if (!c.active[r] && w.jrank == 0) finish_row(p, r);
-            }
-            __syncthreads();
             PROF_MARK(w, 16);
-            if (G > 1) {
-                // tell the other groups about this group's rows, learn about theirs
-                if (w.jrank == 0 && w.tid < rj) {
-                    const int r = g + w.tid * G;
-                    const unsigned payload = ((unsigned)c.last[r] & 0xffffu) |
-                                             ((unsigned)c.sel[r] << 16) | ((unsigned)c.active[r] << 17) |
-                                             ((unsigned)c.emitted[r] << 18);
-                    // two slots per row, by parity of the iteration: a group that runs ahead
-                    // writes the other slot, and reaches this one again only two iterations
-                    // later, after a team-wide meeting that every work-group enters only when
-                    // it has read this one
-                    xstore64(p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r,
-                             ((unsigned long long)outer << 32) | payload);
+            if (w.wave == 0) {
+                // rows that hold a label emit it and move on
+                if (w.lane < rj && c.active[g + w.lane * G] && !c.searching[g + w.lane * G]) {
+                    const int r = g + w.lane * G;
+                    const int dval = c.hold_d[r];
+                    emit_row(p, w, r, c.hold_k[r], c.t[r], c.hold_v[r], c.hold_lp[r], dval);
+                    if (tdt && dval > 0) { c.t[r] += dval; c.n[r] = 0; }
+                    else { c.n[r] += 1; if (c.n[r] == p.S) { c.t[r] += 1; c.n[r] = 0; } }
+                    c.active[r] = c.t[r] < c.len[r];
+                    c.emitted[r] = 1;
+                    if (!c.active[r] && w.jrank == 0) finish_row(p, r);
                 }
-                if (w.tid < R && w.tid % G != g) {
-                    const int r = w.tid;
-                    const unsigned long long *slot =
-                        p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r;
-                    unsigned spins = 0;
-                    unsigned long long v = xload64(slot);
-                    while ((unsigned)(v >> 32) != outer) {
-                        ++spins;
-                        if ((spins & 127u) == 0 &&
-                            __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                            c.bar_ok = 0;
-                            break;
-                        }
-                        if (spins > p.spin_limit) {
-                            __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            c.bar_ok = 0;
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
-                        v = xload64(slot);
+                if (G > 1) {
+                    // tell the other groups about this group's rows, learn about theirs
+                    if (w.jrank == 0 && w.lane < rj) {
+                        const int r = g + w.lane * G;
+                        const unsigned payload = ((unsigned)c.last[r] & 0xffffu) |
+                                                 ((unsigned)c.sel[r] << 16) | ((unsigned)c.active[r] << 17) |
+                                                 ((unsigned)c.emitted[r] << 18);
+                        // two slots per row, by parity of the iteration: a group that runs ahead
+                        // writes the other slot, and reaches this one again only two iterations
+                        // later, after a team-wide meeting that every work-group enters only when
+                        // it has read this one
+                        xstore64(p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r,
+                                 ((unsigned long long)outer << 32) | payload);
                     }
-                    sy.polls += spins;
-                    const unsigned payload = (unsigned)v;
-                    c.last[r] = (int)(payload & 0xffffu);
-                    c.sel[r] = (int)((payload >> 16) & 1u);
-                    c.active[r] = (int)((payload >> 17) & 1u);
-                    c.emitted[r] = (int)((payload >> 18) & 1u);
+                    if (w.lane < R && w.lane % G != g) {
+                        const int r = w.lane;
+                        const unsigned long long *slot =
+                            p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r;
+                        unsigned spins = 0;
+                        unsigned long long v = xload64(slot);
+                        while ((unsigned)(v >> 32) != outer) {
+                            ++spins;
+                            if ((spins & 127u) == 0 &&
+                                __hip_atomic_load(p.abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                                c.bar_ok = 0;
+                                break;
+                            }
+                            if (spins > p.spin_limit) {
+                                __hip_atomic_store(p.abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                c.bar_ok = 0;
+                                break;
+                            }
+                            __builtin_amdgcn_s_sleep(1);
+                            v = xload64(slot);
+                        }
+                        sy.polls += spins;
+                        const unsigned payload = (unsigned)v;
+                        c.last[r] = (int)(payload & 0xffffu);
+                        c.sel[r] = (int)((payload >> 16) & 1u);
+                        c.active[r] = (int)((payload >> 17) & 1u);
+                        c.emitted[r] = (int)((payload >> 18) & 1u);
+                    }
                 }
-                __syncthreads();
-                ok = c.bar_ok != 0;
-            }
-            PROF_MARK(w, 19);
-            any_active = false;
-            need_pred = false;
-            for (int r = 0; r < R; ++r) {
-                any_active = any_active || c.active[r];
-                need_pred = need_pred || c.emitted[r];
+                // the wave's own LDS writes above are visible to its lanes in program order
+                int act = 0, emi = 0;
+                if (w.lane < R) { act = c.active[w.lane]; emi = c.emitted[w.lane]; }
+                const bool any_act = __ballot(act != 0) != 0ull, any_emi = __ballot(emi != 0) != 0ull;
+                if (w.lane == 0) { c.f_any_active = any_act; c.f_need_pred = any_emi; }
             }
             __syncthreads();
+            ok = c.bar_ok != 0;
+            PROF_MARK(w, 19);
         }
     }
     // epilogue

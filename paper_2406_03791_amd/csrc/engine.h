@@ -40,6 +40,9 @@ struct DecodeParams {
     int lds_xz, lds_red, lds_c, lds_part, lds_bias, lds_q;
     int rcap;               // rows the LDS state buffers are laid out for (>= rows of any team)
     int rg_planned;         // row groups the activation rows and partial sums in LDS are sized for
+    int samples_cap;        // samples of a joint step the z rows and argmax candidates in LDS are sized for
+    int fast_pred;          // teams of up to 4 rows: hidden vectors kept in LDS, tagged exchange (no barriers)
+    int lds_hc;             // offset of the LDS copies of the hidden vectors [2][L][4][xstride]
     int q_in_lds;           // q = W_pred h + b_pred of the team's rows is kept in LDS
     int qstride;            // floats per q row in LDS
     unsigned lds_bytes;
@@ -64,6 +67,8 @@ struct DecodeParams {
     unsigned long long *dpart;    // same for durations
     unsigned long long *lpart;    // same layout: a rank's sum of exp(logit - its maximum)
     unsigned long long *rowx;     // [n_teams][2][kMaxRows]: row state published by the owning joint group
+    unsigned long long *xh;       // [n_teams][L][kMaxRows][H]: candidate hidden values as (step tag, float bits)
+    unsigned long long *xq;       // [n_teams][kMaxRows][J]: q the same way
     unsigned *bar;                // [n_teams * 32]: one counter per team, 128 B apart
     unsigned *abort_flag;
     int *status;

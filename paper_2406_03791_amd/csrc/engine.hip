@@ -75,6 +75,7 @@ struct Workspace {
     float *P = nullptr;                 // [B, T, J] projected frames
     float *hbuf = nullptr, *qbuf = nullptr;
     unsigned long long *part = nullptr, *dpart = nullptr, *lpart = nullptr, *rowx = nullptr;
+    unsigned long long *xh = nullptr, *xq = nullptr;
     unsigned *bar = nullptr, *abort_flag = nullptr;
     int *status = nullptr, *xcc = nullptr;
     long long *stats = nullptr;
@@ -82,17 +83,19 @@ struct Workspace {
 
 // Bytes of each part of the team workspace for a layout (everything but P).
 struct WorkspaceSizes {
-    size_t hbuf, qbuf, part, rowx, bar, stats, xcc;
+    size_t hbuf, qbuf, part, rowx, bar, stats, xcc, xh, xq;
 };
 
 struct TeamConfig {
     int n_teams = 0, team_size = 0, groups = 1, jteam_size = 0;
     PackedStage st0, stl[kMaxLayers], spred, sjoint;
-    DevBuf hbuf, qbuf, part, dpart, lpart, rowx, bar, stats, xcc;
+    DevBuf hbuf, qbuf, part, dpart, lpart, rowx, bar, stats, xcc, xh, xq;
     Workspace ws;          // the buffers above plus the engine's P, abort flag and status word
     int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
     int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
     int q_in_lds = 0, qstride = 0;
+    int fast_pred = 0, lds_hc = 0;
+    int samples_cap = kMaxSamples;   // (utterance, frame) pairs of a joint step the LDS layout has room for
     int rcap = 0;
     int rg_planned = 0;
     unsigned lds_bytes = 0;
@@ -131,7 +134,9 @@ namespace {
 int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups,
                  const std::function<const float *(int, int, int)> &row_of)
 {
-    const std::vector<uint32_t> host = pack_stage(ps.plan, ts, ngroups, row_of);
+    std::vector<uint32_t> host = pack_stage(ps.plan, ts, ngroups, row_of);
+    // the kernel's prefetch may run a few steps past the end of the last wave's run
+    host.resize(host.size() + (size_t)kAheadSteps * 64 * 4, 0u);
     HIP_TRY(ps.w.alloc(host.size() * sizeof(uint32_t)));
     HIP_TRY(hipMemcpy(ps.w.p, host.data(), host.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     return RNNT_OK;
@@ -148,6 +153,8 @@ WorkspaceSizes workspace_sizes(int n_teams, int ts, int groups, int L, int H, in
     z.bar = (size_t)n_teams * 32 * sizeof(unsigned);
     z.stats = (size_t)n_teams * kStatStride * sizeof(long long);
     z.xcc = (size_t)n_teams * ts * sizeof(int);
+    z.xh = (size_t)n_teams * L * kMaxRows * H * sizeof(unsigned long long);
+    z.xq = (size_t)n_teams * kMaxRows * J * sizeof(unsigned long long);
     return z;
 }
 
@@ -179,7 +186,12 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     // the prediction kernels exist for 1, 2 and 4 row groups (pred_row_groups): the layout is
     // sized for the instance that will run, not for the rows alone
     const int rgp = pred_row_groups(rows_max), rows_pad = rgp * 4;
-    const int rgj = kMaxSamples / 4;
+    // Samples a joint step may hold: rows of a joint group x frames examined per row (the
+    // configured lookahead, else 8; 16 is always allowed for), at most kMaxSamples.  The z rows
+    // and the argmax candidates in LDS are sized for it.
+    const int rows_j_max = (rows_max + groups - 1) / groups;
+    const int samples_cap = std::min(kMaxSamples, std::max(16, rows_j_max * (e->lookahead > 0 ? e->lookahead : 8)));
+    const int rgj = samples_cap / 4;
     int off = 0;
     auto take = [&](int n) { int o = off; off += (n + 3) & ~3; return o; };
     int xstride = 0;
@@ -195,17 +207,27 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         auto red_need = [&](const StagePlan &pl, int grp, int rg) {
             return std::min(grp * pl.nks, kBlocksPerWg * pl.slots) * red_task_stride(rg);
         };
-        int xz = std::max(L * rows_pad * xstride, kMaxSamples * xstride);
+        int xz = std::max(L * rows_pad * xstride, samples_cap * xstride);
         int red = red_need(t.st0.plan, L * nu_max, rgp);
         for (int l = 1; l < L; ++l) red = std::max(red, red_need(t.stl[l].plan, nu_max, rgp));
         red = std::max(red, red_need(t.spred.plan, gp_max, rgp));
-        if (t.sjoint.plan.slots == 1) xz = std::max(xz, red_need(t.sjoint.plan, gj_max, rgj));
-        else red = std::max(red, red_need(t.sjoint.plan, gj_max, rgj));
+        // the joint step's argmax candidates (two 64-bit keys per sample and output group, the
+        // per-sample maxima and the per-group exponential sums of the scores) go into the
+        // partial-sum region when the joint sums sit in the z rows, else into the z rows
+        const int cand_need = samples_cap * gj_max * 4 + kMaxSamples + samples_cap * gj_max + 8;
+        if (t.sjoint.plan.slots == 1) {
+            xz = std::max(xz, red_need(t.sjoint.plan, gj_max, rgj));
+            red = std::max(red, cand_need);
+        } else {
+            red = std::max(red, red_need(t.sjoint.plan, gj_max, rgj));
+            xz = std::max(xz, cand_need);
+        }
         off = 0;
         t.lds_xz = take(xz);
         t.lds_red = take(red);
         t.rcap = rows_max;
         t.rg_planned = rgp;
+        t.samples_cap = samples_cap;
         t.lds_c = take(L * 2 * nu_max * rows_max);
         t.lds_part = take(L * nu_max * rows_max * 4);
         t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
@@ -222,6 +244,13 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     // rewriting the global copy: they need the LDS copy
     if (groups > 1 && !t.q_in_lds) return RNNT_ERR_UNSUPPORTED;
     t.lds_q = t.q_in_lds ? take(q_rows * t.qstride) : 0;
+    // Teams of up to four utterances keep copies of all their hidden vectors in LDS and exchange
+    // them as tagged words (prediction_step_fast), when there is room and the widths fit the
+    // two words per row a thread polls.
+    const int hc_need = 2 * L * 4 * xstride;
+    t.fast_pred = rows_max <= 4 && t.q_in_lds && H <= 2 * kThreads && J <= 2 * kThreads &&
+                  (unsigned)(off + hc_need) * 4u + (unsigned)kStaticLds <= (unsigned)kLdsBytes;
+    t.lds_hc = t.fast_pred ? take(hc_need) : 0;
     t.lds_bytes = (unsigned)off * 4u;
     t.xstride = xstride; t.nu_max = nu_max; t.gj_max = gj_max; t.gp_max = gp_max;
 
@@ -262,6 +291,8 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     HIP_TRY(t.bar.alloc(z.bar));
     HIP_TRY(t.stats.alloc(z.stats));
     HIP_TRY(t.xcc.alloc(z.xcc));
+    HIP_TRY(t.xh.alloc(z.xh));
+    HIP_TRY(t.xq.alloc(z.xq));
     HIP_TRY(hipMemset(t.hbuf.p, 0, z.hbuf));
     HIP_TRY(hipMemset(t.qbuf.p, 0, z.qbuf));
     HIP_TRY(hipMemset(t.stats.p, 0, z.stats));
@@ -278,6 +309,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     t.ws.part = t.part.as<unsigned long long>(); t.ws.dpart = t.dpart.as<unsigned long long>();
     t.ws.lpart = t.lpart.as<unsigned long long>(); t.ws.rowx = t.rowx.as<unsigned long long>();
     t.ws.bar = t.bar.as<unsigned>(); t.ws.stats = t.stats.as<long long>(); t.ws.xcc = t.xcc.as<int>();
+    t.ws.xh = t.xh.as<unsigned long long>(); t.ws.xq = t.xq.as<unsigned long long>();
     return RNNT_OK;
 }
 
@@ -331,7 +363,7 @@ int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
     // next to its fixed cost, and 16 frames per step measured 2-3 % faster than 8 (slower from
     // four utterances on)
     if (e->lookahead == 0 && &t != &e->frame_cfg && B <= 2) la = 16;
-    if (la * rows > kMaxSamples) la = std::max(1, kMaxSamples / rows);
+    if (la * rows > t.samples_cap) la = std::max(1, t.samples_cap / rows);
     return la;
 }
 
@@ -407,8 +439,10 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
     p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
     p.lds_q = t.lds_q; p.q_in_lds = t.q_in_lds; p.qstride = t.qstride;
+    p.fast_pred = t.fast_pred; p.lds_hc = t.lds_hc;
     p.rcap = t.rcap;
     p.rg_planned = t.rg_planned;
+    p.samples_cap = t.samples_cap;
     p.spin_limit = 1u << 22;
     p.enc_len = enc_len; p.P = ws.P;
     p.tokens = tokens_out; p.tok_len = tok_len_out; p.frames = frames_out; p.logits = logit_out;
@@ -425,6 +459,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.part = ws.part; p.dpart = ws.dpart; p.lpart = ws.lpart; p.rowx = ws.rowx;
     p.bar = ws.bar; p.abort_flag = ws.abort_flag;
     p.status = ws.status; p.stats = ws.stats; p.xcc = ws.xcc;
+    p.xh = ws.xh; p.xq = ws.xq;
     e->last_B = B;
     e->last_cfg = &t;
     e->last_ws = ws;
@@ -572,6 +607,7 @@ int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_group
     if (n_teams > 0) {
         eng->last_cfg = nullptr;      // the workspace the last call's statistics live in goes away
         eng->last_ws = Workspace();
+        eng->lookahead = lookahead;   // the layouts are sized for it
         // plain teams for Algorithm 1; the label-looping decoders split each team further
         if (eng->n_wg % n_teams != 0) return RNNT_ERR_SHAPE;
         int rc = plan_and_pack(eng, eng->frame_cfg, n_teams, 1);
@@ -581,8 +617,21 @@ int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_group
             return rc;
         }
     }
+    const bool replan = n_teams == 0 && lookahead != eng->lookahead;
     eng->lookahead = lookahead;
     eng->search_steps = search_steps;
+    if (replan) {
+        // the LDS layouts are sized for the samples of a joint step, which depend on the lookahead
+        eng->last_cfg = nullptr;
+        eng->last_ws = Workspace();
+        int rc = plan_and_pack(eng, eng->frame_cfg, eng->frame_cfg.n_teams, 1);
+        if (!rc) rc = plan_and_pack(eng, eng->label_cfg, eng->label_cfg.n_teams, eng->label_cfg.groups);
+        if (rc) {
+            eng->lookahead = 0;
+            (void)default_layouts(eng);
+            return rc;
+        }
+    }
     return RNNT_OK;
 }
 
@@ -643,6 +692,7 @@ int rnnt_label_looping_decode_noalloc(rnnt_engine *eng, const float *enc_out, co
     const size_t o_h = take(z.hbuf), o_q = take(z.qbuf), o_p = take(z.part), o_d = take(z.part);
     const size_t o_l = take(z.part), o_r = take(z.rowx), o_b = take(z.bar), o_s = take(z.stats);
     const size_t o_x = take(z.xcc), o_a = take(sizeof(unsigned)), o_st = take(sizeof(int));
+    const size_t o_xh = take(z.xh), o_xq = take(z.xq);
     if (off > (size_t)RNNT_NOALLOC_SCRATCH_BYTES) return RNNT_ERR_SCRATCH;
     unsigned char *base = static_cast<unsigned char *>(eng->scratch);
     Workspace ws;
@@ -658,6 +708,8 @@ int rnnt_label_looping_decode_noalloc(rnnt_engine *eng, const float *enc_out, co
     ws.xcc = reinterpret_cast<int *>(base + o_x);
     ws.abort_flag = reinterpret_cast<unsigned *>(base + o_a);
     ws.status = reinterpret_cast<int *>(base + o_st);
+    ws.xh = reinterpret_cast<unsigned long long *>(base + o_xh);
+    ws.xq = reinterpret_cast<unsigned long long *>(base + o_xq);
     // the reset kernel the decode launch starts with clears the counters, flags, tags and
     // statistics the previous call left; the decode kernel zeroes the state rows it reads
     return run_decode(eng, kLabelLooping, enc_out, enc_len, B, T, max_symbols, tokens_out,
