@@ -33,6 +33,10 @@ def _lib(real: str):
             getattr(lib, name).argtypes = [C.c_void_p, C.c_void_p]
             getattr(lib, name).restype = C.c_int
         lib.orc_follow_sequential.restype = C.c_int
+        lib.orc_lstm_net_emulate_bf16.argtypes = [C.c_void_p]
+        lib.orc_lstm_net_emulate_bf16.restype = None
+        lib.orc_round_bf16.argtypes = [C.c_float if real == "float" else C.c_double]
+        lib.orc_round_bf16.restype = C.c_float if real == "float" else C.c_double
         _LIBS[real] = lib
     return _LIBS[real]
 
@@ -104,7 +108,9 @@ class Net:
 class LstmNet(Net):
     """Embedding + stacked LSTM prediction network and the additive joint."""
 
-    def __init__(self, model, real: str = "float"):
+    def __init__(self, model, real: str = "float", bf16: bool = False):
+        """bf16=True: bfloat16 emulation (weights and every input of a dense product rounded
+        to bfloat16, float accumulation), the reference of the engine's bfloat16 mode."""
         super().__init__(real)
         d = model.dims
         dt = self.dtype
@@ -130,6 +136,9 @@ class LstmNet(Net):
         self.state_size, self.g_size = 2 * d.L * d.H, d.H
         self.V1, self.D, self.blank, self.n_out = d.V1, d.D, d.blank, d.n_out
         self.durations = dur
+        self.bf16 = bool(bf16)
+        if bf16:
+            self.lib.orc_lstm_net_emulate_bf16(C.c_void_p(self.handle))
 
 
 class TableNet(Net):

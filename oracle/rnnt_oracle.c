@@ -31,6 +31,10 @@
  * for, its log-softmax value over the token columns (logps), which is the
  * score Algorithm 1 saves.
  *
+ * A net can be switched to bfloat16 emulation (orc_lstm_net_emulate_bf16: weights
+ * and every input of a dense product rounded to bfloat16, everything else as
+ * before), the reference of the engine's bfloat16 mode.
+ *
  * Arithmetic: every dot product is accumulated one term at a time in index
  * order, in the type REAL (float by default, double with -DREAL=double; build
  * with -ffp-contract=off so no fused multiply-add changes the rounding).
@@ -101,7 +105,24 @@ typedef struct {
     const real *b_pred;
     real *w_out_t;            /* [J][V1+D]                                    */
     const real *b_out;
+    int bf16;                 /* bf16 emulation: see orc_lstm_net_emulate_bf16 */
+    real *emb_rounded;        /* owned copy of emb with bf16 values, or NULL   */
 } lstm_ctx;
+
+/* Nearest bfloat16 value (8 exponent bits, 7 mantissa bits: the upper half of  */
+/* an IEEE float32), ties to even, of a value taken as float32; NaN and         */
+/* infinities pass through.                                                     */
+static real round_bf16(real v)
+{
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (real)f;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, sizeof u);
+    return (real)f;
+}
 
 static real *transpose_copy(const real *w, int n_out, int n_in)
 {
@@ -127,13 +148,26 @@ static void affine(const real *w_t, const real *bias, const real *x, int n_in,
     }
 }
 
+/* The same product with every input rounded to bfloat16 first (the weights    */
+/* were rounded when the mode was switched on).  A product of two bfloat16      */
+/* values is exact in float32, so only the additions round.                     */
+static void affine_in(const lstm_ctx *c, const real *w_t, const real *bias, const real *x,
+                      int n_in, int n_out, real *y)
+{
+    if (!c->bf16) { affine(w_t, bias, x, n_in, n_out, y); return; }
+    real *xr = (real *)malloc(sizeof(real) * (size_t)(n_in > 0 ? n_in : 1));
+    for (int i = 0; i < n_in; ++i) xr[i] = round_bf16(x[i]);
+    affine(w_t, bias, xr, n_in, n_out, y);
+    free(xr);
+}
+
 static real sigmoid_r(real v) { return (real)(1.0 / (1.0 + exp(-(double)v))); }
 static real tanh_r(real v) { return (real)tanh((double)v); }
 
 static void lstm_prep(const net_t *n, const real *x_row, real *p_row)
 {
     const lstm_ctx *c = (const lstm_ctx *)n->ctx;
-    affine(c->w_enc_t, c->b_enc, x_row, c->F, c->J, p_row);
+    affine_in(c, c->w_enc_t, c->b_enc, x_row, c->F, c->J, p_row);
 }
 
 /* state layout per utterance: for each layer l, h_l[H] then c_l[H].          */
@@ -144,15 +178,15 @@ static void lstm_pred(const net_t *n, int last_label, const real *state_in,
     const int H = c->H;
     real *a = (real *)malloc(sizeof(real) * 8 * (size_t)H);
     real *b = a + 4 * H;
-    const real *in = c->emb + (size_t)last_label * c->E;
+    const real *in = (c->emb_rounded ? c->emb_rounded : c->emb) + (size_t)last_label * c->E;
     int n_in = c->E;
     for (int l = 0; l < c->L; ++l) {
         const real *h = state_in + (size_t)l * 2 * H;
         const real *cc = h + H;
         real *h2 = state_out + (size_t)l * 2 * H;
         real *c2 = h2 + H;
-        affine(c->w_ih_t[l], c->b_ih[l], in, n_in, 4 * H, a);
-        affine(c->w_hh_t[l], c->b_hh[l], h, H, 4 * H, b);
+        affine_in(c, c->w_ih_t[l], c->b_ih[l], in, n_in, 4 * H, a);
+        affine_in(c, c->w_hh_t[l], c->b_hh[l], h, H, 4 * H, b);
         for (int j = 0; j < H; ++j) {
             const real gi = sigmoid_r(a[j] + b[j]);
             const real gf = sigmoid_r(a[H + j] + b[H + j]);
@@ -176,12 +210,12 @@ static void lstm_joint(const net_t *n, const real *p_row, const real *g,
     const int J = c->J;
     real *q = (real *)malloc(sizeof(real) * 2 * (size_t)J);
     real *z = q + J;
-    affine(c->w_pred_t, c->b_pred, g, c->H, J, q);
+    affine_in(c, c->w_pred_t, c->b_pred, g, c->H, J, q);
     for (int j = 0; j < J; ++j) {
         const real s = p_row[j] + q[j];
         z[j] = s > (real)0 ? s : (real)0;
     }
-    affine(c->w_out_t, c->b_out, z, J, c->V1 + c->D, logits);
+    affine_in(c, c->w_out_t, c->b_out, z, J, c->V1 + c->D, logits);
     free(q);
 }
 
@@ -222,6 +256,34 @@ net_t *orc_lstm_net_create(int F, int E, int H, int L, int J, int V1, int D,
     n->ctx = c;
     return n;
 }
+
+/* bfloat16 emulation (the paper's experiments run bfloat16 models, section on  */
+/* the experimental set-up): every weight matrix of a dense product -- the      */
+/* embedding table, W_ih and W_hh of every layer, W_enc, W_pred, W_out -- is     */
+/* rounded to bfloat16 once, and every vector that enters such a product (an     */
+/* encoder frame, an embedding row, a hidden vector, the joint's hidden vector)  */
+/* is rounded to bfloat16 at that point.  Products are then exact; sums, biases, */
+/* activations and the argmax stay in REAL as before.  This is what a decoder    */
+/* with bfloat16 operands and float32 accumulation computes, up to the order of  */
+/* the additions.  Not reversible.                                               */
+void orc_lstm_net_emulate_bf16(net_t *n)
+{
+    if (n->prep != lstm_prep) return;
+    lstm_ctx *c = (lstm_ctx *)n->ctx;
+    if (c->bf16) return;
+    c->bf16 = 1;
+    for (int l = 0; l < c->L; ++l) {
+        const size_t n_ih = (size_t)4 * c->H * (l == 0 ? c->E : c->H), n_hh = (size_t)4 * c->H * c->H;
+        for (size_t i = 0; i < n_ih; ++i) c->w_ih_t[l][i] = round_bf16(c->w_ih_t[l][i]);
+        for (size_t i = 0; i < n_hh; ++i) c->w_hh_t[l][i] = round_bf16(c->w_hh_t[l][i]);
+    }
+    for (size_t i = 0; i < (size_t)c->J * c->F; ++i) c->w_enc_t[i] = round_bf16(c->w_enc_t[i]);
+    for (size_t i = 0; i < (size_t)c->J * c->H; ++i) c->w_pred_t[i] = round_bf16(c->w_pred_t[i]);
+    for (size_t i = 0; i < (size_t)(c->V1 + c->D) * c->J; ++i) c->w_out_t[i] = round_bf16(c->w_out_t[i]);
+    c->emb_rounded = (real *)malloc(sizeof(real) * (size_t)c->V1 * c->E);
+    for (size_t i = 0; i < (size_t)c->V1 * c->E; ++i) c->emb_rounded[i] = round_bf16(c->emb[i]);
+}
+real orc_round_bf16(real v) { return round_bf16(v); }
 
 /* ------------------------------ table net -------------------------------- */
 /* x_row[0] carries the integer cell index (utterance * T + frame).  The      */
@@ -284,7 +346,7 @@ void orc_net_destroy(net_t *n)
         lstm_ctx *c = (lstm_ctx *)n->ctx;
         for (int l = 0; l < c->L; ++l) { free(c->w_ih_t[l]); free(c->w_hh_t[l]); }
         free(c->w_ih_t); free(c->w_hh_t); free((void *)c->b_ih); free((void *)c->b_hh);
-        free(c->w_enc_t); free(c->w_pred_t); free(c->w_out_t);
+        free(c->w_enc_t); free(c->w_pred_t); free(c->w_out_t); free(c->emb_rounded);
     }
     free(n->ctx);
     free((void *)n->durations);

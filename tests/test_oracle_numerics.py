@@ -452,3 +452,81 @@ def test_log_probabilities_of_emitted_labels():
     assert rf.tok_len[0] > 0 and np.array_equal(rf.tokens[0], rd.tokens[0])
     assert np.allclose(rf.logps[0], rd.logps[0], atol=1e-5)
     assert np.all(rf.logps[0] <= 0.0)
+
+
+def test_bf16_rounding_matches_torch():
+    """The oracle's bfloat16 rounding (ties to even on the float32 bit pattern) against torch's
+    conversion: random values over the whole exponent range, exact ties, subnormals, signs."""
+    lib = oracle._lib("float")
+    rng = np.random.default_rng(7)
+    vals = np.concatenate([
+        (rng.standard_normal(4000) * np.exp(rng.uniform(-80, 80, 4000))).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.3895314e38, 1e-40, -1e-40,
+                  65280.0, 65408.0, 0.1, -0.1, 2.0 ** -133], dtype=np.float32)])
+    want = torch.from_numpy(vals).to(torch.bfloat16).to(torch.float32).numpy()
+    got = np.array([lib.orc_round_bf16(float(v)) for v in vals], dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    # the generator's rounding (used to build bf16-valued models) is the same function
+    assert np.array_equal(synth.round_to_bf16(vals).view(np.uint32), want.view(np.uint32))
+
+
+def test_bf16_emulation_matches_rounded_operands_in_float64():
+    """bfloat16 emulation: each dense product of the three sub-networks equals the product of
+    the bfloat16-rounded weights and the bfloat16-rounded input, accumulated exactly (torch,
+    float64), plus the unrounded bias; everything else as in the float path.  A model whose
+    widths all differ, non-zero state, two layers."""
+    dims = synth.ModelDims(F=24, E=10, H=12, L=2, J=14, V1=9, durations=(0, 1, 2))
+    m = synth.make_model(dims, seed=11, weight_range=0.7)
+    bf = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float64)
+    f64 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64))
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(dims.F).astype(np.float32)
+    state = (rng.standard_normal(2 * dims.L * dims.H) * 0.5).astype(np.float32)
+    for real, tol in (("float", 3e-6), ("double", 1e-12)):
+        net = oracle.LstmNet(m, real, bf16=True)
+        plain = oracle.LstmNet(m, real)
+        dt = np.float32 if real == "float" else np.float64
+        # encoder-side projection
+        want_p = bf(m.w_enc) @ bf(x) + f64(m.b_enc)
+        got_p = net.prep(x.astype(dt))
+        assert np.allclose(got_p, want_p.numpy(), rtol=tol, atol=tol)
+        assert not np.allclose(got_p, plain.prep(x.astype(dt)), rtol=1e-4, atol=1e-4)   # the mode is on
+        # one prediction step from a non-zero state with label 3
+        H = dims.H
+        inp = bf(m.emb[3])
+        want_state = np.zeros_like(state, dtype=np.float64)
+        for l in range(dims.L):
+            h, cc = f64(state[2 * l * H:(2 * l + 1) * H]), f64(state[(2 * l + 1) * H:(2 * l + 2) * H])
+            gates = (bf(m.w_ih[l]) @ inp + f64(m.b_ih[l])) + (bf(m.w_hh[l]) @ bf(h.numpy()) + f64(m.b_hh[l]))
+            gi, gf, gg, go = (gates[j * H:(j + 1) * H] for j in range(4))
+            cn = torch.sigmoid(gf) * cc + torch.sigmoid(gi) * torch.tanh(gg)
+            hn = torch.sigmoid(go) * torch.tanh(cn)
+            want_state[2 * l * H:(2 * l + 1) * H] = hn.numpy()
+            want_state[(2 * l + 1) * H:(2 * l + 2) * H] = cn.numpy()
+            inp = bf(hn.numpy())        # the next layer's product rounds its input again
+        g, got_state = net.pred(3, state.astype(dt))
+        assert np.allclose(got_state, want_state, rtol=10 * tol, atol=10 * tol)
+        assert np.allclose(g, want_state[2 * (dims.L - 1) * H:(2 * dims.L - 1) * H], rtol=10 * tol, atol=10 * tol)
+        # joint
+        p_row = rng.standard_normal(dims.J).astype(dt)
+        gv = (rng.standard_normal(dims.H) * 0.5).astype(dt)
+        q = bf(m.w_pred) @ bf(gv) + f64(m.b_pred)
+        z = torch.relu(f64(p_row) + q)
+        want_l = bf(m.w_out) @ bf(z.numpy()) + f64(m.b_out)
+        assert np.allclose(net.joint(p_row, gv), want_l.numpy(), rtol=10 * tol, atol=10 * tol)
+
+
+def test_bf16_emulation_schedules_agree_and_differ_from_float():
+    for cfg, kw in [(1, dict(T=50, len_lo=20, len_hi=50)), (4, dict(B=4, T=50, len_lo=20, len_hi=50))]:
+        w = synth.make_workload(cfg, pad="nan", **kw)
+        net = oracle.LstmNet(w.model, bf16=True)
+        scheds = ["label", "seq"] if w.model.dims.D else ["frame", "label", "seq"]
+        rs = [oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, s, record=True) for s in scheds]
+        for r in rs[1:]:
+            assert_same(rs[0], r)
+        plain = oracle.decode(oracle.LstmNet(w.model), w.enc_out, w.enc_len, w.max_symbols, "seq")
+        assert rs[0].tok_len.sum() > 0
+        # same model, other arithmetic: the scores move by about a bfloat16 rounding step
+        diff = max(float(np.max(np.abs(a[:min(len(a), len(b))] - b[:min(len(a), len(b))]))) if len(a) and len(b) else 0.0
+                   for a, b in zip(rs[-1].scores, plain.scores))
+        assert diff > 1e-4
