@@ -142,6 +142,22 @@ typedef struct rnnt_stats {
 #define RNNT_FLAG_FP8_WEIGHTS 2
 
 /*
+ * rnnt_engine_create flag: bfloat16 mode (the precision the paper's experiments
+ * run in, section on the experimental set-up).  Any fp32 model is accepted.
+ * The weight matrices of all dense products -- embedding table, W_ih and W_hh of
+ * every layer, W_enc, W_pred, W_out -- are rounded to bfloat16 (ties to even)
+ * when the engine is created and the streamed ones are stored as bf16; every
+ * vector that enters a product (encoder frames, hidden vectors, the joint's
+ * hidden vector) is rounded to bfloat16 at that point.  Products are then exact
+ * in fp32; sums, biases, activations, logits and the argmax stay fp32.  The
+ * results are those of the fp32 engine on another arithmetic: token sequences
+ * may differ from the fp32 decode of the same model, and are exact against a
+ * reference that rounds at the same places (up to summation order).  Excludes
+ * the two storage flags (RNNT_ERR_SHAPE).
+ */
+#define RNNT_FLAG_BF16_ARITHMETIC 8
+
+/*
  * rnnt_engine_create flag: launch the decode kernel with an ordinary launch
  * instead of a cooperative one.  The kernel's teams synchronise among
  * themselves, which needs all work-groups resident at once; the cooperative
@@ -158,8 +174,9 @@ typedef struct rnnt_stats {
  * Create an engine for up to max_B utterances of up to max_T frames.
  * Copies and repacks the weights on the current device, allocates the
  * workspace (projected frames [max_B, max_T, J], state, exchange buffers).
- * flags: 0 or one of RNNT_FLAG_BF16_WEIGHTS / RNNT_FLAG_FP8_WEIGHTS, optionally
- * with RNNT_FLAG_PLAIN_LAUNCH; other bits are RNNT_ERR_SHAPE.
+ * flags: 0 or one of RNNT_FLAG_BF16_WEIGHTS / RNNT_FLAG_FP8_WEIGHTS /
+ * RNNT_FLAG_BF16_ARITHMETIC, optionally with RNNT_FLAG_PLAIN_LAUNCH; other bits
+ * are RNNT_ERR_SHAPE.
  * Limits of this implementation, checked here before anything is allocated
  * (RNNT_ERR_UNSUPPORTED): F must be a multiple of 16 (K tile of the projection
  * GEMM); V1 at most 65 535 (the argmax exchange carries a 16-bit column index);

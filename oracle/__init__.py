@@ -267,8 +267,10 @@ class Followed:
 
 def follow(net: Net, enc_out_b: np.ndarray, length: int, max_symbols: int,
            tokens: Sequence[int], frames: Sequence[int],
-           durs: Optional[Sequence[int]] = None, max_report: int = 64) -> Followed:
-    """Walk utterance b along a hypothesis; see follow_sequential in the C file."""
+           durs: Optional[Sequence[int]] = None, max_report: int = 64, tol: float = 0.0) -> Followed:
+    """Walk utterance b along a hypothesis; see follow_sequential in the C file.  tol > 0 (TDT):
+    the durations taken on blanks, which a hypothesis does not record, may be any whose logit
+    lies less than tol below the maximum, as long as the walk reaches the next label's frame."""
     x = np.ascontiguousarray(enc_out_b, dtype=net.dtype)
     T = int(x.shape[0])
     tk = np.ascontiguousarray(tokens, dtype=np.int32)
@@ -281,7 +283,7 @@ def follow(net: Net, enc_out_b: np.ndarray, length: int, max_symbols: int,
         C.c_void_p(net.handle), _ptr(x), C.c_int(T), C.c_int(int(length)),
         C.c_int(int(max_symbols)), _ptr(tk), _ptr(fr), _ptr(du), C.c_int(len(tk)),
         C.c_int(max_report), _ptr(rep[0]), _ptr(rep[1]), _ptr(rep[2]), _ptr(rep[3]),
-        _ptr(gap), _ptr(worst))
+        _ptr(gap), _ptr(worst), (C.c_float if net.real == "float" else C.c_double)(tol))
     where = [dict(t=int(rep[0][i]), u=int(rep[1][i]), want=int(rep[2][i]),
                   got=int(rep[3][i]), gap=float(gap[i]))
              for i in range(max(0, min(n, max_report)))]

@@ -753,14 +753,20 @@ int orc_decode_sequential(const net_t *net, decode_io *io)
 /* maximum the chosen logit lies.  Returns the number of such departures, or */
 /* -1 when the sequence cannot be produced by any walk (tokens left over,    */
 /* more than S labels on a frame, frames out of order).                      */
-/* For TDT the duration taken on a blank is not part of a hypothesis; the    */
-/* walk uses its own argmax duration there.                                  */
+/* For TDT the duration taken on a blank is not part of a hypothesis.  With  */
+/* tol = 0 the walk takes its own argmax duration there.  With tol > 0 it    */
+/* looks for the chain of blank evaluations that reaches the frame of the    */
+/* hypothesis' next label (or the end of the utterance) with the smallest    */
+/* worst gap, among chains whose blank and duration choices all lie less     */
+/* than tol below their maxima; the non-argmax choices on that chain are     */
+/* reported like any other departure.  If there is no such chain it falls    */
+/* back to the argmax durations.                                             */
 /* ------------------------------------------------------------------------ */
 int orc_follow_sequential(const net_t *net, const real *x_b, int T, int len,
                           int S, const int32_t *tokens, const int32_t *frames,
                           const int32_t *durs, int n_tok, int max_report,
                           int32_t *rep_t, int32_t *rep_u, int32_t *rep_want,
-                          int32_t *rep_got, real *rep_gap, real *worst_gap)
+                          int32_t *rep_got, real *rep_gap, real *worst_gap, real tol)
 {
     const int SS = net->state_size, GS = net->g_size, V1 = net->V1, D = net->D;
     const int blank = net->blank;
@@ -774,7 +780,79 @@ int orc_follow_sequential(const net_t *net, const real *x_b, int T, int len,
     int t = 0, n = 0, u = 0, last = blank, departures = 0, bad = 0;
     *worst_gap = 0;
     if (len > 0) net->pred(net, last, state, state_prime, g);
+    /* blank chains of TDT (tol > 0): best[t'] = smallest worst gap of a chain from the     */
+    /* current frame to t', from_[t'] / how_[t'] = the step that achieves it                */
+    real *best = (real *)malloc(sizeof(real) * (size_t)(len + 2));
+    int *from_ = (int *)malloc(sizeof(int) * (size_t)(len + 2));
+    int *how_ = (int *)malloc(sizeof(int) * (size_t)(len + 2));
+    real *gap_b = (real *)malloc(sizeof(real) * (size_t)(len + 2));
+    real *gap_d = (real *)malloc(sizeof(real) * (size_t)(len + 2));
+    int *want_b = (int *)malloc(sizeof(int) * (size_t)(len + 2));
+    int *want_d = (int *)malloc(sizeof(int) * (size_t)(len + 2));
     while (t < len) {
+        if (D > 0 && tol > (real)0 && !(u < n_tok && frames[u] == t)) {
+            /* the hypothesis has a blank here: find the chain of blanks to its next label */
+            const int target = (u < n_tok && frames[u] < len) ? frames[u] : len;   /* len = any frame >= len */
+            if (u < n_tok && (frames[u] < t || frames[u] >= len)) { bad = 1; break; }
+            for (int i = t; i <= len; ++i) { best[i] = (real)-1; from_[i] = -1; }
+            best[t] = 0;
+            for (int a = t; a < len && a < target; ++a) {
+                if (best[a] < 0) continue;
+                net->prep(net, x_b + (size_t)a * net->x_size, p);
+                net->joint(net, p, g, logits);
+                real v2, m2, dv2, dm2;
+                const int k2 = argmax_margin(logits, 0, V1, &v2, &m2);
+                const int d2 = argmax_margin(logits, V1, V1 + D, &dv2, &dm2) - V1;
+                const real gb = v2 - logits[blank];
+                gap_b[a] = gb; want_b[a] = k2; want_d[a] = d2;
+                if (!(gb < tol)) continue;                    /* blank is no near-maximum here */
+                for (int i = 0; i < D; ++i) {
+                    const real gd = dv2 - logits[V1 + i];
+                    if (!(gd < tol)) continue;
+                    int to = a + (net->durations[i] > 1 ? net->durations[i] : 1);
+                    if (to > len) to = len;
+                    if (to > target) continue;                /* would skip the next label's frame */
+                    real worst = best[a] > gb ? best[a] : gb;
+                    if (gd > worst) worst = gd;
+                    if (best[to] < 0 || worst < best[to]) { best[to] = worst; from_[to] = a; how_[to] = i; }
+                }
+            }
+            if (best[target] >= 0) {
+                /* report the non-argmax choices of the chain, in frame order */
+                int chain[4096], nc = 0;
+                for (int a = target; a != t && nc < 4096; a = from_[a]) chain[nc++] = a;
+                for (int i = nc - 1; i >= 0; --i) {
+                    const int to = chain[i], a = from_[to];
+                    /* duration gap of the step a -> to: recompute from the stored choice */
+                    net->prep(net, x_b + (size_t)a * net->x_size, p);
+                    net->joint(net, p, g, logits);
+                    real dv2, dm2;
+                    (void)argmax_margin(logits, V1, V1 + D, &dv2, &dm2);
+                    gap_d[a] = dv2 - logits[V1 + how_[to]];
+                    if (gap_b[a] > 0) {
+                        if (departures < max_report) {
+                            rep_t[departures] = a; rep_u[departures] = u;
+                            rep_want[departures] = want_b[a]; rep_got[departures] = blank;
+                            rep_gap[departures] = gap_b[a];
+                        }
+                        departures++;
+                        if (gap_b[a] > *worst_gap) *worst_gap = gap_b[a];
+                    }
+                    if (gap_d[a] > 0) {
+                        if (departures < max_report) {
+                            rep_t[departures] = a; rep_u[departures] = u;
+                            rep_want[departures] = V1 + want_d[a]; rep_got[departures] = V1 + how_[to];
+                            rep_gap[departures] = gap_d[a];
+                        }
+                        departures++;
+                        if (gap_d[a] > *worst_gap) *worst_gap = gap_d[a];
+                    }
+                }
+                t = target; n = 0;
+                continue;
+            }
+            /* no chain within tol: take the argmax durations below and report what that gives */
+        }
         net->prep(net, x_b + (size_t)t * net->x_size, p);
         net->joint(net, p, g, logits);
         real v, mg, dv = 0, dmg = 0;
@@ -827,5 +905,6 @@ int orc_follow_sequential(const net_t *net, const real *x_b, int T, int len,
     }
     if (u != n_tok) bad = 1;
     free(state); free(state_prime); free(g); free(p); free(logits);
+    free(best); free(from_); free(how_); free(gap_b); free(gap_d); free(want_b); free(want_d);
     return bad ? -1 : departures;
 }

@@ -77,7 +77,7 @@ static int run_case(int F, int E, int H, int L, int J, int V1, int D, int B, int
                 int clamped = len[b] < 0 ? 0 : (len[b] > T ? T : len[b]);
                 int dep = orc_follow_sequential(net, x + (size_t)b * T * F, T, clamped, S,
                                                 io.tokens + (size_t)b * cap, io.frames + (size_t)b * cap,
-                                                io.durs + (size_t)b * cap, n, 4, rt, ru, rw, rg, gap, &worst);
+                                                io.durs + (size_t)b * cap, n, 4, rt, ru, rw, rg, gap, &worst, (real)(b & 1 ? 0.05 : 0));
                 if (io.tok_len[b] <= cap && dep != 0) bad = 1;
             }
         }

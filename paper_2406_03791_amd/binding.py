@@ -28,6 +28,7 @@ EXPORTS = (
 RNNT_FLAG_BF16_WEIGHTS = 1
 RNNT_FLAG_FP8_WEIGHTS = 2
 RNNT_FLAG_PLAIN_LAUNCH = 4
+RNNT_FLAG_BF16_ARITHMETIC = 8
 
 
 class RnntError(RuntimeError):

@@ -61,6 +61,17 @@ __device__ __forceinline__ unsigned long long xload64(const unsigned long long *
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// bfloat16 mode: a value that enters a product is rounded to the nearest bfloat16 value (ties to
+// even; NaN and infinities pass through) and kept as a float; other modes leave it alone.
+template <int WT>
+__device__ __forceinline__ float as_operand(float v)
+{
+    if (WT != kWeightBf16Arith) return v;
+    unsigned u = __float_as_uint(v);
+    if ((u & 0x7f800000u) != 0x7f800000u) { u += 0x7fffu + ((u >> 16) & 1u); u &= 0xffff0000u; }
+    return __uint_as_float(u);
+}
+
 // Read-modify-write atomics are issued on pointers typed as global memory: on a generic
 // pointer the compiler has to add a run-time test for the private aperture.
 typedef __attribute__((address_space(1))) unsigned global_u32;
@@ -204,7 +215,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         const bool live = task < n_tasks;
         const int g = live ? task / sd.nks : 0;
         const int ks = live ? task - g * sd.nks : 0;
-        constexpr int KPER = WT == kWeightFp8 ? 16 : (WT == kWeightBf16 ? 8 : 4);
+        constexpr int KPER = WT == kWeightFp8 ? 16 : ((WT == kWeightBf16 || WT == kWeightBf16Arith) ? 8 : 4);
         constexpr int HALVES = KPER / 4;
         const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * KPER;
         // lane r4 of a block accumulates output column r4 of the group for the block's four rows
@@ -239,7 +250,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
                                 xb[rg] = *reinterpret_cast<const float4 *>(
                                     xr + rg * 4 * xstride + ((i + u) * HALVES + h + 1) * 4);
                             float4 wv;
-                            if (WT == kWeightBf16) {
+                            if (WT == kWeightBf16 || WT == kWeightBf16Arith) {
                                 const unsigned lo = __float_as_uint(h == 0 ? raw.x : raw.z);
                                 const unsigned hi = __float_as_uint(h == 0 ? raw.y : raw.w);
                                 wv = make_float4(__uint_as_float(lo << 16), __uint_as_float(lo & 0xffff0000u),
@@ -332,6 +343,7 @@ __device__ __forceinline__ float *h_slot(const DecodeParams &p, int team, int se
 // Fill RG*4 activation rows of `len` floats each into LDS from a global exchange
 // buffer; the tail up to kpad and the rows beyond R are zero.  Loads are issued
 // in batches so that their latencies overlap.
+template <int WT>
 __device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, float *dst,
                                           int rows_pad, int len, int kpad, int layer, bool candidate)
 {
@@ -367,7 +379,8 @@ __device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, fl
             const int idx = base + u * kThreads;
             if (idx < total) {
                 const int r = idx / kp2, k = (idx - r * kp2) * 2;
-                *reinterpret_cast<float2 *>(dst + r * p.xstride + k) = v[u];
+                *reinterpret_cast<float2 *>(dst + r * p.xstride + k) =
+                    make_float2(as_operand<WT>(v[u].x), as_operand<WT>(v[u].y));
             }
         }
     }
@@ -477,7 +490,8 @@ __device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, cons
             for (int i = 0; i < KI; ++i) {
                 const int k = w.tid + i * kThreads;
                 if (r < R && k < p.H)
-                    hc[(((c.sel[r] ^ 1) * p.L + lay) * 4 + r) * xs + k] = __uint_as_float((unsigned)v[r * KI + i]);
+                    hc[(((c.sel[r] ^ 1) * p.L + lay) * 4 + r) * xs + k] =
+                        as_operand<WT>(__uint_as_float((unsigned)v[r * KI + i]));
             }
         return true;
     };
@@ -610,7 +624,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
     WeightStream ws;
     stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks);
     for (int layer = 0; layer < p.L; ++layer)
-        fill_rows(p, w, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
+        fill_rows<WT>(p, w, l.xz + layer * inp_stride, rows_pad, p.H, p.st0.kpad, layer, false);
     __syncthreads();
     // the additive term of this thread's first epilogue item (embedding term of layer 0,
     // bias of the layers above) is fetched before the product so its latency is hidden
@@ -662,7 +676,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
     for (int layer = 1; layer < kMaxLayers; ++layer) {
         if (layer >= p.L) break;
         const StageDev &sd = p.stl[layer];
-        fill_rows(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
+        fill_rows<WT>(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
         __syncthreads();
         PROF_MARK(w, 4);
         run_stage<RG, WT>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
@@ -690,7 +704,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
     // prediction-side joint projection
     {
         const int g0 = gp0, ng = ngp;
-        fill_rows(p, w, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
+        fill_rows<WT>(p, w, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
         __syncthreads();
         PROF_MARK(w, 8);
         run_stage<RG, WT>(p.spred, w, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
@@ -940,7 +954,8 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
                     if (k + 2 < p.J) z.z = fmaxf(pe[i][u].z + qv.z, 0.f);
                     if (k + 3 < p.J) z.w = fmaxf(pe[i][u].w + qv.w, 0.f);
                 }
-                *reinterpret_cast<float4 *>(zrow + k) = z;
+                *reinterpret_cast<float4 *>(zrow + k) =
+                    make_float4(as_operand<WT>(z.x), as_operand<WT>(z.y), as_operand<WT>(z.z), as_operand<WT>(z.w));
             }
             // joint layers wider than 768: the rest of the row, loaded where it is used
             for (int k4 = w.lane + 192; k4 < k4n; k4 += 64) {
@@ -961,7 +976,8 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
                                     k + 2 < p.J ? fmaxf(pv[2] + qv[2], 0.f) : 0.f,
                                     k + 3 < p.J ? fmaxf(pv[3] + qv[3], 0.f) : 0.f);
                 }
-                *reinterpret_cast<float4 *>(zrow + k) = z;
+                *reinterpret_cast<float4 *>(zrow + k) =
+                    make_float4(as_operand<WT>(z.x), as_operand<WT>(z.y), as_operand<WT>(z.z), as_operand<WT>(z.w));
             }
         }
         PROF_MARK(w, 23);

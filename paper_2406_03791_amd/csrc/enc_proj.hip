@@ -9,9 +9,20 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 128, BN = 128, KT = 16, LDP = 4;
 
+// nearest bfloat16 value (ties to even) of a float, as a float; NaN and infinities pass through
+__device__ __forceinline__ float bf16_rne(float v)
+{
+    unsigned u = __float_as_uint(v);
+    if ((u & 0x7f800000u) != 0x7f800000u) { u += 0x7fffu + ((u >> 16) & 1u); u &= 0xffff0000u; }
+    return __uint_as_float(u);
+}
+
 // grid: (ceil(T/BM), ceil(J/BN), B); 256 threads = 4 waves, each a 64x64 tile.
 // Tiles that start at or beyond enc_len[b] do nothing; rows at t >= enc_len[b]
 // inside a tile are computed and not stored.
+// ROUND_X: bfloat16 mode, the frames are rounded to bfloat16 as they enter the product (the
+// engine's copy of W_enc has been rounded once); products of two such values are exact in fp32.
+template <bool ROUND_X>
 __global__ void __launch_bounds__(256)
 enc_proj_kernel(const float *__restrict__ x, const int *__restrict__ enc_len,
                 const float *__restrict__ w_enc, const float *__restrict__ b_enc,
@@ -62,8 +73,13 @@ enc_proj_kernel(const float *__restrict__ x, const int *__restrict__ enc_len,
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int kk = a_k4[i] * 4, r = a_row[i];
-            As[kk + 0][r] = ra[i].x; As[kk + 1][r] = ra[i].y;
-            As[kk + 2][r] = ra[i].z; As[kk + 3][r] = ra[i].w;
+            if (ROUND_X) {
+                As[kk + 0][r] = bf16_rne(ra[i].x); As[kk + 1][r] = bf16_rne(ra[i].y);
+                As[kk + 2][r] = bf16_rne(ra[i].z); As[kk + 3][r] = bf16_rne(ra[i].w);
+            } else {
+                As[kk + 0][r] = ra[i].x; As[kk + 1][r] = ra[i].y;
+                As[kk + 2][r] = ra[i].z; As[kk + 3][r] = ra[i].w;
+            }
             Bs[kk + 0][r] = rb[i].x; Bs[kk + 1][r] = rb[i].y;
             Bs[kk + 2][r] = rb[i].z; Bs[kk + 3][r] = rb[i].w;
         }
@@ -108,11 +124,27 @@ enc_proj_kernel(const float *__restrict__ x, const int *__restrict__ enc_len,
 
 hipError_t launch_encoder_projection(const float *enc_out, const int *enc_len, const float *w_enc,
                                      const float *b_enc, float *proj, int B, int T, int F, int J,
-                                     hipStream_t stream)
+                                     bool round_x, hipStream_t stream)
 {
     dim3 grid((T + BM - 1) / BM, (J + BN - 1) / BN, B);
-    hipLaunchKernelGGL(enc_proj_kernel, grid, dim3(256), 0, stream, enc_out, enc_len, w_enc, b_enc,
-                       proj, T, F, J);
+    if (round_x)
+        hipLaunchKernelGGL(enc_proj_kernel<true>, grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
+                           b_enc, proj, T, F, J);
+    else
+        hipLaunchKernelGGL(enc_proj_kernel<false>, grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
+                           b_enc, proj, T, F, J);
+    return hipGetLastError();
+}
+
+__global__ void round_bf16_kernel(float *v, long long n)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) v[i] = bf16_rne(v[i]);
+}
+
+hipError_t launch_round_bf16(float *v, long long n, hipStream_t stream)
+{
+    hipLaunchKernelGGL(round_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, v, n);
     return hipGetLastError();
 }
 
@@ -120,7 +152,7 @@ hipError_t launch_encoder_projection(const float *enc_out, const int *enc_len, c
 __global__ void fold_embedding_kernel(const float *__restrict__ emb, const float *__restrict__ w_ih0,
                                       const float *__restrict__ b_ih0,
                                       const float *__restrict__ b_hh0, float *__restrict__ T0, int V1,
-                                      int E, int H)
+                                      int E, int H, int round_bf16)
 {
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long long)V1 * H * 4) return;
@@ -130,17 +162,18 @@ __global__ void fold_embedding_kernel(const float *__restrict__ emb, const float
     const float *wr = w_ih0 + (long long)(g * H + u) * E;
     const float *er = emb + (long long)v * E;
     float s = 0.f;
-    for (int e = 0; e < E; ++e) s += wr[e] * er[e];
+    if (round_bf16) { for (int e = 0; e < E; ++e) s += bf16_rne(wr[e]) * bf16_rne(er[e]); }
+    else { for (int e = 0; e < E; ++e) s += wr[e] * er[e]; }
     T0[idx] = s + b_ih0[g * H + u] + b_hh0[g * H + u];
 }
 
 hipError_t launch_fold_embedding(const float *emb, const float *w_ih0, const float *b_ih0,
                                  const float *b_hh0, float *T0, int V1, int E, int H,
-                                 hipStream_t stream)
+                                 bool round_bf16, hipStream_t stream)
 {
     const long long n = (long long)V1 * H * 4;
     hipLaunchKernelGGL(fold_embedding_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
-                       emb, w_ih0, b_ih0, b_hh0, T0, V1, E, H);
+                       emb, w_ih0, b_ih0, b_hh0, T0, V1, E, H, round_bf16 ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -80,10 +80,12 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream);
 
 hipError_t launch_encoder_projection(const float *enc_out, const int *enc_len, const float *w_enc,
                                      const float *b_enc, float *proj, int B, int T, int F, int J,
-                                     hipStream_t stream);
+                                     bool round_x, hipStream_t stream);
+// v[i] = nearest bfloat16 value of v[i] (ties to even), in place
+hipError_t launch_round_bf16(float *v, long long n, hipStream_t stream);
 // T0[v][u][g] = b_ih0[g*H+u] + b_hh0[g*H+u] + sum_e W_ih0[g*H+u][e] * emb[v][e]
 hipError_t launch_fold_embedding(const float *emb, const float *w_ih0, const float *b_ih0,
                                  const float *b_hh0, float *T0, int V1, int E, int H,
-                                 hipStream_t stream);
+                                 bool round_bf16, hipStream_t stream);
 
 }  // namespace rnnt

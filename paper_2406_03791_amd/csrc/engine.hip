@@ -420,7 +420,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     const Workspace &ws = static_ws ? *static_ws : t.ws;
     HIP_TRY(hipEventRecord(e->ev[0], stream));
     HIP_TRY(launch_encoder_projection(enc_out, enc_len, e->w_enc.as<float>(), e->b_enc.as<float>(),
-                                      ws.P, B, T, d.F, d.J, stream));
+                                      ws.P, B, T, d.F, d.J, e->wt == kWeightBf16Arith, stream));
     HIP_TRY(hipEventRecord(e->ev[1], stream));
     DecodeParams p{};
     p.F = d.F; p.E = d.E; p.H = d.H; p.L = d.L; p.J = d.J; p.V1 = d.V1; p.D = d.D;
@@ -477,8 +477,12 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
                        rnnt_engine **out)
 {
     if (!desc || !out) return RNNT_ERR_NULL;
-    if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_PLAIN_LAUNCH)) return RNNT_ERR_SHAPE;
-    if ((flags & RNNT_FLAG_BF16_WEIGHTS) && (flags & RNNT_FLAG_FP8_WEIGHTS)) return RNNT_ERR_SHAPE;
+    if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_PLAIN_LAUNCH | RNNT_FLAG_BF16_ARITHMETIC))
+        return RNNT_ERR_SHAPE;
+    {   // at most one of the three formats
+        const int fmt = flags & (RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC);
+        if (fmt & (fmt - 1)) return RNNT_ERR_SHAPE;
+    }
     const rnnt_model_desc &d = *desc;
     if (!d.emb || !d.w_ih || !d.w_hh || !d.b_ih || !d.b_hh || !d.w_enc || !d.b_enc || !d.w_pred ||
         !d.b_pred || !d.w_out || !d.b_out)
@@ -511,6 +515,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     e->max_B = max_B; e->max_T = max_T;
     e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8
                                             : ((flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32);
+    if (flags & RNNT_FLAG_BF16_ARITHMETIC) e->wt = kWeightBf16Arith;
     e->plain_launch = (flags & RNNT_FLAG_PLAIN_LAUNCH) != 0;
     e->n_wg = (prop.multiProcessorCount / 32) * 32;   // every layout divides it
     if (e->n_wg < 32) return RNNT_ERR_UNSUPPORTED;
@@ -531,6 +536,20 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     }
     if ((rc = fetch(e->w_pred, d.w_pred, J * H))) return rc;
     if ((rc = fetch(e->w_out, d.w_out, (size_t)e->NOUT * J))) return rc;
+    if (e->wt == kWeightBf16Arith) {
+        // bfloat16 mode: the matrices of the per-step products are rounded here (ties to even, the
+        // same rounding the kernels apply to the vectors), then stored as bf16 without loss
+        auto round_all = [](std::vector<float> &v) {
+            for (float &x : v) {
+                uint32_t u;
+                std::memcpy(&u, &x, sizeof u);
+                if ((u & 0x7f800000u) != 0x7f800000u) { u += 0x7fffu + ((u >> 16) & 1u); u &= 0xffff0000u; }
+                std::memcpy(&x, &u, sizeof u);
+            }
+        };
+        round_all(e->w_pred); round_all(e->w_out);
+        for (int l = 0; l < d.L; ++l) { round_all(e->w_hh[l]); if (l > 0) round_all(e->w_ih[l]); }
+    }
     if (e->wt == kWeightBf16) {
         // compact storage is lossless or refused: every streamed weight must be a bf16 value
         auto is_bf16 = [](const std::vector<float> &v) {
@@ -569,8 +588,10 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     HIP_TRY(e->bias_l.alloc(bias_l.size() * sizeof(float)));
     HIP_TRY(hipMemcpy(e->bias_l.p, bias_l.data(), bias_l.size() * sizeof(float), hipMemcpyHostToDevice));
     HIP_TRY(e->T0.alloc((size_t)d.V1 * H * 4 * sizeof(float)));
+    const bool bf16_mode = e->wt == kWeightBf16Arith;
+    if (bf16_mode) HIP_TRY(launch_round_bf16(e->w_enc.as<float>(), (long long)J * d.F, nullptr));
     HIP_TRY(launch_fold_embedding(d.emb, d.w_ih[0], d.b_ih[0], d.b_hh[0], e->T0.as<float>(), d.V1,
-                                  d.E, d.H, nullptr));
+                                  d.E, d.H, bf16_mode, nullptr));
     // this device's copy of the static scratch array (each device has its own, at its own address)
     HIP_TRY(hipGetSymbolAddress(&e->scratch, HIP_SYMBOL(scratch)));
     HIP_TRY(e->P.alloc((size_t)max_B * max_T * J * sizeof(float)));
@@ -738,7 +759,7 @@ int rnnt_encoder_projection(rnnt_engine *eng, const float *enc_out, const int32_
     if ((reinterpret_cast<uintptr_t>(enc_out) & 15u) != 0) return RNNT_ERR_SHAPE;
     HIP_TRY(launch_encoder_projection(enc_out, enc_len, eng->w_enc.as<float>(),
                                       eng->b_enc.as<float>(), proj_out, B, T, eng->d.F, eng->d.J,
-                                      static_cast<hipStream_t>(stream)));
+                                      eng->wt == kWeightBf16Arith, static_cast<hipStream_t>(stream)));
     return RNNT_OK;
 }
 

@@ -29,10 +29,13 @@ constexpr int kStepUnroll = 4;       // weight loads (16 bytes per lane) per sof
 constexpr int kAheadSteps = 2 * kStepUnroll;   // loads a lane keeps in flight: two batches
 
 // Storage of the packed weights: fp32 (4 K values per 16-byte load), bf16 (8 per load) or
-// fp8 in the OCP e4m3 format (16 per load).  The arithmetic is fp32 in every case: a stored
-// weight is widened before it is used.
-enum WeightType { kWeightF32 = 0, kWeightBf16 = 1, kWeightFp8 = 2 };
-RNNT_HD inline int k_per_load(int wt) { return wt == kWeightFp8 ? 16 : (wt == kWeightBf16 ? 8 : 4); }
+// fp8 in the OCP e4m3 format (16 per load).  With the three storage types the arithmetic is
+// fp32 on the stored values (a stored weight is widened before it is used, and the storage is
+// lossless or refused).  kWeightBf16Arith is the bfloat16 mode: the weights are rounded to
+// bf16 and stored as such, and every vector that enters a product is rounded to bf16 too;
+// products of two bf16 values are exact in fp32 and the sums stay fp32.
+enum WeightType { kWeightF32 = 0, kWeightBf16 = 1, kWeightFp8 = 2, kWeightBf16Arith = 3 };
+RNNT_HD inline int k_per_load(int wt) { return wt == kWeightFp8 ? 16 : ((wt == kWeightBf16 || wt == kWeightBf16Arith) ? 8 : 4); }
 
 // Floats between the partial sums of consecutive tasks in LDS: 16 per row group plus a pad that
 // spreads the readers (one lane per output group, so a stride of whole multiples of 16 floats

@@ -10,7 +10,7 @@ import pytest
 
 import oracle
 import synth
-from parity_util import compare, to_lists
+from parity_util import BF16_LOGIT_RTOL, BF16_MARGIN, compare, to_lists
 
 pytestmark = pytest.mark.gpu
 
@@ -56,20 +56,26 @@ def run_gpu(eng, w, variant, S, cap=None, pad_nan=True, logp=False):
     return to_lists(out, w.B), eng.status(), eng.stats()
 
 
-def check(pkg, w, variant, key, S=None, max_B=None, engine=None, expect_status=0, logp=False):
+def check(pkg, w, variant, key, S=None, max_B=None, engine=None, expect_status=0, logp=False,
+          bf16=False):
     S = w.max_symbols if S is None else S
     eng = engine or engine_for(pkg, key, w.model, max_B or w.B, w.T)
-    net = oracle.LstmNet(w.model)
+    net = oracle.LstmNet(w.model, bf16=bf16)
     ref = oracle.decode(net, w.enc_out, w.enc_len, S, "seq", n_threads=N_THREADS)
     got, status, stats = run_gpu(eng, w, variant, S, logp=logp)
     log(f"[{key}/{variant}] B={w.B} T={w.T} S={S} tokens={int(ref.tok_len.sum())} "
         f"status={status} stats={stats}")
     assert status == expect_status
     assert stats["xcd_mismatch"] == 0
-    ties = compare(w, net, ref, got, S)
+    if bf16:
+        ties = compare(w, net, ref, got, S, margin=BF16_MARGIN, logit_rtol=BF16_LOGIT_RTOL)
+    else:
+        ties = compare(w, net, ref, got, S)
     for t in ties:
         log(f"  near-tie divergence accepted: {t}")
-    assert len(ties) <= max(1, w.B // 8)
+    if not bf16:
+        assert len(ties) <= max(1, w.B // 8)
+    stats["near_tie_rows"] = len(ties)
     return ref, got, stats
 
 
@@ -356,7 +362,7 @@ def test_compact_weight_storage(pkg):
             eng.close()
     # unknown flag bits and both storage flags at once are refused
     w8 = dataclasses.replace(w32, model=synth.with_fp8_streamed_weights(w32.model))
-    for flags in (8, pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS):
+    for flags in (16, pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS):
         with pytest.raises(pkg.RnntError) as err:
             pkg.Engine(w8.model, w8.B, w8.T, flags=flags)
         assert err.value.code == -2
@@ -486,3 +492,42 @@ def test_more_joint_steps_than_the_exchange_tag_counts(pkg):
         assert stats["joint_steps"] > 65536
         assert got["tok_len"].tolist() == [66000]
     eng.close()
+
+
+def test_bf16_arithmetic_mode(pkg):
+    """The bfloat16 mode (weights and every input of a dense product rounded to bfloat16, fp32
+    sums) against the oracle's bfloat16 emulation, to the same bar as the fp32 path: tokens,
+    frames and durations exact, logits within 1e-4, a differing row only at near-ties.  Also
+    logs how many rows decode differently from the fp32 arithmetic on the same model, and checks
+    the projection kernel of the mode element by element."""
+    flag = pkg.RNNT_FLAG_BF16_ARITHMETIC
+    for cfg, variants, kw in [(1, ("frame", "label"), {}),
+                              (3, ("frame", "label"), dict(B=12, T=120, len_lo=40, len_hi=120)),
+                              (4, ("tdt",), dict(B=12, T=120, len_lo=40, len_hi=120)),
+                              (3, ("label", "frame"), {}), (4, ("tdt",), {})]:
+        w = synth.make_workload(cfg, pad="nan", **kw)
+        eng = pkg.Engine(w.model, w.B, w.T, flags=flag)
+        ref32 = oracle.decode(oracle.LstmNet(w.model), w.enc_out, w.enc_len, w.max_symbols, "seq",
+                              n_threads=N_THREADS)
+        for variant in variants:
+            ref, got, st = check(pkg, w, variant, f"cfg{cfg}/bf16 arithmetic", engine=eng, bf16=True,
+                                 logp=(variant == "label"))
+            same = sum(int(np.array_equal(ref.tokens[b], got["tokens"][b])) for b in range(w.B))
+            log(f"  rows token-identical to the emulating oracle: {same}/{w.B}; rows accepted at a "
+                f"bfloat16 near-tie: {st['near_tie_rows']}")
+            assert st["near_tie_rows"] <= max(1, w.B // 3)
+            moved = sum(int(not np.array_equal(ref.tokens[b], ref32.tokens[b])) for b in range(w.B))
+            log(f"  rows whose tokens differ from the fp32 arithmetic's: {moved}/{w.B}")
+        if w.B <= 12:
+            enc = torch.from_numpy(w.enc_out).cuda().contiguous()
+            ln = torch.from_numpy(w.enc_len).cuda()
+            proj = eng.encoder_projection(enc, ln).cpu().numpy()
+            net = oracle.LstmNet(w.model, bf16=True)
+            for b in range(w.B):
+                for t in range(0, int(w.enc_len[b]), 7):
+                    assert np.allclose(proj[b, t], net.prep(w.enc_out[b, t]), rtol=1e-5, atol=2e-5), (cfg, b, t)
+        eng.close()
+    # the mode excludes the storage flags
+    with pytest.raises(pkg.RnntError) as err:
+        pkg.Engine(w.model, w.B, w.T, flags=flag | pkg.RNNT_FLAG_BF16_WEIGHTS)
+    assert err.value.code == -2

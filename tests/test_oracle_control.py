@@ -244,3 +244,44 @@ def test_status_bits_and_capacity():
         assert r.tok_len[0] == S * T and len(r.tokens[0]) == 4
         r = oracle.decode(net, net.frames(), np.array([-3]), S, sched)
         assert r.status & 1 and r.tok_len[0] == 0
+
+
+def test_follow_finds_the_blank_durations_a_tdt_hypothesis_does_not_record():
+    """A TDT hypothesis lists labels with frames and durations, not the durations taken on
+    blanks.  Two tables that differ in one blank cell only: there the duration logits of 1 and 2
+    frames are 1e-3 apart, with either sign.  Each table's decode is a hypothesis that the
+    other table's walk can only reach through the runner-up duration of that blank.  With a
+    tolerance above the gap, follow mode finds that chain and reports exactly that departure
+    (duration column, gap 1e-3); with tolerance 0 it walks the argmax durations and ends
+    somewhere else."""
+    V1, durations, S, T = 3, (0, 1, 2), 2, 6
+    D, U = len(durations), 8
+    cells = [[0, 1, 0, -1, 0, 2],     # frame 1, before any label: label 0, then jump two frames
+             [0, 3, 1, -1, 1, 1],     # frame 3, one label out: label 1, then one frame on
+             [0, 2, 0, -1, 1, 1],     # frame 2 (reached only through the 2-frame blank at 0): label 1
+             [0, 4, 2, -1, 0, 1]]
+    tabs = []
+    for eps in (+1e-3, -1e-3):
+        tab = table_from_choices(1, T, U, V1, D, cells)
+        # blank at frame 0, nothing emitted yet: durations "1 frame" and "2 frames" nearly tied
+        tab[0, 0, 0, :, V1:] = 0.0
+        tab[0, 0, 0, :, V1 + 1] = BIG
+        tab[0, 0, 0, :, V1 + 2] = BIG + eps
+        tabs.append(tab)
+    nets = [oracle.TableNet(t, V1, durations) for t in tabs]
+    lens = np.array([T], dtype=np.int32)
+    hyps = [oracle.decode(n, n.frames(), lens, S, "seq") for n in nets]
+    assert hyps[0].frames[0].tolist() != hyps[1].frames[0].tolist()     # the blank's duration matters
+    for a, b in ((0, 1), (1, 0)):
+        net, h = nets[a], hyps[b]
+        args = (net, net.frames()[0], T, S, h.tokens[0], h.frames[0], h.durs[0])
+        own = oracle.follow(nets[b], nets[b].frames()[0], T, S, h.tokens[0], h.frames[0], h.durs[0], tol=1e-2)
+        assert own.departures == 0
+        found = oracle.follow(*args, tol=1e-2)
+        assert found.departures == 1, found
+        rep = found.where[0]
+        assert rep["t"] == 0 and rep["want"] >= V1 and rep["got"] >= V1 and rep["want"] != rep["got"]
+        assert abs(rep["gap"] - 1e-3) < 1e-4 and abs(found.worst_gap - 1e-3) < 1e-4
+        assert oracle.follow(*args, tol=1e-4).departures != 1      # the gap is above this tolerance
+        strict = oracle.follow(*args)                               # argmax durations only
+        assert strict.departures == -1 or strict.worst_gap > 1.0
