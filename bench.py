@@ -84,19 +84,37 @@ def mfma_fraction(dims, stats, B, dec_ms):
             "frac": ach / 157.3}
 
 
-def profiled_traffic(variant):
-    """HBM bytes per launch of the decode kernel from the committed rocprofv3
-    counter summary (FETCH_SIZE and WRITE_SIZE runs, scaled by the copy-kernel
-    calibration stated there), or None when there is no summary."""
+def profiled(variant, key):
+    """A `key: value` figure from the committed rocprofv3 summary of the decode kernel for this
+    variant (profiles/decode_kernel_parakeet_b32_*.md), or None when there is none."""
     tag = {"frame": "frame_looping", "label": "label_looping", "tdt": "tdt_label_looping"}[variant]
     path = os.path.join(ROOT, "profiles", f"decode_kernel_parakeet_b32_{tag}.md")
     try:
         for ln in open(path):
-            if ln.startswith("decode_kernel_traffic_bytes_per_launch:"):
+            if ln.startswith(key + ":"):
                 return float(ln.split(":")[1])
     except OSError:
         pass
     return None
+
+
+def measured_ceiling(key):
+    """A figure from the committed output of `bench.py --probes` (profiles/probes.md), or None."""
+    try:
+        for ln in open(os.path.join(ROOT, "profiles", "probes.md")):
+            if ln.startswith(key + ":"):
+                return float(ln.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def minimum_schedule_bytes(dims, B, variant, enc_len, tok_frames, S, wbytes=4):
+    """The method's own minimum: the fewest batched steps any exact schedule needs on this
+    batch (label looping: one prediction step per label of the utterance with the most labels,
+    plus the first; one joint step per frame and per label of the utterance that needs the
+    most), each touching every weight once."""
+    return algorithmic_bytes(dims, B, "tdt" if variant == "tdt" else "label", enc_len, tok_frames, S, wbytes)
 
 
 def main() -> int:
@@ -116,6 +134,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
                     help="time the chosen decoder only (profiler runs: one decode kernel per trace)")
+    ap.add_argument("--probes", action="store_true",
+                    help="run the library's microbenchmarks instead of the decode (stream out of "
+                         "L2 and out of HBM, team exchanges, fp32 MFMA rate) and print them as JSON: "
+                         "the measured ceilings the roofline figures are read against")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead of the decode: under rocprofv3 "
                          "--pmc it gives the FETCH_SIZE / WRITE_SIZE reading for a known traffic")
@@ -141,6 +163,28 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     pkg.load_library()
+
+    if args.probes:
+        torch.zeros(1, device="cuda")              # the device is initialised through torch first
+        l2, l2_cu = pkg.rnnt_probe_stream(True)
+        hbm, hbm_cu = pkg.rnnt_probe_stream(False)
+        exch = []
+        for ts in (8, 16, 32, 64, 256):
+            for tagged in (False, True):
+                exch.append({"team_size": ts, "floats": 640, "tagged_words": tagged,
+                             "us_per_exchange": pkg.rnnt_probe_exchange(ts, 640, tagged)})
+        for rows, ts in ((2, 16), (4, 32), (16, 16)):
+            for tagged in (False, True):
+                exch.append({"team_size": ts, "floats": 640 * rows, "tagged_words": tagged,
+                             "us_per_exchange": pkg.rnnt_probe_exchange(ts, 640 * rows, tagged)})
+        print(json.dumps({"probes": {
+            "stream_from_l2": {"GBs": l2, "GBs_per_cu": l2_cu,
+                               "pattern": "16 slices of 1.5 MiB, slice i%16 for work-group i, 64 passes"},
+            "stream_from_hbm": {"GBs": hbm, "GBs_per_cu": hbm_cu, "pattern": "8 MiB per work-group, one pass"},
+            "exchange": exch,
+            "mfma_f32_tflops": {"4x4x1_16_blocks": pkg.rnnt_probe_mfma(0), "32x32x2": pkg.rnnt_probe_mfma(1),
+                                "published_peak": 157.3}}}))
+        return 0
 
     if args.copy_calibration:
         n = 1 << 28                                    # 2^28 floats = 1 GiB read + 1 GiB written
@@ -189,8 +233,8 @@ def main() -> int:
         tok_len = out["tok_len"].cpu().numpy()
         frames = [out["frames"][b, :tok_len[b]].cpu().numpy() for b in range(w.B)]
         tokens = [out["tokens"][b, :tok_len[b]].cpu().numpy() for b in range(w.B)]
-        res = dict(w=w, wall=wall, steps=steps, dec_ms=float(np.mean(dec_ms)),
-                   proj_ms=float(np.mean(proj_ms)), dec_ms_min=float(np.min(dec_ms)), stats=st,
+        res = dict(w=w, wall=wall, steps=steps, dec_ms=float(np.median(dec_ms)),
+                   proj_ms=float(np.median(proj_ms)), dec_ms_min=float(np.min(dec_ms)), stats=st,
                    status=status, frames=frames, tokens=tokens, tok_len=tok_len)
         eng.close()
         return res
@@ -200,20 +244,29 @@ def main() -> int:
     n_frames = w.frames
     ms_per_step = 1e3 * r["wall"] / r["steps"]
     value = n_frames * r["steps"] / r["wall"]
-    alg_bytes, pred_steps, joint_steps, alg_flops = algorithmic_bytes(
-        w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols,
-        {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage])
-    # numerator of the roofline: the bytes of the steps the device counted (every team step
-    # touches its streamed weights once); the batched schedule's figure is listed beside it
-    step_bytes = issued_weight_bytes(w.model.dims, r["stats"],
-                                     {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage])
-    achieved = step_bytes / (r["dec_ms"] * 1e-3) / 1e9
+    wb = {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage]
+    lit_bytes, lit_pred, lit_joint, _ = algorithmic_bytes(
+        w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols, wb)
+    min_bytes, min_pred, min_joint, _ = minimum_schedule_bytes(
+        w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols, wb)
+    # bytes of the steps the device counted (every team step reads its streamed weights once,
+    # out of the L2 of its XCD)
+    step_bytes = issued_weight_bytes(w.model.dims, r["stats"], wb)
+    t_dec = r["dec_ms"] * 1e-3
+    achieved = min_bytes / t_dec / 1e9
+    std = args.batch == 32 and args.storage == "fp32"
+    traffic = profiled(args.variant, "decode_kernel_traffic_bytes_per_launch") if std else None
+    l2_peak = measured_ceiling("stream_from_l2_GBs")
     line = {
         "metric": "encoder frames decoded/sec, Parakeet-1.1B decoder shape, B=32",
         "value": value, "unit": "frames/s", "n_gpus": 1, "steps": r["steps"],
         "warmup": args.warmup, "ms_per_step": ms_per_step, "us_per_frame": 1e6 / value,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
+        "timing_note": "value and ms_per_step are host wall time over the timed calls, each followed "
+                       "by rnnt_engine_stats (a device synchronisation and a small copy), so they "
+                       "are conservative; kernel_ms are HIP-event times around each launch, median "
+                       "and minimum over the timed calls",
         "config": {"workload": f"config {dict(frame=2, label=3, tdt=4)[args.variant]}: "
                                f"{w.name}, B={w.B}, T<={w.T}, frames={n_frames}, "
                                f"max_symbols={w.max_symbols}, variant={args.variant}" +
@@ -224,15 +277,34 @@ def main() -> int:
                    "kernel_ms": {"decode": r["dec_ms"], "decode_min": r["dec_ms_min"],
                                  "encoder_projection": r["proj_ms"]},
                    "engine": r["stats"]},
+        # The numerator is the method's minimum: the bytes of the fewest batched steps an exact
+        # schedule needs on this batch, every weight once per step.  The kernel is not bound by
+        # HBM: its weight streams are served by the XCD L2s and its time is the latency of the
+        # longest utterance's chain of dependent steps; the fraction says how far that leaves it
+        # from streaming the minimum schedule at HBM speed.
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (profiled_traffic(args.variant)
-                                 if args.batch == 32 and args.storage == "fp32" else None),
-                     "kernel": "decode_kernel", "algorithmic_bytes": step_bytes,
-                     "bytes_from": "measured team steps x weights streamed per step",
-                     "batched_schedule": {"prediction_steps": pred_steps, "joint_steps": joint_steps,
-                                          "bytes": alg_bytes,
-                                          "achieved": alg_bytes / (r["dec_ms"] * 1e-3) / 1e9},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "decode_kernel", "algorithmic_bytes": min_bytes,
+                     "bytes_from": "minimum batched schedule: prediction steps = most labels of an "
+                                   "utterance + 1, joint steps = most (frames + labels) of an "
+                                   "utterance, each step touching every weight once",
+                     "limited_by": "latency of the dependent step chain of the longest utterance "
+                                   "(weight streams come out of the XCD L2s, not HBM)",
+                     "minimum_schedule": {"prediction_steps": min_pred, "joint_steps": min_joint},
+                     "hbm_measured": None if traffic is None else {
+                         "bytes": traffic, "GBs": traffic / t_dec / 1e9,
+                         "frac": traffic / t_dec / 1e9 / HBM_PEAK_GBS},
+                     "l2_stream": {"served_bytes": step_bytes, "achieved": step_bytes / t_dec / 1e9,
+                                   "peak_measured": l2_peak, "unit": "GB/s",
+                                   "frac": None if not l2_peak else step_bytes / t_dec / 1e9 / l2_peak,
+                                   "note": "bytes of the team steps the device counted x weights "
+                                           "streamed per step; peak from bench.py --probes"},
+                     "literal_schedule": {"prediction_steps": lit_pred, "joint_steps": lit_joint,
+                                          "bytes": lit_bytes, "achieved": lit_bytes / t_dec / 1e9,
+                                          "note": "the timed decoder's own schedule run on the whole "
+                                                  "batch in lock-step; above the peak means the "
+                                                  "kernel does less than that schedule (unchanged "
+                                                  "prediction steps skipped, utterances independent)"},
                      # useful flops of the counted steps against the fp32 matrix peak: small, the
                      # path is not a dense contraction at these batch sizes (the counter-based
                      # figure of the MFMA work executed, row padding included, is in profiles/)

@@ -353,6 +353,30 @@ int rnnt_engine_set_done_flags(rnnt_engine *eng, int32_t *done);
  */
 int rnnt_engine_phase_timers(rnnt_engine *eng, int32_t team, double *us_out, int32_t n);
 
+/*
+ * Microbenchmarks of what bounds the decode path on the current device (not
+ * part of the path; bench.py --probes prints them).  Synchronous; they
+ * allocate and free their own buffers.
+ *   rnnt_probe_stream    from_l2 = 1: every work-group reads, over and over, a
+ *                        weight slice that stays in its XCD's L2, with the
+ *                        decode kernel's access pattern; 0: every work-group
+ *                        streams its own 8 MiB from HBM once.  GB/s over the
+ *                        device and per compute unit.
+ *   rnnt_probe_exchange  microseconds for one hand-over of a vector of `len`
+ *                        floats inside teams of `team_size` work-groups (all
+ *                        teams of the device at once): every work-group
+ *                        writes its share and reads the whole vector, either
+ *                        behind a counter barrier (tagged = 0) or as tagged
+ *                        64-bit words that the readers poll (tagged = 1).
+ *   rnnt_probe_mfma      fp32 matrix rate in TFLOP/s of the MFMA shape 4x4x1
+ *                        in 16 blocks (shape 0, the decode kernel's) or
+ *                        32x32x2 (shape 1, the projection kernel's).
+ * Return RNNT_OK or an RNNT_ERR_* code.
+ */
+int rnnt_probe_stream(int32_t from_l2, double *gbytes_per_s_out, double *per_cu_out);
+int rnnt_probe_exchange(int32_t team_size, int32_t len, int32_t tagged, double *us_per_exchange_out);
+int rnnt_probe_mfma(int32_t shape, double *tflops_out);
+
 /* Text for a return code; for RNNT_ERR_HIP includes the last HIP error text. */
 const char *rnnt_status_string(int code);
 

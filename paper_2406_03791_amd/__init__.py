@@ -23,6 +23,9 @@ from .binding import (  # noqa: F401
     rnnt_engine_set_done_flags,
     rnnt_engine_phase_timers,
     rnnt_engine_stats,
+    rnnt_probe_exchange,
+    rnnt_probe_mfma,
+    rnnt_probe_stream,
     rnnt_engine_status,
     rnnt_greedy_decode,
     rnnt_label_looping_decode,

@@ -22,6 +22,7 @@ EXPORTS = (
     "rnnt_engine_set_done_flags",
     "rnnt_label_looping_decode_noalloc",
     "rnnt_engine_phase_timers",
+    "rnnt_probe_stream", "rnnt_probe_exchange", "rnnt_probe_mfma",
 )
 
 
@@ -107,6 +108,9 @@ def load_library():
         lib.rnnt_engine_set_logp_output.argtypes = [C.c_void_p, C.c_void_p]
         lib.rnnt_engine_set_done_flags.argtypes = [C.c_void_p, C.c_void_p]
         lib.rnnt_engine_phase_timers.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_int32]
+        lib.rnnt_probe_stream.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        lib.rnnt_probe_exchange.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
+        lib.rnnt_probe_mfma.argtypes = [C.c_int32, C.POINTER(C.c_double)]
         lib.rnnt_status_string.argtypes = [C.c_int]
         lib.rnnt_status_string.restype = C.c_char_p
         for name in EXPORTS:
@@ -222,6 +226,25 @@ def rnnt_engine_phase_timers(eng, team: int, n: int = 24):
     out = (C.c_double * n)()
     _check(load_library().rnnt_engine_phase_timers(eng, int(team), out, int(n)))
     return [float(v) for v in out]
+
+
+def rnnt_probe_stream(from_l2: bool):
+    """(GB/s over the device, GB/s per compute unit)"""
+    a, b = C.c_double(0), C.c_double(0)
+    _check(load_library().rnnt_probe_stream(int(bool(from_l2)), C.byref(a), C.byref(b)))
+    return float(a.value), float(b.value)
+
+
+def rnnt_probe_exchange(team_size: int, length: int, tagged: bool) -> float:
+    out = C.c_double(0)
+    _check(load_library().rnnt_probe_exchange(int(team_size), int(length), int(bool(tagged)), C.byref(out)))
+    return float(out.value)
+
+
+def rnnt_probe_mfma(shape: int) -> float:
+    out = C.c_double(0)
+    _check(load_library().rnnt_probe_mfma(int(shape), C.byref(out)))
+    return float(out.value)
 
 
 def rnnt_engine_stats(eng) -> RnntStats:

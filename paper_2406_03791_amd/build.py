@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip"]
+SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip", "probes.hip"]
 # the decode kernel is instantiated in one unit per (loop nest, row groups, weight storage),
 # all compiled from decode_inst.hip, so that the instances build in parallel
 INSTANCES = [(nest, rg, wt) for wt in ("f32", "bf16", "fp8", "bf16a") for nest in ("f", "l")

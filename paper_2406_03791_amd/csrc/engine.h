@@ -78,6 +78,9 @@ struct DecodeParams {
 
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream);
 
+// Keeps the text of a failed HIP call for rnnt_status_string; returns RNNT_ERR_HIP.
+int hip_fail(hipError_t e, const char *what);
+
 hipError_t launch_encoder_projection(const float *enc_out, const int *enc_len, const float *w_enc,
                                      const float *b_enc, float *proj, int B, int T, int F, int J,
                                      bool round_x, hipStream_t stream);

@@ -24,11 +24,16 @@ namespace {
 
 thread_local std::string g_hip_error;
 
-int hip_fail(hipError_t e, const char *what)
+}  // namespace
+
+// Records the text rnnt_status_string(RNNT_ERR_HIP) returns; shared with the probes.
+int rnnt::hip_fail(hipError_t e, const char *what)
 {
     g_hip_error = std::string("HIP error in ") + what + ": " + hipGetErrorString(e);
     return RNNT_ERR_HIP;
 }
+
+namespace {
 
 #define HIP_TRY(expr)                                           \
     do {                                                        \
