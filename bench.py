@@ -24,6 +24,20 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# Phase timers of a profile build (rnnt_engine_phase_timers), in the order of their slots.
+# "general" = prediction step of teams with more than four utterances (barriers, inputs filled
+# from the exchange buffers); the fast step of smaller teams leaves those slots at zero.
+PHASES = ["pred: stage-0 input filled (general)", "pred: recurrent stage of all layers",
+          "pred: layer-0 cell and store", "pred: barrier (general)",
+          "pred: hidden vectors of the layer below received", "pred: input stage of a layer",
+          "pred: cell of a layer and store", "pred: barrier (general)",
+          "pred: top hidden vectors received", "pred: prediction-side projection stage",
+          "pred: q stored", "pred: barrier (general)", "pred: q received",
+          "joint: z rows complete (work-group barrier)", "joint: output stage", "joint: candidates scanned, partial published",
+          "control: results walked, labels emitted", "joint: argmax exchange", "control: before a step",
+          "control: row states exchanged between joint groups", "joint: candidates from partial sums",
+          "unused", "joint: frame loads and first weight loads issued", "joint: z formed"]
+
 
 def algorithmic_bytes(dims, B, variant, enc_len, tok_frames, S, wbytes=4):
     """Bytes the method must touch per launch: every weight once per batched
@@ -134,6 +148,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
                     help="time the chosen decoder only (profiler runs: one decode kernel per trace)")
+    ap.add_argument("--phases", action="store_true",
+                    help="with a library built with RNNT_PROFILE=1: add the phase timers of the "
+                         "slowest team's first work-group to the line (microseconds per launch)")
     ap.add_argument("--probes", action="store_true",
                     help="run the library's microbenchmarks instead of the decode (stream out of "
                          "L2 and out of HBM, team exchanges, fp32 MFMA rate) and print them as JSON: "
@@ -233,7 +250,12 @@ def main() -> int:
         tok_len = out["tok_len"].cpu().numpy()
         frames = [out["frames"][b, :tok_len[b]].cpu().numpy() for b in range(w.B)]
         tokens = [out["tokens"][b, :tok_len[b]].cpu().numpy() for b in range(w.B)]
-        res = dict(w=w, wall=wall, steps=steps, dec_ms=float(np.median(dec_ms)),
+        phases = None
+        if args.phases:
+            per_team = [eng.phase_timers(t) for t in range(st["n_teams"])]
+            slow = max(range(len(per_team)), key=lambda t: sum(per_team[t]))
+            phases = {"team": slow, "us": dict(zip(PHASES, per_team[slow]))}
+        res = dict(w=w, wall=wall, steps=steps, phases=phases, dec_ms=float(np.median(dec_ms)),
                    proj_ms=float(np.median(proj_ms)), dec_ms_min=float(np.min(dec_ms)), stats=st,
                    status=status, frames=frames, tokens=tokens, tok_len=tok_len)
         eng.close()
@@ -312,6 +334,8 @@ def main() -> int:
                      "gpu_busy_frac": (r["dec_ms"] + r["proj_ms"]) / ms_per_step,
                      "us_per_lockstep_frame": 1e3 * ms_per_step / int(w.enc_len.max())},
     }
+    if r["phases"]:
+        line["phases"] = r["phases"]
     # the other decoders on their configurations (label looping decodes config 2's inputs and
     # emits the same tokens; TDT is config 4's model): always listed beside the headline
     line["variants"] = {}

@@ -72,6 +72,47 @@ __device__ __forceinline__ float as_operand(float v)
     return __uint_as_float(u);
 }
 
+// Activation rows in LDS.  In the bfloat16 mode a row holds bf16 values (two bytes each, in K
+// order, at the start of the row's storage) and feeds the bf16 MFMA directly; in the other
+// modes it holds floats.  `row` is the row's first float slot in either case.
+template <int WT>
+__device__ __forceinline__ void x_store(float *row, int k, float v)
+{
+    if (WT == kWeightBf16Arith)
+        reinterpret_cast<unsigned short *>(row)[k] = (unsigned short)(__float_as_uint(as_operand<WT>(v)) >> 16);
+    else
+        row[k] = v;
+}
+template <int WT>
+__device__ __forceinline__ void x_store2(float *row, int k, float2 v)      // k even
+{
+    if (WT == kWeightBf16Arith) {
+        const unsigned lo = __float_as_uint(as_operand<WT>(v.x)) >> 16, hi = __float_as_uint(as_operand<WT>(v.y)) & 0xffff0000u;
+        reinterpret_cast<unsigned *>(row)[k >> 1] = lo | hi;
+    } else {
+        *reinterpret_cast<float2 *>(row + k) = v;
+    }
+}
+template <int WT>
+__device__ __forceinline__ void x_store4(float *row, int k, float4 v)      // k a multiple of 4
+{
+    if (WT == kWeightBf16Arith) {
+        const unsigned a = (__float_as_uint(as_operand<WT>(v.x)) >> 16) | (__float_as_uint(as_operand<WT>(v.y)) & 0xffff0000u);
+        const unsigned b = (__float_as_uint(as_operand<WT>(v.z)) >> 16) | (__float_as_uint(as_operand<WT>(v.w)) & 0xffff0000u);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<unsigned *>(row) + (k >> 1)) = make_uint2(a, b);
+    } else {
+        *reinterpret_cast<float4 *>(row + k) = v;
+    }
+}
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+// four bf16 values held in two 32-bit registers, as the operand type of the bf16 MFMA
+__device__ __forceinline__ v4s bf16x4(float lo, float hi)
+{
+    struct { float a, b; } t = {lo, hi};
+    return __builtin_bit_cast(v4s, t);
+}
+
 // Read-modify-write atomics are issued on pointers typed as global memory: on a generic
 // pointer the compiler has to add a run-time test for the private aperture.
 typedef __attribute__((address_space(1))) unsigned global_u32;
@@ -216,8 +257,12 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         const int g = live ? task / sd.nks : 0;
         const int ks = live ? task - g * sd.nks : 0;
         constexpr int KPER = WT == kWeightFp8 ? 16 : ((WT == kWeightBf16 || WT == kWeightBf16Arith) ? 8 : 4);
-        constexpr int HALVES = KPER / 4;
-        const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * KPER;
+        // bfloat16 mode: the activation rows hold bf16, 16 bytes of a row match the 16 bytes (eight
+        // weights) of a load, and one load feeds two 4x4x4 bf16 MFMAs; otherwise a load is used
+        // in part-steps of four K values on the fp32 4x4x1 MFMA
+        constexpr bool BF = WT == kWeightBf16Arith;
+        constexpr int HALVES = BF ? 1 : KPER / 4;
+        const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * (BF ? 4 : KPER);
         // lane r4 of a block accumulates output column r4 of the group for the block's four rows
         const float b0 = (bias && live && ks == 0) ? bias[g * 4 + r4] : 0.f;
         v4f acc[RG];
@@ -249,8 +294,19 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
                             for (int rg = 0; rg < RG; ++rg)
                                 xb[rg] = *reinterpret_cast<const float4 *>(
                                     xr + rg * 4 * xstride + ((i + u) * HALVES + h + 1) * 4);
+                            if (BF) {
+#pragma unroll
+                                for (int rg = 0; rg < RG; ++rg) {
+                                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(bf16x4(xa[rg].x, xa[rg].y), bf16x4(raw.x, raw.y), acc[rg], 0, 0, 0);
+                                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(bf16x4(xa[rg].z, xa[rg].w), bf16x4(raw.z, raw.w), acc[rg], 0, 0, 0);
+                                }
+#pragma unroll
+                                for (int rg = 0; rg < RG; ++rg) xa[rg] = xb[rg];
+                                __builtin_amdgcn_sched_barrier(0);
+                                continue;
+                            }
                             float4 wv;
-                            if (WT == kWeightBf16 || WT == kWeightBf16Arith) {
+                            if (WT == kWeightBf16) {
                                 const unsigned lo = __float_as_uint(h == 0 ? raw.x : raw.z);
                                 const unsigned hi = __float_as_uint(h == 0 ? raw.y : raw.w);
                                 wv = make_float4(__uint_as_float(lo << 16), __uint_as_float(lo & 0xffff0000u),
@@ -379,8 +435,7 @@ __device__ __forceinline__ void fill_rows(const DecodeParams &p, const Wg &w, fl
             const int idx = base + u * kThreads;
             if (idx < total) {
                 const int r = idx / kp2, k = (idx - r * kp2) * 2;
-                *reinterpret_cast<float2 *>(dst + r * p.xstride + k) =
-                    make_float2(as_operand<WT>(v[u].x), as_operand<WT>(v[u].y));
+                x_store2<WT>(dst + r * p.xstride, k, v[u]);
             }
         }
     }
@@ -490,8 +545,8 @@ __device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, cons
             for (int i = 0; i < KI; ++i) {
                 const int k = w.tid + i * kThreads;
                 if (r < R && k < p.H)
-                    hc[(((c.sel[r] ^ 1) * p.L + lay) * 4 + r) * xs + k] =
-                        as_operand<WT>(__uint_as_float((unsigned)v[r * KI + i]));
+                    x_store<WT>(hc + (((c.sel[r] ^ 1) * p.L + lay) * 4 + r) * xs, k,
+                                __uint_as_float((unsigned)v[r * KI + i]));
             }
         return true;
     };
@@ -954,8 +1009,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
                     if (k + 2 < p.J) z.z = fmaxf(pe[i][u].z + qv.z, 0.f);
                     if (k + 3 < p.J) z.w = fmaxf(pe[i][u].w + qv.w, 0.f);
                 }
-                *reinterpret_cast<float4 *>(zrow + k) =
-                    make_float4(as_operand<WT>(z.x), as_operand<WT>(z.y), as_operand<WT>(z.z), as_operand<WT>(z.w));
+                x_store4<WT>(zrow, k, z);
             }
             // joint layers wider than 768: the rest of the row, loaded where it is used
             for (int k4 = w.lane + 192; k4 < k4n; k4 += 64) {
@@ -976,8 +1030,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
                                     k + 2 < p.J ? fmaxf(pv[2] + qv[2], 0.f) : 0.f,
                                     k + 3 < p.J ? fmaxf(pv[3] + qv[3], 0.f) : 0.f);
                 }
-                *reinterpret_cast<float4 *>(zrow + k) =
-                    make_float4(as_operand<WT>(z.x), as_operand<WT>(z.y), as_operand<WT>(z.z), as_operand<WT>(z.w));
+                x_store4<WT>(zrow, k, z);
             }
         }
         PROF_MARK(w, 23);
