@@ -191,11 +191,11 @@ __device__ __forceinline__ bool team_barrier(const DecodeParams &p, const Wg &w,
 
 // The packed weights of a stage are a fixed stream per lane, independent of the
 // data, so their loads can start before the stage's input is there: kAhead
-// batches of kStepUnroll float4 steps are kept in flight in registers.  (Deeper windows and
-// non-temporal loads both measured slower on MI355X: a wave's loads return in order, so the
-// exchange loads behind a longer window wait longer, and the teams of an XCD profit from
-// each other's L2 lines.)
-constexpr int kAhead = 2;
+// batches of kStepUnroll float4 steps are kept in flight in registers.  Three batches measured
+// 1-2 % faster than two on MI355X and four slower again (registers; and a wave's loads return in
+// order, so the exchange loads behind a longer window wait longer).  Non-temporal loads
+// measured slower: the teams of an XCD profit from each other's L2 lines.
+constexpr int kAhead = 3;
 
 struct WeightStream {
     const float4 *base;   // this wave's run of the current pass (uniform over the wave)
@@ -245,7 +245,6 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
 {
     // two batches in flight: the hand-over of the batches at a pass boundary below is written
     // for that depth
-    static_assert(kAhead == 2, "run_stage: the pass boundary assumes two batches in flight");
     static_assert(kMaxSamples <= 64, "the samples of a joint step are set up by one wave");
     const int r4 = w.lane & 3;
     // The loads run through the passes without a break (a lane without a task in a pass reads
@@ -354,10 +353,21 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         ws.task = task + kBlocksPerWg;
         ws.base += sd.nsteps * 64;
         left -= sd.nsteps;
-        if ((sd.nsteps & kStepUnroll) && slot + 1 < sd.slots) {
+        // The batch that holds the next pass's first step becomes batch 0: a batch holds the
+        // steps it was refilled with kAhead batches earlier, so after a pass of nsteps / 4
+        // batches the roles have moved on by that count modulo kAhead.
+        if (slot + 1 < sd.slots) {
+            static_assert(kAhead == 2 || kAhead == 3, "run_stage: pass boundary written for two or three batches");
+            const int rot = (sd.nsteps / kStepUnroll) % kAhead;
 #pragma unroll
             for (int u = 0; u < kStepUnroll; ++u) {
-                const float4 t_ = ws.q[0][u]; ws.q[0][u] = ws.q[1][u]; ws.q[1][u] = t_;
+                if (kAhead == 2) {
+                    if (rot == 1) { const float4 t_ = ws.q[0][u]; ws.q[0][u] = ws.q[1][u]; ws.q[1][u] = t_; }
+                } else {
+                    const float4 a_ = ws.q[0][u], b_ = ws.q[1][u], c_ = ws.q[kAhead - 1][u];
+                    if (rot == 1) { ws.q[0][u] = b_; ws.q[1][u] = c_; ws.q[kAhead - 1][u] = a_; }
+                    else if (rot == 2) { ws.q[0][u] = c_; ws.q[1][u] = a_; ws.q[kAhead - 1][u] = b_; }
+                }
             }
         }
     }

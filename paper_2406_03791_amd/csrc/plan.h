@@ -26,7 +26,7 @@ constexpr int kMaxDur = 8;
 constexpr int kMaxRows = 16;         // utterances per team
 constexpr int kMaxSamples = 32;      // (utterance, frame) pairs per joint step
 constexpr int kStepUnroll = 4;       // weight loads (16 bytes per lane) per software-pipeline batch
-constexpr int kAheadSteps = 2 * kStepUnroll;   // loads a lane keeps in flight: two batches
+constexpr int kAheadSteps = 4 * kStepUnroll;   // at least the loads a lane keeps in flight (the packed buffers' end padding)
 
 // Storage of the packed weights: fp32 (4 K values per 16-byte load), bf16 (8 per load) or
 // fp8 in the OCP e4m3 format (16 per load).  With the three storage types the arithmetic is
