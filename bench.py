@@ -142,6 +142,10 @@ def main() -> int:
                     help="storage of the streamed weights for the timed decoder; bf16 / fp8 decode "
                          "another model (the one with weights rounded to that format), so their "
                          "figures stand beside the fp32 headline, never for it")
+    ap.add_argument("--arithmetic", default="f32", choices=["f32", "bf16"],
+                    help="bf16: the engine's RNNT_FLAG_BF16_ARITHMETIC mode (weights and every input "
+                         "of a dense product rounded to bfloat16, float accumulation); a reduced-"
+                         "precision mode, so its figures stand beside the f32 headline, never for it")
     ap.add_argument("--plain-launch", action="store_true",
                     help="create the engines with RNNT_FLAG_PLAIN_LAUNCH (ordinary instead of "
                          "cooperative launch): for runs under rocprofv3, see the header")
@@ -214,7 +218,7 @@ def main() -> int:
                                                "launches": 4}}))
         return 0
 
-    def run_variant(variant, steps, warmup, storage="fp32", logp=False, cfg=None):
+    def run_variant(variant, steps, warmup, storage="fp32", logp=False, cfg=None, arithmetic="f32"):
         cfg = {"frame": 2, "label": 3, "tdt": 4}[variant] if cfg is None else cfg
         w = synth.make_workload(cfg, B=args.batch)
         flags = 0
@@ -227,6 +231,8 @@ def main() -> int:
                 "bf16": (synth.with_bf16_streamed_weights, pkg.RNNT_FLAG_BF16_WEIGHTS),
                 "fp8": (synth.with_fp8_streamed_weights, pkg.RNNT_FLAG_FP8_WEIGHTS)}[storage]
             w = dataclasses.replace(w, model=transform(w.model))
+        if arithmetic == "bf16":
+            flags |= pkg.RNNT_FLAG_BF16_ARITHMETIC
         if args.plain_launch:
             flags |= pkg.RNNT_FLAG_PLAIN_LAUNCH
         eng = pkg.Engine(w.model, w.B, w.T, flags=flags)
@@ -261,12 +267,17 @@ def main() -> int:
         eng.close()
         return res
 
-    r = run_variant(args.variant, args.steps, args.warmup, storage=args.storage)
+    if args.arithmetic == "bf16" and args.storage != "fp32":
+        print("bench.py: --arithmetic bf16 stores its weights as bf16 already; leave --storage "
+              "at fp32", file=sys.stderr)
+        return 2
+    r = run_variant(args.variant, args.steps, args.warmup, storage=args.storage,
+                    arithmetic=args.arithmetic)
     w = r["w"]
     n_frames = w.frames
     ms_per_step = 1e3 * r["wall"] / r["steps"]
     value = n_frames * r["steps"] / r["wall"]
-    wb = {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage]
+    wb = 2 if args.arithmetic == "bf16" else {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage]
     lit_bytes, lit_pred, lit_joint, _ = algorithmic_bytes(
         w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols, wb)
     min_bytes, min_pred, min_joint, _ = minimum_schedule_bytes(
@@ -276,14 +287,15 @@ def main() -> int:
     step_bytes = issued_weight_bytes(w.model.dims, r["stats"], wb)
     t_dec = r["dec_ms"] * 1e-3
     achieved = min_bytes / t_dec / 1e9
-    std = args.batch == 32 and args.storage == "fp32"
+    std = args.batch == 32 and args.storage == "fp32" and args.arithmetic == "f32"
     traffic = profiled(args.variant, "decode_kernel_traffic_bytes_per_launch") if std else None
     l2_peak = measured_ceiling("stream_from_l2_GBs")
     line = {
         "metric": "encoder frames decoded/sec, Parakeet-1.1B decoder shape, B=32",
         "value": value, "unit": "frames/s", "n_gpus": 1, "steps": r["steps"],
         "warmup": args.warmup, "ms_per_step": ms_per_step, "us_per_frame": 1e6 / value,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.arithmetic,
         "data": "synthetic",
         "timing_note": "value and ms_per_step are host wall time over the timed calls, each followed "
                        "by rnnt_engine_stats (a device synchronisation and a small copy), so they "
@@ -294,7 +306,10 @@ def main() -> int:
                                f"max_symbols={w.max_symbols}, variant={args.variant}" +
                                ("" if args.storage == "fp32" else
                                 f", streamed weights rounded to and stored as {args.storage} "
-                                f"(another model than the headline's; fp32 arithmetic)"),
+                                f"(another model than the headline's; fp32 arithmetic)") +
+                               ("" if args.arithmetic == "f32" else
+                                ", bfloat16 products with float accumulation (reduced precision: "
+                                "not the headline)"),
                    "tokens": int(r["tok_len"].sum()), "device_status": r["status"],
                    "kernel_ms": {"decode": r["dec_ms"], "decode_min": r["dec_ms_min"],
                                  "encoder_projection": r["proj_ms"]},
@@ -345,6 +360,15 @@ def main() -> int:
         rv = run_variant(v, max(3, args.steps // 2), 2)
         line["variants"][v] = {"frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"],
                                "decode_ms": rv["dec_ms"], "status": rv["status"]}
+    # the engine's bfloat16 mode (bf16 MFMA, float accumulation): reduced precision, so it is
+    # listed beside the f32 figures and never stands for them
+    for v in ("frame", "label", "tdt"):
+        if args.no_variants or args.arithmetic == "bf16":
+            break
+        rv = run_variant(v, max(3, args.steps // 2), 2, arithmetic="bf16")
+        line["variants"][v + "_bf16_arithmetic"] = {
+            "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
+            "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
     if args.all_variants:
         # label looping that also returns the log-probability of every label (fused log-sum-exp)
         rv = run_variant("label", max(3, args.steps // 2), 2, logp=True)
@@ -403,7 +427,9 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         cores = min(16, os.cpu_count() or 1)
-        net = oracle.LstmNet(w.model)
+        # in the bfloat16 mode the reference is the oracle's emulation of that arithmetic (token
+        # identity is then not expected on every row: near-ties resolve by rounding order)
+        net = oracle.LstmNet(w.model, bf16=args.arithmetic == "bf16")
         sched = "seq"
         # repeat the batch until about 12 CPU-seconds have been spent (at most 8 passes)
         passes, dt = 0, 0.0
