@@ -105,6 +105,18 @@ __device__ __forceinline__ void x_store4(float *row, int k, float4 v)      // k 
     }
 }
 
+// four consecutive values of an activation row, as floats
+template <int WT>
+__device__ __forceinline__ float4 x_load4(const float *row, int k)        // k a multiple of 4
+{
+    if (WT == kWeightBf16Arith) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(reinterpret_cast<const unsigned *>(row) + (k >> 1));
+        return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                           __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+    }
+    return *reinterpret_cast<const float4 *>(row + k);
+}
+
 typedef short v4s __attribute__((ext_vector_type(4)));
 // four bf16 values held in two 32-bit registers, as the operand type of the bf16 MFMA
 __device__ __forceinline__ v4s bf16x4(float lo, float hi)
@@ -119,6 +131,17 @@ typedef __attribute__((address_space(1))) unsigned global_u32;
 typedef __attribute__((address_space(1))) int global_i32;
 __device__ __forceinline__ global_u32 *as_global(unsigned *p) { return (global_u32 *)p; }
 __device__ __forceinline__ global_i32 *as_global(int *p) { return (global_i32 *)p; }
+
+// The thread's index as a value the compiler cannot trace back to the start of the kernel.
+// Everything derived from it (row and column numbers, addresses into the exchange buffers and
+// LDS) is then computed where it is used; otherwise those loop-invariant values are all
+// computed once before the decode loop and kept for its whole length, which takes more
+// registers than there are and puts reloads in front of the loads a step waits for.
+__device__ __forceinline__ int rederive(int v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
 
 struct Wg {
     int team, rank, tid, lane, wave;
@@ -357,17 +380,19 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         // steps it was refilled with kAhead batches earlier, so after a pass of nsteps / 4
         // batches the roles have moved on by that count modulo kAhead.
         if (slot + 1 < sd.slots) {
-            static_assert(kAhead == 2 || kAhead == 3, "run_stage: pass boundary written for two or three batches");
             const int rot = (sd.nsteps / kStepUnroll) % kAhead;
 #pragma unroll
             for (int u = 0; u < kStepUnroll; ++u) {
-                if (kAhead == 2) {
-                    if (rot == 1) { const float4 t_ = ws.q[0][u]; ws.q[0][u] = ws.q[1][u]; ws.q[1][u] = t_; }
-                } else {
-                    const float4 a_ = ws.q[0][u], b_ = ws.q[1][u], c_ = ws.q[kAhead - 1][u];
-                    if (rot == 1) { ws.q[0][u] = b_; ws.q[1][u] = c_; ws.q[kAhead - 1][u] = a_; }
-                    else if (rot == 2) { ws.q[0][u] = c_; ws.q[1][u] = a_; ws.q[kAhead - 1][u] = b_; }
-                }
+                float4 t_[kAhead];
+#pragma unroll
+                for (int i = 0; i < kAhead; ++i) t_[i] = ws.q[i][u];
+                // constant indices on every path: the batches stay in registers
+#pragma unroll
+                for (int r = 1; r < kAhead; ++r)
+                    if (rot == r) {
+#pragma unroll
+                        for (int i = 0; i < kAhead; ++i) ws.q[i][u] = t_[(i + r) % kAhead];
+                    }
             }
         }
     }
@@ -391,6 +416,7 @@ __device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf
 
 struct Lds {
     float *xz, *red, *c, *part, *q, *hc;
+    float *tail;                      // this rank's tail column: weight row, then [waves][kMaxSamples] partial sums
     float *b_pred, *b_out, *b_lstm;   // this rank's slices of the bias vectors
 };
 
@@ -524,8 +550,10 @@ template <int Q>
 __device__ __forceinline__ float quad_lane(float v) { return dpp_f32<Q * 0x55>(v); }
 
 template <int WT>
-__device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l)
+__device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, const Wg &w_in, Sync &sy, const Lds &l)
 {
+    Wg w = w_in;
+    w.tid = rederive(w_in.tid); w.lane = w.tid & 63;
     constexpr int RG = 1;
     constexpr int KI = 2;                       // 64-bit words per row a thread polls: H, J <= 1024
     const int u0 = range_lo(w.rank, p.team_size, p.H), nu = range_hi(w.rank, p.team_size, p.H) - u0;
@@ -931,17 +959,22 @@ __device__ __forceinline__ void wait_words4(const DecodeParams &p, Sync &sy, con
 // c.s_valid.  Leaves c.s_k, c.s_v (token argmax and its logit) and c.s_d
 // (duration index) for every valid sample.
 template <int RG, int WT>
-__device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, Sync &sy, const Lds &l)
+__device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in, Sync &sy, const Lds &l)
 {
+    Wg w = w_in;
+    w.tid = rederive(w_in.tid); w.lane = w.tid & 63;
     const int ns = c.ns;
     const int rows_pad = RG * 4;
     const int kpad = p.sjoint.kpad;
     sy.jepoch += 1;
     const unsigned tag = sy.jepoch;
     const int parity = (int)(tag & 1u);
-    const int ng_all = (p.NOUT + 3) / 4;
+    const int ng_all = (p.nout_m + 3) / 4;
     const int g0 = range_lo(w.jrank, p.jteam_size, ng_all);
     const int ng = range_hi(w.jrank, p.jteam_size, ng_all) - g0;
+    // a rank with a tail column has one more candidate per sample than it has output groups
+    const bool has_tail = w.jrank < p.n_tail;
+    const int ngx = ng + (has_tail ? 1 : 0);
     PROF_MARK(w, 18);
     // z = relu(P[b, frame] + q[row]) for every sample.  Wave v builds the samples v, v + 8, ...,
     // so a sample's row addresses are uniform over the wave; a lane takes four floats at k = 4 *
@@ -1047,6 +1080,28 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
     }
     __syncthreads();
     PROF_MARK(w, 13);
+    if (has_tail) {
+        // This rank's tail column (output column nout_m + jrank) for every sample, while the
+        // first weight batches of the stage are on their way: wave v takes the v-th eighth of
+        // K, 64 / rows_pad adjacent lanes share a sample, and the per-wave sums go to LDS.
+        constexpr int NSUB = 64 / (RG * 4);
+        const int k4n = (p.J + 3) >> 2, kw4 = (k4n + kWaves - 1) / kWaves;
+        const int s = w.lane / NSUB, sub = w.lane % NSUB;
+        const int lo = w.wave * kw4, hi = min(lo + kw4, k4n);
+        const float *zrow = l.xz + s * p.xstride;
+        float acc = 0.f;
+        for (int k4 = lo + sub; k4 < hi; k4 += NSUB) {
+            const float4 z = x_load4<WT>(zrow, k4 * 4);
+            const float4 wv = *reinterpret_cast<const float4 *>(l.tail + k4 * 4);
+            acc = fmaf(z.x, wv.x, acc); acc = fmaf(z.y, wv.y, acc);
+            acc = fmaf(z.z, wv.z, acc); acc = fmaf(z.w, wv.w, acc);
+        }
+        if (NSUB >= 2) acc += dpp_f32<0xB1>(acc);
+        if (NSUB >= 4) acc += dpp_f32<0x4E>(acc);
+        if (NSUB >= 8) acc += dpp_f32<0x141>(acc);
+        if (NSUB >= 16) acc += dpp_f32<0x140>(acc);
+        if (sub == 0) l.tail[((p.J + 3) & ~3) + w.wave * kMaxSamples + s] = acc;
+    }
     // with one slot the partial sums may overwrite z once every wave is done with it; the
     // output bias goes into the accumulators of every group's first K slice
     const bool alias = p.sjoint.slots == 1;
@@ -1059,8 +1114,9 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
     // added and the best of the four columns becomes a key.  The keys go where nothing is
     // live: into the partial-sum region when the sums sit in the z rows, else into the z rows.
     unsigned long long *cand = reinterpret_cast<unsigned long long *>(alias ? l.red : l.xz);
-    unsigned long long *cand_d = cand + ns * ng;
-    float *rank_max = reinterpret_cast<float *>(cand + 2 * ns * ng);      // [ns], for the scores
+    unsigned long long *cand_d = cand + ns * ngx;
+    float *rank_max = reinterpret_cast<float *>(cand + 2 * ns * ngx);     // [ns], for the scores
+    float *tail_sum = l.tail + ((p.J + 3) & ~3);
     {
         int nsp = 1, lg = 0;
         while (nsp < ns) { nsp <<= 1; ++lg; }
@@ -1076,8 +1132,19 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
                 if (col < p.V1) { const unsigned long long k = make_key(a[j], col); kt = k > kt ? k : kt; }
                 else if (col < p.NOUT) { const unsigned long long k = make_key(a[j], col - p.V1); kd = k > kd ? k : kd; }
             }
-            cand[s * ng + g] = kt;
-            if (p.D > 0) cand_d[s * ng + g] = kd;
+            cand[s * ngx + g] = kt;
+            if (p.D > 0) cand_d[s * ngx + g] = kd;
+        }
+        if (has_tail && w.tid < ns) {
+            // the tail column's logit: its bias plus the waves' sums; kept in the first wave's
+            // slot for the scores
+            float a = p.b_out[p.nout_m + w.jrank];
+#pragma unroll
+            for (int v = 0; v < kWaves; ++v) a += tail_sum[v * kMaxSamples + w.tid];
+            tail_sum[w.tid] = a;
+            const int col = p.nout_m + w.jrank;
+            cand[w.tid * ngx + ng] = col < p.V1 ? make_key(a, col) : 0ull;
+            if (p.D > 0) cand_d[w.tid * ngx + ng] = col < p.V1 ? 0ull : make_key(a, col - p.V1);
         }
     }
     __syncthreads();
@@ -1087,10 +1154,10 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
         const int s = w.tid >> 3, sub = w.tid & 7;
         unsigned long long kt = 0ull, kd = 0ull;
         if (s < ns)
-            for (int g = sub; g < ng; g += 8) {
-                const unsigned long long k = cand[s * ng + g];
+            for (int g = sub; g < ngx; g += 8) {
+                const unsigned long long k = cand[s * ngx + g];
                 kt = k > kt ? k : kt;
-                if (p.D > 0) { const unsigned long long d = cand_d[s * ng + g]; kd = d > kd ? d : kd; }
+                if (p.D > 0) { const unsigned long long d = cand_d[s * ngx + g]; kd = d > kd ? d : kd; }
             }
         kt = key_max8(kt);
         if (p.D > 0) kd = key_max8(kd);
@@ -1106,7 +1173,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
         // log-softmax of the maximum, first half: this rank's sum of exp(logit - its own maximum)
         // over its token columns (asked for only when the caller wants scores)
         __syncthreads();
-        float *se_part = rank_max + kMaxSamples;          // [ns][ng]
+        float *se_part = rank_max + kMaxSamples;          // [ns][ngx]
         int nsp = 1, lg = 0;
         while (nsp < ns) { nsp <<= 1; ++lg; }
         const int s = w.tid & (nsp - 1);
@@ -1117,12 +1184,14 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w, S
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 if ((g0 + g) * 4 + j < p.V1) se += expf(a[j] - rank_max[s]);
-            se_part[s * ng + g] = se;
+            se_part[s * ngx + g] = se;
         }
+        if (has_tail && w.tid < ns)
+            se_part[w.tid * ngx + ng] = p.nout_m + w.jrank < p.V1 ? expf(tail_sum[w.tid] - rank_max[w.tid]) : 0.f;
         __syncthreads();
         if (w.tid < ns) {
             float se = 0.f;
-            for (int g = 0; g < ng; ++g) se += se_part[w.tid * ng + g];
+            for (int g = 0; g < ngx; ++g) se += se_part[w.tid * ngx + g];
             const long long o =
                 (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + w.tid) * p.jteam_size + w.jrank;
             // the sum travels as a float in the high word (it is positive: no key order needed)
@@ -1240,6 +1309,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     Lds l;
     l.xz = dyn_lds + p.lds_xz; l.red = dyn_lds + p.lds_red; l.c = dyn_lds + p.lds_c;
     l.part = dyn_lds + p.lds_part; l.q = dyn_lds + p.lds_q; l.hc = dyn_lds + p.lds_hc;
+    l.tail = dyn_lds + p.lds_tail;
     l.b_pred = dyn_lds + p.lds_bias;
     l.b_out = l.b_pred + 4 * p.gp_max;
     l.b_lstm = l.b_out + 4 * p.gj_max;
@@ -1287,14 +1357,18 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     __syncthreads();
     // this rank's slices of the bias vectors
     {
-        const int gpa = (p.J + 3) / 4, gja = (p.NOUT + 3) / 4;
+        const int gpa = (p.J + 3) / 4, gja = (p.nout_m + 3) / 4;
         const int gp0 = range_lo(w.rank, p.team_size, gpa), ngp = range_hi(w.rank, p.team_size, gpa) - gp0;
         const int gj0 = range_lo(w.jrank, p.jteam_size, gja), ngj = range_hi(w.jrank, p.jteam_size, gja) - gj0;
         const int hu0 = range_lo(w.rank, p.team_size, p.H), hnu = range_hi(w.rank, p.team_size, p.H) - hu0;
         for (int i = w.tid; i < ngp * 4; i += kThreads)
             l.b_pred[i] = (gp0 * 4 + i < p.J) ? p.b_pred[gp0 * 4 + i] : 0.f;
         for (int i = w.tid; i < ngj * 4; i += kThreads)
-            l.b_out[i] = (gj0 * 4 + i < p.NOUT) ? p.b_out[gj0 * 4 + i] : 0.f;
+            l.b_out[i] = (gj0 * 4 + i < p.nout_m) ? p.b_out[gj0 * 4 + i] : 0.f;
+        if (w.jrank < p.n_tail) {
+            const int tk = (p.J + 3) & ~3;
+            for (int i = w.tid; i < tk; i += kThreads) l.tail[i] = p.w_tail[(long long)w.jrank * tk + i];
+        }
         for (int i = w.tid; i < p.L * hnu * 4; i += kThreads) {
             const int layer = i / (hnu * 4), rem = i - layer * hnu * 4;
             l.b_lstm[(layer * p.nu_max) * 4 + rem] = p.bias_l[((long long)layer * p.H + hu0) * 4 + rem];

@@ -43,6 +43,10 @@ struct DecodeParams {
     int samples_cap;        // samples of a joint step the z rows and argmax candidates in LDS are sized for
     int fast_pred;          // teams of up to 4 rows: hidden vectors kept in LDS, tagged exchange (no barriers)
     int lds_hc;             // offset of the LDS copies of the hidden vectors [2][L][4][xstride]
+    int n_tail;             // joint output columns nout_m .. nout_m + n_tail - 1 are computed by rank 0 .. n_tail - 1 with plain multiply-adds
+    int nout_m;             // joint output columns covered by the MFMA stage (NOUT when n_tail == 0)
+    int lds_tail;           // offset of a tail column's weight row [J rounded up to 4] and partial sums [waves][kMaxSamples]
+    const float *w_tail;    // [n_tail][J rounded up to 4]
     int q_in_lds;           // q = W_pred h + b_pred of the team's rows is kept in LDS
     int qstride;            // floats per q row in LDS
     unsigned lds_bytes;

@@ -100,6 +100,10 @@ struct TeamConfig {
     int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
     int q_in_lds = 0, qstride = 0;
     int fast_pred = 0, lds_hc = 0;
+    int n_tail = 0;        // joint output columns computed outside the MFMA stage, one per rank from rank 0 on
+    int nout_m = 0;        // joint output columns of the MFMA stage (a whole number of groups per rank when n_tail > 0)
+    int lds_tail = 0;
+    DevBuf w_tail;         // [n_tail][J rounded up to 4]: the tail columns' weight rows
     int samples_cap = kMaxSamples;   // (utterance, frame) pairs of a joint step the LDS layout has room for
     int rcap = 0;
     int rg_planned = 0;
@@ -176,7 +180,8 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     if (rows_max > kMaxRows) return RNNT_ERR_SHAPE;
     const int H = d.H, L = d.L, J = d.J;
     auto nu_of = [&](int r) { return range_hi(r, ts, H) - range_lo(r, ts, H); };
-    const int gp_all = (J + 3) / 4, gj_all = (e->NOUT + 3) / 4;
+    const int gp_all = (J + 3) / 4;
+    int gj_all = (e->NOUT + 3) / 4;          // output groups of the joint stage's MFMA part
     auto gp_of = [&](int r) { return range_hi(r, ts, gp_all) - range_lo(r, ts, gp_all); };
     auto gj_of = [&](int r) { return range_hi(r, tj, gj_all) - range_lo(r, tj, gj_all); };
     int nu_max = 0, gp_max = 0, gj_max = 0;
@@ -185,6 +190,15 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         gp_max = std::max(gp_max, gp_of(r));
     }
     for (int r = 0; r < tj; ++r) gj_max = std::max(gj_max, gj_of(r));
+    // Tail columns.  When the output width is a few columns more than a whole number of groups
+    // per rank (1024 labels + blank over 8 ranks: 257 groups), the extra group costs every rank a
+    // coarser K slicing.  Those columns, at most one per rank, can instead be computed with
+    // plain multiply-adds from LDS, and the MFMA part covers nout_m columns that divide evenly.
+    const int per = 4 * tj, nout_even = (e->NOUT / per) * per, tail_cols = e->NOUT - nout_even;
+    const int tail_k = (J + 3) & ~3;
+    auto plan_cost = [](const StagePlan &pl) { return (long)pl.slots * (pl.nsteps + kPassOverheadSteps); };
+    constexpr int kTailCostSteps = 4;        // what the tail's multiply-adds cost, in load steps
+    const int gj_all_full = gj_all, gj_max_full = gj_max;
     // Stage plans and LDS layout.  Stages with more groups than blocks are first planned with K
     // slices over several passes (best use of the blocks); if the partial sums of such a plan do
     // not fit the LDS, they fall back to unsliced tasks.
@@ -205,7 +219,18 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         t.st0.plan = make_stage_plan(H, L * nu_max, e->wt, single);
         for (int l = 1; l < L; ++l) t.stl[l].plan = make_stage_plan(H, nu_max, e->wt, single);
         t.spred.plan = make_stage_plan(H, gp_max, e->wt, single);
+        gj_all = gj_all_full; gj_max = gj_max_full;
         t.sjoint.plan = make_stage_plan(J, gj_max, e->wt, single);
+        t.n_tail = 0; t.nout_m = e->NOUT;
+        if (nout_even > 0 && tail_cols > 0 && tail_cols <= tj) {
+            const StagePlan even = make_stage_plan(J, nout_even / per, e->wt, single);
+            if (plan_cost(even) + kTailCostSteps < plan_cost(t.sjoint.plan)) {
+                t.sjoint.plan = even;
+                t.n_tail = tail_cols; t.nout_m = nout_even;
+                gj_all = nout_even / 4; gj_max = nout_even / per;
+            }
+        }
+        const int gjx = gj_max + (t.n_tail ? 1 : 0);    // candidates per sample: groups + the tail column
         int kpad = std::max({t.st0.plan.kpad, t.spred.plan.kpad, t.sjoint.plan.kpad});
         for (int l = 1; l < L; ++l) kpad = std::max(kpad, t.stl[l].plan.kpad);
         xstride = kpad + 4;
@@ -219,7 +244,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         // the joint step's argmax candidates (two 64-bit keys per sample and output group, the
         // per-sample maxima and the per-group exponential sums of the scores) go into the
         // partial-sum region when the joint sums sit in the z rows, else into the z rows
-        const int cand_need = samples_cap * gj_max * 4 + kMaxSamples + samples_cap * gj_max + 8;
+        const int cand_need = samples_cap * gjx * 4 + kMaxSamples + samples_cap * gjx + 8;
         if (t.sjoint.plan.slots == 1) {
             xz = std::max(xz, red_need(t.sjoint.plan, gj_max, rgj));
             red = std::max(red, cand_need);
@@ -236,6 +261,8 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         t.lds_c = take(L * 2 * nu_max * rows_max);
         t.lds_part = take(L * nu_max * rows_max * 4);
         t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
+        // a tail column's weight row and its per-wave partial sums
+        t.lds_tail = t.n_tail ? take(tail_k + kWaves * kMaxSamples) : 0;
         // room for a joint group's q rows as well (needed by joint groups, see below)
         const int q_need = groups > 1 ? ((rows_max + groups - 1) / groups) * ((J + 3) & ~3) : 0;
         if ((unsigned)(off + q_need) * 4u + (unsigned)kStaticLds <= (unsigned)kLdsBytes) break;
@@ -281,9 +308,16 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     if (rc) return rc;
     rc = upload_stage(t.sjoint, tj, gj_of, [&](int r, int g, int j) -> const float * {
         const int col = (range_lo(r, tj, gj_all) + g) * 4 + j;
-        return col < e->NOUT ? e->w_out.data() + (size_t)col * J : nullptr;
+        return col < t.nout_m ? e->w_out.data() + (size_t)col * J : nullptr;
     });
     if (rc) return rc;
+    if (t.n_tail) {
+        std::vector<float> rows((size_t)t.n_tail * tail_k, 0.f);
+        for (int i = 0; i < t.n_tail; ++i)
+            std::copy_n(e->w_out.data() + (size_t)(t.nout_m + i) * J, J, rows.data() + (size_t)i * tail_k);
+        HIP_TRY(t.w_tail.alloc(rows.size() * sizeof(float)));
+        HIP_TRY(hipMemcpy(t.w_tail.p, rows.data(), rows.size() * sizeof(float), hipMemcpyHostToDevice));
+    }
 
     // team workspace
     const WorkspaceSizes z = workspace_sizes(n_teams, ts, groups, L, H, J);
@@ -445,6 +479,8 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
     p.lds_q = t.lds_q; p.q_in_lds = t.q_in_lds; p.qstride = t.qstride;
     p.fast_pred = t.fast_pred; p.lds_hc = t.lds_hc;
+    p.n_tail = t.n_tail; p.nout_m = t.nout_m; p.lds_tail = t.lds_tail;
+    p.w_tail = t.n_tail ? t.w_tail.as<float>() : nullptr;
     p.rcap = t.rcap;
     p.rg_planned = t.rg_planned;
     p.samples_cap = t.samples_cap;
