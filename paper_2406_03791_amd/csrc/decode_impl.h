@@ -30,7 +30,8 @@ struct Ctl {
     int s_row[kMaxSamples], s_frame[kMaxSamples], s_valid[kMaxSamples];
     int s_k[kMaxSamples], s_d[kMaxSamples];
     float s_v[kMaxSamples], s_lp[kMaxSamples];   // maximum logit and its log-softmax value
-    int R, ns, any, bar_ok, committed;
+    int R, ns, bar_ok, committed;
+    int any[2];                    // Algorithm 1: some row emitted in this inner step (two slots, used in turn)
     int f_any_active, f_need_pred, f_any_searching;   // loop decisions of the control wave
     int st_clamped, st_overflow;   // set to 1 by any thread (same value from all writers)
     int durations[kMaxDur];
@@ -922,13 +923,21 @@ __device__ __forceinline__ bool has_tag(unsigned long long word, unsigned tag)
 // Read up to four tagged words (slots base[r0], base[r0 + stride], ...; n of them) with all
 // loads in flight together, polling again only for those that are not there yet.  Bounded:
 // gives up (and raises the abort flag) after spin_limit polls or when another work-group has
-// raised it.  Tags are stripped from what is returned.
+// raised it.  Tags are stripped from what is returned.  With PRELOADED the caller has already
+// issued the first round of loads into `out` (read_words4), together with those of another set
+// of words it waits for first.
+__device__ __forceinline__ void read_words4(const unsigned long long *base, int stride, int n,
+                                            unsigned long long (&out)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = i < n ? xload64(base + i * stride) : 0ull;
+}
+template <bool PRELOADED = false>
 __device__ __forceinline__ void wait_words4(const DecodeParams &p, Sync &sy, const unsigned long long *base,
                                             int stride, int n, unsigned tag, unsigned long long (&out)[4])
 {
     unsigned spins = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) out[i] = i < n ? xload64(base + i * stride) : 0ull;
+    if (!PRELOADED) read_words4(base, stride, n, out);
     for (;;) {
         bool all = true;
 #pragma unroll
@@ -1211,7 +1220,8 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
                 (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) * p.jteam_size;
             for (int r0 = sub; r0 < p.jteam_size; r0 += 64) {
                 const int n = min(4, (p.jteam_size - r0 + 15) >> 4);
-                unsigned long long wd[4];
+                unsigned long long wd[4], wdur[4];
+                if (p.D > 0) read_words4(p.dpart + o + r0, 16, n, wdur);   // in flight with the token words
                 wait_words4(p, sy, p.part + o + r0, 16, n, tag, wd);
                 if (p.logps) {
                     unsigned long long wl[4];
@@ -1223,9 +1233,9 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
 #pragma unroll
                 for (int i = 0; i < 4; ++i) kt = wd[i] > kt ? wd[i] : kt;
                 if (p.D > 0) {
-                    wait_words4(p, sy, p.dpart + o + r0, 16, n, tag, wd);
+                    wait_words4<true>(p, sy, p.dpart + o + r0, 16, n, tag, wdur);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) kd = wd[i] > kd ? wd[i] : kd;
+                    for (int i = 0; i < 4; ++i) kd = wdur[i] > kd ? wdur[i] : kd;
                 }
             }
         }
@@ -1329,7 +1339,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     }
     if (R == 0) return;            // the whole team leaves: no barrier is ever entered
     if (w.tid == 0) {
-        c.R = R; c.ns = 0; c.bar_ok = 1; c.committed = 0; c.any = 0;
+        c.R = R; c.ns = 0; c.bar_ok = 1; c.committed = 0; c.any[0] = 0; c.any[1] = 0;
         c.st_clamped = 0; c.st_overflow = 0;
 #pragma unroll
         for (int i = 0; i < kMaxDur; ++i) c.durations[i] = p.durations[i];
@@ -1418,6 +1428,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         int max_out_len = 0;
         for (int r = 0; r < R; ++r) max_out_len = max(max_out_len, c.len[r]);
         bool need_pred = true;     // nothing computed yet for (last_label, hidden)
+        int flip = 0;              // slot of c.any the next inner step reports in
         int win0 = 0, win_n = 0;   // frames [win0, win0 + win_n) have results for the current g
         for (int time_idx = 0; ok && time_idx < max_out_len; ++time_idx) {
             // Frames the window already covers and on which every row produced a blank change
@@ -1485,13 +1496,15 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                         if (k == p.blank) { c.mask[r] = 1; }          // blank_mask |= (k == blank)
                         else { emit_row(p, w, r, k, time_idx, c.s_v[off * R + r], c.s_lp[off * R + r], 0); any = 1; }
                     }
-                    c.any = any;
+                    c.any[flip] = any;
                 }
                 __syncthreads();
-                not_blank = c.any != 0;
+                // the next inner step reports in the other slot, and this slot is written again
+                // only after the barrier of that step: no second barrier is needed here
+                not_blank = c.any[flip] != 0;
+                flip ^= 1;
                 need_pred = need_pred || not_blank;
                 symbols_added += 1;
-                __syncthreads();
             }
         }
     } else {
