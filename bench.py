@@ -165,6 +165,10 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true",
                     help="also time Algorithm 1 and label looping over batch sizes 1..128 on the "
                          "typical workload and on the adversarial batches; listed under 'sweep'")
+    ap.add_argument("--team-sweep", action="store_true",
+                    help="instead of the benchmark line: time the decoders under other team layouts "
+                         "(rnnt_engine_configure) than the default ones, one utterance and B = 32, and "
+                         "print them as JSON (the figures behind the default layouts)")
     ap.add_argument("--all-variants", action="store_true",
                     help="also time label looping with log-probabilities, the single-layer second "
                          "workload and the three decoders with bf16-stored and 8-bit (e4m3) stored "
@@ -205,6 +209,41 @@ def main() -> int:
             "exchange": exch,
             "mfma_f32_tflops": {"4x4x1_16_blocks": pkg.rnnt_probe_mfma(0), "32x32x2": pkg.rnnt_probe_mfma(1),
                                 "published_peak": 157.3}}}))
+        return 0
+
+    if args.team_sweep:
+        rows = []
+        for variant, B, layouts in (("label", 1, ((8, 1), (4, 1), (2, 1), (1, 1))),
+                                    ("label", 32, ((16, 2), (16, 1), (8, 4), (8, 2), (32, 1))),
+                                    ("frame", 32, ((32, 1), (16, 1), (8, 1))),
+                                    ("tdt", 32, ((16, 2), (8, 4), (32, 1)))):
+            w = synth.make_workload({"frame": 2, "label": 3, "tdt": 4}[variant], B=B)
+            eng = pkg.Engine(w.model, w.B, w.T)
+            enc = torch.from_numpy(w.enc_out).cuda().contiguous()
+            ln = torch.from_numpy(w.enc_len).cuda()
+            out = eng.alloc_outputs(w.B, w.T * w.max_symbols)
+            ref = None
+            for n_teams, groups in layouts:
+                try:
+                    eng.configure(n_teams=n_teams, joint_groups=groups if variant != "frame" else 0)
+                except Exception as exc:                 # a layout the LDS cannot hold
+                    rows.append({"variant": variant, "B": B, "n_teams": n_teams, "joint_groups": groups,
+                                 "refused": str(exc)})
+                    continue
+                ms = []
+                for i in range(8):
+                    eng.decode(variant, enc, ln, w.max_symbols, out=out)
+                    st = eng.stats()
+                    if i >= 2:
+                        ms.append(st["decode_ms"])
+                tok = out["tokens"].cpu().numpy()
+                ref = tok if ref is None else ref
+                rows.append({"variant": variant, "B": B, "n_teams": st["n_teams"], "team_size": st["team_size"],
+                             "joint_groups": st["joint_groups"], "decode_ms": float(np.median(ms)),
+                             "decode_ms_min": float(np.min(ms)), "status": eng.status(),
+                             "tokens_equal_first_layout": bool(np.array_equal(tok, ref))})
+            eng.close()
+        print(json.dumps({"team_sweep": rows}))
         return 0
 
     if args.copy_calibration:

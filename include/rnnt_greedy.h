@@ -243,7 +243,7 @@ int rnnt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int3
  * library holds as a static device object on every device it runs on, until
  * the process ends.  The entry point calls no hipMalloc, hipFree or other
  * allocating routine; the engine (its packed weights) is created beforehand.
- * A call that needs more (roughly B * T * J * 4 bytes plus 5 MiB at the
+ * A call that needs more (roughly B * T * J * 4 bytes plus 9 MiB at the
  * Parakeet shape) returns RNNT_ERR_SCRATCH and queues nothing.
  * All calls on one device share the array, which keeps the last call's
  * contents (the call clears what must start at zero): calls through this entry

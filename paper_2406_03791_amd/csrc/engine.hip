@@ -358,17 +358,18 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
 //   lock-step waiting between utterances, and a prediction step per label of one utterance
 //   only): 8, 16 or 32 teams; beyond 32 utterances the teams take several rows each.
 //   Label looping: 8 teams of 32 up to 16 utterances, 16 teams of 16 beyond; two joint groups
-//   per team from 9 utterances on.  (Teams of 64 were only faster while a team had to sit on
-//   its own XCDs.)
+//   per team from 9 utterances on.
+//   Engines for one or two utterances: 4 teams of 64 for either decoder (2-5 % faster than 8
+//   teams of 32 there, equal from four utterances on; teams of 128 and 256 are slower).
 int default_layouts(rnnt_engine *e)
 {
     const int max_B = e->max_B;
-    int nf = max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32);
+    int nf = max_B <= 2 ? 4 : (max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32));
     while (nf > 1 && e->n_wg % nf != 0) nf /= 2;
     while ((max_B + nf - 1) / nf > kMaxRows) nf *= 2;
     int rc = plan_and_pack(e, e->frame_cfg, nf, 1);
     if (rc) return rc;
-    int nl = max_B <= 16 ? 8 : 16;
+    int nl = max_B <= 2 ? 4 : (max_B <= 16 ? 8 : 16);
     while (nl > 1 && e->n_wg % nl != 0) nl /= 2;
     while ((max_B + nl - 1) / nl > kMaxRows) nl *= 2;
     const int rows = (max_B + nl - 1) / nl;
