@@ -33,6 +33,8 @@ def _lib(real: str):
             getattr(lib, name).argtypes = [C.c_void_p, C.c_void_p]
             getattr(lib, name).restype = C.c_int
         lib.orc_follow_sequential.restype = C.c_int
+        lib.orc_net_as_multi_blank.argtypes = [C.c_void_p]
+        lib.orc_net_as_multi_blank.restype = None
         lib.orc_lstm_net_emulate_bf16.argtypes = [C.c_void_p]
         lib.orc_lstm_net_emulate_bf16.restype = None
         lib.orc_round_bf16.argtypes = [C.c_float if real == "float" else C.c_double]
@@ -122,20 +124,29 @@ class LstmNet(Net):
         w_hh = [cv(a) for a in model.w_hh]
         b_ih = [cv(a) for a in model.b_ih]
         b_hh = [cv(a) for a in model.b_hh]
-        dur = np.ascontiguousarray(model.durations, dtype=np.int32)
+        # a multi-blank model's extra output columns are its big blanks; the net is created
+        # with them in the place of durations and then told what they are
+        spans = tuple(getattr(d, "big_blanks", ()))
+        assert not (spans and d.D), "a model has durations or big blanks, not both"
+        dur = np.ascontiguousarray(spans if spans else model.durations, dtype=np.int32)
+        n_extra = len(spans) if spans else d.D
         self._keep = [emb, w_enc, b_enc, w_pred, b_pred, w_out, b_out, w_ih, w_hh,
                       b_ih, b_hh, dur]
         PA = C.c_void_p * d.L
         arr = lambda lst: PA(*[a.ctypes.data for a in lst])
         self.handle = self.lib.orc_lstm_net_create(
             C.c_int(d.F), C.c_int(d.E), C.c_int(d.H), C.c_int(d.L), C.c_int(d.J),
-            C.c_int(d.V1), C.c_int(d.D), C.c_int(d.blank), _ptr(dur), _ptr(emb),
+            C.c_int(d.V1), C.c_int(n_extra), C.c_int(d.blank), _ptr(dur), _ptr(emb),
             arr(w_ih), arr(w_hh), arr(b_ih), arr(b_hh), _ptr(w_enc), _ptr(b_enc),
             _ptr(w_pred), _ptr(b_pred), _ptr(w_out), _ptr(b_out))
         self.x_size, self.p_size = d.F, d.J
         self.state_size, self.g_size = 2 * d.L * d.H, d.H
         self.V1, self.D, self.blank, self.n_out = d.V1, d.D, d.blank, d.n_out
         self.durations = dur
+        self.big_blanks = spans
+        if spans:
+            self.D = 0
+            self.lib.orc_net_as_multi_blank(C.c_void_p(self.handle))
         self.bf16 = bool(bf16)
         if bf16:
             self.lib.orc_lstm_net_emulate_bf16(C.c_void_p(self.handle))
@@ -147,8 +158,13 @@ class TableNet(Net):
     not depend on the last label may be given as [B, T, U, V1 + D]."""
 
     def __init__(self, table: np.ndarray, V1: int, durations: Sequence[int] = (),
-                 real: str = "float"):
+                 real: str = "float", big_blanks: Sequence[int] = ()):
+        """big_blanks: spans of a multi-blank model's big-blank symbols, which then take the
+        place of the duration columns (last axis V1 + len(big_blanks))."""
         super().__init__(real)
+        assert not (len(durations) and len(big_blanks))
+        if len(big_blanks):
+            durations = big_blanks
         D = len(durations)
         t = np.asarray(table, dtype=self.dtype)
         if t.ndim == 4:
@@ -163,6 +179,10 @@ class TableNet(Net):
         self.x_size, self.p_size, self.state_size, self.g_size = 1, 1, 1, 2
         self.V1, self.D, self.blank, self.n_out = V1, D, V1 - 1, V1 + D
         self.durations = dur
+        self.big_blanks = tuple(big_blanks)
+        if len(big_blanks):
+            self.D = 0
+            self.lib.orc_net_as_multi_blank(C.c_void_p(self.handle))
 
     def frames(self) -> np.ndarray:
         """The encoder 'output' that carries each cell's index."""

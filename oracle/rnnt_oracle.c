@@ -84,6 +84,8 @@ struct net {
     int D;           /* number of durations (0 = RNN-T)                       */
     int blank;       /* blank index, also the start-of-sequence label         */
     const int32_t *durations; /* [D] */
+    int NB;          /* multi-blank transducer: number of "big blank" symbols  */
+    const int32_t *spans;     /* [NB] frames each big blank advances by        */
     void (*prep)(const net_t *, const real *x_row, real *p_row);
     void (*pred)(const net_t *, int last_label, const real *state_in,
                  real *state_out, real *g);
@@ -339,6 +341,22 @@ net_t *orc_table_net_create(int V1, int D, int blank, const int32_t *durations,
     return n;
 }
 
+/* Multi-blank transducer (the paper's related work names it beside TDT as a  */
+/* model that lets the decoder skip encoder frames): besides the labels and   */
+/* the blank the output layer has NB "big blank" symbols, each with a span of  */
+/* m_i frames.  All V1 + NB outputs form one distribution and one argmax.  A   */
+/* blank advances the frame index by 1 and a big blank by its span; neither    */
+/* is emitted, neither changes the prediction network's input, and both reset  */
+/* the count of labels on the frame.  A label is handled as in an RNN-T.       */
+/* This call re-reads a net created with D extra output columns: the columns   */
+/* become the big blanks and their "durations" the spans; D becomes 0.         */
+void orc_net_as_multi_blank(net_t *n)
+{
+    n->NB = n->D;
+    n->spans = n->durations;
+    n->D = 0;
+}
+
 void orc_net_destroy(net_t *n)
 {
     if (!n) return;
@@ -510,6 +528,7 @@ static void cache_free(frame_cache *fc) { free(fc->p); free(fc->have); }
 int orc_decode_frame_looping(const net_t *net, decode_io *io)
 {
     if (net->D != 0) return -1;   /* batched frame looping is not exact for TDT */
+    if (net->NB != 0) return -1;  /* Algorithm 1 has one frame index for the whole batch */
     const int B = io->B, SS = net->state_size, GS = net->g_size;
     const int blank_index = net->blank;
     clear_outputs(io);
@@ -597,13 +616,14 @@ int orc_decode_label_looping(const net_t *net, decode_io *io)
 {
     const int B = io->B, SS = net->state_size, GS = net->g_size;
     const int V1 = net->V1, D = net->D, blank = net->blank, S = io->S;
+    const int NB = net->NB, VT = V1 + NB;     /* VT: width of the token distribution */
     clear_outputs(io);
     int32_t status = 0;
     frame_cache fc; cache_init(&fc, net, io);
     real *state = (real *)calloc((size_t)B * SS, sizeof(real));
     real *state_prime = (real *)calloc((size_t)B * SS, sizeof(real));
     real *g = (real *)calloc((size_t)B * GS, sizeof(real));
-    real *logits = (real *)calloc((size_t)(V1 + D), sizeof(real));
+    real *logits = (real *)calloc((size_t)(VT + D), sizeof(real));
     int *last = (int *)malloc(sizeof(int) * (size_t)B);
     int *len = (int *)malloc(sizeof(int) * (size_t)B);
     int *t = (int *)calloc((size_t)B, sizeof(int));
@@ -639,24 +659,27 @@ int orc_decode_label_looping(const net_t *net, decode_io *io)
                 if (!searching[b]) continue;
                 if (!first) {
                     /* the previous evaluation of this row was a blank         */
+                    /* (a TDT blank advances by its duration, at least 1; a big   */
+                    /* blank by its span, kept in d[b] as well)                   */
                     int adv = 1;
-                    if (D > 0) adv = d[b] > 1 ? d[b] : 1;
+                    if (D > 0 || NB > 0) adv = d[b] > 1 ? d[b] : 1;
                     t[b] += adv; n[b] = 0;
                     if (t[b] >= len[b]) { searching[b] = 0; active[b] = 0; continue; }
                 }
                 net->joint(net, cache_get(&fc, b, t[b]), g + (size_t)b * GS, logits);
                 io->stat_joint_rows++;
                 real mg, dmg = 0, dv;
-                k[b] = argmax_margin(logits, 0, V1, &v[b], &mg);
-                if (io->logps) lp[b] = log_prob_of_top(logits, V1, v[b]);
+                k[b] = argmax_margin(logits, 0, VT, &v[b], &mg);
+                if (io->logps) lp[b] = log_prob_of_top(logits, VT, v[b]);
                 int dval = 0;
                 if (D > 0) {
                     const int di = argmax_margin(logits, V1, V1 + D, &dv, &dmg) - V1;
                     dval = net->durations[di];
                 }
+                if (k[b] >= V1) dval = net->spans[k[b] - V1];      /* a big blank */
                 d[b] = dval;
                 record(io, b, t[b], k[b], v[b], mg, dval, dmg, &status);
-                if (k[b] != blank) searching[b] = 0;
+                if (k[b] != blank && k[b] < V1) searching[b] = 0;
             }
             first = 0;
             any_searching = 0;
@@ -695,11 +718,12 @@ static void decode_one(const net_t *net, decode_io *io, int b, int32_t *status,
 {
     const int SS = net->state_size, GS = net->g_size, V1 = net->V1, D = net->D;
     const int blank = net->blank, S = io->S;
+    const int NB = net->NB, VT = V1 + NB;
     real *state = (real *)calloc((size_t)SS, sizeof(real));
     real *state_prime = (real *)calloc((size_t)SS, sizeof(real));
     real *g = (real *)calloc((size_t)GS, sizeof(real));
     real *p = (real *)calloc((size_t)net->p_size, sizeof(real));
-    real *logits = (real *)calloc((size_t)(V1 + D), sizeof(real));
+    real *logits = (real *)calloc((size_t)(VT + D), sizeof(real));
     const int len = clamp_len(io, b, status);
     int t = 0, n = 0, last = blank, p_frame = -1;
     if (len > 0) { net->pred(net, last, state, state_prime, g); (*pred_rows)++; }
@@ -711,15 +735,16 @@ static void decode_one(const net_t *net, decode_io *io, int b, int32_t *status,
         net->joint(net, p, g, logits);
         (*joint_rows)++;
         real v, mg, dv, dmg = 0;
-        const int k = argmax_margin(logits, 0, V1, &v, &mg);
+        const int k = argmax_margin(logits, 0, VT, &v, &mg);
         int dval = 0;
         if (D > 0) dval = net->durations[argmax_margin(logits, V1, V1 + D, &dv, &dmg) - V1];
+        if (k >= V1) dval = net->spans[k - V1];                    /* a big blank */
         record(io, b, t, k, v, mg, dval, dmg, status);
-        if (k == blank) {
-            t += (D > 0 && dval > 1) ? dval : 1;
+        if (k == blank || k >= V1) {
+            t += ((D > 0 || NB > 0) && dval > 1) ? dval : 1;
             n = 0;
         } else {
-            emit(io, b, k, t, v, io->logps ? log_prob_of_top(logits, V1, v) : (real)0, dval, status);
+            emit(io, b, k, t, v, io->logps ? log_prob_of_top(logits, VT, v) : (real)0, dval, status);
             last = k;
             memcpy(state, state_prime, sizeof(real) * (size_t)SS);
             if (D > 0 && dval > 0) { t += dval; n = 0; }
