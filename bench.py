@@ -420,6 +420,13 @@ def main() -> int:
             line["variants"][v + "_small_model"] = {
                 "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
                 "frames": rv["w"].frames, "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
+        # the multi-blank transducer of configuration 6 (two big blanks that skip 2 and 4 frames)
+        rv = run_variant("label", max(3, args.steps // 2), 2, cfg=6)
+        line["variants"]["label_multi_blank_model"] = {
+            "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
+            "frames": rv["w"].frames, "tokens": int(rv["tok_len"].sum()),
+            "max_pred_steps": rv["stats"]["max_pred_steps"],
+            "max_joint_steps": rv["stats"]["max_joint_steps"], "status": rv["status"]}
         # the same decoders on the models with bf16-valued / e4m3-valued streamed weights, stored
         # in that format: other models (their tokens differ from the fp32 model's), reported
         # beside, never as value

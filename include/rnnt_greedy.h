@@ -44,7 +44,7 @@ enum {
     RNNT_OK = 0,
     RNNT_ERR_NULL = -1,        /* a required pointer is NULL                   */
     RNNT_ERR_SHAPE = -2,       /* a dimension or count is out of range         */
-    RNNT_ERR_VARIANT = -3,     /* RNN-T call on a TDT engine or the reverse    */
+    RNNT_ERR_VARIANT = -3,     /* the decoder does not run this kind of model  */
     RNNT_ERR_HIP = -4,         /* a HIP runtime call failed                    */
     RNNT_ERR_UNSUPPORTED = -5, /* the device or the model does not fit         */
     RNNT_ERR_SCRATCH = -6      /* rnnt_label_looping_decode_noalloc: the call  */
@@ -169,6 +169,25 @@ typedef struct rnnt_stats {
  * handlers.  May be combined with a storage flag.
  */
 #define RNNT_FLAG_PLAIN_LAUNCH 4
+
+/*
+ * RNNT_FLAG_MULTI_BLANK: the model is a multi-blank transducer (the paper's
+ * related-work section names these models beside TDT: "big blank" symbols let
+ * the decoder skip encoder frames).  The D extra output columns of the
+ * descriptor are then not durations but big-blank symbols, and durations[i]
+ * (>= 1, else RNNT_ERR_SHAPE) is the number of frames big blank i skips.  All
+ * V1 + D outputs form one distribution with one argmax (lowest index on
+ * ties); a blank moves on by one frame and a big blank by its span, neither is
+ * emitted or fed to the prediction network, both reset the count of labels on
+ * the frame; a label is handled as in an RNN-T.  The log-probability output,
+ * when set, is taken over all V1 + D outputs.  Such an engine is decoded with
+ * rnnt_label_looping_decode (or its _noalloc form); rnnt_greedy_decode --
+ * Algorithm 1 keeps one frame index for the whole batch -- and
+ * tdt_label_looping_decode return RNNT_ERR_VARIANT.  May be combined with the
+ * storage flags and RNNT_FLAG_PLAIN_LAUNCH; with RNNT_FLAG_BF16_ARITHMETIC the
+ * engine is refused (RNNT_ERR_UNSUPPORTED).
+ */
+#define RNNT_FLAG_MULTI_BLANK 16
 
 /*
  * Create an engine for up to max_B utterances of up to max_T frames.

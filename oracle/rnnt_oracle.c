@@ -793,6 +793,9 @@ int orc_follow_sequential(const net_t *net, const real *x_b, int T, int len,
                           int32_t *rep_t, int32_t *rep_u, int32_t *rep_want,
                           int32_t *rep_got, real *rep_gap, real *worst_gap, real tol)
 {
+    /* a hypothesis of a multi-blank model does not say which blanks were big ones: not   */
+    /* followed (a differing hypothesis then counts as not producible)                     */
+    if (net->NB != 0) return -1;
     const int SS = net->state_size, GS = net->g_size, V1 = net->V1, D = net->D;
     const int blank = net->blank;
     real *state = (real *)calloc((size_t)SS, sizeof(real));

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     RNNT_FLAG_FP8_WEIGHTS,
     RNNT_FLAG_PLAIN_LAUNCH,
     RNNT_FLAG_BF16_ARITHMETIC,
+    RNNT_FLAG_MULTI_BLANK,
     Engine,
     RnntError,
     RnntStats,

@@ -30,6 +30,7 @@ RNNT_FLAG_BF16_WEIGHTS = 1
 RNNT_FLAG_FP8_WEIGHTS = 2
 RNNT_FLAG_PLAIN_LAUNCH = 4
 RNNT_FLAG_BF16_ARITHMETIC = 8
+RNNT_FLAG_MULTI_BLANK = 16
 
 
 class RnntError(RuntimeError):
@@ -139,6 +140,12 @@ def rnnt_engine_create(dims, weights: dict, max_B: int, max_T: int, flags: int =
     b_pred, w_out, b_out).  Returns the engine handle."""
     L = int(dims.L)
     dur = list(dims.durations)
+    # a multi-blank model's extra output columns are its big blanks: their spans travel in the
+    # descriptor's durations and the flag says what they are
+    spans = list(getattr(dims, "big_blanks", ()))
+    if spans:
+        assert not dur, "a model has durations or big blanks, not both"
+        dur, flags = spans, flags | RNNT_FLAG_MULTI_BLANK
     d = _ModelDesc()
     d.F, d.E, d.H, d.L, d.J, d.V1 = int(dims.F), int(dims.E), int(dims.H), L, int(dims.J), int(dims.V1)
     d.blank, d.D = int(dims.blank), len(dur)
@@ -321,7 +328,7 @@ class Engine:
         elif variant == "label_noalloc":
             rnnt_label_looping_decode_noalloc(*common, stream=stream)
         elif variant == "tdt":
-            tdt_label_looping_decode(*common, durations_out=out["durs"], stream=stream)
+            tdt_label_looping_decode(*common, durations_out=out.get("durs"), stream=stream)
         else:
             raise ValueError(variant)
         return out

@@ -1138,8 +1138,8 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int col = (g0 + g) * 4 + j;
-                if (col < p.V1) { const unsigned long long k = make_key(a[j], col); kt = k > kt ? k : kt; }
-                else if (col < p.NOUT) { const unsigned long long k = make_key(a[j], col - p.V1); kd = k > kd ? k : kd; }
+                if (col < p.VT) { const unsigned long long k = make_key(a[j], col); kt = k > kt ? k : kt; }
+                else if (col < p.NOUT) { const unsigned long long k = make_key(a[j], col - p.VT); kd = k > kd ? k : kd; }
             }
             cand[s * ngx + g] = kt;
             if (p.D > 0) cand_d[s * ngx + g] = kd;
@@ -1152,8 +1152,8 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
             for (int v = 0; v < kWaves; ++v) a += tail_sum[v * kMaxSamples + w.tid];
             tail_sum[w.tid] = a;
             const int col = p.nout_m + w.jrank;
-            cand[w.tid * ngx + ng] = col < p.V1 ? make_key(a, col) : 0ull;
-            if (p.D > 0) cand_d[w.tid * ngx + ng] = col < p.V1 ? 0ull : make_key(a, col - p.V1);
+            cand[w.tid * ngx + ng] = col < p.VT ? make_key(a, col) : 0ull;
+            if (p.D > 0) cand_d[w.tid * ngx + ng] = col < p.VT ? 0ull : make_key(a, col - p.VT);
         }
     }
     __syncthreads();
@@ -1192,11 +1192,11 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
             reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if ((g0 + g) * 4 + j < p.V1) se += expf(a[j] - rank_max[s]);
+                if ((g0 + g) * 4 + j < p.VT) se += expf(a[j] - rank_max[s]);
             se_part[s * ngx + g] = se;
         }
         if (has_tail && w.tid < ns)
-            se_part[w.tid * ngx + ng] = p.nout_m + w.jrank < p.V1 ? expf(tail_sum[w.tid] - rank_max[w.tid]) : 0.f;
+            se_part[w.tid * ngx + ng] = p.nout_m + w.jrank < p.VT ? expf(tail_sum[w.tid] - rank_max[w.tid]) : 0.f;
         __syncthreads();
         if (w.tid < ns) {
             float se = 0.f;
@@ -1249,7 +1249,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
             // no candidate at all cannot happen (every rank owns at least one token column or
             // publishes key 0, and rank 0 always owns column 0); keep the index in range anyway
             int bi = kt ? key_index(kt) : p.blank;
-            if ((unsigned)bi >= (unsigned)p.V1) bi = p.blank;
+            if ((unsigned)bi >= (unsigned)p.VT) bi = p.blank;
             const int di = (p.D > 0 && kd) ? key_index(kd) : 0;
             c.s_k[s] = bi; c.s_v[s] = key_value(kt); c.s_d[s] = di < p.D ? di : 0;
             c.s_lp[s] = p.logps ? -logf(ls) : 0.f;      // the maximum is its own reference: logit - lm = 0
@@ -1583,7 +1583,11 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                             const int s = j * la + pos;
                             const int k = c.s_k[s];
                             const int dval = tdt ? c.durations[c.s_d[s]] : 0;
-                            if (k == p.blank) {
+                            if (k >= p.V1) {
+                                // a big blank of a multi-blank model: skip its span of frames
+                                pos += max(c.durations[k - p.V1], 1);
+                                c.n[r] = 0;
+                            } else if (k == p.blank) {
                                 pos += tdt ? max(dval, 1) : 1;
                                 c.n[r] = 0;
                             } else {

@@ -23,7 +23,8 @@ enum { kStatPred = 0, kStatJoint = 1, kStatSamples = 2, kStatPolls = 3, kStatCou
 
 struct DecodeParams {
     int F, E, H, L, J, V1, D, blank, NOUT;
-    int durations[kMaxDur];
+    int VT;                 // output columns of the token distribution: V1, plus the big blanks of a multi-blank model
+    int durations[kMaxDur]; // TDT: the durations; multi-blank: the spans of the big blanks (output columns V1 ...)
     int B, T, S, cap, variant;
     int wt;                 // WeightType of the packed stages
     int n_teams, team_size, lookahead;

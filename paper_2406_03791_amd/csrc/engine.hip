@@ -119,6 +119,7 @@ struct rnnt_engine {
     int search_steps = 0;  // 0: chosen per call, -1: no limit, > 0: as given
     int wt = kWeightF32;   // storage of the packed (streamed) weights
     bool plain_launch = false;   // RNNT_FLAG_PLAIN_LAUNCH
+    bool multi_blank = false;    // RNNT_FLAG_MULTI_BLANK: the D extra output columns are big blanks
     float *logp_out = nullptr;   // caller's [B, cap] buffer for log-probabilities, or none
     int32_t *done = nullptr;     // caller's [B] completion flags, or none
     // host copies of the weights that get repacked when the team layout changes
@@ -465,6 +466,8 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     DecodeParams p{};
     p.F = d.F; p.E = d.E; p.H = d.H; p.L = d.L; p.J = d.J; p.V1 = d.V1; p.D = d.D;
     p.blank = d.blank; p.NOUT = e->NOUT;
+    p.VT = d.V1;
+    if (e->multi_blank) { p.VT = e->NOUT; p.D = 0; }   // one distribution over labels, blank and big blanks
     for (int i = 0; i < kMaxDur; ++i) p.durations[i] = e->durations[i];
     p.B = B; p.T = T; p.S = S; p.cap = cap; p.variant = variant;
     p.n_teams = t.n_teams; p.team_size = t.team_size;
@@ -519,7 +522,8 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
                        rnnt_engine **out)
 {
     if (!desc || !out) return RNNT_ERR_NULL;
-    if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_PLAIN_LAUNCH | RNNT_FLAG_BF16_ARITHMETIC))
+    if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_PLAIN_LAUNCH | RNNT_FLAG_BF16_ARITHMETIC |
+                  RNNT_FLAG_MULTI_BLANK))
         return RNNT_ERR_SHAPE;
     {   // at most one of the three formats
         const int fmt = flags & (RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC);
@@ -534,11 +538,15 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         d.D < 0 || d.D > kMaxDur || d.blank < 0 || d.blank >= d.V1 || max_B < 1 || max_T < 1)
         return RNNT_ERR_SHAPE;
     if (d.F % 16 != 0) return RNNT_ERR_UNSUPPORTED;   // K tile of the projection GEMM
-    if (d.V1 > 65535) return RNNT_ERR_UNSUPPORTED;    // argmax partials carry a 16-bit column index
+    if (d.V1 + d.D > 65535) return RNNT_ERR_UNSUPPORTED;   // argmax partials carry a 16-bit column index
     for (int l = 0; l < d.L; ++l)
         if (!d.w_ih[l] || !d.w_hh[l] || !d.b_ih[l] || !d.b_hh[l]) return RNNT_ERR_NULL;
+    const bool multi_blank = (flags & RNNT_FLAG_MULTI_BLANK) != 0;
+    if (multi_blank && d.D < 1) return RNNT_ERR_SHAPE;
+    // the bfloat16 mode's reference check needs the oracle's follow mode, which does not cover these models
+    if (multi_blank && (flags & RNNT_FLAG_BF16_ARITHMETIC)) return RNNT_ERR_UNSUPPORTED;
     for (int i = 0; i < d.D; ++i)
-        if (d.durations[i] < 0) return RNNT_ERR_SHAPE;
+        if (d.durations[i] < (multi_blank ? 1 : 0)) return RNNT_ERR_SHAPE;   // a big blank moves on by at least one frame
 
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev));
@@ -559,6 +567,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
                                             : ((flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32);
     if (flags & RNNT_FLAG_BF16_ARITHMETIC) e->wt = kWeightBf16Arith;
     e->plain_launch = (flags & RNNT_FLAG_PLAIN_LAUNCH) != 0;
+    e->multi_blank = multi_blank;
     e->n_wg = (prop.multiProcessorCount / 32) * 32;   // every layout divides it
     if (e->n_wg < 32) return RNNT_ERR_UNSUPPORTED;
 
@@ -731,7 +740,7 @@ int rnnt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int3
 {
     int rc = check_call(eng, enc_out, enc_len, B, T, max_symbols, tokens_out, tok_len_out, cap);
     if (rc) return rc;
-    if (eng->d.D != 0) return RNNT_ERR_VARIANT;
+    if (eng->d.D != 0 && !eng->multi_blank) return RNNT_ERR_VARIANT;
     return run_decode(eng, kLabelLooping, enc_out, enc_len, B, T, max_symbols, tokens_out,
                       tok_len_out, cap, frames_out, logit_out, nullptr,
                       static_cast<hipStream_t>(stream));
@@ -744,7 +753,7 @@ int rnnt_label_looping_decode_noalloc(rnnt_engine *eng, const float *enc_out, co
 {
     int rc = check_call(eng, enc_out, enc_len, B, T, max_symbols, tokens_out, tok_len_out, cap);
     if (rc) return rc;
-    if (eng->d.D != 0) return RNNT_ERR_VARIANT;
+    if (eng->d.D != 0 && !eng->multi_blank) return RNNT_ERR_VARIANT;
     if (!eng->scratch) return RNNT_ERR_UNSUPPORTED;
     // carve the call's workspace out of the static array, every part 256-byte aligned
     const TeamConfig &t = eng->label_cfg;
@@ -787,7 +796,7 @@ int tdt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int32
 {
     int rc = check_call(eng, enc_out, enc_len, B, T, max_symbols, tokens_out, tok_len_out, cap);
     if (rc) return rc;
-    if (eng->d.D == 0) return RNNT_ERR_VARIANT;
+    if (eng->d.D == 0 || eng->multi_blank) return RNNT_ERR_VARIANT;
     return run_decode(eng, kTdtLabelLooping, enc_out, enc_len, B, T, max_symbols, tokens_out,
                       tok_len_out, cap, frames_out, logit_out, durations_out,
                       static_cast<hipStream_t>(stream));
@@ -880,7 +889,7 @@ const char *rnnt_status_string(int code)
     case RNNT_OK: return "ok";
     case RNNT_ERR_NULL: return "a required pointer is NULL";
     case RNNT_ERR_SHAPE: return "a dimension, count or alignment is out of range";
-    case RNNT_ERR_VARIANT: return "RNN-T call on a TDT engine or TDT call on an RNN-T engine";
+    case RNNT_ERR_VARIANT: return "this decoder does not run this kind of model (RNN-T, TDT or multi-blank engine)";
     case RNNT_ERR_HIP: return g_hip_error.empty() ? "HIP runtime error" : g_hip_error.c_str();
     case RNNT_ERR_UNSUPPORTED: return "the device or the model shape is not supported";
     case RNNT_ERR_SCRATCH: return "the call needs more scratch than the static array holds (RNNT_NOALLOC_SCRATCH_BYTES)";

@@ -266,6 +266,42 @@ def test_cfg5_second_workload_single_layer_model(pkg):
     check(pkg, w, "frame", "small_model")
 
 
+def test_cfg6_multi_blank_transducer(pkg):
+    """A multi-blank transducer at the Parakeet shape (two big blanks that skip 2 and 4 frames)
+    against the oracle's rule: full size in the default layout, with the score (taken over all
+    outputs), one utterance, 128 utterances, other team layouts and lookaheads on a cut, bf16
+    weight storage, and the decoders and modes that do not run such a model."""
+    w = synth.make_workload(6, pad="nan")
+    eng = pkg.Engine(w.model, w.B, w.T)
+    ref, got, stats = check(pkg, w, "label", "cfg6/full", engine=eng, logp=True)
+    V1 = w.model.dims.V1
+    assert stats["near_tie_rows"] == 0
+    assert max(int(t.max()) for t in ref.tokens if len(t)) < V1 - 1      # big blanks are never emitted
+    enc = torch.from_numpy(w.enc_out).cuda().contiguous()
+    ln = torch.from_numpy(w.enc_len).cuda()
+    for variant in ("frame", "tdt"):
+        with pytest.raises(pkg.RnntError):
+            eng.decode(variant, enc, ln, w.max_symbols)
+    eng.close()
+    for B in (1, 128):
+        wb = synth.make_workload(6, pad="nan", B=B)
+        check(pkg, wb, "label", f"cfg6/B{B}")
+    wc = synth.make_workload(6, pad="nan", B=9, T=120, len_lo=40, len_hi=120)
+    eng = pkg.Engine(wc.model, wc.B, wc.T)
+    for n_teams, groups, la in [(8, 1, 1), (8, 2, 3), (2, 4, 8), (16, 1, 16), (4, 1, 5)]:
+        eng.configure(n_teams=n_teams, joint_groups=groups, lookahead=la)
+        check(pkg, wc, "label", f"cfg6/cut teams={n_teams}/{groups} la={la}", engine=eng)
+    eng.close()
+    with pytest.raises(pkg.RnntError):      # no reference check for that combination: refused
+        pkg.Engine(wc.model, wc.B, wc.T, flags=pkg.RNNT_FLAG_BF16_ARITHMETIC)
+    # the model with bf16-valued streamed weights, stored as bf16 (fp32 arithmetic)
+    import dataclasses
+    wb = dataclasses.replace(wc, model=synth.with_bf16_streamed_weights(wc.model))
+    eng = pkg.Engine(wb.model, wb.B, wb.T, flags=pkg.RNNT_FLAG_BF16_WEIGHTS)
+    check(pkg, wb, "label", "cfg6/cut/bf16 weights", engine=eng)
+    eng.close()
+
+
 def test_repeat_and_permutation_invariance(pkg):
     w = synth.make_workload(2, pad="nan", B=8, T=60, len_lo=20, len_hi=60)
     eng = engine_for(pkg, "parakeet8", w.model, 8, 60)
