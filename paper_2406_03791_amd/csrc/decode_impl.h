@@ -602,6 +602,16 @@ __device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, cons
         }
     };
     PROF_MARK(w, 18);
+    // the row of the folded embedding table this thread will add after stage 0 (layer 0 of its
+    // first (unit, row, gate) element): requested now, used when the stage's sums are there
+    float t0_first = 0.f;
+    {
+        const int e = w.tid >> 2, j = w.tid & 3;
+        if (w.tid < p.L * nu * R * 4 && e < nu * R) {
+            const int u = e / R, r = e - u * R;
+            t0_first = p.T0[((long long)c.last[r] * p.H + (u0 + u)) * 4 + j];
+        }
+    }
     // stage 0: recurrent parts of every layer from the committed vectors in LDS
     WeightStream ws;
     stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks);
@@ -624,7 +634,7 @@ __device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, cons
         float a = 0.f;
         for (int ks = 0; ks < p.st0.nks; ++ks) a += src[ks * red_task_stride(RG)];
         if (layer == 0) {
-            a += p.T0[((long long)c.last[r] * p.H + (u0 + u)) * 4 + j];
+            a += e4 == w.tid ? t0_first : p.T0[((long long)c.last[r] * p.H + (u0 + u)) * 4 + j];
             cell(0, u, r, j, a);
         } else {
             l.part[((layer * p.nu_max + u) * p.rcap + r) * 4 + j] = a + l.b_lstm[(layer * p.nu_max + u) * 4 + j];
@@ -1436,12 +1446,15 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             // inner loop once, find all blank and leave).  Every thread reads the same results
             // and takes the same decision.
             if (!need_pred && time_idx > win0 && time_idx < win0 + win_n) {
-                int f = time_idx;
-                for (; f < win0 + win_n; ++f) {
-                    bool all_blank = true;
-                    for (int r = 0; r < R; ++r)
-                        if (f < c.len[r] && c.s_k[(f - win0) * R + r] != p.blank) all_blank = false;
-                    if (!all_blank) break;
+                // (every wave looks at all results at once: lane s holds sample s = frame offset
+                // s / R, row s % R, and the first label among the frames from time_idx on decides)
+                int f;
+                {
+                    const int s = w.lane & (kMaxSamples - 1), i = s / R, r = s - i * R;
+                    const int k = c.s_k[s], len_r = c.len[r];
+                    const bool label = w.lane < win_n * R && win0 + i >= time_idx && win0 + i < len_r && k != p.blank;
+                    const unsigned long long m = __ballot(label);
+                    f = m ? win0 + (__ffsll((long long)m) - 1) / R : win0 + win_n;
                 }
                 if (f > time_idx) {
                     // rows whose frames ran out on the way are complete
@@ -1573,7 +1586,35 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 ok = joint_step<RGJ, WT>(p, w, sy, l);
                 if (!ok) break;
                 ++n_joint;
-                if (w.wave == 0) {
+                if (w.wave == 0 && !tdt && p.VT == p.V1) {
+                    // Plain transducer: a blank moves on by one frame, so the walk is the first
+                    // non-blank result among the frames the row still has.  Every lane reads one
+                    // sample's result; lane j then takes row j's part of the ballot.
+                    // (the read is unconditional: lanes past the samples read a slot that exists)
+                    const int mine = c.s_k[w.lane & (kMaxSamples - 1)];
+                    const unsigned long long labels = __ballot(w.lane < c.ns && mine != p.blank);
+                    int still = 0;
+                    if (w.lane < rj && c.searching[g + w.lane * G]) {
+                        const int j = w.lane, r = g + j * G;
+                        const int t0 = c.t[r], avail = min(la, c.len[r] - t0);
+                        const unsigned long long seg = (labels >> (j * la)) & ((1ull << avail) - 1ull);
+                        const int pos = seg ? __ffsll((long long)seg) - 1 : avail;
+                        if (pos > 0) c.n[r] = 0;
+                        c.t[r] = t0 + pos;
+                        still = 1;
+                        if (seg) {
+                            const int s = j * la + pos;
+                            c.hold_k[r] = c.s_k[s]; c.hold_v[r] = c.s_v[s]; c.hold_lp[r] = c.s_lp[s]; c.hold_d[r] = 0;
+                            c.searching[r] = 0; still = 0;
+                        } else if (t0 + pos >= c.len[r]) {
+                            c.searching[r] = 0; c.active[r] = 0; still = 0;
+                            if (w.jrank == 0) finish_row(p, r);
+                        }
+                    }
+                    const bool any = __ballot(still != 0) != 0ull;
+                    if (w.lane == 0) c.f_any_searching = any;
+                    if (any && steps_left > 0) set_up_samples();
+                } else if (w.wave == 0) {
                     // lane j walks the results of the group's row j in frame order
                     int still = 0;
                     if (w.lane < rj && c.searching[g + w.lane * G]) {
