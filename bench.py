@@ -175,8 +175,9 @@ def main() -> int:
                          "weights, listed under 'variants'")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the batch shards with no exchange; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (utterances are independent, so a batch "
+              "shards over GPUs with no exchange; each GPU would run this same path on its "
+              "share); run with --gpus 1", file=sys.stderr)
         return 2
 
     import torch

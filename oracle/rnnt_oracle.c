@@ -406,8 +406,8 @@ typedef struct {
     int64_t stat_pred_rows;  /* utterance-level prediction evaluations         */
     int64_t stat_joint_rows; /* utterance-level joint evaluations              */
     real *logps;           /* [B][cap]  log-softmax value of each emitted label */
-                           /* over the token columns: the v of Algorithm 1's    */
-                           /* k, v = logp.max() (may be NULL)                   */
+                           /* over the token columns: the score Algorithm 1     */
+                           /* keeps beside the label (may be NULL)              */
 } decode_io;
 
 /* argmax over v[lo..hi) with the lowest index winning ties; *margin is the   */

@@ -1475,7 +1475,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             __syncthreads();
             while (ok && not_blank && symbols_added < p.S) {
                 if (need_pred) {
-                    // g, hidden_prime = prediction(last_label, hidden); skipped when neither
+                    // the prediction network's step of Algorithm 1's inner loop; skipped when neither
                     // input changed since the last evaluation (same result)
                     ok = prediction_step<RG, WT>(p, w, sy, l);
                     if (!ok) break;
