@@ -307,9 +307,9 @@ def main() -> int:
         eng.close()
         return res
 
-    if args.arithmetic == "bf16" and args.storage != "fp32":
+    if args.arithmetic == "bf16" and args.storage == "bf16":
         print("bench.py: --arithmetic bf16 stores its weights as bf16 already; leave --storage "
-              "at fp32", file=sys.stderr)
+              "at fp32, or give fp8 for the weight-only 8-bit form of the mode", file=sys.stderr)
         return 2
     r = run_variant(args.variant, args.steps, args.warmup, storage=args.storage,
                     arithmetic=args.arithmetic)
@@ -317,7 +317,9 @@ def main() -> int:
     n_frames = w.frames
     ms_per_step = 1e3 * r["wall"] / r["steps"]
     value = n_frames * r["steps"] / r["wall"]
-    wb = 2 if args.arithmetic == "bf16" else {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage]
+    wb = {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage]
+    if args.arithmetic == "bf16" and args.storage == "fp32":
+        wb = 2
     lit_bytes, lit_pred, lit_joint, _ = algorithmic_bytes(
         w.model.dims, w.B, args.variant, w.enc_len, r["frames"], w.max_symbols, wb)
     min_bytes, min_pred, min_joint, _ = minimum_schedule_bytes(
@@ -346,7 +348,8 @@ def main() -> int:
                                f"max_symbols={w.max_symbols}, variant={args.variant}" +
                                ("" if args.storage == "fp32" else
                                 f", streamed weights rounded to and stored as {args.storage} "
-                                f"(another model than the headline's; fp32 arithmetic)") +
+                                f"(another model than the headline's" +
+                                ("; fp32 arithmetic)" if args.arithmetic == "f32" else ")")) +
                                ("" if args.arithmetic == "f32" else
                                 ", bfloat16 products with float accumulation (reduced precision: "
                                 "not the headline)"),
@@ -407,6 +410,11 @@ def main() -> int:
             break
         rv = run_variant(v, max(3, args.steps // 2), 2, arithmetic="bf16")
         line["variants"][v + "_bf16_arithmetic"] = {
+            "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
+            "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
+        # the same mode on the model with e4m3-valued streamed weights, stored as e4m3
+        rv = run_variant(v, max(3, args.steps // 2), 2, arithmetic="bf16", storage="fp8")
+        line["variants"][v + "_bf16_arithmetic_e4m3_weights"] = {
             "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
             "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
     if args.all_variants:

@@ -153,7 +153,12 @@ typedef struct rnnt_stats {
  * results are those of the fp32 engine on another arithmetic: token sequences
  * may differ from the fp32 decode of the same model, and are exact against a
  * reference that rounds at the same places (up to summation order).  Excludes
- * the two storage flags (RNNT_ERR_SHAPE).
+ * RNNT_FLAG_BF16_WEIGHTS (RNNT_ERR_SHAPE).  Together with RNNT_FLAG_FP8_WEIGHTS
+ * it is the weight-only 8-bit form of the mode (the quantised products of the
+ * paper's conclusion): the streamed weights are kept as e4m3 -- every one must
+ * be an e4m3 value, else RNNT_ERR_SHAPE -- and widened to bf16, which holds all
+ * e4m3 values, on their way to the bf16 matrix instructions; the arithmetic is
+ * that of the bfloat16 mode on that model.
  */
 #define RNNT_FLAG_BF16_ARITHMETIC 8
 
@@ -194,8 +199,9 @@ typedef struct rnnt_stats {
  * Copies and repacks the weights on the current device, allocates the
  * workspace (projected frames [max_B, max_T, J], state, exchange buffers).
  * flags: 0 or one of RNNT_FLAG_BF16_WEIGHTS / RNNT_FLAG_FP8_WEIGHTS /
- * RNNT_FLAG_BF16_ARITHMETIC, optionally with RNNT_FLAG_PLAIN_LAUNCH; other bits
- * are RNNT_ERR_SHAPE.
+ * RNNT_FLAG_BF16_ARITHMETIC (or the last two together), optionally with
+ * RNNT_FLAG_PLAIN_LAUNCH and RNNT_FLAG_MULTI_BLANK; other bits are
+ * RNNT_ERR_SHAPE.
  * Limits of this implementation, checked here before anything is allocated
  * (RNNT_ERR_UNSUPPORTED): F must be a multiple of 16 (K tile of the projection
  * GEMM); V1 at most 65 535 (the argmax exchange carries a 16-bit column index);
@@ -390,8 +396,13 @@ int rnnt_engine_phase_timers(rnnt_engine *eng, int32_t team, double *us_out, int
  *   rnnt_probe_mfma      fp32 matrix rate in TFLOP/s of the MFMA shape 4x4x1
  *                        in 16 blocks (shape 0, the decode kernel's) or
  *                        32x32x2 (shape 1, the projection kernel's).
+ *   rnnt_probe_e4m3_widening  the bf16 (as 16-bit codes) that the conversion
+ *                        used by the bfloat16 mode with e4m3-stored weights
+ *                        makes of every e4m3 code: bf16_out is a HOST array of
+ *                        4 * 256 entries, [byte position in a word][code].
  * Return RNNT_OK or an RNNT_ERR_* code.
  */
+int rnnt_probe_e4m3_widening(uint16_t *bf16_out);
 int rnnt_probe_stream(int32_t from_l2, double *gbytes_per_s_out, double *per_cu_out);
 int rnnt_probe_exchange(int32_t team_size, int32_t len, int32_t tagged, double *us_per_exchange_out);
 int rnnt_probe_mfma(int32_t shape, double *tflops_out);

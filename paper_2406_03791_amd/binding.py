@@ -22,7 +22,7 @@ EXPORTS = (
     "rnnt_engine_set_done_flags",
     "rnnt_label_looping_decode_noalloc",
     "rnnt_engine_phase_timers",
-    "rnnt_probe_stream", "rnnt_probe_exchange", "rnnt_probe_mfma",
+    "rnnt_probe_stream", "rnnt_probe_exchange", "rnnt_probe_mfma", "rnnt_probe_e4m3_widening",
 )
 
 
@@ -112,6 +112,7 @@ def load_library():
         lib.rnnt_probe_stream.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         lib.rnnt_probe_exchange.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
         lib.rnnt_probe_mfma.argtypes = [C.c_int32, C.POINTER(C.c_double)]
+        lib.rnnt_probe_e4m3_widening.argtypes = [C.POINTER(C.c_uint16)]
         lib.rnnt_status_string.argtypes = [C.c_int]
         lib.rnnt_status_string.restype = C.c_char_p
         for name in EXPORTS:
@@ -246,6 +247,14 @@ def rnnt_probe_exchange(team_size: int, length: int, tagged: bool) -> float:
     out = C.c_double(0)
     _check(load_library().rnnt_probe_exchange(int(team_size), int(length), int(bool(tagged)), C.byref(out)))
     return float(out.value)
+
+
+def rnnt_probe_e4m3_widening():
+    """[4][256] uint16 array: the bf16 code each e4m3 code becomes, per byte position."""
+    import numpy as np
+    out = np.zeros((4, 256), dtype=np.uint16)
+    _check(load_library().rnnt_probe_e4m3_widening(out.ctypes.data_as(C.POINTER(C.c_uint16))))
+    return out
 
 
 def rnnt_probe_mfma(shape: int) -> float:

@@ -12,6 +12,7 @@ namespace rnnt {
     RNNT_DECLARE_LAUNCH(launch_decode_f4_##wt); RNNT_DECLARE_LAUNCH(launch_decode_l1_##wt); \
     RNNT_DECLARE_LAUNCH(launch_decode_l2_##wt); RNNT_DECLARE_LAUNCH(launch_decode_l4_##wt)
 RNNT_DECLARE_NEST(f32); RNNT_DECLARE_NEST(bf16); RNNT_DECLARE_NEST(fp8); RNNT_DECLARE_NEST(bf16a);
+RNNT_DECLARE_NEST(fp8a);
 #undef RNNT_DECLARE_NEST
 #undef RNNT_DECLARE_LAUNCH
 
@@ -62,7 +63,7 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
     // that assumes more would write outside its regions
     if (rows > kMaxRows || rg > p.rg_planned || samples > p.samples_cap) return hipErrorInvalidValue;
     typedef hipError_t (*Launch)(const DecodeParams &, int, hipStream_t);
-    static const Launch table[4][2][3] = {
+    static const Launch table[kWeightTypes][2][3] = {
         {{launch_decode_f1_f32, launch_decode_f2_f32, launch_decode_f4_f32},
          {launch_decode_l1_f32, launch_decode_l2_f32, launch_decode_l4_f32}},
         {{launch_decode_f1_bf16, launch_decode_f2_bf16, launch_decode_f4_bf16},
@@ -70,8 +71,10 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
         {{launch_decode_f1_fp8, launch_decode_f2_fp8, launch_decode_f4_fp8},
          {launch_decode_l1_fp8, launch_decode_l2_fp8, launch_decode_l4_fp8}},
         {{launch_decode_f1_bf16a, launch_decode_f2_bf16a, launch_decode_f4_bf16a},
-         {launch_decode_l1_bf16a, launch_decode_l2_bf16a, launch_decode_l4_bf16a}}};
-    if (p.wt < 0 || p.wt > 3) return hipErrorInvalidValue;
+         {launch_decode_l1_bf16a, launch_decode_l2_bf16a, launch_decode_l4_bf16a}},
+        {{launch_decode_f1_fp8a, launch_decode_f2_fp8a, launch_decode_f4_fp8a},
+         {launch_decode_l1_fp8a, launch_decode_l2_fp8a, launch_decode_l4_fp8a}}};
+    if (p.wt < 0 || p.wt >= kWeightTypes) return hipErrorInvalidValue;
     return table[p.wt][p.variant == kFrameLooping ? 0 : 1][rgi](p, rgj, stream);
 }
 

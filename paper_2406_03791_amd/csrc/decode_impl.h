@@ -67,7 +67,7 @@ __device__ __forceinline__ unsigned long long xload64(const unsigned long long *
 template <int WT>
 __device__ __forceinline__ float as_operand(float v)
 {
-    if (WT != kWeightBf16Arith) return v;
+    if (!is_bf16_arith(WT)) return v;
     unsigned u = __float_as_uint(v);
     if ((u & 0x7f800000u) != 0x7f800000u) { u += 0x7fffu + ((u >> 16) & 1u); u &= 0xffff0000u; }
     return __uint_as_float(u);
@@ -79,7 +79,7 @@ __device__ __forceinline__ float as_operand(float v)
 template <int WT>
 __device__ __forceinline__ void x_store(float *row, int k, float v)
 {
-    if (WT == kWeightBf16Arith)
+    if (is_bf16_arith(WT))
         reinterpret_cast<unsigned short *>(row)[k] = (unsigned short)(__float_as_uint(as_operand<WT>(v)) >> 16);
     else
         row[k] = v;
@@ -87,7 +87,7 @@ __device__ __forceinline__ void x_store(float *row, int k, float v)
 template <int WT>
 __device__ __forceinline__ void x_store2(float *row, int k, float2 v)      // k even
 {
-    if (WT == kWeightBf16Arith) {
+    if (is_bf16_arith(WT)) {
         const unsigned lo = __float_as_uint(as_operand<WT>(v.x)) >> 16, hi = __float_as_uint(as_operand<WT>(v.y)) & 0xffff0000u;
         reinterpret_cast<unsigned *>(row)[k >> 1] = lo | hi;
     } else {
@@ -97,7 +97,7 @@ __device__ __forceinline__ void x_store2(float *row, int k, float2 v)      // k 
 template <int WT>
 __device__ __forceinline__ void x_store4(float *row, int k, float4 v)      // k a multiple of 4
 {
-    if (WT == kWeightBf16Arith) {
+    if (is_bf16_arith(WT)) {
         const unsigned a = (__float_as_uint(as_operand<WT>(v.x)) >> 16) | (__float_as_uint(as_operand<WT>(v.y)) & 0xffff0000u);
         const unsigned b = (__float_as_uint(as_operand<WT>(v.z)) >> 16) | (__float_as_uint(as_operand<WT>(v.w)) & 0xffff0000u);
         *reinterpret_cast<uint2 *>(reinterpret_cast<unsigned *>(row) + (k >> 1)) = make_uint2(a, b);
@@ -110,12 +110,21 @@ __device__ __forceinline__ void x_store4(float *row, int k, float4 v)      // k 
 template <int WT>
 __device__ __forceinline__ float4 x_load4(const float *row, int k)        // k a multiple of 4
 {
-    if (WT == kWeightBf16Arith) {
+    if (is_bf16_arith(WT)) {
         const uint2 v = *reinterpret_cast<const uint2 *>(reinterpret_cast<const unsigned *>(row) + (k >> 1));
         return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
                            __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
     }
     return *reinterpret_cast<const float4 *>(row + k);
+}
+
+// two e4m3 codes (the low or the high half of `word`) as one word of two bf16, first code in
+// the low half; v_cvt_scalef32_pk_bf16_fp8 with scale 1
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+template <bool HIGH>
+__device__ __forceinline__ float e4m3x2_to_bf16x2(unsigned word)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, HIGH));
 }
 
 typedef short v4s __attribute__((ext_vector_type(4)));
@@ -279,13 +288,14 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         const bool live = task < n_tasks;
         const int g = live ? task / sd.nks : 0;
         const int ks = live ? task - g * sd.nks : 0;
-        constexpr int KPER = WT == kWeightFp8 ? 16 : ((WT == kWeightBf16 || WT == kWeightBf16Arith) ? 8 : 4);
+        constexpr int KPER = (WT == kWeightFp8 || WT == kWeightFp8Bf16Arith) ? 16 : ((WT == kWeightBf16 || WT == kWeightBf16Arith) ? 8 : 4);
         // bfloat16 mode: the activation rows hold bf16, 16 bytes of a row match the 16 bytes (eight
         // weights) of a load, and one load feeds two 4x4x4 bf16 MFMAs; otherwise a load is used
         // in part-steps of four K values on the fp32 4x4x1 MFMA
-        constexpr bool BF = WT == kWeightBf16Arith;
-        constexpr int HALVES = BF ? 1 : KPER / 4;
-        const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * (BF ? 4 : KPER);
+        // (with e4m3 storage a load carries sixteen weights: two such halves, each widened first)
+        constexpr bool BF = is_bf16_arith(WT);
+        constexpr int HALVES = BF ? KPER / 8 : KPER / 4;
+        const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * (BF ? KPER / 2 : KPER);
         // lane r4 of a block accumulates output column r4 of the group for the block's four rows
         const float b0 = (bias && live && ks == 0) ? bias[g * 4 + r4] : 0.f;
         v4f acc[RG];
@@ -318,10 +328,22 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
                                 xb[rg] = *reinterpret_cast<const float4 *>(
                                     xr + rg * 4 * xstride + ((i + u) * HALVES + h + 1) * 4);
                             if (BF) {
+                                // eight weights of this half as four words of two bf16 each
+                                float w0, w1, w2, w3;
+                                if (WT == kWeightFp8Bf16Arith) {
+                                    // one instruction widens two e4m3 codes to two bf16 (scale 1: every
+                                    // e4m3 value is a bf16 value, so nothing is rounded)
+                                    const unsigned lo_word = __float_as_uint(h == 0 ? raw.x : raw.z);
+                                    const unsigned hi_word = __float_as_uint(h == 0 ? raw.y : raw.w);
+                                    w0 = e4m3x2_to_bf16x2<false>(lo_word); w1 = e4m3x2_to_bf16x2<true>(lo_word);
+                                    w2 = e4m3x2_to_bf16x2<false>(hi_word); w3 = e4m3x2_to_bf16x2<true>(hi_word);
+                                } else {
+                                    w0 = raw.x; w1 = raw.y; w2 = raw.z; w3 = raw.w;
+                                }
 #pragma unroll
                                 for (int rg = 0; rg < RG; ++rg) {
-                                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(bf16x4(xa[rg].x, xa[rg].y), bf16x4(raw.x, raw.y), acc[rg], 0, 0, 0);
-                                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(bf16x4(xa[rg].z, xa[rg].w), bf16x4(raw.z, raw.w), acc[rg], 0, 0, 0);
+                                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(bf16x4(xa[rg].x, xa[rg].y), bf16x4(w0, w1), acc[rg], 0, 0, 0);
+                                    acc[rg] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(bf16x4(xa[rg].z, xa[rg].w), bf16x4(w2, w3), acc[rg], 0, 0, 0);
                                 }
 #pragma unroll
                                 for (int rg = 0; rg < RG; ++rg) xa[rg] = xb[rg];
@@ -759,8 +781,12 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         float a[4];
         reduce_tasks4<RG>(l.red, p.st0.nks, g, r, a);
         if (layer == 0) {
-            const float4 t0 = e == w.tid ? pre : *reinterpret_cast<const float4 *>(
-                p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
+            // (an assignment under a condition, not a conditional expression on the two objects:
+            // that would make the compiler address both through one generic pointer, one of
+            // them on the stack)
+            float4 t0 = pre;
+            if (e != w.tid)
+                t0 = *reinterpret_cast<const float4 *>(p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
             float cn, hn;
             lstm_point(a[0] + t0.x, a[1] + t0.y, a[2] + t0.z, a[3] + t0.w,
                        *c_slot(p, l, 0, c.sel[r], u, r), cn, hn);

@@ -461,7 +461,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     const Workspace &ws = static_ws ? *static_ws : t.ws;
     HIP_TRY(hipEventRecord(e->ev[0], stream));
     HIP_TRY(launch_encoder_projection(enc_out, enc_len, e->w_enc.as<float>(), e->b_enc.as<float>(),
-                                      ws.P, B, T, d.F, d.J, e->wt == kWeightBf16Arith, stream));
+                                      ws.P, B, T, d.F, d.J, is_bf16_arith(e->wt), stream));
     HIP_TRY(hipEventRecord(e->ev[1], stream));
     DecodeParams p{};
     p.F = d.F; p.E = d.E; p.H = d.H; p.L = d.L; p.J = d.J; p.V1 = d.V1; p.D = d.D;
@@ -525,9 +525,9 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_PLAIN_LAUNCH | RNNT_FLAG_BF16_ARITHMETIC |
                   RNNT_FLAG_MULTI_BLANK))
         return RNNT_ERR_SHAPE;
-    {   // at most one of the three formats
+    {   // at most one of the three formats, or the bfloat16 mode with e4m3-stored weights
         const int fmt = flags & (RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC);
-        if (fmt & (fmt - 1)) return RNNT_ERR_SHAPE;
+        if ((fmt & (fmt - 1)) && fmt != (RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC)) return RNNT_ERR_SHAPE;
     }
     const rnnt_model_desc &d = *desc;
     if (!d.emb || !d.w_ih || !d.w_hh || !d.b_ih || !d.b_hh || !d.w_enc || !d.b_enc || !d.w_pred ||
@@ -565,7 +565,8 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     e->max_B = max_B; e->max_T = max_T;
     e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8
                                             : ((flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32);
-    if (flags & RNNT_FLAG_BF16_ARITHMETIC) e->wt = kWeightBf16Arith;
+    if (flags & RNNT_FLAG_BF16_ARITHMETIC)
+        e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8Bf16Arith : kWeightBf16Arith;
     e->plain_launch = (flags & RNNT_FLAG_PLAIN_LAUNCH) != 0;
     e->multi_blank = multi_blank;
     e->n_wg = (prop.multiProcessorCount / 32) * 32;   // every layout divides it
@@ -587,7 +588,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     }
     if ((rc = fetch(e->w_pred, d.w_pred, J * H))) return rc;
     if ((rc = fetch(e->w_out, d.w_out, (size_t)e->NOUT * J))) return rc;
-    if (e->wt == kWeightBf16Arith) {
+    if (is_bf16_arith(e->wt)) {
         // bfloat16 mode: the matrices of the per-step products are rounded here (ties to even, the
         // same rounding the kernels apply to the vectors), then stored as bf16 without loss
         auto round_all = [](std::vector<float> &v) {
@@ -615,7 +616,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         for (int l = 0; l < d.L; ++l) ok = ok && is_bf16(e->w_hh[l]) && (l == 0 || is_bf16(e->w_ih[l]));
         if (!ok) return RNNT_ERR_SHAPE;
     }
-    if (e->wt == kWeightFp8) {
+    if (e->wt == kWeightFp8 || e->wt == kWeightFp8Bf16Arith) {
         auto is_e4m3 = [](const std::vector<float> &v) {
             uint8_t code;
             for (float x : v)
@@ -639,7 +640,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     HIP_TRY(e->bias_l.alloc(bias_l.size() * sizeof(float)));
     HIP_TRY(hipMemcpy(e->bias_l.p, bias_l.data(), bias_l.size() * sizeof(float), hipMemcpyHostToDevice));
     HIP_TRY(e->T0.alloc((size_t)d.V1 * H * 4 * sizeof(float)));
-    const bool bf16_mode = e->wt == kWeightBf16Arith;
+    const bool bf16_mode = is_bf16_arith(e->wt);
     if (bf16_mode) HIP_TRY(launch_round_bf16(e->w_enc.as<float>(), (long long)J * d.F, nullptr));
     HIP_TRY(launch_fold_embedding(d.emb, d.w_ih[0], d.b_ih[0], d.b_hh[0], e->T0.as<float>(), d.V1,
                                   d.E, d.H, bf16_mode, nullptr));
@@ -810,7 +811,7 @@ int rnnt_encoder_projection(rnnt_engine *eng, const float *enc_out, const int32_
     if ((reinterpret_cast<uintptr_t>(enc_out) & 15u) != 0) return RNNT_ERR_SHAPE;
     HIP_TRY(launch_encoder_projection(enc_out, enc_len, eng->w_enc.as<float>(),
                                       eng->b_enc.as<float>(), proj_out, B, T, eng->d.F, eng->d.J,
-                                      eng->wt == kWeightBf16Arith, static_cast<hipStream_t>(stream)));
+                                      is_bf16_arith(eng->wt), static_cast<hipStream_t>(stream)));
     return RNNT_OK;
 }
 

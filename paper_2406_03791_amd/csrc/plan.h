@@ -34,8 +34,15 @@ constexpr int kAheadSteps = 4 * kStepUnroll;   // at least the loads a lane keep
 // lossless or refused).  kWeightBf16Arith is the bfloat16 mode: the weights are rounded to
 // bf16 and stored as such, and every vector that enters a product is rounded to bf16 too;
 // products of two bf16 values are exact in fp32 and the sums stay fp32.
-enum WeightType { kWeightF32 = 0, kWeightBf16 = 1, kWeightFp8 = 2, kWeightBf16Arith = 3 };
-RNNT_HD inline int k_per_load(int wt) { return wt == kWeightFp8 ? 16 : ((wt == kWeightBf16 || wt == kWeightBf16Arith) ? 8 : 4); }
+// kWeightFp8Bf16Arith is the bfloat16 mode with its weights stored as e4m3 (lossless or refused):
+// a stored weight is widened to bf16, which holds every e4m3 value, on its way to the bf16 MFMA.
+enum WeightType { kWeightF32 = 0, kWeightBf16 = 1, kWeightFp8 = 2, kWeightBf16Arith = 3, kWeightFp8Bf16Arith = 4,
+                  kWeightTypes = 5 };
+RNNT_HD constexpr bool is_bf16_arith(int wt) { return wt == kWeightBf16Arith || wt == kWeightFp8Bf16Arith; }
+RNNT_HD inline int k_per_load(int wt)
+{
+    return (wt == kWeightFp8 || wt == kWeightFp8Bf16Arith) ? 16 : ((wt == kWeightBf16 || wt == kWeightBf16Arith) ? 8 : 4);
+}
 
 // Floats between the partial sums of consecutive tasks in LDS: 16 per row group plus a pad that
 // spreads the readers (one lane per output group, so a stride of whole multiples of 16 floats

@@ -563,7 +563,58 @@ def test_bf16_arithmetic_mode(pkg):
                 for t in range(0, int(w.enc_len[b]), 7):
                     assert np.allclose(proj[b, t], net.prep(w.enc_out[b, t]), rtol=1e-5, atol=2e-5), (cfg, b, t)
         eng.close()
-    # the mode excludes the storage flags
+    # the mode excludes bf16 storage of fp32-arithmetic engines
     with pytest.raises(pkg.RnntError) as err:
         pkg.Engine(w.model, w.B, w.T, flags=flag | pkg.RNNT_FLAG_BF16_WEIGHTS)
+    assert err.value.code == -2
+
+
+def test_e4m3_codes_widen_to_their_bf16_values(pkg):
+    """The conversion instruction of the bfloat16 mode with e4m3-stored weights, on every code in
+    every byte position, against the format's definition (1 sign, 4 exponent bits with bias 7, 3
+    mantissa bits, subnormals m * 2^-9, the two all-ones codes NaN): every finite e4m3 value
+    is a bf16 value, so the result must be that value exactly."""
+    got = pkg.rnnt_probe_e4m3_widening()
+    for code in range(256):
+        sign, expo, mant = code >> 7, (code >> 3) & 15, code & 7
+        if expo == 15 and mant == 7:
+            want = None                                   # NaN
+        elif expo == 0:
+            want = mant * 2.0 ** -9
+        else:
+            want = (1 + mant / 8.0) * 2.0 ** (expo - 7)
+        for pos in range(4):
+            bits = np.array([int(got[pos, code]) << 16], dtype=np.uint32).view(np.float32)[0]
+            if want is None:
+                assert np.isnan(bits), (code, pos)
+            else:
+                assert bits == np.float32(-want if sign else want), (code, pos, bits)
+                assert np.signbit(bits) == bool(sign), (code, pos)
+
+
+def test_bf16_arithmetic_with_e4m3_weights(pkg):
+    """Weight-only 8-bit form of the bfloat16 mode: the streamed weights are e4m3 values, stored
+    as such and widened to bf16 for the bf16 matrix instructions.  Reference: the oracle's
+    bfloat16 emulation on that model, to the bar of the bfloat16 mode.  A model with other
+    weights is refused."""
+    import dataclasses
+    flags = pkg.RNNT_FLAG_BF16_ARITHMETIC | pkg.RNNT_FLAG_FP8_WEIGHTS
+    for cfg, variants, kw in [(1, ("frame", "label"), {}),
+                              (3, ("frame", "label"), dict(B=12, T=120, len_lo=40, len_hi=120)),
+                              (4, ("tdt",), dict(B=12, T=120, len_lo=40, len_hi=120)),
+                              (3, ("label", "frame"), {}), (4, ("tdt",), {}),
+                              (3, ("label",), dict(B=128, T=100, len_lo=30, len_hi=100))]:
+        w0 = synth.make_workload(cfg, pad="nan", **kw)
+        w = dataclasses.replace(w0, model=synth.with_fp8_streamed_weights(w0.model))
+        eng = pkg.Engine(w.model, w.B, w.T, flags=flags)
+        for variant in variants:
+            ref, got, st = check(pkg, w, variant, f"cfg{cfg}/bf16 arithmetic, e4m3 weights", engine=eng,
+                                 bf16=True, logp=(variant == "label"))
+            same = sum(int(np.array_equal(ref.tokens[b], got["tokens"][b])) for b in range(w.B))
+            log(f"  rows token-identical to the emulating oracle: {same}/{w.B}; rows accepted at a "
+                f"bfloat16 near-tie: {st['near_tie_rows']}")
+            assert st["near_tie_rows"] <= max(1, w.B // 3)
+        eng.close()
+    with pytest.raises(pkg.RnntError) as err:      # weights that are not e4m3 values
+        pkg.Engine(w0.model, w0.B, w0.T, flags=flags)
     assert err.value.code == -2
