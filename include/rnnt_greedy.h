@@ -204,8 +204,9 @@ typedef struct rnnt_stats {
  * RNNT_ERR_SHAPE.
  * Limits of this implementation, checked here before anything is allocated
  * (RNNT_ERR_UNSUPPORTED): F must be a multiple of 16 (K tile of the projection
- * GEMM); V1 at most 65 535 (the argmax exchange carries a 16-bit column index);
- * the device must support cooperative launches.  1 <= L <= 4, D <= 8, blank in
+ * GEMM); V1 + D at most 65 535 (the argmax exchange carries a 16-bit column
+ * index); max_B * max_T below 2^31 (frame numbers are 32-bit); the device must
+ * support cooperative launches.  1 <= L <= 4, D <= 8, blank in
  * [0, V1) and positive sizes are RNNT_ERR_SHAPE.
  * The two bias vectors of an LSTM layer are added once on the host while the
  * weights are repacked (b_ih + b_hh in fp32).

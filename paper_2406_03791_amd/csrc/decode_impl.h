@@ -28,6 +28,8 @@ struct Ctl {
     int emitted[kMaxRows];         // label looping: the row emitted in the current outer iteration
     float hold_v[kMaxRows], hold_lp[kMaxRows];
     int s_row[kMaxSamples], s_frame[kMaxSamples], s_valid[kMaxSamples];
+    int s_pidx[kMaxSamples];       // row of the projected frames (utterance * T + frame) of a valid sample, else -1
+    int s_qoff[kMaxSamples];       // where the sample's q row starts (LDS copy or exchange buffer)
     int s_k[kMaxSamples], s_d[kMaxSamples];
     float s_v[kMaxSamples], s_lp[kMaxSamples];   // maximum logit and its log-softmax value
     int R, ns, bar_ok, committed;
@@ -1040,13 +1042,13 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
             valid[i] = 0; qoff[i] = 0;
 #pragma unroll
             for (int u = 0; u < 3; ++u) pe[i][u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (s < ns) valid[i] = __builtin_amdgcn_readfirstlane(c.s_valid[s]);
+            // (both were worked out when the samples were set up: two independent reads here)
+            const int pidx = s < ns ? __builtin_amdgcn_readfirstlane(c.s_pidx[s]) : -1;
+            const int qo = __builtin_amdgcn_readfirstlane(c.s_qoff[s & (kMaxSamples - 1)]);
+            valid[i] = pidx >= 0;
             if (valid[i]) {
-                const int r = __builtin_amdgcn_readfirstlane(c.s_row[s]);
-                const int fr = __builtin_amdgcn_readfirstlane(c.s_frame[s]);
-                const int b = __builtin_amdgcn_readfirstlane(c.b[r]);
-                qoff[i] = p.q_in_lds ? (r / p.groups) * p.qstride : r;
-                const float *pr = p.P + ((long long)b * p.T + fr) * p.J;
+                qoff[i] = qo;
+                const float *pr = p.P + (long long)pidx * p.J;
                 if (vec) {
 #pragma unroll
                     for (int u = 0; u < 3; ++u) {
@@ -1517,8 +1519,10 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                     if (w.tid < kMaxSamples) {
                         const int s = w.tid, i = s / R, r = s - i * R;
                         const int fr = time_idx + i;
-                        c.s_row[s] = r; c.s_frame[s] = fr;
-                        c.s_valid[s] = i < n_ahead && (i == 0 ? !c.mask[r] : fr < c.len[r]);
+                        const int valid = i < n_ahead && (i == 0 ? !c.mask[r] : fr < c.len[r]);
+                        c.s_row[s] = r; c.s_frame[s] = fr; c.s_valid[s] = valid;
+                        c.s_pidx[s] = valid ? c.b[r] * p.T + fr : -1;
+                        c.s_qoff[s] = p.q_in_lds ? (r / p.groups) * p.qstride : r;
                     }
                     if (w.tid == 0) c.ns = R * n_ahead;
                     __syncthreads();
@@ -1568,7 +1572,11 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 row = g + j * G; fr = c.t[row] + i;
                 valid = c.searching[row] && fr < c.len[row];
             }
-            if (s < kMaxSamples) { c.s_row[s] = row; c.s_frame[s] = fr; c.s_valid[s] = valid; }
+            if (s < kMaxSamples) {
+                c.s_row[s] = row; c.s_frame[s] = fr; c.s_valid[s] = valid;
+                c.s_pidx[s] = valid ? c.b[row] * p.T + fr : -1;
+                c.s_qoff[s] = p.q_in_lds ? (row / G) * p.qstride : row;
+            }
             const unsigned long long vmask = __ballot(valid != 0);
             if (w.lane == 0) { c.ns = rj * la; n_samples += __popcll(vmask); }
         };
