@@ -278,8 +278,6 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
                                           int x_inp_stride, int groups_per_inp, float *red,
                                           bool red_aliases_x, const float *bias = nullptr)
 {
-    // two batches in flight: the hand-over of the batches at a pass boundary below is written
-    // for that depth
     static_assert(kMaxSamples <= 64, "the samples of a joint step are set up by one wave");
     const int r4 = w.lane & 3;
     // The loads run through the passes without a break (a lane without a task in a pass reads
@@ -395,9 +393,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
                 *reinterpret_cast<float4 *>(red + task * red_task_stride(RG) + (rg * 4 + r4) * 4) = o;
             }
         }
-        // next pass: same blocks, next kBlocksPerWg tasks.  A batch holds the steps it was
-        // refilled with two batches earlier, so when a pass ends on an odd batch the two
-        // batches change roles.
+        // next pass: same blocks, next kBlocksPerWg tasks
         ws.task = task + kBlocksPerWg;
         ws.base += sd.nsteps * 64;
         left -= sd.nsteps;
@@ -1026,7 +1022,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
     // z = relu(P[b, frame] + q[row]) for every sample.  Wave v builds the samples v, v + 8, ...,
     // so a sample's row addresses are uniform over the wave; a lane takes four floats at k = 4 *
     // (lane, lane + 64, lane + 128).  The loads of the projected frames go out first, then the
-    // first two batches of the weight stream (a wave's loads return in order and z is needed
+    // first batches of the weight stream (a wave's loads return in order and z is needed
     // first), then z is formed and written to LDS.
     WeightStream ws;
     {

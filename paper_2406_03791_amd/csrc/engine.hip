@@ -191,14 +191,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         gp_max = std::max(gp_max, gp_of(r));
     }
     for (int r = 0; r < tj; ++r) gj_max = std::max(gj_max, gj_of(r));
-    // Tail columns.  When the output width is a few columns more than a whole number of groups
-    // per rank (1024 labels + blank over 8 ranks: 257 groups), the extra group costs every rank a
-    // coarser K slicing.  Those columns, at most one per rank, can instead be computed with
-    // plain multiply-adds from LDS, and the MFMA part covers nout_m columns that divide evenly.
-    const int per = 4 * tj, nout_even = (e->NOUT / per) * per, tail_cols = e->NOUT - nout_even;
-    const int tail_k = (J + 3) & ~3;
-    auto plan_cost = [](const StagePlan &pl) { return (long)pl.slots * (pl.nsteps + kPassOverheadSteps); };
-    constexpr int kTailCostSteps = 4;        // what the tail's multiply-adds cost, in load steps
+    const int tail_k = (J + 3) & ~3;          // a tail column's weight row in LDS (see plan_joint_stage)
     const int gj_all_full = gj_all, gj_max_full = gj_max;
     // Stage plans and LDS layout.  Stages with more groups than blocks are first planned with K
     // slices over several passes (best use of the blocks); if the partial sums of such a plan do
@@ -221,15 +214,10 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         for (int l = 1; l < L; ++l) t.stl[l].plan = make_stage_plan(H, nu_max, e->wt, single);
         t.spred.plan = make_stage_plan(H, gp_max, e->wt, single);
         gj_all = gj_all_full; gj_max = gj_max_full;
-        t.sjoint.plan = make_stage_plan(J, gj_max, e->wt, single);
-        t.n_tail = 0; t.nout_m = e->NOUT;
-        if (nout_even > 0 && tail_cols > 0 && tail_cols <= tj) {
-            const StagePlan even = make_stage_plan(J, nout_even / per, e->wt, single);
-            if (plan_cost(even) + kTailCostSteps < plan_cost(t.sjoint.plan)) {
-                t.sjoint.plan = even;
-                t.n_tail = tail_cols; t.nout_m = nout_even;
-                gj_all = nout_even / 4; gj_max = nout_even / per;
-            }
+        {
+            const JointSplit js = plan_joint_stage(e->NOUT, J, tj, e->wt, single);
+            t.sjoint.plan = js.plan; t.n_tail = js.n_tail; t.nout_m = js.nout_m;
+            if (js.n_tail) { gj_all = js.nout_m / 4; gj_max = js.nout_m / (4 * tj); }
         }
         const int gjx = gj_max + (t.n_tail ? 1 : 0);    // candidates per sample: groups + the tail column
         int kpad = std::max({t.st0.plan.kpad, t.spred.plan.kpad, t.sjoint.plan.kpad});

@@ -121,4 +121,29 @@ inline StagePlan make_stage_plan(int K, int groups_max, int wt = kWeightF32,
     return p;
 }
 
+// The joint output stage of a joint group of `tj` ranks.  When the output width NOUT is a few
+// columns more than a whole number of 4-column groups per rank (1024 labels + blank over 8
+// ranks: 257 groups), that extra group costs every rank a coarser K slicing.  Then the MFMA
+// part covers the nout_m columns that divide evenly and the n_tail columns after them, at
+// most one per rank (rank i takes column nout_m + i), are computed with plain multiply-adds.
+// Chosen when its cost, with the tail priced at a few load steps, is below the plain plan's.
+struct JointSplit {
+    int nout_m;      // columns of the MFMA part (NOUT when there is no tail)
+    int n_tail;      // columns computed outside it
+    StagePlan plan;  // plan of the MFMA part, for the rank with the most groups
+};
+constexpr int kTailCostSteps = 4;
+inline JointSplit plan_joint_stage(int NOUT, int J, int tj, int wt, bool single_pass_only)
+{
+    auto cost = [](const StagePlan &pl) { return (long)pl.slots * (pl.nsteps + kPassOverheadSteps); };
+    const int groups = (NOUT + 3) / 4, groups_max = (groups + tj - 1) / tj;
+    JointSplit js{NOUT, 0, make_stage_plan(J, groups_max, wt, single_pass_only)};
+    const int per = 4 * tj, even = (NOUT / per) * per, tail = NOUT - even;
+    if (even > 0 && tail > 0 && tail <= tj) {
+        const StagePlan pl = make_stage_plan(J, even / per, wt, single_pass_only);
+        if (cost(pl) + kTailCostSteps < cost(js.plan)) js = JointSplit{even, tail, pl};
+    }
+    return js;
+}
+
 }  // namespace rnnt

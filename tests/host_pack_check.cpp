@@ -1,9 +1,10 @@
 // Host-only check of the stage planner and the weight packer (csrc/plan.h, csrc/pack.h), meant
 // to be built with AddressSanitizer and UndefinedBehaviorSanitizer and run by the CPU test
-// suite.  For a sweep of shapes and the three weight storages it packs a matrix whose entry
+// suite.  For a sweep of shapes and every weight storage it packs a matrix whose entry
 // (col, k) encodes its own position, then walks the packed image the way the kernel's lanes
 // do and checks that every (col, k) of the matrix turns up exactly once, at the place the
-// plan says, and that everything else is zero.  Also checks e4m3_bits on all 256 codes.
+// plan says, and that everything else is zero.  Also checks e4m3_bits on all 256 codes and
+// the split of the joint output stage into an MFMA part and tail columns.
 #include <cstdio>
 #include <cstdlib>
 #include <vector>
@@ -34,7 +35,7 @@ int main()
         std::printf("e4m3 accepted a value outside the format\n");
         return 1;
     }
-    for (int wt = 0; wt < 3; ++wt)
+    for (int wt = 0; wt < kWeightTypes; ++wt)
         for (int ts : {1, 3, 8, 32})
             for (int K : {4, 20, 64, 100, 640})
                 for (int N : {1, 7, 64, 257, 1030}) {
@@ -87,6 +88,34 @@ int main()
                     for (int v : seen)
                         if (v != 1) { std::printf("wt %d ts %d K %d N %d: a weight appears %d times\n", wt, ts, K, N, v); return 1; }
                 }
+    // joint output stage: columns beyond a whole number of groups per rank become tail columns
+    // when that buys a finer K slicing
+    for (int wt = 0; wt < kWeightTypes; ++wt)
+        for (int tj : {1, 2, 8, 16, 32})
+            for (int J : {64, 320, 640})
+                for (int NOUT : {5, 17, 257, 1024, 1025, 1027, 1030, 1033, 4097}) {
+                    const JointSplit js = plan_joint_stage(NOUT, J, tj, wt, false);
+                    const StagePlan plain = make_stage_plan(J, ((NOUT + 3) / 4 + tj - 1) / tj, wt);
+                    const long cost = (long)js.plan.slots * (js.plan.nsteps + kPassOverheadSteps);
+                    const long cost_plain = (long)plain.slots * (plain.nsteps + kPassOverheadSteps);
+                    bool good = js.nout_m + js.n_tail == NOUT && js.n_tail >= 0 && js.n_tail <= tj;
+                    if (js.n_tail > 0)
+                        good = good && js.nout_m > 0 && js.nout_m % (4 * tj) == 0 && cost + kTailCostSteps < cost_plain;
+                    else
+                        good = good && cost == cost_plain;
+                    if (!good) { std::printf("joint split NOUT %d J %d tj %d wt %d\n", NOUT, J, tj, wt); return 1; }
+                    ++checked;
+                }
+    {   // the case the split was made for: 1024 labels + blank, eight ranks, fp32
+        const JointSplit js = plan_joint_stage(1025, 640, 8, kWeightF32, false);
+        if (js.nout_m != 1024 || js.n_tail != 1 || js.plan.nks != 4 || js.plan.nsteps != 40 || js.plan.slots != 1) {
+            std::printf("joint split of 1025 columns over 8 ranks: %d + %d, nks %d nsteps %d\n", js.nout_m, js.n_tail,
+                        js.plan.nks, js.plan.nsteps);
+            return 1;
+        }
+        const JointSplit even = plan_joint_stage(1024, 640, 8, kWeightF32, false);
+        if (even.n_tail != 0 || even.nout_m != 1024) { std::printf("joint split of 1024 columns\n"); return 1; }
+    }
     std::printf("ok %ld\n", checked);
     return 0;
 }
