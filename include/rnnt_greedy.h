@@ -189,8 +189,7 @@ typedef struct rnnt_stats {
  * rnnt_label_looping_decode (or its _noalloc form); rnnt_greedy_decode --
  * Algorithm 1 keeps one frame index for the whole batch -- and
  * tdt_label_looping_decode return RNNT_ERR_VARIANT.  May be combined with the
- * storage flags and RNNT_FLAG_PLAIN_LAUNCH; with RNNT_FLAG_BF16_ARITHMETIC the
- * engine is refused (RNNT_ERR_UNSUPPORTED).
+ * other flags.
  */
 #define RNNT_FLAG_MULTI_BLANK 16
 

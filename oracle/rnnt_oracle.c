@@ -778,6 +778,10 @@ int orc_decode_sequential(const net_t *net, decode_io *io)
 /* maximum the chosen logit lies.  Returns the number of such departures, or */
 /* -1 when the sequence cannot be produced by any walk (tokens left over,    */
 /* more than S labels on a frame, frames out of order).                      */
+/* A multi-blank hypothesis does not say which of its blanks were big ones:  */
+/* between labels the walk looks for a chain of blanks and big blanks that    */
+/* lands on the next label's frame, each the maximum or less than tol below   */
+/* it, and reports those that are not the maximum.                            */
 /* For TDT the duration taken on a blank is not part of a hypothesis.  With  */
 /* tol = 0 the walk takes its own argmax duration there.  With tol > 0 it    */
 /* looks for the chain of blank evaluations that reaches the frame of the    */
@@ -793,16 +797,14 @@ int orc_follow_sequential(const net_t *net, const real *x_b, int T, int len,
                           int32_t *rep_t, int32_t *rep_u, int32_t *rep_want,
                           int32_t *rep_got, real *rep_gap, real *worst_gap, real tol)
 {
-    /* a hypothesis of a multi-blank model does not say which blanks were big ones: not   */
-    /* followed (a differing hypothesis then counts as not producible)                     */
-    if (net->NB != 0) return -1;
     const int SS = net->state_size, GS = net->g_size, V1 = net->V1, D = net->D;
     const int blank = net->blank;
+    const int NB = net->NB, VT = V1 + NB;     /* multi-blank: one distribution over VT outputs */
     real *state = (real *)calloc((size_t)SS, sizeof(real));
     real *state_prime = (real *)calloc((size_t)SS, sizeof(real));
     real *g = (real *)calloc((size_t)GS, sizeof(real));
     real *p = (real *)calloc((size_t)net->p_size, sizeof(real));
-    real *logits = (real *)calloc((size_t)(V1 + D), sizeof(real));
+    real *logits = (real *)calloc((size_t)(VT + D), sizeof(real));
     if (len > T) len = T;
     if (len < 0) len = 0;
     int t = 0, n = 0, u = 0, last = blank, departures = 0, bad = 0;
@@ -818,6 +820,60 @@ int orc_follow_sequential(const net_t *net, const real *x_b, int T, int len,
     int *want_b = (int *)malloc(sizeof(int) * (size_t)(len + 2));
     int *want_d = (int *)malloc(sizeof(int) * (size_t)(len + 2));
     while (t < len) {
+        if (NB > 0 && !(u < n_tok && frames[u] == t)) {
+            /* Multi-blank, and the hypothesis has no label on this frame: it went on from   */
+            /* here by blanks and big blanks, which it does not record.  Look for the chain   */
+            /* of such symbols that lands exactly on the frame of its next label (or past     */
+            /* the end) with the smallest worst gap, every symbol on it being the maximum or  */
+            /* less than tol below it; the symbols that are not the maximum are reported.     */
+            /* how_: -1 = the blank, i >= 0 = big blank i.                                     */
+            const int target = (u < n_tok && frames[u] < len) ? frames[u] : len;
+            if (u < n_tok && (frames[u] < t || frames[u] >= len)) { bad = 1; break; }
+            for (int i = t; i <= len; ++i) { best[i] = (real)-1; from_[i] = -1; }
+            best[t] = 0;
+            for (int a = t; a < len && a < target; ++a) {
+                if (best[a] < 0) continue;
+                net->prep(net, x_b + (size_t)a * net->x_size, p);
+                net->joint(net, p, g, logits);
+                real v2, m2;
+                const int k2 = argmax_margin(logits, 0, VT, &v2, &m2);
+                want_b[a] = k2;
+                for (int i = -1; i < NB; ++i) {
+                    const int col = i < 0 ? blank : V1 + i;
+                    const real gap = v2 - logits[col];
+                    if (col != k2 && !(gap < tol)) continue;
+                    int to = a + (i < 0 ? 1 : (net->spans[i] > 1 ? net->spans[i] : 1));
+                    if (to > len) to = len;
+                    if (to > target) continue;                /* would skip the next label's frame */
+                    const real worst = best[a] > gap ? best[a] : gap;
+                    if (best[to] < 0 || worst < best[to]) { best[to] = worst; from_[to] = a; how_[to] = i; }
+                }
+            }
+            if (best[target] >= 0) {
+                int chain[4096], nc = 0;
+                for (int a = target; a != t && nc < 4096; a = from_[a]) chain[nc++] = a;
+                for (int i = nc - 1; i >= 0; --i) {
+                    const int to = chain[i], a = from_[to];
+                    const int col = how_[to] < 0 ? blank : V1 + how_[to];
+                    if (col == want_b[a]) continue;
+                    net->prep(net, x_b + (size_t)a * net->x_size, p);
+                    net->joint(net, p, g, logits);
+                    real v2, m2;
+                    (void)argmax_margin(logits, 0, VT, &v2, &m2);
+                    const real gap = v2 - logits[col];
+                    if (departures < max_report) {
+                        rep_t[departures] = a; rep_u[departures] = u;
+                        rep_want[departures] = want_b[a]; rep_got[departures] = col;
+                        rep_gap[departures] = gap;
+                    }
+                    departures++;
+                    if (gap > *worst_gap) *worst_gap = gap;
+                }
+                t = target; n = 0;
+                continue;
+            }
+            /* no such chain: go on by the plain blank below, which reports its gap */
+        }
         if (D > 0 && tol > (real)0 && !(u < n_tok && frames[u] == t)) {
             /* the hypothesis has a blank here: find the chain of blanks to its next label */
             const int target = (u < n_tok && frames[u] < len) ? frames[u] : len;   /* len = any frame >= len */
@@ -884,7 +940,7 @@ int orc_follow_sequential(const net_t *net, const real *x_b, int T, int len,
         net->prep(net, x_b + (size_t)t * net->x_size, p);
         net->joint(net, p, g, logits);
         real v, mg, dv = 0, dmg = 0;
-        const int k = argmax_margin(logits, 0, V1, &v, &mg);
+        const int k = argmax_margin(logits, 0, VT, &v, &mg);
         int di = 0;
         if (D > 0) di = argmax_margin(logits, V1, V1 + D, &dv, &dmg) - V1;
         int choose = blank;

@@ -532,8 +532,6 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         if (!d.w_ih[l] || !d.w_hh[l] || !d.b_ih[l] || !d.b_hh[l]) return RNNT_ERR_NULL;
     const bool multi_blank = (flags & RNNT_FLAG_MULTI_BLANK) != 0;
     if (multi_blank && d.D < 1) return RNNT_ERR_SHAPE;
-    // the bfloat16 mode's reference check needs the oracle's follow mode, which does not cover these models
-    if (multi_blank && (flags & RNNT_FLAG_BF16_ARITHMETIC)) return RNNT_ERR_UNSUPPORTED;
     for (int i = 0; i < d.D; ++i)
         if (d.durations[i] < (multi_blank ? 1 : 0)) return RNNT_ERR_SHAPE;   // a big blank moves on by at least one frame
 

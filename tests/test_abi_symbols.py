@@ -82,10 +82,9 @@ def test_create_refuses_unsupported_shapes_before_touching_the_device():
     assert create(flags=32) == -2                                    # unknown flag bit
     assert create(flags=pkg.RNNT_FLAG_BF16_ARITHMETIC | pkg.RNNT_FLAG_BF16_WEIGHTS) == -2
     assert create(flags=pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS) == -2
-    # multi-blank: needs big blanks, each spanning at least one frame; not in the bfloat16 mode
+    # multi-blank: needs big blanks, each spanning at least one frame
     assert create(flags=pkg.RNNT_FLAG_MULTI_BLANK) == -2
     assert create(flags=pkg.RNNT_FLAG_MULTI_BLANK, D=2) == -2         # the test's spans start at 0
-    assert create(flags=pkg.RNNT_FLAG_MULTI_BLANK | pkg.RNNT_FLAG_BF16_ARITHMETIC, D=2) == -5
     assert create(flags=pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS) == -2
     assert "not supported" in pkg.rnnt_status_string(-5)
     assert "scratch" in pkg.rnnt_status_string(-6)

@@ -269,8 +269,8 @@ def test_cfg5_second_workload_single_layer_model(pkg):
 def test_cfg6_multi_blank_transducer(pkg):
     """A multi-blank transducer at the Parakeet shape (two big blanks that skip 2 and 4 frames)
     against the oracle's rule: full size in the default layout, with the score (taken over all
-    outputs), one utterance, 128 utterances, other team layouts and lookaheads on a cut, bf16
-    weight storage, and the decoders and modes that do not run such a model."""
+    outputs), one utterance, 128 utterances, other team layouts and lookaheads on a cut, the
+    bfloat16 mode, bf16 weight storage, and the decoders that do not run such a model."""
     w = synth.make_workload(6, pad="nan")
     eng = pkg.Engine(w.model, w.B, w.T)
     ref, got, stats = check(pkg, w, "label", "cfg6/full", engine=eng, logp=True)
@@ -292,8 +292,12 @@ def test_cfg6_multi_blank_transducer(pkg):
         eng.configure(n_teams=n_teams, joint_groups=groups, lookahead=la)
         check(pkg, wc, "label", f"cfg6/cut teams={n_teams}/{groups} la={la}", engine=eng)
     eng.close()
-    with pytest.raises(pkg.RnntError):      # no reference check for that combination: refused
-        pkg.Engine(wc.model, wc.B, wc.T, flags=pkg.RNNT_FLAG_BF16_ARITHMETIC)
+    # the bfloat16 mode, on the cut and at full size, against the emulating oracle
+    for wm in (wc, w):
+        eng = pkg.Engine(wm.model, wm.B, wm.T, flags=pkg.RNNT_FLAG_BF16_ARITHMETIC)
+        _, _, st = check(pkg, wm, "label", f"cfg6/B{wm.B}/bf16 arithmetic", engine=eng, bf16=True, logp=True)
+        assert st["near_tie_rows"] <= max(1, wm.B // 3)
+        eng.close()
     # the model with bf16-valued streamed weights, stored as bf16 (fp32 arithmetic)
     import dataclasses
     wb = dataclasses.replace(wc, model=synth.with_bf16_streamed_weights(wc.model))

@@ -161,3 +161,51 @@ def test_score_is_the_log_softmax_over_all_outputs():
     for k, t, u, lp in zip(r.tokens[0], r.frames[0], range(len(r.tokens[0])), r.logps[0]):
         want = torch.log_softmax(torch.from_numpy(tab[0, t, min(u, 2)].astype(np.float64)), dim=0)[k]
         assert abs(float(lp) - float(want)) < 1e-5
+
+
+def test_follow_on_a_multi_blank_model():
+    """The follow mode on these models: the oracle's own hypothesis has no departure; an altered
+    token is reported where it sits; and between labels the walk finds the chain of blanks and
+    big blanks by itself."""
+    w = synth.make_workload(6, B=3, T=80, len_lo=50, len_hi=80)
+    net = oracle.LstmNet(w.model)
+    ref = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "seq", record=True)
+    V1 = w.model.dims.V1
+    assert (np.concatenate(ref.records.k) >= V1).sum() > 5          # big blanks are on the way
+    for b in range(w.B):
+        f = oracle.follow(net, w.enc_out[b], int(w.enc_len[b]), w.max_symbols, ref.tokens[b], ref.frames[b])
+        assert f.departures == 0 and f.worst_gap == 0.0, (b, f)
+    b = int(np.argmax(ref.tok_len))
+    tok = ref.tokens[b].copy()
+    u = len(tok) // 2
+    tok[u] = (tok[u] + 1) % (V1 - 1)
+    f = oracle.follow(net, w.enc_out[b], int(w.enc_len[b]), w.max_symbols, tok, ref.frames[b])
+    assert f.departures >= 1
+    first = f.where[0]
+    assert first["u"] == u and first["t"] == ref.frames[b][u]
+    assert first["want"] == ref.tokens[b][u] and first["got"] == tok[u] and first["gap"] > 0
+
+
+def test_follow_takes_a_big_blank_that_is_nearly_the_maximum():
+    """Hand-made table (labels 0 and 1, blank 2, one big blank of span 2): on frame 0 the blank
+    wins by 0.005 over the big blank; frame 1 would emit label 1; the hypothesis has label 0 on
+    frame 2.  Only the big blank on frame 0 leads there.  With a tolerance above that gap the
+    walk reports that one choice and its gap; with none it falls back to plain blanks and
+    reports the label it had to pass over on frame 1."""
+    V1, T = 3, 3
+    tab = np.zeros((1, T, 3, V1 + 1), dtype=np.float32)
+    tab[..., V1 - 1] = 10.0                       # blank wherever nothing else is said
+    tab[0, 0, 0] = [0, 0, 10.0, 9.995]
+    tab[0, 1, 0] = [0, 10.0, 0, 0]
+    tab[0, 2, 0] = [10.0, 0, 0, 0]
+    net = oracle.TableNet(tab, V1, big_blanks=(2,))
+    x = net.frames()[0]
+    own = oracle.decode(net, net.frames(), np.array([T]), 2, "seq")
+    assert own.tokens[0].tolist() == [1] and own.frames[0].tolist() == [1]   # the model's own walk
+    near = oracle.follow(net, x, T, 2, [0], [2], tol=0.01)
+    assert near.departures == 1
+    assert near.where[0]["t"] == 0 and near.where[0]["want"] == 2 and near.where[0]["got"] == 3
+    assert abs(near.where[0]["gap"] - 0.005) < 1e-5 and abs(near.worst_gap - 0.005) < 1e-5
+    strict = oracle.follow(net, x, T, 2, [0], [2])
+    assert strict.departures == 1 and strict.where[0]["t"] == 1
+    assert strict.where[0]["want"] == 1 and strict.where[0]["got"] == 2 and strict.worst_gap == 10.0
