@@ -1709,7 +1709,8 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                         xstore64(p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r,
                                  ((unsigned long long)outer << 32) | payload);
                     }
-                    if (w.lane < R && w.lane % G != g) {
+                    // (a row that has ended stays ended: nothing more to learn about it)
+                    if (w.lane < R && w.lane % G != g && c.active[w.lane]) {
                         const int r = w.lane;
                         const unsigned long long *slot =
                             p.rowx + ((long long)w.team * 2 + (outer & 1u)) * kMaxRows + r;
