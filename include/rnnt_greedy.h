@@ -203,7 +203,7 @@ typedef struct rnnt_stats {
  * RNNT_ERR_SHAPE.
  * Limits of this implementation, checked here before anything is allocated
  * (RNNT_ERR_UNSUPPORTED): F must be a multiple of 16 (K tile of the projection
- * GEMM); V1 + D at most 65 535 (the argmax exchange carries a 16-bit column
+ * GEMM); H and J multiples of 4 (rows are read 16 bytes at a time); V1 + D at most 65 535 (the argmax exchange carries a 16-bit column
  * index); max_B * max_T below 2^31 (frame numbers are 32-bit); the device must
  * support cooperative launches.  1 <= L <= 4, D <= 8, blank in
  * [0, V1) and positive sizes are RNNT_ERR_SHAPE.

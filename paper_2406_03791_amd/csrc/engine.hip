@@ -527,6 +527,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         return RNNT_ERR_SHAPE;
     if (d.F % 16 != 0) return RNNT_ERR_UNSUPPORTED;   // K tile of the projection GEMM
     if ((long long)max_B * max_T > 0x7fffffffLL) return RNNT_ERR_UNSUPPORTED;   // frame numbers are 32-bit
+    if (d.H % 4 != 0 || d.J % 4 != 0) return RNNT_ERR_UNSUPPORTED;   // rows are read 16 bytes at a time
     if (d.V1 + d.D > 65535) return RNNT_ERR_UNSUPPORTED;   // argmax partials carry a 16-bit column index
     for (int l = 0; l < d.L; ++l)
         if (!d.w_ih[l] || !d.w_hh[l] || !d.b_ih[l] || !d.b_hh[l]) return RNNT_ERR_NULL;

@@ -75,6 +75,7 @@ def test_create_refuses_unsupported_shapes_before_touching_the_device():
 
     assert create(F=17) == -5
     assert create(F=24) == -5
+    assert create(H=10) == -5 and create(J=6) == -5                  # widths are multiples of 4
     assert create(V1=65536, blank=0) == -5
     assert create(L=0) == -2 and create(L=5) == -2
     assert create(blank=5) == -2 and create(blank=-1) == -2

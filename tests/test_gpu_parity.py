@@ -306,6 +306,29 @@ def test_cfg6_multi_blank_transducer(pkg):
     eng.close()
 
 
+def test_widths_that_divide_unevenly(pkg):
+    """Models whose widths are multiples of 4 and of nothing larger, three layers, a vocabulary
+    of 23 and (TDT) three durations: hidden units, projection columns and output groups divide
+    unevenly over the ranks, some ranks own none, and every K is padded.  All decoders, the
+    default layouts for 3 and 20 utterances and two configured ones, fp32 and the bfloat16 mode."""
+    for durations, variants in (((), ("frame", "label")), ((0, 1, 3), ("tdt",))):
+        dims = synth.ModelDims(F=48, E=36, H=52, L=3, J=76, V1=23, durations=durations)
+        model = synth.make_model(dims, seed=21, weight_range=0.3, blank_bias=1.5)
+        for B, T in ((3, 40), (20, 30)):
+            x, ln = synth.make_inputs(77 + B, B, T, dims.F, T // 3, T, pad="nan")
+            w = synth.Workload("odd", variants[0], model, x, ln, 3)
+            for flags, bf16 in ((0, False), (pkg.RNNT_FLAG_BF16_ARITHMETIC, True)):
+                eng = pkg.Engine(model, B, T, flags=flags)
+                for variant in variants:
+                    check(pkg, w, variant, f"odd widths B={B}", engine=eng, bf16=bf16, logp=(variant != "frame"))
+                    if B == 20:
+                        for n_teams, groups in ((8, 2), (32, 1)):
+                            eng.configure(n_teams=n_teams, joint_groups=groups if variant != "frame" else 0)
+                            check(pkg, w, variant, f"odd widths teams={n_teams}/{groups}", engine=eng, bf16=bf16)
+                        eng.configure()
+                eng.close()
+
+
 def test_repeat_and_permutation_invariance(pkg):
     w = synth.make_workload(2, pad="nan", B=8, T=60, len_lo=20, len_hi=60)
     eng = engine_for(pkg, "parakeet8", w.model, 8, 60)
