@@ -329,6 +329,25 @@ def test_widths_that_divide_unevenly(pkg):
                 eng.close()
 
 
+def test_wide_joint_and_wide_hidden_layers(pkg):
+    """A joint layer wider than the 768 columns a wave holds in registers while it forms z (the
+    rest of a row is loaded where it is used), and a hidden width above 1024, for which the
+    teams of few utterances use the general prediction step (barriers) instead of the one with
+    tagged words."""
+    for dims, bias in ((synth.ModelDims(F=64, E=48, H=128, L=2, J=832, V1=33), 1.2),
+                       (synth.ModelDims(F=64, E=48, H=1088, L=1, J=832, V1=33), 1.2),
+                       (synth.ModelDims(F=64, E=48, H=1088, L=1, J=128, V1=33, durations=(0, 1, 2)), 0.4)):
+        model = synth.make_model(dims, seed=31, weight_range=0.1, blank_bias=bias)
+        x, ln = synth.make_inputs(91, 3, 24, dims.F, 10, 24, pad="nan")
+        variants = ("tdt",) if dims.D else ("frame", "label")
+        w = synth.Workload("wide", variants[0], model, x, ln, 3)
+        eng = pkg.Engine(model, 3, 24)
+        for variant in variants:
+            ref, _, _ = check(pkg, w, variant, f"wide H={dims.H} J={dims.J}", engine=eng, logp=(variant == "label"))
+            assert int(ref.tok_len.sum()) > 10
+        eng.close()
+
+
 def test_repeat_and_permutation_invariance(pkg):
     w = synth.make_workload(2, pad="nan", B=8, T=60, len_lo=20, len_hi=60)
     eng = engine_for(pkg, "parakeet8", w.model, 8, 60)
