@@ -212,7 +212,11 @@ typedef struct rnnt_stats {
  * A team of work-groups holds at most 16 utterances and its state has to fit
  * the compute units' local memory: with the Parakeet shape on 256 compute
  * units max_B up to 256 is accepted, a larger one returns
- * RNNT_ERR_UNSUPPORTED (decode a larger batch in several calls).
+ * RNNT_ERR_UNSUPPORTED (decode a larger batch in several calls).  The argmax
+ * candidates of a joint step sit there too, one per sample and group of four
+ * output columns of a rank: vocabularies of a few thousand labels fit for any
+ * batch, 16 385 labels only for engines of a few utterances, and much larger
+ * ones are refused the same way.
  * Synchronous.  *out is set only on success.
  */
 int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T,

@@ -348,6 +348,27 @@ def test_wide_joint_and_wide_hidden_layers(pkg):
         eng.close()
 
 
+def test_four_layers_and_large_vocabularies(pkg):
+    """The largest layer count (4), and vocabularies of 4 097 and 16 385 labels (513 output groups
+    per rank of a joint group of 8): the second fits the local memory only for engines of few
+    utterances, and a vocabulary of 60 001 is refused when the engine is created."""
+    for dims, bias, sizes in ((synth.ModelDims(F=64, E=64, H=320, L=4, J=320, V1=129), 1.0, (3, 40)),
+                              (synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=4097), 1.5, (3, 40)),
+                              (synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=16385), 2.0, (3,))):
+        model = synth.make_model(dims, seed=41, weight_range=0.1, blank_bias=bias)
+        for B in sizes:
+            x, ln = synth.make_inputs(93, B, 24, dims.F, 10, 24, pad="nan")
+            w = synth.Workload("vocab", "label", model, x, ln, 3)
+            eng = pkg.Engine(model, B, 24)
+            for variant in ("frame", "label"):
+                check(pkg, w, variant, f"L={dims.L} V1={dims.V1} B={B}", engine=eng, logp=(variant == "label"))
+            eng.close()
+    big = synth.make_model(synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=60001), seed=41)
+    with pytest.raises(pkg.RnntError) as err:
+        pkg.Engine(big, 3, 24)
+    assert err.value.code == -5
+
+
 def test_repeat_and_permutation_invariance(pkg):
     w = synth.make_workload(2, pad="nan", B=8, T=60, len_lo=20, len_hi=60)
     eng = engine_for(pkg, "parakeet8", w.model, 8, 60)
