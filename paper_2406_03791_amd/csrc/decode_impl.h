@@ -1027,8 +1027,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
     WeightStream ws;
     {
         const int k4n = kpad >> 2;                 // float4 per z row, zero padding included
-        const int j4 = p.J >> 2;                   // whole float4 of a row
-        const bool vec = (p.J & 3) == 0;
+        const int j4 = p.J >> 2;                   // float4 of a row (J is a multiple of 4)
         constexpr int SPW = (RG * 4 + kWaves - 1) / kWaves;    // samples per wave
         float4 pe[SPW][3];
         int valid[SPW], qoff[SPW];
@@ -1045,22 +1044,11 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
             if (valid[i]) {
                 qoff[i] = qo;
                 const float *pr = p.P + (long long)pidx * p.J;
-                if (vec) {
 #pragma unroll
-                    for (int u = 0; u < 3; ++u) {
-                        const int k4 = w.lane + 64 * u;
-                        if (64 * u < j4)       // uniform; lanes past the row read its first float4
-                            pe[i][u] = reinterpret_cast<const float4 *>(pr)[k4 < j4 ? k4 : 0];
-                    }
-                } else {
-#pragma unroll
-                    for (int u = 0; u < 3; ++u) {
-                        const int k = (w.lane + 64 * u) * 4;
-                        if (k < p.J) pe[i][u].x = pr[k];
-                        if (k + 1 < p.J) pe[i][u].y = pr[k + 1];
-                        if (k + 2 < p.J) pe[i][u].z = pr[k + 2];
-                        if (k + 3 < p.J) pe[i][u].w = pr[k + 3];
-                    }
+                for (int u = 0; u < 3; ++u) {
+                    const int k4 = w.lane + 64 * u;
+                    if (64 * u < j4)       // uniform; lanes past the row read its first float4
+                        pe[i][u] = reinterpret_cast<const float4 *>(pr)[k4 < j4 ? k4 : 0];
                 }
             }
         }
@@ -1080,20 +1068,15 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
                 const int k = k4 * 4;
                 float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (valid[i] && k < p.J) {
-                    float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
+                    float4 qv;
                     if (p.q_in_lds) {
                         qv = *reinterpret_cast<const float4 *>(l.q + qoff[i] + k);
                     } else {
                         const float *qr = p.qbuf + ((long long)w.team * kMaxRows + qoff[i]) * p.J + k;
-                        qv.x = xload(qr);
-                        if (k + 1 < p.J) qv.y = xload(qr + 1);
-                        if (k + 2 < p.J) qv.z = xload(qr + 2);
-                        if (k + 3 < p.J) qv.w = xload(qr + 3);
+                        qv = make_float4(xload(qr), xload(qr + 1), xload(qr + 2), xload(qr + 3));
                     }
-                    z.x = fmaxf(pe[i][u].x + qv.x, 0.f);
-                    if (k + 1 < p.J) z.y = fmaxf(pe[i][u].y + qv.y, 0.f);
-                    if (k + 2 < p.J) z.z = fmaxf(pe[i][u].z + qv.z, 0.f);
-                    if (k + 3 < p.J) z.w = fmaxf(pe[i][u].w + qv.w, 0.f);
+                    z = make_float4(fmaxf(pe[i][u].x + qv.x, 0.f), fmaxf(pe[i][u].y + qv.y, 0.f),
+                                    fmaxf(pe[i][u].z + qv.z, 0.f), fmaxf(pe[i][u].w + qv.w, 0.f));
                 }
                 x_store4<WT>(zrow, k, z);
             }
@@ -1109,12 +1092,11 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
                     float pv[4], qv[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        pv[j] = k + j < p.J ? pr[j] : 0.f;
-                        qv[j] = k + j >= p.J ? 0.f : (p.q_in_lds ? l.q[qoff[i] + k + j] : xload(qr + j));
+                        pv[j] = pr[j];
+                        qv[j] = p.q_in_lds ? l.q[qoff[i] + k + j] : xload(qr + j);
                     }
-                    z = make_float4(fmaxf(pv[0] + qv[0], 0.f), k + 1 < p.J ? fmaxf(pv[1] + qv[1], 0.f) : 0.f,
-                                    k + 2 < p.J ? fmaxf(pv[2] + qv[2], 0.f) : 0.f,
-                                    k + 3 < p.J ? fmaxf(pv[3] + qv[3], 0.f) : 0.f);
+                    z = make_float4(fmaxf(pv[0] + qv[0], 0.f), fmaxf(pv[1] + qv[1], 0.f),
+                                    fmaxf(pv[2] + qv[2], 0.f), fmaxf(pv[3] + qv[3], 0.f));
                 }
                 x_store4<WT>(zrow, k, z);
             }
