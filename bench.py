@@ -429,6 +429,29 @@ def main() -> int:
             line["variants"][v + "_small_model"] = {
                 "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
                 "frames": rv["w"].frames, "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
+        # the bfloat16 mode (bf16 and e4m3 storage) with its divergence counts: rows whose tokens are
+        # those of the oracle's emulation of the same arithmetic, and rows whose tokens differ
+        # from the fp32 oracle's on the same model
+        import oracle as _orc
+        for v in ("frame", "label", "tdt"):
+            for storage in ("fp32", "fp8"):
+                rv = run_variant(v, max(3, args.steps // 2), 2, arithmetic="bf16", storage=storage)
+                wv = rv["w"]
+                nthr = min(16, os.cpu_count() or 1)
+                emul = _orc.decode(_orc.LstmNet(wv.model, bf16=True), wv.enc_out, wv.enc_len,
+                                   wv.max_symbols, "seq", n_threads=nthr)
+                f32 = _orc.decode(_orc.LstmNet(wv.model), wv.enc_out, wv.enc_len, wv.max_symbols,
+                                  "seq", n_threads=nthr)
+                same = sum(int(np.array_equal(emul.tokens[b], rv["tokens"][b])) for b in range(wv.B))
+                moved = sum(int(not np.array_equal(f32.tokens[b], rv["tokens"][b])) for b in range(wv.B))
+                name = v + "_bf16_arithmetic" + ("_e4m3_weights" if storage == "fp8" else "")
+                line["variants"][name + "_divergence"] = {
+                    "decode_ms": rv["dec_ms"], "tokens": int(rv["tok_len"].sum()),
+                    "tokens_fp32_oracle_same_model": int(f32.tok_len.sum()),
+                    "rows": wv.B, "rows_token_identical_to_emulating_oracle": same,
+                    "rows_differing_from_fp32_oracle": moved,
+                    "max_pred_steps": rv["stats"]["max_pred_steps"],
+                    "max_joint_steps": rv["stats"]["max_joint_steps"], "status": rv["status"]}
         # the multi-blank transducer of configuration 6 (two big blanks that skip 2 and 4 frames)
         rv = run_variant("label", max(3, args.steps // 2), 2, cfg=6)
         line["variants"]["label_multi_blank_model"] = {
