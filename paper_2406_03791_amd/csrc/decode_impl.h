@@ -1140,7 +1140,9 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
     // live: into the partial-sum region when the sums sit in the z rows, else into the z rows.
     unsigned long long *cand = reinterpret_cast<unsigned long long *>(alias ? l.red : l.xz);
     unsigned long long *cand_d = cand + ns * ngx;
-    float *rank_max = reinterpret_cast<float *>(cand + 2 * ns * ngx);     // [ns], for the scores
+    // for the scores: per (sample, group) the sum of exp(logit - the group's maximum) over its
+    // token columns, merged below like the keys (asked for only when the caller wants scores)
+    float *se_part = reinterpret_cast<float *>(cand + 2 * ns * ngx) + kMaxSamples;   // [ns][ngx]
     float *tail_sum = l.tail + ((p.J + 3) & ~3);
     {
         int nsp = 1, lg = 0;
@@ -1159,6 +1161,16 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
             }
             cand[s * ngx + g] = kt;
             if (p.D > 0) cand_d[s * ngx + g] = kd;
+            if (p.logps) {
+                float m4 = -INFINITY, se = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((g0 + g) * 4 + j < p.VT) m4 = fmaxf(m4, a[j]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((g0 + g) * 4 + j < p.VT) se += expf(a[j] - m4);
+                se_part[s * ngx + g] = se;
+            }
         }
         if (has_tail && w.tid < ns) {
             // the tail column's logit: its bias plus the waves' sums; kept in the first wave's
@@ -1170,6 +1182,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
             const int col = p.nout_m + w.jrank;
             cand[w.tid * ngx + ng] = col < p.VT ? make_key(a, col) : 0ull;
             if (p.D > 0) cand_d[w.tid * ngx + ng] = col < p.VT ? 0ull : make_key(a, col - p.VT);
+            if (p.logps) se_part[w.tid * ngx + ng] = col < p.VT ? 1.f : 0.f;
         }
     }
     __syncthreads();
@@ -1178,49 +1191,25 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
     if (w.wave * 8 < ns) {
         const int s = w.tid >> 3, sub = w.tid & 7;
         unsigned long long kt = 0ull, kd = 0ull;
+        float lm = -INFINITY, ls = 0.f;        // running (maximum, sum of exp relative to it)
         if (s < ns)
             for (int g = sub; g < ngx; g += 8) {
                 const unsigned long long k = cand[s * ngx + g];
                 kt = k > kt ? k : kt;
                 if (p.D > 0) { const unsigned long long d = cand_d[s * ngx + g]; kd = d > kd ? d : kd; }
+                if (p.logps && k) lse_merge(lm, ls, key_value(k), se_part[s * ngx + g]);
             }
         kt = key_max8(kt);
         if (p.D > 0) kd = key_max8(kd);
+        if (p.logps) { lse_merge_dpp<0xB1>(lm, ls); lse_merge_dpp<0x4E>(lm, ls); lse_merge_dpp<0x141>(lm, ls); }
         if (s < ns && sub == 0) {
             const long long o =
                 (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + s) * p.jteam_size + w.jrank;
             xstore64(p.part + o, with_tag(kt, tag));
             if (p.D > 0) xstore64(p.dpart + o, with_tag(kd, tag));
-            if (p.logps) rank_max[s] = kt ? key_value(kt) : -INFINITY;
-        }
-    }
-    if (p.logps) {
-        // log-softmax of the maximum, first half: this rank's sum of exp(logit - its own maximum)
-        // over its token columns (asked for only when the caller wants scores)
-        __syncthreads();
-        float *se_part = rank_max + kMaxSamples;          // [ns][ngx]
-        int nsp = 1, lg = 0;
-        while (nsp < ns) { nsp <<= 1; ++lg; }
-        const int s = w.tid & (nsp - 1);
-        for (int g = w.tid >> lg; g < ng; g += kThreads >> lg) {
-            if (s >= ns) continue;
-            float a[4], se = 0.f;
-            reduce_tasks4<RG>(red, p.sjoint.nks, g, s, a);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((g0 + g) * 4 + j < p.VT) se += expf(a[j] - rank_max[s]);
-            se_part[s * ngx + g] = se;
-        }
-        if (has_tail && w.tid < ns)
-            se_part[w.tid * ngx + ng] = p.nout_m + w.jrank < p.VT ? expf(tail_sum[w.tid] - rank_max[w.tid]) : 0.f;
-        __syncthreads();
-        if (w.tid < ns) {
-            float se = 0.f;
-            for (int g = 0; g < ngx; ++g) se += se_part[w.tid * ngx + g];
-            const long long o =
-                (((long long)(w.team * p.groups + w.jg) * 2 + parity) * kMaxSamples + w.tid) * p.jteam_size + w.jrank;
-            // the sum travels as a float in the high word (it is positive: no key order needed)
-            xstore64(p.lpart + o, with_tag((unsigned long long)__float_as_uint(se) << 32, tag));
+            // the rank's sum, relative to its own maximum (the value of kt), travels as a float
+            // in the high word (it is positive: no key order needed)
+            if (p.logps) xstore64(p.lpart + o, with_tag((unsigned long long)__float_as_uint(ls) << 32, tag));
         }
     }
     PROF_MARK(w, 15);
@@ -1237,11 +1226,12 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
             for (int r0 = sub; r0 < p.jteam_size; r0 += 64) {
                 const int n = min(4, (p.jteam_size - r0 + 15) >> 4);
                 unsigned long long wd[4], wdur[4];
+                unsigned long long wl[4];
                 if (p.D > 0) read_words4(p.dpart + o + r0, 16, n, wdur);   // in flight with the token words
+                if (p.logps) read_words4(p.lpart + o + r0, 16, n, wl);
                 wait_words4(p, sy, p.part + o + r0, 16, n, tag, wd);
                 if (p.logps) {
-                    unsigned long long wl[4];
-                    wait_words4(p, sy, p.lpart + o + r0, 16, n, tag, wl);
+                    wait_words4<true>(p, sy, p.lpart + o + r0, 16, n, tag, wl);
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
                         if (i < n && wd[i]) lse_merge(lm, ls, key_value(wd[i]), __uint_as_float((unsigned)(wl[i] >> 32)));
