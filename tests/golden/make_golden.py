@@ -19,6 +19,7 @@ CASES = {
     "cfg1": dict(cfg=1),
     "cfg2_cut": dict(cfg=2, B=4, T=60, len_lo=30, len_hi=60),
     "cfg4_cut": dict(cfg=4, B=4, T=60, len_lo=30, len_hi=60),
+    "cfg6_cut": dict(cfg=6, B=4, T=60, len_lo=30, len_hi=60),      # multi-blank
 }
 
 
