@@ -203,8 +203,12 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     // configured lookahead, else 8; 16 is always allowed for), at most kMaxSamples.  The z rows
     // and the argmax candidates in LDS are sized for it.
     const int rows_j_max = (rows_max + groups - 1) / groups;
-    const int samples_cap = std::min(kMaxSamples, std::max(16, rows_j_max * (e->lookahead > 0 ? e->lookahead : 8)));
-    const int rgj = samples_cap / 4;
+    // The joint kernels exist for 1, 2, 4 and 8 row groups (joint_row_groups) and an instance
+    // uses all of its rows and the partial-sum stride of its own group count: the capacity is
+    // that of the instance that runs the largest step, not the largest step itself.
+    const int samples_want = std::min(kMaxSamples, std::max(16, rows_j_max * (e->lookahead > 0 ? e->lookahead : 8)));
+    const int rgj = joint_row_groups(samples_want);
+    const int samples_cap = rgj * 4;
     int off = 0;
     auto take = [&](int n) { int o = off; off += (n + 3) & ~3; return o; };
     int xstride = 0;

@@ -532,6 +532,36 @@ def test_row_group_counts_between_the_kernel_instances(pkg):
     eng.close()
 
 
+def test_joint_steps_between_the_kernel_instances(pkg):
+    """Joint steps of 17-31 samples run the kernels built for 32: the z rows and the stride of
+    the partial sums have to be those of that instance.  max_B = 96 and 80 in the default
+    label-looping layout (3 rows per joint group x 8 frames = 24 samples), TDT at 72, and
+    lookaheads that give 18, 20, 25 and 28 samples."""
+    w = synth.make_workload(3, pad="nan", B=96, T=48, len_lo=10, len_hi=48)
+    check(pkg, w, "label", "parakeet96")
+    check(pkg, w, "frame", "parakeet96")
+    eng = pkg.Engine(w.model, w.B, w.T)
+    eng.configure(lookahead=6)                      # 3 rows x 6 frames
+    check(pkg, w, "frame", "parakeet96/lookahead 6", engine=eng)
+    check(pkg, w, "label", "parakeet96/lookahead 6", engine=eng)
+    eng.close()
+    w80 = synth.make_workload(3, pad="nan", B=80, T=48, len_lo=10, len_hi=48)
+    check(pkg, w80, "label", "parakeet80")
+    w40 = synth.make_workload(3, pad="nan", B=40, T=40, len_lo=10, len_hi=40)
+    eng = pkg.Engine(w40.model, w40.B, w40.T)
+    for la in (4, 5):                               # 5 rows per joint group x 4 or 5 frames
+        eng.configure(n_teams=4, joint_groups=2, lookahead=la)
+        check(pkg, w40, "label", f"parakeet40/4 teams/2 groups/lookahead {la}", engine=eng)
+    eng.close()
+    w56 = synth.make_workload(3, pad="nan", B=56, T=40, len_lo=10, len_hi=40)
+    eng = pkg.Engine(w56.model, w56.B, w56.T)       # 7 rows per team x 4 frames
+    eng.configure(n_teams=8, joint_groups=1, lookahead=4)
+    check(pkg, w56, "label", "parakeet56/8 teams/lookahead 4", engine=eng)
+    eng.close()
+    w4 = synth.make_workload(4, pad="nan", B=72, T=48, len_lo=10, len_hi=48)
+    check(pkg, w4, "tdt", "tdt72")
+
+
 def test_optional_outputs_may_be_null(pkg):
     """frames_out, logit_out and durations_out are optional in the C ABI: with NULL for all of
     them every decoder still writes the same tokens and counts."""
