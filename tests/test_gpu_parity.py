@@ -562,6 +562,45 @@ def test_joint_steps_between_the_kernel_instances(pkg):
     check(pkg, w4, "tdt", "tdt72")
 
 
+def test_every_default_layout_class_of_the_parakeet_shape(pkg):
+    """Engines of many sizes, each decoding a full batch of short utterances in its default
+    layout: every combination of rows per team, joint groups and lookahead the defaults
+    produce between 1 and 256 utterances is run once against the oracle."""
+    sizes = [1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 24, 31, 33, 40, 48, 56, 63, 65, 72, 88, 104, 112,
+             120, 129, 144, 176, 192, 208, 224, 240, 255, 256]
+    for B in sizes:
+        w = synth.make_workload(3, pad="nan", B=B, T=16, len_lo=5, len_hi=16)
+        eng = pkg.Engine(w.model, w.B, w.T)
+        check(pkg, w, "label", f"parakeet{B}", engine=eng)
+        check(pkg, w, "frame", f"parakeet{B}", engine=eng)
+        eng.close()
+    for B in [3, 9, 20, 36, 66, 90, 100, 136, 200, 250]:
+        w = synth.make_workload(4, pad="nan", B=B, T=16, len_lo=5, len_hi=16)
+        eng = pkg.Engine(w.model, w.B, w.T)
+        check(pkg, w, "tdt", f"tdt{B}", engine=eng)
+        eng.close()
+
+
+def test_default_layout_classes_of_the_other_weight_forms(pkg):
+    """The LDS layout depends on the K values a load carries: the same sweep, coarser, for bf16
+    and e4m3 storage and for the bfloat16 arithmetic with either storage."""
+    import dataclasses
+    forms = [("bf16w", pkg.RNNT_FLAG_BF16_WEIGHTS, synth.with_bf16_streamed_weights, False),
+             ("fp8w", pkg.RNNT_FLAG_FP8_WEIGHTS, synth.with_fp8_streamed_weights, False),
+             ("bf16 arithmetic", pkg.RNNT_FLAG_BF16_ARITHMETIC, None, True),
+             ("bf16 arithmetic/fp8w", pkg.RNNT_FLAG_BF16_ARITHMETIC | pkg.RNNT_FLAG_FP8_WEIGHTS,
+              synth.with_fp8_streamed_weights, True)]
+    for B in [5, 24, 72, 104, 160, 256]:
+        for cfg, variants in [(3, ("label", "frame")), (4, ("tdt",))]:
+            w0 = synth.make_workload(cfg, pad="nan", B=B, T=16, len_lo=5, len_hi=16)
+            for name, flag, transform, bf16 in forms:
+                w = dataclasses.replace(w0, model=transform(w0.model)) if transform else w0
+                eng = pkg.Engine(w.model, w.B, w.T, flags=flag)
+                for variant in variants:
+                    check(pkg, w, variant, f"cfg{cfg}/{name}/{B}", engine=eng, bf16=bf16)
+                eng.close()
+
+
 def test_optional_outputs_may_be_null(pkg):
     """frames_out, logit_out and durations_out are optional in the C ABI: with NULL for all of
     them every decoder still writes the same tokens and counts."""
