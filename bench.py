@@ -261,8 +261,16 @@ def main() -> int:
     def run_variant(variant, steps, warmup, storage="fp32", logp=False, cfg=None, arithmetic="f32"):
         cfg = {"frame": 2, "label": 3, "tdt": 4}[variant] if cfg is None else cfg
         w = synth.make_workload(cfg, B=args.batch)
+        w_orig = w
         flags = 0
-        if storage != "fp32":
+        if storage == "fp8" and arithmetic == "bf16":
+            # weight-only 8-bit quantisation: every streamed matrix row by row to e4m3 codes with a
+            # power-of-two scale (the library's host-side quantiser), kept in that form by the engine
+            import dataclasses
+            flags = pkg.RNNT_FLAG_FP8_WEIGHTS
+            w = dataclasses.replace(w, model=synth.with_streamed_weights(
+                w.model, lambda a: pkg.rnnt_quantize_rows_e4m3(a)[0]))
+        elif storage != "fp32":
             # the model a bf16 / 8-bit e4m3 checkpoint would give for the streamed matrices, kept
             # in that format by the engine (lossless); fp32 arithmetic, checked against the
             # oracle on that model
@@ -301,7 +309,7 @@ def main() -> int:
             per_team = [eng.phase_timers(t) for t in range(st["n_teams"])]
             slow = max(range(len(per_team)), key=lambda t: sum(per_team[t]))
             phases = {"team": slow, "us": dict(zip(PHASES, per_team[slow]))}
-        res = dict(w=w, wall=wall, steps=steps, phases=phases, dec_ms=float(np.median(dec_ms)),
+        res = dict(w=w, w_orig=w_orig, wall=wall, steps=steps, phases=phases, dec_ms=float(np.median(dec_ms)),
                    proj_ms=float(np.median(proj_ms)), dec_ms_min=float(np.min(dec_ms)), stats=st,
                    status=status, frames=frames, tokens=tokens, tok_len=tok_len)
         eng.close()
@@ -412,7 +420,7 @@ def main() -> int:
         line["variants"][v + "_bf16_arithmetic"] = {
             "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
             "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
-        # the same mode on the model with e4m3-valued streamed weights, stored as e4m3
+        # the same mode with the streamed weights quantised to e4m3 codes with row scales
         rv = run_variant(v, max(3, args.steps // 2), 2, arithmetic="bf16", storage="fp8")
         line["variants"][v + "_bf16_arithmetic_e4m3_weights"] = {
             "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
@@ -445,13 +453,22 @@ def main() -> int:
                 same = sum(int(np.array_equal(emul.tokens[b], rv["tokens"][b])) for b in range(wv.B))
                 moved = sum(int(not np.array_equal(f32.tokens[b], rv["tokens"][b])) for b in range(wv.B))
                 name = v + "_bf16_arithmetic" + ("_e4m3_weights" if storage == "fp8" else "")
+                extra = {}
+                if storage == "fp8":
+                    # against the fp32 decode of the model before it was quantised
+                    wo = rv["w_orig"]
+                    f32o = _orc.decode(_orc.LstmNet(wo.model), wo.enc_out, wo.enc_len, wo.max_symbols,
+                                       "seq", n_threads=nthr)
+                    extra = {"rows_differing_from_fp32_oracle_on_unquantised_model":
+                             sum(int(not np.array_equal(f32o.tokens[b], rv["tokens"][b])) for b in range(wv.B)),
+                             "tokens_fp32_oracle_unquantised_model": int(f32o.tok_len.sum())}
                 line["variants"][name + "_divergence"] = {
                     "decode_ms": rv["dec_ms"], "tokens": int(rv["tok_len"].sum()),
                     "tokens_fp32_oracle_same_model": int(f32.tok_len.sum()),
                     "rows": wv.B, "rows_token_identical_to_emulating_oracle": same,
                     "rows_differing_from_fp32_oracle": moved,
                     "max_pred_steps": rv["stats"]["max_pred_steps"],
-                    "max_joint_steps": rv["stats"]["max_joint_steps"], "status": rv["status"]}
+                    "max_joint_steps": rv["stats"]["max_joint_steps"], "status": rv["status"], **extra}
         # the multi-blank transducer of configuration 6 (two big blanks that skip 2 and 4 frames)
         rv = run_variant("label", max(3, args.steps // 2), 2, cfg=6)
         line["variants"]["label_multi_blank_model"] = {

@@ -155,12 +155,31 @@ typedef struct rnnt_stats {
  * reference that rounds at the same places (up to summation order).  Excludes
  * RNNT_FLAG_BF16_WEIGHTS (RNNT_ERR_SHAPE).  Together with RNNT_FLAG_FP8_WEIGHTS
  * it is the weight-only 8-bit form of the mode (the quantised products of the
- * paper's conclusion): the streamed weights are kept as e4m3 -- every one must
- * be an e4m3 value, else RNNT_ERR_SHAPE -- and widened to bf16, which holds all
- * e4m3 values, on their way to the bf16 matrix instructions; the arithmetic is
- * that of the bfloat16 mode on that model.
+ * paper's conclusion): the streamed weights are kept as e4m3 codes with one
+ * power-of-two scale per weight row (per output of the product).  The engine
+ * finds the scale itself -- 2^k with the smallest k for which the row's largest
+ * magnitude times 2^-k is at most 448 -- and every weight of the row times 2^-k
+ * must then be an e4m3 value, else RNNT_ERR_SHAPE (lossless or refused, per
+ * row; rnnt_quantize_rows_e4m3 below maps any matrix to the nearest such one).
+ * The codes are widened to bf16 and multiplied by the row's power of two in one
+ * instruction on their way to the bf16 matrix instructions, without rounding;
+ * the arithmetic is that of the bfloat16 mode on that model.
  */
 #define RNNT_FLAG_BF16_ARITHMETIC 8
+
+/*
+ * Weight-only 8-bit quantisation of a matrix for the flags above (a host-side
+ * helper; nothing runs on the device).  w and out are HOST arrays of
+ * rows * cols floats, row-major, one row per output of the product; they may
+ * be the same array.  For each row: k is the smallest integer with
+ * max|row| * 2^-k <= 448 (0 for a row of zeros; kept within +-100), and every weight becomes
+ * 2^k times the e4m3 value nearest to weight * 2^-k (ties to the even code).
+ * scales_out, if not NULL, receives the rows' 2^k.  An engine created with
+ * RNNT_FLAG_BF16_ARITHMETIC | RNNT_FLAG_FP8_WEIGHTS accepts the result for
+ * any of its streamed matrices.  Weights that are not finite are
+ * RNNT_ERR_SHAPE; NULL arrays RNNT_ERR_NULL.
+ */
+int rnnt_quantize_rows_e4m3(const float *w, int64_t rows, int64_t cols, float *out, float *scales_out);
 
 /*
  * rnnt_engine_create flag: launch the decode kernel with an ordinary launch
@@ -402,11 +421,13 @@ int rnnt_engine_phase_timers(rnnt_engine *eng, int32_t team, double *us_out, int
  *                        32x32x2 (shape 1, the projection kernel's).
  *   rnnt_probe_e4m3_widening  the bf16 (as 16-bit codes) that the conversion
  *                        used by the bfloat16 mode with e4m3-stored weights
- *                        makes of every e4m3 code: bf16_out is a HOST array of
- *                        4 * 256 entries, [byte position in a word][code].
+ *                        makes of every e4m3 code under the scale operand
+ *                        `scale` (the decode kernel passes a weight row's
+ *                        power of two): bf16_out is a HOST array of 4 * 256
+ *                        entries, [byte position in a word][code].
  * Return RNNT_OK or an RNNT_ERR_* code.
  */
-int rnnt_probe_e4m3_widening(uint16_t *bf16_out);
+int rnnt_probe_e4m3_widening(float scale, uint16_t *bf16_out);
 int rnnt_probe_stream(int32_t from_l2, double *gbytes_per_s_out, double *per_cu_out);
 int rnnt_probe_exchange(int32_t team_size, int32_t len, int32_t tagged, double *us_per_exchange_out);
 int rnnt_probe_mfma(int32_t shape, double *tflops_out);

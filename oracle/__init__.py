@@ -39,6 +39,8 @@ def _lib(real: str):
         lib.orc_lstm_net_emulate_bf16.restype = None
         lib.orc_round_bf16.argtypes = [C.c_float if real == "float" else C.c_double]
         lib.orc_round_bf16.restype = C.c_float if real == "float" else C.c_double
+        lib.orc_quantize_rows_e4m3.argtypes = [C.c_void_p, C.c_long, C.c_long, C.c_void_p, C.c_void_p]
+        lib.orc_quantize_rows_e4m3.restype = None
         _LIBS[real] = lib
     return _LIBS[real]
 
@@ -308,3 +310,16 @@ def follow(net: Net, enc_out_b: np.ndarray, length: int, max_symbols: int,
                   got=int(rep[3][i]), gap=float(gap[i]))
              for i in range(max(0, min(n, max_report)))]
     return Followed(int(n), float(worst[0]), where)
+
+
+def quantize_rows_e4m3(w: np.ndarray, real: str = "float"):
+    """(quantised copy, row scales) of a 2-D matrix: every row as e4m3 values times a power
+    of two of its own (orc_quantize_rows_e4m3)."""
+    dt = _np_real(real)
+    w = np.ascontiguousarray(w, dtype=dt)
+    assert w.ndim == 2
+    out = np.empty_like(w)
+    scales = np.empty(w.shape[0], dtype=dt)
+    _lib(real).orc_quantize_rows_e4m3(w.ctypes.data, w.shape[0], w.shape[1], out.ctypes.data,
+                                      scales.ctypes.data)
+    return out, scales

@@ -287,6 +287,49 @@ void orc_lstm_net_emulate_bf16(net_t *n)
 }
 real orc_round_bf16(real v) { return round_bf16(v); }
 
+/* Weight-only 8-bit quantisation of a matrix, one power-of-two scale per row    */
+/* (the quantised products the paper's conclusion points to, here in the 8-bit    */
+/* floating-point format OCP e4m3: 1 sign bit, 4 exponent bits with bias 7, 3      */
+/* mantissa bits, subnormals m * 2^-9, no infinities, largest value 448).  For a   */
+/* row with largest magnitude M > 0, k is the smallest integer with                 */
+/* M * 2^-k <= 448 (kept within +-100; k = 0 for a row of zeros), and each weight   */
+/* w becomes 2^k * e, e the e4m3 value nearest to w * 2^-k, a tie going to the      */
+/* value with the even code.  Written as a search over the table of the 127         */
+/* non-negative e4m3 values.  scales may be NULL.  The result holds bfloat16        */
+/* values, so a net built on it and switched to bfloat16 emulation is the           */
+/* reference of an engine that stores its weights this way.                         */
+void orc_quantize_rows_e4m3(const real *w, long rows, long cols, real *out, real *scales)
+{
+    double table[127];
+    int n = 0;
+    for (int code = 0; code < 127; ++code) {        /* code 127 (all ones) is NaN */
+        const int expo = code >> 3, mant = code & 7;
+        table[n++] = expo == 0 ? ldexp((double)mant, -9) : ldexp(1.0 + mant / 8.0, expo - 7);
+    }
+    for (long r = 0; r < rows; ++r) {
+        const real *row = w + r * cols;
+        double M = 0.0;
+        for (long i = 0; i < cols; ++i)
+            if (fabs((double)row[i]) > M) M = fabs((double)row[i]);
+        int k = 0;
+        if (M > 0.0) {
+            while (k < 100 && ldexp(M, -k) > 448.0) ++k;
+            while (k > -100 && ldexp(M, -(k - 1)) <= 448.0) --k;
+        }
+        for (long i = 0; i < cols; ++i) {
+            const double v = ldexp(fabs((double)row[i]), -k);
+            int best = 0;
+            for (int c = 1; c < 127; ++c) {
+                const double d = fabs(v - table[c]), db = fabs(v - table[best]);
+                if (d < db || (d == db && (c & 1) == 0)) best = c;
+            }
+            const double q = ldexp(table[best], k);
+            out[r * cols + i] = (real)(row[i] < 0 ? -q : q);
+        }
+        if (scales) scales[r] = (real)ldexp(1.0, k);
+    }
+}
+
 /* ------------------------------ table net -------------------------------- */
 /* x_row[0] carries the integer cell index (utterance * T + frame).  The      */
 /* prediction state is the number of labels consumed so far; g = (tokens      */

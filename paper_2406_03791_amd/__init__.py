@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     rnnt_engine_phase_timers,
     rnnt_engine_stats,
     rnnt_probe_e4m3_widening,
+    rnnt_quantize_rows_e4m3,
     rnnt_probe_exchange,
     rnnt_probe_mfma,
     rnnt_probe_stream,

@@ -23,6 +23,7 @@ EXPORTS = (
     "rnnt_label_looping_decode_noalloc",
     "rnnt_engine_phase_timers",
     "rnnt_probe_stream", "rnnt_probe_exchange", "rnnt_probe_mfma", "rnnt_probe_e4m3_widening",
+    "rnnt_quantize_rows_e4m3",
 )
 
 
@@ -112,7 +113,9 @@ def load_library():
         lib.rnnt_probe_stream.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         lib.rnnt_probe_exchange.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
         lib.rnnt_probe_mfma.argtypes = [C.c_int32, C.POINTER(C.c_double)]
-        lib.rnnt_probe_e4m3_widening.argtypes = [C.POINTER(C.c_uint16)]
+        lib.rnnt_probe_e4m3_widening.argtypes = [C.c_float, C.POINTER(C.c_uint16)]
+        lib.rnnt_quantize_rows_e4m3.argtypes = [C.POINTER(C.c_float), C.c_int64, C.c_int64,
+                                                C.POINTER(C.c_float), C.POINTER(C.c_float)]
         lib.rnnt_status_string.argtypes = [C.c_int]
         lib.rnnt_status_string.restype = C.c_char_p
         for name in EXPORTS:
@@ -249,12 +252,27 @@ def rnnt_probe_exchange(team_size: int, length: int, tagged: bool) -> float:
     return float(out.value)
 
 
-def rnnt_probe_e4m3_widening():
-    """[4][256] uint16 array: the bf16 code each e4m3 code becomes, per byte position."""
+def rnnt_probe_e4m3_widening(scale: float = 1.0):
+    """[4][256] uint16 array: the bf16 code each e4m3 code becomes under the scale operand,
+    per byte position."""
     import numpy as np
     out = np.zeros((4, 256), dtype=np.uint16)
-    _check(load_library().rnnt_probe_e4m3_widening(out.ctypes.data_as(C.POINTER(C.c_uint16))))
+    _check(load_library().rnnt_probe_e4m3_widening(C.c_float(scale), out.ctypes.data_as(C.POINTER(C.c_uint16))))
     return out
+
+
+def rnnt_quantize_rows_e4m3(w):
+    """(quantised copy, row scales) of a 2-D float32 numpy array: every row as e4m3 values
+    times a power of two (host-side helper of the library, no device work)."""
+    import numpy as np
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    assert w.ndim == 2
+    out = np.empty_like(w)
+    scales = np.empty(w.shape[0], dtype=np.float32)
+    fp = C.POINTER(C.c_float)
+    _check(load_library().rnnt_quantize_rows_e4m3(w.ctypes.data_as(fp), w.shape[0], w.shape[1],
+                                                  out.ctypes.data_as(fp), scales.ctypes.data_as(fp)))
+    return out, scales
 
 
 def rnnt_probe_mfma(shape: int) -> float:

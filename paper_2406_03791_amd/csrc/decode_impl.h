@@ -121,12 +121,15 @@ __device__ __forceinline__ float4 x_load4(const float *row, int k)        // k a
 }
 
 // two e4m3 codes (the low or the high half of `word`) as one word of two bf16, first code in
-// the low half; v_cvt_scalef32_pk_bf16_fp8 with scale 1
+// the low half; v_cvt_scalef32_pk_bf16_fp8.  The instruction multiplies by the power of two
+// that `scale` has as its exponent (its mantissa is ignored): with scale 1 every e4m3 value
+// comes out as the bf16 value it is, with the scale of a weight row as that value times the
+// row's power of two, still without rounding.
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 template <bool HIGH>
-__device__ __forceinline__ float e4m3x2_to_bf16x2(unsigned word)
+__device__ __forceinline__ float e4m3x2_to_bf16x2(unsigned word, float scale)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, HIGH));
+    return __builtin_bit_cast(float, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, scale, HIGH));
 }
 
 typedef short v4s __attribute__((ext_vector_type(4)));
@@ -272,11 +275,14 @@ __device__ __forceinline__ void stream_begin(WeightStream &ws, const StageDev &s
 //   bias         LDS, the rank's slice of the stage's bias vector (4 per group), or nullptr:
 //                the accumulators of a group's first K slice start from it, as the sum the
 //                oracle forms does
+//   scale        kWeightFp8Bf16Arith only: LDS, the power of two of each of the rank's weight
+//                rows (4 per group); a lane's weights all belong to one row
 template <int RG, int WT>
 __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n_tasks,
                                           WeightStream &ws, const float *x, int xstride,
                                           int x_inp_stride, int groups_per_inp, float *red,
-                                          bool red_aliases_x, const float *bias = nullptr)
+                                          bool red_aliases_x, const float *scale,
+                                          const float *bias = nullptr)
 {
     static_assert(kMaxSamples <= 64, "the samples of a joint step are set up by one wave");
     const int r4 = w.lane & 3;
@@ -298,6 +304,8 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         const float *xr = x + (g / groups_per_inp) * x_inp_stride + r4 * xstride + ks * sd.nsteps * (BF ? KPER / 2 : KPER);
         // lane r4 of a block accumulates output column r4 of the group for the block's four rows
         const float b0 = (bias && live && ks == 0) ? bias[g * 4 + r4] : 0.f;
+        float sc = 1.0f;
+        if (WT == kWeightFp8Bf16Arith && live) sc = scale[g * 4 + r4];
         v4f acc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){b0, b0, b0, b0};
@@ -331,12 +339,12 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
                                 // eight weights of this half as four words of two bf16 each
                                 float w0, w1, w2, w3;
                                 if (WT == kWeightFp8Bf16Arith) {
-                                    // one instruction widens two e4m3 codes to two bf16 (scale 1: every
-                                    // e4m3 value is a bf16 value, so nothing is rounded)
+                                    // one instruction widens two e4m3 codes to two bf16 and applies the
+                                    // row's power of two (nothing is rounded)
                                     const unsigned lo_word = __float_as_uint(h == 0 ? raw.x : raw.z);
                                     const unsigned hi_word = __float_as_uint(h == 0 ? raw.y : raw.w);
-                                    w0 = e4m3x2_to_bf16x2<false>(lo_word); w1 = e4m3x2_to_bf16x2<true>(lo_word);
-                                    w2 = e4m3x2_to_bf16x2<false>(hi_word); w3 = e4m3x2_to_bf16x2<true>(hi_word);
+                                    w0 = e4m3x2_to_bf16x2<false>(lo_word, sc); w1 = e4m3x2_to_bf16x2<true>(lo_word, sc);
+                                    w2 = e4m3x2_to_bf16x2<false>(hi_word, sc); w3 = e4m3x2_to_bf16x2<true>(hi_word, sc);
                                 } else {
                                     w0 = raw.x; w1 = raw.y; w2 = raw.z; w3 = raw.w;
                                 }
@@ -439,6 +447,9 @@ struct Lds {
     float *xz, *red, *c, *part, *q, *hc;
     float *tail;                      // this rank's tail column: weight row, then [waves][kMaxSamples] partial sums
     float *b_pred, *b_out, *b_lstm;   // this rank's slices of the bias vectors
+    // this rank's slices of the row scales (kWeightFp8Bf16Arith), indexed like a stage's groups:
+    // s_hh[(layer * units + u) * 4 + gate], s_ih likewise, s_pred and s_out by column
+    float *s_pred, *s_out, *s_hh, *s_ih;
 };
 
 // c state of this rank's units: [layer][sel][unit][row]
@@ -637,7 +648,7 @@ __device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, cons
     stream_begin(ws, p.st0, w, w.rank, p.L * nu * p.st0.nks);
     PROF_MARK(w, 0);
     run_stage<RG, WT>(p.st0, w, p.L * nu * p.st0.nks, ws, hc + (long long)selr * p.L * lay_stride, xs,
-                      (int)lay_stride, nu > 0 ? nu : 1, l.red, false);
+                      (int)lay_stride, nu > 0 ? nu : 1, l.red, false, l.s_hh);
     const int ng_all_p = (p.J + 3) / 4;
     const int gp0 = range_lo(w.rank, p.team_size, ng_all_p);
     const int ngp = range_hi(w.rank, p.team_size, ng_all_p) - gp0;
@@ -670,7 +681,7 @@ __device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, cons
         __syncthreads();
         PROF_MARK(w, 4);
         run_stage<RG, WT>(sd, w, nu * sd.nks, ws, hc + ((long long)(selr ^ 1) * p.L + (layer - 1)) * lay_stride, xs,
-                          0, 1 << 30, l.red, false);
+                          0, 1 << 30, l.red, false, l.s_ih + layer * nu * 4);
         if (layer + 1 < kMaxLayers && layer + 1 < p.L)
             stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
                          nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks);
@@ -693,7 +704,7 @@ __device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, cons
     __syncthreads();
     PROF_MARK(w, 8);
     run_stage<RG, WT>(p.spred, w, ngp * p.spred.nks, ws, hc + ((long long)(selr ^ 1) * p.L + (p.L - 1)) * lay_stride,
-                      xs, 0, 1 << 30, l.red, false);
+                      xs, 0, 1 << 30, l.red, false, l.s_pred);
     __syncthreads();
     PROF_MARK(w, 9);
     for (int e4 = w.tid; e4 < ngp * R * 4; e4 += kThreads) {
@@ -762,7 +773,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
             pre = *reinterpret_cast<const float4 *>(p.T0 + ((long long)c.last[r] * p.H + (u0 + u)) * 4);
     }
     run_stage<RG, WT>(p.st0, w, p.L * nu * p.st0.nks, ws, l.xz, p.xstride, inp_stride, nu > 0 ? nu : 1,
-                  l.red, false);
+                  l.red, false, l.s_hh);
     // the next stage's weights start moving while this one finishes and the team meets
     const int ng_all_p = (p.J + 3) / 4;
     const int gp0 = range_lo(w.rank, p.team_size, ng_all_p);
@@ -807,7 +818,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows<WT>(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
         __syncthreads();
         PROF_MARK(w, 4);
-        run_stage<RG, WT>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        run_stage<RG, WT>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false, l.s_ih + layer * nu * 4);
         if (layer + 1 < kMaxLayers && layer + 1 < p.L)
             stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
                          nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks);
@@ -835,7 +846,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows<WT>(p, w, l.xz, rows_pad, p.H, p.spred.kpad, p.L - 1, true);
         __syncthreads();
         PROF_MARK(w, 8);
-        run_stage<RG, WT>(p.spred, w, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false);
+        run_stage<RG, WT>(p.spred, w, ng * p.spred.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false, l.s_pred);
         __syncthreads();
         PROF_MARK(w, 9);
         for (int e = w.tid; e < ng * c.R; e += kThreads) {
@@ -1131,7 +1142,7 @@ __device__ __forceinline__ bool joint_step(const DecodeParams &p, const Wg &w_in
     // output bias goes into the accumulators of every group's first K slice
     const bool alias = p.sjoint.slots == 1;
     float *red = alias ? l.xz : l.red;
-    run_stage<RG, WT>(p.sjoint, w, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias, l.b_out);
+    run_stage<RG, WT>(p.sjoint, w, ng * p.sjoint.nks, ws, l.xz, p.xstride, 0, 1 << 30, red, alias, l.s_out, l.b_out);
     __syncthreads();
     PROF_MARK(w, 14);
     // Per sample, this rank's best token column and best duration column, in two steps through
@@ -1329,6 +1340,10 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     l.b_pred = dyn_lds + p.lds_bias;
     l.b_out = l.b_pred + 4 * p.gp_max;
     l.b_lstm = l.b_out + 4 * p.gj_max;
+    l.s_pred = dyn_lds + p.lds_scale;
+    l.s_out = l.s_pred + 4 * p.gp_max;
+    l.s_hh = l.s_out + 4 * p.gj_max;
+    l.s_ih = l.s_hh + 4 * p.L * p.nu_max;
 
     if (w.tid == 0) {
         // XCC_ID hardware register, bits [3:0]
@@ -1388,6 +1403,17 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         for (int i = w.tid; i < p.L * hnu * 4; i += kThreads) {
             const int layer = i / (hnu * 4), rem = i - layer * hnu * 4;
             l.b_lstm[(layer * p.nu_max) * 4 + rem] = p.bias_l[((long long)layer * p.H + hu0) * 4 + rem];
+        }
+        if (WT == kWeightFp8Bf16Arith) {
+            for (int i = w.tid; i < ngp * 4; i += kThreads)
+                l.s_pred[i] = (gp0 * 4 + i < p.J) ? p.sc_pred[gp0 * 4 + i] : 1.0f;
+            for (int i = w.tid; i < ngj * 4; i += kThreads)
+                l.s_out[i] = (gj0 * 4 + i < p.nout_m) ? p.sc_out[gj0 * 4 + i] : 1.0f;
+            for (int i = w.tid; i < p.L * hnu * 4; i += kThreads) {
+                const int layer = i / (hnu * 4), rem = i - layer * hnu * 4;
+                l.s_hh[i] = p.sc_hh[((long long)layer * p.H + hu0) * 4 + rem];
+                l.s_ih[i] = p.sc_ih[((long long)layer * p.H + hu0) * 4 + rem];
+            }
         }
     }
     // zero state: c of both selectors, committed h of this rank's units

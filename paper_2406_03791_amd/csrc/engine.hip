@@ -98,6 +98,7 @@ struct TeamConfig {
     Workspace ws;          // the buffers above plus the engine's P, abort flag and status word
     int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
     int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
+    int lds_scale = 0;     // row scales of e4m3-stored weights in the bfloat16 mode, laid out like the biases
     int q_in_lds = 0, qstride = 0;
     int fast_pred = 0, lds_hc = 0;
     int n_tail = 0;        // joint output columns computed outside the MFMA stage, one per rank from rank 0 on
@@ -127,6 +128,7 @@ struct rnnt_engine {
     std::vector<float> w_pred, w_out;
     // device: weights used as they are, derived tables, workspace
     DevBuf w_enc, b_enc, T0, bias_l, b_pred, b_out;
+    DevBuf sc_hh, sc_ih, sc_pred, sc_out;   // e4m3 storage in the bfloat16 mode: power-of-two scale of every weight row
     DevBuf P, abort_flag, status;
     TeamConfig frame_cfg;   // Algorithm 1
     TeamConfig label_cfg;   // label looping, RNN-T and TDT
@@ -142,9 +144,9 @@ struct rnnt_engine {
 namespace {
 
 int upload_stage(PackedStage &ps, int ts, const std::function<int(int)> &ngroups,
-                 const std::function<const float *(int, int, int)> &row_of)
+                 const std::function<const float *(int, int, int)> &row_of, bool row_scaled)
 {
-    std::vector<uint32_t> host = pack_stage(ps.plan, ts, ngroups, row_of);
+    std::vector<uint32_t> host = pack_stage(ps.plan, ts, ngroups, row_of, row_scaled);
     // the kernel's prefetch may run a few steps past the end of the last wave's run
     host.resize(host.size() + (size_t)kAheadSteps * 64 * 4, 0u);
     HIP_TRY(ps.w.alloc(host.size() * sizeof(uint32_t)));
@@ -254,6 +256,8 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         t.lds_c = take(L * 2 * nu_max * rows_max);
         t.lds_part = take(L * nu_max * rows_max * 4);
         t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
+        // row scales: projection, output, recurrent and input matrices of every layer
+        t.lds_scale = e->wt == kWeightFp8Bf16Arith ? take(4 * (gp_max + gj_max + 2 * L * nu_max)) : 0;
         // a tail column's weight row and its per-wave partial sums
         t.lds_tail = t.n_tail ? take(tail_k + kWaves * kMaxSamples) : 0;
         // room for a joint group's q rows as well (needed by joint groups, see below)
@@ -281,28 +285,29 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
 
     // weights
     int rc;
+    const bool scaled = e->wt == kWeightFp8Bf16Arith;
     rc = upload_stage(t.st0, ts, [&](int r) { return L * nu_of(r); },
                       [&](int r, int g, int j) -> const float * {
                           const int nu = nu_of(r);
                           const int layer = g / nu, u = range_lo(r, ts, H) + g % nu;
                           return e->w_hh[layer].data() + (size_t)(j * H + u) * H;
-                      });
+                      }, scaled);
     if (rc) return rc;
     for (int l = 1; l < L; ++l) {
         rc = upload_stage(t.stl[l], ts, nu_of, [&](int r, int g, int j) -> const float * {
             return e->w_ih[l].data() + (size_t)(j * H + range_lo(r, ts, H) + g) * H;
-        });
+        }, scaled);
         if (rc) return rc;
     }
     rc = upload_stage(t.spred, ts, gp_of, [&](int r, int g, int j) -> const float * {
         const int col = (range_lo(r, ts, gp_all) + g) * 4 + j;
         return col < J ? e->w_pred.data() + (size_t)col * H : nullptr;
-    });
+    }, scaled);
     if (rc) return rc;
     rc = upload_stage(t.sjoint, tj, gj_of, [&](int r, int g, int j) -> const float * {
         const int col = (range_lo(r, tj, gj_all) + g) * 4 + j;
         return col < t.nout_m ? e->w_out.data() + (size_t)col * J : nullptr;
-    });
+    }, scaled);
     if (rc) return rc;
     if (t.n_tail) {
         std::vector<float> rows((size_t)t.n_tail * tail_k, 0.f);
@@ -472,6 +477,9 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.search_steps = effective_search_steps(e, t, B);
     p.xstride = t.xstride; p.nu_max = t.nu_max; p.gj_max = t.gj_max;
     p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
+    p.lds_scale = t.lds_scale;
+    p.sc_hh = e->sc_hh.as<float>(); p.sc_ih = e->sc_ih.as<float>();
+    p.sc_pred = e->sc_pred.as<float>(); p.sc_out = e->sc_out.as<float>();
     p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
     p.lds_q = t.lds_q; p.q_in_lds = t.q_in_lds; p.qstride = t.qstride;
     p.fast_pred = t.fast_pred; p.lds_hc = t.lds_hc;
@@ -608,7 +616,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         for (int l = 0; l < d.L; ++l) ok = ok && is_bf16(e->w_hh[l]) && (l == 0 || is_bf16(e->w_ih[l]));
         if (!ok) return RNNT_ERR_SHAPE;
     }
-    if (e->wt == kWeightFp8 || e->wt == kWeightFp8Bf16Arith) {
+    if (e->wt == kWeightFp8) {
         auto is_e4m3 = [](const std::vector<float> &v) {
             uint8_t code;
             for (float x : v)
@@ -618,6 +626,45 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         bool ok = is_e4m3(e->w_pred) && is_e4m3(e->w_out);
         for (int l = 0; l < d.L; ++l) ok = ok && is_e4m3(e->w_hh[l]) && (l == 0 || is_e4m3(e->w_ih[l]));
         if (!ok) return RNNT_ERR_SHAPE;
+    }
+    if (e->wt == kWeightFp8Bf16Arith) {
+        // Every row is kept as e4m3 codes times a power of two of its own, which the kernel's
+        // widening instruction applies for free: lossless or refused, as above, but per row.
+        // scales[row] = 2^k with k = e4m3_row_exponent(row).
+        auto scan = [](const std::vector<float> &m, size_t rows, size_t cols, std::vector<float> &scales) {
+            scales.assign(rows, 1.0f);
+            uint8_t code;
+            for (size_t r = 0; r < rows; ++r) {
+                const float *row = m.data() + r * cols;
+                const int k = e4m3_row_exponent(row, (int)cols);
+                for (size_t i = 0; i < cols; ++i)
+                    if (!e4m3_bits(std::ldexp(row[i], -k), &code)) return false;
+                scales[r] = std::ldexp(1.0f, k);
+            }
+            return true;
+        };
+        std::vector<float> s_pred, s_out, rows_s;
+        std::vector<float> s_hh((size_t)d.L * H * 4, 1.0f), s_ih((size_t)d.L * H * 4, 1.0f);
+        bool ok = scan(e->w_pred, J, H, s_pred) && scan(e->w_out, (size_t)e->NOUT, J, s_out);
+        for (int l = 0; ok && l < d.L; ++l) {
+            // unit-major with the four gates together, as the biases of the layers are kept
+            ok = scan(e->w_hh[l], 4 * H, H, rows_s);
+            for (size_t u = 0; ok && u < H; ++u)
+                for (size_t g = 0; g < 4; ++g) s_hh[((size_t)l * H + u) * 4 + g] = rows_s[g * H + u];
+            if (l == 0 || !ok) continue;
+            ok = scan(e->w_ih[l], 4 * H, H, rows_s);
+            for (size_t u = 0; ok && u < H; ++u)
+                for (size_t g = 0; g < 4; ++g) s_ih[((size_t)l * H + u) * 4 + g] = rows_s[g * H + u];
+        }
+        if (!ok) return RNNT_ERR_SHAPE;
+        auto put = [&](DevBuf &dst, const std::vector<float> &v) -> int {
+            HIP_TRY(dst.alloc(v.size() * sizeof(float)));
+            HIP_TRY(hipMemcpy(dst.p, v.data(), v.size() * sizeof(float), hipMemcpyHostToDevice));
+            return RNNT_OK;
+        };
+        if ((rc = put(e->sc_pred, s_pred)) || (rc = put(e->sc_out, s_out)) || (rc = put(e->sc_hh, s_hh)) ||
+            (rc = put(e->sc_ih, s_ih)))
+            return rc;
     }
 
     auto clone = [&](DevBuf &dst, const float *src, size_t n) -> int {
@@ -648,6 +695,28 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     HIP_TRY(hipDeviceSynchronize());
     guard.e = nullptr;
     *out = e;
+    return RNNT_OK;
+}
+
+int rnnt_quantize_rows_e4m3(const float *w, int64_t rows, int64_t cols, float *out, float *scales_out)
+{
+    if (!w || !out) return RNNT_ERR_NULL;
+    if (rows < 0 || cols < 0 || cols > 0x7fffffff) return RNNT_ERR_SHAPE;
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *row = w + r * cols;
+        for (int64_t i = 0; i < cols; ++i)
+            if (!std::isfinite(row[i])) return RNNT_ERR_SHAPE;
+    }
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *row = w + r * cols;
+        float *dst = out + r * cols;
+        const int k = e4m3_row_exponent(row, (int)cols);
+        for (int64_t i = 0; i < cols; ++i) {
+            const float v = std::ldexp(row[i], -k);
+            dst[i] = std::ldexp(e4m3_round(std::fabs(v) > 448.0f ? std::copysign(448.0f, v) : v), k);
+        }
+        if (scales_out) scales_out[r] = std::ldexp(1.0f, k);
+    }
     return RNNT_OK;
 }
 

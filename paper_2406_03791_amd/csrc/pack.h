@@ -44,14 +44,47 @@ inline bool e4m3_bits(float v, uint8_t *code)
     return true;
 }
 
+// Exponent k of the power-of-two scale of a weight row stored as e4m3 codes with a row scale:
+// the smallest k with max|row| * 2^-k <= 448, the largest e4m3 value (0 for a row of zeros),
+// kept within +-100 so that the scale and every scaled weight stay normal floats.
+// With the smallest such k the row keeps the finest grid it can have without overflow, so a row
+// that is representable under any scale is representable under this one.
+inline int e4m3_row_exponent(const float *row, int n)
+{
+    float m = 0.f;
+    for (int i = 0; i < n; ++i) {
+        const float a = std::fabs(row[i]);
+        if (!(a <= m)) m = a;                                 // also picks up a NaN
+    }
+    if (!(m > 0.f) || !std::isfinite(m)) return 0;
+    int k = std::ilogb(m) - 8;                                // m * 2^-k in [256, 512)
+    if (std::ldexp(m, -k) > 448.0f) ++k;
+    return k < -100 ? -100 : (k > 100 ? 100 : k);
+}
+
+// Nearest e4m3 value (ties to the even code) of a finite float of magnitude at most 448.
+inline float e4m3_round(float v)
+{
+    const float a = std::fabs(v);
+    if (!(a > 0.f)) return v;
+    // spacing of the grid around a: 2^(e-3) in the binade of exponent e >= -6, 2^-9 below
+    int e = std::ilogb(a);
+    if (e < -6) e = -6;
+    const float step = std::ldexp(1.0f, e - 3);
+    const float r = std::nearbyint(a / step) * step;          // exact: a / step has at most 24 bits
+    return std::copysign(r, v);
+}
+
 // The packed image of one stage: 16 bytes per (rank, wave, slot, step, lane) holding 4 floats,
 // 8 bf16 codes or 16 e4m3 codes of consecutive K for the output column the lane owns.
 //   ngroups(rank)        output groups (of 4 columns) the rank owns
 //   row_of(rank, g, j)   the weight row (length plan.K) of column j of the rank's group g, or
 //                        nullptr for a column beyond the matrix (stays zero)
+//   row_scaled           e4m3 only: the codes are those of row * 2^-k, k = e4m3_row_exponent(row)
 inline std::vector<uint32_t> pack_stage(const StagePlan &pl, int ts,
                                         const std::function<int(int)> &ngroups,
-                                        const std::function<const float *(int, int, int)> &row_of)
+                                        const std::function<const float *(int, int, int)> &row_of,
+                                        bool row_scaled = false)
 {
     std::vector<uint32_t> host((size_t)ts * pl.rank_stride * 4, 0u);
     for (int rank = 0; rank < ts; ++rank) {
@@ -64,6 +97,7 @@ inline std::vector<uint32_t> pack_stage(const StagePlan &pl, int ts,
                     const int g = task / pl.nks, ks = task % pl.nks;
                     const float *row = row_of(rank, g, lane & 3);
                     if (!row) continue;
+                    const int kexp = (row_scaled && pl.kper == 16) ? e4m3_row_exponent(row, pl.K) : 0;
                     for (int step = 0; step < pl.nsteps; ++step) {
                         uint32_t *dst = host.data() +
                                         ((size_t)rank * pl.rank_stride +
@@ -80,7 +114,7 @@ inline std::vector<uint32_t> pack_stage(const StagePlan &pl, int ts,
                             for (int c = 0; c < 16; ++c)
                                 if (k0 + c < pl.K) {
                                     uint8_t code = 0;
-                                    e4m3_bits(row[k0 + c], &code);   // checked when the engine was created
+                                    e4m3_bits(std::ldexp(row[k0 + c], -kexp), &code);   // checked when the engine was created
                                     dst[c >> 2] |= (uint32_t)code << (8 * (c & 3));
                                 }
                         }

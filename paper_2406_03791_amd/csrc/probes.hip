@@ -165,14 +165,13 @@ struct Timer {
 
 // Every e4m3 code through the conversion the bfloat16 mode with e4m3-stored weights uses, in
 // each of the four byte positions of a word: out[pos * 256 + code] = the bf16 it becomes.
-__global__ void widen_kernel(uint16_t *out)
+__global__ void widen_kernel(float scale, uint16_t *out)
 {
-    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
     const unsigned code = threadIdx.x;
     for (int pos = 0; pos < 4; ++pos) {
         const unsigned word = code << (8 * pos);
-        const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, false));
-        const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, true));
+        const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, scale, false));
+        const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, scale, true));
         const unsigned two = pos < 2 ? lo : hi;
         out[pos * 256 + code] = (uint16_t)((pos & 1) ? (two >> 16) : (two & 0xffffu));
     }
@@ -267,12 +266,12 @@ int rnnt_probe_exchange(int32_t team_size, int32_t len, int32_t tagged, double *
     return RNNT_OK;
 }
 
-int rnnt_probe_e4m3_widening(uint16_t *bf16_out)
+int rnnt_probe_e4m3_widening(float scale, uint16_t *bf16_out)
 {
     if (!bf16_out) return RNNT_ERR_NULL;
     uint16_t *dev = nullptr;
     PROBE_TRY(hipMalloc(&dev, 4 * 256 * sizeof(uint16_t)));
-    hipLaunchKernelGGL(widen_kernel, dim3(1), dim3(256), 0, nullptr, dev);
+    hipLaunchKernelGGL(widen_kernel, dim3(1), dim3(256), 0, nullptr, scale, dev);
     PROBE_TRY(hipGetLastError());
     PROBE_TRY(hipMemcpy(bf16_out, dev, 4 * 256 * sizeof(uint16_t), hipMemcpyDeviceToHost));
     (void)hipFree(dev);

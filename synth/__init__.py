@@ -23,6 +23,7 @@ from .workloads import (
     round_to_e4m3,
     with_bf16_streamed_weights,
     with_fp8_streamed_weights,
+    with_streamed_weights,
 )
 
 from .adversarial import PATTERNS, emit_mask, make_adversarial, steer_frames
@@ -32,5 +33,5 @@ __all__ = [
     "Stream", "uniform", "normal", "randint",
     "ModelDims", "Model", "Workload", "CONFIGS",
     "make_model", "make_inputs", "make_workload", "param_count",
-    "round_to_bf16", "round_to_e4m3", "with_bf16_streamed_weights", "with_fp8_streamed_weights",
+    "round_to_bf16", "round_to_e4m3", "with_bf16_streamed_weights", "with_fp8_streamed_weights", "with_streamed_weights",
 ]

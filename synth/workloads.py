@@ -294,6 +294,13 @@ def _with_streamed_weights(model: Model, f) -> Model:
     return replace(model, w_ih=w_ih, w_hh=w_hh, w_pred=f(model.w_pred), w_out=f(model.w_out))
 
 
+def with_streamed_weights(model: Model, f) -> Model:
+    """A copy of `model` with f applied to each per-step streamed matrix (W_hh of every layer,
+    W_ih of the layers above the first, W_pred, W_out); f maps a 2-D float32 array to one of
+    the same shape (a quantiser under test, for instance)."""
+    return _with_streamed_weights(model, f)
+
+
 def with_fp8_streamed_weights(model: Model) -> Model:
     """Like with_bf16_streamed_weights, with e4m3 values: the model an 8-bit weight-only
     checkpoint (without scale factors) would give for the streamed matrices."""

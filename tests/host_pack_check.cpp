@@ -3,8 +3,9 @@
 // suite.  For a sweep of shapes and every weight storage it packs a matrix whose entry
 // (col, k) encodes its own position, then walks the packed image the way the kernel's lanes
 // do and checks that every (col, k) of the matrix turns up exactly once, at the place the
-// plan says, and that everything else is zero.  Also checks e4m3_bits on all 256 codes and
-// the split of the joint output stage into an MFMA part and tail columns.
+// plan says, and that everything else is zero.  Also checks e4m3_bits on all 256 codes, the
+// row-scaled e4m3 form (exponent rule, rounding, packed codes) and the split of the joint
+// output stage into an MFMA part and tail columns.
 #include <cstdio>
 #include <cstdlib>
 #include <vector>
@@ -115,6 +116,61 @@ int main()
         }
         const JointSplit even = plan_joint_stage(1024, 640, 8, kWeightF32, false);
         if (even.n_tail != 0 || even.nout_m != 1024) { std::printf("joint split of 1024 columns\n"); return 1; }
+    }
+    {   // row-scaled e4m3: exponent rule, rounding to the grid, and a packed image whose codes
+        // times the row's power of two give the weights back
+        const float one[3] = {448.0f, -1.0f, 0.25f}, two[2] = {449.0f, 3.0f}, three[2] = {0.f, 0.f};
+        const float four[2] = {224.0f, -7.0f}, five[1] = {1e-45f};
+        if (e4m3_row_exponent(one, 3) != 0 || e4m3_row_exponent(two, 2) != 1 || e4m3_row_exponent(three, 2) != 0 ||
+            e4m3_row_exponent(four, 2) != -1 || e4m3_row_exponent(five, 1) != -100) {
+            std::printf("row exponent\n");
+            return 1;
+        }
+        for (int code = 0; code < 127; ++code) {       // every value is a fixed point; midpoints go to the even code
+            const float v = e4m3_value(code);
+            if (e4m3_round(v) != v || e4m3_round(-v) != -v) { std::printf("round fixed point %d\n", code); return 1; }
+            if (code + 1 < 127) {
+                const float mid = 0.5f * (v + e4m3_value(code + 1));
+                const float want = e4m3_value((code & 1) ? code + 1 : code);
+                if (e4m3_round(mid) != want) { std::printf("round tie %d\n", code); return 1; }
+                if (e4m3_round(std::nextafter(mid, 0.f)) != v || e4m3_round(std::nextafter(mid, 1e9f)) != e4m3_value(code + 1)) {
+                    std::printf("round next to tie %d\n", code);
+                    return 1;
+                }
+            }
+        }
+        const int K = 100, N = 37, ts = 3, ng_all = (N + 3) / 4;
+        auto ng_of = [&](int r) { return range_hi(r, ts, ng_all) - range_lo(r, ts, ng_all); };
+        int gmax = 0;
+        for (int r = 0; r < ts; ++r) gmax = std::max(gmax, ng_of(r));
+        const StagePlan pl = make_stage_plan(K, gmax, kWeightFp8Bf16Arith);
+        std::vector<float> W((size_t)N * K);
+        for (int c = 0; c < N; ++c)             // e4m3 values times 2^(c - 20), one entry at the top of the range
+            for (int k = 0; k < K; ++k)
+                W[(size_t)c * K + k] = std::ldexp(k == c ? 448.0f : e4m3_value((c * 31 + k * 7) % 127), c - 20);
+        const std::vector<uint32_t> img = pack_stage(
+            pl, ts, ng_of, [&](int r, int g, int j) -> const float * {
+                const int col = (range_lo(r, ts, ng_all) + g) * 4 + j;
+                return col < N ? W.data() + (size_t)col * K : nullptr;
+            }, true);
+        for (int rank = 0; rank < ts; ++rank)
+            for (int wave = 0; wave < kWaves; ++wave)
+                for (int slot = 0; slot < pl.slots; ++slot)
+                    for (int step = 0; step < pl.nsteps; ++step)
+                        for (int lane = 0; lane < 64; ++lane) {
+                            const uint32_t *q = img.data() + ((size_t)rank * pl.rank_stride +
+                                ((size_t)(wave * pl.slots + slot) * pl.nsteps + step) * 64 + lane) * 4;
+                            const int task = slot * kBlocksPerWg + wave * 16 + (lane >> 2);
+                            const int g = task / pl.nks, ks = task % pl.nks;
+                            const int col = (range_lo(rank, ts, ng_all) + g) * 4 + (lane & 3);
+                            for (int c = 0; c < 16; ++c) {
+                                const int k = (ks * pl.nsteps + step) * 16 + c;
+                                if (!(task < ng_of(rank) * pl.nks && col < N && k < K)) continue;
+                                const float v = std::ldexp(e4m3_value((q[c >> 2] >> (8 * (c & 3))) & 0xff), col - 20);
+                                if (v != W[(size_t)col * K + k]) { std::printf("row-scaled value\n"); return 1; }
+                                ++checked;
+                            }
+                        }
     }
     std::printf("ok %ld\n", checked);
     return 0;

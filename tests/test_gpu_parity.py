@@ -709,23 +709,26 @@ def test_e4m3_codes_widen_to_their_bf16_values(pkg):
     """The conversion instruction of the bfloat16 mode with e4m3-stored weights, on every code in
     every byte position, against the format's definition (1 sign, 4 exponent bits with bias 7, 3
     mantissa bits, subnormals m * 2^-9, the two all-ones codes NaN): every finite e4m3 value
-    is a bf16 value, so the result must be that value exactly."""
-    got = pkg.rnnt_probe_e4m3_widening()
-    for code in range(256):
-        sign, expo, mant = code >> 7, (code >> 3) & 15, code & 7
-        if expo == 15 and mant == 7:
-            want = None                                   # NaN
-        elif expo == 0:
-            want = mant * 2.0 ** -9
-        else:
-            want = (1 + mant / 8.0) * 2.0 ** (expo - 7)
-        for pos in range(4):
-            bits = np.array([int(got[pos, code]) << 16], dtype=np.uint32).view(np.float32)[0]
-            if want is None:
-                assert np.isnan(bits), (code, pos)
+    is a bf16 value, so the result must be that value exactly, times the power of two of the
+    scale operand (a weight row's scale); the operand's mantissa is ignored."""
+    for scale, factor in [(1.0, 1.0), (2.0 ** -12, 2.0 ** -12), (32.0, 32.0), (2.0 ** -30, 2.0 ** -30),
+                          (1.5, 1.0), (0.75, 0.5)]:
+        got = pkg.rnnt_probe_e4m3_widening(scale)
+        for code in range(256):
+            sign, expo, mant = code >> 7, (code >> 3) & 15, code & 7
+            if expo == 15 and mant == 7:
+                want = None                                   # NaN
+            elif expo == 0:
+                want = mant * 2.0 ** -9 * factor
             else:
-                assert bits == np.float32(-want if sign else want), (code, pos, bits)
-                assert np.signbit(bits) == bool(sign), (code, pos)
+                want = (1 + mant / 8.0) * 2.0 ** (expo - 7) * factor
+            for pos in range(4):
+                bits = np.array([int(got[pos, code]) << 16], dtype=np.uint32).view(np.float32)[0]
+                if want is None:
+                    assert np.isnan(bits), (scale, code, pos)
+                else:
+                    assert bits == np.float32(-want if sign else want), (scale, code, pos, bits)
+                    assert np.signbit(bits) == bool(sign), (scale, code, pos)
 
 
 def test_bf16_arithmetic_with_e4m3_weights(pkg):
@@ -753,4 +756,51 @@ def test_bf16_arithmetic_with_e4m3_weights(pkg):
         eng.close()
     with pytest.raises(pkg.RnntError) as err:      # weights that are not e4m3 values
         pkg.Engine(w0.model, w0.B, w0.T, flags=flags)
+    assert err.value.code == -2
+
+
+def test_weight_only_8_bit_quantised_models(pkg):
+    """Any model, quantised row by row to e4m3 codes with a power-of-two scale (the library's
+    host-side quantiser; the oracle's own gives the same matrices), decoded in the bfloat16 mode
+    with those codes as the stored weights.  Reference: the oracle's bfloat16 emulation on the
+    quantised model, to the bar of the bfloat16 mode.  Rows are also given very different
+    magnitudes, so that the scales matter.  Logs how far the decode moves from the fp32 one."""
+    import dataclasses
+    flags = pkg.RNNT_FLAG_BF16_ARITHMETIC | pkg.RNNT_FLAG_FP8_WEIGHTS
+    for cfg, variants, kw, spread in [(1, ("frame", "label"), {}, False),
+                                      (3, ("frame", "label"), dict(B=12, T=120, len_lo=40, len_hi=120), True),
+                                      (4, ("tdt",), dict(B=12, T=120, len_lo=40, len_hi=120), True),
+                                      (3, ("label", "frame"), {}, False), (4, ("tdt",), {}, False),
+                                      (6, ("label",), dict(B=12, T=120, len_lo=40, len_hi=120), False)]:
+        w0 = synth.make_workload(cfg, pad="nan", **kw)
+        model = w0.model
+        if spread:
+            # output rows of W_pred scaled by powers of two between 2^-10 and 2^6, undone in
+            # the columns of W_out: the same function, rows of very different magnitudes
+            rng = np.random.default_rng(5)
+            f = np.ldexp(1.0, rng.integers(-10, 7, size=model.w_pred.shape[0])).astype(np.float32)
+            model = dataclasses.replace(model, w_pred=model.w_pred * f[:, None], b_pred=model.b_pred * f,
+                                        w_out=model.w_out / f[None, :])
+            model = dataclasses.replace(model, w_enc=model.w_enc * f[:, None], b_enc=model.b_enc * f)
+        m_lib = synth.with_streamed_weights(model, lambda a: pkg.rnnt_quantize_rows_e4m3(a)[0])
+        m_orc = synth.with_streamed_weights(model, lambda a: oracle.quantize_rows_e4m3(a)[0])
+        for a, b in [(m_lib.w_pred, m_orc.w_pred), (m_lib.w_out, m_orc.w_out)] + \
+                list(zip(m_lib.w_hh, m_orc.w_hh)) + list(zip(m_lib.w_ih, m_orc.w_ih)):
+            assert np.array_equal(a, b)
+        w = dataclasses.replace(w0, model=m_orc)
+        eng = pkg.Engine(m_lib, w.B, w.T, flags=flags)
+        ref32 = oracle.decode(oracle.LstmNet(model), w.enc_out, w.enc_len, w.max_symbols, "seq",
+                              n_threads=N_THREADS)
+        for variant in variants:
+            ref, got, st = check(pkg, w, variant, f"cfg{cfg}/quantised to e4m3 rows", engine=eng,
+                                 bf16=True, logp=(variant == "label"))
+            assert st["near_tie_rows"] <= max(1, w.B // 3)
+            moved = sum(int(not np.array_equal(ref.tokens[b], ref32.tokens[b])) for b in range(w.B))
+            log(f"  rows whose tokens differ from the fp32 decode of the unquantised model: {moved}/{w.B}")
+        eng.close()
+    # a row that no power of two brings onto the e4m3 grid is refused
+    bad = dataclasses.replace(m_lib, w_pred=m_lib.w_pred.copy())
+    bad.w_pred[3, 5] = np.float32(bad.w_pred[3, 5]) * np.float32(1.01)
+    with pytest.raises(pkg.RnntError) as err:
+        pkg.Engine(bad, w.B, w.T, flags=flags)
     assert err.value.code == -2
