@@ -138,7 +138,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--variant", default="frame", choices=["frame", "label", "tdt"])
     ap.add_argument("--batch", type=int, default=32)
-    ap.add_argument("--storage", default="fp32", choices=["fp32", "bf16", "fp8"],
+    ap.add_argument("--storage", default="fp32", choices=["fp32", "bf16", "fp8", "fp4"],
                     help="storage of the streamed weights for the timed decoder; bf16 / fp8 decode "
                          "another model (the one with weights rounded to that format), so their "
                          "figures stand beside the fp32 headline, never for it")
@@ -270,6 +270,12 @@ def main() -> int:
             flags = pkg.RNNT_FLAG_FP8_WEIGHTS
             w = dataclasses.replace(w, model=synth.with_streamed_weights(
                 w.model, lambda a: pkg.rnnt_quantize_rows_e4m3(a)[0]))
+        elif storage == "fp4":
+            # weight-only 4-bit quantisation: e2m1 codes with a power-of-two scale per 128 weights
+            import dataclasses
+            flags = pkg.RNNT_FLAG_FP4_WEIGHTS
+            w = dataclasses.replace(w, model=synth.with_streamed_weights(
+                w.model, lambda a: pkg.rnnt_quantize_blocks_e2m1(a)[0]))
         elif storage != "fp32":
             # the model a bf16 / 8-bit e4m3 checkpoint would give for the streamed matrices, kept
             # in that format by the engine (lossless); fp32 arithmetic, checked against the
@@ -315,6 +321,9 @@ def main() -> int:
         eng.close()
         return res
 
+    if args.storage == "fp4" and args.arithmetic != "bf16":
+        print("bench.py: --storage fp4 exists for --arithmetic bf16 only", file=sys.stderr)
+        return 2
     if args.arithmetic == "bf16" and args.storage == "bf16":
         print("bench.py: --arithmetic bf16 stores its weights as bf16 already; leave --storage "
               "at fp32, or give fp8 for the weight-only 8-bit form of the mode", file=sys.stderr)
@@ -325,7 +334,7 @@ def main() -> int:
     n_frames = w.frames
     ms_per_step = 1e3 * r["wall"] / r["steps"]
     value = n_frames * r["steps"] / r["wall"]
-    wb = {"fp32": 4, "bf16": 2, "fp8": 1}[args.storage]
+    wb = {"fp32": 4, "bf16": 2, "fp8": 1, "fp4": 0.5}[args.storage]
     if args.arithmetic == "bf16" and args.storage == "fp32":
         wb = 2
     lit_bytes, lit_pred, lit_joint, _ = algorithmic_bytes(
@@ -425,6 +434,11 @@ def main() -> int:
         line["variants"][v + "_bf16_arithmetic_e4m3_weights"] = {
             "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
             "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
+        # and quantised to e2m1 codes with a scale per 128 weights
+        rv = run_variant(v, max(3, args.steps // 2), 2, arithmetic="bf16", storage="fp4")
+        line["variants"][v + "_bf16_arithmetic_e2m1_weights"] = {
+            "frames_per_s": rv["w"].frames * rv["steps"] / rv["wall"], "decode_ms": rv["dec_ms"],
+            "tokens": int(rv["tok_len"].sum()), "status": rv["status"]}
     if args.all_variants:
         # label looping that also returns the log-probability of every label (fused log-sum-exp)
         rv = run_variant("label", max(3, args.steps // 2), 2, logp=True)
@@ -442,7 +456,7 @@ def main() -> int:
         # from the fp32 oracle's on the same model
         import oracle as _orc
         for v in ("frame", "label", "tdt"):
-            for storage in ("fp32", "fp8"):
+            for storage in ("fp32", "fp8", "fp4"):
                 rv = run_variant(v, max(3, args.steps // 2), 2, arithmetic="bf16", storage=storage)
                 wv = rv["w"]
                 nthr = min(16, os.cpu_count() or 1)
@@ -452,9 +466,9 @@ def main() -> int:
                                   "seq", n_threads=nthr)
                 same = sum(int(np.array_equal(emul.tokens[b], rv["tokens"][b])) for b in range(wv.B))
                 moved = sum(int(not np.array_equal(f32.tokens[b], rv["tokens"][b])) for b in range(wv.B))
-                name = v + "_bf16_arithmetic" + ("_e4m3_weights" if storage == "fp8" else "")
+                name = v + "_bf16_arithmetic" + {"fp32": "", "fp8": "_e4m3_weights", "fp4": "_e2m1_weights"}[storage]
                 extra = {}
-                if storage == "fp8":
+                if storage != "fp32":
                     # against the fp32 decode of the model before it was quantised
                     wo = rv["w_orig"]
                     f32o = _orc.decode(_orc.LstmNet(wo.model), wo.enc_out, wo.enc_len, wo.max_symbols,

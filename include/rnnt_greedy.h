@@ -182,6 +182,33 @@ typedef struct rnnt_stats {
 int rnnt_quantize_rows_e4m3(const float *w, int64_t rows, int64_t cols, float *out, float *scales_out);
 
 /*
+ * rnnt_engine_create flag, only together with RNNT_FLAG_BF16_ARITHMETIC (alone,
+ * or with another format flag, RNNT_ERR_SHAPE): the weight-only 4-bit form of
+ * the bfloat16 mode.  The streamed weights are kept as codes of the OCP e2m1
+ * format (1 sign, 2 exponent, 1 mantissa bit: magnitudes 0, 0.5, 1, 1.5, 2, 3,
+ * 4, 6) with one power-of-two scale per block of RNNT_FP4_BLOCK consecutive
+ * weights of a row (the last block of a row may be shorter).  The engine finds
+ * the scales itself -- 2^k with the smallest k for which the block's largest
+ * magnitude times 2^-k is at most 6 -- and every weight of the block times 2^-k
+ * must be an e2m1 value, else RNNT_ERR_SHAPE; rnnt_quantize_blocks_e2m1 maps
+ * any matrix to the nearest such one.  Codes are widened to bf16 and scaled in
+ * one instruction, without rounding; the arithmetic is the bfloat16 mode's on
+ * that model.
+ */
+#define RNNT_FLAG_FP4_WEIGHTS 32
+#define RNNT_FP4_BLOCK 128
+
+/*
+ * Weight-only 4-bit quantisation of a matrix for RNNT_FLAG_FP4_WEIGHTS (host
+ * side, as rnnt_quantize_rows_e4m3): every block of RNNT_FP4_BLOCK consecutive
+ * weights of a row becomes 2^k times the e2m1 values nearest to the weights
+ * times 2^-k (ties to the even code), k the smallest integer with
+ * max|block| * 2^-k <= 6 (0 for zeros; kept within +-100).  scales_out, if not
+ * NULL, receives rows * ceil(cols / RNNT_FP4_BLOCK) values 2^k, row-major.
+ */
+int rnnt_quantize_blocks_e2m1(const float *w, int64_t rows, int64_t cols, float *out, float *scales_out);
+
+/*
  * rnnt_engine_create flag: launch the decode kernel with an ordinary launch
  * instead of a cooperative one.  The kernel's teams synchronise among
  * themselves, which needs all work-groups resident at once; the cooperative
@@ -217,7 +244,8 @@ int rnnt_quantize_rows_e4m3(const float *w, int64_t rows, int64_t cols, float *o
  * Copies and repacks the weights on the current device, allocates the
  * workspace (projected frames [max_B, max_T, J], state, exchange buffers).
  * flags: 0 or one of RNNT_FLAG_BF16_WEIGHTS / RNNT_FLAG_FP8_WEIGHTS /
- * RNNT_FLAG_BF16_ARITHMETIC (or the last two together), optionally with
+ * RNNT_FLAG_BF16_ARITHMETIC (or the last with RNNT_FLAG_FP8_WEIGHTS or
+ * RNNT_FLAG_FP4_WEIGHTS), optionally with
  * RNNT_FLAG_PLAIN_LAUNCH and RNNT_FLAG_MULTI_BLANK; other bits are
  * RNNT_ERR_SHAPE.
  * Limits of this implementation, checked here before anything is allocated
@@ -425,9 +453,13 @@ int rnnt_engine_phase_timers(rnnt_engine *eng, int32_t team, double *us_out, int
  *                        `scale` (the decode kernel passes a weight row's
  *                        power of two): bf16_out is a HOST array of 4 * 256
  *                        entries, [byte position in a word][code].
+ *   rnnt_probe_e2m1_widening  the same for the 4-bit form: bf16_out is a HOST
+ *                        array of 4 * 256 * 2 entries, [byte position][byte
+ *                        value][code in the low, then the high nibble].
  * Return RNNT_OK or an RNNT_ERR_* code.
  */
 int rnnt_probe_e4m3_widening(float scale, uint16_t *bf16_out);
+int rnnt_probe_e2m1_widening(float scale, uint16_t *bf16_out);
 int rnnt_probe_stream(int32_t from_l2, double *gbytes_per_s_out, double *per_cu_out);
 int rnnt_probe_exchange(int32_t team_size, int32_t len, int32_t tagged, double *us_per_exchange_out);
 int rnnt_probe_mfma(int32_t shape, double *tflops_out);

@@ -41,6 +41,8 @@ def _lib(real: str):
         lib.orc_round_bf16.restype = C.c_float if real == "float" else C.c_double
         lib.orc_quantize_rows_e4m3.argtypes = [C.c_void_p, C.c_long, C.c_long, C.c_void_p, C.c_void_p]
         lib.orc_quantize_rows_e4m3.restype = None
+        lib.orc_quantize_blocks_e2m1.argtypes = [C.c_void_p, C.c_long, C.c_long, C.c_long, C.c_void_p, C.c_void_p]
+        lib.orc_quantize_blocks_e2m1.restype = None
         _LIBS[real] = lib
     return _LIBS[real]
 
@@ -322,4 +324,18 @@ def quantize_rows_e4m3(w: np.ndarray, real: str = "float"):
     scales = np.empty(w.shape[0], dtype=dt)
     _lib(real).orc_quantize_rows_e4m3(w.ctypes.data, w.shape[0], w.shape[1], out.ctypes.data,
                                       scales.ctypes.data)
+    return out, scales
+
+
+def quantize_blocks_e2m1(w: np.ndarray, block: int = 128, real: str = "float"):
+    """(quantised copy, block scales [rows, ceil(cols / block)]) of a 2-D matrix: every block
+    of `block` consecutive weights of a row as e2m1 values times a power of two
+    (orc_quantize_blocks_e2m1)."""
+    dt = _np_real(real)
+    w = np.ascontiguousarray(w, dtype=dt)
+    assert w.ndim == 2
+    out = np.empty_like(w)
+    scales = np.empty((w.shape[0], (w.shape[1] + block - 1) // block), dtype=dt)
+    _lib(real).orc_quantize_blocks_e2m1(w.ctypes.data, w.shape[0], w.shape[1], block, out.ctypes.data,
+                                        scales.ctypes.data)
     return out, scales

@@ -330,6 +330,42 @@ void orc_quantize_rows_e4m3(const real *w, long rows, long cols, real *out, real
     }
 }
 
+/* Weight-only 4-bit quantisation: the same with the 4-bit format OCP e2m1 (1      */
+/* sign bit, 2 exponent bits with bias 1, 1 mantissa bit: magnitudes 0, 0.5, 1,    */
+/* 1.5, 2, 3, 4, 6 for the codes 0..7) and one power-of-two scale per block of     */
+/* `block` consecutive weights of a row (the last block of a row may be shorter):  */
+/* k is the smallest integer with max|block| * 2^-k <= 6.  scales, if not NULL,    */
+/* is [rows][ceil(cols / block)].                                                  */
+void orc_quantize_blocks_e2m1(const real *w, long rows, long cols, long block, real *out,
+                              real *scales)
+{
+    static const double table[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+    const long nb = (cols + block - 1) / block;
+    for (long r = 0; r < rows; ++r)
+        for (long b = 0; b < nb; ++b) {
+            const long lo = b * block, hi = lo + block < cols ? lo + block : cols;
+            double M = 0.0;
+            for (long i = lo; i < hi; ++i)
+                if (fabs((double)w[r * cols + i]) > M) M = fabs((double)w[r * cols + i]);
+            int k = 0;
+            if (M > 0.0) {
+                while (k < 100 && ldexp(M, -k) > 6.0) ++k;
+                while (k > -100 && ldexp(M, -(k - 1)) <= 6.0) --k;
+            }
+            for (long i = lo; i < hi; ++i) {
+                const double v = ldexp(fabs((double)w[r * cols + i]), -k);
+                int best = 0;
+                for (int c = 1; c < 8; ++c) {
+                    const double d = fabs(v - table[c]), db = fabs(v - table[best]);
+                    if (d < db || (d == db && (c & 1) == 0)) best = c;
+                }
+                const double q = ldexp(table[best], k);
+                out[r * cols + i] = (real)(w[r * cols + i] < 0 ? -q : q);
+            }
+            if (scales) scales[r * nb + b] = (real)ldexp(1.0, k);
+        }
+}
+
 /* ------------------------------ table net -------------------------------- */
 /* x_row[0] carries the integer cell index (utterance * T + frame).  The      */
 /* prediction state is the number of labels consumed so far; g = (tokens      */

@@ -26,6 +26,10 @@ from .binding import (  # noqa: F401
     rnnt_engine_stats,
     rnnt_probe_e4m3_widening,
     rnnt_quantize_rows_e4m3,
+    rnnt_quantize_blocks_e2m1,
+    rnnt_probe_e2m1_widening,
+    RNNT_FLAG_FP4_WEIGHTS,
+    RNNT_FP4_BLOCK,
     rnnt_probe_exchange,
     rnnt_probe_mfma,
     rnnt_probe_stream,

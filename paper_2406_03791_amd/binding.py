@@ -23,7 +23,7 @@ EXPORTS = (
     "rnnt_label_looping_decode_noalloc",
     "rnnt_engine_phase_timers",
     "rnnt_probe_stream", "rnnt_probe_exchange", "rnnt_probe_mfma", "rnnt_probe_e4m3_widening",
-    "rnnt_quantize_rows_e4m3",
+    "rnnt_quantize_rows_e4m3", "rnnt_quantize_blocks_e2m1", "rnnt_probe_e2m1_widening",
 )
 
 
@@ -32,6 +32,8 @@ RNNT_FLAG_FP8_WEIGHTS = 2
 RNNT_FLAG_PLAIN_LAUNCH = 4
 RNNT_FLAG_BF16_ARITHMETIC = 8
 RNNT_FLAG_MULTI_BLANK = 16
+RNNT_FLAG_FP4_WEIGHTS = 32
+RNNT_FP4_BLOCK = 128
 
 
 class RnntError(RuntimeError):
@@ -114,8 +116,10 @@ def load_library():
         lib.rnnt_probe_exchange.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
         lib.rnnt_probe_mfma.argtypes = [C.c_int32, C.POINTER(C.c_double)]
         lib.rnnt_probe_e4m3_widening.argtypes = [C.c_float, C.POINTER(C.c_uint16)]
-        lib.rnnt_quantize_rows_e4m3.argtypes = [C.POINTER(C.c_float), C.c_int64, C.c_int64,
-                                                C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        for name in ("rnnt_quantize_rows_e4m3", "rnnt_quantize_blocks_e2m1"):
+            getattr(lib, name).argtypes = [C.POINTER(C.c_float), C.c_int64, C.c_int64,
+                                           C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        lib.rnnt_probe_e2m1_widening.argtypes = [C.c_float, C.POINTER(C.c_uint16)]
         lib.rnnt_status_string.argtypes = [C.c_int]
         lib.rnnt_status_string.restype = C.c_char_p
         for name in EXPORTS:
@@ -273,6 +277,29 @@ def rnnt_quantize_rows_e4m3(w):
     _check(load_library().rnnt_quantize_rows_e4m3(w.ctypes.data_as(fp), w.shape[0], w.shape[1],
                                                   out.ctypes.data_as(fp), scales.ctypes.data_as(fp)))
     return out, scales
+
+
+def rnnt_quantize_blocks_e2m1(w):
+    """(quantised copy, block scales [rows, ceil(cols / 128)]) of a 2-D float32 numpy array:
+    every block of 128 consecutive weights of a row as e2m1 values times a power of two."""
+    import numpy as np
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    assert w.ndim == 2
+    out = np.empty_like(w)
+    scales = np.empty((w.shape[0], (w.shape[1] + RNNT_FP4_BLOCK - 1) // RNNT_FP4_BLOCK), dtype=np.float32)
+    fp = C.POINTER(C.c_float)
+    _check(load_library().rnnt_quantize_blocks_e2m1(w.ctypes.data_as(fp), w.shape[0], w.shape[1],
+                                                    out.ctypes.data_as(fp), scales.ctypes.data_as(fp)))
+    return out, scales
+
+
+def rnnt_probe_e2m1_widening(scale: float = 1.0):
+    """[4][256][2] uint16 array: the two bf16 codes a byte of two e2m1 codes becomes under the
+    scale operand, per byte position (low nibble first)."""
+    import numpy as np
+    out = np.zeros((4, 256, 2), dtype=np.uint16)
+    _check(load_library().rnnt_probe_e2m1_widening(C.c_float(scale), out.ctypes.data_as(C.POINTER(C.c_uint16))))
+    return out
 
 
 def rnnt_probe_mfma(shape: int) -> float:

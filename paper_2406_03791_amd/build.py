@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip", "probes.hip"]
 # the decode kernel is instantiated in one unit per (loop nest, row groups, weight storage),
 # all compiled from decode_inst.hip, so that the instances build in parallel
-INSTANCES = [(nest, rg, wt) for wt in ("f32", "bf16", "fp8", "bf16a", "fp8a") for nest in ("f", "l")
+INSTANCES = [(nest, rg, wt) for wt in ("f32", "bf16", "fp8", "bf16a", "fp8a", "fp4a") for nest in ("f", "l")
              for rg in (1, 2, 4)]
 LIB = os.path.join(HERE, "librnnt_greedy.so")
 OBJ_DIR = os.path.join(HERE, "_build")

@@ -13,6 +13,7 @@ namespace rnnt {
     RNNT_DECLARE_LAUNCH(launch_decode_l2_##wt); RNNT_DECLARE_LAUNCH(launch_decode_l4_##wt)
 RNNT_DECLARE_NEST(f32); RNNT_DECLARE_NEST(bf16); RNNT_DECLARE_NEST(fp8); RNNT_DECLARE_NEST(bf16a);
 RNNT_DECLARE_NEST(fp8a);
+RNNT_DECLARE_NEST(fp4a);
 #undef RNNT_DECLARE_NEST
 #undef RNNT_DECLARE_LAUNCH
 
@@ -73,7 +74,9 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
         {{launch_decode_f1_bf16a, launch_decode_f2_bf16a, launch_decode_f4_bf16a},
          {launch_decode_l1_bf16a, launch_decode_l2_bf16a, launch_decode_l4_bf16a}},
         {{launch_decode_f1_fp8a, launch_decode_f2_fp8a, launch_decode_f4_fp8a},
-         {launch_decode_l1_fp8a, launch_decode_l2_fp8a, launch_decode_l4_fp8a}}};
+         {launch_decode_l1_fp8a, launch_decode_l2_fp8a, launch_decode_l4_fp8a}},
+        {{launch_decode_f1_fp4a, launch_decode_f2_fp4a, launch_decode_f4_fp4a},
+         {launch_decode_l1_fp4a, launch_decode_l2_fp4a, launch_decode_l4_fp4a}}};
     if (p.wt < 0 || p.wt >= kWeightTypes) return hipErrorInvalidValue;
     return table[p.wt][p.variant == kFrameLooping ? 0 : 1][rgi](p, rgj, stream);
 }

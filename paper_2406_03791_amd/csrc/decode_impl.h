@@ -132,6 +132,20 @@ __device__ __forceinline__ float e4m3x2_to_bf16x2(unsigned word, float scale)
     return __builtin_bit_cast(float, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, scale, HIGH));
 }
 
+// Two e2m1 codes (byte BYTE of `word`, low nibble first) as two bf16 in one 32-bit register,
+// times the power of two of `scale`: v_cvt_scalef32_pk_bf16_fp4.
+template <int BYTE>
+__device__ __forceinline__ float e2m1x2_to_bf16x2(unsigned word, float scale)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(word, scale, BYTE));
+}
+
+// Exponent byte of a power-of-two scale (all the widening instructions use of it).
+__device__ __forceinline__ unsigned char scale_byte(float scale)
+{
+    return (unsigned char)((__float_as_uint(scale) >> 23) & 0xffu);
+}
+
 typedef short v4s __attribute__((ext_vector_type(4)));
 // four bf16 values held in two 32-bit registers, as the operand type of the bf16 MFMA
 __device__ __forceinline__ v4s bf16x4(float lo, float hi)
@@ -275,13 +289,15 @@ __device__ __forceinline__ void stream_begin(WeightStream &ws, const StageDev &s
 //   bias         LDS, the rank's slice of the stage's bias vector (4 per group), or nullptr:
 //                the accumulators of a group's first K slice start from it, as the sum the
 //                oracle forms does
-//   scale        kWeightFp8Bf16Arith only: LDS, the power of two of each of the rank's weight
-//                rows (4 per group); a lane's weights all belong to one row
+//   scale        kWeightFp8Bf16Arith: LDS, the power of two of each of the rank's weight rows
+//                (4 per group), kept as the exponent byte of that float; a lane's weights all
+//                belong to one row.  kWeightFp4Bf16Arith: [row][block], one per kScaleBlock K
+//                values of the padded row, which is one batch of a lane's loads
 template <int RG, int WT>
 __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n_tasks,
                                           WeightStream &ws, const float *x, int xstride,
                                           int x_inp_stride, int groups_per_inp, float *red,
-                                          bool red_aliases_x, const float *scale,
+                                          bool red_aliases_x, const unsigned char *scale,
                                           const float *bias = nullptr)
 {
     static_assert(kMaxSamples <= 64, "the samples of a joint step are set up by one wave");
@@ -294,7 +310,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         const bool live = task < n_tasks;
         const int g = live ? task / sd.nks : 0;
         const int ks = live ? task - g * sd.nks : 0;
-        constexpr int KPER = (WT == kWeightFp8 || WT == kWeightFp8Bf16Arith) ? 16 : ((WT == kWeightBf16 || WT == kWeightBf16Arith) ? 8 : 4);
+        constexpr int KPER = k_per_load(WT);
         // bfloat16 mode: the activation rows hold bf16, 16 bytes of a row match the 16 bytes (eight
         // weights) of a load, and one load feeds two 4x4x4 bf16 MFMAs; otherwise a load is used
         // in part-steps of four K values on the fp32 4x4x1 MFMA
@@ -305,7 +321,11 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
         // lane r4 of a block accumulates output column r4 of the group for the block's four rows
         const float b0 = (bias && live && ks == 0) ? bias[g * 4 + r4] : 0.f;
         float sc = 1.0f;
-        if (WT == kWeightFp8Bf16Arith && live) sc = scale[g * 4 + r4];
+        if (WT == kWeightFp8Bf16Arith && live) sc = __uint_as_float((unsigned)scale[g * 4 + r4] << 23);
+        // 4-bit codes: this task's run of block scales
+        const unsigned char *scp = scale;
+        if (WT == kWeightFp4Bf16Arith)
+            scp = scale + (g * 4 + r4) * (sd.nks * (sd.nsteps / kStepUnroll)) + ks * (sd.nsteps / kStepUnroll);
         v4f acc[RG];
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) acc[rg] = (v4f){b0, b0, b0, b0};
@@ -324,6 +344,7 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
             for (int a = 0; a < kAhead; ++a) {
                 const int i = i0 + a * kStepUnroll;
                 if (i < sd.nsteps) {
+                    if (WT == kWeightFp4Bf16Arith) sc = live ? __uint_as_float((unsigned)scp[i / kStepUnroll] << 23) : 1.0f;
 #pragma unroll
                     for (int u = 0; u < kStepUnroll; ++u) {
                         const float4 raw = ws.q[a][u];
@@ -345,6 +366,12 @@ __device__ __forceinline__ void run_stage(const StageDev &sd, const Wg &w, int n
                                     const unsigned hi_word = __float_as_uint(h == 0 ? raw.y : raw.w);
                                     w0 = e4m3x2_to_bf16x2<false>(lo_word, sc); w1 = e4m3x2_to_bf16x2<true>(lo_word, sc);
                                     w2 = e4m3x2_to_bf16x2<false>(hi_word, sc); w3 = e4m3x2_to_bf16x2<true>(hi_word, sc);
+                                } else if (WT == kWeightFp4Bf16Arith) {
+                                    // a word holds the eight codes of this half; one instruction widens
+                                    // the two of a byte and applies the block's power of two
+                                    const unsigned word = __float_as_uint(h == 0 ? raw.x : (h == 1 ? raw.y : (h == 2 ? raw.z : raw.w)));
+                                    w0 = e2m1x2_to_bf16x2<0>(word, sc); w1 = e2m1x2_to_bf16x2<1>(word, sc);
+                                    w2 = e2m1x2_to_bf16x2<2>(word, sc); w3 = e2m1x2_to_bf16x2<3>(word, sc);
                                 } else {
                                     w0 = raw.x; w1 = raw.y; w2 = raw.z; w3 = raw.w;
                                 }
@@ -447,9 +474,11 @@ struct Lds {
     float *xz, *red, *c, *part, *q, *hc;
     float *tail;                      // this rank's tail column: weight row, then [waves][kMaxSamples] partial sums
     float *b_pred, *b_out, *b_lstm;   // this rank's slices of the bias vectors
-    // this rank's slices of the row scales (kWeightFp8Bf16Arith), indexed like a stage's groups:
-    // s_hh[(layer * units + u) * 4 + gate], s_ih likewise, s_pred and s_out by column
-    float *s_pred, *s_out, *s_hh, *s_ih;
+    // this rank's slices of the weight scales (e4m3 and e2m1 storage), indexed like a stage's
+    // groups, [row][scale block of the stage's padded K]: rows of s_hh are (layer * units + u) * 4
+    // + gate, s_ih likewise (a layer's table starts at layer * units * 4 * sc_nb_in), s_pred and
+    // s_out by column
+    unsigned char *s_pred, *s_out, *s_hh, *s_ih;   // exponent bytes of the power-of-two scales
 };
 
 // c state of this rank's units: [layer][sel][unit][row]
@@ -681,7 +710,7 @@ __device__ __forceinline__ bool prediction_step_fast(const DecodeParams &p, cons
         __syncthreads();
         PROF_MARK(w, 4);
         run_stage<RG, WT>(sd, w, nu * sd.nks, ws, hc + ((long long)(selr ^ 1) * p.L + (layer - 1)) * lay_stride, xs,
-                          0, 1 << 30, l.red, false, l.s_ih + layer * nu * 4);
+                          0, 1 << 30, l.red, false, l.s_ih + layer * nu * 4 * p.sc_nb_in);
         if (layer + 1 < kMaxLayers && layer + 1 < p.L)
             stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
                          nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks);
@@ -818,7 +847,7 @@ __device__ __forceinline__ bool prediction_step(const DecodeParams &p, const Wg 
         fill_rows<WT>(p, w, l.xz, rows_pad, p.H, sd.kpad, layer - 1, true);
         __syncthreads();
         PROF_MARK(w, 4);
-        run_stage<RG, WT>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false, l.s_ih + layer * nu * 4);
+        run_stage<RG, WT>(sd, w, nu * sd.nks, ws, l.xz, p.xstride, 0, 1 << 30, l.red, false, l.s_ih + layer * nu * 4 * p.sc_nb_in);
         if (layer + 1 < kMaxLayers && layer + 1 < p.L)
             stream_begin(ws, p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer], w, w.rank,
                          nu * p.stl[layer + 1 < kMaxLayers ? layer + 1 : layer].nks);
@@ -1340,10 +1369,10 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     l.b_pred = dyn_lds + p.lds_bias;
     l.b_out = l.b_pred + 4 * p.gp_max;
     l.b_lstm = l.b_out + 4 * p.gj_max;
-    l.s_pred = dyn_lds + p.lds_scale;
-    l.s_out = l.s_pred + 4 * p.gp_max;
-    l.s_hh = l.s_out + 4 * p.gj_max;
-    l.s_ih = l.s_hh + 4 * p.L * p.nu_max;
+    l.s_pred = reinterpret_cast<unsigned char *>(dyn_lds + p.lds_scale);
+    l.s_out = l.s_pred + 4 * p.gp_max * scale_blocks(WT, p.spred.kpad);
+    l.s_hh = l.s_out + 4 * p.gj_max * scale_blocks(WT, p.sjoint.kpad);
+    l.s_ih = l.s_hh + 4 * p.L * p.nu_max * scale_blocks(WT, p.st0.kpad);
 
     if (w.tid == 0) {
         // XCC_ID hardware register, bits [3:0]
@@ -1404,15 +1433,31 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
             const int layer = i / (hnu * 4), rem = i - layer * hnu * 4;
             l.b_lstm[(layer * p.nu_max) * 4 + rem] = p.bias_l[((long long)layer * p.H + hu0) * 4 + rem];
         }
-        if (WT == kWeightFp8Bf16Arith) {
-            for (int i = w.tid; i < ngp * 4; i += kThreads)
-                l.s_pred[i] = (gp0 * 4 + i < p.J) ? p.sc_pred[gp0 * 4 + i] : 1.0f;
-            for (int i = w.tid; i < ngj * 4; i += kThreads)
-                l.s_out[i] = (gj0 * 4 + i < p.nout_m) ? p.sc_out[gj0 * 4 + i] : 1.0f;
-            for (int i = w.tid; i < p.L * hnu * 4; i += kThreads) {
-                const int layer = i / (hnu * 4), rem = i - layer * hnu * 4;
-                l.s_hh[i] = p.sc_hh[((long long)layer * p.H + hu0) * 4 + rem];
-                l.s_ih[i] = p.sc_ih[((long long)layer * p.H + hu0) * 4 + rem];
+        if (WT == kWeightFp8Bf16Arith || WT == kWeightFp4Bf16Arith) {
+            // table entry [row][b] = the matrix's scale of that row's block b, 1 beyond the matrix
+            const int nbp = scale_blocks(WT, p.spred.kpad), nbo = scale_blocks(WT, p.sjoint.kpad);
+            const int nbh = scale_blocks(WT, p.st0.kpad);
+            const int gbh = scale_blocks_of_matrix(WT, p.H), gbj = scale_blocks_of_matrix(WT, p.J);
+            for (int i = w.tid; i < ngp * 4 * nbp; i += kThreads) {
+                const int col = gp0 * 4 + i / nbp, b = i % nbp;
+                l.s_pred[i] = scale_byte((col < p.J && b < gbh) ? p.sc_pred[(long long)col * gbh + b] : 1.0f);
+            }
+            for (int i = w.tid; i < ngj * 4 * nbo; i += kThreads) {
+                const int col = gj0 * 4 + i / nbo, b = i % nbo;
+                l.s_out[i] = scale_byte((col < p.nout_m && b < gbj) ? p.sc_out[(long long)col * gbj + b] : 1.0f);
+            }
+            for (int i = w.tid; i < p.L * hnu * 4 * nbh; i += kThreads) {
+                const int row = i / nbh, b = i % nbh;
+                const int layer = row / (hnu * 4), rem = row - layer * hnu * 4;
+                l.s_hh[i] = scale_byte(b < gbh ? p.sc_hh[(((long long)layer * p.H + hu0) * 4 + rem) * gbh + b] : 1.0f);
+            }
+            for (int layer = 1; layer < p.L; ++layer) {
+                const int nbi = scale_blocks(WT, p.stl[layer < kMaxLayers ? layer : 0].kpad);
+                for (int i = w.tid; i < hnu * 4 * nbi; i += kThreads) {
+                    const int rem = i / nbi, b = i % nbi;
+                    l.s_ih[layer * hnu * 4 * p.sc_nb_in + i] =
+                        scale_byte(b < gbh ? p.sc_ih[(((long long)layer * p.H + hu0) * 4 + rem) * gbh + b] : 1.0f);
+                }
             }
         }
     }

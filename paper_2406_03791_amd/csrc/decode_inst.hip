@@ -2,8 +2,8 @@
 // this file once per (loop nest, prediction row groups, weight storage) with
 //   -DRNNT_INST_NEST=f|l     Algorithm 1 (frame looping) or label looping / TDT
 //   -DRNNT_INST_RG=1|2|4     row groups (of 4 utterances) of a team in the prediction stages
-//   -DRNNT_INST_WT=f32|bf16|fp8|bf16a|fp8a   storage of the packed weights (bf16a: the bfloat16 mode;
-//                            fp8a: the bfloat16 mode with e4m3-stored weights)
+//   -DRNNT_INST_WT=f32|bf16|fp8|bf16a|fp8a|fp4a   storage of the packed weights (bf16a: the bfloat16 mode;
+//                            fp8a / fp4a: the bfloat16 mode with e4m3- / e2m1-stored weights)
 // so that the instances compile in parallel; decode.hip declares the launch functions and
 // picks one per call.
 #include "decode_impl.h"
@@ -17,6 +17,7 @@
 #define RNNT_WT_fp8 kWeightFp8
 #define RNNT_WT_bf16a kWeightBf16Arith
 #define RNNT_WT_fp8a kWeightFp8Bf16Arith
+#define RNNT_WT_fp4a kWeightFp4Bf16Arith
 #define RNNT_CAT2_(a, b) a##b
 #define RNNT_CAT2(a, b) RNNT_CAT2_(a, b)
 

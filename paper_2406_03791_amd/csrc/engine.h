@@ -39,7 +39,8 @@ struct DecodeParams {
     int gp_max;             // most prediction-projection output groups owned by a rank
     // dynamic LDS layout, offsets in floats
     int lds_xz, lds_red, lds_c, lds_part, lds_bias, lds_q;
-    int lds_scale;          // row scales of e4m3-stored weights (bfloat16 mode), see Lds::s_pred
+    int lds_scale;          // scales of e4m3- or e2m1-stored weights (bfloat16 mode), see Lds::s_pred
+    int sc_nb_in;           // scale blocks per row of the input stages' tables in LDS
     int rcap;               // rows the LDS state buffers are laid out for (>= rows of any team)
     int rg_planned;         // row groups the activation rows and partial sums in LDS are sized for
     int samples_cap;        // samples of a joint step the z rows and argmax candidates in LDS are sized for
@@ -66,10 +67,11 @@ struct DecodeParams {
     const float *bias_l;    // [L][H][4]: b_ih + b_hh of layers >= 1 (layer 0 unused)
     const float *b_pred;    // [J]
     const float *b_out;     // [NOUT]
-    // e4m3 storage in the bfloat16 mode: the power of two each weight row's codes are multiplied by
-    const float *sc_hh, *sc_ih;   // [L][H][4], as bias_l (sc_ih of layer 0 unused)
-    const float *sc_pred;   // [J]
-    const float *sc_out;    // [NOUT]
+    // e4m3 / e2m1 storage in the bfloat16 mode: the power of two the codes of a weight row (e4m3)
+    // or of each block of kScaleBlock weights of a row (e2m1) are multiplied by; nb = scale_blocks_of_matrix
+    const float *sc_hh, *sc_ih;   // [L][H][4][nb], as bias_l (sc_ih of layer 0 unused)
+    const float *sc_pred;   // [J][nb]
+    const float *sc_out;    // [NOUT][nb]
     // team workspace
     float *hbuf;                  // [n_teams][2][L][kMaxRows][H]
     float *qbuf;                  // [n_teams][kMaxRows][J]

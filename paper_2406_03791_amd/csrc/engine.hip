@@ -98,7 +98,8 @@ struct TeamConfig {
     Workspace ws;          // the buffers above plus the engine's P, abort flag and status word
     int xstride = 0, nu_max = 0, gj_max = 0, gp_max = 0;
     int lds_xz = 0, lds_red = 0, lds_c = 0, lds_part = 0, lds_bias = 0, lds_q = 0;
-    int lds_scale = 0;     // row scales of e4m3-stored weights in the bfloat16 mode, laid out like the biases
+    int lds_scale = 0;     // scales of e4m3- or e2m1-stored weights in the bfloat16 mode, per stage [column][block]
+    int sc_nb_in = 1;      // scale blocks per row the input stages of the layers above the first have in LDS
     int q_in_lds = 0, qstride = 0;
     int fast_pred = 0, lds_hc = 0;
     int n_tail = 0;        // joint output columns computed outside the MFMA stage, one per rank from rank 0 on
@@ -257,7 +258,17 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
         t.lds_part = take(L * nu_max * rows_max * 4);
         t.lds_bias = take(4 * (gp_max + gj_max + L * nu_max));
         // row scales: projection, output, recurrent and input matrices of every layer
-        t.lds_scale = e->wt == kWeightFp8Bf16Arith ? take(4 * (gp_max + gj_max + 2 * L * nu_max)) : 0;
+        {
+            int nb_in = 1;
+            for (int l = 1; l < L; ++l) nb_in = std::max(nb_in, scale_blocks(e->wt, t.stl[l].plan.kpad));
+            t.sc_nb_in = nb_in;
+            const bool scales = e->wt == kWeightFp8Bf16Arith || e->wt == kWeightFp4Bf16Arith;
+            // one byte per scale (its exponent)
+            t.lds_scale = scales ? take((gp_max * scale_blocks(e->wt, t.spred.plan.kpad) +
+                                         gj_max * scale_blocks(e->wt, t.sjoint.plan.kpad) +
+                                         L * nu_max * (scale_blocks(e->wt, t.st0.plan.kpad) + nb_in)))
+                                 : 0;
+        }
         // a tail column's weight row and its per-wave partial sums
         t.lds_tail = t.n_tail ? take(tail_k + kWaves * kMaxSamples) : 0;
         // room for a joint group's q rows as well (needed by joint groups, see below)
@@ -477,7 +488,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.search_steps = effective_search_steps(e, t, B);
     p.xstride = t.xstride; p.nu_max = t.nu_max; p.gj_max = t.gj_max;
     p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
-    p.lds_scale = t.lds_scale;
+    p.lds_scale = t.lds_scale; p.sc_nb_in = t.sc_nb_in;
     p.sc_hh = e->sc_hh.as<float>(); p.sc_ih = e->sc_ih.as<float>();
     p.sc_pred = e->sc_pred.as<float>(); p.sc_out = e->sc_out.as<float>();
     p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
@@ -523,11 +534,15 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
 {
     if (!desc || !out) return RNNT_ERR_NULL;
     if (flags & ~(RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_PLAIN_LAUNCH | RNNT_FLAG_BF16_ARITHMETIC |
-                  RNNT_FLAG_MULTI_BLANK))
+                  RNNT_FLAG_MULTI_BLANK | RNNT_FLAG_FP4_WEIGHTS))
         return RNNT_ERR_SHAPE;
-    {   // at most one of the three formats, or the bfloat16 mode with e4m3-stored weights
-        const int fmt = flags & (RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC);
-        if ((fmt & (fmt - 1)) && fmt != (RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC)) return RNNT_ERR_SHAPE;
+    {   // at most one of the three formats, or the bfloat16 mode with e4m3- or e2m1-stored weights
+        const int fmt = flags & (RNNT_FLAG_BF16_WEIGHTS | RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC |
+                                 RNNT_FLAG_FP4_WEIGHTS);
+        if ((fmt & (fmt - 1)) && fmt != (RNNT_FLAG_FP8_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC) &&
+            fmt != (RNNT_FLAG_FP4_WEIGHTS | RNNT_FLAG_BF16_ARITHMETIC))
+            return RNNT_ERR_SHAPE;
+        if (fmt == RNNT_FLAG_FP4_WEIGHTS) return RNNT_ERR_SHAPE;   // 4-bit codes exist for the bfloat16 mode only
     }
     const rnnt_model_desc &d = *desc;
     if (!d.emb || !d.w_ih || !d.w_hh || !d.b_ih || !d.b_hh || !d.w_enc || !d.b_enc || !d.w_pred ||
@@ -566,7 +581,8 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8
                                             : ((flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32);
     if (flags & RNNT_FLAG_BF16_ARITHMETIC)
-        e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8Bf16Arith : kWeightBf16Arith;
+        e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8Bf16Arith
+                                                : ((flags & RNNT_FLAG_FP4_WEIGHTS) ? kWeightFp4Bf16Arith : kWeightBf16Arith);
     e->plain_launch = (flags & RNNT_FLAG_PLAIN_LAUNCH) != 0;
     e->multi_blank = multi_blank;
     e->n_wg = (prop.multiProcessorCount / 32) * 32;   // every layout divides it
@@ -627,34 +643,48 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
         for (int l = 0; l < d.L; ++l) ok = ok && is_e4m3(e->w_hh[l]) && (l == 0 || is_e4m3(e->w_ih[l]));
         if (!ok) return RNNT_ERR_SHAPE;
     }
-    if (e->wt == kWeightFp8Bf16Arith) {
-        // Every row is kept as e4m3 codes times a power of two of its own, which the kernel's
-        // widening instruction applies for free: lossless or refused, as above, but per row.
-        // scales[row] = 2^k with k = e4m3_row_exponent(row).
-        auto scan = [](const std::vector<float> &m, size_t rows, size_t cols, std::vector<float> &scales) {
-            scales.assign(rows, 1.0f);
+    if (e->wt == kWeightFp8Bf16Arith || e->wt == kWeightFp4Bf16Arith) {
+        // e4m3: every row is kept as codes times a power of two of its own, which the kernel's
+        // widening instruction applies for free: lossless or refused, as above, but per row,
+        // the scale 2^k with k = e4m3_row_exponent(row).  e2m1: the same per block of
+        // kScaleBlock consecutive weights of a row, k = e2m1_block_exponent(block).
+        // scales[row][block], nb blocks per row.
+        const bool fp4 = e->wt == kWeightFp4Bf16Arith;
+        const int wt = e->wt;
+        auto scan = [fp4, wt](const std::vector<float> &m, size_t rows, size_t cols, std::vector<float> &scales) {
+            const size_t nb = (size_t)scale_blocks_of_matrix(wt, (int)cols);
+            scales.assign(rows * nb, 1.0f);
             uint8_t code;
-            for (size_t r = 0; r < rows; ++r) {
-                const float *row = m.data() + r * cols;
-                const int k = e4m3_row_exponent(row, (int)cols);
-                for (size_t i = 0; i < cols; ++i)
-                    if (!e4m3_bits(std::ldexp(row[i], -k), &code)) return false;
-                scales[r] = std::ldexp(1.0f, k);
-            }
+            for (size_t r = 0; r < rows; ++r)
+                for (size_t b = 0; b < nb; ++b) {
+                    const size_t lo = fp4 ? b * kScaleBlock : 0, n = fp4 ? std::min((size_t)kScaleBlock, cols - lo) : cols;
+                    const float *blk = m.data() + r * cols + lo;
+                    const int k = fp4 ? e2m1_block_exponent(blk, (int)n) : e4m3_row_exponent(blk, (int)n);
+                    for (size_t i = 0; i < n; ++i) {
+                        const float v = std::ldexp(blk[i], -k);
+                        if (!(fp4 ? e2m1_bits(v, &code) : e4m3_bits(v, &code))) return false;
+                    }
+                    scales[r * nb + b] = std::ldexp(1.0f, k);
+                }
             return true;
         };
+        const size_t nbh = (size_t)scale_blocks_of_matrix(wt, (int)H);
         std::vector<float> s_pred, s_out, rows_s;
-        std::vector<float> s_hh((size_t)d.L * H * 4, 1.0f), s_ih((size_t)d.L * H * 4, 1.0f);
+        std::vector<float> s_hh((size_t)d.L * H * 4 * nbh, 1.0f), s_ih((size_t)d.L * H * 4 * nbh, 1.0f);
         bool ok = scan(e->w_pred, J, H, s_pred) && scan(e->w_out, (size_t)e->NOUT, J, s_out);
         for (int l = 0; ok && l < d.L; ++l) {
             // unit-major with the four gates together, as the biases of the layers are kept
             ok = scan(e->w_hh[l], 4 * H, H, rows_s);
             for (size_t u = 0; ok && u < H; ++u)
-                for (size_t g = 0; g < 4; ++g) s_hh[((size_t)l * H + u) * 4 + g] = rows_s[g * H + u];
+                for (size_t g = 0; g < 4; ++g)
+                    for (size_t b = 0; b < nbh; ++b)
+                        s_hh[(((size_t)l * H + u) * 4 + g) * nbh + b] = rows_s[(g * H + u) * nbh + b];
             if (l == 0 || !ok) continue;
             ok = scan(e->w_ih[l], 4 * H, H, rows_s);
             for (size_t u = 0; ok && u < H; ++u)
-                for (size_t g = 0; g < 4; ++g) s_ih[((size_t)l * H + u) * 4 + g] = rows_s[g * H + u];
+                for (size_t g = 0; g < 4; ++g)
+                    for (size_t b = 0; b < nbh; ++b)
+                        s_ih[(((size_t)l * H + u) * 4 + g) * nbh + b] = rows_s[(g * H + u) * nbh + b];
         }
         if (!ok) return RNNT_ERR_SHAPE;
         auto put = [&](DevBuf &dst, const std::vector<float> &v) -> int {
@@ -717,6 +747,29 @@ int rnnt_quantize_rows_e4m3(const float *w, int64_t rows, int64_t cols, float *o
         }
         if (scales_out) scales_out[r] = std::ldexp(1.0f, k);
     }
+    return RNNT_OK;
+}
+
+int rnnt_quantize_blocks_e2m1(const float *w, int64_t rows, int64_t cols, float *out, float *scales_out)
+{
+    static_assert(kScaleBlock == RNNT_FP4_BLOCK, "the header states the block length");
+    if (!w || !out) return RNNT_ERR_NULL;
+    if (rows < 0 || cols < 0 || cols > 0x7fffffff) return RNNT_ERR_SHAPE;
+    for (int64_t i = 0; i < rows * cols; ++i)
+        if (!std::isfinite(w[i])) return RNNT_ERR_SHAPE;
+    const int64_t nb = (cols + kScaleBlock - 1) / kScaleBlock;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t b = 0; b < nb; ++b) {
+            const int64_t lo = b * kScaleBlock, n = std::min<int64_t>(kScaleBlock, cols - lo);
+            const float *blk = w + r * cols + lo;
+            float *dst = out + r * cols + lo;
+            const int k = e2m1_block_exponent(blk, (int)n);
+            for (int64_t i = 0; i < n; ++i) {
+                const float v = std::ldexp(blk[i], -k);
+                dst[i] = std::ldexp(e2m1_round(std::fabs(v) > 6.0f ? std::copysign(6.0f, v) : v), k);
+            }
+            if (scales_out) scales_out[r * nb + b] = std::ldexp(1.0f, k);
+        }
     return RNNT_OK;
 }
 

@@ -2,6 +2,7 @@
 // them in (see plan.h for the task decomposition).  No device code and no HIP calls here, so
 // that the packer can be built and run under host sanitizers on its own.
 #pragma once
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -75,12 +76,50 @@ inline float e4m3_round(float v)
     return std::copysign(r, v);
 }
 
+// OCP e2m1 (4 bits: 1 sign, 2 exponent bits with bias 1, 1 mantissa bit; magnitudes 0, 0.5, 1,
+// 1.5, 2, 3, 4, 6) code of a float, if the float is one of its values.
+inline bool e2m1_bits(float v, uint8_t *code)
+{
+    static const float mags[8] = {0.f, 0.5f, 1.f, 1.5f, 2.f, 3.f, 4.f, 6.f};
+    const float a = std::fabs(v);
+    for (int c = 0; c < 8; ++c)
+        if (a == mags[c]) { *code = (uint8_t)(c | (std::signbit(v) ? 8 : 0)); return true; }
+    return false;
+}
+
+// Nearest e2m1 value (ties to the even code) of a finite float of magnitude at most 6.
+inline float e2m1_round(float v)
+{
+    const float a = std::fabs(v);
+    // the grid's spacing is 0.5 below 2, 1 from 2 to 4 and 2 above
+    const float step = a < 2.f ? 0.5f : (a < 4.f ? 1.f : 2.f);
+    return std::copysign(std::nearbyint(a / step) * step, v);
+}
+
+// Exponent k of the power-of-two scale of a block of weights stored as e2m1 codes: the
+// smallest k with max|block| * 2^-k <= 6 (0 for zeros), kept within +-100.
+inline int e2m1_block_exponent(const float *blk, int n)
+{
+    float m = 0.f;
+    for (int i = 0; i < n; ++i) {
+        const float a = std::fabs(blk[i]);
+        if (!(a <= m)) m = a;
+    }
+    if (!(m > 0.f) || !std::isfinite(m)) return 0;
+    int k = std::ilogb(m) - 2;                                // m * 2^-k in [4, 8)
+    if (std::ldexp(m, -k) > 6.0f) ++k;
+    return k < -100 ? -100 : (k > 100 ? 100 : k);
+}
+
 // The packed image of one stage: 16 bytes per (rank, wave, slot, step, lane) holding 4 floats,
-// 8 bf16 codes or 16 e4m3 codes of consecutive K for the output column the lane owns.
+// 8 bf16 codes, 16 e4m3 codes or 32 e2m1 codes (low nibble first) of consecutive K for the
+// output column the lane owns.
 //   ngroups(rank)        output groups (of 4 columns) the rank owns
 //   row_of(rank, g, j)   the weight row (length plan.K) of column j of the rank's group g, or
 //                        nullptr for a column beyond the matrix (stays zero)
 //   row_scaled           e4m3 only: the codes are those of row * 2^-k, k = e4m3_row_exponent(row)
+//                        (e2m1 codes are always scaled, per block of kScaleBlock K values:
+//                        k = e2m1_block_exponent of the block)
 inline std::vector<uint32_t> pack_stage(const StagePlan &pl, int ts,
                                         const std::function<int(int)> &ngroups,
                                         const std::function<const float *(int, int, int)> &row_of,
@@ -110,6 +149,15 @@ inline std::vector<uint32_t> pack_stage(const StagePlan &pl, int ts,
                             for (int c = 0; c < 8; ++c)
                                 if (k0 + c < pl.K)
                                     dst[c >> 1] |= (uint32_t)bf16_bits(row[k0 + c]) << (16 * (c & 1));
+                        } else if (pl.kper == 32) {
+                            const int b0 = k0 / kScaleBlock * kScaleBlock;     // a load lies inside one block
+                            const int kb = b0 < pl.K ? e2m1_block_exponent(row + b0, std::min(kScaleBlock, pl.K - b0)) : 0;
+                            for (int c = 0; c < 32; ++c)
+                                if (k0 + c < pl.K) {
+                                    uint8_t code = 0;
+                                    e2m1_bits(std::ldexp(row[k0 + c], -kb), &code);   // checked when the engine was created
+                                    dst[c >> 3] |= (uint32_t)code << (4 * (c & 7));
+                                }
                         } else {
                             for (int c = 0; c < 16; ++c)
                                 if (k0 + c < pl.K) {

@@ -35,13 +35,32 @@ constexpr int kAheadSteps = 4 * kStepUnroll;   // at least the loads a lane keep
 // bf16 and stored as such, and every vector that enters a product is rounded to bf16 too;
 // products of two bf16 values are exact in fp32 and the sums stay fp32.
 // kWeightFp8Bf16Arith is the bfloat16 mode with its weights stored as e4m3 (lossless or refused):
-// a stored weight is widened to bf16, which holds every e4m3 value, on its way to the bf16 MFMA.
+// a stored weight is widened to bf16, which holds every e4m3 value, on its way to the bf16 MFMA,
+// and multiplied by its row's power-of-two scale in the same instruction.
+// kWeightFp4Bf16Arith: the same with 4-bit codes in the OCP e2m1 format (32 per load) and one
+// power-of-two scale per kScaleBlock consecutive K values of a row.
 enum WeightType { kWeightF32 = 0, kWeightBf16 = 1, kWeightFp8 = 2, kWeightBf16Arith = 3, kWeightFp8Bf16Arith = 4,
-                  kWeightTypes = 5 };
-RNNT_HD constexpr bool is_bf16_arith(int wt) { return wt == kWeightBf16Arith || wt == kWeightFp8Bf16Arith; }
-RNNT_HD inline int k_per_load(int wt)
+                  kWeightFp4Bf16Arith = 5, kWeightTypes = 6 };
+RNNT_HD constexpr bool is_bf16_arith(int wt)
 {
-    return (wt == kWeightFp8 || wt == kWeightFp8Bf16Arith) ? 16 : ((wt == kWeightBf16 || wt == kWeightBf16Arith) ? 8 : 4);
+    return wt == kWeightBf16Arith || wt == kWeightFp8Bf16Arith || wt == kWeightFp4Bf16Arith;
+}
+RNNT_HD constexpr int k_per_load(int wt)
+{
+    return wt == kWeightFp4Bf16Arith ? 32
+         : ((wt == kWeightFp8 || wt == kWeightFp8Bf16Arith) ? 16 : ((wt == kWeightBf16 || wt == kWeightBf16Arith) ? 8 : 4));
+}
+// K values that share a scale in the 4-bit form: the K values of one software-pipeline batch of
+// a lane (kStepUnroll loads of 32), so a K slice of a task is a whole number of blocks and a
+// lane changes its scale only between batches.
+constexpr int kScaleBlock = kStepUnroll * 32;
+// Scales a weight row of a stage has in LDS: one per block of the padded K in the 4-bit form,
+// one per row with e4m3 codes.
+RNNT_HD constexpr int scale_blocks(int wt, int kpad) { return wt == kWeightFp4Bf16Arith ? kpad / kScaleBlock : 1; }
+// Scales per row of a matrix with K columns as the engine keeps them in device memory.
+RNNT_HD constexpr int scale_blocks_of_matrix(int wt, int K)
+{
+    return wt == kWeightFp4Bf16Arith ? (K + kScaleBlock - 1) / kScaleBlock : 1;
 }
 
 // Floats between the partial sums of consecutive tasks in LDS: 16 per row group plus a pad that
@@ -72,7 +91,7 @@ struct StagePlan {
     int nks;        // K slices per group
     int nsteps;     // 16-byte loads per lane and task (multiple of kStepUnroll)
     int slots;      // passes over the 128 blocks
-    int kper;       // K values per load (4: fp32 weights, 8: bf16, 16: fp8)
+    int kper;       // K values per load (4: fp32 weights, 8: bf16, 16: fp8, 32: fp4)
     int kpad;       // nks * nsteps * kper: padded input length
     int64_t rank_stride;   // 16-byte elements of packed weights per rank
 };

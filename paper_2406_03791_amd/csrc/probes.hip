@@ -177,6 +177,20 @@ __global__ void widen_kernel(float scale, uint16_t *out)
     }
 }
 
+__global__ void widen4_kernel(float scale, uint16_t *out)
+{
+    const unsigned byte = threadIdx.x;
+    unsigned two[4];
+    two[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(byte, scale, 0));
+    two[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(byte << 8, scale, 1));
+    two[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(byte << 16, scale, 2));
+    two[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(byte << 24, scale, 3));
+    for (int pos = 0; pos < 4; ++pos) {
+        out[(pos * 256 + byte) * 2] = (uint16_t)(two[pos] & 0xffffu);
+        out[(pos * 256 + byte) * 2 + 1] = (uint16_t)(two[pos] >> 16);
+    }
+}
+
 extern "C" {
 
 int rnnt_probe_stream(int32_t from_l2, double *gbytes_per_s_out, double *per_cu_out)
@@ -274,6 +288,18 @@ int rnnt_probe_e4m3_widening(float scale, uint16_t *bf16_out)
     hipLaunchKernelGGL(widen_kernel, dim3(1), dim3(256), 0, nullptr, scale, dev);
     PROBE_TRY(hipGetLastError());
     PROBE_TRY(hipMemcpy(bf16_out, dev, 4 * 256 * sizeof(uint16_t), hipMemcpyDeviceToHost));
+    (void)hipFree(dev);
+    return RNNT_OK;
+}
+
+int rnnt_probe_e2m1_widening(float scale, uint16_t *bf16_out)
+{
+    if (!bf16_out) return RNNT_ERR_NULL;
+    uint16_t *dev = nullptr;
+    PROBE_TRY(hipMalloc(&dev, 4 * 256 * 2 * sizeof(uint16_t)));
+    hipLaunchKernelGGL(widen4_kernel, dim3(1), dim3(256), 0, nullptr, scale, dev);
+    PROBE_TRY(hipGetLastError());
+    PROBE_TRY(hipMemcpy(bf16_out, dev, 4 * 256 * 2 * sizeof(uint16_t), hipMemcpyDeviceToHost));
     (void)hipFree(dev);
     return RNNT_OK;
 }

@@ -4,7 +4,7 @@
 // (col, k) encodes its own position, then walks the packed image the way the kernel's lanes
 // do and checks that every (col, k) of the matrix turns up exactly once, at the place the
 // plan says, and that everything else is zero.  Also checks e4m3_bits on all 256 codes, the
-// row-scaled e4m3 form (exponent rule, rounding, packed codes) and the split of the joint
+// row-scaled e4m3 and block-scaled e2m1 forms (exponent rules, rounding, packed codes) and the split of the joint
 // output stage into an MFMA part and tail columns.
 #include <cstdio>
 #include <cstdlib>
@@ -47,8 +47,11 @@ int main()
                     const StagePlan pl = make_stage_plan(K, gmax, wt);
                     // values: small integers that are exact in every storage (e4m3 holds 0..15 exactly)
                     std::vector<float> W((size_t)N * K);
+                    static const float mags4[7] = {0.5f, 1.f, 1.5f, 2.f, 3.f, 4.f, 6.f};
                     for (int c = 0; c < N; ++c)
-                        for (int k = 0; k < K; ++k) W[(size_t)c * K + k] = (float)(1 + (c * 7 + k * 3) % 15);
+                        for (int k = 0; k < K; ++k)
+                            W[(size_t)c * K + k] = pl.kper == 32 ? std::ldexp(mags4[(c * 7 + k * 3) % 7], (c + k / kScaleBlock) % 5 - 2)
+                                                                 : (float)(1 + (c * 7 + k * 3) % 15);
                     const std::vector<uint32_t> img = pack_stage(
                         pl, ts, ng_of, [&](int r, int g, int j) -> const float * {
                             const int col = (range_lo(r, ts, ng_all) + g) * 4 + j;
@@ -72,6 +75,17 @@ int main()
                                             else if (pl.kper == 8) {
                                                 const uint32_t bits = ((q[c >> 1] >> (16 * (c & 1))) & 0xffffu) << 16;
                                                 std::memcpy(&v, &bits, 4);
+                                            } else if (pl.kper == 32) {
+                                                // low nibble first; the block's power of two comes from the matrix
+                                                const int code = (q[c >> 3] >> (4 * (c & 7))) & 0xf;
+                                                const float mag = (code & 7) ? mags4[(code & 7) - 1] : 0.f;
+                                                v = (code & 8) ? -mag : mag;
+                                                const int kk = (ks * pl.nsteps + step) * pl.kper + c;
+                                                if (col < N && kk < K) {
+                                                    const int b0 = kk / kScaleBlock * kScaleBlock;
+                                                    v = std::ldexp(v, e2m1_block_exponent(W.data() + (size_t)col * K + b0,
+                                                                                          std::min(kScaleBlock, K - b0)));
+                                                }
                                             } else {
                                                 v = e4m3_value((q[c >> 2] >> (8 * (c & 3))) & 0xff);
                                             }
@@ -137,6 +151,33 @@ int main()
                     std::printf("round next to tie %d\n", code);
                     return 1;
                 }
+            }
+        }
+        {   // e2m1: codes, rounding (ties to the even code) and the block exponent
+            static const float mags[8] = {0.f, 0.5f, 1.f, 1.5f, 2.f, 3.f, 4.f, 6.f};
+            uint8_t code = 0xff;
+            for (int c = 0; c < 8; ++c) {
+                if (!e2m1_bits(mags[c], &code) || code != c) { std::printf("e2m1 code %d\n", c); return 1; }
+                if (c && (!e2m1_bits(-mags[c], &code) || code != (c | 8))) { std::printf("e2m1 code -%d\n", c); return 1; }
+                if (e2m1_round(mags[c]) != mags[c]) { std::printf("e2m1 fixed point %d\n", c); return 1; }
+                if (c + 1 < 8) {
+                    const float mid = 0.5f * (mags[c] + mags[c + 1]);
+                    if (e2m1_round(mid) != mags[(c & 1) ? c + 1 : c] || e2m1_round(-mid) != -mags[(c & 1) ? c + 1 : c] ||
+                        e2m1_round(std::nextafter(mid, 0.f)) != mags[c] || e2m1_round(std::nextafter(mid, 9.f)) != mags[c + 1]) {
+                        std::printf("e2m1 round near %g\n", mid);
+                        return 1;
+                    }
+                }
+            }
+            if (e2m1_bits(0.25f, &code) || e2m1_bits(5.f, &code) || e2m1_bits(8.f, &code) || e2m1_bits(NAN, &code)) {
+                std::printf("e2m1 accepted a value outside the format\n");
+                return 1;
+            }
+            const float a[2] = {6.f, -1.f}, b[2] = {6.5f, 1.f}, c3[2] = {3.f, 0.f}, z[2] = {0.f, 0.f};
+            if (e2m1_block_exponent(a, 2) != 0 || e2m1_block_exponent(b, 2) != 1 || e2m1_block_exponent(c3, 2) != -1 ||
+                e2m1_block_exponent(z, 2) != 0) {
+                std::printf("block exponent\n");
+                return 1;
             }
         }
         const int K = 100, N = 37, ts = 3, ng_all = (N + 3) / 4;

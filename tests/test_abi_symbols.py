@@ -80,7 +80,8 @@ def test_create_refuses_unsupported_shapes_before_touching_the_device():
     assert create(L=0) == -2 and create(L=5) == -2
     assert create(blank=5) == -2 and create(blank=-1) == -2
     assert create(D=9) == -2
-    assert create(flags=32) == -2                                    # unknown flag bit
+    assert create(flags=64) == -2                                    # unknown flag bit
+    assert create(flags=32) == -2                                    # 4-bit weights without the bfloat16 mode
     assert create(flags=pkg.RNNT_FLAG_BF16_ARITHMETIC | pkg.RNNT_FLAG_BF16_WEIGHTS) == -2
     assert create(flags=pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS) == -2
     # multi-blank: needs big blanks, each spanning at least one frame

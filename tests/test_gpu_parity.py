@@ -465,7 +465,7 @@ def test_compact_weight_storage(pkg):
             eng.close()
     # unknown flag bits and both storage flags at once are refused
     w8 = dataclasses.replace(w32, model=synth.with_fp8_streamed_weights(w32.model))
-    for flags in (16, pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS):
+    for flags in (64, pkg.RNNT_FLAG_BF16_WEIGHTS | pkg.RNNT_FLAG_FP8_WEIGHTS):
         with pytest.raises(pkg.RnntError) as err:
             pkg.Engine(w8.model, w8.B, w8.T, flags=flags)
         assert err.value.code == -2
@@ -583,13 +583,15 @@ def test_every_default_layout_class_of_the_parakeet_shape(pkg):
 
 def test_default_layout_classes_of_the_other_weight_forms(pkg):
     """The LDS layout depends on the K values a load carries: the same sweep, coarser, for bf16
-    and e4m3 storage and for the bfloat16 arithmetic with either storage."""
+    and e4m3 storage and for the bfloat16 arithmetic with bf16, e4m3 or e2m1 storage."""
     import dataclasses
     forms = [("bf16w", pkg.RNNT_FLAG_BF16_WEIGHTS, synth.with_bf16_streamed_weights, False),
              ("fp8w", pkg.RNNT_FLAG_FP8_WEIGHTS, synth.with_fp8_streamed_weights, False),
              ("bf16 arithmetic", pkg.RNNT_FLAG_BF16_ARITHMETIC, None, True),
              ("bf16 arithmetic/fp8w", pkg.RNNT_FLAG_BF16_ARITHMETIC | pkg.RNNT_FLAG_FP8_WEIGHTS,
-              synth.with_fp8_streamed_weights, True)]
+              synth.with_fp8_streamed_weights, True),
+             ("bf16 arithmetic/fp4w", pkg.RNNT_FLAG_BF16_ARITHMETIC | pkg.RNNT_FLAG_FP4_WEIGHTS,
+              lambda m: synth.with_streamed_weights(m, lambda a: oracle.quantize_blocks_e2m1(a)[0]), True)]
     for B in [5, 24, 72, 104, 160, 256]:
         for cfg, variants in [(3, ("label", "frame")), (4, ("tdt",))]:
             w0 = synth.make_workload(cfg, pad="nan", B=B, T=16, len_lo=5, len_hi=16)
@@ -804,3 +806,59 @@ def test_weight_only_8_bit_quantised_models(pkg):
     with pytest.raises(pkg.RnntError) as err:
         pkg.Engine(bad, w.B, w.T, flags=flags)
     assert err.value.code == -2
+
+
+def test_e2m1_codes_widen_to_their_bf16_values(pkg):
+    """The conversion instruction of the 4-bit form, on every byte value in every byte position,
+    against the format's definition (1 sign, 2 exponent bits with bias 1, 1 mantissa bit; the low
+    nibble is the first code), under several scale operands."""
+    mags = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    for scale, factor in [(1.0, 1.0), (2.0 ** -12, 2.0 ** -12), (32.0, 32.0), (2.0 ** -30, 2.0 ** -30), (1.5, 1.0)]:
+        got = pkg.rnnt_probe_e2m1_widening(scale)
+        for byte in range(256):
+            for half, code in enumerate((byte & 15, byte >> 4)):
+                want = np.float32(mags[code & 7] * factor * (-1.0 if code & 8 else 1.0))
+                for pos in range(4):
+                    bits = np.array([int(got[pos, byte, half]) << 16], dtype=np.uint32).view(np.float32)[0]
+                    assert bits == want and np.signbit(bits) == bool(code & 8), (scale, byte, half, pos, bits)
+
+
+def test_weight_only_4_bit_quantised_models(pkg):
+    """Any model, quantised to e2m1 codes with a power-of-two scale per block of 128 weights of a
+    row (the library's host-side quantiser; the oracle's own gives the same matrices), decoded
+    in the bfloat16 mode with those codes as the stored weights.  Reference: the oracle's
+    bfloat16 emulation on the quantised model, to the bar of the bfloat16 mode."""
+    import dataclasses
+    flags = pkg.RNNT_FLAG_BF16_ARITHMETIC | pkg.RNNT_FLAG_FP4_WEIGHTS
+    for cfg, variants, kw in [(1, ("frame", "label"), {}),
+                              (3, ("frame", "label"), dict(B=12, T=120, len_lo=40, len_hi=120)),
+                              (4, ("tdt",), dict(B=12, T=120, len_lo=40, len_hi=120)),
+                              (3, ("label", "frame"), {}), (4, ("tdt",), {}),
+                              (5, ("label", "frame"), dict(B=12, T=120, len_lo=40, len_hi=120)),
+                              (6, ("label",), dict(B=12, T=120, len_lo=40, len_hi=120)),
+                              (3, ("label",), dict(B=128, T=60, len_lo=20, len_hi=60))]:
+        w0 = synth.make_workload(cfg, pad="nan", **kw)
+        m_lib = synth.with_streamed_weights(w0.model, lambda a: pkg.rnnt_quantize_blocks_e2m1(a)[0])
+        m_orc = synth.with_streamed_weights(w0.model, lambda a: oracle.quantize_blocks_e2m1(a)[0])
+        for a, b in [(m_lib.w_pred, m_orc.w_pred), (m_lib.w_out, m_orc.w_out)] + \
+                list(zip(m_lib.w_hh, m_orc.w_hh)) + list(zip(m_lib.w_ih, m_orc.w_ih)):
+            assert np.array_equal(a, b)
+        w = dataclasses.replace(w0, model=m_orc)
+        eng = pkg.Engine(m_lib, w.B, w.T, flags=flags)
+        ref32 = oracle.decode(oracle.LstmNet(w0.model), w.enc_out, w.enc_len, w.max_symbols, "seq",
+                              n_threads=N_THREADS)
+        for variant in variants:
+            ref, got, st = check(pkg, w, variant, f"cfg{cfg}/quantised to e2m1 blocks", engine=eng,
+                                 bf16=True, logp=(variant == "label"))
+            assert st["near_tie_rows"] <= max(1, w.B // 3)
+            moved = sum(int(not np.array_equal(ref.tokens[b], ref32.tokens[b])) for b in range(w.B))
+            log(f"  rows whose tokens differ from the fp32 decode of the unquantised model: {moved}/{w.B}")
+        eng.close()
+    # refused: a weight off its block's grid; the flag without the bfloat16 mode; two formats
+    bad = dataclasses.replace(m_lib, w_pred=m_lib.w_pred.copy())
+    bad.w_pred[3, 5] = np.float32(bad.w_pred[3, 5] * 1.01 + 1e-6)
+    for model, fl in [(bad, flags), (m_lib, pkg.RNNT_FLAG_FP4_WEIGHTS),
+                      (m_lib, flags | pkg.RNNT_FLAG_FP8_WEIGHTS)]:
+        with pytest.raises(pkg.RnntError) as err:
+            pkg.Engine(model, w.B, w.T, flags=fl)
+        assert err.value.code == -2
