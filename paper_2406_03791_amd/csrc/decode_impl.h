@@ -1504,6 +1504,55 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         if (la < 1) la = 1;
         int max_out_len = 0;
         for (int r = 0; r < R; ++r) max_out_len = max(max_out_len, c.len[r]);
+        if (R == 1) {
+            // One utterance per team (the default up to 32 utterances): there are no batch mates
+            // to keep in step, so the loop nest reduces to its decisions.  Every thread reads the
+            // same results of a joint step and takes the same decisions from them; only an
+            // emission, whose state the prediction step reads next, needs a barrier.
+            //   t      frame index (Algorithm 1's time_idx), n_sym labels emitted on frame t
+            //   window frames [win0, win0 + win_n) have joint results for the current g
+            max_out_len = 0;       // the general loop below does not run
+            const int len = c.len[0];
+            int t = 0, n_sym = 0, win0 = 0, win_n = 0;
+            bool need_pred = true;
+            while (ok && t < len) {
+                if (need_pred) {
+                    ok = prediction_step<RG, WT>(p, w, sy, l);
+                    if (!ok) break;
+                    ++n_pred;
+                    need_pred = false;
+                    win_n = 0;
+                }
+                if (t >= win0 + win_n) {
+                    const int n_ahead = min(la, len - t);
+                    if (w.tid < kMaxSamples) {
+                        const int s = w.tid, valid = s < n_ahead;
+                        c.s_row[s] = 0; c.s_frame[s] = t + s; c.s_valid[s] = valid;
+                        c.s_pidx[s] = valid ? c.b[0] * p.T + t + s : -1;
+                        c.s_qoff[s] = 0;
+                    }
+                    if (w.tid == 0) c.ns = n_ahead;
+                    __syncthreads();
+                    ok = joint_step<RGJ, WT>(p, w, sy, l);
+                    if (!ok) break;
+                    ++n_joint; n_samples += n_ahead;
+                    win0 = t; win_n = n_ahead;
+                }
+                // the first label among the window's frames from t on; blanks before it only
+                // move the frame index
+                const int s = w.lane & (kMaxSamples - 1);
+                const bool label = w.lane < win_n && win0 + s >= t && c.s_k[s] != p.blank;
+                const unsigned long long m = __ballot(label);
+                if (!m) { t = win0 + win_n; n_sym = 0; continue; }
+                const int i = __ffsll((long long)m) - 1;
+                if (win0 + i > t) { t = win0 + i; n_sym = 0; }
+                if (w.tid == 0) emit_row(p, w, 0, c.s_k[i], t, c.s_v[i], c.s_lp[i], 0);
+                need_pred = true;
+                if (++n_sym == p.S) { ++t; n_sym = 0; }     // max_symbols labels on this frame: move on
+                // the emission's state (last label, selector, count) before the prediction step reads it
+                __syncthreads();
+            }
+        }
         bool need_pred = true;     // nothing computed yet for (last_label, hidden)
         int flip = 0;              // slot of c.any the next inner step reports in
         int win0 = 0, win_n = 0;   // frames [win0, win0 + win_n) have results for the current g
