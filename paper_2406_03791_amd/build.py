@@ -11,7 +11,7 @@ SOURCES = ["engine.hip", "decode.hip", "enc_proj.hip", "probes.hip"]
 # the decode kernel is instantiated in one unit per (loop nest, row groups, weight storage),
 # all compiled from decode_inst.hip, so that the instances build in parallel
 INSTANCES = [(nest, rg, wt) for wt in ("f32", "bf16", "fp8", "bf16a", "fp8a", "fp4a") for nest in ("f", "l")
-             for rg in (1, 2, 4)]
+             for rg in (1, 2, 4)] + [("s", 1, wt) for wt in ("f32", "bf16", "fp8", "bf16a", "fp8a", "fp4a")]
 LIB = os.path.join(HERE, "librnnt_greedy.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 FLAGS = ((["-DRNNT_PROFILE"] if os.environ.get("RNNT_PROFILE") else []) +
@@ -32,9 +32,25 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
         src, name, defs = job
         obj = os.path.join(OBJ_DIR, name + ".o")
         cmd = ["hipcc", *FLAGS, *defs, "-c", os.path.join(CSRC, src), "-o", obj]
+        if not defs:
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True)
+            return obj
+        # decode kernel instances: also ask for the register report and say so when an instance
+        # uses scratch memory: spilled registers or a stack object cost time without failing a test
+        cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
         if verbose:
             print(" ".join(cmd), flush=True)
-        subprocess.run(cmd, check=True)
+        r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+        if r.returncode != 0:
+            sys.stderr.write(r.stderr)
+            raise subprocess.CalledProcessError(r.returncode, cmd)
+        spilled = [ln for ln in r.stderr.splitlines() if "ScratchSize [bytes/lane]:" in ln
+                   and not ln.rstrip().endswith(": 0 [-Rpass-analysis=kernel-resource-usage]")]
+        if spilled:
+            print(f"build.py: {name}: {len(spilled)} kernel instance(s) use scratch memory (a stack object or spilled registers)",
+                  file=sys.stderr, flush=True)
         return obj
 
     jobs_ = [("decode_inst.hip", f"decode_{nest}{rg}_{wt}",

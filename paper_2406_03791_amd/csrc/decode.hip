@@ -10,7 +10,8 @@ namespace rnnt {
 #define RNNT_DECLARE_NEST(wt)                                                            \
     RNNT_DECLARE_LAUNCH(launch_decode_f1_##wt); RNNT_DECLARE_LAUNCH(launch_decode_f2_##wt); \
     RNNT_DECLARE_LAUNCH(launch_decode_f4_##wt); RNNT_DECLARE_LAUNCH(launch_decode_l1_##wt); \
-    RNNT_DECLARE_LAUNCH(launch_decode_l2_##wt); RNNT_DECLARE_LAUNCH(launch_decode_l4_##wt)
+    RNNT_DECLARE_LAUNCH(launch_decode_l2_##wt); RNNT_DECLARE_LAUNCH(launch_decode_l4_##wt); \
+    RNNT_DECLARE_LAUNCH(launch_decode_s1_##wt)
 RNNT_DECLARE_NEST(f32); RNNT_DECLARE_NEST(bf16); RNNT_DECLARE_NEST(fp8); RNNT_DECLARE_NEST(bf16a);
 RNNT_DECLARE_NEST(fp8a);
 RNNT_DECLARE_NEST(fp4a);
@@ -78,6 +79,10 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
         {{launch_decode_f1_fp4a, launch_decode_f2_fp4a, launch_decode_f4_fp4a},
          {launch_decode_l1_fp4a, launch_decode_l2_fp4a, launch_decode_l4_fp4a}}};
     if (p.wt < 0 || p.wt >= kWeightTypes) return hipErrorInvalidValue;
+    // Algorithm 1 with one utterance per team has an instance of its own
+    static const Launch single[kWeightTypes] = {launch_decode_s1_f32, launch_decode_s1_bf16, launch_decode_s1_fp8,
+                                                launch_decode_s1_bf16a, launch_decode_s1_fp8a, launch_decode_s1_fp4a};
+    if (p.variant == kFrameLooping && rows == 1) return single[p.wt](p, rgj, stream);
     return table[p.wt][p.variant == kFrameLooping ? 0 : 1][rgi](p, rgj, stream);
 }
 

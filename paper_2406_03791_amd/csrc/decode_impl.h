@@ -1494,7 +1494,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
 
     long long n_pred = 0, n_joint = 0, n_samples = 0;
 
-    if constexpr (VARIANT == kFrameLooping) {
+    if constexpr (VARIANT == kFrameLooping || VARIANT == kFrameLoopingSingle) {
         // Algorithm 1 on this team's rows.  A joint step also evaluates the next frames of
         // every row with the same g (lookahead); those results stand in for the first joint
         // evaluation of the following frames for as long as no row emits, that is, for as
@@ -1504,14 +1504,13 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
         if (la < 1) la = 1;
         int max_out_len = 0;
         for (int r = 0; r < R; ++r) max_out_len = max(max_out_len, c.len[r]);
-        if (R == 1) {
+        if constexpr (VARIANT == kFrameLoopingSingle) {
             // One utterance per team (the default up to 32 utterances): there are no batch mates
             // to keep in step, so the loop nest reduces to its decisions.  Every thread reads the
             // same results of a joint step and takes the same decisions from them; only an
             // emission, whose state the prediction step reads next, needs a barrier.
             //   t      frame index (Algorithm 1's time_idx), n_sym labels emitted on frame t
             //   window frames [win0, win0 + win_n) have joint results for the current g
-            max_out_len = 0;       // the general loop below does not run
             const int len = c.len[0];
             int t = 0, n_sym = 0, win0 = 0, win_n = 0;
             bool need_pred = true;
@@ -1552,90 +1551,91 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                 // the emission's state (last label, selector, count) before the prediction step reads it
                 __syncthreads();
             }
-        }
-        bool need_pred = true;     // nothing computed yet for (last_label, hidden)
-        int flip = 0;              // slot of c.any the next inner step reports in
-        int win0 = 0, win_n = 0;   // frames [win0, win0 + win_n) have results for the current g
-        for (int time_idx = 0; ok && time_idx < max_out_len; ++time_idx) {
-            // Frames the window already covers and on which every row produced a blank change
-            // nothing but the frame index: they are passed over in one go (each would run the
-            // inner loop once, find all blank and leave).  Every thread reads the same results
-            // and takes the same decision.
-            if (!need_pred && time_idx > win0 && time_idx < win0 + win_n) {
-                // (every wave looks at all results at once: lane s holds sample s = frame offset
-                // s / R, row s % R, and the first label among the frames from time_idx on decides)
-                int f;
-                {
-                    const int s = w.lane & (kMaxSamples - 1), i = s / R, r = s - i * R;
-                    const int k = c.s_k[s], len_r = c.len[r];
-                    const bool label = w.lane < win_n * R && win0 + i >= time_idx && win0 + i < len_r && k != p.blank;
-                    const unsigned long long m = __ballot(label);
-                    f = m ? win0 + (__ffsll((long long)m) - 1) / R : win0 + win_n;
-                }
-                if (f > time_idx) {
-                    // rows whose frames ran out on the way are complete
-                    if (w.rank == 0 && w.tid < R && c.len[w.tid] >= time_idx && c.len[w.tid] < f &&
-                        c.len[w.tid] > 0)
-                        finish_row(p, w.tid);
-                    time_idx = f;
-                    if (time_idx >= max_out_len) break;
-                }
-            }
-            if (w.tid < R) {
-                c.mask[w.tid] = time_idx >= c.len[w.tid];   // blank_mask
-                // a row whose frames have run out is complete although the team goes on
-                if (w.rank == 0 && time_idx == c.len[w.tid] && time_idx > 0) finish_row(p, w.tid);
-            }
-            int symbols_added = 0;
-            bool not_blank = true;
-            __syncthreads();
-            while (ok && not_blank && symbols_added < p.S) {
-                if (need_pred) {
-                    // the prediction network's step of Algorithm 1's inner loop; skipped when neither
-                    // input changed since the last evaluation (same result)
-                    ok = prediction_step<RG, WT>(p, w, sy, l);
-                    if (!ok) break;
-                    ++n_pred;
-                    need_pred = false;
-                    win_n = 0;
-                }
-                int off = 0;
-                if (symbols_added == 0 && time_idx >= win0 && time_idx < win0 + win_n) {
-                    off = time_idx - win0;
-                } else {
-                    const int n_ahead = min(la, max_out_len - time_idx);
-                    if (w.tid < kMaxSamples) {
-                        const int s = w.tid, i = s / R, r = s - i * R;
-                        const int fr = time_idx + i;
-                        const int valid = i < n_ahead && (i == 0 ? !c.mask[r] : fr < c.len[r]);
-                        c.s_row[s] = r; c.s_frame[s] = fr; c.s_valid[s] = valid;
-                        c.s_pidx[s] = valid ? c.b[r] * p.T + fr : -1;
-                        c.s_qoff[s] = p.q_in_lds ? (r / p.groups) * p.qstride : r;
+        } else {
+            bool need_pred = true;     // nothing computed yet for (last_label, hidden)
+            int flip = 0;              // slot of c.any the next inner step reports in
+            int win0 = 0, win_n = 0;   // frames [win0, win0 + win_n) have results for the current g
+            for (int time_idx = 0; ok && time_idx < max_out_len; ++time_idx) {
+                // Frames the window already covers and on which every row produced a blank change
+                // nothing but the frame index: they are passed over in one go (each would run the
+                // inner loop once, find all blank and leave).  Every thread reads the same results
+                // and takes the same decision.
+                if (!need_pred && time_idx > win0 && time_idx < win0 + win_n) {
+                    // (every wave looks at all results at once: lane s holds sample s = frame offset
+                    // s / R, row s % R, and the first label among the frames from time_idx on decides)
+                    int f;
+                    {
+                        const int s = w.lane & (kMaxSamples - 1), i = s / R, r = s - i * R;
+                        const int k = c.s_k[s], len_r = c.len[r];
+                        const bool label = w.lane < win_n * R && win0 + i >= time_idx && win0 + i < len_r && k != p.blank;
+                        const unsigned long long m = __ballot(label);
+                        f = m ? win0 + (__ffsll((long long)m) - 1) / R : win0 + win_n;
                     }
-                    if (w.tid == 0) c.ns = R * n_ahead;
-                    __syncthreads();
-                    ok = joint_step<RGJ, WT>(p, w, sy, l);
-                    if (!ok) break;
-                    ++n_joint; n_samples += R * n_ahead;
-                    win0 = time_idx; win_n = n_ahead;
-                }
-                if (w.tid == 0) {
-                    int any = 0;
-                    for (int r = 0; r < R; ++r) {
-                        if (c.mask[r]) continue;
-                        const int k = c.s_k[off * R + r];
-                        if (k == p.blank) { c.mask[r] = 1; }          // blank_mask |= (k == blank)
-                        else { emit_row(p, w, r, k, time_idx, c.s_v[off * R + r], c.s_lp[off * R + r], 0); any = 1; }
+                    if (f > time_idx) {
+                        // rows whose frames ran out on the way are complete
+                        if (w.rank == 0 && w.tid < R && c.len[w.tid] >= time_idx && c.len[w.tid] < f &&
+                            c.len[w.tid] > 0)
+                            finish_row(p, w.tid);
+                        time_idx = f;
+                        if (time_idx >= max_out_len) break;
                     }
-                    c.any[flip] = any;
                 }
+                if (w.tid < R) {
+                    c.mask[w.tid] = time_idx >= c.len[w.tid];   // blank_mask
+                    // a row whose frames have run out is complete although the team goes on
+                    if (w.rank == 0 && time_idx == c.len[w.tid] && time_idx > 0) finish_row(p, w.tid);
+                }
+                int symbols_added = 0;
+                bool not_blank = true;
                 __syncthreads();
-                // the next inner step reports in the other slot, and this slot is written again
-                // only after the barrier of that step: no second barrier is needed here
-                not_blank = c.any[flip] != 0;
-                flip ^= 1;
-                need_pred = need_pred || not_blank;
-                symbols_added += 1;
+                while (ok && not_blank && symbols_added < p.S) {
+                    if (need_pred) {
+                        // the prediction network's step of Algorithm 1's inner loop; skipped when neither
+                        // input changed since the last evaluation (same result)
+                        ok = prediction_step<RG, WT>(p, w, sy, l);
+                        if (!ok) break;
+                        ++n_pred;
+                        need_pred = false;
+                        win_n = 0;
+                    }
+                    int off = 0;
+                    if (symbols_added == 0 && time_idx >= win0 && time_idx < win0 + win_n) {
+                        off = time_idx - win0;
+                    } else {
+                        const int n_ahead = min(la, max_out_len - time_idx);
+                        if (w.tid < kMaxSamples) {
+                            const int s = w.tid, i = s / R, r = s - i * R;
+                            const int fr = time_idx + i;
+                            const int valid = i < n_ahead && (i == 0 ? !c.mask[r] : fr < c.len[r]);
+                            c.s_row[s] = r; c.s_frame[s] = fr; c.s_valid[s] = valid;
+                            c.s_pidx[s] = valid ? c.b[r] * p.T + fr : -1;
+                            c.s_qoff[s] = p.q_in_lds ? (r / p.groups) * p.qstride : r;
+                        }
+                        if (w.tid == 0) c.ns = R * n_ahead;
+                        __syncthreads();
+                        ok = joint_step<RGJ, WT>(p, w, sy, l);
+                        if (!ok) break;
+                        ++n_joint; n_samples += R * n_ahead;
+                        win0 = time_idx; win_n = n_ahead;
+                    }
+                    if (w.tid == 0) {
+                        int any = 0;
+                        for (int r = 0; r < R; ++r) {
+                            if (c.mask[r]) continue;
+                            const int k = c.s_k[off * R + r];
+                            if (k == p.blank) { c.mask[r] = 1; }          // blank_mask |= (k == blank)
+                            else { emit_row(p, w, r, k, time_idx, c.s_v[off * R + r], c.s_lp[off * R + r], 0); any = 1; }
+                        }
+                        c.any[flip] = any;
+                    }
+                    __syncthreads();
+                    // the next inner step reports in the other slot, and this slot is written again
+                    // only after the barrier of that step: no second barrier is needed here
+                    not_blank = c.any[flip] != 0;
+                    flip ^= 1;
+                    need_pred = need_pred || not_blank;
+                    symbols_added += 1;
+                }
             }
         }
     } else {

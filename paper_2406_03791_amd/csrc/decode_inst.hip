@@ -1,6 +1,7 @@
 // One instantiation unit of the persistent decode kernel (decode_impl.h).  The build compiles
 // this file once per (loop nest, prediction row groups, weight storage) with
-//   -DRNNT_INST_NEST=f|l     Algorithm 1 (frame looping) or label looping / TDT
+//   -DRNNT_INST_NEST=f|l|s   Algorithm 1 (frame looping), label looping / TDT, or Algorithm 1 for
+//                            teams of one utterance (row groups 1 only)
 //   -DRNNT_INST_RG=1|2|4     row groups (of 4 utterances) of a team in the prediction stages
 //   -DRNNT_INST_WT=f32|bf16|fp8|bf16a|fp8a|fp4a   storage of the packed weights (bf16a: the bfloat16 mode;
 //                            fp8a / fp4a: the bfloat16 mode with e4m3- / e2m1-stored weights)
@@ -12,6 +13,7 @@
 #define RNNT_CAT5(a, b, c, d, e) RNNT_CAT5_(a, b, c, d, e)
 #define RNNT_NEST_f kFrameLooping
 #define RNNT_NEST_l kLabelLooping
+#define RNNT_NEST_s kFrameLoopingSingle
 #define RNNT_WT_f32 kWeightF32
 #define RNNT_WT_bf16 kWeightBf16
 #define RNNT_WT_fp8 kWeightFp8

@@ -9,6 +9,8 @@
 namespace rnnt {
 
 enum Variant { kFrameLooping = 0, kLabelLooping = 1, kTdtLabelLooping = 2 };
+// Kernel instance of Algorithm 1 for teams of one utterance (chosen by the launch, never a caller's variant).
+constexpr int kFrameLoopingSingle = 3;
 
 // Packed weights of one dense stage on the device.
 struct StageDev {
