@@ -79,10 +79,14 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream)
         {{launch_decode_f1_fp4a, launch_decode_f2_fp4a, launch_decode_f4_fp4a},
          {launch_decode_l1_fp4a, launch_decode_l2_fp4a, launch_decode_l4_fp4a}}};
     if (p.wt < 0 || p.wt >= kWeightTypes) return hipErrorInvalidValue;
-    // Algorithm 1 with one utterance per team has an instance of its own
+    // Algorithm 1 with one utterance per team has an instance of its own.  For a single row the
+    // label-looping schedule of an RNN-T is the same sequence of prediction and joint steps
+    // (the two differ in how a batch is kept in step), so such teams use it too; TDT and
+    // multi-blank models have rules of their own for the frame index and stay with theirs.
     static const Launch single[kWeightTypes] = {launch_decode_s1_f32, launch_decode_s1_bf16, launch_decode_s1_fp8,
                                                 launch_decode_s1_bf16a, launch_decode_s1_fp8a, launch_decode_s1_fp4a};
-    if (p.variant == kFrameLooping && rows == 1) return single[p.wt](p, rgj, stream);
+    const bool plain_label = p.variant == kLabelLooping && p.D == 0 && p.VT == p.V1 && p.groups == 1;
+    if ((p.variant == kFrameLooping || plain_label) && rows == 1) return single[p.wt](p, rgj, stream);
     return table[p.wt][p.variant == kFrameLooping ? 0 : 1][rgi](p, rgj, stream);
 }
 
