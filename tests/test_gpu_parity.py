@@ -862,3 +862,51 @@ def test_weight_only_4_bit_quantised_models(pkg):
         with pytest.raises(pkg.RnntError) as err:
             pkg.Engine(model, w.B, w.T, flags=fl)
         assert err.value.code == -2
+
+
+def test_random_shapes_layouts_and_lookaheads(pkg):
+    """Seeded random models (widths that are multiples of 4 and nothing else in particular, 1-4
+    layers, vocabularies of 2-200, with and without durations), batches, team layouts, joint
+    groups, lookaheads and max_symbols, fp32 and the bfloat16 mode: each case against the oracle.
+    A layout the planner refuses (it does not divide the device, or does not fit) is skipped."""
+    rng = np.random.default_rng(2406)
+    ran = 0
+    for case in range(136):
+        big = case >= 120                      # the last cases: wide layers, large vocabularies, up to 96 utterances
+        tdt = bool(rng.integers(0, 3) == 0)
+        durations = tuple(sorted(set([0] + list(rng.integers(1, 5, size=rng.integers(1, 4)))))) if tdt else ()
+        dims = synth.ModelDims(F=int(rng.choice([16, 48, 128])), E=int(rng.integers(4, 80)),
+                               H=4 * int(rng.integers(100, 257) if big else rng.integers(1, 41)),
+                               L=int(rng.integers(1, 5)),
+                               J=4 * int(rng.integers(100, 257) if big else rng.integers(1, 61)),
+                               V1=int(rng.integers(500, 5001) if big else rng.integers(2, 201)),
+                               durations=tuple(int(d) for d in durations))
+        model = synth.make_model(dims, seed=1000 + case, weight_range=0.3 if not big else 0.1,
+                                 blank_bias=float(rng.uniform(0.5, 2.0)))
+        B, T, S = int(rng.integers(1, 97 if big else 49)), int(rng.integers(4, 21 if big else 31)), int(rng.integers(1, 5))
+        x, ln = synth.make_inputs(5000 + case, B, T, dims.F, max(1, T // 3), T, pad="nan")
+        bf16 = bool(rng.integers(0, 3) == 0)
+        variants = ("tdt",) if tdt else ("frame", "label")
+        w = synth.Workload(f"random{case}", variants[0], model, x, ln, S)
+        n_teams = int(rng.choice([0, 0, 4, 8, 16, 32]))
+        groups = int(rng.choice([1, 2, 4])) if n_teams else 0
+        la = int(rng.choice([0, 0, 1, 3, 8]))
+        try:
+            eng = pkg.Engine(model, B, T, flags=pkg.RNNT_FLAG_BF16_ARITHMETIC if bf16 else 0)
+        except pkg.RnntError as err:        # the model's state for this many utterances does not fit a compute unit
+            assert err.code == -5 and big, (err, dims, B)
+            log(f"random {case}: refused (-5) {dims} B={B}")
+            continue
+        try:
+            eng.configure(n_teams=n_teams, joint_groups=groups, lookahead=la)
+        except pkg.RnntError as err:
+            assert err.code in (-2, -5), err
+            eng.close()
+            continue
+        for variant in variants:
+            check(pkg, w, variant, f"random {case}: {dims} B={B} T={T} S={S} teams={n_teams}/{groups} la={la} bf16={bf16}",
+                  engine=eng, bf16=bf16, logp=(variant != "frame"))
+        ran += 1
+        eng.close()
+    log(f"random cases run: {ran}")
+    assert ran >= 90
