@@ -262,8 +262,10 @@ int rnnt_quantize_blocks_e2m1(const float *w, int64_t rows, int64_t cols, float 
  * RNNT_ERR_UNSUPPORTED (decode a larger batch in several calls).  The argmax
  * candidates of a joint step sit there too, one per sample and group of four
  * output columns of a rank: vocabularies of a few thousand labels fit for any
- * batch, 16 385 labels only for engines of a few utterances, and much larger
- * ones are refused the same way.
+ * batch, tens of thousands only for engines of a few utterances.  When the
+ * preferred team layout does not fit, the engine tries the others that divide
+ * the device (fewer joint groups, then more teams, then fewer) before it
+ * refuses.
  * Synchronous.  *out is set only on success.
  */
 int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T,

@@ -376,20 +376,27 @@ int default_layouts(rnnt_engine *e)
     int nf = max_B <= 2 ? 4 : (max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32));
     while (nf > 1 && e->n_wg % nf != 0) nf /= 2;
     while ((max_B + nf - 1) / nf > kMaxRows) nf *= 2;
-    int rc = plan_and_pack(e, e->frame_cfg, nf, 1);
+    // A layout whose state does not fit the compute units' local memory (wide layers, many
+    // layers, many rows per team) is followed by the others that divide the device, teams
+    // with fewer rows first, before the engine is refused.
+    auto with_fallbacks = [&](TeamConfig &cfg, int first, int groups_first) {
+        int rc = plan_and_pack(e, cfg, first, groups_first);
+        for (int g = groups_first / 2; rc == RNNT_ERR_UNSUPPORTED && g >= 1; g /= 2) rc = plan_and_pack(e, cfg, first, g);
+        for (int n = first * 2; rc == RNNT_ERR_UNSUPPORTED && n <= e->n_wg / 2; n *= 2)
+            if (e->n_wg % n == 0) rc = plan_and_pack(e, cfg, n, 1);
+        for (int n = first / 2; rc == RNNT_ERR_UNSUPPORTED && n >= 1; n /= 2)
+            if (e->n_wg % n == 0 && (max_B + n - 1) / n <= kMaxRows) rc = plan_and_pack(e, cfg, n, 1);
+        return rc;
+    };
+    int rc = with_fallbacks(e->frame_cfg, nf, 1);
     if (rc) return rc;
     int nl = max_B <= 2 ? 4 : (max_B <= 16 ? 8 : 16);
     while (nl > 1 && e->n_wg % nl != 0) nl /= 2;
     while ((max_B + nl - 1) / nl > kMaxRows) nl *= 2;
     const int rows = (max_B + nl - 1) / nl;
     const int ts = e->n_wg / nl;
-    int groups = (max_B > 8 && rows >= 2 && ts % 2 == 0 && ts / 2 >= 8) ? 2 : 1;
-    rc = plan_and_pack(e, e->label_cfg, nl, groups);
-    while (rc == RNNT_ERR_UNSUPPORTED && groups > 1) {
-        groups /= 2;
-        rc = plan_and_pack(e, e->label_cfg, nl, groups);
-    }
-    return rc;
+    const int groups = (max_B > 8 && rows >= 2 && ts % 2 == 0 && ts / 2 >= 8) ? 2 : 1;
+    return with_fallbacks(e->label_cfg, nl, groups);
 }
 
 int fetch(std::vector<float> &dst, const float *dev, size_t n)

@@ -349,12 +349,15 @@ def test_wide_joint_and_wide_hidden_layers(pkg):
 
 
 def test_four_layers_and_large_vocabularies(pkg):
-    """The largest layer count (4), and vocabularies of 4 097 and 16 385 labels (513 output groups
-    per rank of a joint group of 8): the second fits the local memory only for engines of few
-    utterances, and a vocabulary of 60 001 is refused when the engine is created."""
+    """The largest layer count (4), and vocabularies of 4 097, 16 385 and 60 001 labels: the
+    argmax candidates of the large ones fit the local memory only for engines of few utterances
+    and, for the largest, only in a layout with more work-groups per team than the preferred
+    one, which the engine falls back to; a vocabulary beyond the 16-bit column index of the
+    argmax exchange is refused when the engine is created."""
     for dims, bias, sizes in ((synth.ModelDims(F=64, E=64, H=320, L=4, J=320, V1=129), 1.0, (3, 40)),
                               (synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=4097), 1.5, (3, 40)),
-                              (synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=16385), 2.0, (3,))):
+                              (synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=16385), 2.0, (3,)),
+                              (synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=60001), 1.1, (3,))):
         model = synth.make_model(dims, seed=41, weight_range=0.1, blank_bias=bias)
         for B in sizes:
             x, ln = synth.make_inputs(93, B, 24, dims.F, 10, 24, pad="nan")
@@ -363,7 +366,7 @@ def test_four_layers_and_large_vocabularies(pkg):
             for variant in ("frame", "label"):
                 check(pkg, w, variant, f"L={dims.L} V1={dims.V1} B={B}", engine=eng, logp=(variant == "label"))
             eng.close()
-    big = synth.make_model(synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=60001), seed=41)
+    big = synth.make_model(synth.ModelDims(F=64, E=64, H=320, L=1, J=320, V1=65536), seed=41)
     with pytest.raises(pkg.RnntError) as err:
         pkg.Engine(big, 3, 24)
     assert err.value.code == -5
