@@ -870,7 +870,8 @@ def test_weight_only_4_bit_quantised_models(pkg):
 def test_random_shapes_layouts_and_lookaheads(pkg):
     """Seeded random models (widths that are multiples of 4 and nothing else in particular, 1-4
     layers, vocabularies of 2-200, with and without durations), batches, team layouts, joint
-    groups, lookaheads and max_symbols, fp32 and the bfloat16 mode: each case against the oracle.
+    groups, lookaheads and max_symbols, fp32 and the bfloat16 mode with bf16, e4m3 and e2m1
+    storage: each case against the oracle.
     A layout the planner refuses (it does not divide the device, or does not fit) is skipped."""
     rng = np.random.default_rng(2406)
     ran = 0
@@ -888,14 +889,22 @@ def test_random_shapes_layouts_and_lookaheads(pkg):
                                  blank_bias=float(rng.uniform(0.5, 2.0)))
         B, T, S = int(rng.integers(1, 97 if big else 49)), int(rng.integers(4, 21 if big else 31)), int(rng.integers(1, 5))
         x, ln = synth.make_inputs(5000 + case, B, T, dims.F, max(1, T // 3), T, pad="nan")
-        bf16 = bool(rng.integers(0, 3) == 0)
+        form = str(rng.choice(["f32", "f32", "bf16", "e4m3", "e2m1"]))
+        bf16 = form != "f32"
+        flags = pkg.RNNT_FLAG_BF16_ARITHMETIC if bf16 else 0
+        if form == "e4m3":      # weights quantised by the oracle's quantisers, stored as codes with scales
+            model = synth.with_streamed_weights(model, lambda a: oracle.quantize_rows_e4m3(a)[0])
+            flags |= pkg.RNNT_FLAG_FP8_WEIGHTS
+        elif form == "e2m1":
+            model = synth.with_streamed_weights(model, lambda a: oracle.quantize_blocks_e2m1(a)[0])
+            flags |= pkg.RNNT_FLAG_FP4_WEIGHTS
         variants = ("tdt",) if tdt else ("frame", "label")
         w = synth.Workload(f"random{case}", variants[0], model, x, ln, S)
         n_teams = int(rng.choice([0, 0, 4, 8, 16, 32]))
         groups = int(rng.choice([1, 2, 4])) if n_teams else 0
         la = int(rng.choice([0, 0, 1, 3, 8]))
         try:
-            eng = pkg.Engine(model, B, T, flags=pkg.RNNT_FLAG_BF16_ARITHMETIC if bf16 else 0)
+            eng = pkg.Engine(model, B, T, flags=flags)
         except pkg.RnntError as err:        # the model's state for this many utterances does not fit a compute unit
             assert err.code == -5 and big, (err, dims, B)
             log(f"random {case}: refused (-5) {dims} B={B}")
@@ -907,7 +916,7 @@ def test_random_shapes_layouts_and_lookaheads(pkg):
             eng.close()
             continue
         for variant in variants:
-            check(pkg, w, variant, f"random {case}: {dims} B={B} T={T} S={S} teams={n_teams}/{groups} la={la} bf16={bf16}",
+            check(pkg, w, variant, f"random {case}: {dims} B={B} T={T} S={S} teams={n_teams}/{groups} la={la} {form}",
                   engine=eng, bf16=bf16, logp=(variant != "frame"))
         ran += 1
         eng.close()
