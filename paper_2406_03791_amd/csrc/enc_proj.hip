@@ -1,6 +1,7 @@
 // Encoder-side joint projection  P[b, t, :] = W_enc x[b, t, :] + b_enc  for every
-// valid frame, as one fp32 MFMA GEMM (v_mfma_f32_32x32x2_f32), and the one-time
-// folding of the embedding table into the first LSTM layer's input term.
+// valid frame, as one MFMA GEMM (fp32: v_mfma_f32_32x32x2_f32; bfloat16 mode:
+// v_mfma_f32_32x32x8_bf16_1k), and the one-time folding of the embedding table into the
+// first LSTM layer's input term.
 #include "engine.h"
 
 namespace rnnt {
@@ -24,9 +25,7 @@ __device__ __forceinline__ float bf16_rne(float v)
 // B = 128 with the smaller tile).
 // Tiles that start at or beyond enc_len[b] do nothing; rows at t >= enc_len[b]
 // inside a tile are computed and not stored.
-// ROUND_X: bfloat16 mode, the frames are rounded to bfloat16 as they enter the product (the
-// engine's copy of W_enc has been rounded once); products of two such values are exact in fp32.
-template <bool ROUND_X, int BM>
+template <int BM>
 __global__ void __launch_bounds__(256)
 enc_proj_kernel(const float *__restrict__ x, const int *__restrict__ enc_len,
                 const float *__restrict__ w_enc, const float *__restrict__ b_enc,
@@ -82,13 +81,8 @@ enc_proj_kernel(const float *__restrict__ x, const int *__restrict__ enc_len,
         for (int i = 0; i < 2; ++i) {
             const int kk = a_k4[i] * 4, r = a_row[i];
             if (i < NA) {
-                if (ROUND_X) {
-                    As[kk + 0][r] = bf16_rne(ra[i].x); As[kk + 1][r] = bf16_rne(ra[i].y);
-                    As[kk + 2][r] = bf16_rne(ra[i].z); As[kk + 3][r] = bf16_rne(ra[i].w);
-                } else {
-                    As[kk + 0][r] = ra[i].x; As[kk + 1][r] = ra[i].y;
-                    As[kk + 2][r] = ra[i].z; As[kk + 3][r] = ra[i].w;
-                }
+                As[kk + 0][r] = ra[i].x; As[kk + 1][r] = ra[i].y;
+                As[kk + 2][r] = ra[i].z; As[kk + 3][r] = ra[i].w;
             }
             Bs[kk + 0][r] = rb[i].x; Bs[kk + 1][r] = rb[i].y;
             Bs[kk + 2][r] = rb[i].z; Bs[kk + 3][r] = rb[i].w;
@@ -132,6 +126,125 @@ enc_proj_kernel(const float *__restrict__ x, const int *__restrict__ enc_len,
         }
 }
 
+// The same product in the bfloat16 mode, on the bf16 matrix cores (v_mfma_f32_32x32x8_bf16_1k):
+// the frames are rounded to bfloat16 (ties to even) as they are staged, the engine's copy of
+// W_enc holds bfloat16 values already (its low halves are zero), products are exact in fp32 and
+// the sums are fp32.  Both operands have K contiguous in memory, which is what the instruction
+// wants per lane (four consecutive k of one row), so the tiles sit in LDS row-major as bf16 and
+// nothing is transposed.  Same grid and wave arrangement as the fp32 kernel, K tiles of 32.
+typedef short v4s_ __attribute__((ext_vector_type(4)));
+constexpr int KTB = 32, LDB = KTB + 4;       // bf16 per LDS row: 72 bytes, 8-byte aligned rows
+
+__device__ __forceinline__ uint2 pack_bf16x4_rne(float4 v)
+{
+    const unsigned a = __float_as_uint(bf16_rne(v.x)) >> 16, b = __float_as_uint(bf16_rne(v.y)) >> 16;
+    const unsigned c = __float_as_uint(bf16_rne(v.z)) >> 16, d = __float_as_uint(bf16_rne(v.w)) >> 16;
+    return make_uint2(a | (b << 16), c | (d << 16));
+}
+
+template <int BM>
+__global__ void __launch_bounds__(256)
+enc_proj_bf16_kernel(const float *__restrict__ x, const int *__restrict__ enc_len,
+                     const float *__restrict__ w_enc, const float *__restrict__ b_enc,
+                     float *__restrict__ proj, int T, int F, int J)
+{
+    constexpr int MI = BM / 64;
+    constexpr int NA = BM / 32;          // float4 of A a thread stages per K tile (BM * 8 / 256)
+    constexpr int NB = BN / 32;
+    __shared__ __align__(16) unsigned short As[BM][LDB];
+    __shared__ __align__(16) unsigned short Bs[BN][LDB];
+    const int b = blockIdx.z;
+    int len = enc_len[b];
+    len = min(max(len, 0), T);
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    if (m0 >= len) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const float *xa = x + (long long)b * T * F;
+    // float4 number idx of a tile: row idx / 8, k = 4 * (idx % 8)
+    const float *a_src[NA], *b_src[NB];
+    bool b_ok[NB];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int idx = tid + i * 256;
+        a_src[i] = xa + (long long)min(m0 + (idx >> 3), T - 1) * F + (idx & 7) * 4;
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int idx = tid + i * 256, n = n0 + (idx >> 3);
+        b_ok[i] = n < J;
+        b_src[i] = w_enc + (long long)min(n, J - 1) * F + (idx & 7) * 4;
+    }
+    v16f acc[MI][2];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    float4 ra[NA], rb[NB];
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    // K is a multiple of 16 (checked when the engine is created); a last half tile reads zeros
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            ra[i] = zero4;
+            if (k0 + ((tid + i * 256) & 7) * 4 < F) ra[i] = *reinterpret_cast<const float4 *>(a_src[i] + k0);
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            rb[i] = zero4;
+            if (b_ok[i] && k0 + ((tid + i * 256) & 7) * 4 < F) rb[i] = *reinterpret_cast<const float4 *>(b_src[i] + k0);
+        }
+    };
+    fetch(0);
+    const int kh = lane >> 5, c = lane & 31;
+    for (int k0 = 0; k0 < F; k0 += KTB) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int idx = tid + i * 256;
+            *reinterpret_cast<uint2 *>(&As[idx >> 3][(idx & 7) * 4]) = pack_bf16x4_rne(ra[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int idx = tid + i * 256;
+            // the weights are bfloat16 values: their upper halves are the codes
+            const uint2 wv = make_uint2((__float_as_uint(rb[i].x) >> 16) | (__float_as_uint(rb[i].y) & 0xffff0000u),
+                                        (__float_as_uint(rb[i].z) >> 16) | (__float_as_uint(rb[i].w) & 0xffff0000u));
+            *reinterpret_cast<uint2 *>(&Bs[idx >> 3][(idx & 7) * 4]) = wv;
+        }
+        __syncthreads();
+        if (k0 + KTB < F) fetch(k0 + KTB);
+#pragma unroll
+        for (int ks = 0; ks < KTB / 8; ++ks) {
+            const int k = ks * 8 + kh * 4;
+            const v4s_ b0 = *reinterpret_cast<const v4s_ *>(&Bs[wn * 64 + c][k]);
+            const v4s_ b1 = *reinterpret_cast<const v4s_ *>(&Bs[wn * 64 + 32 + c][k]);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const v4s_ a = *reinterpret_cast<const v4s_ *>(&As[wm * 32 * MI + mi * 32 + c][k]);
+                acc[mi][0] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, b0, acc[mi][0], 0, 0, 0);
+                acc[mi][1] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, b1, acc[mi][1], 0, 0, 0);
+            }
+        }
+    }
+    // accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int col = n0 + wn * 64 + ni * 32 + c;
+            if (col >= J) continue;
+            const float bias = b_enc[col];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * 32 * MI + mi * 32 + 8 * (v >> 2) + 4 * kh + (v & 3);
+                if (row < len) proj[((long long)b * T + row) * J + col] = acc[mi][ni][v] + bias;
+            }
+        }
+}
+
 hipError_t launch_encoder_projection(const float *enc_out, const int *enc_len, const float *w_enc,
                                      const float *b_enc, float *proj, int B, int T, int F, int J,
                                      bool round_x, hipStream_t stream)
@@ -143,17 +256,17 @@ hipError_t launch_encoder_projection(const float *enc_out, const int *enc_len, c
     const dim3 grid((T + bm - 1) / bm, (J + BN - 1) / BN, B);
     if (small_tile) {
         if (round_x)
-            hipLaunchKernelGGL((enc_proj_kernel<true, 64>), grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
+            hipLaunchKernelGGL((enc_proj_bf16_kernel<64>), grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
                                b_enc, proj, T, F, J);
         else
-            hipLaunchKernelGGL((enc_proj_kernel<false, 64>), grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
+            hipLaunchKernelGGL((enc_proj_kernel<64>), grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
                                b_enc, proj, T, F, J);
     } else {
         if (round_x)
-            hipLaunchKernelGGL((enc_proj_kernel<true, 128>), grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
+            hipLaunchKernelGGL((enc_proj_bf16_kernel<128>), grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
                                b_enc, proj, T, F, J);
         else
-            hipLaunchKernelGGL((enc_proj_kernel<false, 128>), grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
+            hipLaunchKernelGGL((enc_proj_kernel<128>), grid, dim3(256), 0, stream, enc_out, enc_len, w_enc,
                                b_enc, proj, T, F, J);
     }
     return hipGetLastError();
