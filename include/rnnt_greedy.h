@@ -256,10 +256,14 @@ int rnnt_quantize_blocks_e2m1(const float *w, int64_t rows, int64_t cols, float 
  * [0, V1) and positive sizes are RNNT_ERR_SHAPE.
  * The two bias vectors of an LSTM layer are added once on the host while the
  * weights are repacked (b_ih + b_hh in fp32).
- * A team of work-groups holds at most 16 utterances and its state has to fit
- * the compute units' local memory: with the Parakeet shape on 256 compute
- * units max_B up to 256 is accepted, a larger one returns
- * RNNT_ERR_UNSUPPORTED (decode a larger batch in several calls).  The argmax
+ * max_B itself has no limit but memory (the projected frames take
+ * max_B * max_T * J floats): a call with more than 128 utterances is decoded
+ * by consecutive launches of up to 128 utterances each, in the caller's order,
+ * after one projection of the whole batch (on MI355X that is faster than
+ * larger launches); status word and statistics cover the whole call, and
+ * completion flags are raised launch by launch.  The state of a team of
+ * work-groups has to fit the compute units' local memory; a model for which
+ * no team layout does returns RNNT_ERR_UNSUPPORTED.  The argmax
  * candidates of a joint step sit there too, one per sample and group of four
  * output columns of a rank: vocabularies of a few thousand labels fit for any
  * batch, tens of thousands only for engines of a few utterances.  When the

@@ -1852,10 +1852,11 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
     }
     if (w.rank == 0 && w.tid == 0) {
         long long *sp = p.stats + (long long)w.team * kStatStride;
-        sp[kStatPred] = n_pred; sp[kStatJoint] = n_joint; sp[kStatSamples] = n_samples;
-        sp[kStatPolls] = sy.polls;
+        // (added: the launches of one call share the counters, the reset kernel zeroes them first)
+        sp[kStatPred] += n_pred; sp[kStatJoint] += n_joint; sp[kStatSamples] += n_samples;
+        sp[kStatPolls] += sy.polls;
 #ifdef RNNT_PROFILE
-        for (int i = 0; i < 24; ++i) sp[kStatCount + i] = g_prof[i];
+        for (int i = 0; i < 24; ++i) sp[kStatCount + i] += g_prof[i];
 #endif
     } else if (!ok && w.tid == 0) {
         __hip_atomic_fetch_or(as_global(p.status), 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -90,7 +90,9 @@ struct DecodeParams {
     int *xcc;                     // [n_teams * team_size]
 };
 
-hipError_t launch_decode(const DecodeParams &p, hipStream_t stream);
+// first: the call's first launch (a call of many utterances takes several): status word and step
+// counts start at zero; later launches add to them.
+hipError_t launch_decode(const DecodeParams &p, bool first, hipStream_t stream);
 
 // Keeps the text of a failed HIP call for rnnt_status_string; returns RNNT_ERR_HIP.
 int hip_fail(hipError_t e, const char *what);

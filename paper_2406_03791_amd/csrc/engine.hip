@@ -42,6 +42,12 @@ namespace {
     } while (0)
 
 constexpr int kLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit
+// Utterances one launch of the decode kernel takes.  A call with more is decoded in consecutive
+// launches of up to this many (the projection runs once for the whole call): with more than 8
+// rows per team the joint steps hold few frames per row and the prediction stages run on four
+// row groups, and one launch of 256 utterances measured 29 ms against 2 x 10.8 ms for two of 128
+// (label looping; Algorithm 1 52 against 2 x 19 ms, TDT 16.6 against 2 x 5.9 ms).
+constexpr int kLaunchRows = 128;
 constexpr int kStaticLds = 3072;        // kept free for the kernel's static LDS (control block)
 
 // Scratch of the entry point that allocates nothing (rnnt_label_looping_decode_noalloc): the
@@ -116,6 +122,7 @@ struct rnnt_engine {
     rnnt_model_desc d{};
     int durations[kMaxDur] = {0};
     int NOUT = 0, max_B = 0, max_T = 0;
+    int plan_B = 0;        // utterances the team layouts are planned for: min(max_B, kLaunchRows)
     int n_wg = 0;          // work-groups the device can keep resident (one per CU)
     int lookahead = 0;
     int search_steps = 0;  // 0: chosen per call, -1: no limit, > 0: as given
@@ -180,7 +187,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     const int ts = e->n_wg / n_teams;
     if (ts < 1 || ts % groups != 0) return RNNT_ERR_SHAPE;
     const int tj = ts / groups;
-    const int rows_max = (e->max_B + n_teams - 1) / n_teams;
+    const int rows_max = (e->plan_B + n_teams - 1) / n_teams;
     if (rows_max > kMaxRows) return RNNT_ERR_SHAPE;
     const int H = d.H, L = d.L, J = d.J;
     auto nu_of = [&](int r) { return range_hi(r, ts, H) - range_lo(r, ts, H); };
@@ -372,7 +379,7 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
 //   teams of 32 there, equal from four utterances on; teams of 128 and 256 are slower).
 int default_layouts(rnnt_engine *e)
 {
-    const int max_B = e->max_B;
+    const int max_B = e->plan_B;
     int nf = max_B <= 2 ? 4 : (max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32));
     while (nf > 1 && e->n_wg % nf != 0) nf /= 2;
     while ((max_B + nf - 1) / nf > kMaxRows) nf *= 2;
@@ -486,15 +493,13 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.VT = d.V1;
     if (e->multi_blank) { p.VT = e->NOUT; p.D = 0; }   // one distribution over labels, blank and big blanks
     for (int i = 0; i < kMaxDur; ++i) p.durations[i] = e->durations[i];
-    p.B = B; p.T = T; p.S = S; p.cap = cap; p.variant = variant;
+    p.T = T; p.S = S; p.cap = cap; p.variant = variant;
     p.n_teams = t.n_teams; p.team_size = t.team_size;
     p.groups = t.groups; p.jteam_size = t.jteam_size;
     p.serpentine = 1;
     p.spread = spread_layout(t) ? 1 : 0;
     p.plain_launch = e->plain_launch ? 1 : 0;
     p.wt = e->wt;
-    p.lookahead = effective_lookahead(e, t, B);
-    p.search_steps = effective_search_steps(e, t, B);
     p.xstride = t.xstride; p.nu_max = t.nu_max; p.gj_max = t.gj_max;
     p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
     p.lds_scale = t.lds_scale; p.sc_nb_in = t.sc_nb_in;
@@ -509,11 +514,6 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     p.rg_planned = t.rg_planned;
     p.samples_cap = t.samples_cap;
     p.spin_limit = 1u << 22;
-    p.enc_len = enc_len; p.P = ws.P;
-    p.tokens = tokens_out; p.tok_len = tok_len_out; p.frames = frames_out; p.logits = logit_out;
-    p.durs = durs_out;
-    p.logps = e->logp_out;
-    p.done = e->done;
     p.st0 = dev_stage(t.st0);
     for (int l = 1; l < d.L; ++l) p.stl[l] = dev_stage(t.stl[l]);
     p.spred = dev_stage(t.spred);
@@ -528,7 +528,22 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     e->last_B = B;
     e->last_cfg = &t;
     e->last_ws = ws;
-    HIP_TRY(launch_decode(p, stream));
+    // the utterances [off, off + nb) per launch; status word and step counts add up over the launches
+    for (int off = 0; off < B; off += kLaunchRows) {
+        const int nb = std::min(kLaunchRows, B - off);
+        const long long oc = (long long)off * cap;
+        p.B = nb;
+        p.lookahead = effective_lookahead(e, t, nb);
+        p.search_steps = effective_search_steps(e, t, nb);
+        p.enc_len = enc_len + off; p.P = ws.P + (long long)off * T * d.J;
+        p.tokens = tokens_out + oc; p.tok_len = tok_len_out + off;
+        p.frames = frames_out ? frames_out + oc : nullptr;
+        p.logits = logit_out ? logit_out + oc : nullptr;
+        p.durs = durs_out ? durs_out + oc : nullptr;
+        p.logps = e->logp_out ? e->logp_out + oc : nullptr;
+        p.done = e->done ? e->done + off : nullptr;
+        HIP_TRY(launch_decode(p, off == 0, stream));
+    }
     HIP_TRY(hipEventRecord(e->ev[2], stream));
     e->timed = true;
     return RNNT_OK;
@@ -587,6 +602,7 @@ int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T
     for (int i = 0; i < d.D; ++i) e->durations[i] = d.durations[i];
     e->NOUT = d.V1 + d.D;
     e->max_B = max_B; e->max_T = max_T;
+    e->plan_B = std::min((int)max_B, kLaunchRows);
     e->wt = (flags & RNNT_FLAG_FP8_WEIGHTS) ? kWeightFp8
                                             : ((flags & RNNT_FLAG_BF16_WEIGHTS) ? kWeightBf16 : kWeightF32);
     if (flags & RNNT_FLAG_BF16_ARITHMETIC)

@@ -213,18 +213,39 @@ def test_host_side_errors(pkg):
     with pytest.raises(pkg.RnntError) as ei:
         pkg.rnnt_encoder_projection(eng.handle, shifted, ln, 1, w.T, torch.zeros(1, w.T, 64, device="cuda"))
     assert ei.value.code == -2
-    # a batch too large for the team layouts is refused when the engine is created
+    # more frames than 32-bit frame numbers can count are refused when the engine is created
     w2 = synth.make_workload(2, B=1, T=8, len_lo=8, len_hi=8)
     with pytest.raises(pkg.RnntError) as ei:
-        pkg.Engine(w2.model, 1024, 8)
+        pkg.Engine(w2.model, 1 << 20, 1 << 12)
     assert ei.value.code == -5
 
 
-def test_max_batch_of_the_parakeet_shape(pkg):
-    # 256 utterances: 8 rows per team in frame looping, 16 in label looping
-    w = synth.make_workload(2, pad="nan", B=256, T=40, len_lo=10, len_hi=40)
-    check(pkg, w, "frame", "parakeet256")
-    check(pkg, w, "label", "parakeet256")
+def test_calls_of_more_utterances_than_one_launch_takes(pkg):
+    """A call with more than 128 utterances is decoded by consecutive launches of up to 128: 256
+    (two full launches), 300 and 129 (a last launch of 44 and of one utterance) on one engine,
+    all decoders, completion flags, log-probabilities, and the call's status and step counts;
+    also small batches on an engine whose layouts were planned for 128 (four joint groups)."""
+    w = synth.make_workload(2, pad="nan", B=300, T=40, len_lo=10, len_hi=40)
+    eng = pkg.Engine(w.model, 300, w.T)
+    import dataclasses
+    for B in (300, 256, 129, 128, 17, 3, 1):
+        wb = dataclasses.replace(w, enc_out=w.enc_out[:B].copy(), enc_len=w.enc_len[:B].copy())
+        _, _, st_f = check(pkg, wb, "frame", f"parakeet300/{B}", engine=eng)
+        _, _, st_l = check(pkg, wb, "label", f"parakeet300/{B}", engine=eng, logp=True)
+        # every utterance takes at least one prediction step in either decoder
+        assert st_f["pred_steps"] >= B and st_l["pred_steps"] >= 1
+    eng.close()
+    w4 = synth.make_workload(4, pad="nan", B=200, T=40, len_lo=10, len_hi=40)
+    check(pkg, w4, "tdt", "tdt200")
+    # a length out of range in the second launch still sets the call's status bit
+    wc = dataclasses.replace(w, enc_len=w.enc_len.copy())
+    wc.enc_len[250] = w.T + 5
+    eng = pkg.Engine(w.model, 300, w.T)
+    x = torch.from_numpy(np.nan_to_num(wc.enc_out)).cuda().contiguous()
+    eng.decode("label", x, torch.from_numpy(wc.enc_len.astype(np.int32)).cuda(), wc.max_symbols)
+    torch.cuda.synchronize()
+    assert eng.status() & 1
+    eng.close()
 
 
 def test_cfg2_cut_and_tdt_cut(pkg):
@@ -515,11 +536,18 @@ def test_full_size_label_looping_with_scores_and_compact_storage(pkg):
 
 def test_row_group_counts_between_the_kernel_instances(pkg):
     """Teams of 9-12 utterances run the prediction kernels built for 16 rows: the LDS layout has
-    to be sized for the instance, not for the rows.  max_B = 160 in label looping (10 rows per
-    team) and 4 teams with 40 utterances."""
+    to be sized for the instance, not for the rows.  96 utterances on 8 teams (12 rows per
+    team), 4 teams with 40 utterances (10 rows), and 160 utterances in the default layouts (two
+    launches)."""
     w = synth.make_workload(3, pad="nan", B=160, T=40, len_lo=10, len_hi=40)
     check(pkg, w, "label", "parakeet160")
     check(pkg, w, "frame", "parakeet160")
+    w96 = synth.make_workload(3, pad="nan", B=96, T=40, len_lo=10, len_hi=40)
+    eng = pkg.Engine(w96.model, w96.B, w96.T)
+    eng.configure(n_teams=8, joint_groups=2)
+    check(pkg, w96, "label", "parakeet96/8 teams/2 groups", engine=eng)
+    check(pkg, w96, "frame", "parakeet96/8 teams", engine=eng)
+    eng.close()
     w40 = synth.make_workload(3, pad="nan", B=40, T=40, len_lo=10, len_hi=40)
     eng = pkg.Engine(w40.model, w40.B, w40.T)
     eng.configure(n_teams=4)
