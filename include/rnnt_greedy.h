@@ -326,7 +326,8 @@ int rnnt_label_looping_decode(rnnt_engine *eng, const float *enc_out, const int3
  * the process ends.  The entry point calls no hipMalloc, hipFree or other
  * allocating routine; the engine (its packed weights) is created beforehand.
  * A call that needs more (roughly B * T * J * 4 bytes plus 9 MiB at the
- * Parakeet shape) returns RNNT_ERR_SCRATCH and queues nothing.
+ * Parakeet shape), or one of more than 128 utterances (it would take more than
+ * one launch), returns RNNT_ERR_SCRATCH and queues nothing.
  * All calls on one device share the array, which keeps the last call's
  * contents (the call clears what must start at zero): calls through this entry
  * point that overlap on one device race, whatever engines and streams they use;
@@ -371,9 +372,13 @@ int rnnt_engine_status(rnnt_engine *eng, int32_t *status_out);
 int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out);
 
 /*
- * Tuning knobs, for measurement.  n_teams > 0: cut the device into that many
- * teams for every decoder; 0 keeps the current layout (the default one is
- * chosen from max_B).  joint_groups (needs n_teams > 0): joint groups per team
+ * Tuning knobs, for measurement.  By default an engine holds one team layout
+ * per range of launch sizes (1-2, 3-8, 9-16, ... utterances, up to
+ * min(max_B, 128)), each with its own packed copy of the weights, and a
+ * launch runs in the one for its size: a small batch is decoded the way an
+ * engine created for that batch would decode it.  n_teams > 0 replaces them by
+ * one layout of that many teams for every decoder and launch size; 0 keeps
+ * the current layouts.  joint_groups (needs n_teams > 0): joint groups per team
  * in the label-looping calls, 0 or 1 = none; Algorithm 1 always runs plain
  * teams.  lookahead: frames examined per utterance per joint step (0 = default:
  * 8 in the label-looping calls, 16 when a call has one or two utterances; up
@@ -385,8 +390,9 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out);
  * Synchronous; repacks the weights when n_teams is given.  Returns
  * RNNT_ERR_SHAPE for values the engine cannot run (the work-groups do not
  * divide into the teams or groups, more than 16 utterances per team) and
- * RNNT_ERR_UNSUPPORTED when the layout does not fit the LDS; the default
- * layouts are then back in force.
+ * RNNT_ERR_UNSUPPORTED when the layout does not fit the LDS; the layouts in
+ * force stay as they were (after a lookahead that no layout fits: the default
+ * layouts and lookahead).
  */
 int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_groups,
                           int32_t lookahead, int32_t search_steps);

@@ -20,8 +20,9 @@ RNNT_DECLARE_NEST(fp4a);
 
 // Clears what must start at zero for a launch: barrier counters, abort flag and the tagged
 // argmax partials and row states (a tag left by the previous launch must not look current);
-// status word and statistics only for the first launch of a call (keep_totals = 0).
-__global__ void reset_kernel(unsigned *bar, int n_bar, unsigned *abort_flag, int *status, int keep_totals,
+// the status word only in the first launch of a call and the statistics only in the first
+// launch that uses their buffer.
+__global__ void reset_kernel(unsigned *bar, int n_bar, unsigned *abort_flag, int *status, int zero_status, int zero_stats,
                              long long *stats, int n_stats, unsigned long long *part,
                              unsigned long long *dpart, unsigned long long *lpart, int n_part,
                              unsigned long long *rowx, int n_rowx, unsigned long long *xh, int n_xh,
@@ -29,16 +30,16 @@ __global__ void reset_kernel(unsigned *bar, int n_bar, unsigned *abort_flag, int
 {
     const int i0 = blockIdx.x * blockDim.x + threadIdx.x;
     if (i0 < n_bar) bar[i0] = 0u;
-    if (i0 < n_stats && !keep_totals) stats[i0] = 0;
+    if (i0 < n_stats && zero_stats) stats[i0] = 0;
     if (i0 < n_part) { part[i0] = 0ull; dpart[i0] = 0ull; lpart[i0] = 0ull; }
     if (i0 < n_rowx) rowx[i0] = 0ull;
-    if (i0 == 0) { *abort_flag = 0u; if (!keep_totals) *status = 0; }
+    if (i0 == 0) { *abort_flag = 0u; if (zero_status) *status = 0; }
     // the tagged hidden-vector and q words (the larger arrays): grid-stride
     for (int i = i0; i < n_xh; i += gridDim.x * blockDim.x) xh[i] = 0ull;
     for (int i = i0; i < n_xq; i += gridDim.x * blockDim.x) xq[i] = 0ull;
 }
 
-hipError_t launch_decode(const DecodeParams &p, bool first, hipStream_t stream)
+hipError_t launch_decode(const DecodeParams &p, bool zero_status, bool zero_stats, hipStream_t stream)
 {
     const int n_bar = p.n_teams * 32, n_stats = p.n_teams * kStatStride;
     const int n_part = p.n_teams * p.groups * 2 * kMaxSamples * p.jteam_size;
@@ -49,7 +50,7 @@ hipError_t launch_decode(const DecodeParams &p, bool first, hipStream_t stream)
     int blocks = (n + 255) / 256;
     if (p.fast_pred && blocks < 256) blocks = 256;
     hipLaunchKernelGGL(reset_kernel, dim3(blocks), dim3(256), 0, stream, p.bar, n_bar,
-                       p.abort_flag, p.status, first ? 0 : 1, p.stats, n_stats, p.part, p.dpart, p.lpart, n_part, p.rowx,
+                       p.abort_flag, p.status, zero_status ? 1 : 0, zero_stats ? 1 : 0, p.stats, n_stats, p.part, p.dpart, p.lpart, n_part, p.rowx,
                        p.n_teams * 2 * kMaxRows, p.xh, n_xh, p.xq, n_xq);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

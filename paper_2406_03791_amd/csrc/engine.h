@@ -90,9 +90,10 @@ struct DecodeParams {
     int *xcc;                     // [n_teams * team_size]
 };
 
-// first: the call's first launch (a call of many utterances takes several): status word and step
-// counts start at zero; later launches add to them.
-hipError_t launch_decode(const DecodeParams &p, bool first, hipStream_t stream);
+// A call of many utterances takes several launches: the status word starts at zero in the call's
+// first launch (zero_status) and the step counts in the first launch that uses their buffer
+// (zero_stats); later launches add to them.
+hipError_t launch_decode(const DecodeParams &p, bool zero_status, bool zero_stats, hipStream_t stream);
 
 // Keeps the text of a failed HIP call for rnnt_status_string; returns RNNT_ERR_HIP.
 int hip_fail(hipError_t e, const char *what);

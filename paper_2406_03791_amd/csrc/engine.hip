@@ -12,6 +12,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <functional>
+#include <initializer_list>
+#include <memory>
 #include <string>
 #include <vector>
 
@@ -99,6 +101,8 @@ struct WorkspaceSizes {
 
 struct TeamConfig {
     int n_teams = 0, team_size = 0, groups = 1, jteam_size = 0;
+    int for_B = 0;          // utterances per launch the layout was planned for (its rows per team follow)
+    bool is_frame = false;  // a layout of Algorithm 1 (else of the label-looping decoders)
     PackedStage st0, stl[kMaxLayers], spred, sjoint;
     DevBuf hbuf, qbuf, part, dpart, lpart, rowx, bar, stats, xcc, xh, xq;
     Workspace ws;          // the buffers above plus the engine's P, abort flag and status word
@@ -138,10 +142,16 @@ struct rnnt_engine {
     DevBuf w_enc, b_enc, T0, bias_l, b_pred, b_out;
     DevBuf sc_hh, sc_ih, sc_pred, sc_out;   // e4m3 storage in the bfloat16 mode: power-of-two scale of every weight row
     DevBuf P, abort_flag, status;
-    TeamConfig frame_cfg;   // Algorithm 1
-    TeamConfig label_cfg;   // label looping, RNN-T and TDT
-    const TeamConfig *last_cfg = nullptr;
-    Workspace last_ws;      // where the last call kept its status word and statistics
+    // Team layouts, one per range of launch sizes in which the measured best arrangement (or
+    // the rows per team, hence the prediction path) changes, in ascending order of for_B: a
+    // launch of nb utterances runs in the first layout planned for at least nb.  An engine for
+    // many utterances so decodes a small batch the way an engine made for that batch would.
+    std::vector<std::unique_ptr<TeamConfig>> frame_cfgs;   // Algorithm 1
+    std::vector<std::unique_ptr<TeamConfig>> label_cfgs;   // label looping, RNN-T and TDT
+    // layouts (and workspaces) the launches of the last call ran in: where its statistics are
+    struct Used { const TeamConfig *t; Workspace ws; int nb; };   // nb: utterances of its latest launch
+    std::vector<Used> last_used;
+    Workspace last_ws;      // where the last call kept its status word
     int last_B = 0;
     void *scratch = nullptr;   // device address of the library's static scratch array on the engine's device
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before projection, before decode, after
@@ -180,14 +190,15 @@ WorkspaceSizes workspace_sizes(int n_teams, int ts, int groups, int L, int H, in
 
 // Choose the stage plans and the LDS layout for `n_teams` teams of `groups` joint groups and
 // upload the repacked weights.  Synchronous.
-int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
+int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups, int for_B)
 {
     const rnnt_model_desc &d = e->d;
     if (n_teams < 1 || n_teams > e->n_wg || groups < 1) return RNNT_ERR_SHAPE;
     const int ts = e->n_wg / n_teams;
     if (ts < 1 || ts % groups != 0) return RNNT_ERR_SHAPE;
     const int tj = ts / groups;
-    const int rows_max = (e->plan_B + n_teams - 1) / n_teams;
+    const int rows_max = (for_B + n_teams - 1) / n_teams;
+    t.for_B = for_B;
     if (rows_max > kMaxRows) return RNNT_ERR_SHAPE;
     const int H = d.H, L = d.L, J = d.J;
     auto nu_of = [&](int r) { return range_hi(r, ts, H) - range_lo(r, ts, H); };
@@ -216,7 +227,9 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
     // The joint kernels exist for 1, 2, 4 and 8 row groups (joint_row_groups) and an instance
     // uses all of its rows and the partial-sum stride of its own group count: the capacity is
     // that of the instance that runs the largest step, not the largest step itself.
-    const int samples_want = std::min(kMaxSamples, std::max(16, rows_j_max * (e->lookahead > 0 ? e->lookahead : 8)));
+    // (Algorithm 1 examines as many frames per row as keep a step at 16 samples unless configured)
+    const int la_plan = e->lookahead > 0 ? e->lookahead : (t.is_frame ? std::max(1, std::min(8, 16 / rows_j_max)) : 8);
+    const int samples_want = std::min(kMaxSamples, std::max(16, rows_j_max * la_plan));
     const int rgj = joint_row_groups(samples_want);
     const int samples_cap = rgj * 4;
     int off = 0;
@@ -379,34 +392,67 @@ int plan_and_pack(rnnt_engine *e, TeamConfig &t, int n_teams, int groups)
 //   teams of 32 there, equal from four utterances on; teams of 128 and 256 are slower).
 int default_layouts(rnnt_engine *e)
 {
-    const int max_B = e->plan_B;
-    int nf = max_B <= 2 ? 4 : (max_B <= 8 ? 8 : (max_B <= 16 ? 16 : 32));
-    while (nf > 1 && e->n_wg % nf != 0) nf /= 2;
-    while ((max_B + nf - 1) / nf > kMaxRows) nf *= 2;
     // A layout whose state does not fit the compute units' local memory (wide layers, many
     // layers, many rows per team) is followed by the others that divide the device, teams
     // with fewer rows first, before the engine is refused.
-    auto with_fallbacks = [&](TeamConfig &cfg, int first, int groups_first) {
-        int rc = plan_and_pack(e, cfg, first, groups_first);
-        for (int g = groups_first / 2; rc == RNNT_ERR_UNSUPPORTED && g >= 1; g /= 2) rc = plan_and_pack(e, cfg, first, g);
+    auto with_fallbacks = [&](TeamConfig &cfg, int first, int groups_first, int for_B) {
+        int rc = plan_and_pack(e, cfg, first, groups_first, for_B);
+        for (int g = groups_first / 2; rc == RNNT_ERR_UNSUPPORTED && g >= 1; g /= 2)
+            rc = plan_and_pack(e, cfg, first, g, for_B);
         for (int n = first * 2; rc == RNNT_ERR_UNSUPPORTED && n <= e->n_wg / 2; n *= 2)
-            if (e->n_wg % n == 0) rc = plan_and_pack(e, cfg, n, 1);
+            if (e->n_wg % n == 0) rc = plan_and_pack(e, cfg, n, 1, for_B);
         for (int n = first / 2; rc == RNNT_ERR_UNSUPPORTED && n >= 1; n /= 2)
-            if (e->n_wg % n == 0 && (max_B + n - 1) / n <= kMaxRows) rc = plan_and_pack(e, cfg, n, 1);
+            if (e->n_wg % n == 0 && (for_B + n - 1) / n <= kMaxRows) rc = plan_and_pack(e, cfg, n, 1, for_B);
         return rc;
     };
-    int rc = with_fallbacks(e->frame_cfg, nf, 1);
-    if (rc) return rc;
-    int nl = max_B <= 2 ? 4 : (max_B <= 16 ? 8 : 16);
-    while (nl > 1 && e->n_wg % nl != 0) nl /= 2;
-    while ((max_B + nl - 1) / nl > kMaxRows) nl *= 2;
-    const int rows = (max_B + nl - 1) / nl;
-    const int ts = e->n_wg / nl;
-    int groups = (max_B > 8 && rows >= 2 && ts % 2 == 0 && ts / 2 >= 8) ? 2 : 1;
-    // five to eight rows per team: four groups of two rows keep a joint step at 16 samples
-    // (2-3 % faster than two groups for an RNN-T at 72-128 utterances; slower for TDT)
-    if (groups == 2 && rows >= 5 && rows <= 8 && ts % 4 == 0 && e->d.D == 0) groups = 4;
-    return with_fallbacks(e->label_cfg, nl, groups);
+    // launch sizes up to which one arrangement is the measured best; the last layout is planned
+    // for the largest launch the engine makes
+    auto sizes = [&](std::initializer_list<int> upto) {
+        std::vector<int> v;
+        for (int b : upto)
+            if (b < e->plan_B) v.push_back(b);
+        v.push_back(e->plan_B);
+        return v;
+    };
+    e->frame_cfgs.clear();
+    e->label_cfgs.clear();
+    e->last_used.clear();
+    // (32 and 64: one and two rows per team of the 32-team arrangement, whose LDS plan keeps the
+    // finer K slicing that the plan for four rows has no room for)
+    for (int B : sizes({2, 8, 16, 32, 64})) {
+        int nf = B <= 2 ? 4 : (B <= 8 ? 8 : (B <= 16 ? 16 : 32));
+        while (nf > 1 && e->n_wg % nf != 0) nf /= 2;
+        while ((B + nf - 1) / nf > kMaxRows) nf *= 2;
+        e->frame_cfgs.emplace_back(new TeamConfig());
+        e->frame_cfgs.back()->is_frame = true;
+        const int rc = with_fallbacks(*e->frame_cfgs.back(), nf, 1, B);
+        if (rc) return rc;
+    }
+    // label looping: up to 64 utterances a team has at most four rows (the prediction step
+    // that keeps the hidden vectors in LDS), beyond that four joint groups for an RNN-T
+    for (int B : sizes({2, 8, 16, 64})) {
+        int nl = B <= 2 ? 4 : (B <= 16 ? 8 : 16);
+        while (nl > 1 && e->n_wg % nl != 0) nl /= 2;
+        while ((B + nl - 1) / nl > kMaxRows) nl *= 2;
+        const int rows = (B + nl - 1) / nl;
+        const int ts = e->n_wg / nl;
+        int groups = (B > 8 && rows >= 2 && ts % 2 == 0 && ts / 2 >= 8) ? 2 : 1;
+        // five to eight rows per team: four groups of two rows keep a joint step at 16 samples
+        // (2-3 % faster than two groups for an RNN-T at 72-128 utterances; slower for TDT)
+        if (groups == 2 && rows >= 5 && rows <= 8 && ts % 4 == 0 && e->d.D == 0) groups = 4;
+        e->label_cfgs.emplace_back(new TeamConfig());
+        const int rc = with_fallbacks(*e->label_cfgs.back(), nl, groups, B);
+        if (rc) return rc;
+    }
+    return RNNT_OK;
+}
+
+// The layout a launch of nb utterances runs in: the first one planned for at least nb.
+const TeamConfig &pick_layout(const std::vector<std::unique_ptr<TeamConfig>> &cfgs, int nb)
+{
+    for (const auto &t : cfgs)
+        if (t->for_B >= nb) return *t;
+    return *cfgs.back();
 }
 
 int fetch(std::vector<float> &dst, const float *dev, size_t n)
@@ -424,7 +470,7 @@ int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
     const int rows_team = (B + t.n_teams - 1) / t.n_teams;
     const int rows = std::max(1, (rows_team + t.groups - 1) / t.groups);
     int la = e->lookahead > 0 ? e->lookahead : 8;
-    if (e->lookahead == 0 && &t == &e->frame_cfg) la = std::min(8, std::max(1, 16 / rows));
+    if (e->lookahead == 0 && t.is_frame) la = std::min(8, std::max(1, 16 / rows));
     // one or two utterances: most of the device idles, a joint step is cheap next to its fixed
     // cost, and 16 frames per step measured 2-5 % faster than 8 (slower from four utterances on)
     if (e->lookahead == 0 && B <= 2) la = 16;
@@ -438,7 +484,7 @@ int effective_lookahead(const rnnt_engine *e, const TeamConfig &t, int B)
 // have their label; single-row groups of a team with four or more rows stop after two.
 int effective_search_steps(const rnnt_engine *e, const TeamConfig &t, int B)
 {
-    if (&t == &e->frame_cfg) return 0;      // Algorithm 1 has no label search
+    if (t.is_frame) return 0;      // Algorithm 1 has no label search
     if (e->search_steps < 0) return 0;
     if (e->search_steps > 0) return e->search_steps;
     const int rows_team = (B + t.n_teams - 1) / t.n_teams;
@@ -481,68 +527,77 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
                const Workspace *static_ws = nullptr)
 {
     const rnnt_model_desc &d = e->d;
-    const TeamConfig &t = variant == kFrameLooping ? e->frame_cfg : e->label_cfg;
-    const Workspace &ws = static_ws ? *static_ws : t.ws;
+    const auto &cfgs = variant == kFrameLooping ? e->frame_cfgs : e->label_cfgs;
+    // every launch reads the projected frames of the whole call from one buffer
+    float *P = static_ws ? static_ws->P : e->P.as<float>();
     HIP_TRY(hipEventRecord(e->ev[0], stream));
     HIP_TRY(launch_encoder_projection(enc_out, enc_len, e->w_enc.as<float>(), e->b_enc.as<float>(),
-                                      ws.P, B, T, d.F, d.J, is_bf16_arith(e->wt), stream));
+                                      P, B, T, d.F, d.J, is_bf16_arith(e->wt), stream));
     HIP_TRY(hipEventRecord(e->ev[1], stream));
-    DecodeParams p{};
-    p.F = d.F; p.E = d.E; p.H = d.H; p.L = d.L; p.J = d.J; p.V1 = d.V1; p.D = d.D;
-    p.blank = d.blank; p.NOUT = e->NOUT;
-    p.VT = d.V1;
-    if (e->multi_blank) { p.VT = e->NOUT; p.D = 0; }   // one distribution over labels, blank and big blanks
-    for (int i = 0; i < kMaxDur; ++i) p.durations[i] = e->durations[i];
-    p.T = T; p.S = S; p.cap = cap; p.variant = variant;
-    p.n_teams = t.n_teams; p.team_size = t.team_size;
-    p.groups = t.groups; p.jteam_size = t.jteam_size;
-    p.serpentine = 1;
-    p.spread = spread_layout(t) ? 1 : 0;
-    p.plain_launch = e->plain_launch ? 1 : 0;
-    p.wt = e->wt;
-    p.xstride = t.xstride; p.nu_max = t.nu_max; p.gj_max = t.gj_max;
-    p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
-    p.lds_scale = t.lds_scale; p.sc_nb_in = t.sc_nb_in;
-    p.sc_hh = e->sc_hh.as<float>(); p.sc_ih = e->sc_ih.as<float>();
-    p.sc_pred = e->sc_pred.as<float>(); p.sc_out = e->sc_out.as<float>();
-    p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
-    p.lds_q = t.lds_q; p.q_in_lds = t.q_in_lds; p.qstride = t.qstride;
-    p.fast_pred = t.fast_pred; p.lds_hc = t.lds_hc;
-    p.n_tail = t.n_tail; p.nout_m = t.nout_m; p.lds_tail = t.lds_tail;
-    p.w_tail = t.n_tail ? t.w_tail.as<float>() : nullptr;
-    p.rcap = t.rcap;
-    p.rg_planned = t.rg_planned;
-    p.samples_cap = t.samples_cap;
-    p.spin_limit = 1u << 22;
-    p.st0 = dev_stage(t.st0);
-    for (int l = 1; l < d.L; ++l) p.stl[l] = dev_stage(t.stl[l]);
-    p.spred = dev_stage(t.spred);
-    p.sjoint = dev_stage(t.sjoint);
-    p.T0 = e->T0.as<float>(); p.bias_l = e->bias_l.as<float>();
-    p.b_pred = e->b_pred.as<float>(); p.b_out = e->b_out.as<float>();
-    p.hbuf = ws.hbuf; p.qbuf = ws.qbuf;
-    p.part = ws.part; p.dpart = ws.dpart; p.lpart = ws.lpart; p.rowx = ws.rowx;
-    p.bar = ws.bar; p.abort_flag = ws.abort_flag;
-    p.status = ws.status; p.stats = ws.stats; p.xcc = ws.xcc;
-    p.xh = ws.xh; p.xq = ws.xq;
     e->last_B = B;
-    e->last_cfg = &t;
-    e->last_ws = ws;
+    e->last_used.clear();
     // the utterances [off, off + nb) per launch; status word and step counts add up over the launches
     for (int off = 0; off < B; off += kLaunchRows) {
         const int nb = std::min(kLaunchRows, B - off);
+        const TeamConfig &t = pick_layout(cfgs, nb);
+        const Workspace &ws = static_ws ? *static_ws : t.ws;
+        bool first_in_layout = true;
+        for (auto &u : e->last_used)
+            if (u.t == &t) { first_in_layout = false; u.nb = nb; }
+        if (first_in_layout) e->last_used.push_back({&t, ws, nb});
+        e->last_ws = ws;
+        DecodeParams p{};
+        p.F = d.F; p.E = d.E; p.H = d.H; p.L = d.L; p.J = d.J; p.V1 = d.V1; p.D = d.D;
+        p.blank = d.blank; p.NOUT = e->NOUT;
+        p.VT = d.V1;
+        if (e->multi_blank) { p.VT = e->NOUT; p.D = 0; }   // one distribution over labels, blank and big blanks
+        for (int i = 0; i < kMaxDur; ++i) p.durations[i] = e->durations[i];
+        p.T = T; p.S = S; p.cap = cap; p.variant = variant;
+        p.n_teams = t.n_teams; p.team_size = t.team_size;
+        p.groups = t.groups; p.jteam_size = t.jteam_size;
+        p.serpentine = 1;
+        p.spread = spread_layout(t) ? 1 : 0;
+        p.plain_launch = e->plain_launch ? 1 : 0;
+        p.wt = e->wt;
+        p.xstride = t.xstride; p.nu_max = t.nu_max; p.gj_max = t.gj_max;
+        p.lds_xz = t.lds_xz; p.lds_red = t.lds_red; p.lds_c = t.lds_c; p.lds_part = t.lds_part;
+        p.lds_scale = t.lds_scale; p.sc_nb_in = t.sc_nb_in;
+        p.sc_hh = e->sc_hh.as<float>(); p.sc_ih = e->sc_ih.as<float>();
+        p.sc_pred = e->sc_pred.as<float>(); p.sc_out = e->sc_out.as<float>();
+        p.lds_bias = t.lds_bias; p.lds_bytes = t.lds_bytes; p.gp_max = t.gp_max;
+        p.lds_q = t.lds_q; p.q_in_lds = t.q_in_lds; p.qstride = t.qstride;
+        p.fast_pred = t.fast_pred; p.lds_hc = t.lds_hc;
+        p.n_tail = t.n_tail; p.nout_m = t.nout_m; p.lds_tail = t.lds_tail;
+        p.w_tail = t.n_tail ? t.w_tail.as<float>() : nullptr;
+        p.rcap = t.rcap;
+        p.rg_planned = t.rg_planned;
+        p.samples_cap = t.samples_cap;
+        p.spin_limit = 1u << 22;
+        p.st0 = dev_stage(t.st0);
+        for (int l = 1; l < d.L; ++l) p.stl[l] = dev_stage(t.stl[l]);
+        p.spred = dev_stage(t.spred);
+        p.sjoint = dev_stage(t.sjoint);
+        p.T0 = e->T0.as<float>(); p.bias_l = e->bias_l.as<float>();
+        p.b_pred = e->b_pred.as<float>(); p.b_out = e->b_out.as<float>();
+        p.hbuf = ws.hbuf; p.qbuf = ws.qbuf;
+        p.part = ws.part; p.dpart = ws.dpart; p.lpart = ws.lpart; p.rowx = ws.rowx;
+        p.bar = ws.bar; p.abort_flag = ws.abort_flag;
+        p.status = ws.status; p.stats = ws.stats; p.xcc = ws.xcc;
+        p.xh = ws.xh; p.xq = ws.xq;
         const long long oc = (long long)off * cap;
         p.B = nb;
         p.lookahead = effective_lookahead(e, t, nb);
         p.search_steps = effective_search_steps(e, t, nb);
-        p.enc_len = enc_len + off; p.P = ws.P + (long long)off * T * d.J;
+        p.enc_len = enc_len + off; p.P = P + (long long)off * T * d.J;
         p.tokens = tokens_out + oc; p.tok_len = tok_len_out + off;
         p.frames = frames_out ? frames_out + oc : nullptr;
         p.logits = logit_out ? logit_out + oc : nullptr;
         p.durs = durs_out ? durs_out + oc : nullptr;
         p.logps = e->logp_out ? e->logp_out + oc : nullptr;
         p.done = e->done ? e->done + off : nullptr;
-        HIP_TRY(launch_decode(p, off == 0, stream));
+        // the status word is the engine's (or the static workspace's) for all layouts; the
+        // step counts are kept per layout and start at zero in a layout's first launch
+        HIP_TRY(launch_decode(p, off == 0, first_in_layout, stream));
     }
     HIP_TRY(hipEventRecord(e->ev[2], stream));
     e->timed = true;
@@ -817,27 +872,33 @@ int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_group
     if (search_steps < -1) return RNNT_ERR_SHAPE;
     HIP_TRY(hipDeviceSynchronize());
     if (n_teams > 0) {
-        eng->last_cfg = nullptr;      // the workspace the last call's statistics live in goes away
+        eng->last_used.clear();       // the workspaces the last call's statistics live in go away
         eng->last_ws = Workspace();
         eng->lookahead = lookahead;   // the layouts are sized for it
-        // plain teams for Algorithm 1; the label-looping decoders split each team further
+        // one layout for launches of every size: plain teams for Algorithm 1; the label-looping
+        // decoders split each team further
         if (eng->n_wg % n_teams != 0) return RNNT_ERR_SHAPE;
-        int rc = plan_and_pack(eng, eng->frame_cfg, n_teams, 1);
-        if (!rc) rc = plan_and_pack(eng, eng->label_cfg, n_teams, joint_groups ? joint_groups : 1);
-        if (rc) {   // put the default layouts back
-            (void)default_layouts(eng);
-            return rc;
-        }
+        std::unique_ptr<TeamConfig> f(new TeamConfig()), l(new TeamConfig());
+        f->is_frame = true;
+        int rc = plan_and_pack(eng, *f, n_teams, 1, eng->plan_B);
+        if (!rc) rc = plan_and_pack(eng, *l, n_teams, joint_groups ? joint_groups : 1, eng->plan_B);
+        if (rc) return rc;            // the layouts in use stay as they were
+        eng->frame_cfgs.clear(); eng->label_cfgs.clear();
+        eng->frame_cfgs.push_back(std::move(f));
+        eng->label_cfgs.push_back(std::move(l));
     }
     const bool replan = n_teams == 0 && lookahead != eng->lookahead;
     eng->lookahead = lookahead;
     eng->search_steps = search_steps;
     if (replan) {
         // the LDS layouts are sized for the samples of a joint step, which depend on the lookahead
-        eng->last_cfg = nullptr;
+        eng->last_used.clear();
         eng->last_ws = Workspace();
-        int rc = plan_and_pack(eng, eng->frame_cfg, eng->frame_cfg.n_teams, 1);
-        if (!rc) rc = plan_and_pack(eng, eng->label_cfg, eng->label_cfg.n_teams, eng->label_cfg.groups);
+        int rc = RNNT_OK;
+        for (auto &t : eng->frame_cfgs)
+            if (!rc) rc = plan_and_pack(eng, *t, t->n_teams, 1, t->for_B);
+        for (auto &t : eng->label_cfgs)
+            if (!rc) rc = plan_and_pack(eng, *t, t->n_teams, t->groups, t->for_B);
         if (rc) {
             eng->lookahead = 0;
             (void)default_layouts(eng);
@@ -895,8 +956,10 @@ int rnnt_label_looping_decode_noalloc(rnnt_engine *eng, const float *enc_out, co
     if (rc) return rc;
     if (eng->d.D != 0 && !eng->multi_blank) return RNNT_ERR_VARIANT;
     if (!eng->scratch) return RNNT_ERR_UNSUPPORTED;
+    // one launch only: the workspace is that of one layout
+    if (B > kLaunchRows) return RNNT_ERR_SCRATCH;
     // carve the call's workspace out of the static array, every part 256-byte aligned
-    const TeamConfig &t = eng->label_cfg;
+    const TeamConfig &t = pick_layout(eng->label_cfgs, B);
     const WorkspaceSizes z = workspace_sizes(t.n_teams, t.team_size, t.groups, eng->d.L, eng->d.H, eng->d.J);
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
@@ -968,36 +1031,43 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
     if (!eng || !out) return RNNT_ERR_NULL;
     HIP_TRY(hipDeviceSynchronize());
     std::memset(out, 0, sizeof(*out));
-    const TeamConfig *t = eng->last_cfg;
-    if (!t) return RNNT_OK;
-    std::vector<long long> st((size_t)t->n_teams * kStatStride);
-    std::vector<int> xcc((size_t)t->n_teams * t->team_size);
-    HIP_TRY(hipMemcpy(st.data(), eng->last_ws.stats, st.size() * sizeof(long long), hipMemcpyDeviceToHost));
-    HIP_TRY(hipMemcpy(xcc.data(), eng->last_ws.xcc, xcc.size() * sizeof(int), hipMemcpyDeviceToHost));
-    for (int i = 0; i < t->n_teams; ++i) {
-        const long long *s = st.data() + (size_t)i * kStatStride;
-        out->pred_steps += s[kStatPred];
-        out->joint_steps += s[kStatJoint];
-        out->joint_samples += s[kStatSamples];
-        out->barrier_polls += s[kStatPolls];
-        out->max_pred_steps = std::max<int64_t>(out->max_pred_steps, s[kStatPred]);
-        out->max_joint_steps = std::max<int64_t>(out->max_joint_steps, s[kStatJoint]);
-        if (i >= std::min(eng->last_B, t->n_teams)) continue;   // the team had no utterance and left at once
-        // Work-groups whose XCD is not the one their rank's weight slice is kept on: rank r of
-        // every team is meant to sit on the XCD of rank r % 8 of the first team (layouts whose
-        // teams are not multiples of 8 keep a team on one XCD instead).
-        for (int r = 0; r < t->team_size; ++r) {
-            const int id = xcc[(size_t)r * t->n_teams + i];
-            const int want = spread_layout(*t) ? xcc[(size_t)(r % 8) * t->n_teams]
-                                               : xcc[(size_t)i];
-            out->xcd_mismatch += id != want;
+    if (eng->last_used.empty()) return RNNT_OK;
+    // a call of more utterances than one launch takes may have run in more than one layout:
+    // the counts are sums over them, the longest chains the largest per-team sums
+    for (const auto &u : eng->last_used) {
+        const TeamConfig *t = u.t;
+        std::vector<long long> st((size_t)t->n_teams * kStatStride);
+        std::vector<int> xcc((size_t)t->n_teams * t->team_size);
+        HIP_TRY(hipMemcpy(st.data(), u.ws.stats, st.size() * sizeof(long long), hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(xcc.data(), u.ws.xcc, xcc.size() * sizeof(int), hipMemcpyDeviceToHost));
+        for (int i = 0; i < t->n_teams; ++i) {
+            const long long *s = st.data() + (size_t)i * kStatStride;
+            out->pred_steps += s[kStatPred];
+            out->joint_steps += s[kStatJoint];
+            out->joint_samples += s[kStatSamples];
+            out->barrier_polls += s[kStatPolls];
+            out->max_pred_steps = std::max<int64_t>(out->max_pred_steps, s[kStatPred]);
+            out->max_joint_steps = std::max<int64_t>(out->max_joint_steps, s[kStatJoint]);
+            if (i >= std::min(u.nb, t->n_teams)) continue;   // the team had no utterance and left at once
+            // Work-groups whose XCD is not the one their rank's weight slice is kept on: rank r of
+            // every team is meant to sit on the XCD of rank r % 8 of the first team (layouts whose
+            // teams are not multiples of 8 keep a team on one XCD instead).
+            for (int r = 0; r < t->team_size; ++r) {
+                const int id = xcc[(size_t)r * t->n_teams + i];
+                const int want = spread_layout(*t) ? xcc[(size_t)(r % 8) * t->n_teams]
+                                                   : xcc[(size_t)i];
+                out->xcd_mismatch += id != want;
+            }
         }
     }
+    // the layout of the call's first launch
+    const TeamConfig *t = eng->last_used.front().t;
+    const int nb = std::max(1, std::min(eng->last_B, kLaunchRows));
     out->n_teams = t->n_teams;
     out->team_size = t->team_size;
     out->joint_groups = t->groups;
-    out->lookahead = effective_lookahead(eng, *t, std::max(1, eng->last_B));
-    out->search_steps = effective_search_steps(eng, *t, std::max(1, eng->last_B));
+    out->lookahead = effective_lookahead(eng, *t, nb);
+    out->search_steps = effective_search_steps(eng, *t, nb);
     if (eng->timed) {
         HIP_TRY(hipEventElapsedTime(&out->projection_ms, eng->ev[0], eng->ev[1]));
         HIP_TRY(hipEventElapsedTime(&out->decode_ms, eng->ev[1], eng->ev[2]));
@@ -1009,11 +1079,13 @@ int rnnt_engine_phase_timers(rnnt_engine *eng, int32_t team, double *us_out, int
 {
     if (!eng || !us_out) return RNNT_ERR_NULL;
 #ifdef RNNT_PROFILE
-    const TeamConfig *t = eng->last_cfg;
-    if (!t || team < 0 || team >= t->n_teams || n < 0) return RNNT_ERR_SHAPE;
+    // (of the layout the call's first launch ran in)
+    if (eng->last_used.empty()) return RNNT_ERR_SHAPE;
+    const TeamConfig *t = eng->last_used.front().t;
+    if (team < 0 || team >= t->n_teams || n < 0) return RNNT_ERR_SHAPE;
     HIP_TRY(hipDeviceSynchronize());
     long long raw[kStatProf];
-    HIP_TRY(hipMemcpy(raw, eng->last_ws.stats + (size_t)team * kStatStride + kStatCount, sizeof raw,
+    HIP_TRY(hipMemcpy(raw, eng->last_used.front().ws.stats + (size_t)team * kStatStride + kStatCount, sizeof raw,
                       hipMemcpyDeviceToHost));
     for (int i = 0; i < n; ++i) us_out[i] = i < kStatProf ? raw[i] * 0.01 : 0.0;   // 100 MHz clock
     return RNNT_OK;
