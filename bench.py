@@ -510,7 +510,7 @@ def main() -> int:
         # alternating batch and an input that emits max_symbols labels on every frame
         line["sweep"] = []
         for kind in ("typical",) + tuple(synth.PATTERNS[1:]):
-            for B in (1, 8, 32, 128):
+            for B in (1, 8, 32, 128) + ((256,) if kind == "typical" else ()):   # 256: two launches of 128
                 if kind == "typical":
                     ws = synth.make_workload(2, B=B)
                 else:
