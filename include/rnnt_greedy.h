@@ -262,8 +262,10 @@ int rnnt_quantize_blocks_e2m1(const float *w, int64_t rows, int64_t cols, float 
  * after one projection of the whole batch (on MI355X that is faster than
  * larger launches); status word and statistics cover the whole call, and
  * completion flags are raised launch by launch.  The state of a team of
- * work-groups has to fit the compute units' local memory; a model for which
- * no team layout does returns RNNT_ERR_UNSUPPORTED.  The argmax
+ * work-groups has to fit the compute units' local memory: a model whose
+ * state for 128 utterances fits in no team layout is decoded in launches of
+ * the largest size that does fit (64, 16, ...), and one for which not even
+ * the layout for two utterances fits returns RNNT_ERR_UNSUPPORTED.  The argmax
  * candidates of a joint step sit there too, one per sample and group of four
  * output columns of a rank: vocabularies of a few thousand labels fit for any
  * batch, tens of thousands only for engines of a few utterances.  When the

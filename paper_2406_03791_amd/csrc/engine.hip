@@ -426,6 +426,9 @@ int default_layouts(rnnt_engine *e)
         e->frame_cfgs.emplace_back(new TeamConfig());
         e->frame_cfgs.back()->is_frame = true;
         const int rc = with_fallbacks(*e->frame_cfgs.back(), nf, 1, B);
+        // a launch size whose state fits in no layout ends the list: larger calls are then
+        // decoded in launches of the largest size that does fit
+        if (rc == RNNT_ERR_UNSUPPORTED && e->frame_cfgs.size() > 1) { e->frame_cfgs.pop_back(); break; }
         if (rc) return rc;
     }
     // label looping: up to 64 utterances a team has at most four rows (the prediction step
@@ -442,6 +445,7 @@ int default_layouts(rnnt_engine *e)
         if (groups == 2 && rows >= 5 && rows <= 8 && ts % 4 == 0 && e->d.D == 0) groups = 4;
         e->label_cfgs.emplace_back(new TeamConfig());
         const int rc = with_fallbacks(*e->label_cfgs.back(), nl, groups, B);
+        if (rc == RNNT_ERR_UNSUPPORTED && e->label_cfgs.size() > 1) { e->label_cfgs.pop_back(); break; }
         if (rc) return rc;
     }
     return RNNT_OK;
@@ -537,8 +541,9 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
     e->last_B = B;
     e->last_used.clear();
     // the utterances [off, off + nb) per launch; status word and step counts add up over the launches
-    for (int off = 0; off < B; off += kLaunchRows) {
-        const int nb = std::min(kLaunchRows, B - off);
+    const int launch_rows = cfgs.back()->for_B;      // at most kLaunchRows
+    for (int off = 0; off < B; off += launch_rows) {
+        const int nb = std::min(launch_rows, B - off);
         const TeamConfig &t = pick_layout(cfgs, nb);
         const Workspace &ws = static_ws ? *static_ws : t.ws;
         bool first_in_layout = true;
@@ -957,7 +962,7 @@ int rnnt_label_looping_decode_noalloc(rnnt_engine *eng, const float *enc_out, co
     if (eng->d.D != 0 && !eng->multi_blank) return RNNT_ERR_VARIANT;
     if (!eng->scratch) return RNNT_ERR_UNSUPPORTED;
     // one launch only: the workspace is that of one layout
-    if (B > kLaunchRows) return RNNT_ERR_SCRATCH;
+    if (B > eng->label_cfgs.back()->for_B) return RNNT_ERR_SCRATCH;
     // carve the call's workspace out of the static array, every part 256-byte aligned
     const TeamConfig &t = pick_layout(eng->label_cfgs, B);
     const WorkspaceSizes z = workspace_sizes(t.n_teams, t.team_size, t.groups, eng->d.L, eng->d.H, eng->d.J);
@@ -1062,7 +1067,7 @@ int rnnt_engine_stats(rnnt_engine *eng, rnnt_stats *out)
     }
     // the layout of the call's first launch
     const TeamConfig *t = eng->last_used.front().t;
-    const int nb = std::max(1, std::min(eng->last_B, kLaunchRows));
+    const int nb = std::max(1, std::min(eng->last_B, t->for_B));
     out->n_teams = t->n_teams;
     out->team_size = t->team_size;
     out->joint_groups = t->groups;
