@@ -234,6 +234,10 @@ def test_calls_of_more_utterances_than_one_launch_takes(pkg):
         _, _, st_l = check(pkg, wb, "label", f"parakeet300/{B}", engine=eng, logp=True)
         # every utterance takes at least one prediction step in either decoder
         assert st_f["pred_steps"] >= B and st_l["pred_steps"] >= 1
+    # one configured layout for launches of every size
+    eng.configure(n_teams=16, joint_groups=2)
+    check(pkg, w, "label", "parakeet300/16 teams/2 groups", engine=eng)
+    check(pkg, w, "frame", "parakeet300/16 teams", engine=eng)
     eng.close()
     w4 = synth.make_workload(4, pad="nan", B=200, T=40, len_lo=10, len_hi=40)
     check(pkg, w4, "tdt", "tdt200")
