@@ -60,7 +60,9 @@ def compare(w, net, ref, got, S, check_fill=True, margin=MARGIN, logit_rtol=LOGI
                 f"row {b}: logits differ by {np.max(np.abs(rv - gv)):.3e}")
             if "logps" in got:
                 rl, gl = ref.logps[b].astype(np.float64), got["logps"][b].astype(np.float64)
-                tol = logit_rtol * np.maximum(1.0, np.abs(rl))
+                # a log-probability is the difference of the top logit and the log-sum-exp of all
+                # logits, each within the logit tolerance
+                tol = 2 * logit_rtol * np.maximum(1.0, np.abs(rl))
                 assert np.all(np.abs(rl - gl) <= tol), (
                     f"row {b}: log-probabilities differ by {np.max(np.abs(rl - gl)):.3e}")
         else:

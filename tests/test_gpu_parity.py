@@ -907,8 +907,9 @@ def test_random_shapes_layouts_and_lookaheads(pkg):
     A layout the planner refuses (it does not divide the device, or does not fit) is skipped."""
     rng = np.random.default_rng(2406)
     ran = 0
-    for case in range(136):
-        big = case >= 120                      # the last cases: wide layers, large vocabularies, up to 96 utterances
+    n_cases = int(os.environ.get("RNNT_RANDOM_CASES", "136"))      # more for a longer run
+    for case in range(n_cases):
+        big = case % 136 >= 120                # some cases: wide layers, large vocabularies, up to 96 utterances
         tdt = bool(rng.integers(0, 3) == 0)
         durations = tuple(sorted(set([0] + list(rng.integers(1, 5, size=rng.integers(1, 4)))))) if tdt else ()
         dims = synth.ModelDims(F=int(rng.choice([16, 48, 128])), E=int(rng.integers(4, 80)),
