@@ -901,7 +901,7 @@ def test_weight_only_4_bit_quantised_models(pkg):
 
 def test_random_shapes_layouts_and_lookaheads(pkg):
     """Seeded random models (widths that are multiples of 4 and nothing else in particular, 1-4
-    layers, vocabularies of 2-200, with and without durations), batches, team layouts, joint
+    layers, vocabularies of 2-200; RNN-T, TDT and multi-blank models), batches, team layouts, joint
     groups, lookaheads and max_symbols, fp32 and the bfloat16 mode with bf16, e4m3 and e2m1
     storage: each case against the oracle.
     A layout the planner refuses (it does not divide the device, or does not fit) is skipped."""
@@ -910,14 +910,16 @@ def test_random_shapes_layouts_and_lookaheads(pkg):
     n_cases = int(os.environ.get("RNNT_RANDOM_CASES", "136"))      # more for a longer run
     for case in range(n_cases):
         big = case % 136 >= 120                # some cases: wide layers, large vocabularies, up to 96 utterances
-        tdt = bool(rng.integers(0, 3) == 0)
+        kind = str(rng.choice(["rnnt", "rnnt", "rnnt", "tdt", "tdt", "multi-blank"]))
+        tdt = kind == "tdt"
         durations = tuple(sorted(set([0] + list(rng.integers(1, 5, size=rng.integers(1, 4)))))) if tdt else ()
+        spans = tuple(int(x) for x in sorted(set(rng.integers(2, 6, size=rng.integers(1, 3))))) if kind == "multi-blank" else ()
         dims = synth.ModelDims(F=int(rng.choice([16, 48, 128])), E=int(rng.integers(4, 80)),
                                H=4 * int(rng.integers(100, 257) if big else rng.integers(1, 41)),
                                L=int(rng.integers(1, 5)),
                                J=4 * int(rng.integers(100, 257) if big else rng.integers(1, 61)),
                                V1=int(rng.integers(500, 5001) if big else rng.integers(2, 201)),
-                               durations=tuple(int(d) for d in durations))
+                               durations=tuple(int(d) for d in durations), big_blanks=spans)
         model = synth.make_model(dims, seed=1000 + case, weight_range=0.3 if not big else 0.1,
                                  blank_bias=float(rng.uniform(0.5, 2.0)))
         B, T, S = int(rng.integers(1, 97 if big else 49)), int(rng.integers(4, 21 if big else 31)), int(rng.integers(1, 5))
@@ -931,7 +933,7 @@ def test_random_shapes_layouts_and_lookaheads(pkg):
         elif form == "e2m1":
             model = synth.with_streamed_weights(model, lambda a: oracle.quantize_blocks_e2m1(a)[0])
             flags |= pkg.RNNT_FLAG_FP4_WEIGHTS
-        variants = ("tdt",) if tdt else ("frame", "label")
+        variants = ("tdt",) if tdt else (("label",) if spans else ("frame", "label"))
         w = synth.Workload(f"random{case}", variants[0], model, x, ln, S)
         n_teams = int(rng.choice([0, 0, 4, 8, 16, 32]))
         groups = int(rng.choice([1, 2, 4])) if n_teams else 0
