@@ -167,6 +167,33 @@ def test_schedules_agree_bit_for_bit(cfg, kw):
     assert rs["seq"].tok_len.sum() > 0
 
 
+def test_schedules_agree_on_random_models():
+    """The same claim on seeded random models: 1-3 layers, small widths, RNN-T, TDT and
+    multi-blank, random lengths and max_symbols; float and double builds."""
+    rng = np.random.default_rng(8)
+    emitted = 0
+    for case in range(40):
+        kind = ["rnnt", "tdt", "multi-blank"][case % 3]
+        durations = tuple(sorted(set([0] + [int(d) for d in rng.integers(1, 4, size=2)]))) if kind == "tdt" else ()
+        spans = (2, int(rng.integers(3, 6))) if kind == "multi-blank" else ()
+        dims = synth.ModelDims(F=16, E=int(rng.integers(3, 20)), H=4 * int(rng.integers(1, 9)),
+                               L=int(rng.integers(1, 4)), J=4 * int(rng.integers(1, 9)),
+                               V1=int(rng.integers(2, 30)), durations=durations, big_blanks=spans)
+        model = synth.make_model(dims, seed=300 + case, weight_range=0.4, blank_bias=float(rng.uniform(0.3, 1.5)))
+        B, T, S = int(rng.integers(1, 7)), int(rng.integers(3, 25)), int(rng.integers(1, 4))
+        x, ln = synth.make_inputs(700 + case, B, T, dims.F, 1, T, pad="nan")
+        w = synth.Workload(f"r{case}", "label", model, x, ln, S)
+        for real in ("float", "double"):
+            net = oracle.LstmNet(w.model, real)
+            scheds = ["label", "seq"] if (durations or spans) else ["frame", "label", "seq"]
+            rs = {sc: oracle.decode(net, w.enc_out, w.enc_len, S, sc, record=True) for sc in scheds}
+            for sc, r in rs.items():
+                assert r.status == 0
+                assert_same(r, rs["seq"])
+            emitted += int(rs["seq"].tok_len.sum())
+    assert emitted > 200
+
+
 def test_frame_looping_masked_rows_do_not_matter():
     """Algorithm 1 runs both networks for the whole batch at every inner step, rows that are
     already masked included (the oracle's default); their results are discarded, so passing
