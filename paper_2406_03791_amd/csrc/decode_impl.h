@@ -1,11 +1,14 @@
 // Persistent decode kernel for exact RNN-T / TDT greedy decoding on gfx950: the device code,
-// included by the translation units that instantiate it (decode_f*.hip, decode_l*.hip).
+// included by the translation unit that instantiates it (decode_inst.hip, compiled once per
+// loop nest, row-group count and weight storage).
 //
 // One launch runs the whole data-dependent double loop of Algorithm 1 (or of
 // its label-looping form) on the device.  The work-groups form independent
-// teams, each on one XCD when the dispatcher deals work-groups round-robin over
-// the XCDs; a team owns a subset of the utterances and runs the loops for them
-// with its own barrier, so no team ever waits for another.  Inside a team every
+// teams, whose ranks are spread over the XCDs so that every XCD streams only its
+// eighth of the packed weights (see spread_layout in engine.hip); a team owns a
+// subset of the utterances and runs the loops for them with its own barrier, so
+// no team ever waits for another.  Teams of one utterance have a loop nest of
+// their own (kFrameLoopingSingle).  Inside a team every
 // dense stage is split over the ranks by output columns and exchanged through
 // small global buffers; the loop control (blank mask, symbols_added, not_blank,
 // per-utterance frame index) is recomputed identically by every rank from the
