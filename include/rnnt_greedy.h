@@ -272,6 +272,10 @@ int rnnt_quantize_blocks_e2m1(const float *w, int64_t rows, int64_t cols, float 
  * preferred team layout does not fit, the engine tries the others that divide
  * the device (fewer joint groups, then more teams, then fewer) before it
  * refuses.
+ * Device memory of an engine: the projected frames (max_B * max_T * J floats)
+ * and, per team layout (up to eleven, see rnnt_engine_configure), a packed
+ * copy of the streamed weights and a few megabytes of workspace: about
+ * 0.4 GB besides the projected frames for the Parakeet shape in fp32.
  * Synchronous.  *out is set only on success.
  */
 int rnnt_engine_create(const rnnt_model_desc *desc, int32_t max_B, int32_t max_T,
