@@ -1584,7 +1584,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                     }
                 }
                 if (w.tid < R) {
-                    c.mask[w.tid] = time_idx >= c.len[w.tid];   // blank_mask
+                    c.mask[w.tid] = time_idx >= c.len[w.tid];   // a row whose frames have run out starts the frame masked
                     // a row whose frames have run out is complete although the team goes on
                     if (w.rank == 0 && time_idx == c.len[w.tid] && time_idx > 0) finish_row(p, w.tid);
                 }
@@ -1626,7 +1626,7 @@ __global__ void __launch_bounds__(kThreads) decode_kernel(const DecodeParams p)
                         for (int r = 0; r < R; ++r) {
                             if (c.mask[r]) continue;
                             const int k = c.s_k[off * R + r];
-                            if (k == p.blank) { c.mask[r] = 1; }          // blank_mask |= (k == blank)
+                            if (k == p.blank) { c.mask[r] = 1; }          // a blank masks the row for the rest of the frame
                             else { emit_row(p, w, r, k, time_idx, c.s_v[off * R + r], c.s_lp[off * R + r], 0); any = 1; }
                         }
                         c.any[flip] = any;
