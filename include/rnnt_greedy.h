@@ -172,8 +172,8 @@ typedef struct rnnt_stats {
  * helper; nothing runs on the device).  w and out are HOST arrays of
  * rows * cols floats, row-major, one row per output of the product; they may
  * be the same array.  For each row: k is the smallest integer with
- * max|row| * 2^-k <= 448 (0 for a row of zeros; kept within +-100), and every weight becomes
- * 2^k times the e4m3 value nearest to weight * 2^-k (ties to the even code).
+ * max|row| * 2^-k <= 448 (0 for a row of zeros; kept within +-100), and every
+ * weight becomes 2^k times the e4m3 value nearest to weight * 2^-k (ties to the even code).
  * scales_out, if not NULL, receives the rows' 2^k.  An engine created with
  * RNNT_FLAG_BF16_ARITHMETIC | RNNT_FLAG_FP8_WEIGHTS accepts the result for
  * any of its streamed matrices.  Weights that are not finite are
@@ -250,8 +250,9 @@ int rnnt_quantize_blocks_e2m1(const float *w, int64_t rows, int64_t cols, float 
  * RNNT_ERR_SHAPE.
  * Limits of this implementation, checked here before anything is allocated
  * (RNNT_ERR_UNSUPPORTED): F must be a multiple of 16 (K tile of the projection
- * GEMM); H and J multiples of 4 (rows are read 16 bytes at a time); V1 + D at most 65 535 (the argmax exchange carries a 16-bit column
- * index); max_B * max_T below 2^31 (frame numbers are 32-bit); the device must
+ * GEMM); H and J multiples of 4 (rows are read 16 bytes at a time); V1 + D at
+ * most 65 535 (the argmax exchange carries a 16-bit column index);
+ * max_B * max_T below 2^31 (frame numbers are 32-bit); the device must
  * support cooperative launches.  1 <= L <= 4, D <= 8, blank in
  * [0, V1) and positive sizes are RNNT_ERR_SHAPE.
  * The two bias vectors of an LSTM layer are added once on the host while the
@@ -406,8 +407,9 @@ int rnnt_engine_configure(rnnt_engine *eng, int32_t n_teams, int32_t joint_group
 /*
  * Optional extra output of the decode calls that follow: logp_out, a DEVICE
  * buffer [B, cap] laid out like tokens_out, receives for every emitted label
- * its log-softmax value over the V1 token columns -- the v of Algorithm 1's
- * "k, v = logp.max()" (logit_out carries the maximum before the softmax).  The
+ * its log-softmax value over the V1 token columns -- the value v that Algorithm 1
+ * takes together with the argmax k from the log-probabilities of the joint
+ * output (logit_out carries the maximum before the softmax).  The
  * log-sum-exp is fused into the argmax exchange of the joint step; nothing is
  * computed while no buffer is set.  NULL switches it off again.  The caller
  * owns the buffer and keeps it alive (cap as in the decode call) until the

@@ -448,7 +448,7 @@ def test_e4m3_rounding_of_inputs_matches_torch():
 
 
 def test_log_probabilities_of_emitted_labels():
-    """The v of Algorithm 1's `k, v = logp.max()`: log_softmax over the token columns at the
+    """The value v that Algorithm 1 takes with the argmax k: log_softmax over the token columns at the
     chosen label.  Pinned against torch.log_softmax on table-driven logits (the duration
     columns of a TDT table do not enter), the closed form for equal logits, and the LSTM net's
     own joint output re-evaluated through the direct-access entry points."""
