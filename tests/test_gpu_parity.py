@@ -899,6 +899,52 @@ def test_weight_only_4_bit_quantised_models(pkg):
         assert err.value.code == -2
 
 
+def test_engines_side_by_side_and_engine_lifetime(pkg):
+    """Calls of two engines (an RNN-T and a TDT model) queued back to back on one side stream
+    with no host synchronisation between them, each engine twice with different inputs: the
+    stream alone orders them and every result is the oracle's.  Then engines created, used and
+    destroyed in a row: the device memory they held comes back."""
+    wa1 = synth.make_workload(1, B=6, T=50, len_lo=10, len_hi=50)
+    wt1 = synth.make_workload(4, B=5, T=40, len_lo=10, len_hi=40)
+    rows = lambda w, r: synth.Workload(w.name, w.variant, w.model, w.enc_out[r].copy(), w.enc_len[r].copy(),
+                                       w.max_symbols)
+    wa2, wt2 = rows(wa1, [5, 2, 0]), rows(wt1, [4, 1])
+    ea, et = pkg.Engine(wa1.model, 6, 50), pkg.Engine(wt1.model, 5, 40)
+    side = torch.cuda.Stream()
+    queued = []
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for eng, w, variant in ((ea, wa1, "label"), (et, wt1, "tdt"), (ea, wa2, "frame"), (et, wt2, "tdt")):
+            enc = torch.from_numpy(w.enc_out).cuda().contiguous()
+            ln = torch.from_numpy(w.enc_len.astype(np.int32)).cuda()
+            queued.append((w, variant, eng.decode(variant, enc, ln, w.max_symbols), enc, ln))
+    side.synchronize()
+    assert ea.status() == 0 and et.status() == 0
+    for w, variant, out, _, _ in queued:
+        net = oracle.LstmNet(w.model)
+        ref = oracle.decode(net, w.enc_out, w.enc_len, w.max_symbols, "seq", n_threads=N_THREADS)
+        compare(w, net, ref, to_lists(out, w.B), w.max_symbols)
+    ea.close(); et.close()
+    enc = torch.from_numpy(wa1.enc_out).cuda().contiguous()
+    ln = torch.from_numpy(wa1.enc_len.astype(np.int32)).cuda()
+    first, free = None, []
+    for i in range(16):
+        eng = pkg.Engine(wa1.model, 64, 200)
+        out = eng.decode("label", enc, ln, wa1.max_symbols)
+        torch.cuda.synchronize()
+        tok = out["tokens"].cpu().numpy()
+        first = tok if first is None else first
+        assert np.array_equal(tok, first) and eng.status() == 0
+        eng.close()
+        del out
+        torch.cuda.synchronize()
+        free.append(torch.cuda.mem_get_info()[0])
+    # the first engines also pay for what the runtime and torch's allocator keep once
+    free_before, free_after = free[3], free[-1]
+    log(f"[lifetime] free memory after each engine, MiB below the first: {[(free[0] - x) >> 20 for x in free]}")
+    assert free_before - free_after < (16 << 20), "engines give their device memory back"
+
+
 def test_random_shapes_layouts_and_lookaheads(pkg):
     """Seeded random models (widths that are multiples of 4 and nothing else in particular, 1-4
     layers, vocabularies of 2-200; RNN-T, TDT and multi-blank models), batches, team layouts, joint
