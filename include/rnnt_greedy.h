@@ -440,6 +440,22 @@ int rnnt_engine_set_logp_output(rnnt_engine *eng, float *logp_out);
 int rnnt_engine_set_done_flags(rnnt_engine *eng, int32_t *done);
 
 /*
+ * How long the device-side waits of the decode calls that follow may last.  The
+ * work-groups of a team wait for each other's results by polling; every such
+ * wait gives up after `polls` repeated polls (one takes about a microsecond),
+ * raises a flag that makes every other wait of the launch give up too, and the
+ * call ends in the ordinary way with RNNT_DEV_ABORTED in the status word and
+ * outputs that must not be used (Algorithm 1's loops have no such exit: this
+ * is the bound that keeps a launch that did not get all its work-groups
+ * resident, or a failing device, from hanging the stream).  polls = -1
+ * restores the default, 2^22 (a few seconds); 0 lets a wait poll once, which
+ * makes the first wait of a launch fail -- the way the tests reach the failure
+ * path.  A later call on the engine starts clean.  RNNT_ERR_SHAPE for values
+ * below -1 or above 2^32 - 1.
+ */
+int rnnt_engine_set_wait_limit(rnnt_engine *eng, int64_t polls);
+
+/*
  * Phase timers of the last decode call, for libraries built with
  * -DRNNT_PROFILE (RNNT_PROFILE=1 in the environment of build.py): microseconds
  * rank 0 of `team` spent in each phase of the prediction and joint steps, as

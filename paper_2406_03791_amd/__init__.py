@@ -6,6 +6,9 @@ C names and only marshal arguments; every step of the decode runs in the HIP
 kernels.  There is no fallback: importing fails if the library is not built.
 """
 from .binding import (  # noqa: F401
+    RNNT_DEV_ABORTED,
+    RNNT_DEV_LEN_CLAMPED,
+    RNNT_DEV_OVERFLOW,
     RNNT_FLAG_BF16_WEIGHTS,
     RNNT_FLAG_FP8_WEIGHTS,
     RNNT_FLAG_PLAIN_LAUNCH,
@@ -22,6 +25,7 @@ from .binding import (  # noqa: F401
     rnnt_engine_destroy,
     rnnt_engine_set_logp_output,
     rnnt_engine_set_done_flags,
+    rnnt_engine_set_wait_limit,
     rnnt_engine_phase_timers,
     rnnt_engine_stats,
     rnnt_probe_e4m3_widening,

@@ -19,7 +19,7 @@ EXPORTS = (
     "rnnt_label_looping_decode", "tdt_label_looping_decode", "rnnt_encoder_projection",
     "rnnt_engine_status", "rnnt_engine_stats", "rnnt_engine_configure", "rnnt_status_string",
     "rnnt_engine_set_logp_output",
-    "rnnt_engine_set_done_flags",
+    "rnnt_engine_set_done_flags", "rnnt_engine_set_wait_limit",
     "rnnt_label_looping_decode_noalloc",
     "rnnt_engine_phase_timers",
     "rnnt_probe_stream", "rnnt_probe_exchange", "rnnt_probe_mfma", "rnnt_probe_e4m3_widening",
@@ -111,6 +111,7 @@ def load_library():
         lib.rnnt_engine_configure.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         lib.rnnt_engine_set_logp_output.argtypes = [C.c_void_p, C.c_void_p]
         lib.rnnt_engine_set_done_flags.argtypes = [C.c_void_p, C.c_void_p]
+        lib.rnnt_engine_set_wait_limit.argtypes = [C.c_void_p, C.c_int64]
         lib.rnnt_engine_phase_timers.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_int32]
         lib.rnnt_probe_stream.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         lib.rnnt_probe_exchange.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
@@ -181,6 +182,10 @@ def rnnt_engine_set_logp_output(eng, logp_out) -> None:
 
 def rnnt_engine_set_done_flags(eng, done) -> None:
     _check(load_library().rnnt_engine_set_done_flags(eng, _p(done)))
+
+
+def rnnt_engine_set_wait_limit(eng, polls: int = -1) -> None:
+    _check(load_library().rnnt_engine_set_wait_limit(eng, int(polls)))
 
 
 def rnnt_engine_configure(eng, n_teams: int = 0, joint_groups: int = 0, lookahead: int = 0,
@@ -343,6 +348,10 @@ class Engine:
     def configure(self, n_teams: int = 0, joint_groups: int = 0, lookahead: int = 0,
                   search_steps: int = 0) -> None:
         rnnt_engine_configure(self.handle, n_teams, joint_groups, lookahead, search_steps)
+
+    def set_wait_limit(self, polls: int = -1) -> None:
+        """Polls a device-side wait may repeat before the call gives up (-1 = default)."""
+        rnnt_engine_set_wait_limit(self.handle, polls)
 
     def alloc_outputs(self, B: int, cap: int, pinned: bool = False):
         """Output tensors on the device, or (pinned=True) in pinned host memory,

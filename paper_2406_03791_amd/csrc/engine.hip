@@ -50,6 +50,8 @@ constexpr int kLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit
 // row groups, and one launch of 256 utterances measured 29 ms against 2 x 10.8 ms for two of 128
 // (label looping; Algorithm 1 52 against 2 x 19 ms, TDT 16.6 against 2 x 5.9 ms).
 constexpr int kLaunchRows = 128;
+// A wait on another work-group polls again about once a microsecond: a few seconds.
+constexpr unsigned kDefaultSpinLimit = 1u << 22;
 constexpr int kStaticLds = 3072;        // kept free for the kernel's static LDS (control block)
 
 // Scratch of the entry point that allocates nothing (rnnt_label_looping_decode_noalloc): the
@@ -135,6 +137,7 @@ struct rnnt_engine {
     bool multi_blank = false;    // RNNT_FLAG_MULTI_BLANK: the D extra output columns are big blanks
     float *logp_out = nullptr;   // caller's [B, cap] buffer for log-probabilities, or none
     int32_t *done = nullptr;     // caller's [B] completion flags, or none
+    unsigned spin_limit = kDefaultSpinLimit;   // polls a device-side wait may repeat before the call gives up
     // host copies of the weights that get repacked when the team layout changes
     std::vector<std::vector<float>> w_ih, w_hh;
     std::vector<float> w_pred, w_out;
@@ -577,7 +580,7 @@ int run_decode(rnnt_engine *e, int variant, const float *enc_out, const int32_t 
         p.rcap = t.rcap;
         p.rg_planned = t.rg_planned;
         p.samples_cap = t.samples_cap;
-        p.spin_limit = 1u << 22;
+        p.spin_limit = e->spin_limit;
         p.st0 = dev_stage(t.st0);
         for (int l = 1; l < d.L; ++l) p.stl[l] = dev_stage(t.stl[l]);
         p.spred = dev_stage(t.spred);
@@ -924,6 +927,14 @@ int rnnt_engine_set_done_flags(rnnt_engine *eng, int32_t *done)
 {
     if (!eng) return RNNT_ERR_NULL;
     eng->done = done;
+    return RNNT_OK;
+}
+
+int rnnt_engine_set_wait_limit(rnnt_engine *eng, int64_t polls)
+{
+    if (!eng) return RNNT_ERR_NULL;
+    if (polls < -1 || polls > 0xffffffffll) return RNNT_ERR_SHAPE;
+    eng->spin_limit = polls < 0 ? kDefaultSpinLimit : (unsigned)polls;
     return RNNT_OK;
 }
 

@@ -45,6 +45,7 @@ def test_status_strings_and_null_checks_need_no_gpu():
     assert lib.rnnt_engine_create(None, 1, 1, 0, None) == -1
     st = ctypes.c_int32(0)
     assert lib.rnnt_engine_status(None, ctypes.byref(st)) == -1
+    assert lib.rnnt_engine_set_wait_limit(None, 0) == -1
 
 
 def test_create_refuses_unsupported_shapes_before_touching_the_device():

@@ -899,6 +899,32 @@ def test_weight_only_4_bit_quantised_models(pkg):
         assert err.value.code == -2
 
 
+def test_a_wait_that_expires_ends_the_call_with_the_aborted_bit(pkg):
+    """The failure path, forced from the host: with a wait limit of 0 polls the first wait on
+    another work-group gives up, every other wait follows, and each launch ends in the ordinary
+    way with RNNT_DEV_ABORTED.  The next call on the engine, with the default limit back,
+    decodes as if nothing had happened."""
+    w = synth.make_workload(1)
+    eng = pkg.Engine(w.model, w.B, w.T)
+    for bad in (-2, 1 << 32):
+        with pytest.raises(pkg.RnntError) as ei:
+            eng.set_wait_limit(bad)
+        assert ei.value.code == -2
+    enc = torch.from_numpy(w.enc_out).cuda().contiguous()
+    ln = torch.from_numpy(w.enc_len).cuda()
+    for variant in ("frame", "label"):
+        check(pkg, w, variant, "abort/before", engine=eng)
+        eng.set_wait_limit(0)
+        eng.decode(variant, enc, ln, w.max_symbols)
+        torch.cuda.synchronize()
+        status = eng.status()
+        log(f"[abort/{variant}] status with a wait limit of 0 polls: {status}")
+        assert status & pkg.RNNT_DEV_ABORTED
+        eng.set_wait_limit(-1)
+        check(pkg, w, variant, "abort/after", engine=eng)
+    eng.close()
+
+
 def test_engines_side_by_side_and_engine_lifetime(pkg):
     """Calls of two engines (an RNN-T and a TDT model) queued back to back on one side stream
     with no host synchronisation between them, each engine twice with different inputs: the
